@@ -1,0 +1,330 @@
+"""CPU oracle for the Select-and-Pack Attention (SPA) hot path.  TEST INFRASTRUCTURE.
+
+This file is a plain, slow, fp64 NumPy statement of what the path computes, written
+from the paper (Section 3.2 "Select and Pack Attention", Eqs. for s / r_g / r_p,
+"Token Packing", and the selection loss of Section 3.3).  It exists only so that
+tests, the smoke check and the benchmark's cpu_baseline leg can compare the HIP
+kernels against it.  It shares no code with the HIP path, is never imported by the
+product package, and is not tuned for speed.
+
+Given the selection mask, SPA reaches exactly the plain result "softmax self-attention
+of each image restricted to that image's selected tokens" (packing is a re-arrangement,
+the attention mask keeps images apart).  So the attention oracle is that definition,
+evaluated per image directly on the un-packed [B, N, .] tensors: it never looks at the
+packed layout.
+
+Readings taken where the paper is silent (each listed in the design notes):
+  * gate = one linear map w in R^C plus a scalar bias (Section 3.2: "linear gating layer",
+    scores of shape B x N x 1);
+  * selection = noise-free hard decision of the two-class Gumbel-Softmax on [s, 0]:
+    sigmoid(s) > tau, i.e. s > ln(tau / (1 - tau)), strict, ties not selected;
+  * packed order = images in batch order, tokens in ascending position (stable);
+  * attention scale 1/sqrt(Dh), no bias, no dropout;
+  * the post-max score s feeds the sigmoid scale and the loss; where s_up wins the max,
+    no gradient reaches (w, b); a tie goes to the gate;
+  * the hard mask is a constant in the backward pass.
+
+Pins: every function below is checked in tests/test_oracle_*.py against closed forms,
+library routines on special cases, brute force and finite differences.
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional, Tuple
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------- dtype
+def round_to_dtype(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Round fp64 values to the storage type of the workload ("f32" or "bf16"),
+    returned as fp64.  bf16 = keep the top 16 bits of the fp32 pattern, nearest-even."""
+    f = np.asarray(a, dtype=np.float32)
+    if dtype == "f32":
+        return f.astype(F64)
+    if dtype != "bf16":
+        raise ValueError(dtype)
+    bits = np.ascontiguousarray(f).view(np.uint32).astype(np.uint64)
+    lsb = (bits >> 16) & 1
+    bits = (bits + 0x7FFF + lsb) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).reshape(f.shape).astype(F64)
+
+
+# ---------------------------------------------------------------------------- gate
+def gate_scores(x: np.ndarray, w: np.ndarray, bias: float,
+                s_up: Optional[np.ndarray] = None) -> np.ndarray:
+    """Eq. s = Max(f_g(r), s_up) (Section 3.2).  f_g(r)_i = bias + sum_c w_c x_ic, summed
+    left to right in fp64.  x [B,N,C], w [C], s_up [B,N] or None.  Returns logits [B,N]."""
+    x = np.asarray(x, dtype=F64)
+    w = np.asarray(w, dtype=F64)
+    B, N, C = x.shape
+    g = np.full((B, N), float(bias), dtype=F64)
+    for c in range(C):
+        g = g + w[c] * x[:, :, c]
+    if s_up is not None:
+        g = np.maximum(g, np.asarray(s_up, dtype=F64))
+    return g
+
+
+def gate_only(x, w, bias) -> np.ndarray:
+    """The linear gate alone, f_g(r), before the max with the up-scale scores."""
+    return gate_scores(x, w, bias, None)
+
+
+def threshold_logit(tau: float) -> float:
+    """sigmoid(s) > tau  <=>  s > ln(tau / (1 - tau))."""
+    if not (0.0 < tau < 1.0):
+        raise ValueError("tau must lie in (0, 1)")
+    return math.log(tau / (1.0 - tau))
+
+
+def select(s: np.ndarray, tau: float) -> Tuple[np.ndarray, float]:
+    """Hard selection (Eq. r_p = Gumbel-Softmax(s) . r_g, noise-free): mask_i = [s_i > theta].
+    Returns (mask [B,N] uint8, margin = min_i |s_i - theta|)."""
+    theta = threshold_logit(tau)
+    s = np.asarray(s, dtype=F64)
+    mask = (s > theta).astype(np.uint8)
+    margin = float(np.min(np.abs(s - theta))) if s.size else float("inf")
+    return mask, margin
+
+
+def maxpool2x2(s: np.ndarray, h: int, w: int) -> np.ndarray:
+    """Up-scale scores resized to the next (2x coarser) stage by 2x2 stride-2 max-pooling
+    (Section 3.2: scores from up-scaled features are "adjusted via max-pooling").
+    s [B, h*w] -> [B, (h/2)*(w/2)]."""
+    s = np.asarray(s, dtype=F64)
+    B = s.shape[0]
+    out = np.empty((B, (h // 2) * (w // 2)), dtype=F64)
+    for b in range(B):
+        g = s[b].reshape(h, w)
+        for i in range(h // 2):
+            for j in range(w // 2):
+                out[b, i * (w // 2) + j] = max(g[2 * i, 2 * j], g[2 * i, 2 * j + 1],
+                                               g[2 * i + 1, 2 * j], g[2 * i + 1, 2 * j + 1])
+    return out
+
+
+def sigmoid(s: np.ndarray) -> np.ndarray:
+    s = np.asarray(s, dtype=F64)
+    e = np.exp(-np.abs(s))
+    return np.where(s >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+
+
+# ---------------------------------------------------------------------------- pack
+def pack_indices(mask: np.ndarray):
+    """Token Packing (Section 3.2): walk images in batch order and tokens in ascending
+    position, appending survivors.  Returns
+      cu_seqlens [B+1] i32 (segment of image b is [cu[b], cu[b+1])),
+      gather_idx [T] i32  (flat token id b*N+n of the j-th packed row),
+      inv_pos [B*N] i32   (packed row of a token, -1 if not selected),
+      total T."""
+    mask = np.asarray(mask)
+    B, N = mask.shape
+    cu = np.zeros(B + 1, dtype=np.int32)
+    gather = []
+    inv = np.full(B * N, -1, dtype=np.int32)
+    for b in range(B):
+        for n in range(N):
+            if mask[b, n]:
+                inv[b * N + n] = len(gather)
+                gather.append(b * N + n)
+        cu[b + 1] = len(gather)
+    return cu, np.asarray(gather, dtype=np.int32), inv, len(gather)
+
+
+def packed_rows(total: int, container_len: int) -> int:
+    """Rows of the packed buffer: T rounded up to whole containers of length L; only
+    the last container is padded (Section 3.2 "Token Packing").  L = 0: no padding."""
+    if container_len <= 0:
+        return total
+    return -(-total // container_len) * container_len
+
+
+def pack_rows(x: np.ndarray, gather_idx: np.ndarray, scores: Optional[np.ndarray] = None,
+              container_len: int = 0, dtype: Optional[str] = None) -> np.ndarray:
+    """packed[j] = x[gather_idx[j]], times sigmoid(s) of that token when scores are given
+    (Eq. r_g = Sigmoid(s) . r); pad rows up to whole containers are zero.  If dtype is
+    given the scaled rows are rounded to it (what a kernel storing that type can hold)."""
+    x = np.asarray(x, dtype=F64)
+    C = x.shape[-1]
+    flat = x.reshape(-1, C)
+    T = len(gather_idx)
+    out = np.zeros((packed_rows(T, container_len), C), dtype=F64)
+    for j in range(T):
+        row = flat[gather_idx[j]]
+        if scores is not None:
+            row = row * sigmoid(np.asarray(scores, dtype=F64).reshape(-1)[gather_idx[j]])
+        out[j] = row
+    if dtype is not None:
+        out = round_to_dtype(out, dtype)
+    return out
+
+
+def unpack(o: np.ndarray, inv_pos: np.ndarray, B: int, N: int,
+           base: Optional[np.ndarray] = None) -> np.ndarray:
+    """Scatter back (Section 3.2 / SPA-block figure): selected tokens receive their
+    attention output at their original position; the others keep `base` (the tokens that
+    bypass attention) or zero.  With base given, selected rows get base + o."""
+    o = np.asarray(o, dtype=F64)
+    C = o.shape[-1]
+    y = np.zeros((B * N, C), dtype=F64) if base is None else np.array(base, dtype=F64).reshape(B * N, C)
+    for i in range(B * N):
+        j = inv_pos[i]
+        if j >= 0:
+            y[i] = y[i] + o[j]
+    return y.reshape(B, N, C)
+
+
+# ----------------------------------------------------------------------- attention
+def _split_heads(t: np.ndarray, H: int) -> np.ndarray:
+    B, N, C = t.shape
+    return np.asarray(t, dtype=F64).reshape(B, N, H, C // H)
+
+
+def attention_per_image(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray,
+                        H: int, scale: Optional[float] = None):
+    """Multi-head self-attention in which a token attends only to the selected tokens of
+    its own image (Section 3.2, last paragraph).  q, k, v are the UN-packed [B,N,C]
+    tensors; for each image the selected rows are taken with the mask, the full n_b x n_b
+    score matrix is formed, and softmax(QK^T * scale) V is evaluated row by row.
+    Returns out [T, C] in packed order and lse [H, T] (log-sum-exp of the scaled scores)."""
+    qh, kh, vh = _split_heads(q, H), _split_heads(k, H), _split_heads(v, H)
+    B, N, _, Dh = qh.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(Dh)
+    mask = np.asarray(mask).astype(bool)
+    T = int(mask.sum())
+    out = np.zeros((T, H * Dh), dtype=F64)
+    lse = np.zeros((H, T), dtype=F64)
+    row0 = 0
+    for b in range(B):
+        sel = np.flatnonzero(mask[b])
+        n = len(sel)
+        if n == 0:
+            continue
+        for h in range(H):
+            Q, K, V = qh[b, sel, h], kh[b, sel, h], vh[b, sel, h]
+            S = (Q @ K.T) * scale
+            m = S.max(axis=1, keepdims=True)
+            E = np.exp(S - m)
+            Z = E.sum(axis=1, keepdims=True)
+            P = E / Z
+            out[row0:row0 + n, h * Dh:(h + 1) * Dh] = P @ V
+            lse[h, row0:row0 + n] = (m + np.log(Z))[:, 0]
+        row0 += n
+    return out, lse
+
+
+def attention_backward_per_image(q, k, v, mask, dout_packed, H: int,
+                                 scale: Optional[float] = None):
+    """Gradient of attention_per_image with respect to the selected rows of q, k, v.
+    dout_packed [T, C] is the gradient of the packed output.  Textbook softmax-attention
+    calculus with explicit n_b x n_b matrices:
+      P = softmax(S), dV = P^T dO, dP = dO V^T, dS = P * (dP - rowsum(P * dP)),
+      dQ = dS K * scale, dK = dS^T Q * scale.
+    Returns dq, dk, dv, each [T, C] in packed order."""
+    qh, kh, vh = _split_heads(q, H), _split_heads(k, H), _split_heads(v, H)
+    B, N, _, Dh = qh.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(Dh)
+    mask = np.asarray(mask).astype(bool)
+    T = int(mask.sum())
+    dO = np.asarray(dout_packed, dtype=F64).reshape(T, H, Dh)
+    dq = np.zeros((T, H * Dh), dtype=F64)
+    dk = np.zeros_like(dq)
+    dv = np.zeros_like(dq)
+    row0 = 0
+    for b in range(B):
+        sel = np.flatnonzero(mask[b])
+        n = len(sel)
+        if n == 0:
+            continue
+        for h in range(H):
+            Q, K, V = qh[b, sel, h], kh[b, sel, h], vh[b, sel, h]
+            G = dO[row0:row0 + n, h]
+            S = (Q @ K.T) * scale
+            E = np.exp(S - S.max(axis=1, keepdims=True))
+            P = E / E.sum(axis=1, keepdims=True)
+            dP = G @ V.T
+            dS = P * (dP - (P * dP).sum(axis=1, keepdims=True))
+            sl = slice(h * Dh, (h + 1) * Dh)
+            dv[row0:row0 + n, sl] = P.T @ G
+            dq[row0:row0 + n, sl] = (dS @ K) * scale
+            dk[row0:row0 + n, sl] = (dS.T @ Q) * scale
+        row0 += n
+    return dq, dk, dv
+
+
+# ------------------------------------------------------------------ loss / gate bwd
+def selection_loss(s: np.ndarray, labels: np.ndarray, loss_scale: float) -> float:
+    """Selection loss (Section 3.3): binary cross-entropy between sigmoid(s) and the
+    label, summed over tokens and multiplied by loss_scale.  Evaluated in the stable
+    form  max(s,0) - y s + log(1 + exp(-|s|))  which equals
+    -(y log sigma(s) + (1-y) log(1 - sigma(s)))."""
+    s = np.asarray(s, dtype=F64)
+    y = np.asarray(labels, dtype=F64)
+    per = np.maximum(s, 0.0) - y * s + np.log1p(np.exp(-np.abs(s)))
+    return float(loss_scale * per.sum())
+
+
+def gate_backward(x, w, bias, s_up, labels, d_rg, gate_scaled: bool, loss_scale: float):
+    """Backward of the gate: scores s = Max(x.w + b, s_up); optional gated representation
+    r_g = sigmoid(s) . x whose gradient d_rg [B,N,C] arrives from the packed path (zero
+    rows for unselected tokens); selection loss = loss_scale * BCE(sigmoid(s), labels).
+
+      ds_i = loss_scale * (sigmoid(s_i) - y_i) + [gate_scaled] p_i (1 - p_i) <d_rg_i, x_i>
+      dx_i = [gate_scaled] p_i * d_rg_i + own_i * ds_i * w
+      dw   = sum_i own_i * ds_i * x_i,   db = sum_i own_i * ds_i
+    where own_i = 1 when the gate's own logit produced s_i (g_i >= s_up_i) and 0 where the
+    up-scale score won the max.  Returns dict(loss, ds, dx, dw, db)."""
+    x = np.asarray(x, dtype=F64)
+    w = np.asarray(w, dtype=F64)
+    B, N, C = x.shape
+    g = gate_only(x, w, bias)
+    if s_up is None:
+        s = g
+        own = np.ones((B, N), dtype=F64)
+    else:
+        su = np.asarray(s_up, dtype=F64)
+        s = np.maximum(g, su)
+        own = (g >= su).astype(F64)
+    p = sigmoid(s)
+    y = np.asarray(labels, dtype=F64)
+    ds = loss_scale * (p - y)
+    dx = np.zeros_like(x)
+    if gate_scaled and d_rg is not None:
+        d_rg = np.asarray(d_rg, dtype=F64)
+        ds = ds + p * (1.0 - p) * (d_rg * x).sum(axis=2)
+        dx = dx + p[:, :, None] * d_rg
+    dsg = ds * own
+    dx = dx + dsg[:, :, None] * w[None, None, :]
+    dw = (dsg[:, :, None] * x).sum(axis=(0, 1))
+    db = float(dsg.sum())
+    return {"loss": selection_loss(s, labels, loss_scale), "ds": ds, "dx": dx, "dw": dw, "db": db,
+            "scores": s}
+
+
+# ------------------------------------------------------------------------ whole path
+def spa_forward(x, w, bias, qkv, H: int, tau: float, dtype: str,
+                s_up: Optional[np.ndarray] = None, container_len: int = 0,
+                base: Optional[np.ndarray] = None):
+    """The forward hot path in the paper's order: score (Eq. s) -> select (Eq. r_p) ->
+    pack -> per-image attention on the selected tokens -> scatter back.
+    qkv [B,N,3C] holds the (already projected) q | k | v of every token.
+    Returns a dict of every intermediate the HIP path exposes."""
+    x = np.asarray(x, dtype=F64)
+    B, N, C = x.shape
+    s = gate_scores(x, w, bias, s_up)
+    mask, margin = select(s, tau)
+    cu, gidx, inv, T = pack_indices(mask)
+    qkv = np.asarray(qkv, dtype=F64)
+    q, k, v = qkv[:, :, :C], qkv[:, :, C:2 * C], qkv[:, :, 2 * C:]
+    packed_qkv = pack_rows(qkv, gidx, None, container_len)
+    packed_rg = pack_rows(x, gidx, s, container_len, dtype)
+    out, lse = attention_per_image(q, k, v, mask, H)
+    y = unpack(out, inv, B, N, base)
+    return {"scores": s, "mask": mask, "margin": margin, "counts": mask.sum(axis=1).astype(np.int32),
+            "cu_seqlens": cu, "gather_idx": gidx, "inv_pos": inv, "total": T,
+            "packed_qkv": packed_qkv, "packed_rg": packed_rg, "out": out, "lse": lse, "y": y}
