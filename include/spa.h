@@ -1,0 +1,215 @@
+/*
+ * libspa — Select-and-Pack Attention (SPA) hot path for AMD MI355X (gfx950).
+ *
+ * The calls follow the paper's statement of the SPA / SnP block (Section 3.2):
+ *   scores  s   = Max(f_g(r), s_up)                      spa_gate_select
+ *   select  r_p = hard(Gumbel-Softmax(s)) . r_g          spa_gate_select (mask) + spa_pack
+ *   pack    survivors of every image, in order, no padding to the batch maximum
+ *                                                        spa_pack
+ *   masked multi-head self-attention on the packed tokens, a token attends only to
+ *   tokens of its own image                              spa_packed_attention
+ *   selected tokens return to their positions, the others bypass attention
+ *                                                        spa_unpack
+ * and, for training, the transposes of those steps plus the selection loss of
+ * Section 3.3.
+ *
+ * Conventions (all entry points)
+ *   - Every pointer is a DEVICE pointer unless it is said to be a host value; scalars are
+ *     passed by value.  The caller owns every buffer; the library allocates, frees and
+ *     retains nothing.  Buffers must not overlap unless stated.
+ *   - Row-major, innermost dimension contiguous.  Token t of image b is flat token b*N + t.
+ *   - dtype is SPA_F32 or SPA_BF16 and names the storage type of the feature tensors
+ *     (x, packed, q/k/v, out, y, their gradients).  Scores, lse, loss, dw, db are fp32.
+ *     Arithmetic accumulates in fp32; bf16 attention uses bf16 MFMA with fp32 softmax.
+ *   - `stream` is a hipStream_t (NULL = the null stream).  Calls enqueue work and return
+ *     without synchronising.  No call reads device memory on the host: output buffers are
+ *     sized by the capacity B*N, and the number of selected tokens stays on the device.
+ *   - Return value: SPA_OK, or a negative SPA_ERR_* code.  Arguments are validated before
+ *     anything is launched; on error nothing has been enqueued and spa_last_error() (a
+ *     thread-local, host string) says what was wrong.
+ *   - Feature rows must be 16-byte aligned: base pointers 16-byte aligned and row length
+ *     in bytes (C * element size, row_stride * element size) a multiple of 16.
+ *   - B >= 1, N >= 1, B*N < 2^31.
+ */
+#ifndef SPA_H
+#define SPA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPA_OK 0
+#define SPA_ERR_INVALID_ARG (-1)  /* null pointer, bad size, misalignment, tau outside (0,1) */
+#define SPA_ERR_UNSUPPORTED (-2)  /* dtype / head dim the kernels do not cover */
+#define SPA_ERR_WORKSPACE (-3)    /* workspace missing or too small */
+#define SPA_ERR_HIP (-4)          /* the HIP runtime reported an error at launch */
+
+#define SPA_F32 0
+#define SPA_BF16 1
+
+/* Library version (major*10000 + minor*100 + patch). Host. */
+int spa_version(void);
+
+/* Message of the last failing call on this thread ("" if none). Host string owned by the
+ * library; valid until the next failing call on the same thread. */
+const char* spa_last_error(void);
+
+/*
+ * Gate scoring and selection (Section 3.2, equations for s and r_p).
+ *   g_i      = bias + sum_c w[c] * x[i,c]            (linear gating layer f_g)
+ *   scores_i = max(g_i, s_up[i]) if s_up else g_i    (s = Max(f_g(r), s_up))
+ *   mask_i   = scores_i > ln(tau/(1-tau))            (hard, noise-free Gumbel-Softmax
+ *                                                     decision sigmoid(s) > tau; a tie is
+ *                                                     not selected)
+ *   counts_b = number of selected tokens of image b
+ * in:  x [B,N,C] dtype; w [C] dtype; bias (host float); s_up [B,N] fp32 or NULL (scores of
+ *      the finer stage already max-pooled to this stage's grid, see spa_maxpool2x2);
+ *      tau in (0,1) (host float).
+ * out: scores [B,N] fp32 logits; mask [B,N] uint8 (0/1); counts [B] int32 or NULL.
+ */
+int spa_gate_select(const void* x, const void* w, float bias, const float* s_up, float tau,
+                    int B, int N, int C, int dtype,
+                    float* scores, uint8_t* mask, int32_t* counts, void* stream);
+
+/*
+ * 2x2 stride-2 max-pooling of a score map, used to hand the scores of a finer stage to
+ * the next one (Section 3.2: up-scale scores "adjusted via max-pooling").
+ * in:  s [B, h*w] fp32 (h, w even).   out: pooled [B, (h/2)*(w/2)] fp32.
+ */
+int spa_maxpool2x2(const float* s, int B, int h, int w, float* pooled, void* stream);
+
+/*
+ * Token packing (Section 3.2 "Token Packing").  Stable compaction of the selected tokens:
+ * images in batch order, tokens in ascending position.
+ *   cu_seqlens[b]  = number of selected tokens in images < b    (cu_seqlens[B] = T)
+ *   gather_idx[j]  = flat token id of packed row j              (j < T)
+ *   inv_pos[i]     = packed row of flat token i, or -1
+ *   packed[j,:]    = x[gather_idx[j],:]  (times sigmoid(gate_scores[gather_idx[j]]) when
+ *                    gate_scores is given: r_g = Sigmoid(s) . r), rounded to dtype
+ *   rows T .. ceil(T/container_len)*container_len - 1 of packed are zero (only the last
+ *   container is padded); container_len = 0 means no padding.  Rows beyond that are left
+ *   untouched.
+ * in:  x [B,N,C] dtype (C may be a fused row such as 3*C of q|k|v); mask [B,N] uint8
+ *      (non-zero = selected); counts [B] int32 or NULL: the per-image selected counts that
+ *      spa_gate_select wrote for this mask (when given, a workgroup scans only its own
+ *      image's mask instead of the whole prefix; results are identical);
+ *      gate_scores [B,N] fp32 or NULL.
+ * out: packed [B*N (+ container_len - 1 if padding), C] dtype; cu_seqlens [B+1] int32;
+ *      gather_idx [B*N] int32 (first T valid); inv_pos [B*N] int32; total [1] int32.
+ *      gather_idx, inv_pos, cu_seqlens, total may each be NULL if not wanted.
+ */
+int spa_pack(const void* x, const uint8_t* mask, const int32_t* counts, const float* gate_scores,
+             int B, int N, int C, int dtype, int container_len,
+             void* packed, int32_t* cu_seqlens, int32_t* gather_idx, int32_t* inv_pos,
+             int32_t* total, void* stream);
+
+/*
+ * Multi-head self-attention on packed tokens in which a token attends only to tokens of
+ * its own image (Section 3.2, last paragraph).  For every image b and head h, over packed
+ * rows [cu_seqlens[b], cu_seqlens[b+1]):
+ *   O = softmax(Q K^T * softmax_scale) V,   lse = log sum_j exp(S_ij)
+ * The attention mask is never materialised; segments are addressed by cu_seqlens.
+ * in:  q, k, v: packed rows, element (j, h, d) at ptr[j*row_stride + h*Dh + d]; the three
+ *      may point into one fused [*, 3*H*Dh] buffer.  row_stride in elements.
+ *      cu_seqlens [B+1] int32; max_seqlen >= every segment length (N); Dh in {32, 64};
+ *      softmax_scale (host float; 0 means 1/sqrt(Dh)).
+ * out: out [>= T, H*Dh] dtype, contiguous rows; lse [H, B*max_seqlen] fp32 or NULL
+ *      (entry (h, j) for packed row j).  Rows >= T are not written.
+ */
+int spa_packed_attention(const void* q, const void* k, const void* v, int64_t row_stride,
+                         const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
+                         int dtype, float softmax_scale, void* out, float* lse, void* stream);
+
+/*
+ * Scatter back (Section 3.2: positive tokens undergo attention, negative tokens go on
+ * directly).  y[i,:] = packed_out[inv_pos[i],:] if inv_pos[i] >= 0 else 0; with base given,
+ * y[i,:] = base[i,:] (+ packed_out[inv_pos[i],:] on selected rows).
+ * in:  packed_out [>= T, C] dtype; inv_pos [B*N] int32; base [B,N,C] dtype or NULL.
+ * out: y [B,N,C] dtype (may alias base).
+ */
+int spa_unpack(const void* packed_out, const int32_t* inv_pos, const void* base,
+               int B, int N, int C, int dtype, void* y, void* stream);
+
+/* ----------------------------------------------------------------- training ---- */
+
+/*
+ * Transpose of spa_unpack: dout[j,:] = dy[gather_idx[j],:] for j < total.
+ * in:  dy [B,N,C] dtype; gather_idx [B*N] int32; total [1] int32 (device).
+ * out: dout [B*N, C] dtype (rows >= T untouched).
+ */
+int spa_unpack_bwd(const void* dy, const int32_t* gather_idx, const int32_t* total,
+                   int B, int N, int C, int dtype, void* dout, void* stream);
+
+/*
+ * Transpose of spa_pack's row gather: d_rg[i,:] = dpacked[inv_pos[i],:] or 0.  The
+ * sigmoid factor of a gate-scaled pack is applied by spa_gate_bwd, not here.
+ * in:  dpacked [>= T, C] dtype; inv_pos [B*N] int32.   out: d_rg [B,N,C] dtype.
+ */
+int spa_pack_bwd(const void* dpacked, const int32_t* inv_pos, int B, int N, int C, int dtype,
+                 void* d_rg, void* stream);
+
+/* Bytes of workspace spa_packed_attention_bwd needs. Host. */
+size_t spa_attention_bwd_workspace_bytes(int B, int max_seqlen, int H, int Dh, int dtype);
+
+/*
+ * Backward of spa_packed_attention (softmax-attention calculus per image and head):
+ *   P = exp(S - lse), dV = P^T dO, dP = dO V^T, D_i = sum_d dO_id O_id,
+ *   dS = P * (dP - D), dQ = dS K * scale, dK = dS^T Q * scale.
+ * in:  q, k, v as in the forward (row_stride); out, dout [>= T, H*Dh] dtype contiguous;
+ *      lse [H, B*max_seqlen] fp32 from the forward; workspace (device, 256-byte aligned)
+ *      of at least spa_attention_bwd_workspace_bytes bytes.
+ * out: dq, dk, dv: element (j,h,d) at ptr[j*grad_row_stride + h*Dh + d] (may point into one
+ *      fused buffer).  Rows >= T are not written.  Results are run-to-run bit-stable.
+ */
+int spa_packed_attention_bwd(const void* q, const void* k, const void* v, int64_t row_stride,
+                             const void* out, const void* dout, const float* lse,
+                             const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
+                             int dtype, float softmax_scale,
+                             void* dq, void* dk, void* dv, int64_t grad_row_stride,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace spa_gate_bwd needs. Host. */
+size_t spa_gate_bwd_workspace_bytes(int B, int N, int C, int dtype);
+
+/*
+ * Backward of the gate with the selection loss (Section 3.3: binary cross-entropy between
+ * sigmoid(s) and the selection label, summed over tokens, weighted by loss_scale):
+ *   p_i  = sigmoid(scores_i)
+ *   loss = loss_scale * sum_i [ max(s_i,0) - y_i s_i + log(1 + exp(-|s_i|)) ]
+ *   ds_i = loss_scale (p_i - y_i) + [gate_scaled] p_i (1-p_i) <d_rg[i,:], x[i,:]>
+ *   dx_i = [gate_scaled] p_i d_rg[i,:] + own_i ds_i w
+ *   dw   = sum_i own_i ds_i x[i,:],  db = sum_i own_i ds_i
+ * own_i = 0 where the up-scale score won the max (scores_i came from s_up, i.e.
+ * g_i < s_up_i), else 1; the hard mask is a constant.
+ * in:  x [B,N,C], w [C] dtype; bias; scores [B,N] fp32 (output of spa_gate_select);
+ *      s_up [B,N] fp32 or NULL; labels [B,N] uint8; d_rg [B,N,C] dtype or NULL (gradient of
+ *      r_g = Sigmoid(s) . r, zero rows for unselected tokens); gate_scaled 0/1;
+ *      workspace of at least spa_gate_bwd_workspace_bytes bytes.
+ * out: loss [1] fp32; dx [B,N,C] dtype; dw [C] fp32; db [1] fp32.  Deterministic.
+ */
+int spa_gate_bwd(const void* x, const void* w, float bias, const float* scores,
+                 const float* s_up, const uint8_t* labels, const void* d_rg, int gate_scaled,
+                 float loss_scale, int B, int N, int C, int dtype,
+                 float* loss, void* dx, float* dw, float* db,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* -------------------------------------------------- comparison baseline -------- */
+
+/*
+ * Padded-to-max masked attention, the scheme the paper contrasts SPA with (Section 1:
+ * padding every image's selected tokens to the batch maximum).  q, k, v, out are
+ * [B, n_pad, H*Dh] with n_pad >= every seqlens[b]; all n_pad query rows of every image are
+ * computed, keys >= seqlens[b] are masked.  Same kernels as spa_packed_attention.
+ * in:  seqlens [B] int32.  out rows of padded queries hold finite, meaningless values.
+ */
+int spa_padded_attention(const void* q, const void* k, const void* v, int64_t row_stride,
+                         const int32_t* seqlens, int B, int n_pad, int H, int Dh, int dtype,
+                         float softmax_scale, void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPA_H */

@@ -1,0 +1,294 @@
+// Token packing (Section 3.2 "Token Packing"), the scatter back, and their transposes.
+// All kernels move feature rows with 16-byte accesses and are bandwidth-bound.
+//
+// spa_pack is ONE launch with no scratch memory and no inter-workgroup dependency: a
+// workgroup owns one tile of <= 256 consecutive tokens of one image, counts the selected
+// tokens that precede its tile (from the per-image counts when the caller has them, else
+// from the mask bytes themselves — B*N bytes that sit in L2), ranks its own tokens with
+// wave ballots, and copies its survivors' rows to their final place.
+#include "spa_common.h"
+
+namespace spa {
+
+constexpr int kPackThreads = 256;
+constexpr int kPackWaves = kPackThreads / kWave;
+
+// number of non-zero bytes in a 32-bit word
+__device__ __forceinline__ int nonzero_bytes(uint32_t w) {
+  uint32_t t = (((w & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | w) & 0x80808080u;
+  return __popc(t);
+}
+
+// Sum over the workgroup; every thread gets the result.  red: kPackWaves ints of LDS.
+__device__ __forceinline__ int block_sum(int v, int* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  __syncthreads();
+  if (lane_id() == 0) red[threadIdx.x / kWave] = v;
+  __syncthreads();
+  int s = 0;
+#pragma unroll
+  for (int i = 0; i < kPackWaves; ++i) s += red[i];
+  return s;
+}
+
+// Non-zero bytes of m[0 .. n), counted cooperatively by the workgroup (partial per thread).
+__device__ __forceinline__ int count_bytes_partial(const uint8_t* m, long n) {
+  int cnt = 0;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(m);
+  long head = (16 - (a & 15)) & 15;
+  if (head > n) head = n;
+  for (long i = threadIdx.x; i < head; i += kPackThreads) cnt += m[i] != 0;
+  const long nvec = (n - head) / 16;
+  const uintx4* mv = reinterpret_cast<const uintx4*>(m + head);
+  for (long i = threadIdx.x; i < nvec; i += kPackThreads) {
+    uintx4 v = mv[i];
+    cnt += nonzero_bytes(v[0]) + nonzero_bytes(v[1]) + nonzero_bytes(v[2]) + nonzero_bytes(v[3]);
+  }
+  for (long i = head + nvec * 16 + threadIdx.x; i < n; i += kPackThreads) cnt += m[i] != 0;
+  return cnt;
+}
+
+template <typename T, bool kScale>
+__global__ void __launch_bounds__(kPackThreads)
+pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
+            const int32_t* __restrict__ counts, const float* __restrict__ gate_scores,
+            int B, int N, int C, int tile, int tiles_per_image, int container_len,
+            T* __restrict__ packed, int32_t* __restrict__ cu_seqlens,
+            int32_t* __restrict__ gather_idx, int32_t* __restrict__ inv_pos,
+            int32_t* __restrict__ total) {
+  constexpr int VE = 16 / sizeof(T);
+  __shared__ int red[kPackWaves];
+  __shared__ int wave_cnt[kPackWaves];
+  __shared__ int sel_src[kPackThreads];
+  __shared__ float sel_scale[kPackThreads];
+
+  const int b = blockIdx.x / tiles_per_image;
+  const int t = blockIdx.x % tiles_per_image;
+  const int tile_start = t * tile;
+  const int tile_n = min(tile, N - tile_start);
+  const long flat0 = (long)b * N + tile_start;
+
+  // 1. selected tokens before this tile
+  int part = 0;
+  if (counts != nullptr) {
+    for (int i = threadIdx.x; i < b; i += kPackThreads) part += counts[i];
+    part += count_bytes_partial(mask + (long)b * N, tile_start);
+  } else {
+    part = count_bytes_partial(mask, flat0);
+  }
+  const int base = block_sum(part, red);
+
+  // 2. rank of each token of the tile among the tile's survivors
+  const int tid = threadIdx.x;
+  const bool in_tile = tid < tile_n;
+  const bool flag = in_tile && mask[flat0 + tid] != 0;
+  const uint64_t bal = __ballot(flag);
+  const int wv = tid / kWave;
+  if (lane_id() == 0) wave_cnt[wv] = __popcll(bal);
+  __syncthreads();
+  int wave_off = 0, nsel = 0;
+#pragma unroll
+  for (int i = 0; i < kPackWaves; ++i) {
+    const int c = wave_cnt[i];
+    if (i < wv) wave_off += c;
+    nsel += c;
+  }
+  const int local_rank = wave_off + rank_in_ballot(bal);
+  if (in_tile && inv_pos != nullptr) inv_pos[flat0 + tid] = flag ? base + local_rank : -1;
+  if (flag) {
+    if (gather_idx != nullptr) gather_idx[base + local_rank] = (int32_t)(flat0 + tid);
+    sel_src[local_rank] = tid;
+    if (kScale) sel_scale[local_rank] = sigmoidf_dev(gate_scores[flat0 + tid]);
+  }
+  if (t == 0 && tid == 0 && cu_seqlens != nullptr) cu_seqlens[b] = base;
+  __syncthreads();
+
+  const int chunks = C / VE;
+  // 3. the last tile knows T: publish it and zero the tail of the last container
+  if (b == B - 1 && t == tiles_per_image - 1) {
+    const int T_sel = base + nsel;
+    if (tid == 0) {
+      if (cu_seqlens != nullptr) cu_seqlens[B] = T_sel;
+      if (total != nullptr) total[0] = T_sel;
+    }
+    if (container_len > 0) {
+      const long t_pad = ((long)T_sel + container_len - 1) / container_len * container_len;
+      const long nz = (t_pad - T_sel) * chunks;
+      uintx4* dst = reinterpret_cast<uintx4*>(packed + (long)T_sel * C);
+      const uintx4 z = {0u, 0u, 0u, 0u};
+      for (long i = tid; i < nz; i += kPackThreads) dst[i] = z;
+    }
+  }
+
+  // 4. copy the survivors' rows: consecutive threads take consecutive 16-byte chunks
+  const long work = (long)nsel * chunks;
+  for (long i = tid; i < work; i += kPackThreads) {
+    const int r = (int)(i / chunks);
+    const int ch = (int)(i - (long)r * chunks);
+    const T* src = x + (flat0 + sel_src[r]) * (long)C + ch * VE;
+    T* dst = packed + ((long)base + r) * C + ch * VE;
+    if (kScale) {
+      const float sc = sel_scale[r];
+      if constexpr (sizeof(T) == 2) {
+        floatx8 v = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(src));
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= sc;
+        *reinterpret_cast<bf16x8*>(dst) = float_to_bf16x8(v);
+      } else {
+        floatx4 v = *reinterpret_cast<const floatx4*>(src);
+        v *= sc;
+        *reinterpret_cast<floatx4*>(dst) = v;
+      }
+    } else {
+      *reinterpret_cast<uintx4*>(dst) = *reinterpret_cast<const uintx4*>(src);
+    }
+  }
+}
+
+// y[i] = base[i] (+ src[inv[i]]) or src[inv[i]] or 0, one 16-byte chunk per thread.
+template <typename T, bool kBase>
+__global__ void __launch_bounds__(256)
+unpack_kernel(const T* __restrict__ src, const int32_t* __restrict__ inv_pos,
+              const T* base, long rows, int C, T* y) {
+  constexpr int VE = 16 / sizeof(T);
+  const int chunks = C / VE;
+  const long work = rows * chunks;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < work; i += (long)gridDim.x * blockDim.x) {
+    const long r = i / chunks;
+    const int ch = (int)(i - r * chunks);
+    const int j = inv_pos[r];
+    uintx4 v = {0u, 0u, 0u, 0u};
+    if (j >= 0) v = *reinterpret_cast<const uintx4*>(src + (long)j * C + ch * VE);
+    if (kBase) {
+      const uintx4 bv = *reinterpret_cast<const uintx4*>(base + r * C + ch * VE);
+      if (j >= 0) {
+        if constexpr (sizeof(T) == 2) {
+          floatx8 a = bf16x8_to_float(__builtin_bit_cast(bf16x8, v));
+          floatx8 c = bf16x8_to_float(__builtin_bit_cast(bf16x8, bv));
+          v = __builtin_bit_cast(uintx4, float_to_bf16x8(a + c));
+        } else {
+          v = __builtin_bit_cast(uintx4, __builtin_bit_cast(floatx4, v) + __builtin_bit_cast(floatx4, bv));
+        }
+      } else {
+        v = bv;
+      }
+    }
+    *reinterpret_cast<uintx4*>(y + r * C + ch * VE) = v;
+  }
+}
+
+// dst[j] = src[idx[j]] for j < *total (rows of `bytes16` 16-byte chunks)
+__global__ void __launch_bounds__(256)
+gather_rows_kernel(const uintx4* __restrict__ src, const int32_t* __restrict__ idx,
+                   const int32_t* __restrict__ total, long cap_rows, int chunks,
+                   uintx4* __restrict__ dst) {
+  const long rows = min((long)total[0], cap_rows);
+  const long work = rows * chunks;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < work; i += (long)gridDim.x * blockDim.x) {
+    const long r = i / chunks;
+    const int ch = (int)(i - r * chunks);
+    dst[r * chunks + ch] = src[(long)idx[r] * chunks + ch];
+  }
+}
+
+static int pick_tile(int B, int N, bool have_counts) {
+  // Small tiles give more workgroups (bandwidth), but without per-image counts every
+  // workgroup re-reads the mask prefix, so keep tiles larger when B*N is large.
+  const long want = (!have_counts && (long)B * N > 16384) ? 512 : 1024;
+  int tile = 256;
+  while (tile > 32 && (long)B * ((N + tile - 1) / tile) < want) tile >>= 1;
+  return tile;
+}
+
+static int check_rows(const char* fn, int B, int N, int C, int dtype) {
+  SPA_REQUIRE(B >= 1 && N >= 1 && C >= 1, SPA_ERR_INVALID_ARG, "%s: B, N, C must be >= 1", fn);
+  SPA_REQUIRE((long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*N must be < 2^31", fn);
+  SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
+  SPA_REQUIRE(((long)C * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG,
+              "%s: row length C*elem = %ld bytes is not a multiple of 16", fn, (long)C * elem_size(dtype));
+  return SPA_OK;
+}
+
+static unsigned grid_for(long work, int threads) {
+  long g = (work + threads - 1) / threads;
+  if (g > 16384) g = 16384;
+  if (g < 1) g = 1;
+  return (unsigned)g;
+}
+
+template <typename T>
+static void launch_unpack(const void* src, const int32_t* inv, const void* base, long rows, int C,
+                          void* y, hipStream_t st) {
+  constexpr int VE = 16 / sizeof(T);
+  const unsigned g = grid_for(rows * (C / VE), 256);
+  if (base != nullptr)
+    hipLaunchKernelGGL((unpack_kernel<T, true>), dim3(g), dim3(256), 0, st, static_cast<const T*>(src), inv,
+                       static_cast<const T*>(base), rows, C, static_cast<T*>(y));
+  else
+    hipLaunchKernelGGL((unpack_kernel<T, false>), dim3(g), dim3(256), 0, st, static_cast<const T*>(src), inv,
+                       static_cast<const T*>(nullptr), rows, C, static_cast<T*>(y));
+}
+
+}  // namespace spa
+
+using namespace spa;
+
+extern "C" int spa_pack(const void* x, const uint8_t* mask, const int32_t* counts,
+                        const float* gate_scores, int B, int N, int C, int dtype, int container_len,
+                        void* packed, int32_t* cu_seqlens, int32_t* gather_idx, int32_t* inv_pos,
+                        int32_t* total, void* stream) {
+  SPA_REQUIRE(x && mask && packed, SPA_ERR_INVALID_ARG, "spa_pack: null pointer");
+  if (int rc = check_rows("spa_pack", B, N, C, dtype)) return rc;
+  SPA_REQUIRE(container_len >= 0, SPA_ERR_INVALID_ARG, "spa_pack: container_len must be >= 0");
+  SPA_REQUIRE(aligned16(x) && aligned16(packed), SPA_ERR_INVALID_ARG, "spa_pack: x / packed not 16-byte aligned");
+  const int tile = pick_tile(B, N, counts != nullptr);
+  const int tpi = (N + tile - 1) / tile;
+  SPA_REQUIRE((long)B * tpi < 2147483647L, SPA_ERR_INVALID_ARG, "spa_pack: too many tiles");
+  const dim3 grid((unsigned)((long)B * tpi)), block(kPackThreads);
+  hipStream_t st = as_stream(stream);
+#define SPA_PACK_LAUNCH(T, S)                                                                        \
+  hipLaunchKernelGGL((pack_kernel<T, S>), grid, block, 0, st, static_cast<const T*>(x), mask, counts, \
+                     gate_scores, B, N, C, tile, tpi, container_len, static_cast<T*>(packed),        \
+                     cu_seqlens, gather_idx, inv_pos, total)
+  if (dtype == SPA_F32) {
+    if (gate_scores) SPA_PACK_LAUNCH(float, true); else SPA_PACK_LAUNCH(float, false);
+  } else {
+    if (gate_scores) SPA_PACK_LAUNCH(__bf16, true); else SPA_PACK_LAUNCH(__bf16, false);
+  }
+#undef SPA_PACK_LAUNCH
+  return check_launch("spa_pack");
+}
+
+extern "C" int spa_unpack(const void* packed_out, const int32_t* inv_pos, const void* base,
+                          int B, int N, int C, int dtype, void* y, void* stream) {
+  SPA_REQUIRE(packed_out && inv_pos && y, SPA_ERR_INVALID_ARG, "spa_unpack: null pointer");
+  if (int rc = check_rows("spa_unpack", B, N, C, dtype)) return rc;
+  SPA_REQUIRE(aligned16(packed_out) && aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG,
+              "spa_unpack: buffers not 16-byte aligned");
+  if (dtype == SPA_F32) launch_unpack<float>(packed_out, inv_pos, base, (long)B * N, C, y, as_stream(stream));
+  else launch_unpack<__bf16>(packed_out, inv_pos, base, (long)B * N, C, y, as_stream(stream));
+  return check_launch("spa_unpack");
+}
+
+extern "C" int spa_pack_bwd(const void* dpacked, const int32_t* inv_pos, int B, int N, int C,
+                            int dtype, void* d_rg, void* stream) {
+  SPA_REQUIRE(dpacked && inv_pos && d_rg, SPA_ERR_INVALID_ARG, "spa_pack_bwd: null pointer");
+  if (int rc = check_rows("spa_pack_bwd", B, N, C, dtype)) return rc;
+  SPA_REQUIRE(aligned16(dpacked) && aligned16(d_rg), SPA_ERR_INVALID_ARG, "spa_pack_bwd: buffers not 16-byte aligned");
+  if (dtype == SPA_F32) launch_unpack<float>(dpacked, inv_pos, nullptr, (long)B * N, C, d_rg, as_stream(stream));
+  else launch_unpack<__bf16>(dpacked, inv_pos, nullptr, (long)B * N, C, d_rg, as_stream(stream));
+  return check_launch("spa_pack_bwd");
+}
+
+extern "C" int spa_unpack_bwd(const void* dy, const int32_t* gather_idx, const int32_t* total,
+                              int B, int N, int C, int dtype, void* dout, void* stream) {
+  SPA_REQUIRE(dy && gather_idx && total && dout, SPA_ERR_INVALID_ARG, "spa_unpack_bwd: null pointer");
+  if (int rc = check_rows("spa_unpack_bwd", B, N, C, dtype)) return rc;
+  SPA_REQUIRE(aligned16(dy) && aligned16(dout), SPA_ERR_INVALID_ARG, "spa_unpack_bwd: buffers not 16-byte aligned");
+  const int chunks = (int)((long)C * elem_size(dtype) / 16);
+  const long cap = (long)B * N;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(grid_for(cap * chunks, 256)), dim3(256), 0, as_stream(stream),
+                     static_cast<const uintx4*>(dy), gather_idx, total, cap, chunks, static_cast<uintx4*>(dout));
+  return check_launch("spa_unpack_bwd");
+}

@@ -1,0 +1,175 @@
+"""ctypes binding over libspa.so: same names as the C entry points in include/spa.h.
+
+Argument marshalling only — torch tensors supply device memory and the current stream;
+every step of the path runs in the library's HIP kernels.  There is no fallback: if the
+shared library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_float, c_int, c_int64, c_size_t, c_void_p
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspa.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2410_23608_amd.build` "
+        "(the SPA path has no CPU or PyTorch fallback)")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+SPA_OK, SPA_F32, SPA_BF16 = 0, 0, 1
+
+_P = c_void_p
+_SIGNATURES = {
+    "spa_version": (c_int, []),
+    "spa_last_error": (c_char_p, []),
+    "spa_gate_select": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, _P, _P, _P, _P]),
+    "spa_maxpool2x2": (c_int, [_P, c_int, c_int, c_int, _P, _P]),
+    "spa_pack": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, _P, _P, _P, _P, _P, _P]),
+    "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
+    "spa_unpack": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
+    "spa_unpack_bwd": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
+    "spa_pack_bwd": (c_int, [_P, _P, c_int, c_int, c_int, c_int, _P, _P]),
+    "spa_attention_bwd_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int, c_int]),
+    "spa_packed_attention_bwd": (c_int, [_P, _P, _P, c_int64, _P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int,
+                                         c_float, _P, _P, _P, c_int64, _P, c_size_t, _P]),
+    "spa_gate_bwd_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int]),
+    "spa_gate_bwd": (c_int, [_P, _P, c_float, _P, _P, _P, _P, c_int, c_float, c_int, c_int, c_int, c_int,
+                             _P, _P, _P, _P, _P, c_size_t, _P]),
+    "spa_padded_attention": (c_int, [_P, _P, _P, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P]),
+}
+for _name, (_res, _args) in _SIGNATURES.items():
+    _fn = getattr(lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+EXPORTS = tuple(_SIGNATURES)
+
+
+class SpaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libspa error {code}: {msg}")
+        self.code = code
+
+
+def _check(rc: int) -> None:
+    if rc != SPA_OK:
+        raise SpaError(rc, lib.spa_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libspa takes device tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SPA_F32
+    if t.dtype == torch.bfloat16:
+        return SPA_BF16
+    raise ValueError(f"unsupported dtype {t.dtype}")
+
+
+def _contig(*ts):
+    for t in ts:
+        if t is not None and not t.is_contiguous():
+            raise ValueError("libspa takes contiguous tensors")
+
+
+def spa_version() -> int:
+    return lib.spa_version()
+
+
+def spa_gate_select(x, w, bias, s_up, tau, scores, mask, counts=None):
+    """x [B,N,C]; w [C]; s_up [B,N] f32 or None -> scores [B,N] f32, mask [B,N] u8, counts [B] i32."""
+    B, N, C = x.shape
+    _contig(x, w, s_up, scores, mask, counts)
+    _check(lib.spa_gate_select(_ptr(x), _ptr(w), float(bias), _ptr(s_up), float(tau), B, N, C, dtype_code(x),
+                               _ptr(scores), _ptr(mask), _ptr(counts), _stream()))
+
+
+def spa_maxpool2x2(s, h, w, pooled):
+    B = s.shape[0]
+    _contig(s, pooled)
+    _check(lib.spa_maxpool2x2(_ptr(s), B, h, w, _ptr(pooled), _stream()))
+
+
+def spa_pack(x, mask, counts, gate_scores, container_len, packed, cu_seqlens, gather_idx, inv_pos, total):
+    """x [B,N,C] (C may be a fused q|k|v row) -> packed [cap,C], cu_seqlens [B+1], gather_idx, inv_pos, total."""
+    B, N, C = x.shape
+    _contig(x, mask, counts, gate_scores, packed, cu_seqlens, gather_idx, inv_pos, total)
+    _check(lib.spa_pack(_ptr(x), _ptr(mask), _ptr(counts), _ptr(gate_scores), B, N, C, dtype_code(x),
+                        int(container_len), _ptr(packed), _ptr(cu_seqlens), _ptr(gather_idx), _ptr(inv_pos),
+                        _ptr(total), _stream()))
+
+
+def spa_packed_attention(q, k, v, row_stride, cu_seqlens, B, max_seqlen, H, Dh, out, lse=None, softmax_scale=0.0):
+    """q, k, v: tensors (or views into one fused packed buffer) whose element (j,h,d) sits at
+    data_ptr + (j*row_stride + h*Dh + d) elements."""
+    _contig(out, lse, cu_seqlens)
+    _check(lib.spa_packed_attention(_ptr(q), _ptr(k), _ptr(v), int(row_stride), _ptr(cu_seqlens), B, max_seqlen,
+                                    H, Dh, dtype_code(out), float(softmax_scale), _ptr(out), _ptr(lse), _stream()))
+
+
+def spa_unpack(packed_out, inv_pos, base, y):
+    B, N, C = y.shape
+    _contig(packed_out, inv_pos, base, y)
+    _check(lib.spa_unpack(_ptr(packed_out), _ptr(inv_pos), _ptr(base), B, N, C, dtype_code(y), _ptr(y), _stream()))
+
+
+def spa_unpack_bwd(dy, gather_idx, total, dout):
+    B, N, C = dy.shape
+    _contig(dy, gather_idx, total, dout)
+    _check(lib.spa_unpack_bwd(_ptr(dy), _ptr(gather_idx), _ptr(total), B, N, C, dtype_code(dy), _ptr(dout), _stream()))
+
+
+def spa_pack_bwd(dpacked, inv_pos, d_rg):
+    B, N, C = d_rg.shape
+    _contig(dpacked, inv_pos, d_rg)
+    _check(lib.spa_pack_bwd(_ptr(dpacked), _ptr(inv_pos), B, N, C, dtype_code(d_rg), _ptr(d_rg), _stream()))
+
+
+def spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype) -> int:
+    return int(lib.spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype))
+
+
+def spa_packed_attention_bwd(q, k, v, row_stride, out, dout, lse, cu_seqlens, B, max_seqlen, H, Dh,
+                             dq, dk, dv, grad_row_stride, workspace, softmax_scale=0.0):
+    _contig(out, dout, lse, cu_seqlens, workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.spa_packed_attention_bwd(_ptr(q), _ptr(k), _ptr(v), int(row_stride), _ptr(out), _ptr(dout), _ptr(lse),
+                                        _ptr(cu_seqlens), B, max_seqlen, H, Dh, dtype_code(out), float(softmax_scale),
+                                        _ptr(dq), _ptr(dk), _ptr(dv), int(grad_row_stride), _ptr(workspace),
+                                        ws_bytes, _stream()))
+
+
+def spa_gate_bwd_workspace_bytes(B, N, C, dtype) -> int:
+    return int(lib.spa_gate_bwd_workspace_bytes(B, N, C, dtype))
+
+
+def spa_gate_bwd(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, loss, dx, dw, db, workspace):
+    B, N, C = x.shape
+    _contig(x, w, scores, s_up, labels, d_rg, loss, dx, dw, db, workspace)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.spa_gate_bwd(_ptr(x), _ptr(w), float(bias), _ptr(scores), _ptr(s_up), _ptr(labels), _ptr(d_rg),
+                            int(bool(gate_scaled)), float(loss_scale), B, N, C, dtype_code(x), _ptr(loss), _ptr(dx),
+                            _ptr(dw), _ptr(db), _ptr(workspace), ws_bytes, _stream()))
+
+
+def spa_padded_attention(q, k, v, row_stride, seqlens, B, n_pad, H, Dh, out, softmax_scale=0.0):
+    _contig(out, seqlens)
+    _check(lib.spa_padded_attention(_ptr(q), _ptr(k), _ptr(v), int(row_stride), _ptr(seqlens), B, n_pad, H, Dh,
+                                    dtype_code(out), float(softmax_scale), _ptr(out), _stream()))

@@ -1,0 +1,266 @@
+"""Parity of the HIP forward path against the CPU oracle, through the C-ABI binding.
+Integers (mask, counts, cu_seqlens, gather_idx, inv_pos, total) bit-exact; unscaled row
+copies bit-exact; fp32 values max-abs <= 1e-5; bf16 attention outputs max-abs <= 2e-2."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import spa_oracle as orc
+from paper_2410_23608_amd import workloads as wlmod
+from spa_harness import Forward, dev, host, tdtype
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+SCORE_TOL = {"f32": 1e-5, "bf16": 1e-3}
+
+
+@pytest.fixture(scope="module")
+def spa():
+    from paper_2410_23608_amd import spa as mod
+    return mod
+
+
+def small(wl, B):
+    return dataclasses.replace(wl, B=B)
+
+
+CASES = [
+    ("tiny", None),          # fp32, Dh 32, the whole tiny workload
+    ("vit_s", 8),            # bf16, Dh 64, N=196 (ragged 64/32 tails)
+    ("vit_b_train", 4),      # bf16, Dh 64, C=768
+    ("det", 2),              # bf16, Dh 32, N=4200, long segments (many key tiles)
+]
+
+
+def run_case(spa, wl, seed, container_len=0, use_counts=True, s_up=None, base=None):
+    bun = wlmod.generate(wl, seed)
+    ref = orc.spa_forward(bun["x"], bun["w"], bun["bias"], bun["qkv"], wl.H, wl.tau, wl.dtype,
+                          s_up=s_up, container_len=container_len, base=base)
+    f = Forward(spa, wl.B, wl.N, wl.C, wl.H, wl.dtype, container_len, use_counts)
+    f.run(dev(bun["x"], wl.dtype), dev(bun["w"], wl.dtype), bun["bias"], dev(bun["qkv"], wl.dtype), wl.tau,
+          s_up=None if s_up is None else dev(s_up.astype(np.float32)),
+          base=None if base is None else dev(base, wl.dtype))
+    torch.cuda.synchronize()
+    return bun, ref, f
+
+
+def check_forward(wl, bun, ref, f, container_len=0):
+    T = ref["total"]
+    assert ref["margin"] > 1e-3                      # bit-exact masks are well defined
+    s = host(f.scores)
+    assert np.max(np.abs(s - ref["scores"]) / (1 + np.abs(ref["scores"]))) <= SCORE_TOL[wl.dtype]
+    assert np.array_equal(host(f.mask), ref["mask"])
+    if f.counts is not None:
+        assert np.array_equal(host(f.counts), ref["counts"])
+    assert np.array_equal(host(f.cu), ref["cu_seqlens"])
+    assert int(host(f.total)[0]) == T
+    assert np.array_equal(host(f.gidx)[:T], ref["gather_idx"])
+    assert np.all(host(f.gidx)[T:] == -7)            # nothing written past T
+    assert np.array_equal(host(f.inv), ref["inv_pos"])
+    pq = host(f.packed_qkv)
+    t_pad = ref["packed_qkv"].shape[0]
+    assert np.array_equal(pq[:t_pad].astype(np.float64), ref["packed_qkv"])     # bit-exact copies, zero pad rows
+    assert np.all(np.isnan(pq[t_pad:]))              # canary rows untouched
+    out = host(f.out)
+    assert np.all(np.isnan(out[T:]))
+    err = np.max(np.abs(out[:T] - ref["out"])) if T else 0.0
+    assert err <= TOL[wl.dtype], err
+    lse = host(f.lse)
+    assert np.max(np.abs(lse[:, :T] - ref["lse"])) <= 1e-3 if T else True
+    y = host(f.y)
+    assert np.max(np.abs(y - ref["y"])) <= TOL[wl.dtype]
+    return err
+
+
+@pytest.mark.parametrize("name,B", CASES)
+def test_forward_chain_matches_oracle(spa, name, B):
+    wl = wlmod.WORKLOADS[name]
+    if B is not None:
+        wl = small(wl, B)
+    bun, ref, f = run_case(spa, wl, seed=0)
+    check_forward(wl, bun, ref, f)
+    # unselected rows of y are exactly zero, selected rows are exact copies of the packed output
+    y, out, inv = host(f.y).reshape(-1, wl.C), host(f.out), ref["inv_pos"]
+    assert np.all(y[inv < 0] == 0)
+    assert np.array_equal(y[inv >= 0], out[inv[inv >= 0]])
+
+
+@pytest.mark.parametrize("name,B", [("tiny", None), ("vit_s", 4)])
+def test_forward_without_counts_and_with_containers(spa, name, B):
+    wl = wlmod.WORKLOADS[name]
+    if B is not None:
+        wl = small(wl, B)
+    bun, ref, f = run_case(spa, wl, seed=1, container_len=49, use_counts=False)
+    check_forward(wl, bun, ref, f, 49)
+    T = ref["total"]
+    assert ref["packed_qkv"].shape[0] == -(-T // 49) * 49
+
+
+def test_forward_with_upscale_scores_and_base(spa):
+    wl = small(wlmod.WORKLOADS["vit_s"], 4)
+    rng = np.random.default_rng(5)
+    # up-scale scores: mostly far below, sometimes well above the threshold (adds tokens)
+    s_up = np.where(rng.uniform(size=(wl.B, wl.N)) < 0.2, 3.0, -9.0) + rng.uniform(0, 1, size=(wl.B, wl.N))
+    s_up = s_up.astype(np.float32)
+    base = wlmod.round_bf16(rng.standard_normal((wl.B, wl.N, wl.C)).astype(np.float32))
+    bun, ref, f = run_case(spa, wl, seed=2, s_up=s_up, base=base)
+    assert ref["mask"].sum() > bun["planted_mask"].sum()
+    # y = base (+ out): compare against the oracle evaluated on the device's own bf16 out
+    T = ref["total"]
+    assert np.array_equal(host(f.mask), ref["mask"])
+    assert np.array_equal(host(f.inv), ref["inv_pos"])
+    assert np.max(np.abs(host(f.out)[:T] - ref["out"])) <= TOL["bf16"]
+    y = host(f.y)
+    sel = ref["mask"].astype(bool)
+    assert np.array_equal(y[~sel], base[~sel])
+    assert np.max(np.abs(y - ref["y"])) <= 2 * TOL["bf16"]      # two bf16 roundings (out, then the sum)
+
+
+def test_gate_scaled_pack(spa):
+    # r_g = Sigmoid(s) . r on the packed rows
+    for name, B in (("tiny", None), ("vit_s", 4)):
+        wl = wlmod.WORKLOADS[name]
+        if B is not None:
+            wl = small(wl, B)
+        bun = wlmod.generate(wl, 3, with_qkv=False)
+        s = orc.gate_scores(bun["x"], bun["w"], bun["bias"])
+        mask, _ = orc.select(s, wl.tau)
+        cu, gidx, inv, T = orc.pack_indices(mask)
+        ref = orc.pack_rows(bun["x"], gidx, s.astype(np.float32), 0, wl.dtype)
+        cap = wl.B * wl.N
+        packed = torch.full((cap, wl.C), float("nan"), dtype=tdtype(wl.dtype), device="cuda")
+        cu_d = torch.empty(wl.B + 1, dtype=torch.int32, device="cuda")
+        spa.spa_pack(dev(bun["x"], wl.dtype), dev(mask), None, dev(s.astype(np.float32)), 0, packed, cu_d,
+                     None, None, None)
+        torch.cuda.synchronize()
+        got = host(packed)
+        assert np.array_equal(host(cu_d), cu)
+        tol = 1e-6 if wl.dtype == "f32" else 2.0 ** -7       # one bf16 ulp at |x| < 4 ... rounding of the product
+        assert np.max(np.abs(got[:T] - ref) / np.maximum(1.0, np.abs(ref))) <= tol
+        assert np.all(np.isnan(got[T:]))
+
+
+def _attention_only(spa, q, k, v, mask, H, dtype, want_lse=True):
+    """Packs q|k|v with a given mask on the device and runs the packed attention."""
+    B, N, C = q.shape
+    qkv = np.concatenate([q, k, v], axis=2).astype(np.float32)
+    cap = B * N
+    td = tdtype(dtype)
+    packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    inv = torch.empty(cap, dtype=torch.int32, device="cuda")
+    out = torch.full((cap, C), float("nan"), dtype=td, device="cuda")
+    lse = torch.full((H, cap), float("nan"), dtype=torch.float32, device="cuda")
+    spa.spa_pack(dev(qkv, dtype), dev(mask), None, None, 0, packed, cu, None, inv, None)
+    spa.spa_packed_attention(packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:], 3 * C, cu, B, N, H, C // H,
+                             out, lse if want_lse else None)
+    torch.cuda.synchronize()
+    return host(out), host(lse), host(cu), host(inv)
+
+
+@pytest.mark.parametrize("dtype,Dh", [("f32", 32), ("f32", 64), ("bf16", 32), ("bf16", 64)])
+def test_attention_edge_cases(spa, dtype, Dh):
+    """empty images, single-token segments, all selected, lengths around the 32/64/128 tile edges."""
+    H = 2
+    C = H * Dh
+    lens = [0, 1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200, 0, 257]
+    B, N = len(lens), 257
+    rng = np.random.default_rng(11)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    q, k, v = (mk(rng.standard_normal((B, N, C)).astype(np.float32)) for _ in range(3))
+    mask = np.zeros((B, N), np.uint8)
+    for b, n in enumerate(lens):
+        mask[b, rng.permutation(N)[:n]] = 1
+    assert mask[-1].all()                                     # last image: every token selected
+    ref_out, ref_lse = orc.attention_per_image(q, k, v, mask, H)
+    out, lse, cu, inv = _attention_only(spa, q, k, v, mask, H, dtype)
+    T = int(mask.sum())
+    assert np.array_equal(cu, orc.pack_indices(mask)[0])
+    assert np.max(np.abs(out[:T] - ref_out)) <= TOL[dtype]
+    assert np.max(np.abs(lse[:, :T] - ref_lse)) <= (1e-5 if dtype == "f32" else 1e-3) * (1 + np.abs(ref_lse).max())
+    assert np.all(np.isnan(out[T:]))
+    # single-token segment: O = v exactly
+    j = cu[1]
+    assert np.array_equal(out[j], v[1, mask[1].astype(bool)][0])
+    # all selected == ordinary full self-attention of that image (library softmax)
+    import scipy.special
+    b = B - 1
+    for h in range(H):
+        sl = slice(h * Dh, (h + 1) * Dh)
+        S = q[b, :, sl].astype(np.float64) @ k[b, :, sl].astype(np.float64).T / np.sqrt(Dh)
+        full = scipy.special.softmax(S, axis=1) @ v[b, :, sl].astype(np.float64)
+        assert np.max(np.abs(out[cu[b]:cu[b + 1], sl] - full)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attention_no_cross_image_leakage(spa, dtype):
+    """Poisoning every other image and every unselected token leaves an image's outputs
+    bit-identical (segments never mix)."""
+    B, N, H, Dh = 3, 150, 2, 32
+    C = H * Dh
+    rng = np.random.default_rng(12)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    q, k, v = (mk(rng.standard_normal((B, N, C)).astype(np.float32)) for _ in range(3))
+    mask = (rng.uniform(size=(B, N)) < 0.5).astype(np.uint8)
+    out0, _, cu, _ = _attention_only(spa, q, k, v, mask, H, dtype)
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    for t in (q2, k2, v2):
+        t[0] = 1e30
+        t[2] = -1e30
+        t[1, mask[1] == 0] = 1e30
+    out1, _, _, _ = _attention_only(spa, q2, k2, v2, mask, H, dtype)
+    assert np.array_equal(out0[cu[1]:cu[2]], out1[cu[1]:cu[2]])
+
+
+def test_all_unselected_batch_is_noop(spa):
+    wl = wlmod.WORKLOADS["tiny"]
+    bun = wlmod.generate(wl, 0)
+    f = Forward(spa, wl.B, wl.N, wl.C, wl.H, wl.dtype)
+    # bias far below the threshold: nothing selected
+    f.run(dev(bun["x"], "f32"), dev(bun["w"], "f32"), -1e4, dev(bun["qkv"], "f32"), wl.tau)
+    torch.cuda.synchronize()
+    assert int(host(f.total)[0]) == 0 and np.all(host(f.cu) == 0) and np.all(host(f.inv) == -1)
+    assert np.all(host(f.y) == 0) and np.all(np.isnan(host(f.out)))
+
+
+def test_padded_baseline_matches_oracle(spa):
+    """The padded-to-max baseline computes the same attention on the valid rows."""
+    B, H, Dh = 5, 2, 64
+    C = H * Dh
+    lens = np.array([40, 97, 1, 0, 130], np.int32)
+    n_pad = int(lens.max())
+    rng = np.random.default_rng(13)
+    q, k, v = (wlmod.round_bf16(rng.standard_normal((B, n_pad, C)).astype(np.float32)) for _ in range(3))
+    mask = (np.arange(n_pad)[None, :] < lens[:, None]).astype(np.uint8)
+    ref, _ = orc.attention_per_image(q, k, v, mask, H)
+    qkv = dev(np.concatenate([q, k, v], axis=2), "bf16")
+    out = torch.empty(B, n_pad, C, dtype=torch.bfloat16, device="cuda")
+    flat = qkv.view(B * n_pad, 3 * C)
+    spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], 3 * C, dev(lens), B, n_pad, H, Dh, out)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.all(np.isfinite(got))
+    row = 0
+    for b in range(B):
+        n = int(lens[b])
+        assert np.max(np.abs(got[b, :n] - ref[row:row + n]), initial=0.0) <= TOL["bf16"]
+        row += n
+
+
+def test_argument_validation_returns_errors_before_launch(spa):
+    x = torch.zeros(2, 8, 64, device="cuda")
+    w = torch.zeros(64, device="cuda")
+    scores = torch.empty(2, 8, device="cuda")
+    mask = torch.empty(2, 8, dtype=torch.uint8, device="cuda")
+    with pytest.raises(spa.SpaError) as e:
+        spa.spa_gate_select(x, w, 0.0, None, 1.5, scores, mask)
+    assert e.value.code == -1 and "tau" in str(e.value)
+    out = torch.empty(16, 48, device="cuda")
+    cu = torch.zeros(3, dtype=torch.int32, device="cuda")
+    with pytest.raises(spa.SpaError) as e:
+        spa.spa_packed_attention(out, out, out, 48, cu, 2, 8, 2, 24, out)
+    assert e.value.code == -2
+    torch.cuda.synchronize()
