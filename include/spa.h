@@ -112,15 +112,16 @@ int spa_pack(const void* x, const uint8_t* mask, const int32_t* counts, const fl
  * rows [cu_seqlens[b], cu_seqlens[b+1]):
  *   O = softmax(Q K^T * softmax_scale) V,   lse = log sum_j exp(S_ij)
  * The attention mask is never materialised; segments are addressed by cu_seqlens.
- * in:  q, k, v: packed rows, element (j, h, d) at ptr[j*row_stride + h*Dh + d]; the three
- *      may point into one fused [*, 3*H*Dh] buffer.  row_stride in elements.
+ * in:  q, k, v: packed rows, element (j, h, d) of q at q[j*q_row_stride + h*Dh + d] (likewise
+ *      k, v); the three may point into one fused [*, 3*H*Dh] buffer or into separate ones.
+ *      Row strides in elements.
  *      cu_seqlens [B+1] int32; max_seqlen >= every segment length (N); Dh in {32, 64};
  *      softmax_scale (host float; 0 means 1/sqrt(Dh)).
  * out: out [>= T, H*Dh] dtype, contiguous rows; lse [H, B*max_seqlen] fp32 or NULL
  *      (entry (h, j) for packed row j).  Rows >= T are not written.
  */
-int spa_packed_attention(const void* q, const void* k, const void* v, int64_t row_stride,
-                         const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
+int spa_packed_attention(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                         int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
                          int dtype, float softmax_scale, void* out, float* lse, void* stream);
 
 /*
@@ -158,17 +159,21 @@ size_t spa_attention_bwd_workspace_bytes(int B, int max_seqlen, int H, int Dh, i
  * Backward of spa_packed_attention (softmax-attention calculus per image and head):
  *   P = exp(S - lse), dV = P^T dO, dP = dO V^T, D_i = sum_d dO_id O_id,
  *   dS = P * (dP - D), dQ = dS K * scale, dK = dS^T Q * scale.
- * in:  q, k, v as in the forward (row_stride); out, dout [>= T, H*Dh] dtype contiguous;
+ * in:  q, k, v as in the forward (with their row strides); out, dout [>= T, H*Dh] dtype
+ *      contiguous;
  *      lse [H, B*max_seqlen] fp32 from the forward; workspace (device, 256-byte aligned)
  *      of at least spa_attention_bwd_workspace_bytes bytes.
- * out: dq, dk, dv: element (j,h,d) at ptr[j*grad_row_stride + h*Dh + d] (may point into one
- *      fused buffer).  Rows >= T are not written.  Results are run-to-run bit-stable.
+ * out: dq, dk, dv: element (j,h,d) of dq at dq[j*dq_row_stride + h*Dh + d] (likewise dk,
+ *      dv; they may point into one fused buffer).  Rows >= T are not written.  Results are
+ *      run-to-run bit-stable.
  */
-int spa_packed_attention_bwd(const void* q, const void* k, const void* v, int64_t row_stride,
+int spa_packed_attention_bwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                             int64_t k_row_stride, int64_t v_row_stride,
                              const void* out, const void* dout, const float* lse,
                              const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
                              int dtype, float softmax_scale,
-                             void* dq, void* dk, void* dv, int64_t grad_row_stride,
+                             void* dq, void* dk, void* dv, int64_t dq_row_stride,
+                             int64_t dk_row_stride, int64_t dv_row_stride,
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace spa_gate_bwd needs. Host. */

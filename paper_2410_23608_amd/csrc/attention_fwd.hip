@@ -46,7 +46,7 @@ constexpr int kBN = 64;   // keys per LDS tile
 template <int DH, int NW>
 __global__ void __launch_bounds__(64 * NW)
 attn_fwd_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                     const __bf16* __restrict__ v, long stride, const int32_t* __restrict__ cu,
+                     const __bf16* __restrict__ v, long qs, long ks, long vs, const int32_t* __restrict__ cu,
                      const int32_t* __restrict__ key_lens, int n_pad, int H, float scale_log2,
                      __bf16* __restrict__ out, float* __restrict__ lse, long lse_stride) {
   constexpr int KS = DH + 8;    // LDS row stride of the K tile (elements): conflict-free b128 reads
@@ -74,7 +74,7 @@ attn_fwd_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   for (int kk = 0; kk < KK; ++kk) {
     bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
     qf[kk] = z;
-    if (q_ok) qf[kk] = *reinterpret_cast<const bf16x8*>(q + (seg.row0 + qi) * stride + h * DH + kk * 16 + hh * 8);
+    if (q_ok) qf[kk] = *reinterpret_cast<const bf16x8*>(q + (seg.row0 + qi) * qs + h * DH + kk * 16 + hh * 8);
   }
 
   floatx16 o[DB];
@@ -92,9 +92,8 @@ attn_fwd_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
       bf16x8 kv = {0, 0, 0, 0, 0, 0, 0, 0};
       bf16x8 vv = kv;
       if (kt + r < seg.nk) {
-        const long off = (seg.row0 + kt + r) * stride + h * DH + c * 8;
-        kv = *reinterpret_cast<const bf16x8*>(k + off);
-        vv = *reinterpret_cast<const bf16x8*>(v + off);
+        kv = *reinterpret_cast<const bf16x8*>(k + (seg.row0 + kt + r) * ks + h * DH + c * 8);
+        vv = *reinterpret_cast<const bf16x8*>(v + (seg.row0 + kt + r) * vs + h * DH + c * 8);
       }
       *reinterpret_cast<bf16x8*>(&Ks[r * KS + c * 8]) = kv;
 #pragma unroll
@@ -180,7 +179,7 @@ attn_fwd_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 template <int DH>
 __global__ void __launch_bounds__(128)
 attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
-                    const float* __restrict__ v, long stride, const int32_t* __restrict__ cu,
+                    const float* __restrict__ v, long qs, long ks, long vs, const int32_t* __restrict__ cu,
                     const int32_t* __restrict__ key_lens, int n_pad, int H, float scale,
                     float* __restrict__ out, float* __restrict__ lse, long lse_stride) {
   constexpr int BM = 128, BN = 32;
@@ -200,7 +199,7 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
 #pragma unroll
   for (int d = 0; d < DH; ++d) { qr[d] = 0.f; o[d] = 0.f; }
   if (q_ok) {
-    const float* qp = q + (seg.row0 + qi) * stride + h * DH;
+    const float* qp = q + (seg.row0 + qi) * qs + h * DH;
 #pragma unroll
     for (int d = 0; d < DH; d += 4) {
       const floatx4 t = *reinterpret_cast<const floatx4*>(qp + d);
@@ -215,9 +214,8 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
       const int r = i / (DH / 4), c = i % (DH / 4);
       floatx4 kv = {0.f, 0.f, 0.f, 0.f}, vv = kv;
       if (kt + r < seg.nk) {
-        const long off = (seg.row0 + kt + r) * stride + h * DH + c * 4;
-        kv = *reinterpret_cast<const floatx4*>(k + off);
-        vv = *reinterpret_cast<const floatx4*>(v + off);
+        kv = *reinterpret_cast<const floatx4*>(k + (seg.row0 + kt + r) * ks + h * DH + c * 4);
+        vv = *reinterpret_cast<const floatx4*>(v + (seg.row0 + kt + r) * vs + h * DH + c * 4);
       }
       *reinterpret_cast<floatx4*>(&Ks[r * DH + c * 4]) = kv;
       *reinterpret_cast<floatx4*>(&Vs[r * DH + c * 4]) = vv;
@@ -261,7 +259,7 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
 
 // ------------------------------------------------------------------------------- host
 static int attention_common(const char* fn, const void* q, const void* k, const void* v,
-                            int64_t row_stride, const int32_t* cu, const int32_t* key_lens, int B,
+                            int64_t q_stride, int64_t k_stride, int64_t v_stride, const int32_t* cu, const int32_t* key_lens, int B,
                             int n_max, int H, int Dh, int dtype, float softmax_scale, void* out,
                             float* lse, void* stream) {
   SPA_REQUIRE(q && k && v && out && (cu || key_lens), SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
@@ -270,8 +268,11 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
   SPA_REQUIRE(B <= 65535 && H <= 65535, SPA_ERR_INVALID_ARG, "%s: B and H must be <= 65535", fn);
   SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
   SPA_REQUIRE(Dh == 32 || Dh == 64, SPA_ERR_UNSUPPORTED, "%s: head dim %d not supported (32 or 64)", fn, Dh);
-  SPA_REQUIRE(row_stride >= (int64_t)H * Dh, SPA_ERR_INVALID_ARG, "%s: row_stride %ld < H*Dh", fn, (long)row_stride);
-  SPA_REQUIRE((row_stride * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG, "%s: row stride is not a multiple of 16 bytes", fn);
+  const int64_t strides[3] = {q_stride, k_stride, v_stride};
+  for (int64_t rs : strides) {
+    SPA_REQUIRE(rs >= (int64_t)H * Dh, SPA_ERR_INVALID_ARG, "%s: row stride %ld < H*Dh", fn, (long)rs);
+    SPA_REQUIRE((rs * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG, "%s: row stride is not a multiple of 16 bytes", fn);
+  }
   SPA_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(out), SPA_ERR_INVALID_ARG,
               "%s: q/k/v/out not 16-byte aligned", fn);
   SPA_REQUIRE(softmax_scale >= 0.f && std::isfinite(softmax_scale), SPA_ERR_INVALID_ARG,
@@ -283,7 +284,7 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
     const dim3 grid((n_max + 127) / 128, H, B), block(128);
 #define SPA_F32_LAUNCH(D)                                                                                \
   hipLaunchKernelGGL((attn_fwd_f32_kernel<D>), grid, block, 0, st, (const float*)q, (const float*)k,    \
-                     (const float*)v, (long)row_stride, cu, key_lens, n_max, H, scale, (float*)out, lse, \
+                     (const float*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu, key_lens, n_max, H, scale, (float*)out, lse, \
                      lse_stride)
     if (Dh == 32) SPA_F32_LAUNCH(32); else SPA_F32_LAUNCH(64);
 #undef SPA_F32_LAUNCH
@@ -293,7 +294,7 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
     const dim3 grid((n_max + 32 * NW - 1) / (32 * NW), H, B), block(64 * NW);
 #define SPA_BF16_LAUNCH(D, W)                                                                              \
   hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, W>), grid, block, 0, st, (const __bf16*)q, (const __bf16*)k, \
-                     (const __bf16*)v, (long)row_stride, cu, key_lens, n_max, H, scale_log2, (__bf16*)out, \
+                     (const __bf16*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu, key_lens, n_max, H, scale_log2, (__bf16*)out, \
                      lse, lse_stride)
     if (Dh == 32) { if (NW == 2) SPA_BF16_LAUNCH(32, 2); else SPA_BF16_LAUNCH(32, 4); }
     else          { if (NW == 2) SPA_BF16_LAUNCH(64, 2); else SPA_BF16_LAUNCH(64, 4); }
@@ -306,11 +307,11 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
 
 using namespace spa;
 
-extern "C" int spa_packed_attention(const void* q, const void* k, const void* v, int64_t row_stride,
-                                    const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
+extern "C" int spa_packed_attention(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                    int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
                                     int dtype, float softmax_scale, void* out, float* lse, void* stream) {
   SPA_REQUIRE(cu_seqlens, SPA_ERR_INVALID_ARG, "spa_packed_attention: cu_seqlens is null");
-  return attention_common("spa_packed_attention", q, k, v, row_stride, cu_seqlens, nullptr, B, max_seqlen,
+  return attention_common("spa_packed_attention", q, k, v, q_row_stride, k_row_stride, v_row_stride, cu_seqlens, nullptr, B, max_seqlen,
                           H, Dh, dtype, softmax_scale, out, lse, stream);
 }
 
@@ -318,6 +319,6 @@ extern "C" int spa_padded_attention(const void* q, const void* k, const void* v,
                                     const int32_t* seqlens, int B, int n_pad, int H, int Dh, int dtype,
                                     float softmax_scale, void* out, void* stream) {
   SPA_REQUIRE(seqlens, SPA_ERR_INVALID_ARG, "spa_padded_attention: seqlens is null");
-  return attention_common("spa_padded_attention", q, k, v, row_stride, nullptr, seqlens, B, n_pad, H, Dh,
+  return attention_common("spa_padded_attention", q, k, v, row_stride, row_stride, row_stride, nullptr, seqlens, B, n_pad, H, Dh,
                           dtype, softmax_scale, out, nullptr, stream);
 }

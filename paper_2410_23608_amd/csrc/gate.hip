@@ -50,8 +50,7 @@ template <typename T, int G>
 __global__ void __launch_bounds__(kGateThreads)
 gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
                    const float* __restrict__ s_up, float theta, int ntok, int N, int C,
-                   float* __restrict__ scores, uint8_t* __restrict__ mask,
-                   int32_t* __restrict__ counts) {
+                   float* __restrict__ scores, uint8_t* __restrict__ mask) {
   constexpr int VE = Vec16<T>::kElems;
   extern __shared__ float w_lds[];
   for (int c = threadIdx.x; c < C; c += kGateThreads) w_lds[c] = static_cast<float>(w[c]);
@@ -79,14 +78,22 @@ gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
       const bool sel = s > theta;
       scores[tok] = s;
       mask[tok] = sel ? 1 : 0;
-      if (counts != nullptr && sel) atomicAdd(&counts[tok / N], 1);
     }
   }
 }
 
-__global__ void zero_i32_kernel(int32_t* p, int n) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0;
+// counts[b] = selected tokens of image b: one workgroup per image, no atomics.
+__global__ void __launch_bounds__(256)
+count_selected_kernel(const uint8_t* __restrict__ mask, int N, int32_t* __restrict__ counts) {
+  __shared__ int red[4];
+  const uint8_t* m = mask + (long)blockIdx.x * N;
+  int c = 0;
+  for (int i = threadIdx.x; i < N; i += 256) c += m[i] != 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, kWave);
+  if (lane_id() == 0) red[threadIdx.x / kWave] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) counts[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
 __global__ void maxpool2x2_kernel(const float* __restrict__ s, int B, int h, int w,
@@ -102,6 +109,135 @@ __global__ void maxpool2x2_kernel(const float* __restrict__ s, int B, int h, int
   }
 }
 
+
+// ---------------------------------------------------------------------- gate backward
+// Selection loss (binary cross-entropy on sigmoid(s)) + gradient of r_g = sigmoid(s) . r.
+// A group of G lanes owns a token; the row's chunks live in registers (IT per lane), so x
+// and d_rg are read once.  dw / db / loss are reduced without atomics: lanes accumulate
+// over their tokens, groups are folded in a fixed order into LDS, every workgroup writes one
+// partial row, and a second kernel adds the partial rows in order.
+template <typename T, int G, int IT>
+__global__ void __launch_bounds__(kGateThreads)
+gate_bwd_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
+                const float* __restrict__ scores, const float* __restrict__ s_up,
+                const uint8_t* __restrict__ labels, const T* __restrict__ d_rg, int gate_scaled,
+                float loss_scale, int ntok, int C, T* __restrict__ dx, float* __restrict__ partial) {
+  constexpr int VE = Vec16<T>::kElems;
+  constexpr int kGroups = kGateThreads / G;
+  extern __shared__ float lds[];
+  float* w_lds = lds;            // [C]
+  float* sdw = lds + C;          // [C]
+  __shared__ float s_loss[kGroups], s_db[kGroups];
+  for (int c = threadIdx.x; c < C; c += kGateThreads) { w_lds[c] = static_cast<float>(w[c]); sdw[c] = 0.f; }
+  __syncthreads();
+
+  const int grp = threadIdx.x / G, gl = threadIdx.x % G;
+  const int chunks = C / VE;
+  const bool scaled = gate_scaled != 0 && d_rg != nullptr;
+  float dwa[IT][VE];
+#pragma unroll
+  for (int it = 0; it < IT; ++it)
+#pragma unroll
+    for (int e = 0; e < VE; ++e) dwa[it][e] = 0.f;
+  float loss_acc = 0.f, db_acc = 0.f;
+
+  for (long tok = (long)blockIdx.x * kGroups + grp; tok < ntok; tok += (long)gridDim.x * kGroups) {
+    float xr[IT][VE], dr[IT][VE];
+    float dot = 0.f, g = 0.f;
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int ch = gl + it * G;
+#pragma unroll
+      for (int e = 0; e < VE; ++e) { xr[it][e] = 0.f; dr[it][e] = 0.f; }
+      if (ch < chunks) {
+        Vec16<T>::load(x + tok * (long)C + ch * VE, xr[it]);
+        if (scaled) Vec16<T>::load(d_rg + tok * (long)C + ch * VE, dr[it]);
+#pragma unroll
+        for (int e = 0; e < VE; ++e) {
+          dot = fmaf(dr[it][e], xr[it][e], dot);
+          g = fmaf(xr[it][e], w_lds[ch * VE + e], g);
+        }
+      }
+    }
+    dot = group_sum<G>(dot);
+    const float s = scores[tok];
+    bool own = true;
+    if (s_up != nullptr) {
+      g = group_sum<G>(g) + bias;
+      own = g >= s_up[tok];                 // the up-scale score won the max: no gradient to (w, b)
+    }
+    const float p = sigmoidf_dev(s);
+    const float y = labels[tok] != 0 ? 1.f : 0.f;
+    float ds = loss_scale * (p - y);
+    if (scaled) ds = fmaf(p * (1.f - p), dot, ds);
+    const float dsg = own ? ds : 0.f;
+    const float pg = scaled ? p : 0.f;
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int ch = gl + it * G;
+      if (ch < chunks) {
+        float o[VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) {
+          o[e] = fmaf(dsg, w_lds[ch * VE + e], pg * dr[it][e]);
+          dwa[it][e] = fmaf(dsg, xr[it][e], dwa[it][e]);
+        }
+        Vec16<T>::store(dx + tok * (long)C + ch * VE, o);
+      }
+    }
+    if (gl == 0) {
+      loss_acc += fmaxf(s, 0.f) - y * s + log1pf(__expf(-fabsf(s)));
+      db_acc += dsg;
+    }
+  }
+
+  // fold the groups in a fixed order
+  for (int gsel = 0; gsel < kGroups; ++gsel) {
+    if (grp == gsel) {
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const int ch = gl + it * G;
+        if (ch < chunks) {
+#pragma unroll
+          for (int e = 0; e < VE; ++e) sdw[ch * VE + e] += dwa[it][e];
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (gl == 0) { s_loss[grp] = loss_acc; s_db[grp] = db_acc; }
+  __syncthreads();
+  float* prow = partial + (long)blockIdx.x * (C + 2);
+  for (int c = threadIdx.x; c < C; c += kGateThreads) prow[c] = sdw[c];
+  if (threadIdx.x == 0) {
+    float a = 0.f, b = 0.f;
+    for (int i = 0; i < kGroups; ++i) { a += s_loss[i]; b += s_db[i]; }
+    prow[C] = a;
+    prow[C + 1] = b;
+  }
+}
+
+__global__ void __launch_bounds__(256)
+gate_bwd_reduce_kernel(const float* __restrict__ partial, int nparts, int C, float loss_scale,
+                       float* __restrict__ loss, float* __restrict__ dw, float* __restrict__ db) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C + 2) return;
+  float a = 0.f;
+  for (int i = 0; i < nparts; ++i) a += partial[(long)i * (C + 2) + c];
+  if (c < C) dw[c] = a;
+  else if (c == C) loss[0] = a * loss_scale;
+  else db[0] = a;
+}
+
+constexpr int kGateBwdMaxParts = 1024;
+
+static int gate_bwd_parts(long ntok) {
+  long p = (ntok + 15) / 16;
+  if (p > kGateBwdMaxParts) p = kGateBwdMaxParts;
+  if (p < 1) p = 1;
+  return (int)p;
+}
+
 template <typename T>
 static int launch_gate(const void* x, const void* w, float bias, const float* s_up, float theta,
                        int B, int N, int C, float* scores, uint8_t* mask, int32_t* counts,
@@ -110,9 +246,6 @@ static int launch_gate(const void* x, const void* w, float bias, const float* s_
   const int chunks = C / VE;
   const long ntok = (long)B * N;
   const size_t lds = (size_t)C * sizeof(float);
-  if (counts != nullptr) {
-    hipLaunchKernelGGL(zero_i32_kernel, dim3((B + 255) / 256), dim3(256), 0, st, counts, B);
-  }
   auto go = [&](auto gtag) {
     constexpr int G = decltype(gtag)::value;
     const long per_wg = kGateThreads / G;
@@ -120,12 +253,14 @@ static int launch_gate(const void* x, const void* w, float bias, const float* s_
     if (wgs > 4096) wgs = 4096;
     hipLaunchKernelGGL((gate_select_kernel<T, G>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
                        static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, theta,
-                       (int)ntok, N, C, scores, mask, counts);
+                       (int)ntok, N, C, scores, mask);
   };
   if (chunks <= 8) go(std::integral_constant<int, 8>{});
   else if (chunks <= 64) go(std::integral_constant<int, 16>{});
   else if (chunks <= 256) go(std::integral_constant<int, 32>{});
   else go(std::integral_constant<int, 64>{});
+  if (counts != nullptr)
+    hipLaunchKernelGGL(count_selected_kernel, dim3(B), dim3(256), 0, st, mask, N, counts);
   return check_launch("spa_gate_select");
 }
 
@@ -160,4 +295,63 @@ extern "C" int spa_maxpool2x2(const float* s, int B, int h, int w, float* pooled
   if (wgs > 2048) wgs = 2048;
   hipLaunchKernelGGL(maxpool2x2_kernel, dim3((unsigned)wgs), dim3(256), 0, as_stream(stream), s, B, h, w, pooled);
   return check_launch("spa_maxpool2x2");
+}
+
+extern "C" size_t spa_gate_bwd_workspace_bytes(int B, int N, int C, int dtype) {
+  (void)dtype;
+  if (B < 1 || N < 1 || C < 1) return 0;
+  return (size_t)gate_bwd_parts((long)B * N) * (size_t)(C + 2) * sizeof(float);
+}
+
+template <typename T>
+static int launch_gate_bwd(const void* x, const void* w, float bias, const float* scores, const float* s_up,
+                           const uint8_t* labels, const void* d_rg, int gate_scaled, float loss_scale,
+                           long ntok, int C, float* loss, void* dx, float* dw, float* db, float* partial,
+                           hipStream_t st) {
+  constexpr int VE = Vec16<T>::kElems;
+  const int chunks = C / VE;
+  const int parts = gate_bwd_parts(ntok);
+  const size_t lds = 2 * (size_t)C * sizeof(float);
+#define SPA_GB(G, IT)                                                                                         \
+  hipLaunchKernelGGL((gate_bwd_kernel<T, G, IT>), dim3(parts), dim3(kGateThreads), lds, st,                  \
+                     static_cast<const T*>(x), static_cast<const T*>(w), bias, scores, s_up, labels,         \
+                     static_cast<const T*>(d_rg), gate_scaled, loss_scale, (int)ntok, C, static_cast<T*>(dx), \
+                     partial)
+  if (chunks <= 16) SPA_GB(16, 1);
+  else if (chunks <= 32) SPA_GB(16, 2);
+  else if (chunks <= 64) SPA_GB(16, 4);
+  else if (chunks <= 128) SPA_GB(16, 8);
+  else if (chunks <= 256) SPA_GB(64, 4);
+  else if (chunks <= 512) SPA_GB(64, 8);
+  else return fail(SPA_ERR_UNSUPPORTED, "spa_gate_bwd: C = %d too large (at most %d)", C, 512 * VE);
+#undef SPA_GB
+  hipLaunchKernelGGL(gate_bwd_reduce_kernel, dim3((C + 2 + 255) / 256), dim3(256), 0, st, partial, parts, C,
+                     loss_scale, loss, dw, db);
+  return check_launch("spa_gate_bwd");
+}
+
+extern "C" int spa_gate_bwd(const void* x, const void* w, float bias, const float* scores,
+                            const float* s_up, const uint8_t* labels, const void* d_rg, int gate_scaled,
+                            float loss_scale, int B, int N, int C, int dtype, float* loss, void* dx,
+                            float* dw, float* db, void* workspace, size_t workspace_bytes, void* stream) {
+  SPA_REQUIRE(x && w && scores && labels && loss && dx && dw && db, SPA_ERR_INVALID_ARG, "spa_gate_bwd: null pointer");
+  SPA_REQUIRE(B >= 1 && N >= 1 && C >= 1, SPA_ERR_INVALID_ARG, "spa_gate_bwd: B, N, C must be >= 1");
+  SPA_REQUIRE((long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "spa_gate_bwd: B*N must be < 2^31");
+  SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "spa_gate_bwd: unknown dtype %d", dtype);
+  SPA_REQUIRE(((long)C * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG,
+              "spa_gate_bwd: row length C*elem = %ld bytes is not a multiple of 16", (long)C * elem_size(dtype));
+  SPA_REQUIRE(aligned16(x) && aligned16(dx) && aligned16(d_rg), SPA_ERR_INVALID_ARG,
+              "spa_gate_bwd: x / dx / d_rg not 16-byte aligned");
+  SPA_REQUIRE(!(gate_scaled && !d_rg), SPA_ERR_INVALID_ARG, "spa_gate_bwd: gate_scaled needs d_rg");
+  SPA_REQUIRE(C <= kMaxGateC, SPA_ERR_UNSUPPORTED, "spa_gate_bwd: C = %d exceeds %d", C, kMaxGateC);
+  const size_t need = spa_gate_bwd_workspace_bytes(B, N, C, dtype);
+  SPA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SPA_ERR_WORKSPACE,
+              "spa_gate_bwd: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+  hipStream_t st = as_stream(stream);
+  float* partial = static_cast<float*>(workspace);
+  if (dtype == SPA_F32)
+    return launch_gate_bwd<float>(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, (long)B * N, C,
+                                  loss, dx, dw, db, partial, st);
+  return launch_gate_bwd<__bf16>(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, (long)B * N, C,
+                                 loss, dx, dw, db, partial, st);
 }

@@ -32,13 +32,14 @@ _SIGNATURES = {
     "spa_gate_select": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, _P, _P, _P, _P]),
     "spa_maxpool2x2": (c_int, [_P, c_int, c_int, c_int, _P, _P]),
     "spa_pack": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, _P, _P, _P, _P, _P, _P]),
-    "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
+    "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
     "spa_unpack": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_unpack_bwd": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_pack_bwd": (c_int, [_P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_attention_bwd_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int, c_int]),
-    "spa_packed_attention_bwd": (c_int, [_P, _P, _P, c_int64, _P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int,
-                                         c_float, _P, _P, _P, c_int64, _P, c_size_t, _P]),
+    "spa_packed_attention_bwd": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
+                                         c_int, c_int, c_float, _P, _P, _P, c_int64, c_int64, c_int64, _P,
+                                         c_size_t, _P]),
     "spa_gate_bwd_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int]),
     "spa_gate_bwd": (c_int, [_P, _P, c_float, _P, _P, _P, _P, c_int, c_float, c_int, c_int, c_int, c_int,
                              _P, _P, _P, _P, _P, c_size_t, _P]),
@@ -116,11 +117,18 @@ def spa_pack(x, mask, counts, gate_scores, container_len, packed, cu_seqlens, ga
                         _ptr(total), _stream()))
 
 
-def spa_packed_attention(q, k, v, row_stride, cu_seqlens, B, max_seqlen, H, Dh, out, lse=None, softmax_scale=0.0):
-    """q, k, v: tensors (or views into one fused packed buffer) whose element (j,h,d) sits at
-    data_ptr + (j*row_stride + h*Dh + d) elements."""
+def _row_stride(t) -> int:
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("expected a 2-D [rows, H*Dh] tensor or column-slice view with unit inner stride")
+    return int(t.stride(0))
+
+
+def spa_packed_attention(q, k, v, cu_seqlens, B, max_seqlen, H, Dh, out, lse=None, softmax_scale=0.0):
+    """q, k, v: [rows, H*Dh] tensors or column-slice views of fused packed buffers; the row
+    strides are taken from the views."""
     _contig(out, lse, cu_seqlens)
-    _check(lib.spa_packed_attention(_ptr(q), _ptr(k), _ptr(v), int(row_stride), _ptr(cu_seqlens), B, max_seqlen,
+    _check(lib.spa_packed_attention(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
+                                    _ptr(cu_seqlens), B, max_seqlen,
                                     H, Dh, dtype_code(out), float(softmax_scale), _ptr(out), _ptr(lse), _stream()))
 
 
@@ -146,13 +154,14 @@ def spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype) -> int:
     return int(lib.spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype))
 
 
-def spa_packed_attention_bwd(q, k, v, row_stride, out, dout, lse, cu_seqlens, B, max_seqlen, H, Dh,
-                             dq, dk, dv, grad_row_stride, workspace, softmax_scale=0.0):
+def spa_packed_attention_bwd(q, k, v, out, dout, lse, cu_seqlens, B, max_seqlen, H, Dh,
+                             dq, dk, dv, workspace, softmax_scale=0.0):
     _contig(out, dout, lse, cu_seqlens, workspace)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.spa_packed_attention_bwd(_ptr(q), _ptr(k), _ptr(v), int(row_stride), _ptr(out), _ptr(dout), _ptr(lse),
-                                        _ptr(cu_seqlens), B, max_seqlen, H, Dh, dtype_code(out), float(softmax_scale),
-                                        _ptr(dq), _ptr(dk), _ptr(dv), int(grad_row_stride), _ptr(workspace),
+    _check(lib.spa_packed_attention_bwd(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
+                                        _ptr(out), _ptr(dout), _ptr(lse), _ptr(cu_seqlens), B, max_seqlen, H, Dh,
+                                        dtype_code(out), float(softmax_scale), _ptr(dq), _ptr(dk), _ptr(dv),
+                                        _row_stride(dq), _row_stride(dk), _row_stride(dv), _ptr(workspace),
                                         ws_bytes, _stream()))
 
 
@@ -169,7 +178,9 @@ def spa_gate_bwd(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale
                             _ptr(dw), _ptr(db), _ptr(workspace), ws_bytes, _stream()))
 
 
-def spa_padded_attention(q, k, v, row_stride, seqlens, B, n_pad, H, Dh, out, softmax_scale=0.0):
+def spa_padded_attention(q, k, v, seqlens, B, n_pad, H, Dh, out, softmax_scale=0.0):
     _contig(out, seqlens)
-    _check(lib.spa_padded_attention(_ptr(q), _ptr(k), _ptr(v), int(row_stride), _ptr(seqlens), B, n_pad, H, Dh,
+    if not (_row_stride(q) == _row_stride(k) == _row_stride(v)):
+        raise ValueError("spa_padded_attention takes one row stride for q, k, v")
+    _check(lib.spa_padded_attention(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _ptr(seqlens), B, n_pad, H, Dh,
                                     dtype_code(out), float(softmax_scale), _ptr(out), _stream()))

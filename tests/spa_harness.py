@@ -57,7 +57,7 @@ class Forward:
         spa.spa_pack(qkv, self.mask, self.counts, None, self.container_len, self.packed_qkv, self.cu,
                      self.gidx, self.inv, self.total)
         p = self.packed_qkv
-        spa.spa_packed_attention(p[:, :C], p[:, C:2 * C], p[:, 2 * C:], 3 * C, self.cu, self.B, self.N,
+        spa.spa_packed_attention(p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.cu, self.B, self.N,
                                  self.H, self.Dh, self.out, self.lse)
         spa.spa_unpack(self.out, self.inv, base, self.y)
         return self

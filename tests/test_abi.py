@@ -54,8 +54,8 @@ def test_version_and_validation_without_gpu(lib):
     assert b"multiple of 16" in lib.spa_last_error()
     assert lib.spa_gate_select(fake, fake, 0.0, None, 0.5, 1, 1, 8, 5, fake, fake, None, None) == -2
     lib.spa_packed_attention.restype = ctypes.c_int
-    lib.spa_packed_attention.argtypes = [P, P, P, ctypes.c_int64, P] + [ctypes.c_int] * 5 + [ctypes.c_float, P, P, P]
-    assert lib.spa_packed_attention(fake, fake, fake, 48, fake, 1, 8, 2, 24, 1, 0.0, fake, None, None) == -2
+    lib.spa_packed_attention.argtypes = [P, P, P, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, P] + [ctypes.c_int] * 5 + [ctypes.c_float, P, P, P]
+    assert lib.spa_packed_attention(fake, fake, fake, 48, 48, 48, fake, 1, 8, 2, 24, 1, 0.0, fake, None, None) == -2
     assert b"head dim" in lib.spa_last_error()
 
 

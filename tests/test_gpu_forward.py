@@ -155,7 +155,7 @@ def _attention_only(spa, q, k, v, mask, H, dtype, want_lse=True):
     out = torch.full((cap, C), float("nan"), dtype=td, device="cuda")
     lse = torch.full((H, cap), float("nan"), dtype=torch.float32, device="cuda")
     spa.spa_pack(dev(qkv, dtype), dev(mask), None, None, 0, packed, cu, None, inv, None)
-    spa.spa_packed_attention(packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:], 3 * C, cu, B, N, H, C // H,
+    spa.spa_packed_attention(packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:], cu, B, N, H, C // H,
                              out, lse if want_lse else None)
     torch.cuda.synchronize()
     return host(out), host(lse), host(cu), host(inv)
@@ -239,7 +239,7 @@ def test_padded_baseline_matches_oracle(spa):
     qkv = dev(np.concatenate([q, k, v], axis=2), "bf16")
     out = torch.empty(B, n_pad, C, dtype=torch.bfloat16, device="cuda")
     flat = qkv.view(B * n_pad, 3 * C)
-    spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], 3 * C, dev(lens), B, n_pad, H, Dh, out)
+    spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], dev(lens), B, n_pad, H, Dh, out)
     torch.cuda.synchronize()
     got = host(out)
     assert np.all(np.isfinite(got))
@@ -261,6 +261,6 @@ def test_argument_validation_returns_errors_before_launch(spa):
     out = torch.empty(16, 48, device="cuda")
     cu = torch.zeros(3, dtype=torch.int32, device="cuda")
     with pytest.raises(spa.SpaError) as e:
-        spa.spa_packed_attention(out, out, out, 48, cu, 2, 8, 2, 24, out)
+        spa.spa_packed_attention(out, out, out, cu, 2, 8, 2, 24, out)
     assert e.value.code == -2
     torch.cuda.synchronize()
