@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of the SPA hot path on one MI355X.
+
+A step is one pass of the whole forward path (gate score + selection, pack, per-image
+attention on the packed tokens, scatter back) over one seeded synthetic batch that is
+already resident in HBM.  The default workload is the ViT-S-shaped classification batch
+(64 images x 196 tokens, dim 384, 6 heads, bf16, per-image selected fraction U[0.1, 0.9]).
+
+Prints ONE JSON line: whole-path throughput in selected tokens/s, the roofline of the
+dominant kernel (durations measured live with events on the launch stream), the CPU
+oracle timed on this machine's host cores, and secondary measurements (per-kernel table,
+hipGraph replay, the padded-to-max attention baseline, the forward+backward training
+step of the ViT-B-shaped workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="vit_s", choices=["tiny", "vit_s", "vit_b_train", "det"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip graph / padded / training measurements")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    return ap.parse_args()
+
+
+def timed(fn, steps, torch):
+    """K calls bracketed by synchronize on both sides -> seconds."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def per_stage_us(stages, steps, torch):
+    """Average duration of every stage, from event pairs recorded on the launch stream
+    around each launch of the timed steps."""
+    names = [n for n, _ in stages]
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in stages]
+          for _ in range(steps)]
+    torch.cuda.synchronize()
+    for s in range(steps):
+        for i, (_, fn) in enumerate(stages):
+            a, b = ev[s][i]
+            a.record()
+            fn()
+            b.record()
+    torch.cuda.synchronize()
+    out = {}
+    for i, n in enumerate(names):
+        out[n] = 1e3 * float(np.mean([ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)]))
+    return out
+
+
+def back_to_back_us(fn, steps, torch):
+    """Average duration of one launch when the same kernel is enqueued `steps` times between
+    two events (no per-launch event overhead)."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(steps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return 1e3 * a.elapsed_time(b) / steps
+
+
+def graph_replay_s(make_step, steps, torch):
+    """Capture one step (prepared on the capture stream) into a hipGraph and time replays."""
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run = make_step()
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=side):
+        run()
+    for _ in range(3):
+        g.replay()
+    return timed(g.replay, steps, torch)
+
+
+def cpu_oracle_baseline(wl, bundle, seconds):
+    """The oracle as it stands, timed on this machine's host cores on the same batch."""
+    from oracle import spa_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    reps, tokens = 0, 0
+    t0 = time.perf_counter()
+    while True:
+        r = orc.spa_forward(bundle["x"], bundle["w"], bundle["bias"], bundle["qkv"], wl.H, wl.tau, wl.dtype)
+        reps += 1
+        tokens += r["total"]
+        dt = time.perf_counter() - t0
+        if dt >= seconds or reps >= 50:
+            break
+    return {"value": tokens / dt, "unit": "selected tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{reps} full forward passes of the {wl.name} batch (NumPy fp64, {dt:.1f} s)"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2410_23608_amd import spa, workloads
+    from paper_2410_23608_amd.pipeline import ForwardPass, TrainPass
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    wl = workloads.WORKLOADS[args.workload]
+    e = 2 if wl.dtype == "bf16" else 4
+    td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    bun = workloads.generate(wl, args.seed)
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(td).contiguous()
+
+    x, w, qkv = up(bun["x"]), up(bun["w"]), up(bun["qkv"])
+    fp = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias)
+    stages = fp.stages(x, w, qkv)
+
+    def step():
+        for _, fn in stages:
+            fn()
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    T = int(fp.total.item())
+    n = np.diff(fp.cu_seqlens.cpu().numpy()).astype(np.float64)
+    sum_n2 = float((n * n).sum())
+
+    # ---- the timed region: exactly K steps
+    dt = timed(step, args.steps, torch)
+    ms_per_step = 1e3 * dt / args.steps
+    value = T * args.steps / dt
+
+    # ---- per-kernel durations, live, events on the launch stream
+    st_us = per_stage_us(stages, args.steps, torch)
+    b2b_us = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in stages}
+    B, N, C, H = wl.B, wl.N, wl.C, wl.H
+    work = {  # algorithmic bytes / flops per launch
+        "gate_select": ("hbm", B * N * (C * e + 5)),
+        "pack": ("hbm", 2 * T * 3 * C * e + 4 * T + 5 * B * N + 4 * (B + 1)),
+        "packed_attention": ("mfma", 4.0 * C * sum_n2),
+        "unpack": ("hbm", T * C * e + 4 * B * N + B * N * C * e),
+    }
+    kernels = {}
+    for nme, (bound, amount) in work.items():
+        us = min(st_us[nme], b2b_us[nme])
+        if bound == "hbm":
+            ach, peak, unit = amount / us / 1e3, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = amount / us / 1e6, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+        kernels[nme] = {"bound": bound, "event_us": round(st_us[nme], 2), "back_to_back_us": round(b2b_us[nme], 2),
+                        "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)}
+    dom = max(kernels, key=lambda k_: min(st_us[k_], b2b_us[k_]))
+    kd = kernels[dom]
+    roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": None,
+                "avg_launch_us": min(kd["event_us"], kd["back_to_back_us"])}
+    if wl.dtype == "f32" and dom == "packed_attention":
+        roofline.update({"bound": "alu", "peak": 157.3, "frac": round(kd["achieved"] / 157.3, 4)})
+
+    result = {
+        "metric": "selected tokens/sec (SPA fwd) at 1 GPU", "value": value, "unit": "selected tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={B} N={N} C={C} H={H} Dh={wl.Dh} {wl.dtype}, selected fraction "
+                               f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward select+pack+attention+unpack",
+                   "selected_tokens": T, "sum_n2": sum_n2, "seed": args.seed, "launch": "eager, 4 launches per step"},
+        "roofline": roofline, "kernels": kernels,
+    }
+
+    if not args.no_extras:
+        # the same step replayed as a hipGraph
+        try:
+            def make_step():
+                st = fp.stages(x, w, qkv)
+                return lambda: [fn() for _, fn in st]
+            gdt = graph_replay_s(make_step, args.steps, torch)
+            result["graph_replay"] = {"ms_per_step": 1e3 * gdt / args.steps, "value": T * args.steps / gdt}
+        except Exception as ex:  # capture refused: report, do not hide
+            result["graph_replay"] = {"error": str(ex)[:200]}
+        # padded-to-max masked attention on the same selected tokens
+        n_max = int(n.max())
+        pad = torch.zeros(B, n_max, 3 * C, dtype=td, device="cuda")
+        cu = fp.cu_seqlens.cpu().numpy()
+        for b in range(B):
+            pad[b, :cu[b + 1] - cu[b]] = fp.packed_qkv[cu[b]:cu[b + 1]]
+        lens = torch.from_numpy(np.diff(cu).astype(np.int32)).cuda()
+        pout = torch.empty(B, n_max, C, dtype=td, device="cuda")
+        flat = pad.view(B * n_max, 3 * C)
+        pfn = lambda: spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], lens, B, n_max, H,
+                                               wl.Dh, pout)
+        pfn()
+        pus = back_to_back_us(pfn, args.steps, torch)
+        aus = b2b_us["packed_attention"]
+        result["padded_baseline"] = {"n_max": n_max, "padded_attention_us": round(pus, 2),
+                                     "packed_attention_us": round(aus, 2), "speedup": round(pus / aus, 3),
+                                     "work_ratio_B_nmax2_over_sum_n2": round(B * n_max * n_max / sum_n2, 3)}
+        # forward + backward training step, ViT-B-shaped
+        twl = workloads.WORKLOADS["vit_b_train"]
+        tb = workloads.generate(twl, args.seed)
+        tp = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias)
+        tx, tw = up(tb["x"]), up(tb["w"])
+        tqk = up(tb["qkv"][:, :, :2 * twl.C])
+        tdy = up(tb["dy"])
+        tlab = torch.from_numpy(tb["labels"]).cuda()
+        tstages = tp.stages(tx, tw, tqk, tlab, tdy)
+
+        def tstep():
+            for _, fn in tstages:
+                fn()
+
+        for _ in range(5):
+            tstep()
+        torch.cuda.synchronize()
+        tT = int(tp.total.item())
+        tn = np.diff(tp.cu_seqlens.cpu().numpy()).astype(np.float64)
+        tdt = timed(tstep, args.steps, torch)
+        tus = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in tstages}
+        bwd_flops = 10.0 * twl.C * float((tn * tn).sum())
+        result["fwd_bwd"] = {"workload": "vit_b_train: B=64 N=196 C=768 H=12 bf16, fwd+bwd with selection loss",
+                             "value": tT * args.steps / tdt, "unit": "selected tokens/s",
+                             "ms_per_step": 1e3 * tdt / args.steps, "selected_tokens": tT,
+                             "stage_us": {k_: round(v_, 2) for k_, v_ in tus.items()},
+                             "attention_bwd_tflops": round(bwd_flops / tus["packed_attention_bwd"] / 1e6, 2)}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_oracle_baseline(wl, bun, args.cpu_seconds)
+        result["cpu_baseline"]["gpu_over_cpu"] = round(value / result["cpu_baseline"]["value"], 1)
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

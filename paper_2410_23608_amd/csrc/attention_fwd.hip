@@ -14,6 +14,11 @@
 // K/V tiles broadcast from LDS, plain fp32 FMA.
 #include <cmath>
 
+#include <cstdio>
+#include <cstdlib>
+#include <type_traits>
+
+#include "attn_tiles.h"
 #include "spa_common.h"
 
 namespace spa {
@@ -41,106 +46,79 @@ __device__ __forceinline__ Segment segment_of(int b, const int32_t* cu, const in
 }
 
 // ------------------------------------------------------------------------- bf16 / MFMA
-constexpr int kBN = 64;   // keys per LDS tile
-
-template <int DH, int NW>
-__global__ void __launch_bounds__(64 * NW)
-attn_fwd_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                     const __bf16* __restrict__ v, long qs, long ks, long vs, const int32_t* __restrict__ cu,
-                     const int32_t* __restrict__ key_lens, int n_pad, int H, float scale_log2,
-                     __bf16* __restrict__ out, float* __restrict__ lse, long lse_stride) {
-  constexpr int KS = DH + 8;    // LDS row stride of the K tile (elements): conflict-free b128 reads
-  constexpr int VS = kBN + 4;   // LDS row stride of the transposed V tile: conflict-free b64 reads
-  constexpr int KK = DH / 16;   // MFMA k-steps over the head dim
-  constexpr int DB = DH / 32;   // 32-row blocks of O^T
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[kBN * KS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vt[DH * VS];
-
-  const int h = blockIdx.y;
-  const Segment seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
-  const int q0 = blockIdx.x * (32 * NW);
-  if (q0 >= seg.nq) return;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wv = tid >> 6;
-  const int l32 = lane & 31, hh = lane >> 5;
-  const int qi = q0 + wv * 32 + l32;
-  const bool wave_live = q0 + wv * 32 < seg.nq;
-  const bool q_ok = qi < seg.nq;
-  const long C = (long)H * DH;
-
-  bf16x8 qf[KK];
+// Per-wave state of the online softmax: O^T accumulators (rows = head dim, cols = this
+// wave's 32 queries), running max m (log2 domain, scale folded in) and running sum l (the
+// two halves of the wave keep partial sums that are added at the end).
+template <int DH>
+struct FwdAcc {
+  floatx16 o[DH / 32];
+  float m, l;
+  __device__ __forceinline__ void init() {
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    qf[kk] = z;
-    if (q_ok) qf[kk] = *reinterpret_cast<const bf16x8*>(q + (seg.row0 + qi) * qs + h * DH + kk * 16 + hh * 8);
+    for (int d = 0; d < DH / 32; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+    m = -INFINITY;
+    l = 0.f;
   }
+};
 
-  floatx16 o[DB];
+// One tile of NSB*32 keys held in LDS (K rows at kbuf, row stride RS; V^T at vbuf, row
+// stride TS, the tile's keys starting at column vcol0): all score sub-tiles S^T = K Q^T
+// first, then ONE online-softmax update (max, rescale, exp, sum) over the whole tile, then
+// O^T += V^T P^T.  rem = valid keys in the tile; FULL = every key valid (no masking code).
+template <int DH, int RS, int TS, int NSB, bool FULL>
+__device__ __forceinline__ void fwd_process_tile(const __bf16* kbuf, const __bf16* vbuf, int vcol0, int rem,
+                                                 const bf16x8 (&qf)[DH / 16], FwdAcc<DH>& acc,
+                                                 float scale_log2, int l32, int hh) {
+  constexpr int KK = DH / 16, DB = DH / 32;
+  floatx16 s[NSB];
 #pragma unroll
-  for (int d = 0; d < DB; ++d)
+  for (int sb = 0; sb < NSB; ++sb) {
+    if (FULL || sb * 32 < rem) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
-  float m = -INFINITY, l = 0.f;
-
-  for (int kt = 0; kt < seg.nk; kt += kBN) {
-    __syncthreads();
-    constexpr int CPR = DH / 8;
-    for (int i = tid; i < kBN * CPR; i += 64 * NW) {
-      const int r = i / CPR, c = i % CPR;
-      bf16x8 kv = {0, 0, 0, 0, 0, 0, 0, 0};
-      bf16x8 vv = kv;
-      if (kt + r < seg.nk) {
-        kv = *reinterpret_cast<const bf16x8*>(k + (seg.row0 + kt + r) * ks + h * DH + c * 8);
-        vv = *reinterpret_cast<const bf16x8*>(v + (seg.row0 + kt + r) * vs + h * DH + c * 8);
-      }
-      *reinterpret_cast<bf16x8*>(&Ks[r * KS + c * 8]) = kv;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * VS + r] = vv[e];
-    }
-    __syncthreads();
-    if (!wave_live) continue;
-
-#pragma unroll
-    for (int sb = 0; sb < kBN / 32; ++sb) {
-      const int key0 = kt + sb * 32;
-      if (key0 >= seg.nk) break;
-      // S^T tile: rows = 32 keys, cols = this wave's 32 queries
-      floatx16 s;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+      for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(sb * 32 + l32) * KS + kk * 16 + hh * 8]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&kbuf[(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
+        s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s[sb], 0, 0, 0);
       }
-      // accumulator register r of this lane is key key0 + 8*(r/4) + 4*hh + r%4
-      if (key0 + 32 > seg.nk) {
+      if (!FULL && rem - sb * 32 < 32) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (key0 + 8 * (r / 4) + 4 * hh + (r % 4) >= seg.nk) s[r] = -INFINITY;
+          if (sb * 32 + acc_row(r, hh) >= rem) s[sb][r] = -INFINITY;
       }
-      float mx = s[0];
+    } else {
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float m_new = fmaxf(m, mx * scale_log2);
-      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      for (int r = 0; r < 16; ++r) s[sb][r] = -INFINITY;
+    }
+  }
+  float mx = s[0][0];
+#pragma unroll
+  for (int sb = 0; sb < NSB; ++sb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+  const float m_new = fmaxf(acc.m, mx * scale_log2);
+  if (__ballot(m_new != acc.m) != 0) {       // some query's running max moved: rescale
+    const float alpha = __builtin_amdgcn_exp2f(acc.m - m_new);
+    acc.l *= alpha;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc.o[d][r] *= alpha;
+    acc.m = m_new;
+  }
+  float psum = 0.f;
+#pragma unroll
+  for (int sb = 0; sb < NSB; ++sb) {
+    if (FULL || sb * 32 < rem) {
       float p[16];
-      float psum = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -m_new));
+        p[r] = __builtin_amdgcn_exp2f(fmaf(s[sb][r], scale_log2, -m_new));
         psum += p[r];
       }
-      l = fmaf(l, alpha, psum);
-      m = m_new;
-#pragma unroll
-      for (int d = 0; d < DB; ++d)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-      // O^T += V^T P^T, 16 keys per MFMA: registers 8*mf .. 8*mf+7 are the B operand
 #pragma unroll
       for (int mf = 0; mf < 2; ++mf) {
         floatx8 pf;
@@ -149,30 +127,187 @@ attn_fwd_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
         const bf16x8 pb = float_to_bf16x8(pf);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          const __bf16* vr = &Vt[(d * 32 + l32) * VS + sb * 32 + 16 * mf + 4 * hh];
-          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vr);
-          const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vr + 8);
-          const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[d], 0, 0, 0);
+          const bf16x8 a = transposed_frag<TS>(vbuf, d * 32 + l32, vcol0 + sb * 32, mf, hh);
+          acc.o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, acc.o[d], 0, 0, 0);
         }
       }
     }
   }
+  acc.l += psum;
+}
 
-  if (!wave_live) return;
-  const float l_tot = l + __shfl_xor(l, 32, kWave);
+// Normalise and store this wave's 32 output rows (+ lse).  Called by every lane of a live wave.
+template <int DH>
+__device__ __forceinline__ void fwd_store(FwdAcc<DH>& acc, bool q_ok, bool have_keys, __bf16* orow,
+                                          float* lse_ptr, int hh) {
+  const float l_tot = acc.l + __shfl_xor(acc.l, 32, kWave);
   if (!q_ok) return;
-  const float inv = seg.nk > 0 ? 1.0f / l_tot : 0.f;
-  __bf16* orow = out + (seg.row0 + qi) * C + h * DH;
+  const float inv = have_keys ? 1.0f / l_tot : 0.f;
 #pragma unroll
-  for (int d = 0; d < DB; ++d)
+  for (int d = 0; d < DH / 32; ++d)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      floatx4 f = {o[d][4 * g] * inv, o[d][4 * g + 1] * inv, o[d][4 * g + 2] * inv, o[d][4 * g + 3] * inv};
+      floatx4 f = {acc.o[d][4 * g] * inv, acc.o[d][4 * g + 1] * inv, acc.o[d][4 * g + 2] * inv,
+                   acc.o[d][4 * g + 3] * inv};
       *reinterpret_cast<bf16x4*>(orow + d * 32 + 8 * g + 4 * hh) = __builtin_convertvector(f, bf16x4);
     }
-  if (lse != nullptr && hh == 0)
-    lse[h * lse_stride + seg.row0 + qi] = seg.nk > 0 ? (m + __log2f(l_tot)) * 0.69314718055994531f : -INFINITY;
+  if (lse_ptr != nullptr && hh == 0)
+    *lse_ptr = have_keys ? (acc.m + __log2f(l_tot)) * 0.69314718055994531f : -INFINITY;
+}
+
+// Register staging of key/value rows on their way to LDS: task i = 16-byte chunk column
+// c = i % CPR of the row pair (2*(i / CPR), +1); K goes row-major, V transposed.
+template <int DH, int THREADS, int TASKS>
+struct KvStage {
+  static constexpr int CPR = DH / 8;
+  static constexpr int TPT = (TASKS + THREADS - 1) / THREADS;
+  bf16x8 kreg[TPT][2], vreg[TPT][2];
+
+  // rows are relative to row `base` of the segment; rows >= nrows read as zero
+  __device__ __forceinline__ void load(const __bf16* kh, const __bf16* vh, long base, int nrows, long ks, long vs) {
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) {
+      const int i = threadIdx.x + t * THREADS;
+      const int c = i % CPR, r0 = 2 * (i / CPR);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        kreg[t][u] = zero_bf16x8();
+        vreg[t][u] = zero_bf16x8();
+        if (i < TASKS && r0 + u < nrows) {
+          kreg[t][u] = *reinterpret_cast<const bf16x8*>(kh + (base + r0 + u) * ks + c * 8);
+          vreg[t][u] = *reinterpret_cast<const bf16x8*>(vh + (base + r0 + u) * vs + c * 8);
+        }
+      }
+    }
+  }
+  // K rows -> kbuf[row * RS], V -> vbuf[d * TS + col0 + row]
+  template <int RS, int TS>
+  __device__ __forceinline__ void store(__bf16* kbuf, __bf16* vbuf, int col0) const {
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) {
+      const int i = threadIdx.x + t * THREADS;
+      if (i < TASKS) {
+        const int c = i % CPR, r0 = 2 * (i / CPR);
+        *reinterpret_cast<bf16x8*>(&kbuf[r0 * RS + c * 8]) = kreg[t][0];
+        *reinterpret_cast<bf16x8*>(&kbuf[(r0 + 1) * RS + c * 8]) = kreg[t][1];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          bf16x2 pr = {vreg[t][0][e], vreg[t][1][e]};
+          *reinterpret_cast<bf16x2*>(&vbuf[(c * 8 + e) * TS + col0 + r0]) = pr;
+        }
+      }
+    }
+  }
+};
+
+template <int DH>
+__device__ __forceinline__ void load_q_frags(const __bf16* qrow, bool q_ok, int hh, bf16x8 (&qf)[DH / 16]) {
+#pragma unroll
+  for (int kk = 0; kk < DH / 16; ++kk) {
+    qf[kk] = zero_bf16x8();
+    if (q_ok) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16 + hh * 8);
+  }
+}
+
+// Long segments.  Workgroup = NW waves x 32 queries; the keys of the segment stream through
+// LDS in tiles of BN keys, double-buffered: while a tile is consumed the next one is already
+// in flight from global memory into registers, and is written to the other LDS buffer
+// before the single barrier that ends the iteration.
+template <int DH, int NW, int BN>
+__global__ void __launch_bounds__(64 * NW)
+attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                           const __bf16* __restrict__ v, long qs, long ks, long vs,
+                           const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
+                           int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
+                           long lse_stride) {
+  constexpr int RS = DH + 8, TS = transposed_stride(BN), NSB = BN / 32;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][BN * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vt[2][DH * TS];
+
+  const int h = blockIdx.y;
+  const Segment seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
+  const int q0 = blockIdx.x * (32 * NW);
+  if (q0 >= seg.nq) return;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int qi = q0 + wv * 32 + l32;
+  const bool wave_live = q0 + wv * 32 < seg.nq;
+  const bool q_ok = qi < seg.nq;
+  const long C = (long)H * DH;
+  const __bf16* kh = k + h * DH;
+  const __bf16* vh = v + h * DH;
+
+  KvStage<DH, 64 * NW, (BN / 2) * (DH / 8)> stage;
+  stage.load(kh, vh, seg.row0, seg.nk, ks, vs);
+  bf16x8 qf[DH / 16];
+  load_q_frags<DH>(q + (seg.row0 + qi) * qs + h * DH, q_ok, hh, qf);
+  FwdAcc<DH> acc;
+  acc.init();
+  stage.template store<RS, TS>(Ks[0], Vt[0], 0);
+  __syncthreads();
+
+  const int nt = (seg.nk + BN - 1) / BN;
+  for (int t = 0; t < nt; ++t) {
+    const int buf = t & 1, kt = t * BN;
+    if (t + 1 < nt) stage.load(kh, vh, seg.row0 + kt + BN, seg.nk - kt - BN, ks, vs);
+    if (wave_live) {
+      const int rem = seg.nk - kt;               // valid keys from this tile on (may exceed BN)
+      if (rem >= BN) fwd_process_tile<DH, RS, TS, NSB, true>(Ks[buf], Vt[buf], 0, BN, qf, acc, scale_log2, l32, hh);
+      else fwd_process_tile<DH, RS, TS, NSB, false>(Ks[buf], Vt[buf], 0, rem, qf, acc, scale_log2, l32, hh);
+    }
+    if (t + 1 < nt) stage.template store<RS, TS>(Ks[buf ^ 1], Vt[buf ^ 1], 0);
+    __syncthreads();
+  }
+  if (!wave_live) return;
+  fwd_store<DH>(acc, q_ok, seg.nk > 0, out + (seg.row0 + qi) * C + h * DH,
+                lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr, hh);
+}
+
+// Short segments (every segment <= NKMAX keys).  ONE workgroup per (image, head): all K / V
+// rows of the segment are staged once (each element is read from memory exactly once per
+// head), one barrier, then wave w owns queries [32w, 32w+32) and walks the keys in LDS with
+// no further synchronisation.  No workgroup is launched for nothing.
+template <int DH, int NKMAX>
+__global__ void __launch_bounds__(2 * NKMAX)
+attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                           const __bf16* __restrict__ v, long qs, long ks, long vs,
+                           const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
+                           int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
+                           long lse_stride) {
+  constexpr int THREADS = 2 * NKMAX;                       // one wave per 32 queries
+  constexpr int RS = DH + 8, TS = transposed_stride(NKMAX);
+  constexpr int TILE = NKMAX < 128 ? NKMAX : 128;           // keys per softmax update
+  constexpr int NSB = TILE / 32;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[NKMAX * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vt[DH * TS];
+
+  const int h = blockIdx.x;
+  Segment seg = segment_of(blockIdx.y, cu, key_lens, n_pad);
+  seg.nq = min(seg.nq, NKMAX);   // never index past the LDS tile, whatever cu_seqlens holds
+  seg.nk = min(seg.nk, NKMAX);
+  if (seg.nq <= 0) return;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int qi = wv * 32 + l32;
+  const bool wave_live = wv * 32 < seg.nq;
+  const bool q_ok = qi < seg.nq;
+  const long C = (long)H * DH;
+
+  KvStage<DH, THREADS, (NKMAX / 2) * (DH / 8)> stage;
+  stage.load(k + h * DH, v + h * DH, seg.row0, seg.nk, ks, vs);
+  bf16x8 qf[DH / 16];
+  load_q_frags<DH>(q + (seg.row0 + qi) * qs + h * DH, q_ok, hh, qf);
+  FwdAcc<DH> acc;
+  acc.init();
+  stage.template store<RS, TS>(Ks, Vt, 0);
+  __syncthreads();
+  if (!wave_live) return;
+
+  for (int kt = 0; kt < seg.nk; kt += TILE) {
+    const int rem = seg.nk - kt;
+    if (rem >= TILE) fwd_process_tile<DH, RS, TS, NSB, true>(Ks + kt * RS, Vt, kt, TILE, qf, acc, scale_log2, l32, hh);
+    else fwd_process_tile<DH, RS, TS, NSB, false>(Ks + kt * RS, Vt, kt, rem, qf, acc, scale_log2, l32, hh);
+  }
+  fwd_store<DH>(acc, q_ok, seg.nk > 0, out + (seg.row0 + qi) * C + h * DH,
+                lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr, hh);
 }
 
 // ------------------------------------------------------------------------------- fp32
@@ -290,15 +425,40 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
 #undef SPA_F32_LAUNCH
   } else {
     const float scale_log2 = scale * 1.4426950408889634f;
-    const int NW = n_max <= 256 ? 2 : 4;
-    const dim3 grid((n_max + 32 * NW - 1) / (32 * NW), H, B), block(64 * NW);
-#define SPA_BF16_LAUNCH(D, W)                                                                              \
-  hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, W>), grid, block, 0, st, (const __bf16*)q, (const __bf16*)k, \
-                     (const __bf16*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu, key_lens, n_max, H, scale_log2, (__bf16*)out, \
-                     lse, lse_stride)
-    if (Dh == 32) { if (NW == 2) SPA_BF16_LAUNCH(32, 2); else SPA_BF16_LAUNCH(32, 4); }
-    else          { if (NW == 2) SPA_BF16_LAUNCH(64, 2); else SPA_BF16_LAUNCH(64, 4); }
-#undef SPA_BF16_LAUNCH
+#define SPA_ARGS                                                                                              \
+  (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu,   \
+      key_lens, n_max, H, scale_log2, (__bf16*)out, lse, lse_stride
+    // SPA_ATTN_FWD_CFG="NW,BN" forces the tiled kernel with that launch shape (tuning aid).
+    int NW = 0, BN = 0;
+    if (const char* env = std::getenv("SPA_ATTN_FWD_CFG")) {
+      int a = 0, b = 0;
+      if (std::sscanf(env, "%d,%d", &a, &b) == 2 && (a == 2 || a == 4) && (b == 64 || b == 128)) { NW = a; BN = b; }
+    }
+    if (NW == 0 && n_max <= 256) {
+      // short segments: one workgroup per (image, head), whole segment in LDS
+      const dim3 grid(H, B);
+#define SPA_WHOLE(D)                                                                                          \
+  do {                                                                                                        \
+    if (n_max <= 64) hipLaunchKernelGGL((attn_fwd_bf16_whole_kernel<D, 64>), grid, dim3(128), 0, st, SPA_ARGS);       \
+    else if (n_max <= 128) hipLaunchKernelGGL((attn_fwd_bf16_whole_kernel<D, 128>), grid, dim3(256), 0, st, SPA_ARGS); \
+    else hipLaunchKernelGGL((attn_fwd_bf16_whole_kernel<D, 256>), grid, dim3(512), 0, st, SPA_ARGS);          \
+  } while (0)
+      if (Dh == 32) SPA_WHOLE(32); else SPA_WHOLE(64);
+#undef SPA_WHOLE
+    } else {
+      if (NW == 0) { NW = 4; BN = 128; }
+      const dim3 grid((n_max + 32 * NW - 1) / (32 * NW), H, B), block(64 * NW);
+#define SPA_TILED(D)                                                                                          \
+  do {                                                                                                        \
+    if (NW == 2 && BN == 64) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 2, 64>), grid, block, 0, st, SPA_ARGS);        \
+    else if (NW == 2) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 2, 128>), grid, block, 0, st, SPA_ARGS);              \
+    else if (BN == 64) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 4, 64>), grid, block, 0, st, SPA_ARGS);              \
+    else hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 4, 128>), grid, block, 0, st, SPA_ARGS);           \
+  } while (0)
+      if (Dh == 32) SPA_TILED(32); else SPA_TILED(64);
+#undef SPA_TILED
+    }
+#undef SPA_ARGS
   }
   return check_launch(fn);
 }

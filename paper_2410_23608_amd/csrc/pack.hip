@@ -121,75 +121,139 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
     }
   }
 
-  // 4. copy the survivors' rows: consecutive threads take consecutive 16-byte chunks
-  const long work = (long)nsel * chunks;
-  for (long i = tid; i < work; i += kPackThreads) {
-    const int r = (int)(i / chunks);
-    const int ch = (int)(i - (long)r * chunks);
-    const T* src = x + (flat0 + sel_src[r]) * (long)C + ch * VE;
-    T* dst = packed + ((long)base + r) * C + ch * VE;
-    if (kScale) {
-      const float sc = sel_scale[r];
-      if constexpr (sizeof(T) == 2) {
-        floatx8 v = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(src));
+  // 4. copy the survivors' rows: consecutive threads take consecutive 16-byte chunks, four
+  //    independent loads in flight per thread before the first store
+  constexpr int U = 4;
+  const unsigned work = (unsigned)nsel * (unsigned)chunks;
+  const T* xt = x + flat0 * (long)C;
+  T* pt = packed + (long)base * C;
+  for (unsigned i0 = tid; i0 < work; i0 += kPackThreads * U) {
+    uintx4 v[U];
+    unsigned dst_off[U];
+    float sc[U];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] *= sc;
-        *reinterpret_cast<bf16x8*>(dst) = float_to_bf16x8(v);
-      } else {
-        floatx4 v = *reinterpret_cast<const floatx4*>(src);
-        v *= sc;
-        *reinterpret_cast<floatx4*>(dst) = v;
+    for (int u = 0; u < U; ++u) {
+      const unsigned i = i0 + u * kPackThreads;
+      if (i < work) {
+        const unsigned r = i / (unsigned)chunks;
+        const unsigned ch = i - r * (unsigned)chunks;
+        v[u] = *reinterpret_cast<const uintx4*>(xt + (long)sel_src[r] * C + ch * VE);
+        dst_off[u] = r * (unsigned)C + ch * VE;
+        if (kScale) sc[u] = sel_scale[r];
       }
-    } else {
-      *reinterpret_cast<uintx4*>(dst) = *reinterpret_cast<const uintx4*>(src);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned i = i0 + u * kPackThreads;
+      if (i < work) {
+        uintx4 o = v[u];
+        if (kScale) {
+          if constexpr (sizeof(T) == 2) {
+            floatx8 f = bf16x8_to_float(__builtin_bit_cast(bf16x8, o));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] *= sc[u];
+            o = __builtin_bit_cast(uintx4, float_to_bf16x8(f));
+          } else {
+            o = __builtin_bit_cast(uintx4, __builtin_bit_cast(floatx4, o) * sc[u]);
+          }
+        }
+        *reinterpret_cast<uintx4*>(pt + dst_off[u]) = o;
+      }
     }
   }
 }
 
-// y[i] = base[i] (+ src[inv[i]]) or src[inv[i]] or 0, one 16-byte chunk per thread.
+// y[i] = base[i] (+ src[inv[i]]) or src[inv[i]] or 0.  A block owns `rpb` consecutive output
+// rows; consecutive threads take consecutive 16-byte chunks.
 template <typename T, bool kBase>
 __global__ void __launch_bounds__(256)
 unpack_kernel(const T* __restrict__ src, const int32_t* __restrict__ inv_pos,
-              const T* base, long rows, int C, T* y) {
+              const T* base, long rows, int C, int rpb, T* y) {
   constexpr int VE = 16 / sizeof(T);
-  const int chunks = C / VE;
-  const long work = rows * chunks;
-  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < work; i += (long)gridDim.x * blockDim.x) {
-    const long r = i / chunks;
-    const int ch = (int)(i - r * chunks);
-    const int j = inv_pos[r];
-    uintx4 v = {0u, 0u, 0u, 0u};
-    if (j >= 0) v = *reinterpret_cast<const uintx4*>(src + (long)j * C + ch * VE);
-    if (kBase) {
-      const uintx4 bv = *reinterpret_cast<const uintx4*>(base + r * C + ch * VE);
-      if (j >= 0) {
-        if constexpr (sizeof(T) == 2) {
-          floatx8 a = bf16x8_to_float(__builtin_bit_cast(bf16x8, v));
-          floatx8 c = bf16x8_to_float(__builtin_bit_cast(bf16x8, bv));
-          v = __builtin_bit_cast(uintx4, float_to_bf16x8(a + c));
-        } else {
-          v = __builtin_bit_cast(uintx4, __builtin_bit_cast(floatx4, v) + __builtin_bit_cast(floatx4, bv));
-        }
-      } else {
-        v = bv;
+  constexpr int U = 4;
+  const unsigned chunks = C / VE;
+  const long row0 = (long)blockIdx.x * rpb;
+  const unsigned nrows = (unsigned)min((long)rpb, rows - row0);
+  const unsigned work = nrows * chunks;
+  const int32_t* inv = inv_pos + row0;
+  const T* bt = kBase ? base + row0 * C : nullptr;
+  T* yt = y + row0 * C;
+  for (unsigned i0 = threadIdx.x; i0 < work; i0 += 256 * U) {
+    uintx4 v[U], bv[U];
+    int j[U];
+    unsigned off[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned i = i0 + u * 256;
+      if (i < work) {
+        const unsigned r = i / chunks, ch = i - r * chunks;
+        off[u] = r * (unsigned)C + ch * VE;
+        j[u] = inv[r];
+        const uintx4 z = {0u, 0u, 0u, 0u};
+        v[u] = z;
+        if (j[u] >= 0) v[u] = *reinterpret_cast<const uintx4*>(src + (long)j[u] * C + ch * VE);
+        if (kBase) bv[u] = *reinterpret_cast<const uintx4*>(bt + off[u]);
       }
     }
-    *reinterpret_cast<uintx4*>(y + r * C + ch * VE) = v;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned i = i0 + u * 256;
+      if (i < work) {
+        uintx4 o = v[u];
+        if (kBase) {
+          if (j[u] >= 0) {
+            if constexpr (sizeof(T) == 2) {
+              floatx8 a = bf16x8_to_float(__builtin_bit_cast(bf16x8, v[u]));
+              floatx8 c = bf16x8_to_float(__builtin_bit_cast(bf16x8, bv[u]));
+              o = __builtin_bit_cast(uintx4, float_to_bf16x8(a + c));
+            } else {
+              o = __builtin_bit_cast(uintx4, __builtin_bit_cast(floatx4, v[u]) + __builtin_bit_cast(floatx4, bv[u]));
+            }
+          } else {
+            o = bv[u];
+          }
+        }
+        *reinterpret_cast<uintx4*>(yt + off[u]) = o;
+      }
+    }
   }
 }
 
-// dst[j] = src[idx[j]] for j < *total (rows of `bytes16` 16-byte chunks)
+// dst[j] = src[idx[j]] for j < *total (rows of `chunks` 16-byte chunks); a block owns rpb rows
 __global__ void __launch_bounds__(256)
 gather_rows_kernel(const uintx4* __restrict__ src, const int32_t* __restrict__ idx,
-                   const int32_t* __restrict__ total, long cap_rows, int chunks,
+                   const int32_t* __restrict__ total, long cap_rows, unsigned chunks, int rpb,
                    uintx4* __restrict__ dst) {
+  constexpr int U = 4;
   const long rows = min((long)total[0], cap_rows);
-  const long work = rows * chunks;
-  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < work; i += (long)gridDim.x * blockDim.x) {
-    const long r = i / chunks;
-    const int ch = (int)(i - r * chunks);
-    dst[r * chunks + ch] = src[(long)idx[r] * chunks + ch];
+  const long row0 = (long)blockIdx.x * rpb;
+  if (row0 >= rows) return;
+  const unsigned nrows = (unsigned)min((long)rpb, rows - row0);
+  const unsigned work = nrows * chunks;
+  const int32_t* id = idx + row0;
+  uintx4* dt = dst + row0 * chunks;
+  for (unsigned i0 = threadIdx.x; i0 < work; i0 += 256 * U) {
+    uintx4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned i = i0 + u * 256;
+      if (i < work) {
+        const unsigned r = i / chunks, ch = i - r * chunks;
+        v[u] = src[(long)id[r] * chunks + ch];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned i = i0 + u * 256;
+      if (i < work) dt[i] = v[u];
+    }
   }
+}
+
+// rows per block for the row-copy kernels: about 4 chunks per thread
+static int rows_per_block(long chunks) {
+  long r = (1024 + chunks - 1) / chunks;
+  return (int)(r < 1 ? 1 : r);
 }
 
 static int pick_tile(int B, int N, bool have_counts) {
@@ -207,27 +271,22 @@ static int check_rows(const char* fn, int B, int N, int C, int dtype) {
   SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
   SPA_REQUIRE(((long)C * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG,
               "%s: row length C*elem = %ld bytes is not a multiple of 16", fn, (long)C * elem_size(dtype));
+  SPA_REQUIRE(C <= (1 << 20), SPA_ERR_UNSUPPORTED, "%s: C = %d exceeds 2^20", fn, C);
   return SPA_OK;
-}
-
-static unsigned grid_for(long work, int threads) {
-  long g = (work + threads - 1) / threads;
-  if (g > 16384) g = 16384;
-  if (g < 1) g = 1;
-  return (unsigned)g;
 }
 
 template <typename T>
 static void launch_unpack(const void* src, const int32_t* inv, const void* base, long rows, int C,
                           void* y, hipStream_t st) {
   constexpr int VE = 16 / sizeof(T);
-  const unsigned g = grid_for(rows * (C / VE), 256);
+  const int rpb = rows_per_block(C / VE);
+  const unsigned g = (unsigned)((rows + rpb - 1) / rpb);
   if (base != nullptr)
     hipLaunchKernelGGL((unpack_kernel<T, true>), dim3(g), dim3(256), 0, st, static_cast<const T*>(src), inv,
-                       static_cast<const T*>(base), rows, C, static_cast<T*>(y));
+                       static_cast<const T*>(base), rows, C, rpb, static_cast<T*>(y));
   else
     hipLaunchKernelGGL((unpack_kernel<T, false>), dim3(g), dim3(256), 0, st, static_cast<const T*>(src), inv,
-                       static_cast<const T*>(nullptr), rows, C, static_cast<T*>(y));
+                       static_cast<const T*>(nullptr), rows, C, rpb, static_cast<T*>(y));
 }
 
 }  // namespace spa
@@ -288,7 +347,9 @@ extern "C" int spa_unpack_bwd(const void* dy, const int32_t* gather_idx, const i
   SPA_REQUIRE(aligned16(dy) && aligned16(dout), SPA_ERR_INVALID_ARG, "spa_unpack_bwd: buffers not 16-byte aligned");
   const int chunks = (int)((long)C * elem_size(dtype) / 16);
   const long cap = (long)B * N;
-  hipLaunchKernelGGL(gather_rows_kernel, dim3(grid_for(cap * chunks, 256)), dim3(256), 0, as_stream(stream),
-                     static_cast<const uintx4*>(dy), gather_idx, total, cap, chunks, static_cast<uintx4*>(dout));
+  const int rpb = rows_per_block(chunks);
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((cap + rpb - 1) / rpb)), dim3(256), 0, as_stream(stream),
+                     static_cast<const uintx4*>(dy), gather_idx, total, cap, (unsigned)chunks, rpb,
+                     static_cast<uintx4*>(dout));
   return check_launch("spa_unpack_bwd");
 }

@@ -1,0 +1,132 @@
+"""Buffer owners for the SPA hot path: they allocate the device tensors once and issue the
+C-ABI calls of one forward (or forward + backward) pass in order.  No arithmetic happens
+here; every step runs in libspa's HIP kernels on the current stream, without host syncs.
+
+Order of the forward pass (Section 3.2): gate score -> hard selection -> pack ->
+per-image attention on the packed tokens -> scatter back.  The projected q | k | v of every
+token are supplied by the caller as one fused [B, N, 3C] tensor (the projections are not
+part of this path) and are packed with the gate's mask.
+"""
+from __future__ import annotations
+
+from typing import Callable, List, Optional, Tuple
+
+import torch
+
+from . import spa
+
+
+def _td(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+class ForwardPass:
+    """gate_select(x) -> pack(qkv) -> packed_attention -> unpack."""
+
+    def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
+                 container_len: int = 0):
+        self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
+        self.tau, self.bias, self.container_len = tau, bias, container_len
+        td, cap = _td(dtype), B * N
+        dv = dict(device="cuda")
+        self.scores = torch.empty(B, N, dtype=torch.float32, **dv)
+        self.mask = torch.empty(B, N, dtype=torch.uint8, **dv)
+        self.packed_qkv = torch.zeros(cap + max(container_len - 1, 0), 3 * C, dtype=td, **dv)
+        self.cu_seqlens = torch.zeros(B + 1, dtype=torch.int32, **dv)
+        self.gather_idx = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.inv_pos = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.total = torch.zeros(1, dtype=torch.int32, **dv)
+        self.out = torch.zeros(cap, C, dtype=td, **dv)
+        self.lse = torch.zeros(H, cap, dtype=torch.float32, **dv)
+        self.y = torch.empty(B, N, C, dtype=td, **dv)
+
+    def stages(self, x, w, qkv, s_up=None, base=None) -> List[Tuple[str, Callable[[], None]]]:
+        """The pass as named, prepared launches (bound to the stream that is current now), so a
+        caller can time each of them or replay them with no marshalling cost."""
+        C, p = self.C, self.packed_qkv
+        q, k, v = p[:, :C], p[:, C:2 * C], p[:, 2 * C:]
+        return [
+            ("gate_select", spa.spa_gate_select(x, w, self.bias, s_up, self.tau, self.scores, self.mask, None, prepare=True)),
+            ("pack", spa.spa_pack(qkv, self.mask, None, None, self.container_len, p, self.cu_seqlens,
+                                          self.gather_idx, self.inv_pos, self.total, prepare=True)),
+            ("packed_attention", spa.spa_packed_attention(q, k, v, self.cu_seqlens, self.B, self.N, self.H,
+                                                                  self.Dh, self.out, self.lse, prepare=True)),
+            ("unpack", spa.spa_unpack(self.out, self.inv_pos, base, self.y, prepare=True)),
+        ]
+
+    def run(self, x, w, qkv, s_up=None, base=None):
+        for _, fn in self.stages(x, w, qkv, s_up, base):
+            fn()
+        return self.y
+
+
+class TrainPass:
+    """Forward + backward of one SPA block with the selection loss (Section 3.3).
+
+    q | k are supplied ([B, N, 2C], stand-ins for projected tokens); v is the packed gated
+    representation r_g = Sigmoid(s) . r, so the gate receives the attention's gradient:
+      fwd: gate_select(x) -> pack(qk) -> pack(x, scaled by sigmoid(s)) -> attention -> unpack
+      bwd: unpack_bwd(dy) -> attention_bwd -> pack_bwd(dv) [-> pack_bwd(dq|dk)] -> gate_bwd
+    """
+
+    def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
+                 loss_scale: Optional[float] = None):
+        self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
+        self.tau, self.bias = tau, bias
+        self.loss_scale = 0.01 / (B * N) if loss_scale is None else loss_scale
+        td, cap = _td(dtype), B * N
+        code = spa.SPA_BF16 if dtype == "bf16" else spa.SPA_F32
+        dv = dict(device="cuda")
+        self.scores = torch.empty(B, N, dtype=torch.float32, **dv)
+        self.mask = torch.empty(B, N, dtype=torch.uint8, **dv)
+        self.packed_qk = torch.zeros(cap, 2 * C, dtype=td, **dv)
+        self.packed_v = torch.zeros(cap, C, dtype=td, **dv)
+        self.cu_seqlens = torch.zeros(B + 1, dtype=torch.int32, **dv)
+        self.gather_idx = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.inv_pos = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.total = torch.zeros(1, dtype=torch.int32, **dv)
+        self.out = torch.zeros(cap, C, dtype=td, **dv)
+        self.lse = torch.zeros(H, cap, dtype=torch.float32, **dv)
+        self.y = torch.empty(B, N, C, dtype=td, **dv)
+        self.dout = torch.zeros(cap, C, dtype=td, **dv)
+        self.dqk_packed = torch.zeros(cap, 2 * C, dtype=td, **dv)
+        self.dv_packed = torch.zeros(cap, C, dtype=td, **dv)
+        self.d_rg = torch.empty(B, N, C, dtype=td, **dv)
+        self.dqk = torch.empty(B, N, 2 * C, dtype=td, **dv)
+        self.dx = torch.empty(B, N, C, dtype=td, **dv)
+        self.dw = torch.empty(C, dtype=torch.float32, **dv)
+        self.db = torch.empty(1, dtype=torch.float32, **dv)
+        self.loss = torch.empty(1, dtype=torch.float32, **dv)
+        self.ws_attn = torch.empty(max(spa.spa_attention_bwd_workspace_bytes(B, N, H, self.Dh, code), 256),
+                                   dtype=torch.uint8, **dv)
+        self.ws_gate = torch.empty(max(spa.spa_gate_bwd_workspace_bytes(B, N, C, code), 256), dtype=torch.uint8, **dv)
+
+    def stages(self, x, w, qk, labels, dy) -> List[Tuple[str, Callable[[], None]]]:
+        C = self.C
+        pq, pk, pv = self.packed_qk[:, :C], self.packed_qk[:, C:], self.packed_v
+        dq, dk = self.dqk_packed[:, :C], self.dqk_packed[:, C:]
+        B, N, H, Dh = self.B, self.N, self.H, self.Dh
+        return [
+            ("gate_select", spa.spa_gate_select(x, w, self.bias, None, self.tau, self.scores, self.mask, None, prepare=True)),
+            ("pack_qk", spa.spa_pack(qk, self.mask, None, None, 0, self.packed_qk, self.cu_seqlens,
+                                             self.gather_idx, self.inv_pos, self.total, prepare=True)),
+            ("pack_rg", spa.spa_pack(x, self.mask, None, self.scores, 0, self.packed_v, None, None, None, None,
+                                          prepare=True)),
+            ("packed_attention", spa.spa_packed_attention(pq, pk, pv, self.cu_seqlens, B, N, H, Dh, self.out,
+                                                          self.lse, prepare=True)),
+            ("unpack", spa.spa_unpack(self.out, self.inv_pos, None, self.y, prepare=True)),
+            ("unpack_bwd", spa.spa_unpack_bwd(dy, self.gather_idx, self.total, self.dout, prepare=True)),
+            ("packed_attention_bwd", spa.spa_packed_attention_bwd(
+                pq, pk, pv, self.out, self.dout, self.lse, self.cu_seqlens, B, N, H, Dh, dq, dk, self.dv_packed,
+                self.ws_attn, prepare=True)),
+            ("pack_bwd_v", spa.spa_pack_bwd(self.dv_packed, self.inv_pos, self.d_rg, prepare=True)),
+            ("pack_bwd_qk", spa.spa_pack_bwd(self.dqk_packed, self.inv_pos, self.dqk, prepare=True)),
+            ("gate_bwd", spa.spa_gate_bwd(x, w, self.bias, self.scores, None, labels, self.d_rg, True,
+                                                  self.loss_scale, self.loss, self.dx, self.dw, self.db, self.ws_gate,
+                                          prepare=True)),
+        ]
+
+    def run(self, x, w, qk, labels, dy):
+        for _, fn in self.stages(x, w, qk, labels, dy):
+            fn()
+        return self.loss

@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libspa.so")
+LIB_PATH = os.environ.get("SPA_LIB_PATH", os.path.join(_HERE, "libspa.so"))
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -64,6 +64,31 @@ def _check(rc: int) -> None:
         raise SpaError(rc, lib.spa_last_error().decode())
 
 
+class Prepared:
+    """A C-ABI call with its arguments already marshalled (pointers, sizes and the stream that
+    was current at preparation).  Calling it enqueues the work again with no per-call
+    conversion cost; the tensors it refers to are kept alive by the object."""
+    __slots__ = ("_fn", "_args", "_keep")
+
+    def __init__(self, fn, args, keep):
+        self._fn = fn
+        self._args = tuple(a if not isinstance(a, int) or t is not _P else _P(a)
+                           for a, t in zip(args, fn.argtypes))
+        self._keep = keep
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != SPA_OK:
+            raise SpaError(rc, lib.spa_last_error().decode())
+
+
+def _dispatch(fn, args, keep, prepare):
+    if prepare:
+        return Prepared(fn, args, keep)
+    _check(fn(*args))
+    return None
+
+
 def _ptr(t: Optional[torch.Tensor]):
     if t is None:
         return None
@@ -94,27 +119,31 @@ def spa_version() -> int:
     return lib.spa_version()
 
 
-def spa_gate_select(x, w, bias, s_up, tau, scores, mask, counts=None):
+def spa_gate_select(x, w, bias, s_up, tau, scores, mask, counts=None, prepare=False):
     """x [B,N,C]; w [C]; s_up [B,N] f32 or None -> scores [B,N] f32, mask [B,N] u8, counts [B] i32."""
     B, N, C = x.shape
-    _contig(x, w, s_up, scores, mask, counts)
-    _check(lib.spa_gate_select(_ptr(x), _ptr(w), float(bias), _ptr(s_up), float(tau), B, N, C, dtype_code(x),
-                               _ptr(scores), _ptr(mask), _ptr(counts), _stream()))
+    _keep = (x, w, s_up, scores, mask, counts,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_gate_select, (_ptr(x), _ptr(w), float(bias), _ptr(s_up), float(tau), B, N, C, dtype_code(x),
+                               _ptr(scores), _ptr(mask), _ptr(counts), _stream(),), _keep, prepare)
 
 
-def spa_maxpool2x2(s, h, w, pooled):
+def spa_maxpool2x2(s, h, w, pooled, prepare=False):
     B = s.shape[0]
-    _contig(s, pooled)
-    _check(lib.spa_maxpool2x2(_ptr(s), B, h, w, _ptr(pooled), _stream()))
+    _keep = (s, pooled,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_maxpool2x2, (_ptr(s), B, h, w, _ptr(pooled), _stream(),), _keep, prepare)
 
 
-def spa_pack(x, mask, counts, gate_scores, container_len, packed, cu_seqlens, gather_idx, inv_pos, total):
+def spa_pack(x, mask, counts, gate_scores, container_len, packed, cu_seqlens, gather_idx, inv_pos, total,
+             prepare=False):
     """x [B,N,C] (C may be a fused q|k|v row) -> packed [cap,C], cu_seqlens [B+1], gather_idx, inv_pos, total."""
     B, N, C = x.shape
-    _contig(x, mask, counts, gate_scores, packed, cu_seqlens, gather_idx, inv_pos, total)
-    _check(lib.spa_pack(_ptr(x), _ptr(mask), _ptr(counts), _ptr(gate_scores), B, N, C, dtype_code(x),
+    _keep = (x, mask, counts, gate_scores, packed, cu_seqlens, gather_idx, inv_pos, total,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_pack, (_ptr(x), _ptr(mask), _ptr(counts), _ptr(gate_scores), B, N, C, dtype_code(x),
                         int(container_len), _ptr(packed), _ptr(cu_seqlens), _ptr(gather_idx), _ptr(inv_pos),
-                        _ptr(total), _stream()))
+                        _ptr(total), _stream(),), _keep, prepare)
 
 
 def _row_stride(t) -> int:
@@ -123,31 +152,36 @@ def _row_stride(t) -> int:
     return int(t.stride(0))
 
 
-def spa_packed_attention(q, k, v, cu_seqlens, B, max_seqlen, H, Dh, out, lse=None, softmax_scale=0.0):
+def spa_packed_attention(q, k, v, cu_seqlens, B, max_seqlen, H, Dh, out, lse=None, softmax_scale=0.0,
+                         prepare=False):
     """q, k, v: [rows, H*Dh] tensors or column-slice views of fused packed buffers; the row
     strides are taken from the views."""
-    _contig(out, lse, cu_seqlens)
-    _check(lib.spa_packed_attention(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
+    _keep = (out, lse, cu_seqlens,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_packed_attention, (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
                                     _ptr(cu_seqlens), B, max_seqlen,
-                                    H, Dh, dtype_code(out), float(softmax_scale), _ptr(out), _ptr(lse), _stream()))
+                                    H, Dh, dtype_code(out), float(softmax_scale), _ptr(out), _ptr(lse), _stream(),), _keep, prepare)
 
 
-def spa_unpack(packed_out, inv_pos, base, y):
+def spa_unpack(packed_out, inv_pos, base, y, prepare=False):
     B, N, C = y.shape
-    _contig(packed_out, inv_pos, base, y)
-    _check(lib.spa_unpack(_ptr(packed_out), _ptr(inv_pos), _ptr(base), B, N, C, dtype_code(y), _ptr(y), _stream()))
+    _keep = (packed_out, inv_pos, base, y,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_unpack, (_ptr(packed_out), _ptr(inv_pos), _ptr(base), B, N, C, dtype_code(y), _ptr(y), _stream(),), _keep, prepare)
 
 
-def spa_unpack_bwd(dy, gather_idx, total, dout):
+def spa_unpack_bwd(dy, gather_idx, total, dout, prepare=False):
     B, N, C = dy.shape
-    _contig(dy, gather_idx, total, dout)
-    _check(lib.spa_unpack_bwd(_ptr(dy), _ptr(gather_idx), _ptr(total), B, N, C, dtype_code(dy), _ptr(dout), _stream()))
+    _keep = (dy, gather_idx, total, dout,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_unpack_bwd, (_ptr(dy), _ptr(gather_idx), _ptr(total), B, N, C, dtype_code(dy), _ptr(dout), _stream(),), _keep, prepare)
 
 
-def spa_pack_bwd(dpacked, inv_pos, d_rg):
+def spa_pack_bwd(dpacked, inv_pos, d_rg, prepare=False):
     B, N, C = d_rg.shape
-    _contig(dpacked, inv_pos, d_rg)
-    _check(lib.spa_pack_bwd(_ptr(dpacked), _ptr(inv_pos), B, N, C, dtype_code(d_rg), _ptr(d_rg), _stream()))
+    _keep = (dpacked, inv_pos, d_rg,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_pack_bwd, (_ptr(dpacked), _ptr(inv_pos), B, N, C, dtype_code(d_rg), _ptr(d_rg), _stream(),), _keep, prepare)
 
 
 def spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype) -> int:
@@ -155,32 +189,36 @@ def spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype) -> int:
 
 
 def spa_packed_attention_bwd(q, k, v, out, dout, lse, cu_seqlens, B, max_seqlen, H, Dh,
-                             dq, dk, dv, workspace, softmax_scale=0.0):
-    _contig(out, dout, lse, cu_seqlens, workspace)
+                             dq, dk, dv, workspace, softmax_scale=0.0, prepare=False):
+    _keep = (out, dout, lse, cu_seqlens, workspace,)
+    _contig(*_keep)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.spa_packed_attention_bwd(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
+    return _dispatch(lib.spa_packed_attention_bwd, (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
                                         _ptr(out), _ptr(dout), _ptr(lse), _ptr(cu_seqlens), B, max_seqlen, H, Dh,
                                         dtype_code(out), float(softmax_scale), _ptr(dq), _ptr(dk), _ptr(dv),
                                         _row_stride(dq), _row_stride(dk), _row_stride(dv), _ptr(workspace),
-                                        ws_bytes, _stream()))
+                                        ws_bytes, _stream(),), _keep, prepare)
 
 
 def spa_gate_bwd_workspace_bytes(B, N, C, dtype) -> int:
     return int(lib.spa_gate_bwd_workspace_bytes(B, N, C, dtype))
 
 
-def spa_gate_bwd(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, loss, dx, dw, db, workspace):
+def spa_gate_bwd(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, loss, dx, dw, db, workspace,
+                 prepare=False):
     B, N, C = x.shape
-    _contig(x, w, scores, s_up, labels, d_rg, loss, dx, dw, db, workspace)
+    _keep = (x, w, scores, s_up, labels, d_rg, loss, dx, dw, db, workspace,)
+    _contig(*_keep)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.spa_gate_bwd(_ptr(x), _ptr(w), float(bias), _ptr(scores), _ptr(s_up), _ptr(labels), _ptr(d_rg),
+    return _dispatch(lib.spa_gate_bwd, (_ptr(x), _ptr(w), float(bias), _ptr(scores), _ptr(s_up), _ptr(labels), _ptr(d_rg),
                             int(bool(gate_scaled)), float(loss_scale), B, N, C, dtype_code(x), _ptr(loss), _ptr(dx),
-                            _ptr(dw), _ptr(db), _ptr(workspace), ws_bytes, _stream()))
+                            _ptr(dw), _ptr(db), _ptr(workspace), ws_bytes, _stream(),), _keep, prepare)
 
 
-def spa_padded_attention(q, k, v, seqlens, B, n_pad, H, Dh, out, softmax_scale=0.0):
-    _contig(out, seqlens)
+def spa_padded_attention(q, k, v, seqlens, B, n_pad, H, Dh, out, softmax_scale=0.0, prepare=False):
+    _keep = (out, seqlens,)
+    _contig(*_keep)
     if not (_row_stride(q) == _row_stride(k) == _row_stride(v)):
         raise ValueError("spa_padded_attention takes one row stride for q, k, v")
-    _check(lib.spa_padded_attention(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _ptr(seqlens), B, n_pad, H, Dh,
-                                    dtype_code(out), float(softmax_scale), _ptr(out), _stream()))
+    return _dispatch(lib.spa_padded_attention, (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _ptr(seqlens), B, n_pad, H, Dh,
+                                    dtype_code(out), float(softmax_scale), _ptr(out), _stream(),), _keep, prepare)
