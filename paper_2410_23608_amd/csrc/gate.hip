@@ -217,19 +217,32 @@ gate_bwd_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
   }
 }
 
+// Adds the partial rows in a fixed order: a block owns 16 columns; 16 row slices run in
+// parallel (slice s adds rows s, s+16, ...), then the slices are added 0..15.
 __global__ void __launch_bounds__(256)
 gate_bwd_reduce_kernel(const float* __restrict__ partial, int nparts, int C, float loss_scale,
                        float* __restrict__ loss, float* __restrict__ dw, float* __restrict__ db) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= C + 2) return;
+  __shared__ float red[16][17];
+  const int cl = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl;
   float a = 0.f;
-  for (int i = 0; i < nparts; ++i) a += partial[(long)i * (C + 2) + c];
-  if (c < C) dw[c] = a;
-  else if (c == C) loss[0] = a * loss_scale;
-  else db[0] = a;
+  if (c < C + 2) {
+#pragma unroll 8
+    for (int i = sl; i < nparts; i += 16) a += partial[(long)i * (C + 2) + c];
+  }
+  red[sl][cl] = a;
+  __syncthreads();
+  if (sl == 0 && c < C + 2) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += red[i][cl];
+    if (c < C) dw[c] = t;
+    else if (c == C) loss[0] = t * loss_scale;
+    else db[0] = t;
+  }
 }
 
-constexpr int kGateBwdMaxParts = 1024;
+constexpr int kGateBwdMaxParts = 512;
 
 static int gate_bwd_parts(long ntok) {
   long p = (ntok + 15) / 16;
@@ -325,7 +338,7 @@ static int launch_gate_bwd(const void* x, const void* w, float bias, const float
   else if (chunks <= 512) SPA_GB(64, 8);
   else return fail(SPA_ERR_UNSUPPORTED, "spa_gate_bwd: C = %d too large (at most %d)", C, 512 * VE);
 #undef SPA_GB
-  hipLaunchKernelGGL(gate_bwd_reduce_kernel, dim3((C + 2 + 255) / 256), dim3(256), 0, st, partial, parts, C,
+  hipLaunchKernelGGL(gate_bwd_reduce_kernel, dim3((C + 2 + 15) / 16), dim3(256), 0, st, partial, parts, C,
                      loss_scale, loss, dw, db);
   return check_launch("spa_gate_bwd");
 }
