@@ -136,12 +136,13 @@ __device__ __forceinline__ void fwd_process_tile(const __bf16* kbuf, const __bf1
   acc.l += psum;
 }
 
-// Normalise and store this wave's 32 output rows (+ lse).  Called by every lane of a live wave.
-template <int DH>
-__device__ __forceinline__ void fwd_store(FwdAcc<DH>& acc, bool q_ok, bool have_keys, __bf16* orow,
-                                          float* lse_ptr, int hh) {
+// Output stage, phase 1: normalise this wave's O^T accumulators and park the 32 x DH bf16
+// tile in LDS (row = query, row stride RS), so that phase 2 can write whole rows.
+// Also writes lse.  Called by every lane of a live wave.
+template <int DH, int RS>
+__device__ __forceinline__ void fwd_park(FwdAcc<DH>& acc, bool q_ok, bool have_keys, __bf16* tile,
+                                         float* lse_ptr, int l32, int hh) {
   const float l_tot = acc.l + __shfl_xor(acc.l, 32, kWave);
-  if (!q_ok) return;
   const float inv = have_keys ? 1.0f / l_tot : 0.f;
 #pragma unroll
   for (int d = 0; d < DH / 32; ++d)
@@ -149,10 +150,73 @@ __device__ __forceinline__ void fwd_store(FwdAcc<DH>& acc, bool q_ok, bool have_
     for (int g = 0; g < 4; ++g) {
       floatx4 f = {acc.o[d][4 * g] * inv, acc.o[d][4 * g + 1] * inv, acc.o[d][4 * g + 2] * inv,
                    acc.o[d][4 * g + 3] * inv};
-      *reinterpret_cast<bf16x4*>(orow + d * 32 + 8 * g + 4 * hh) = __builtin_convertvector(f, bf16x4);
+      *reinterpret_cast<bf16x4*>(&tile[l32 * RS + d * 32 + 8 * g + 4 * hh]) = __builtin_convertvector(f, bf16x4);
     }
-  if (lse_ptr != nullptr && hh == 0)
+  if (q_ok && lse_ptr != nullptr && hh == 0)
     *lse_ptr = have_keys ? (acc.m + __log2f(l_tot)) * 0.69314718055994531f : -INFINITY;
+}
+
+// Output stage, phase 2 (after a barrier): the wave copies its parked tile to global memory,
+// consecutive lanes writing consecutive 16-byte chunks of a row.  nrows = valid rows (<= 32).
+template <int DH, int RS>
+__device__ __forceinline__ void fwd_flush(const __bf16* tile, __bf16* orow0, long C, int nrows, int lane) {
+  constexpr int CPR = DH / 8;
+#pragma unroll
+  for (int i = lane; i < 32 * CPR; i += 64) {
+    const int r = i / CPR, c = i % CPR;
+    if (r < nrows)
+      *reinterpret_cast<bf16x8*>(orow0 + r * C + c * 8) = *reinterpret_cast<const bf16x8*>(&tile[r * RS + c * 8]);
+  }
+}
+
+// Longest-segment-first launch order.  Work per segment grows like n^2 and workgroups are
+// handed to compute units in launch order, so the heaviest images should start first.  Maps
+// launch rank -> image by ranking the segment lengths (ties by index) and returns that
+// image's segment; all threads of the workgroup call it.  The bounds are staged in LDS once,
+// so no second dependent global load is needed.  For B > kLptMaxB the order is the identity.
+// Used by the long-segment kernel only: short-segment workgroups are all resident at once
+// and the ranking would cost more than it gains.
+// s_cu: 2*kLptMaxB + 1 ints of LDS.
+constexpr int kLptMaxB = 256;
+template <int THREADS>
+__device__ __forceinline__ Segment lpt_segment(int rank, int B, const int32_t* cu, const int32_t* key_lens,
+                                               int n_pad, int* s_cu, int* s_pick) {
+  if (B > kLptMaxB || B == 1) return segment_of(rank, cu, key_lens, n_pad);
+  // s_cu[b] = segment start (packed mode only), s_len[b] = segment / key length
+  int* s_len = s_cu + kLptMaxB + 1;
+  const bool padded = key_lens != nullptr;
+  for (int b = threadIdx.x; b < B; b += THREADS) {
+    if (padded) {
+      s_len[b] = key_lens[b];
+    } else {
+      const int a = cu[b], e = cu[b + 1];
+      s_cu[b] = a;
+      s_len[b] = e - a;
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < B; b += THREADS) {
+    const int nb = s_len[b];
+    int r = 0;
+#pragma unroll 8
+    for (int j = 0; j < B; ++j) {
+      const int nj = s_len[j];
+      r += (nj > nb) | ((nj == nb) & (j < b));
+    }
+    if (r == rank) *s_pick = b;
+  }
+  __syncthreads();
+  const int img = *s_pick;
+  Segment s;
+  if (padded) {
+    s.row0 = (long)img * n_pad;
+    s.nq = n_pad;
+    s.nk = min(max(s_len[img], 0), n_pad);
+  } else {
+    s.row0 = s_cu[img];
+    s.nq = s.nk = s_len[img];
+  }
+  return s;
 }
 
 // Register staging of key/value rows on their way to LDS: task i = 16-byte chunk column
@@ -223,9 +287,12 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   constexpr int RS = DH + 8, TS = transposed_stride(BN), NSB = BN / 32;
   __shared__ __attribute__((aligned(16))) __bf16 Ks[2][BN * RS];
   __shared__ __attribute__((aligned(16))) __bf16 Vt[2][DH * TS];
+  __shared__ int s_cu[2 * kLptMaxB + 1];
+  __shared__ int s_pick;
+  static_assert(2 * BN >= 32 * NW, "the K buffers double as the output staging tile");
 
   const int h = blockIdx.y;
-  const Segment seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
+  const Segment seg = lpt_segment<64 * NW>(blockIdx.z, gridDim.z, cu, key_lens, n_pad, s_cu, &s_pick);
   const int q0 = blockIdx.x * (32 * NW);
   if (q0 >= seg.nq) return;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -257,9 +324,14 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
     if (t + 1 < nt) stage.template store<RS, TS>(Ks[buf ^ 1], Vt[buf ^ 1], 0);
     __syncthreads();
   }
-  if (!wave_live) return;
-  fwd_store<DH>(acc, q_ok, seg.nk > 0, out + (seg.row0 + qi) * C + h * DH,
-                lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr, hh);
+  // every wave is past its last read of the K buffers (the loop ends with a barrier)
+  __bf16* tile = &Ks[0][0] + wv * 32 * RS;
+  if (wave_live)
+    fwd_park<DH, RS>(acc, q_ok, seg.nk > 0, tile, lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr,
+                     l32, hh);
+  __syncthreads();
+  if (wave_live)
+    fwd_flush<DH, RS>(tile, out + (seg.row0 + q0 + wv * 32) * C + h * DH, C, min(32, seg.nq - q0 - wv * 32), lane);
 }
 
 // Short segments (every segment <= NKMAX keys).  ONE workgroup per (image, head): all K / V
@@ -299,15 +371,21 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   acc.init();
   stage.template store<RS, TS>(Ks, Vt, 0);
   __syncthreads();
-  if (!wave_live) return;
-
-  for (int kt = 0; kt < seg.nk; kt += TILE) {
-    const int rem = seg.nk - kt;
-    if (rem >= TILE) fwd_process_tile<DH, RS, TS, NSB, true>(Ks + kt * RS, Vt, kt, TILE, qf, acc, scale_log2, l32, hh);
-    else fwd_process_tile<DH, RS, TS, NSB, false>(Ks + kt * RS, Vt, kt, rem, qf, acc, scale_log2, l32, hh);
+  if (wave_live) {
+    for (int kt = 0; kt < seg.nk; kt += TILE) {
+      const int rem = seg.nk - kt;
+      if (rem >= TILE) fwd_process_tile<DH, RS, TS, NSB, true>(Ks + kt * RS, Vt, kt, TILE, qf, acc, scale_log2, l32, hh);
+      else fwd_process_tile<DH, RS, TS, NSB, false>(Ks + kt * RS, Vt, kt, rem, qf, acc, scale_log2, l32, hh);
+    }
   }
-  fwd_store<DH>(acc, q_ok, seg.nk > 0, out + (seg.row0 + qi) * C + h * DH,
-                lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr, hh);
+  __syncthreads();                       // all waves are done reading K: its rows become the output tile
+  __bf16* tile = Ks + wv * 32 * RS;
+  if (wave_live)
+    fwd_park<DH, RS>(acc, q_ok, seg.nk > 0, tile, lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr,
+                     l32, hh);
+  __syncthreads();
+  if (wave_live)
+    fwd_flush<DH, RS>(tile, out + (seg.row0 + wv * 32) * C + h * DH, C, min(32, seg.nq - wv * 32), lane);
 }
 
 // ------------------------------------------------------------------------------- fp32
