@@ -1,0 +1,258 @@
+"""Full-size parity of the HIP path in the launch configuration bench.py times (through
+paper_2410_23608_amd.pipeline), the multi-stage hierarchy with up-scale scores, property
+tests over random shapes, and run-to-run determinism."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import spa_oracle as orc
+from paper_2410_23608_amd import workloads as wlmod
+from spa_harness import dev, host, tdtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def spa():
+    from paper_2410_23608_amd import spa as mod
+    return mod
+
+
+@pytest.fixture(scope="module")
+def pipeline():
+    from paper_2410_23608_amd import pipeline as mod
+    return mod
+
+
+def _sampled_attention_reference(q, k, v, mask, H, rows):
+    """Oracle attention for a sample of packed rows only, one row at a time: row j of image b
+    attends to all selected tokens of b.  Plain definition, fp64."""
+    B, N, C = q.shape
+    Dh = C // H
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    out = np.zeros((len(rows), C))
+    for t, j in enumerate(rows):
+        b = int(np.searchsorted(cu, j, side="right") - 1)
+        sel = np.flatnonzero(mask[b])
+        n = gidx[j] - b * N
+        for h in range(H):
+            sl = slice(h * Dh, (h + 1) * Dh)
+            s = k[b, sel, sl].astype(np.float64) @ q[b, n, sl].astype(np.float64) / np.sqrt(Dh)
+            p = np.exp(s - s.max())
+            out[t, sl] = (p / p.sum()) @ v[b, sel, sl].astype(np.float64)
+    return out
+
+
+@pytest.mark.parametrize("name", ["vit_s", "det"])
+def test_full_size_forward_as_benchmarked(spa, pipeline, name):
+    """The exact batch and launch path of bench.py: integers bit-exact, packed rows bit-exact,
+    attention checked on every row (vit_s) or on sampled rows computed one by one (det)."""
+    wl = wlmod.WORKLOADS[name]
+    bun = wlmod.generate(wl, 0)
+    C = wl.C
+    fp = pipeline.ForwardPass(wl.B, wl.N, C, wl.H, wl.dtype, wl.tau, wl.bias)
+    fp.run(dev(bun["x"], wl.dtype), dev(bun["w"], wl.dtype), dev(bun["qkv"], wl.dtype))
+    torch.cuda.synchronize()
+    s = orc.gate_scores(bun["x"], bun["w"], bun["bias"])
+    mask, margin = orc.select(s, wl.tau)
+    assert margin > 1e-3
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    assert np.array_equal(host(fp.mask), mask)
+    assert np.array_equal(host(fp.cu_seqlens), cu) and int(host(fp.total)[0]) == T
+    assert np.array_equal(host(fp.gather_idx)[:T], gidx) and np.array_equal(host(fp.inv_pos), inv)
+    assert np.array_equal(host(fp.packed_qkv)[:T], bun["qkv"].reshape(-1, 3 * C)[gidx])
+    q, k, v = bun["qkv"][..., :C], bun["qkv"][..., C:2 * C], bun["qkv"][..., 2 * C:]
+    out = host(fp.out)
+    if name == "vit_s":
+        ref, _ = orc.attention_per_image(q, k, v, mask, wl.H)
+        assert np.max(np.abs(out[:T] - ref)) <= 2e-2
+    else:
+        rng = np.random.default_rng(0)
+        rows = np.unique(np.concatenate([rng.integers(0, T, 48), cu[:-1][np.diff(cu) > 0], cu[1:][np.diff(cu) > 0] - 1]))
+        ref = _sampled_attention_reference(q, k, v, mask, wl.H, rows)
+        assert np.max(np.abs(out[rows] - ref)) <= 2e-2
+    # scatter back: exact copies at selected positions, zeros elsewhere (a property at any size)
+    y = host(fp.y).reshape(-1, C)
+    assert np.array_equal(y[gidx], out[:T]) and np.all(y[inv < 0] == 0)
+
+
+def test_full_size_training_step_as_benchmarked(spa, pipeline):
+    """ViT-B-shaped forward+backward step at full batch through pipeline.TrainPass."""
+    wl = wlmod.WORKLOADS["vit_b_train"]
+    B, N, C, H = wl.B, wl.N, wl.C, wl.H
+    bun = wlmod.generate(wl, 0)
+    tp = pipeline.TrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias)
+    qk = bun["qkv"][:, :, :2 * C]
+    tp.run(dev(bun["x"], "bf16"), dev(bun["w"], "bf16"), dev(qk, "bf16"), dev(bun["labels"]), dev(bun["dy"], "bf16"))
+    torch.cuda.synchronize()
+    x, w, bias = bun["x"], bun["w"], bun["bias"]
+    s = orc.gate_scores(x, w, bias)
+    mask, margin = orc.select(s, wl.tau)
+    assert margin > 1e-3
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    assert np.array_equal(host(tp.mask), mask) and np.array_equal(host(tp.cu_seqlens), cu)
+    rg = orc.round_to_dtype(orc.sigmoid(s.astype(np.float32).astype(np.float64))[:, :, None] * x, "bf16")
+    out_ref, _ = orc.attention_per_image(qk[:, :, :C], qk[:, :, C:], rg, mask, H)
+    assert np.max(np.abs(host(tp.out)[:T] - out_ref)) <= 2e-2
+    dO = bun["dy"].reshape(-1, C)[gidx]
+    rdq, rdk, rdv = orc.attention_backward_per_image(qk[:, :, :C], qk[:, :, C:], rg, mask, dO, H)
+
+    def rel(got, ref):
+        return float(np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref))))
+
+    dqk = host(tp.dqk_packed)
+    assert rel(dqk[:T, :C], rdq) <= 2e-2 and rel(dqk[:T, C:], rdk) <= 2e-2
+    assert rel(host(tp.dv_packed)[:T], rdv) <= 2e-2
+    g = orc.gate_backward(x, w, bias, None, bun["labels"], orc.unpack(rdv, inv, B, N), True, tp.loss_scale)
+    assert rel(host(tp.dx), g["dx"]) <= 2e-2
+    assert rel(host(tp.dw), g["dw"]) <= 2e-2
+    assert abs(float(host(tp.loss)[0]) - g["loss"]) <= 1e-3 * abs(g["loss"])
+    # gradient w.r.t. the un-packed q|k: packed gradients at selected positions, zero elsewhere
+    dqk_full = host(tp.dqk).reshape(-1, 2 * C)
+    assert np.array_equal(dqk_full[gidx], dqk[:T]) and np.all(dqk_full[inv < 0] == 0)
+
+
+def test_maxpool_matches_oracle(spa):
+    rng = np.random.default_rng(3)
+    for B, h, w in ((3, 8, 6), (2, 56, 56), (1, 2, 2)):
+        s = rng.standard_normal((B, h * w)).astype(np.float32)
+        out = torch.empty(B, (h // 2) * (w // 2), dtype=torch.float32, device="cuda")
+        spa.spa_maxpool2x2(dev(s), h, w, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(out).astype(np.float64), orc.maxpool2x2(s, h, w))
+
+
+def test_hierarchy_forward_with_upscale_scores(spa, pipeline):
+    """Four Swin-like stages (reduced batch): each stage's scores are max-merged with the
+    2x2 max-pooled scores of the finer stage; selection, packing and attention per stage."""
+    bundles = wlmod.generate_hierarchy(seed=1, B=3)
+    s_up_ref, s_up_dev = None, None
+    for i, bun in enumerate(bundles):
+        wl = bun["workload"]
+        h, w = wl.grid
+        C = wl.C
+        ref = orc.spa_forward(bun["x"], bun["w"], bun["bias"], bun["qkv"], wl.H, wl.tau, wl.dtype, s_up=s_up_ref)
+        assert ref["margin"] > 1e-3
+        fp = pipeline.ForwardPass(wl.B, wl.N, C, wl.H, wl.dtype, wl.tau, wl.bias)
+        fp.run(dev(bun["x"], wl.dtype), dev(bun["w"], wl.dtype), dev(bun["qkv"], wl.dtype), s_up=s_up_dev)
+        torch.cuda.synchronize()
+        T = ref["total"]
+        assert np.array_equal(host(fp.mask), ref["mask"])
+        assert np.array_equal(host(fp.cu_seqlens), ref["cu_seqlens"])
+        assert np.array_equal(host(fp.gather_idx)[:T], ref["gather_idx"])
+        assert np.max(np.abs(host(fp.out)[:T] - ref["out"])) <= 2e-2
+        assert np.max(np.abs(host(fp.y) - ref["y"])) <= 2e-2
+        if i > 0:
+            # the up-scale scores added tokens the stage's own gate would have dropped,
+            # and the stage covers the pooled foreground of the finer stage
+            own, _ = orc.select(orc.gate_scores(bun["x"], bun["w"], bun["bias"]), wl.tau)
+            assert ref["mask"].sum() > own.sum()
+            assert np.all(ref["mask"] >= bun["stage_foreground"])
+        if i + 1 < len(bundles):
+            # hand the post-max scores to the next (2x coarser) stage
+            s_up_ref = orc.maxpool2x2(ref["scores"].astype(np.float32), h, w).astype(np.float32)
+            pooled = torch.empty(wl.B, (h // 2) * (w // 2), dtype=torch.float32, device="cuda")
+            spa.spa_maxpool2x2(fp.scores, h, w, pooled)
+            s_up_dev = pooled
+            torch.cuda.synchronize()
+            assert np.max(np.abs(host(pooled) - s_up_ref)) <= 1e-3
+
+
+def test_hierarchy_backward_stage_with_upscale_scores(spa, pipeline):
+    """Backward of a coarse stage whose scores were partly taken from s_up: no gradient to
+    (w, b) where the up-scale score won the max."""
+    bundles = wlmod.generate_hierarchy(seed=2, B=2)
+    b2, b3 = bundles[1], bundles[2]
+    wl2, wl3 = b2["workload"], b3["workload"]
+    s2 = orc.gate_scores(b2["x"], b2["w"], b2["bias"])
+    s_up = orc.maxpool2x2(s2.astype(np.float32), *wl2.grid).astype(np.float32)
+    B, N, C = wl3.B, wl3.N, wl3.C
+    x, w = b3["x"], b3["w"]
+    g_own = orc.gate_only(x, w, b3["bias"])
+    assert np.min(np.abs(g_own - s_up)) > 1e-4 and (g_own < s_up).any() and (g_own > s_up).any()
+    rng = np.random.default_rng(5)
+    d_rg = wlmod.round_bf16(rng.standard_normal((B, N, C)).astype(np.float32))
+    lam = 0.01 / (B * N)
+    ref = orc.gate_backward(x, w, b3["bias"], s_up, b3["labels"], d_rg, True, lam)
+    xd, wd, sup_d = dev(x, "bf16"), dev(w, "bf16"), dev(s_up)
+    scores = torch.empty(B, N, dtype=torch.float32, device="cuda")
+    mask = torch.empty(B, N, dtype=torch.uint8, device="cuda")
+    spa.spa_gate_select(xd, wd, b3["bias"], sup_d, wl3.tau, scores, mask)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    dx = torch.empty(B, N, C, dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty(C, dtype=torch.float32, device="cuda")
+    db = torch.empty(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(spa.spa_gate_bwd_workspace_bytes(B, N, C, spa.SPA_BF16), dtype=torch.uint8, device="cuda")
+    spa.spa_gate_bwd(xd, wd, b3["bias"], scores, sup_d, dev(b3["labels"]), dev(d_rg, "bf16"), True, lam, loss, dx, dw, db, ws)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(host(scores) - ref["scores"])) <= 1e-3 * (1 + np.abs(ref["scores"]).max())
+    assert np.max(np.abs(host(dx) - ref["dx"])) / max(1.0, np.abs(ref["dx"]).max()) <= 2e-2
+    assert np.max(np.abs(host(dw) - ref["dw"])) / max(1.0, np.abs(ref["dw"]).max()) <= 1e-3
+    assert abs(float(host(db)[0]) - ref["db"]) <= 1e-3 * max(1.0, abs(ref["db"]))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_forward(spa, seed):
+    """Random B, N, H, head dim, dtype, selection density (including empty and full images,
+    N not a multiple of any tile): integers bit-exact, values within tolerance."""
+    rng = np.random.default_rng(100 + seed)
+    dtype = ["f32", "bf16"][seed % 2]
+    Dh = [32, 64][(seed // 2) % 2]
+    H = int(rng.integers(1, 5))
+    C = H * Dh
+    B = int(rng.integers(1, 7))
+    N = int(rng.integers(1, 400))
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    x = mk(rng.standard_normal((B, N, C)).astype(np.float32))
+    w = mk((rng.standard_normal(C) / np.sqrt(C)).astype(np.float32))
+    qkv = mk(rng.standard_normal((B, N, 3 * C)).astype(np.float32))
+    bias = float(rng.normal() * 0.5)
+    ref = orc.spa_forward(x, w, bias, qkv, H, 0.5, dtype)
+    near = np.abs(ref["scores"]) < 1e-3        # tokens whose decision is a rounding tie are excluded
+    td = tdtype(dtype)
+    cap = B * N
+    scores = torch.empty(B, N, dtype=torch.float32, device="cuda")
+    mask = torch.empty(B, N, dtype=torch.uint8, device="cuda")
+    spa.spa_gate_select(dev(x, dtype), dev(w, dtype), bias, None, 0.5, scores, mask)
+    torch.cuda.synchronize()
+    got_mask = host(mask)
+    assert np.array_equal(got_mask[~near], ref["mask"][~near])
+    # continue from the device's own mask so a near-tie cannot change the rest of the check
+    ref_cu, ref_gidx, ref_inv, T = orc.pack_indices(got_mask)
+    packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    gidx = torch.empty(cap, dtype=torch.int32, device="cuda")
+    inv = torch.empty(cap, dtype=torch.int32, device="cuda")
+    total = torch.empty(1, dtype=torch.int32, device="cuda")
+    out = torch.zeros(cap, C, dtype=td, device="cuda")
+    lse = torch.zeros(H, cap, dtype=torch.float32, device="cuda")
+    y = torch.empty(B, N, C, dtype=td, device="cuda")
+    spa.spa_pack(dev(qkv, dtype), mask, None, None, 0, packed, cu, gidx, inv, total)
+    spa.spa_packed_attention(packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:], cu, B, N, H, Dh, out, lse)
+    spa.spa_unpack(out, inv, None, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(cu), ref_cu) and int(host(total)[0]) == T
+    assert np.array_equal(host(gidx)[:T], ref_gidx) and np.array_equal(host(inv), ref_inv)
+    ref_out, _ = orc.attention_per_image(qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], got_mask, H)
+    tol = 1e-5 if dtype == "f32" else 2e-2
+    assert np.max(np.abs(host(out)[:T] - ref_out), initial=0.0) <= tol
+    assert np.max(np.abs(host(y) - orc.unpack(ref_out, ref_inv, B, N))) <= tol
+
+
+def test_forward_is_run_to_run_bit_stable(spa, pipeline):
+    wl = dataclasses.replace(wlmod.WORKLOADS["vit_s"], B=16)
+    bun = wlmod.generate(wl, 4)
+    fp = pipeline.ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias)
+    x, w, qkv = dev(bun["x"], "bf16"), dev(bun["w"], "bf16"), dev(bun["qkv"], "bf16")
+    first = None
+    for _ in range(5):
+        fp.run(x, w, qkv)
+        torch.cuda.synchronize()
+        snap = [host(t).copy() for t in (fp.scores, fp.mask, fp.cu_seqlens, fp.inv_pos, fp.out, fp.lse, fp.y)]
+        if first is None:
+            first = snap
+        else:
+            for a, b in zip(first, snap):
+                assert np.array_equal(a, b)
