@@ -134,6 +134,24 @@ int spa_packed_attention(const void* q, const void* k, const void* v, int64_t q_
 int spa_unpack(const void* packed_out, const int32_t* inv_pos, const void* base,
                int B, int N, int C, int dtype, void* y, void* stream);
 
+/*
+ * spa_packed_attention followed by spa_unpack, in one launch: packed output row j is written
+ * to y[gather_idx[j], :] (plus base) by the attention kernel itself, and the rows that
+ * bypass attention (inv_pos < 0) are filled with base or zero by the same kernel.  Results
+ * equal the two separate calls (same arithmetic, same roundings).
+ * in:  q, k, v, strides, cu_seqlens, softmax_scale as in spa_packed_attention; gather_idx,
+ *      inv_pos [B*N] int32 from spa_pack; base [B,N,C] dtype or NULL; N tokens per image
+ *      (also the bound on every segment length); C = H*Dh.
+ * out: y [B,N,C] dtype; out [>= T, H*Dh] dtype or NULL (the packed output, kept when a
+ *      backward pass needs it); lse [H, B*N] fp32 or NULL.  y may alias base.
+ */
+int spa_packed_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                int64_t k_row_stride, int64_t v_row_stride,
+                                const int32_t* cu_seqlens, const int32_t* gather_idx,
+                                const int32_t* inv_pos, const void* base, int B, int N, int H, int Dh,
+                                int dtype, float softmax_scale, void* out, float* lse, void* y,
+                                void* stream);
+
 /* ----------------------------------------------------------------- training ---- */
 
 /*

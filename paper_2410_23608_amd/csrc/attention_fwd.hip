@@ -16,6 +16,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <type_traits>
 
 #include "attn_tiles.h"
@@ -45,6 +46,36 @@ __device__ __forceinline__ Segment segment_of(int b, const int32_t* cu, const in
   return s;
 }
 
+// Optional fused scatter-back (the unpack step folded into the attention kernel): packed
+// output row j goes to y[gather_idx[j]] (plus base), and every workgroup first fills its
+// share of the rows that bypass attention (inv_pos < 0) with base or zero.  All-null = off.
+struct Scatter {
+  const int32_t* gather_idx;   // [B*N] packed row -> flat token
+  const int32_t* inv_pos;      // [B*N] flat token -> packed row or -1
+  const void* base;            // [B*N, C] residual or nullptr
+  void* y;                     // [B*N, C]
+  int N;                       // tokens per image
+};
+
+// Fill the head slice [h*DH, (h+1)*DH) of the bypassing rows among tokens [t0, t1) of image b.
+// Shared by `nthreads` threads, this one being number `tid` of them.
+template <typename T, int DH>
+__device__ __forceinline__ void scatter_fill(const Scatter& sc, int b, int t0, int t1, int h, long C, int tid,
+                                             int nthreads) {
+  constexpr int VE = 16 / sizeof(T), CPR = DH / VE;
+  const long tok0 = (long)b * sc.N;
+  const int work = (t1 - t0) * CPR;
+  for (int i = tid; i < work; i += nthreads) {
+    const int t = t0 + i / CPR, c = i % CPR;
+    if (sc.inv_pos[tok0 + t] < 0) {
+      const long off = (tok0 + t) * C + h * DH + c * VE;
+      uintx4 val = {0u, 0u, 0u, 0u};
+      if (sc.base != nullptr) val = *reinterpret_cast<const uintx4*>(static_cast<const T*>(sc.base) + off);
+      *reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off) = val;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------- bf16 / MFMA
 // Per-wave state of the online softmax: O^T accumulators (rows = head dim, cols = this
 // wave's 32 queries), running max m (log2 domain, scale folded in) and running sum l (the
@@ -63,39 +94,43 @@ struct FwdAcc {
   }
 };
 
-// One tile of NSB*32 keys held in LDS (K rows at kbuf, row stride RS; V^T at vbuf, row
-// stride TS, the tile's keys starting at column vcol0): all score sub-tiles S^T = K Q^T
-// first, then ONE online-softmax update (max, rescale, exp, sum) over the whole tile, then
-// O^T += V^T P^T.  rem = valid keys in the tile; FULL = every key valid (no masking code).
-template <int DH, int RS, int TS, int NSB, bool FULL>
-__device__ __forceinline__ void fwd_process_tile(const __bf16* kbuf, const __bf16* vbuf, int vcol0, int rem,
-                                                 const bf16x8 (&qf)[DH / 16], FwdAcc<DH>& acc,
-                                                 float scale_log2, int l32, int hh) {
-  constexpr int KK = DH / 16, DB = DH / 32;
-  floatx16 s[NSB];
+// Score sub-tiles of one group of GSB*32 keys: S^T = K Q^T (rows = keys, cols = queries).
+// key0 = first key of the group inside the LDS tile, rem = valid keys of the tile.
+template <int DH, int RS, int GSB, bool FULL>
+__device__ __forceinline__ void fwd_scores(const __bf16* kbuf, int key0, int rem, const bf16x8 (&qf)[DH / 16],
+                                           floatx16 (&s)[GSB], int l32, int hh) {
 #pragma unroll
-  for (int sb = 0; sb < NSB; ++sb) {
-    if (FULL || sb * 32 < rem) {
+  for (int sb = 0; sb < GSB; ++sb) {
+    const int k0 = key0 + sb * 32;
+    if (FULL || k0 < rem) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&kbuf[(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
+      for (int kk = 0; kk < DH / 16; ++kk) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&kbuf[(k0 + l32) * RS + kk * 16 + hh * 8]);
         s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s[sb], 0, 0, 0);
       }
-      if (!FULL && rem - sb * 32 < 32) {
+      if (!FULL && rem - k0 < 32) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (sb * 32 + acc_row(r, hh) >= rem) s[sb][r] = -INFINITY;
+          if (k0 + acc_row(r, hh) >= rem) s[sb][r] = -INFINITY;
       }
     } else {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[sb][r] = -INFINITY;
     }
   }
+}
+
+// One online-softmax update (max, rescale, exp, sum) over a group of GSB*32 keys, then
+// O^T += V^T P^T for the group.  V^T at vbuf (row stride TS), the group's keys at column vcol.
+template <int DH, int TS, int GSB, bool FULL>
+__device__ __forceinline__ void fwd_softmax_pv(const floatx16 (&s)[GSB], const __bf16* vbuf, int vcol, int key0,
+                                               int rem, FwdAcc<DH>& acc, float scale_log2, int l32, int hh) {
+  constexpr int DB = DH / 32;
   float mx = s[0][0];
 #pragma unroll
-  for (int sb = 0; sb < NSB; ++sb)
+  for (int sb = 0; sb < GSB; ++sb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
   mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
@@ -111,8 +146,8 @@ __device__ __forceinline__ void fwd_process_tile(const __bf16* kbuf, const __bf1
   }
   float psum = 0.f;
 #pragma unroll
-  for (int sb = 0; sb < NSB; ++sb) {
-    if (FULL || sb * 32 < rem) {
+  for (int sb = 0; sb < GSB; ++sb) {
+    if (FULL || key0 + sb * 32 < rem) {
       float p[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -127,13 +162,37 @@ __device__ __forceinline__ void fwd_process_tile(const __bf16* kbuf, const __bf1
         const bf16x8 pb = float_to_bf16x8(pf);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          const bf16x8 a = transposed_frag<TS>(vbuf, d * 32 + l32, vcol0 + sb * 32, mf, hh);
+          const bf16x8 a = transposed_frag<TS>(vbuf, d * 32 + l32, vcol + sb * 32, mf, hh);
           acc.o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, acc.o[d], 0, 0, 0);
         }
       }
     }
   }
   acc.l += psum;
+}
+
+// One tile of NSB*32 keys held in LDS (K rows at kbuf, row stride RS; V^T at vbuf, row
+// stride TS, the tile's keys starting at column vcol0), processed in groups of 64 keys with
+// a two-stage software pipeline: the score MFMAs of group g+1 are issued before the softmax
+// VALU work of group g, and that group's P V MFMAs run under the next group's softmax, so
+// the matrix pipe and the vector ALU overlap inside one wave.  rem = valid keys in the tile;
+// FULL = every key valid (no masking code).
+template <int DH, int RS, int TS, int NSB, bool FULL>
+__device__ __forceinline__ void fwd_process_tile(const __bf16* kbuf, const __bf16* vbuf, int vcol0, int rem,
+                                                 const bf16x8 (&qf)[DH / 16], FwdAcc<DH>& acc,
+                                                 float scale_log2, int l32, int hh) {
+  constexpr int GSB = NSB >= 4 ? 2 : 1;     // sub-tiles per softmax group
+  constexpr int NG = NSB / GSB;
+  floatx16 s[2][GSB];
+  fwd_scores<DH, RS, GSB, FULL>(kbuf, 0, rem, qf, s[0], l32, hh);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const int key0 = g * GSB * 32;
+    if (!FULL && key0 >= rem) break;
+    if (g + 1 < NG && (FULL || key0 + GSB * 32 < rem))
+      fwd_scores<DH, RS, GSB, FULL>(kbuf, key0 + GSB * 32, rem, qf, s[(g + 1) & 1], l32, hh);
+    fwd_softmax_pv<DH, TS, GSB, FULL>(s[g & 1], vbuf, vcol0 + key0, key0, rem, acc, scale_log2, l32, hh);
+  }
 }
 
 // Output stage, phase 1: normalise this wave's O^T accumulators and park the 32 x DH bf16
@@ -157,15 +216,27 @@ __device__ __forceinline__ void fwd_park(FwdAcc<DH>& acc, bool q_ok, bool have_k
 }
 
 // Output stage, phase 2 (after a barrier): the wave copies its parked tile to global memory,
-// consecutive lanes writing consecutive 16-byte chunks of a row.  nrows = valid rows (<= 32).
+// consecutive lanes writing consecutive 16-byte chunks of a row.  nrows = valid rows (<= 32);
+// prow0 = packed row of the tile's first row.  out may be null when only y is wanted.
 template <int DH, int RS>
-__device__ __forceinline__ void fwd_flush(const __bf16* tile, __bf16* orow0, long C, int nrows, int lane) {
+__device__ __forceinline__ void fwd_flush(const __bf16* tile, __bf16* out, const Scatter& sc, long prow0, int h,
+                                          long C, int nrows, int lane) {
   constexpr int CPR = DH / 8;
 #pragma unroll
   for (int i = lane; i < 32 * CPR; i += 64) {
     const int r = i / CPR, c = i % CPR;
-    if (r < nrows)
-      *reinterpret_cast<bf16x8*>(orow0 + r * C + c * 8) = *reinterpret_cast<const bf16x8*>(&tile[r * RS + c * 8]);
+    if (r < nrows) {
+      bf16x8 val = *reinterpret_cast<const bf16x8*>(&tile[r * RS + c * 8]);
+      if (out != nullptr) *reinterpret_cast<bf16x8*>(out + (prow0 + r) * C + h * DH + c * 8) = val;
+      if (sc.y != nullptr) {
+        const long off = (long)sc.gather_idx[prow0 + r] * C + h * DH + c * 8;
+        if (sc.base != nullptr) {
+          const floatx8 bv = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(sc.base) + off));
+          val = float_to_bf16x8(bf16x8_to_float(val) + bv);
+        }
+        *reinterpret_cast<bf16x8*>(static_cast<__bf16*>(sc.y) + off) = val;
+      }
+    }
   }
 }
 
@@ -283,7 +354,7 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
                            const __bf16* __restrict__ v, long qs, long ks, long vs,
                            const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
                            int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
-                           long lse_stride) {
+                           long lse_stride, Scatter sc) {
   constexpr int RS = DH + 8, TS = transposed_stride(BN), NSB = BN / 32;
   __shared__ __attribute__((aligned(16))) __bf16 Ks[2][BN * RS];
   __shared__ __attribute__((aligned(16))) __bf16 Vt[2][DH * TS];
@@ -293,13 +364,21 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
 
   const int h = blockIdx.y;
   const Segment seg = lpt_segment<64 * NW>(blockIdx.z, gridDim.z, cu, key_lens, n_pad, s_cu, &s_pick);
+  const long C = (long)H * DH;
+  // this workgroup's share of the image's bypassing tokens: filled right away by a
+  // workgroup that has no queries, after the main loop by one that has
+  const int fill_per = sc.y != nullptr ? (sc.N + gridDim.x - 1) / gridDim.x : 0;
+  const int fill_img = key_lens == nullptr && gridDim.z > 1 && gridDim.z <= kLptMaxB ? s_pick : blockIdx.z;
+  const int fill_t0 = min(sc.N, (int)blockIdx.x * fill_per), fill_t1 = min(sc.N, ((int)blockIdx.x + 1) * fill_per);
   const int q0 = blockIdx.x * (32 * NW);
-  if (q0 >= seg.nq) return;
+  if (q0 >= seg.nq) {
+    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fill_img, fill_t0, fill_t1, h, C, threadIdx.x, 64 * NW);
+    return;
+  }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
   const int qi = q0 + wv * 32 + l32;
   const bool wave_live = q0 + wv * 32 < seg.nq;
   const bool q_ok = qi < seg.nq;
-  const long C = (long)H * DH;
   const __bf16* kh = k + h * DH;
   const __bf16* vh = v + h * DH;
 
@@ -331,7 +410,131 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
                      l32, hh);
   __syncthreads();
   if (wave_live)
-    fwd_flush<DH, RS>(tile, out + (seg.row0 + q0 + wv * 32) * C + h * DH, C, min(32, seg.nq - q0 - wv * 32), lane);
+    fwd_flush<DH, RS>(tile, out, sc, seg.row0 + q0 + wv * 32, h, C, min(32, seg.nq - q0 - wv * 32), lane);
+  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fill_img, fill_t0, fill_t1, h, C, threadIdx.x, 64 * NW);
+}
+
+// Short segments, wave-autonomous.  ONE wave per (image, head, 32-query block), no
+// workgroup barriers, no shared state between waves: the wave streams its segment's K and V
+// rows in steps of 64 keys through a private LDS tile (coalesced 16-byte row loads, the next
+// step's rows already in flight in registers), reads K fragments back as MFMA A operands
+// and V fragments through the transposing LDS read, and keeps the online softmax state in
+// registers.  Work units are small (<= n/32 steps each), so the load spreads over all SIMDs
+// instead of concentrating a heavy (image, head) on one compute unit.
+template <int DH, int STEP>
+__global__ void __launch_bounds__(64)
+attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                          const __bf16* __restrict__ v, long qs, long ks, long vs,
+                          const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
+                          int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
+                          long lse_stride, Scatter sc) {
+  constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, CPR = DH / 8;
+  constexpr int NSB = STEP / 32;                 // 32-key sub-tiles per step (one softmax update)
+  constexpr int LPL = STEP * CPR / 64;           // 16-byte loads per lane per tensor per step
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[STEP * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[STEP * RS];
+
+  const int h = blockIdx.y;
+  const Segment seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
+  const long C = (long)H * DH;
+  // this wave's share of the image's bypassing tokens: at once if it has no queries, else last
+  const int fill_per = sc.y != nullptr ? (sc.N + gridDim.x - 1) / gridDim.x : 0;
+  const int fill_t0 = min(sc.N, (int)blockIdx.x * fill_per), fill_t1 = min(sc.N, ((int)blockIdx.x + 1) * fill_per);
+  const int q0 = blockIdx.x * 32;
+  if (q0 >= seg.nq) {
+    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, blockIdx.z, fill_t0, fill_t1, h, C, threadIdx.x, 64);
+    return;
+  }
+  const int lane = threadIdx.x, l32 = lane & 31, hh = lane >> 5;
+  const int qi = q0 + l32;
+  const bool q_ok = qi < seg.nq;
+  const __bf16* kh = k + h * DH;
+  const __bf16* vh = v + h * DH;
+
+  // lane -> (row, chunk) of the step's tile: 8 (Dh 64) or 4 (Dh 32) lanes cover one row
+  bf16x8 kreg[LPL], vreg[LPL];
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int t = 0; t < LPL; ++t) {
+      const int i = lane + 64 * t, r = i / CPR, c = i % CPR;
+      kreg[t] = zero_bf16x8();
+      vreg[t] = zero_bf16x8();
+      if (kt + r < seg.nk) {
+        kreg[t] = *reinterpret_cast<const bf16x8*>(kh + (seg.row0 + kt + r) * ks + c * 8);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(vh + (seg.row0 + kt + r) * vs + c * 8);
+      }
+    }
+  };
+  auto lstore = [&]() {
+#pragma unroll
+    for (int t = 0; t < LPL; ++t) {
+      const int i = lane + 64 * t, r = i / CPR, c = i % CPR;
+      *reinterpret_cast<bf16x8*>(&Ks[r * RS + c * 8]) = kreg[t];
+      *reinterpret_cast<bf16x8*>(&Vs[r * RS + c * 8]) = vreg[t];
+    }
+  };
+
+  gload(0);
+  bf16x8 qf[KK];
+  load_q_frags<DH>(q + (seg.row0 + qi) * qs + h * DH, q_ok, hh, qf);
+  FwdAcc<DH> acc;
+  acc.init();
+
+  for (int kt = 0; kt < seg.nk; kt += STEP) {
+    lstore();                                     // this step's rows: registers -> LDS
+    if (kt + STEP < seg.nk) gload(kt + STEP);     // next step's rows: in flight during the math
+    const int rem = seg.nk - kt;
+    // scores of the step: S^T = K Q^T, NSB 32-key sub-tiles, one softmax update for all
+    floatx16 s[NSB];
+    fwd_scores<DH, RS, NSB, false>(Ks, 0, rem, qf, s, l32, hh);
+    float mx = s[0][0];
+#pragma unroll
+    for (int sb = 0; sb < NSB; ++sb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float m_new = fmaxf(acc.m, mx * scale_log2);
+    if (__ballot(m_new != acc.m) != 0) {
+      const float alpha = __builtin_amdgcn_exp2f(acc.m - m_new);
+      acc.l *= alpha;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc.o[d][r] *= alpha;
+      acc.m = m_new;
+    }
+    float psum = 0.f;
+#pragma unroll
+    for (int sb = 0; sb < NSB; ++sb) {
+      if (sb * 32 < rem) {
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[r] = __builtin_amdgcn_exp2f(fmaf(s[sb][r], scale_log2, -m_new));
+          psum += p[r];
+        }
+#pragma unroll
+        for (int mf = 0; mf < 2; ++mf) {
+          floatx8 pf;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) pf[j] = p[8 * mf + j];
+          const bf16x8 pb = float_to_bf16x8(pf);
+#pragma unroll
+          for (int d = 0; d < DB; ++d) {
+            const bf16x8 a = transposed_frag_rowmajor<RS>(Vs, d, sb * 32, mf, lane);
+            acc.o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, acc.o[d], 0, 0, 0);
+          }
+        }
+      }
+    }
+    acc.l += psum;
+  }
+
+  // output: park the 32 x DH tile in the (now free) K tile, then write whole rows
+  fwd_park<DH, RS>(acc, q_ok, seg.nk > 0, Ks, lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr, l32,
+                   hh);
+  fwd_flush<DH, RS>(Ks, out, sc, seg.row0 + q0, h, C, min(32, seg.nq - q0), lane);
+  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, blockIdx.z, fill_t0, fill_t1, h, C, threadIdx.x, 64);
 }
 
 // Short segments (every segment <= NKMAX keys).  ONE workgroup per (image, head): all K / V
@@ -344,7 +547,7 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
                            const __bf16* __restrict__ v, long qs, long ks, long vs,
                            const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
                            int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
-                           long lse_stride) {
+                           long lse_stride, Scatter sc) {
   constexpr int THREADS = 2 * NKMAX;                       // one wave per 32 queries
   constexpr int RS = DH + 8, TS = transposed_stride(NKMAX);
   constexpr int TILE = NKMAX < 128 ? NKMAX : 128;           // keys per softmax update
@@ -356,12 +559,15 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   Segment seg = segment_of(blockIdx.y, cu, key_lens, n_pad);
   seg.nq = min(seg.nq, NKMAX);   // never index past the LDS tile, whatever cu_seqlens holds
   seg.nk = min(seg.nk, NKMAX);
-  if (seg.nq <= 0) return;
+  const long C = (long)H * DH;
+  if (seg.nq <= 0) {
+    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, blockIdx.y, 0, sc.N, h, C, threadIdx.x, THREADS);
+    return;
+  }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
   const int qi = wv * 32 + l32;
   const bool wave_live = wv * 32 < seg.nq;
   const bool q_ok = qi < seg.nq;
-  const long C = (long)H * DH;
 
   KvStage<DH, THREADS, (NKMAX / 2) * (DH / 8)> stage;
   stage.load(k + h * DH, v + h * DH, seg.row0, seg.nk, ks, vs);
@@ -371,6 +577,11 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   acc.init();
   stage.template store<RS, TS>(Ks, Vt, 0);
   __syncthreads();
+  // the rows that bypass attention are filled by the waves that own no queries while the
+  // others compute; if every wave has queries (few rows bypass then) all do it at the end
+  const int live_threads = ((seg.nq + 31) / 32) * 64;
+  if (!wave_live && sc.y != nullptr)
+    scatter_fill<__bf16, DH>(sc, blockIdx.y, 0, sc.N, h, C, threadIdx.x - live_threads, THREADS - live_threads);
   if (wave_live) {
     for (int kt = 0; kt < seg.nk; kt += TILE) {
       const int rem = seg.nk - kt;
@@ -384,8 +595,9 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
     fwd_park<DH, RS>(acc, q_ok, seg.nk > 0, tile, lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr,
                      l32, hh);
   __syncthreads();
-  if (wave_live)
-    fwd_flush<DH, RS>(tile, out + (seg.row0 + wv * 32) * C + h * DH, C, min(32, seg.nq - wv * 32), lane);
+  if (wave_live) fwd_flush<DH, RS>(tile, out, sc, seg.row0 + wv * 32, h, C, min(32, seg.nq - wv * 32), lane);
+  if (sc.y != nullptr && live_threads >= THREADS)
+    scatter_fill<__bf16, DH>(sc, blockIdx.y, 0, sc.N, h, C, threadIdx.x, THREADS);
 }
 
 // ------------------------------------------------------------------------------- fp32
@@ -394,19 +606,24 @@ __global__ void __launch_bounds__(128)
 attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
                     const float* __restrict__ v, long qs, long ks, long vs, const int32_t* __restrict__ cu,
                     const int32_t* __restrict__ key_lens, int n_pad, int H, float scale,
-                    float* __restrict__ out, float* __restrict__ lse, long lse_stride) {
+                    float* __restrict__ out, float* __restrict__ lse, long lse_stride, Scatter sc) {
   constexpr int BM = 128, BN = 32;
   __shared__ __attribute__((aligned(16))) float Ks[BN * DH];
   __shared__ __attribute__((aligned(16))) float Vs[BN * DH];
 
   const int h = blockIdx.y;
   const Segment seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
+  const long C = (long)H * DH;
+  if (sc.y != nullptr) {
+    const int per = (sc.N + gridDim.x - 1) / gridDim.x;
+    scatter_fill<float, DH>(sc, blockIdx.z, min(sc.N, (int)blockIdx.x * per), min(sc.N, ((int)blockIdx.x + 1) * per), h, C,
+                            threadIdx.x, BM);
+  }
   const int q0 = blockIdx.x * BM;
   if (q0 >= seg.nq) return;
   const int tid = threadIdx.x;
   const int qi = q0 + tid;
   const bool q_ok = qi < seg.nq;
-  const long C = (long)H * DH;
 
   float qr[DH], o[DH];
 #pragma unroll
@@ -461,11 +678,16 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
   }
   if (!q_ok) return;
   const float inv = seg.nk > 0 ? 1.0f / l : 0.f;
-  float* op = out + (seg.row0 + qi) * C + h * DH;
+  float* op = out != nullptr ? out + (seg.row0 + qi) * C + h * DH : nullptr;
+  const long yoff = sc.y != nullptr ? (long)sc.gather_idx[seg.row0 + qi] * C + h * DH : 0;
 #pragma unroll
   for (int d = 0; d < DH; d += 4) {
     floatx4 t = {o[d] * inv, o[d + 1] * inv, o[d + 2] * inv, o[d + 3] * inv};
-    *reinterpret_cast<floatx4*>(op + d) = t;
+    if (op != nullptr) *reinterpret_cast<floatx4*>(op + d) = t;
+    if (sc.y != nullptr) {
+      if (sc.base != nullptr) t += *reinterpret_cast<const floatx4*>(static_cast<const float*>(sc.base) + yoff + d);
+      *reinterpret_cast<floatx4*>(static_cast<float*>(sc.y) + yoff + d) = t;
+    }
   }
   if (lse != nullptr) lse[h * lse_stride + seg.row0 + qi] = seg.nk > 0 ? m + logf(l) : -INFINITY;
 }
@@ -474,8 +696,8 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
 static int attention_common(const char* fn, const void* q, const void* k, const void* v,
                             int64_t q_stride, int64_t k_stride, int64_t v_stride, const int32_t* cu, const int32_t* key_lens, int B,
                             int n_max, int H, int Dh, int dtype, float softmax_scale, void* out,
-                            float* lse, void* stream) {
-  SPA_REQUIRE(q && k && v && out && (cu || key_lens), SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+                            float* lse, const Scatter& sc, void* stream) {
+  SPA_REQUIRE(q && k && v && (out || sc.y) && (cu || key_lens), SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(B >= 1 && n_max >= 1 && H >= 1, SPA_ERR_INVALID_ARG, "%s: B, max_seqlen, H must be >= 1", fn);
   SPA_REQUIRE((long)B * n_max < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*max_seqlen must be < 2^31", fn);
   SPA_REQUIRE(B <= 65535 && H <= 65535, SPA_ERR_INVALID_ARG, "%s: B and H must be <= 65535", fn);
@@ -498,21 +720,34 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
 #define SPA_F32_LAUNCH(D)                                                                                \
   hipLaunchKernelGGL((attn_fwd_f32_kernel<D>), grid, block, 0, st, (const float*)q, (const float*)k,    \
                      (const float*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu, key_lens, n_max, H, scale, (float*)out, lse, \
-                     lse_stride)
+                     lse_stride, sc)
     if (Dh == 32) SPA_F32_LAUNCH(32); else SPA_F32_LAUNCH(64);
 #undef SPA_F32_LAUNCH
   } else {
     const float scale_log2 = scale * 1.4426950408889634f;
 #define SPA_ARGS                                                                                              \
   (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu,   \
-      key_lens, n_max, H, scale_log2, (__bf16*)out, lse, lse_stride
+      key_lens, n_max, H, scale_log2, (__bf16*)out, lse, lse_stride, sc
     // SPA_ATTN_FWD_CFG="NW,BN" forces the tiled kernel with that launch shape (tuning aid).
     int NW = 0, BN = 0;
     if (const char* env = std::getenv("SPA_ATTN_FWD_CFG")) {
       int a = 0, b = 0;
       if (std::sscanf(env, "%d,%d", &a, &b) == 2 && (a == 2 || a == 4) && (b == 64 || b == 128)) { NW = a; BN = b; }
     }
-    if (NW == 0 && n_max <= 256) {
+    const char* short_env = std::getenv("SPA_ATTN_FWD_SHORT");      // "whole" | "wave" (tuning aid)
+    const bool use_whole = short_env != nullptr && short_env[0] == 'w' && short_env[1] == 'h';
+    if (NW == 0 && n_max <= 256 && !use_whole) {
+      // short segments: one wave per (image, head, 32 queries)
+      const dim3 grid((n_max + 31) / 32, H, B);
+      const bool step64 = short_env != nullptr && std::strstr(short_env, "64") != nullptr;
+      if (Dh == 32) {
+        if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 64>), grid, dim3(64), 0, st, SPA_ARGS);
+        else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 32>), grid, dim3(64), 0, st, SPA_ARGS);
+      } else {
+        if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<64, 64>), grid, dim3(64), 0, st, SPA_ARGS);
+        else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<64, 32>), grid, dim3(64), 0, st, SPA_ARGS);
+      }
+    } else if (NW == 0 && n_max <= 256) {
       // short segments: one workgroup per (image, head), whole segment in LDS
       const dim3 grid(H, B);
 #define SPA_WHOLE(D)                                                                                          \
@@ -549,14 +784,33 @@ extern "C" int spa_packed_attention(const void* q, const void* k, const void* v,
                                     int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
                                     int dtype, float softmax_scale, void* out, float* lse, void* stream) {
   SPA_REQUIRE(cu_seqlens, SPA_ERR_INVALID_ARG, "spa_packed_attention: cu_seqlens is null");
+  SPA_REQUIRE(out, SPA_ERR_INVALID_ARG, "spa_packed_attention: out is null");
+  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0};
   return attention_common("spa_packed_attention", q, k, v, q_row_stride, k_row_stride, v_row_stride, cu_seqlens, nullptr, B, max_seqlen,
-                          H, Dh, dtype, softmax_scale, out, lse, stream);
+                          H, Dh, dtype, softmax_scale, out, lse, none, stream);
 }
 
 extern "C" int spa_padded_attention(const void* q, const void* k, const void* v, int64_t row_stride,
                                     const int32_t* seqlens, int B, int n_pad, int H, int Dh, int dtype,
                                     float softmax_scale, void* out, void* stream) {
   SPA_REQUIRE(seqlens, SPA_ERR_INVALID_ARG, "spa_padded_attention: seqlens is null");
+  SPA_REQUIRE(out, SPA_ERR_INVALID_ARG, "spa_padded_attention: out is null");
+  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0};
   return attention_common("spa_padded_attention", q, k, v, row_stride, row_stride, row_stride, nullptr, seqlens, B, n_pad, H, Dh,
-                          dtype, softmax_scale, out, nullptr, stream);
+                          dtype, softmax_scale, out, nullptr, none, stream);
+}
+
+extern "C" int spa_packed_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                           int64_t k_row_stride, int64_t v_row_stride,
+                                           const int32_t* cu_seqlens, const int32_t* gather_idx,
+                                           const int32_t* inv_pos, const void* base, int B, int N, int H, int Dh,
+                                           int dtype, float softmax_scale, void* out, float* lse, void* y,
+                                           void* stream) {
+  SPA_REQUIRE(cu_seqlens && gather_idx && inv_pos && y, SPA_ERR_INVALID_ARG,
+              "spa_packed_attention_unpack: null pointer");
+  SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG,
+              "spa_packed_attention_unpack: y / base not 16-byte aligned");
+  const Scatter sc = {gather_idx, inv_pos, base, y, N};
+  return attention_common("spa_packed_attention_unpack", q, k, v, q_row_stride, k_row_stride, v_row_stride,
+                          cu_seqlens, nullptr, B, N, H, Dh, dtype, softmax_scale, out, lse, sc, stream);
 }

@@ -65,6 +65,27 @@ __device__ __forceinline__ bf16x8 transposed_frag(const __bf16* tr, int d, int t
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// The same A-operand fragment taken from a ROW-MAJOR tile (rows = tokens, row stride RS
+// elements) with the transposing LDS read ds_read_b64_tr_b16.  Within each block of 16 lanes
+// that instruction hands lane i, element e, the value that lane (4e + i/4) of the block
+// addressed at its own element i%4.  So lane s of a block points at token row k0 + s/4,
+// head-dim columns d0 + 4*(s%4) .. +3, and lane i receives tokens k0..k0+3 at column d0+i.
+// The four 16-lane blocks of the wave cover (d0 = 0 | 16 of the 32-row block) x (hh = 0 | 1).
+typedef short shortx4_lds __attribute__((ext_vector_type(4)));
+template <int RS>
+__device__ __forceinline__ bf16x8 transposed_frag_rowmajor(const __bf16* rows, int dblock, int tok0, int mf,
+                                                           int lane) {
+  const int blk = lane >> 4, s = lane & 15;
+  const int hh = blk >> 1;
+  const int d = dblock * 32 + 16 * (blk & 1) + 4 * (s & 3);
+  const __bf16* p = rows + (tok0 + 16 * mf + 4 * hh + (s >> 2)) * RS + d;
+  typedef shortx4_lds __attribute__((address_space(3))) * lds_ptr;
+  const shortx4_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const shortx4_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * RS));
+  const bf16x4 l4 = __builtin_bit_cast(bf16x4, lo), h4 = __builtin_bit_cast(bf16x4, hi);
+  return __builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 // Row of a 32x32 fp32 accumulator tile held in register r of a lane in half hh.
 __device__ __forceinline__ constexpr int acc_row(int r, int hh) { return 8 * (r / 4) + 4 * hh + (r % 4); }
 

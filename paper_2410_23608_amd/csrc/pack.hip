@@ -6,6 +6,8 @@
 // tokens that precede its tile (from the per-image counts when the caller has them, else
 // from the mask bytes themselves — B*N bytes that sit in L2), ranks its own tokens with
 // wave ballots, and copies its survivors' rows to their final place.
+#include <cstdlib>
+
 #include "spa_common.h"
 
 namespace spa {
@@ -123,7 +125,7 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
 
   // 4. copy the survivors' rows: consecutive threads take consecutive 16-byte chunks, four
   //    independent loads in flight per thread before the first store
-  constexpr int U = 4;
+  constexpr int U = 8;
   const unsigned work = (unsigned)nsel * (unsigned)chunks;
   const T* xt = x + flat0 * (long)C;
   T* pt = packed + (long)base * C;
@@ -261,7 +263,11 @@ static int pick_tile(int B, int N, bool have_counts) {
   // workgroup re-reads the mask prefix, so keep tiles larger when B*N is large.
   const long want = (!have_counts && (long)B * N > 16384) ? 512 : 1024;
   int tile = 256;
-  while (tile > 32 && (long)B * ((N + tile - 1) / tile) < want) tile >>= 1;
+  while (tile > 16 && (long)B * ((N + tile - 1) / tile) < want) tile >>= 1;
+  if (const char* env = std::getenv("SPA_PACK_TILE")) {       // tuning aid
+    const int t = std::atoi(env);
+    if (t == 16 || t == 32 || t == 64 || t == 128 || t == 256) tile = t;
+  }
   return tile;
 }
 

@@ -21,12 +21,17 @@ def _td(dtype: str):
 
 
 class ForwardPass:
-    """gate_select(x) -> pack(qkv) -> packed_attention -> unpack."""
+    """gate_select(x) -> pack(qkv) -> packed_attention -> unpack.
+
+    fused_unpack=True (default) issues the last two steps as ONE launch
+    (spa_packed_attention_unpack: the attention kernel scatters its rows back itself and
+    fills the bypassing rows); the results are bit-identical to the two separate calls."""
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
-                 container_len: int = 0):
+                 container_len: int = 0, fused_unpack: bool = True):
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
         self.tau, self.bias, self.container_len = tau, bias, container_len
+        self.fused_unpack = fused_unpack
         td, cap = _td(dtype), B * N
         dv = dict(device="cuda")
         self.scores = torch.empty(B, N, dtype=torch.float32, **dv)
@@ -45,12 +50,21 @@ class ForwardPass:
         caller can time each of them or replay them with no marshalling cost."""
         C, p = self.C, self.packed_qkv
         q, k, v = p[:, :C], p[:, C:2 * C], p[:, 2 * C:]
-        return [
-            ("gate_select", spa.spa_gate_select(x, w, self.bias, s_up, self.tau, self.scores, self.mask, None, prepare=True)),
+        head = [
+            ("gate_select", spa.spa_gate_select(x, w, self.bias, s_up, self.tau, self.scores, self.mask, None,
+                                                prepare=True)),
             ("pack", spa.spa_pack(qkv, self.mask, None, None, self.container_len, p, self.cu_seqlens,
-                                          self.gather_idx, self.inv_pos, self.total, prepare=True)),
+                                  self.gather_idx, self.inv_pos, self.total, prepare=True)),
+        ]
+        if self.fused_unpack:
+            return head + [
+                ("packed_attention_unpack", spa.spa_packed_attention_unpack(
+                    q, k, v, self.cu_seqlens, self.gather_idx, self.inv_pos, base, self.H, self.Dh, self.y,
+                    self.out, self.lse, prepare=True)),
+            ]
+        return head + [
             ("packed_attention", spa.spa_packed_attention(q, k, v, self.cu_seqlens, self.B, self.N, self.H,
-                                                                  self.Dh, self.out, self.lse, prepare=True)),
+                                                          self.Dh, self.out, self.lse, prepare=True)),
             ("unpack", spa.spa_unpack(self.out, self.inv_pos, base, self.y, prepare=True)),
         ]
 
@@ -65,7 +79,7 @@ class TrainPass:
 
     q | k are supplied ([B, N, 2C], stand-ins for projected tokens); v is the packed gated
     representation r_g = Sigmoid(s) . r, so the gate receives the attention's gradient:
-      fwd: gate_select(x) -> pack(qk) -> pack(x, scaled by sigmoid(s)) -> attention -> unpack
+      fwd: gate_select(x) -> pack(qk) -> pack(x, scaled by sigmoid(s)) -> attention + unpack (one launch)
       bwd: unpack_bwd(dy) -> attention_bwd -> pack_bwd(dv) [-> pack_bwd(dq|dk)] -> gate_bwd
     """
 
@@ -112,9 +126,9 @@ class TrainPass:
                                              self.gather_idx, self.inv_pos, self.total, prepare=True)),
             ("pack_rg", spa.spa_pack(x, self.mask, None, self.scores, 0, self.packed_v, None, None, None, None,
                                           prepare=True)),
-            ("packed_attention", spa.spa_packed_attention(pq, pk, pv, self.cu_seqlens, B, N, H, Dh, self.out,
-                                                          self.lse, prepare=True)),
-            ("unpack", spa.spa_unpack(self.out, self.inv_pos, None, self.y, prepare=True)),
+            ("packed_attention_unpack", spa.spa_packed_attention_unpack(
+                pq, pk, pv, self.cu_seqlens, self.gather_idx, self.inv_pos, None, H, Dh, self.y, self.out, self.lse,
+                prepare=True)),
             ("unpack_bwd", spa.spa_unpack_bwd(dy, self.gather_idx, self.total, self.dout, prepare=True)),
             ("packed_attention_bwd", spa.spa_packed_attention_bwd(
                 pq, pk, pv, self.out, self.dout, self.lse, self.cu_seqlens, B, N, H, Dh, dq, dk, self.dv_packed,

@@ -33,6 +33,8 @@ _SIGNATURES = {
     "spa_maxpool2x2": (c_int, [_P, c_int, c_int, c_int, _P, _P]),
     "spa_pack": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, _P, _P, _P, _P, _P, _P]),
     "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
+    "spa_packed_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
+                                            c_int, c_int, c_float, _P, _P, _P, _P]),
     "spa_unpack": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_unpack_bwd": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_pack_bwd": (c_int, [_P, _P, c_int, c_int, c_int, c_int, _P, _P]),
@@ -161,6 +163,18 @@ def spa_packed_attention(q, k, v, cu_seqlens, B, max_seqlen, H, Dh, out, lse=Non
     return _dispatch(lib.spa_packed_attention, (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
                                     _ptr(cu_seqlens), B, max_seqlen,
                                     H, Dh, dtype_code(out), float(softmax_scale), _ptr(out), _ptr(lse), _stream(),), _keep, prepare)
+
+
+def spa_packed_attention_unpack(q, k, v, cu_seqlens, gather_idx, inv_pos, base, H, Dh, y, out=None, lse=None,
+                                softmax_scale=0.0, prepare=False):
+    """Attention on the packed rows + scatter back to y [B,N,C] in one launch."""
+    B, N, C = y.shape
+    _keep = (cu_seqlens, gather_idx, inv_pos, base, y, out, lse,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_packed_attention_unpack,
+                     (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(cu_seqlens),
+                      _ptr(gather_idx), _ptr(inv_pos), _ptr(base), B, N, H, Dh, dtype_code(y), float(softmax_scale),
+                      _ptr(out), _ptr(lse), _ptr(y), _stream(),), _keep, prepare)
 
 
 def spa_unpack(packed_out, inv_pos, base, y, prepare=False):

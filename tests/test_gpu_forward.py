@@ -264,3 +264,51 @@ def test_argument_validation_returns_errors_before_launch(spa):
         spa.spa_packed_attention(out, out, out, cu, 2, 8, 2, 24, out)
     assert e.value.code == -2
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype,Dh,N,short", [("f32", 32, 150, ""), ("bf16", 64, 196, ""), ("bf16", 64, 196, "wave"),
+                                              ("bf16", 32, 49, ""), ("bf16", 32, 700, ""), ("bf16", 64, 300, "")])
+@pytest.mark.parametrize("with_base,keep_out", [(False, True), (True, False)])
+def test_fused_attention_unpack_equals_separate_calls(spa, monkeypatch, dtype, Dh, N, short, with_base, keep_out):
+    """spa_packed_attention_unpack == spa_packed_attention followed by spa_unpack, bit for bit,
+    for the short-segment kernels (whole / wave), the tiled kernel and the fp32 kernel; and
+    both equal the oracle within tolerance."""
+    if short:
+        monkeypatch.setenv("SPA_ATTN_FWD_SHORT", short)
+    else:
+        monkeypatch.setenv("SPA_ATTN_FWD_SHORT", "whole")
+    B, H = 5, 2
+    C = H * Dh
+    rng = np.random.default_rng(31)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    qkv = mk(rng.standard_normal((B, N, 3 * C)).astype(np.float32))
+    base = mk(rng.standard_normal((B, N, C)).astype(np.float32)) if with_base else None
+    mask = (rng.uniform(size=(B, N)) < rng.uniform(0.1, 0.9, size=(B, 1))).astype(np.uint8)
+    mask[1] = 0                                   # an image with nothing selected
+    mask[2] = 1                                   # an image with everything selected
+    td, cap = tdtype(dtype), B * N
+    packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    gidx = torch.zeros(cap, dtype=torch.int32, device="cuda")
+    inv = torch.empty(cap, dtype=torch.int32, device="cuda")
+    spa.spa_pack(dev(qkv, dtype), dev(mask), None, None, 0, packed, cu, gidx, inv, None)
+    pq, pk, pv = packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:]
+    base_d = None if base is None else dev(base, dtype)
+    out1 = torch.zeros(cap, C, dtype=td, device="cuda")
+    lse1 = torch.zeros(H, cap, dtype=torch.float32, device="cuda")
+    y1 = torch.full((B, N, C), float("nan"), dtype=td, device="cuda")
+    spa.spa_packed_attention(pq, pk, pv, cu, B, N, H, Dh, out1, lse1)
+    spa.spa_unpack(out1, inv, base_d, y1)
+    out2 = torch.zeros(cap, C, dtype=td, device="cuda") if keep_out else None
+    lse2 = torch.zeros(H, cap, dtype=torch.float32, device="cuda")
+    y2 = torch.full((B, N, C), float("nan"), dtype=td, device="cuda")
+    spa.spa_packed_attention_unpack(pq, pk, pv, cu, gidx, inv, base_d, H, Dh, y2, out2, lse2)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(y1), host(y2))
+    assert np.array_equal(host(lse1), host(lse2))
+    if keep_out:
+        assert np.array_equal(host(out1), host(out2))
+    ref_out, _ = orc.attention_per_image(qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], mask, H)
+    ref_y = orc.unpack(ref_out, orc.pack_indices(mask)[2], B, N, base)
+    tol = TOL[dtype] * (2 if with_base and dtype == "bf16" else 1)
+    assert np.max(np.abs(host(y2) - ref_y)) <= tol
