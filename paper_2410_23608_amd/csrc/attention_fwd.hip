@@ -240,6 +240,33 @@ __device__ __forceinline__ void fwd_flush(const __bf16* tile, __bf16* out, const
   }
 }
 
+// XCD-aware launch order.  Workgroups are handed to the 8 XCDs round-robin by linear id and
+// each XCD has its own L2, so the query blocks that share one (image, head)'s K and V must
+// sit on the same XCD or every XCD fetches those rows from memory again.  The grid is 1-D:
+// id -> (xcd = id % 8, j = id / 8); inside an XCD j walks (pair, query block) with the query
+// block fastest, and pair = 8 * (j / nqb) + xcd spreads consecutive pairs over the XCDs.
+// pair -> (launch rank of the image = pair / H, head = pair % H).  Ids past the last pair
+// (the grid is padded to a multiple of 8 pairs) are invalid.
+struct TileId {
+  int qb, h, rank;
+  bool valid;
+};
+__device__ __forceinline__ TileId xcd_tile(int nqb, int H, int B) {
+  const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
+  const int pl = j / nqb;
+  TileId t;
+  t.qb = j - pl * nqb;
+  const int pair = pl * 8 + xcd;
+  t.valid = pair < H * B;
+  t.h = pair % H;
+  t.rank = pair / H;
+  return t;
+}
+static unsigned xcd_grid(int nqb, int H, int B) {
+  const long pairs8 = ((long)H * B + 7) / 8;
+  return (unsigned)(pairs8 * 8 * nqb);
+}
+
 // Longest-segment-first launch order.  Work per segment grows like n^2 and workgroups are
 // handed to compute units in launch order, so the heaviest images should start first.  Maps
 // launch rank -> image by ranking the segment lengths (ties by index) and returns that
@@ -354,7 +381,7 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
                            const __bf16* __restrict__ v, long qs, long ks, long vs,
                            const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
                            int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
-                           long lse_stride, Scatter sc) {
+                           long lse_stride, Scatter sc, int B, int nqb) {
   constexpr int RS = DH + 8, TS = transposed_stride(BN), NSB = BN / 32;
   __shared__ __attribute__((aligned(16))) __bf16 Ks[2][BN * RS];
   __shared__ __attribute__((aligned(16))) __bf16 Vt[2][DH * TS];
@@ -362,15 +389,17 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   __shared__ int s_pick;
   static_assert(2 * BN >= 32 * NW, "the K buffers double as the output staging tile");
 
-  const int h = blockIdx.y;
-  const Segment seg = lpt_segment<64 * NW>(blockIdx.z, gridDim.z, cu, key_lens, n_pad, s_cu, &s_pick);
+  const TileId tile_id = xcd_tile(nqb, H, B);
+  if (!tile_id.valid) return;
+  const int h = tile_id.h;
+  const Segment seg = lpt_segment<64 * NW>(tile_id.rank, B, cu, key_lens, n_pad, s_cu, &s_pick);
   const long C = (long)H * DH;
   // this workgroup's share of the image's bypassing tokens: filled right away by a
   // workgroup that has no queries, after the main loop by one that has
-  const int fill_per = sc.y != nullptr ? (sc.N + gridDim.x - 1) / gridDim.x : 0;
-  const int fill_img = key_lens == nullptr && gridDim.z > 1 && gridDim.z <= kLptMaxB ? s_pick : blockIdx.z;
-  const int fill_t0 = min(sc.N, (int)blockIdx.x * fill_per), fill_t1 = min(sc.N, ((int)blockIdx.x + 1) * fill_per);
-  const int q0 = blockIdx.x * (32 * NW);
+  const int fill_per = sc.y != nullptr ? (sc.N + nqb - 1) / nqb : 0;
+  const int fill_img = key_lens == nullptr && B > 1 && B <= kLptMaxB ? s_pick : tile_id.rank;
+  const int fill_t0 = min(sc.N, tile_id.qb * fill_per), fill_t1 = min(sc.N, (tile_id.qb + 1) * fill_per);
+  const int q0 = tile_id.qb * (32 * NW);
   if (q0 >= seg.nq) {
     if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fill_img, fill_t0, fill_t1, h, C, threadIdx.x, 64 * NW);
     return;
@@ -427,22 +456,24 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           const __bf16* __restrict__ v, long qs, long ks, long vs,
                           const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
                           int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
-                          long lse_stride, Scatter sc) {
+                          long lse_stride, Scatter sc, int B, int nqb) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, CPR = DH / 8;
   constexpr int NSB = STEP / 32;                 // 32-key sub-tiles per step (one softmax update)
   constexpr int LPL = STEP * CPR / 64;           // 16-byte loads per lane per tensor per step
   __shared__ __attribute__((aligned(16))) __bf16 Ks[STEP * RS];
   __shared__ __attribute__((aligned(16))) __bf16 Vs[STEP * RS];
 
-  const int h = blockIdx.y;
-  const Segment seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
+  const TileId tile_id = xcd_tile(nqb, H, B);
+  if (!tile_id.valid) return;
+  const int h = tile_id.h, img = tile_id.rank;
+  const Segment seg = segment_of(img, cu, key_lens, n_pad);
   const long C = (long)H * DH;
   // this wave's share of the image's bypassing tokens: at once if it has no queries, else last
-  const int fill_per = sc.y != nullptr ? (sc.N + gridDim.x - 1) / gridDim.x : 0;
-  const int fill_t0 = min(sc.N, (int)blockIdx.x * fill_per), fill_t1 = min(sc.N, ((int)blockIdx.x + 1) * fill_per);
-  const int q0 = blockIdx.x * 32;
+  const int fill_per = sc.y != nullptr ? (sc.N + nqb - 1) / nqb : 0;
+  const int fill_t0 = min(sc.N, tile_id.qb * fill_per), fill_t1 = min(sc.N, (tile_id.qb + 1) * fill_per);
+  const int q0 = tile_id.qb * 32;
   if (q0 >= seg.nq) {
-    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, blockIdx.z, fill_t0, fill_t1, h, C, threadIdx.x, 64);
+    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, img, fill_t0, fill_t1, h, C, threadIdx.x, 64);
     return;
   }
   const int lane = threadIdx.x, l32 = lane & 31, hh = lane >> 5;
@@ -534,7 +565,7 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   fwd_park<DH, RS>(acc, q_ok, seg.nk > 0, Ks, lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr, l32,
                    hh);
   fwd_flush<DH, RS>(Ks, out, sc, seg.row0 + q0, h, C, min(32, seg.nq - q0), lane);
-  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, blockIdx.z, fill_t0, fill_t1, h, C, threadIdx.x, 64);
+  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, img, fill_t0, fill_t1, h, C, threadIdx.x, 64);
 }
 
 // Short segments (every segment <= NKMAX keys).  ONE workgroup per (image, head): all K / V
@@ -701,6 +732,8 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
   SPA_REQUIRE(B >= 1 && n_max >= 1 && H >= 1, SPA_ERR_INVALID_ARG, "%s: B, max_seqlen, H must be >= 1", fn);
   SPA_REQUIRE((long)B * n_max < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*max_seqlen must be < 2^31", fn);
   SPA_REQUIRE(B <= 65535 && H <= 65535, SPA_ERR_INVALID_ARG, "%s: B and H must be <= 65535", fn);
+  SPA_REQUIRE(((long)H * B + 8) * ((n_max + 31) / 32) < 2147483647L, SPA_ERR_INVALID_ARG,
+              "%s: B*H*ceil(max_seqlen/32) must be < 2^31", fn);
   SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
   SPA_REQUIRE(Dh == 32 || Dh == 64, SPA_ERR_UNSUPPORTED, "%s: head dim %d not supported (32 or 64)", fn, Dh);
   const int64_t strides[3] = {q_stride, k_stride, v_stride};
@@ -738,14 +771,15 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
     const bool use_whole = short_env != nullptr && short_env[0] == 'w' && short_env[1] == 'h';
     if (NW == 0 && n_max <= 256 && !use_whole) {
       // short segments: one wave per (image, head, 32 queries)
-      const dim3 grid((n_max + 31) / 32, H, B);
+      const int nqb = (n_max + 31) / 32;
+      const dim3 grid(xcd_grid(nqb, H, B));
       const bool step64 = short_env != nullptr && std::strstr(short_env, "64") != nullptr;
       if (Dh == 32) {
-        if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 64>), grid, dim3(64), 0, st, SPA_ARGS);
-        else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 32>), grid, dim3(64), 0, st, SPA_ARGS);
+        if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 64>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
+        else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 32>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
       } else {
-        if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<64, 64>), grid, dim3(64), 0, st, SPA_ARGS);
-        else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<64, 32>), grid, dim3(64), 0, st, SPA_ARGS);
+        if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<64, 64>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
+        else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<64, 32>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
       }
     } else if (NW == 0 && n_max <= 256) {
       // short segments: one workgroup per (image, head), whole segment in LDS
@@ -760,13 +794,14 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
 #undef SPA_WHOLE
     } else {
       if (NW == 0) { NW = 4; BN = 128; }
-      const dim3 grid((n_max + 32 * NW - 1) / (32 * NW), H, B), block(64 * NW);
+      const int nqb = (n_max + 32 * NW - 1) / (32 * NW);
+      const dim3 grid(xcd_grid(nqb, H, B)), block(64 * NW);
 #define SPA_TILED(D)                                                                                          \
   do {                                                                                                        \
-    if (NW == 2 && BN == 64) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 2, 64>), grid, block, 0, st, SPA_ARGS);        \
-    else if (NW == 2) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 2, 128>), grid, block, 0, st, SPA_ARGS);              \
-    else if (BN == 64) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 4, 64>), grid, block, 0, st, SPA_ARGS);              \
-    else hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 4, 128>), grid, block, 0, st, SPA_ARGS);           \
+    if (NW == 2 && BN == 64) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 2, 64>), grid, block, 0, st, SPA_ARGS, B, nqb);        \
+    else if (NW == 2) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 2, 128>), grid, block, 0, st, SPA_ARGS, B, nqb);              \
+    else if (BN == 64) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 4, 64>), grid, block, 0, st, SPA_ARGS, B, nqb);              \
+    else hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 4, 128>), grid, block, 0, st, SPA_ARGS, B, nqb);           \
   } while (0)
       if (Dh == 32) SPA_TILED(32); else SPA_TILED(64);
 #undef SPA_TILED
