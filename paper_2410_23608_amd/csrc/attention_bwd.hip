@@ -33,6 +33,13 @@ __device__ __forceinline__ Seg seg_of(int b, const int32_t* cu) {
 
 constexpr int kBwdTile = 64;   // tokens staged per LDS tile
 
+// Both bf16 kernels use the forward's launch scheme: 1-D XCD-aware grid (the blocks that
+// share one (image, head)'s rows sit on one L2), longest image first, 4 waves x 32 rows per
+// workgroup, the other side of the product streaming through double-buffered row-major LDS
+// tiles of 64 tokens with the next tile's rows in flight in registers.  Operands whose
+// k-dimension is the token index are read with the transposing LDS read from the same
+// row-major tiles, so nothing is staged twice.
+
 // --------------------------------------------------------------------------- dQ (bf16)
 template <int DH, int NW>
 __global__ void __launch_bounds__(64 * NW)
@@ -40,22 +47,33 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
                         const __bf16* __restrict__ v, long qs, long ks, long vs,
                         const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                         const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
-                        float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec) {
-  constexpr int RS = DH + 8, TS = transposed_stride(kBwdTile), KK = DH / 16, DB = DH / 32;
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[kBwdTile * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[kBwdTile * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Kt[DH * TS];
+                        float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B,
+                        int nqb) {
+  constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kBwdTile * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[2][kBwdTile * RS];
+  __shared__ int s_cu[2 * kLptMaxB + 1];
+  __shared__ int s_pick;
+  static_assert(2 * kBwdTile >= 32 * NW, "the K buffers double as the output staging tile");
 
-  const int h = blockIdx.y;
-  const Seg seg = seg_of(blockIdx.z, cu);
-  const int q0 = blockIdx.x * (32 * NW);
-  if (q0 >= seg.n) return;
+  const TileId tile_id = xcd_tile(nqb, H, B);
+  if (!tile_id.valid) return;
+  const int h = tile_id.h;
+  const Segment seg = lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick);
+  const int q0 = tile_id.qb * (32 * NW);
+  if (q0 >= seg.nq) return;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
   const int qi = q0 + wv * 32 + l32;
-  const bool wave_live = q0 + wv * 32 < seg.n;
-  const bool q_ok = qi < seg.n;
+  const bool wave_live = q0 + wv * 32 < seg.nq;
+  const bool q_ok = qi < seg.nq;
   const long C = (long)H * DH;
   const float scale_log2 = scale * kLog2e;
+  const __bf16* kh = k + h * DH;
+  const __bf16* vh = v + h * DH;
+
+  RowStage<DH, THREADS, kBwdTile> kst, vst;
+  kst.load(kh, seg.row0, seg.nk, ks);
+  vst.load(vh, seg.row0, seg.nk, vs);
 
   bf16x8 qf[KK], dof[KK];
   float dpart = 0.f;
@@ -84,59 +102,64 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[d][r] = 0.f;
 
-  for (int kt = 0; kt < seg.n; kt += kBwdTile) {
-    __syncthreads();
-    const __bf16* kh = k + h * DH;
-    const __bf16* vh = v + h * DH;
-    stage_tile<DH, kBwdTile, 64 * NW, true, true>(kh, seg.row0 + kt, seg.n - kt, ks, Ks, Kt);
-    stage_tile<DH, kBwdTile, 64 * NW, true, false>(vh, seg.row0 + kt, seg.n - kt, vs, Vs, nullptr);
-    __syncthreads();
-    if (!wave_live) continue;
+  kst.store(Ks[0]);
+  vst.store(Vs[0]);
+  __syncthreads();
+  const int nt = (seg.nk + kBwdTile - 1) / kBwdTile;
+  for (int t = 0; t < nt; ++t) {
+    const int buf = t & 1, kt = t * kBwdTile;
+    if (t + 1 < nt) {
+      kst.load(kh, seg.row0 + kt + kBwdTile, seg.nk - kt - kBwdTile, ks);
+      vst.load(vh, seg.row0 + kt + kBwdTile, seg.nk - kt - kBwdTile, vs);
+    }
+    if (wave_live) {
 #pragma unroll
-    for (int sb = 0; sb < kBwdTile / 32; ++sb) {
-      const int key0 = kt + sb * 32;
-      if (key0 >= seg.n) break;
-      floatx16 s, dp;
+      for (int sb = 0; sb < kBwdTile / 32; ++sb) {
+        const int key0 = kt + sb * 32;
+        if (key0 >= seg.nk) break;
+        floatx16 s, dp;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&Ks[(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[kk], s, 0, 0, 0);
-        const bf16x8 va = *reinterpret_cast<const bf16x8*>(&Vs[(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[kk], dp, 0, 0, 0);
-      }
-      float ds[16];
+        for (int kk = 0; kk < KK; ++kk) {
+          const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&Ks[buf][(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[kk], s, 0, 0, 0);
+          const bf16x8 va = *reinterpret_cast<const bf16x8*>(&Vs[buf][(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[kk], dp, 0, 0, 0);
+        }
+        float ds[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -lse2));
-        if (key0 + acc_row(r, hh) >= seg.n) p = 0.f;
-        ds[r] = p * (dp[r] - D);
-      }
+        for (int r = 0; r < 16; ++r) {
+          float p = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -lse2));
+          if (key0 + acc_row(r, hh) >= seg.nk) p = 0.f;
+          ds[r] = p * (dp[r] - D);
+        }
 #pragma unroll
-      for (int mf = 0; mf < 2; ++mf) {
-        floatx8 f;
+        for (int mf = 0; mf < 2; ++mf) {
+          floatx8 f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) f[j] = ds[8 * mf + j];
-        const bf16x8 dsb = float_to_bf16x8(f);
+          for (int j = 0; j < 8; ++j) f[j] = ds[8 * mf + j];
+          const bf16x8 dsb = float_to_bf16x8(f);
 #pragma unroll
-        for (int d = 0; d < DB; ++d) {
-          const bf16x8 a = transposed_frag<TS>(Kt, d * 32 + l32, sb * 32, mf, hh);
-          acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb, acc[d], 0, 0, 0);
+          for (int d = 0; d < DB; ++d) {
+            const bf16x8 a = transposed_frag_rowmajor<RS>(Ks[buf], d, sb * 32, mf, lane);   // K^T
+            acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb, acc[d], 0, 0, 0);
+          }
         }
       }
     }
-  }
-  if (!wave_live || !q_ok) return;
-  __bf16* row = dq + (seg.row0 + qi) * gstride + h * DH;
-#pragma unroll
-  for (int d = 0; d < DB; ++d)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      floatx4 f = {acc[d][4 * g] * scale, acc[d][4 * g + 1] * scale, acc[d][4 * g + 2] * scale,
-                   acc[d][4 * g + 3] * scale};
-      *reinterpret_cast<bf16x4*>(row + d * 32 + 8 * g + 4 * hh) = __builtin_convertvector(f, bf16x4);
+    if (t + 1 < nt) {
+      kst.store(Ks[buf ^ 1]);
+      vst.store(Vs[buf ^ 1]);
     }
+    __syncthreads();
+  }
+  __bf16* tile = &Ks[0][0] + wv * 32 * RS;
+  if (wave_live) park_tile<DH, RS>(acc, scale, tile, l32, hh);
+  __syncthreads();
+  if (wave_live)
+    flush_tile<DH, RS>(tile, dq + (seg.row0 + q0 + wv * 32) * gstride + h * DH, gstride,
+                       min(32, seg.nq - q0 - wv * 32), lane);
 }
 
 // ------------------------------------------------------------------------ dK, dV (bf16)
@@ -146,25 +169,52 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           const __bf16* __restrict__ v, long qs, long ks, long vs,
                           const __bf16* __restrict__ dout, const float* __restrict__ lse,
                           const float* __restrict__ dvec, long lse_stride, const int32_t* __restrict__ cu, int H,
-                          float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs) {
-  constexpr int RS = DH + 8, TS = transposed_stride(kBwdTile), KK = DH / 16, DB = DH / 32;
-  __shared__ __attribute__((aligned(16))) __bf16 Qs[kBwdTile * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Gs[kBwdTile * RS];     // dO rows
-  __shared__ __attribute__((aligned(16))) __bf16 Qt[DH * TS];
-  __shared__ __attribute__((aligned(16))) __bf16 Gt[DH * TS];
-  __shared__ __attribute__((aligned(16))) float lse2s[kBwdTile];
-  __shared__ __attribute__((aligned(16))) float Ds[kBwdTile];
+                          float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs,
+                          int B, int nkb) {
+  constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW;
+  __shared__ __attribute__((aligned(16))) __bf16 Qs[2][kBwdTile * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Gs[2][kBwdTile * RS];     // dO rows
+  __shared__ __attribute__((aligned(16))) float lse2s[2][kBwdTile];
+  __shared__ __attribute__((aligned(16))) float Ds[2][kBwdTile];
+  __shared__ int s_cu[2 * kLptMaxB + 1];
+  __shared__ int s_pick;
+  static_assert(2 * kBwdTile >= 32 * NW, "the Q / dO buffers double as the output staging tiles");
 
-  const int h = blockIdx.y;
-  const Seg seg = seg_of(blockIdx.z, cu);
-  const int k0 = blockIdx.x * (32 * NW);
-  if (k0 >= seg.n) return;
+  const TileId tile_id = xcd_tile(nkb, H, B);
+  if (!tile_id.valid) return;
+  const int h = tile_id.h;
+  const Segment seg = lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick);
+  const int k0 = tile_id.qb * (32 * NW);
+  if (k0 >= seg.nk) return;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
   const int ki = k0 + wv * 32 + l32;
-  const bool wave_live = k0 + wv * 32 < seg.n;
-  const bool k_ok = ki < seg.n;
+  const bool wave_live = k0 + wv * 32 < seg.nk;
+  const bool k_ok = ki < seg.nk;
   const long C = (long)H * DH;
   const float scale_log2 = scale * kLog2e;
+  const __bf16* qh = q + h * DH;
+  const __bf16* gh = dout + h * DH;
+  const float* lse_h = lse + h * lse_stride + seg.row0;
+  const float* dvec_h = dvec + h * lse_stride + seg.row0;
+
+  RowStage<DH, THREADS, kBwdTile> qst, gst;
+  float lreg = 0.f, dreg = 0.f;            // lse / D of query row `tid` of the tile (tid < 64)
+  auto load_stats = [&](int qt) {
+    if (tid < kBwdTile) {
+      const bool ok = qt + tid < seg.nq;
+      lreg = ok ? lse_h[qt + tid] * kLog2e : INFINITY;   // invalid rows: probability 0
+      dreg = ok ? dvec_h[qt + tid] : 0.f;
+    }
+  };
+  auto store_stats = [&](int buf) {
+    if (tid < kBwdTile) {
+      lse2s[buf][tid] = lreg;
+      Ds[buf][tid] = dreg;
+    }
+  };
+  qst.load(qh, seg.row0, seg.nq, qs);
+  gst.load(gh, seg.row0, seg.nq, C);
+  load_stats(0);
 
   bf16x8 kf[KK], vf[KK];
 #pragma unroll
@@ -183,73 +233,80 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dka[d][r] = 0.f; dva[d][r] = 0.f; }
 
-  for (int qt = 0; qt < seg.n; qt += kBwdTile) {
-    __syncthreads();
-    stage_tile<DH, kBwdTile, 64 * NW, true, true>(q + h * DH, seg.row0 + qt, seg.n - qt, qs, Qs, Qt);
-    stage_tile<DH, kBwdTile, 64 * NW, true, true>(dout + h * DH, seg.row0 + qt, seg.n - qt, C, Gs, Gt);
-    for (int i = tid; i < kBwdTile; i += 64 * NW) {
-      const bool ok = qt + i < seg.n;
-      // invalid query rows: lse = +inf makes their probabilities 0
-      lse2s[i] = ok ? lse[h * lse_stride + seg.row0 + qt + i] * kLog2e : INFINITY;
-      Ds[i] = ok ? dvec[h * lse_stride + seg.row0 + qt + i] : 0.f;
+  qst.store(Qs[0]);
+  gst.store(Gs[0]);
+  store_stats(0);
+  __syncthreads();
+  const int nt = (seg.nq + kBwdTile - 1) / kBwdTile;
+  for (int t = 0; t < nt; ++t) {
+    const int buf = t & 1, qt = t * kBwdTile;
+    if (t + 1 < nt) {
+      qst.load(qh, seg.row0 + qt + kBwdTile, seg.nq - qt - kBwdTile, qs);
+      gst.load(gh, seg.row0 + qt + kBwdTile, seg.nq - qt - kBwdTile, C);
+      load_stats(qt + kBwdTile);
     }
-    __syncthreads();
-    if (!wave_live) continue;
+    if (wave_live) {
 #pragma unroll
-    for (int sb = 0; sb < kBwdTile / 32; ++sb) {
-      if (qt + sb * 32 >= seg.n) break;
-      // S tile: rows = 32 queries, cols = this wave's 32 keys
-      floatx16 s, dp;
+      for (int sb = 0; sb < kBwdTile / 32; ++sb) {
+        if (qt + sb * 32 >= seg.nq) break;
+        // S tile: rows = 32 queries, cols = this wave's 32 keys
+        floatx16 s, dp;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 qa = *reinterpret_cast<const bf16x8*>(&Qs[(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
-        const bf16x8 ga = *reinterpret_cast<const bf16x8*>(&Gs[(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vf[kk], dp, 0, 0, 0);
-      }
-      float p[16], ds[16];
+        for (int kk = 0; kk < KK; ++kk) {
+          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(&Qs[buf][(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
+          const bf16x8 ga = *reinterpret_cast<const bf16x8*>(&Gs[buf][(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vf[kk], dp, 0, 0, 0);
+        }
+        float p[16], ds[16];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const floatx4 l4 = *reinterpret_cast<const floatx4*>(&lse2s[sb * 32 + 8 * g + 4 * hh]);
-        const floatx4 d4 = *reinterpret_cast<const floatx4*>(&Ds[sb * 32 + 8 * g + 4 * hh]);
+        for (int g = 0; g < 4; ++g) {
+          const floatx4 l4 = *reinterpret_cast<const floatx4*>(&lse2s[buf][sb * 32 + 8 * g + 4 * hh]);
+          const floatx4 d4 = *reinterpret_cast<const floatx4*>(&Ds[buf][sb * 32 + 8 * g + 4 * hh]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * g + e;
-          p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -l4[e]));
-          ds[r] = p[r] * (dp[r] - d4[e]);
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * g + e;
+            p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -l4[e]));
+            ds[r] = p[r] * (dp[r] - d4[e]);
+          }
+        }
+#pragma unroll
+        for (int mf = 0; mf < 2; ++mf) {
+          floatx8 fp, fd;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { fp[j] = p[8 * mf + j]; fd[j] = ds[8 * mf + j]; }
+          const bf16x8 pb = float_to_bf16x8(fp), dsb = float_to_bf16x8(fd);
+#pragma unroll
+          for (int d = 0; d < DB; ++d) {
+            const bf16x8 ga = transposed_frag_rowmajor<RS>(Gs[buf], d, sb * 32, mf, lane);   // dO^T
+            dva[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, pb, dva[d], 0, 0, 0);
+            const bf16x8 qa = transposed_frag_rowmajor<RS>(Qs[buf], d, sb * 32, mf, lane);   // Q^T
+            dka[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, dsb, dka[d], 0, 0, 0);
+          }
         }
       }
-#pragma unroll
-      for (int mf = 0; mf < 2; ++mf) {
-        floatx8 fp, fd;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) { fp[j] = p[8 * mf + j]; fd[j] = ds[8 * mf + j]; }
-        const bf16x8 pb = float_to_bf16x8(fp), dsb = float_to_bf16x8(fd);
-#pragma unroll
-        for (int d = 0; d < DB; ++d) {
-          const bf16x8 ga = transposed_frag<TS>(Gt, d * 32 + l32, sb * 32, mf, hh);
-          dva[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, pb, dva[d], 0, 0, 0);
-          const bf16x8 qa = transposed_frag<TS>(Qt, d * 32 + l32, sb * 32, mf, hh);
-          dka[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, dsb, dka[d], 0, 0, 0);
-        }
-      }
     }
+    if (t + 1 < nt) {
+      qst.store(Qs[buf ^ 1]);
+      gst.store(Gs[buf ^ 1]);
+      store_stats(buf ^ 1);
+    }
+    __syncthreads();
   }
-  if (!wave_live || !k_ok) return;
-  __bf16* krow = dk + (seg.row0 + ki) * dks + h * DH;
-  __bf16* vrow = dv + (seg.row0 + ki) * dvs + h * DH;
-#pragma unroll
-  for (int d = 0; d < DB; ++d)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      floatx4 fk = {dka[d][4 * g] * scale, dka[d][4 * g + 1] * scale, dka[d][4 * g + 2] * scale,
-                    dka[d][4 * g + 3] * scale};
-      floatx4 fv = {dva[d][4 * g], dva[d][4 * g + 1], dva[d][4 * g + 2], dva[d][4 * g + 3]};
-      *reinterpret_cast<bf16x4*>(krow + d * 32 + 8 * g + 4 * hh) = __builtin_convertvector(fk, bf16x4);
-      *reinterpret_cast<bf16x4*>(vrow + d * 32 + 8 * g + 4 * hh) = __builtin_convertvector(fv, bf16x4);
-    }
+  __bf16* ktile = &Qs[0][0] + wv * 32 * RS;
+  __bf16* vtile = &Gs[0][0] + wv * 32 * RS;
+  if (wave_live) {
+    park_tile<DH, RS>(dka, scale, ktile, l32, hh);
+    park_tile<DH, RS>(dva, 1.0f, vtile, l32, hh);
+  }
+  __syncthreads();
+  if (wave_live) {
+    const int nrows = min(32, seg.nk - k0 - wv * 32);
+    flush_tile<DH, RS>(ktile, dk + (seg.row0 + k0 + wv * 32) * dks + h * DH, dks, nrows, lane);
+    flush_tile<DH, RS>(vtile, dv + (seg.row0 + k0 + wv * 32) * dvs + h * DH, dvs, nrows, lane);
+  }
 }
 
 // ------------------------------------------------------------------------------- fp32
@@ -408,16 +465,18 @@ extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void
 #undef SPA_BWD_F32
   } else {
     constexpr int NW = 4;
-    const dim3 grid((max_seqlen + 32 * NW - 1) / (32 * NW), H, B), block(64 * NW);
+    const int nblk = (max_seqlen + 32 * NW - 1) / (32 * NW);
+    SPA_REQUIRE(((long)H * B + 8) * nblk < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H*blocks must be < 2^31", fn);
+    const dim3 grid(xcd_grid(nblk, H, B)), block(64 * NW);
 #define SPA_BWD_BF16(D)                                                                                         \
   hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D, NW>), grid, block, 0, st, (const __bf16*)q, (const __bf16*)k,  \
                      (const __bf16*)v, (long)q_row_stride, (long)k_row_stride, (long)v_row_stride,              \
                      (const __bf16*)out, (const __bf16*)dout, lse, ls, cu_seqlens, H, scale, (__bf16*)dq,       \
-                     (long)dq_row_stride, dvec);                                                                \
+                     (long)dq_row_stride, dvec, B, nblk);                                                       \
   hipLaunchKernelGGL((attn_bwd_dkdv_bf16_kernel<D, NW>), grid, block, 0, st, (const __bf16*)q,                  \
                      (const __bf16*)k, (const __bf16*)v, (long)q_row_stride, (long)k_row_stride,                \
                      (long)v_row_stride, (const __bf16*)dout, lse, dvec, ls, cu_seqlens, H, scale,              \
-                     (__bf16*)dk, (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride)
+                     (__bf16*)dk, (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride, B, nblk)
     if (Dh == 32) { SPA_BWD_BF16(32); } else { SPA_BWD_BF16(64); }
 #undef SPA_BWD_BF16
   }

@@ -24,28 +24,6 @@
 
 namespace spa {
 
-struct Segment {
-  long row0;   // first packed row of the segment
-  int nq;      // query rows to compute
-  int nk;      // keys to attend to
-};
-
-// packed mode: cu_seqlens bounds.  padded mode (key_lens != nullptr): every image owns
-// n_pad rows, all are queries, only the first key_lens[b] are keys.
-__device__ __forceinline__ Segment segment_of(int b, const int32_t* cu, const int32_t* key_lens, int n_pad) {
-  Segment s;
-  if (key_lens != nullptr) {
-    s.row0 = (long)b * n_pad;
-    s.nq = n_pad;
-    s.nk = min(max(key_lens[b], 0), n_pad);
-  } else {
-    const int a = cu[b];
-    s.row0 = a;
-    s.nq = s.nk = cu[b + 1] - a;
-  }
-  return s;
-}
-
 // Optional fused scatter-back (the unpack step folded into the attention kernel): packed
 // output row j goes to y[gather_idx[j]] (plus base), and every workgroup first fills its
 // share of the rows that bypass attention (inv_pos < 0) with base or zero.  All-null = off.
@@ -238,83 +216,6 @@ __device__ __forceinline__ void fwd_flush(const __bf16* tile, __bf16* out, const
       }
     }
   }
-}
-
-// XCD-aware launch order.  Workgroups are handed to the 8 XCDs round-robin by linear id and
-// each XCD has its own L2, so the query blocks that share one (image, head)'s K and V must
-// sit on the same XCD or every XCD fetches those rows from memory again.  The grid is 1-D:
-// id -> (xcd = id % 8, j = id / 8); inside an XCD j walks (pair, query block) with the query
-// block fastest, and pair = 8 * (j / nqb) + xcd spreads consecutive pairs over the XCDs.
-// pair -> (launch rank of the image = pair / H, head = pair % H).  Ids past the last pair
-// (the grid is padded to a multiple of 8 pairs) are invalid.
-struct TileId {
-  int qb, h, rank;
-  bool valid;
-};
-__device__ __forceinline__ TileId xcd_tile(int nqb, int H, int B) {
-  const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
-  const int pl = j / nqb;
-  TileId t;
-  t.qb = j - pl * nqb;
-  const int pair = pl * 8 + xcd;
-  t.valid = pair < H * B;
-  t.h = pair % H;
-  t.rank = pair / H;
-  return t;
-}
-static unsigned xcd_grid(int nqb, int H, int B) {
-  const long pairs8 = ((long)H * B + 7) / 8;
-  return (unsigned)(pairs8 * 8 * nqb);
-}
-
-// Longest-segment-first launch order.  Work per segment grows like n^2 and workgroups are
-// handed to compute units in launch order, so the heaviest images should start first.  Maps
-// launch rank -> image by ranking the segment lengths (ties by index) and returns that
-// image's segment; all threads of the workgroup call it.  The bounds are staged in LDS once,
-// so no second dependent global load is needed.  For B > kLptMaxB the order is the identity.
-// Used by the long-segment kernel only: short-segment workgroups are all resident at once
-// and the ranking would cost more than it gains.
-// s_cu: 2*kLptMaxB + 1 ints of LDS.
-constexpr int kLptMaxB = 256;
-template <int THREADS>
-__device__ __forceinline__ Segment lpt_segment(int rank, int B, const int32_t* cu, const int32_t* key_lens,
-                                               int n_pad, int* s_cu, int* s_pick) {
-  if (B > kLptMaxB || B == 1) return segment_of(rank, cu, key_lens, n_pad);
-  // s_cu[b] = segment start (packed mode only), s_len[b] = segment / key length
-  int* s_len = s_cu + kLptMaxB + 1;
-  const bool padded = key_lens != nullptr;
-  for (int b = threadIdx.x; b < B; b += THREADS) {
-    if (padded) {
-      s_len[b] = key_lens[b];
-    } else {
-      const int a = cu[b], e = cu[b + 1];
-      s_cu[b] = a;
-      s_len[b] = e - a;
-    }
-  }
-  __syncthreads();
-  for (int b = threadIdx.x; b < B; b += THREADS) {
-    const int nb = s_len[b];
-    int r = 0;
-#pragma unroll 8
-    for (int j = 0; j < B; ++j) {
-      const int nj = s_len[j];
-      r += (nj > nb) | ((nj == nb) & (j < b));
-    }
-    if (r == rank) *s_pick = b;
-  }
-  __syncthreads();
-  const int img = *s_pick;
-  Segment s;
-  if (padded) {
-    s.row0 = (long)img * n_pad;
-    s.nq = n_pad;
-    s.nk = min(max(s_len[img], 0), n_pad);
-  } else {
-    s.row0 = s_cu[img];
-    s.nq = s.nk = s_len[img];
-  }
-  return s;
 }
 
 // Register staging of key/value rows on their way to LDS: task i = 16-byte chunk column

@@ -89,4 +89,155 @@ __device__ __forceinline__ bf16x8 transposed_frag_rowmajor(const __bf16* rows, i
 // Row of a 32x32 fp32 accumulator tile held in register r of a lane in half hh.
 __device__ __forceinline__ constexpr int acc_row(int r, int hh) { return 8 * (r / 4) + 4 * hh + (r % 4); }
 
+// ------------------------------------------------------------------ segments and launch order
+struct Segment {
+  long row0;   // first packed row of the segment
+  int nq;      // query rows to compute
+  int nk;      // keys to attend to
+};
+
+// packed mode: cu_seqlens bounds.  padded mode (key_lens != nullptr): every image owns
+// n_pad rows, all are queries, only the first key_lens[b] are keys.
+__device__ __forceinline__ Segment segment_of(int b, const int32_t* cu, const int32_t* key_lens, int n_pad) {
+  Segment s;
+  if (key_lens != nullptr) {
+    s.row0 = (long)b * n_pad;
+    s.nq = n_pad;
+    s.nk = min(max(key_lens[b], 0), n_pad);
+  } else {
+    const int a = cu[b];
+    s.row0 = a;
+    s.nq = s.nk = cu[b + 1] - a;
+  }
+  return s;
+}
+
+// XCD-aware launch order.  Workgroups are handed to the 8 XCDs round-robin by linear id and
+// each XCD has its own L2, so the query blocks that share one (image, head)'s K and V must
+// sit on the same XCD or every XCD fetches those rows from memory again.  The grid is 1-D:
+// id -> (xcd = id % 8, j = id / 8); inside an XCD j walks (pair, query block) with the query
+// block fastest, and pair = 8 * (j / nqb) + xcd spreads consecutive pairs over the XCDs.
+// pair -> (launch rank of the image = pair / H, head = pair % H).  Ids past the last pair
+// (the grid is padded to a multiple of 8 pairs) are invalid.
+struct TileId {
+  int qb, h, rank;
+  bool valid;
+};
+__device__ __forceinline__ TileId xcd_tile(int nqb, int H, int B) {
+  const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
+  const int pl = j / nqb;
+  TileId t;
+  t.qb = j - pl * nqb;
+  const int pair = pl * 8 + xcd;
+  t.valid = pair < H * B;
+  t.h = pair % H;
+  t.rank = pair / H;
+  return t;
+}
+static unsigned xcd_grid(int nqb, int H, int B) {
+  const long pairs8 = ((long)H * B + 7) / 8;
+  return (unsigned)(pairs8 * 8 * nqb);
+}
+
+// Longest-segment-first launch order.  Work per segment grows like n^2 and workgroups are
+// handed to compute units in launch order, so the heaviest images should start first.  Maps
+// launch rank -> image by ranking the segment lengths (ties by index) and returns that
+// image's segment; all threads of the workgroup call it.  The bounds are staged in LDS once,
+// so no second dependent global load is needed.  For B > kLptMaxB the order is the identity.
+// Used by the long-segment kernel only: short-segment workgroups are all resident at once
+// and the ranking would cost more than it gains.
+// s_cu: 2*kLptMaxB + 1 ints of LDS.
+constexpr int kLptMaxB = 256;
+template <int THREADS>
+__device__ __forceinline__ Segment lpt_segment(int rank, int B, const int32_t* cu, const int32_t* key_lens,
+                                               int n_pad, int* s_cu, int* s_pick) {
+  if (B > kLptMaxB || B == 1) return segment_of(rank, cu, key_lens, n_pad);
+  // s_cu[b] = segment start (packed mode only), s_len[b] = segment / key length
+  int* s_len = s_cu + kLptMaxB + 1;
+  const bool padded = key_lens != nullptr;
+  for (int b = threadIdx.x; b < B; b += THREADS) {
+    if (padded) {
+      s_len[b] = key_lens[b];
+    } else {
+      const int a = cu[b], e = cu[b + 1];
+      s_cu[b] = a;
+      s_len[b] = e - a;
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < B; b += THREADS) {
+    const int nb = s_len[b];
+    int r = 0;
+#pragma unroll 8
+    for (int j = 0; j < B; ++j) {
+      const int nj = s_len[j];
+      r += (nj > nb) | ((nj == nb) & (j < b));
+    }
+    if (r == rank) *s_pick = b;
+  }
+  __syncthreads();
+  const int img = *s_pick;
+  Segment s;
+  if (padded) {
+    s.row0 = (long)img * n_pad;
+    s.nq = n_pad;
+    s.nk = min(max(s_len[img], 0), n_pad);
+  } else {
+    s.row0 = s_cu[img];
+    s.nq = s.nk = s_len[img];
+  }
+  return s;
+}
+
+// Row-major staging of `ROWS` rows of one head slice on their way to LDS: global -> registers
+// (16-byte chunks, consecutive lanes on consecutive chunks of a row) -> LDS rows of stride
+// DH + 8.  load() and store() are separate so that the next tile's rows can be in flight
+// while the current tile is consumed.  Rows >= nrows read as zero.
+template <int DH, int THREADS, int ROWS>
+struct RowStage {
+  static constexpr int CPR = DH / 8;
+  static constexpr int CHUNKS = ROWS * CPR;
+  static constexpr int CPT = (CHUNKS + THREADS - 1) / THREADS;
+  bf16x8 reg[CPT];
+  __device__ __forceinline__ void load(const __bf16* src, long base, int nrows, long stride) {
+#pragma unroll
+    for (int t = 0; t < CPT; ++t) {
+      const int i = threadIdx.x + t * THREADS, r = i / CPR, c = i % CPR;
+      reg[t] = zero_bf16x8();
+      if (i < CHUNKS && r < nrows) reg[t] = *reinterpret_cast<const bf16x8*>(src + (base + r) * stride + c * 8);
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* rows) const {
+#pragma unroll
+    for (int t = 0; t < CPT; ++t) {
+      const int i = threadIdx.x + t * THREADS, r = i / CPR, c = i % CPR;
+      if (i < CHUNKS) *reinterpret_cast<bf16x8*>(&rows[r * (DH + 8) + c * 8]) = reg[t];
+    }
+  }
+};
+
+// Park a wave's transposed accumulator tile (rows = head dim, cols = its 32 tokens) in LDS
+// as 32 token rows of DH bf16 (row stride RS), scaled; then flush_tile writes whole rows.
+template <int DH, int RS>
+__device__ __forceinline__ void park_tile(const floatx16 (&acc)[DH / 32], float scale, __bf16* tile, int l32, int hh) {
+#pragma unroll
+  for (int d = 0; d < DH / 32; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      floatx4 f = {acc[d][4 * g] * scale, acc[d][4 * g + 1] * scale, acc[d][4 * g + 2] * scale,
+                   acc[d][4 * g + 3] * scale};
+      *reinterpret_cast<bf16x4*>(&tile[l32 * RS + d * 32 + 8 * g + 4 * hh]) = __builtin_convertvector(f, bf16x4);
+    }
+}
+template <int DH, int RS>
+__device__ __forceinline__ void flush_tile(const __bf16* tile, __bf16* dst, long row_stride, int nrows, int lane) {
+  constexpr int CPR = DH / 8;
+#pragma unroll
+  for (int i = lane; i < 32 * CPR; i += 64) {
+    const int r = i / CPR, c = i % CPR;
+    if (r < nrows)
+      *reinterpret_cast<bf16x8*>(dst + r * row_stride + c * 8) = *reinterpret_cast<const bf16x8*>(&tile[r * RS + c * 8]);
+  }
+}
+
 }  // namespace spa
