@@ -11,6 +11,7 @@
 //                 dV^T += dO^T P and dK^T += Q^T dS.
 // S and dP are recomputed in both (7 GEMM shapes instead of 5) in exchange for determinism.
 #include <cmath>
+#include <cstdlib>
 
 #include "attn_tiles.h"
 #include "spa_common.h"
@@ -31,17 +32,18 @@ __device__ __forceinline__ Seg seg_of(int b, const int32_t* cu) {
   return s;
 }
 
-constexpr int kBwdTile = 64;   // tokens staged per LDS tile
 
 // Both bf16 kernels use the forward's launch scheme: 1-D XCD-aware grid (the blocks that
 // share one (image, head)'s rows sit on one L2), longest image first, 4 waves x 32 rows per
 // workgroup, the other side of the product streaming through double-buffered row-major LDS
-// tiles of 64 tokens with the next tile's rows in flight in registers.  Operands whose
+// tiles of BT tokens with the next tile's rows in flight in registers.  Short segments
+// (<= 256 tokens) use the same kernels with ONE wave per workgroup and 32-token tiles: small
+// independent work units that spread over all SIMDs, no longest-first ranking.  Operands whose
 // k-dimension is the token index are read with the transposing LDS read from the same
 // row-major tiles, so nothing is staged twice.
 
 // --------------------------------------------------------------------------- dQ (bf16)
-template <int DH, int NW>
+template <int DH, int NW, int BT, bool LPT>
 __global__ void __launch_bounds__(64 * NW)
 attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                         const __bf16* __restrict__ v, long qs, long ks, long vs,
@@ -50,16 +52,17 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
                         float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B,
                         int nqb) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW;
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kBwdTile * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[2][kBwdTile * RS];
-  __shared__ int s_cu[2 * kLptMaxB + 1];
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][BT * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[2][BT * RS];
+  __shared__ int s_cu[LPT ? 2 * kLptMaxB + 1 : 1];
   __shared__ int s_pick;
-  static_assert(2 * kBwdTile >= 32 * NW, "the K buffers double as the output staging tile");
+  static_assert(2 * BT >= 32 * NW, "the K buffers double as the output staging tile");
 
   const TileId tile_id = xcd_tile(nqb, H, B);
   if (!tile_id.valid) return;
   const int h = tile_id.h;
-  const Segment seg = lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick);
+  const Segment seg = LPT ? lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick)
+                          : segment_of(tile_id.rank, cu, nullptr, 0);
   const int q0 = tile_id.qb * (32 * NW);
   if (q0 >= seg.nq) return;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -71,7 +74,7 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   const __bf16* kh = k + h * DH;
   const __bf16* vh = v + h * DH;
 
-  RowStage<DH, THREADS, kBwdTile> kst, vst;
+  RowStage<DH, THREADS, BT> kst, vst;
   kst.load(kh, seg.row0, seg.nk, ks);
   vst.load(vh, seg.row0, seg.nk, vs);
 
@@ -105,16 +108,16 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   kst.store(Ks[0]);
   vst.store(Vs[0]);
   __syncthreads();
-  const int nt = (seg.nk + kBwdTile - 1) / kBwdTile;
+  const int nt = (seg.nk + BT - 1) / BT;
   for (int t = 0; t < nt; ++t) {
-    const int buf = t & 1, kt = t * kBwdTile;
+    const int buf = t & 1, kt = t * BT;
     if (t + 1 < nt) {
-      kst.load(kh, seg.row0 + kt + kBwdTile, seg.nk - kt - kBwdTile, ks);
-      vst.load(vh, seg.row0 + kt + kBwdTile, seg.nk - kt - kBwdTile, vs);
+      kst.load(kh, seg.row0 + kt + BT, seg.nk - kt - BT, ks);
+      vst.load(vh, seg.row0 + kt + BT, seg.nk - kt - BT, vs);
     }
     if (wave_live) {
 #pragma unroll
-      for (int sb = 0; sb < kBwdTile / 32; ++sb) {
+      for (int sb = 0; sb < BT / 32; ++sb) {
         const int key0 = kt + sb * 32;
         if (key0 >= seg.nk) break;
         floatx16 s, dp;
@@ -163,7 +166,7 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
 }
 
 // ------------------------------------------------------------------------ dK, dV (bf16)
-template <int DH, int NW>
+template <int DH, int NW, int BT, bool LPT>
 __global__ void __launch_bounds__(64 * NW)
 attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                           const __bf16* __restrict__ v, long qs, long ks, long vs,
@@ -172,18 +175,19 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs,
                           int B, int nkb) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW;
-  __shared__ __attribute__((aligned(16))) __bf16 Qs[2][kBwdTile * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Gs[2][kBwdTile * RS];     // dO rows
-  __shared__ __attribute__((aligned(16))) float lse2s[2][kBwdTile];
-  __shared__ __attribute__((aligned(16))) float Ds[2][kBwdTile];
-  __shared__ int s_cu[2 * kLptMaxB + 1];
+  __shared__ __attribute__((aligned(16))) __bf16 Qs[2][BT * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Gs[2][BT * RS];     // dO rows
+  __shared__ __attribute__((aligned(16))) float lse2s[2][BT];
+  __shared__ __attribute__((aligned(16))) float Ds[2][BT];
+  __shared__ int s_cu[LPT ? 2 * kLptMaxB + 1 : 1];
   __shared__ int s_pick;
-  static_assert(2 * kBwdTile >= 32 * NW, "the Q / dO buffers double as the output staging tiles");
+  static_assert(2 * BT >= 32 * NW, "the Q / dO buffers double as the output staging tiles");
 
   const TileId tile_id = xcd_tile(nkb, H, B);
   if (!tile_id.valid) return;
   const int h = tile_id.h;
-  const Segment seg = lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick);
+  const Segment seg = LPT ? lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick)
+                          : segment_of(tile_id.rank, cu, nullptr, 0);
   const int k0 = tile_id.qb * (32 * NW);
   if (k0 >= seg.nk) return;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -197,17 +201,17 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   const float* lse_h = lse + h * lse_stride + seg.row0;
   const float* dvec_h = dvec + h * lse_stride + seg.row0;
 
-  RowStage<DH, THREADS, kBwdTile> qst, gst;
+  RowStage<DH, THREADS, BT> qst, gst;
   float lreg = 0.f, dreg = 0.f;            // lse / D of query row `tid` of the tile (tid < 64)
   auto load_stats = [&](int qt) {
-    if (tid < kBwdTile) {
+    if (tid < BT) {
       const bool ok = qt + tid < seg.nq;
       lreg = ok ? lse_h[qt + tid] * kLog2e : INFINITY;   // invalid rows: probability 0
       dreg = ok ? dvec_h[qt + tid] : 0.f;
     }
   };
   auto store_stats = [&](int buf) {
-    if (tid < kBwdTile) {
+    if (tid < BT) {
       lse2s[buf][tid] = lreg;
       Ds[buf][tid] = dreg;
     }
@@ -237,17 +241,17 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   gst.store(Gs[0]);
   store_stats(0);
   __syncthreads();
-  const int nt = (seg.nq + kBwdTile - 1) / kBwdTile;
+  const int nt = (seg.nq + BT - 1) / BT;
   for (int t = 0; t < nt; ++t) {
-    const int buf = t & 1, qt = t * kBwdTile;
+    const int buf = t & 1, qt = t * BT;
     if (t + 1 < nt) {
-      qst.load(qh, seg.row0 + qt + kBwdTile, seg.nq - qt - kBwdTile, qs);
-      gst.load(gh, seg.row0 + qt + kBwdTile, seg.nq - qt - kBwdTile, C);
-      load_stats(qt + kBwdTile);
+      qst.load(qh, seg.row0 + qt + BT, seg.nq - qt - BT, qs);
+      gst.load(gh, seg.row0 + qt + BT, seg.nq - qt - BT, C);
+      load_stats(qt + BT);
     }
     if (wave_live) {
 #pragma unroll
-      for (int sb = 0; sb < kBwdTile / 32; ++sb) {
+      for (int sb = 0; sb < BT / 32; ++sb) {
         if (qt + sb * 32 >= seg.nq) break;
         // S tile: rows = 32 queries, cols = this wave's 32 keys
         floatx16 s, dp;
@@ -464,21 +468,34 @@ extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void
     if (Dh == 32) { SPA_BWD_F32(32); } else { SPA_BWD_F32(64); }
 #undef SPA_BWD_F32
   } else {
-    constexpr int NW = 4;
-    const int nblk = (max_seqlen + 32 * NW - 1) / (32 * NW);
+#define SPA_BWD_ARGS_DQ                                                                                       \
+  (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_row_stride, (long)k_row_stride,               \
+      (long)v_row_stride, (const __bf16*)out, (const __bf16*)dout, lse, ls, cu_seqlens, H, scale, (__bf16*)dq, \
+      (long)dq_row_stride, dvec, B, nblk
+#define SPA_BWD_ARGS_DKDV                                                                                     \
+  (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_row_stride, (long)k_row_stride,               \
+      (long)v_row_stride, (const __bf16*)dout, lse, dvec, ls, cu_seqlens, H, scale, (__bf16*)dk,              \
+      (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride, B, nblk
+    const char* env = std::getenv("SPA_ATTN_BWD_SHORT");                 // "tiled" forces the 4-wave kernels
+    const bool short_seg = max_seqlen <= 256 && !(env != nullptr && env[0] == 't');
+    const int rows_per_block = short_seg ? 32 : 128;
+    const int nblk = (max_seqlen + rows_per_block - 1) / rows_per_block;
     SPA_REQUIRE(((long)H * B + 8) * nblk < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H*blocks must be < 2^31", fn);
-    const dim3 grid(xcd_grid(nblk, H, B)), block(64 * NW);
-#define SPA_BWD_BF16(D)                                                                                         \
-  hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D, NW>), grid, block, 0, st, (const __bf16*)q, (const __bf16*)k,  \
-                     (const __bf16*)v, (long)q_row_stride, (long)k_row_stride, (long)v_row_stride,              \
-                     (const __bf16*)out, (const __bf16*)dout, lse, ls, cu_seqlens, H, scale, (__bf16*)dq,       \
-                     (long)dq_row_stride, dvec, B, nblk);                                                       \
-  hipLaunchKernelGGL((attn_bwd_dkdv_bf16_kernel<D, NW>), grid, block, 0, st, (const __bf16*)q,                  \
-                     (const __bf16*)k, (const __bf16*)v, (long)q_row_stride, (long)k_row_stride,                \
-                     (long)v_row_stride, (const __bf16*)dout, lse, dvec, ls, cu_seqlens, H, scale,              \
-                     (__bf16*)dk, (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride, B, nblk)
-    if (Dh == 32) { SPA_BWD_BF16(32); } else { SPA_BWD_BF16(64); }
+    const dim3 grid(xcd_grid(nblk, H, B));
+#define SPA_BWD_BF16(D)                                                                                          \
+  do {                                                                                                           \
+    if (short_seg) {                                                                                             \
+      hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D, 1, 32, false>), grid, dim3(64), 0, st, SPA_BWD_ARGS_DQ);     \
+      hipLaunchKernelGGL((attn_bwd_dkdv_bf16_kernel<D, 1, 32, false>), grid, dim3(64), 0, st, SPA_BWD_ARGS_DKDV); \
+    } else {                                                                                                     \
+      hipLaunchKernelGGL((attn_bwd_dq_bf16_kernel<D, 4, 64, true>), grid, dim3(256), 0, st, SPA_BWD_ARGS_DQ);     \
+      hipLaunchKernelGGL((attn_bwd_dkdv_bf16_kernel<D, 4, 64, true>), grid, dim3(256), 0, st, SPA_BWD_ARGS_DKDV); \
+    }                                                                                                            \
+  } while (0)
+    if (Dh == 32) SPA_BWD_BF16(32); else SPA_BWD_BF16(64);
 #undef SPA_BWD_BF16
+#undef SPA_BWD_ARGS_DQ
+#undef SPA_BWD_ARGS_DKDV
   }
   return check_launch(fn);
 }
