@@ -121,7 +121,8 @@ __global__ void __launch_bounds__(kGateThreads)
 gate_bwd_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
                 const float* __restrict__ scores, const float* __restrict__ s_up,
                 const uint8_t* __restrict__ labels, const T* __restrict__ d_rg, int gate_scaled,
-                float loss_scale, int ntok, int C, T* __restrict__ dx, float* __restrict__ partial) {
+                float loss_scale, int ntok, int C, T* __restrict__ dx, float* __restrict__ partial,
+                int fold_parallel) {
   constexpr int VE = Vec16<T>::kElems;
   constexpr int kGroups = kGateThreads / G;
   extern __shared__ float lds[];
@@ -191,19 +192,41 @@ gate_bwd_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
     }
   }
 
-  // fold the groups in a fixed order
-  for (int gsel = 0; gsel < kGroups; ++gsel) {
-    if (grp == gsel) {
+  // fold the groups in a fixed order (group 0, 1, ...).  When the per-group partials fit in
+  // LDS every group parks its partial row and each thread adds a column top to bottom; else
+  // the groups take turns adding into one LDS row.
+  if (fold_parallel) {
+    float* grows = sdw + C;                       // [kGroups][C]
 #pragma unroll
-      for (int it = 0; it < IT; ++it) {
-        const int ch = gl + it * G;
-        if (ch < chunks) {
+    for (int it = 0; it < IT; ++it) {
+      const int ch = gl + it * G;
+      if (ch < chunks) {
 #pragma unroll
-          for (int e = 0; e < VE; ++e) sdw[ch * VE + e] += dwa[it][e];
-        }
+        for (int e = 0; e < VE; ++e) grows[grp * C + ch * VE + e] = dwa[it][e];
       }
     }
     __syncthreads();
+    for (int c = threadIdx.x; c < C; c += kGateThreads) {
+      float a = 0.f;
+#pragma unroll
+      for (int g2 = 0; g2 < kGroups; ++g2) a += grows[g2 * C + c];
+      sdw[c] = a;
+    }
+    __syncthreads();
+  } else {
+    for (int gsel = 0; gsel < kGroups; ++gsel) {
+      if (grp == gsel) {
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+          const int ch = gl + it * G;
+          if (ch < chunks) {
+#pragma unroll
+            for (int e = 0; e < VE; ++e) sdw[ch * VE + e] += dwa[it][e];
+          }
+        }
+      }
+      __syncthreads();
+    }
   }
   if (gl == 0) { s_loss[grp] = loss_acc; s_db[grp] = db_acc; }
   __syncthreads();
@@ -324,12 +347,15 @@ static int launch_gate_bwd(const void* x, const void* w, float bias, const float
   constexpr int VE = Vec16<T>::kElems;
   const int chunks = C / VE;
   const int parts = gate_bwd_parts(ntok);
-  const size_t lds = 2 * (size_t)C * sizeof(float);
+  // LDS: w [C] + dw row [C] (+ one partial row per group when that fits in 64 KB)
+  const int groups = chunks <= 128 ? 16 : 4;
+  const int fold_parallel = (size_t)(2 + groups) * C * sizeof(float) <= 65536 ? 1 : 0;
+  const size_t lds = (size_t)(fold_parallel ? 2 + groups : 2) * C * sizeof(float);
 #define SPA_GB(G, IT)                                                                                         \
   hipLaunchKernelGGL((gate_bwd_kernel<T, G, IT>), dim3(parts), dim3(kGateThreads), lds, st,                  \
                      static_cast<const T*>(x), static_cast<const T*>(w), bias, scores, s_up, labels,         \
                      static_cast<const T*>(d_rg), gate_scaled, loss_scale, (int)ntok, C, static_cast<T*>(dx), \
-                     partial)
+                     partial, fold_parallel)
   if (chunks <= 16) SPA_GB(16, 1);
   else if (chunks <= 32) SPA_GB(16, 2);
   else if (chunks <= 64) SPA_GB(16, 4);
