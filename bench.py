@@ -28,6 +28,15 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 
+# HBM bytes per launch (fetch + write) of each stage, seed 0, from two `rocprofv3 --pmc` runs of
+# this script (FETCH_SIZE, then WRITE_SIZE; `--calibration-copy --steps 20 --warmup 5`), each
+# counter scaled by what it reads for the plain 256 MiB device copy of the same run
+# (factors 2.000 and 1.000).  Re-measure after any change to a kernel's access pattern.
+MEASURED_TRAFFIC_BYTES = {
+    ("vit_s", "gate_select"): 9.76e6, ("vit_s", "pack"): 29.44e6, ("vit_s", "packed_attention_unpack"): 29.85e6,
+    ("det", "gate_select"): 17.45e6, ("det", "pack"): 26.63e6, ("det", "packed_attention_unpack"): 49.51e6,
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -135,7 +144,7 @@ def cpu_oracle_baseline(wl, bundle, seconds):
         reps += 1
         tokens += r["total"]
         dt = time.perf_counter() - t0
-        if dt >= seconds or reps >= 50:
+        if dt >= seconds:
             break
     return {"value": tokens / dt, "unit": "selected tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{reps} full forward passes of the {wl.name} batch (NumPy fp64, {dt:.1f} s)"}
@@ -220,7 +229,10 @@ def main():
     dom = max(kernels, key=lambda k_: kernels[k_]["kernel_us"])
     kd = kernels[dom]
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
-                "unit": kd["unit"], "frac": kd["frac"], "traffic": None, "avg_launch_us": kd["kernel_us"],
+                "unit": kd["unit"], "frac": kd["frac"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)) if args.seed == 0 else None,
+                "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
+                "avg_launch_us": kd["kernel_us"],
                 "event_pair_overhead_us": round(ev_overhead, 2)}
     if wl.dtype == "f32" and dom.startswith("packed_attention"):
         roofline.update({"bound": "alu", "peak": 157.3, "frac": round(kd["achieved"] / 157.3, 4)})
