@@ -92,7 +92,8 @@ int spa_maxpool2x2(const float* s, int B, int h, int w, float* pooled, void* str
  *   rows T .. ceil(T/container_len)*container_len - 1 of packed are zero (only the last
  *   container is padded); container_len = 0 means no padding.  Rows beyond that are left
  *   untouched.
- * in:  x [B,N,C] dtype (C may be a fused row such as 3*C of q|k|v); mask [B,N] uint8
+ * in:  x [B,N,C] dtype (C may be a fused row such as 3*C of q|k|v), or NULL together with
+ *      packed = NULL to compute the indices only; mask [B,N] uint8
  *      (non-zero = selected); counts [B] int32 or NULL: the per-image selected counts that
  *      spa_gate_select wrote for this mask (when given, a workgroup scans only its own
  *      image's mask instead of the whole prefix; results are identical);
@@ -151,6 +152,24 @@ int spa_packed_attention_unpack(const void* q, const void* k, const void* v, int
                                 const int32_t* inv_pos, const void* base, int B, int N, int H, int Dh,
                                 int dtype, float softmax_scale, void* out, float* lse, void* y,
                                 void* stream);
+
+/*
+ * Linear projection of packed tokens (the 3 L C^2 / N C^2 terms of the SPA complexity
+ * formula, Section 3.2), with the packing gather and the gate scaling optionally folded into
+ * the operand load:
+ *   a_j     = x[gather_idx[j], :] (or x[j, :] when gather_idx is NULL)
+ *   a_j    *= sigmoid(gate_scores[gather_idx[j]]) when gate_scores is given (r_g = Sigmoid(s) . r),
+ *             rounded to dtype as a materialised packed r_g would be
+ *   out[j,:] = a_j W^T + bias                      for j < min(*total, M_cap)
+ * in:  x [*, K] dtype; gather_idx [>= rows] int32 or NULL; gate_scores fp32 indexed by token
+ *      or NULL (needs gather_idx); total [1] int32 (device) or NULL (= M_cap rows);
+ *      W [N_out, K] dtype (row n = weights of output n); bias [N_out] dtype or NULL.
+ *      bf16: K a multiple of 32, N_out and out_row_stride multiples of 8.
+ * out: out[j*out_row_stride + n] dtype; rows >= min(*total, M_cap) are not written.
+ */
+int spa_linear_packed(const void* x, const int32_t* gather_idx, const float* gate_scores,
+                      const int32_t* total, const void* W, const void* bias, int M_cap, int K,
+                      int N_out, int dtype, void* out, int64_t out_row_stride, void* stream);
 
 /* ----------------------------------------------------------------- training ---- */
 

@@ -306,6 +306,21 @@ def gate_backward(x, w, bias, s_up, labels, d_rg, gate_scaled: bool, loss_scale:
             "scores": s}
 
 
+# ------------------------------------------------------------------------ projections
+def linear_packed(x, gather_idx, W, bias=None, scores=None, dtype: Optional[str] = None) -> np.ndarray:
+    """Projection of the packed tokens (the 3LC^2 / NC^2 terms of the complexity formula of
+    Section 3.2): row j of the result is a_j W^T + bias with a_j = x[gather_idx[j]], first
+    multiplied by sigmoid(score) of that token (r_g = Sigmoid(s) . r) and rounded to the
+    storage type when scores are given.  x [..., K], W [N_out, K].  Plain fp64 matmul."""
+    rows = pack_rows(np.asarray(x, dtype=F64).reshape(-1, np.shape(x)[-1])[None], np.asarray(gather_idx),
+                     None if scores is None else np.asarray(scores, dtype=F64).reshape(1, -1), 0,
+                     dtype if scores is not None else None)
+    y = rows @ np.asarray(W, dtype=F64).T
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=F64)[None, :]
+    return y
+
+
 # ------------------------------------------------------------------------ whole path
 def spa_forward(x, w, bias, qkv, H: int, tau: float, dtype: str,
                 s_up: Optional[np.ndarray] = None, container_len: int = 0,

@@ -114,7 +114,7 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
       if (cu_seqlens != nullptr) cu_seqlens[B] = T_sel;
       if (total != nullptr) total[0] = T_sel;
     }
-    if (container_len > 0) {
+    if (container_len > 0 && packed != nullptr) {
       const long t_pad = ((long)T_sel + container_len - 1) / container_len * container_len;
       const long nz = (t_pad - T_sel) * chunks;
       uintx4* dst = reinterpret_cast<uintx4*>(packed + (long)T_sel * C);
@@ -126,7 +126,7 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
   // 4. copy the survivors' rows: consecutive threads take consecutive 16-byte chunks, four
   //    independent loads in flight per thread before the first store
   constexpr int U = 8;
-  const unsigned work = (unsigned)nsel * (unsigned)chunks;
+  const unsigned work = packed != nullptr ? (unsigned)nsel * (unsigned)chunks : 0u;   // indices only: no rows
   const T* xt = x + flat0 * (long)C;
   T* pt = packed + (long)base * C;
   for (unsigned i0 = tid; i0 < work; i0 += kPackThreads * U) {
@@ -303,7 +303,8 @@ extern "C" int spa_pack(const void* x, const uint8_t* mask, const int32_t* count
                         const float* gate_scores, int B, int N, int C, int dtype, int container_len,
                         void* packed, int32_t* cu_seqlens, int32_t* gather_idx, int32_t* inv_pos,
                         int32_t* total, void* stream) {
-  SPA_REQUIRE(x && mask && packed, SPA_ERR_INVALID_ARG, "spa_pack: null pointer");
+  SPA_REQUIRE(mask && ((x != nullptr) == (packed != nullptr)), SPA_ERR_INVALID_ARG,
+              "spa_pack: mask is null, or only one of x / packed is given");
   if (int rc = check_rows("spa_pack", B, N, C, dtype)) return rc;
   SPA_REQUIRE(container_len >= 0, SPA_ERR_INVALID_ARG, "spa_pack: container_len must be >= 0");
   SPA_REQUIRE(aligned16(x) && aligned16(packed), SPA_ERR_INVALID_ARG, "spa_pack: x / packed not 16-byte aligned");

@@ -35,6 +35,7 @@ _SIGNATURES = {
     "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
     "spa_packed_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
                                             c_int, c_int, c_float, _P, _P, _P, _P]),
+    "spa_linear_packed": (c_int, [_P, _P, _P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, c_int64, _P]),
     "spa_unpack": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_unpack_bwd": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_pack_bwd": (c_int, [_P, _P, c_int, c_int, c_int, c_int, _P, _P]),
@@ -139,11 +140,14 @@ def spa_maxpool2x2(s, h, w, pooled, prepare=False):
 
 def spa_pack(x, mask, counts, gate_scores, container_len, packed, cu_seqlens, gather_idx, inv_pos, total,
              prepare=False):
-    """x [B,N,C] (C may be a fused q|k|v row) -> packed [cap,C], cu_seqlens [B+1], gather_idx, inv_pos, total."""
-    B, N, C = x.shape
+    """x [B,N,C] (C may be a fused q|k|v row) -> packed [cap,C], cu_seqlens [B+1], gather_idx, inv_pos, total.
+    x = packed = None computes the indices only."""
+    B, N = mask.shape
+    C = x.shape[2] if x is not None else 8
     _keep = (x, mask, counts, gate_scores, packed, cu_seqlens, gather_idx, inv_pos, total,)
     _contig(*_keep)
-    return _dispatch(lib.spa_pack, (_ptr(x), _ptr(mask), _ptr(counts), _ptr(gate_scores), B, N, C, dtype_code(x),
+    return _dispatch(lib.spa_pack, (_ptr(x), _ptr(mask), _ptr(counts), _ptr(gate_scores), B, N, C,
+                        dtype_code(x) if x is not None else SPA_BF16,
                         int(container_len), _ptr(packed), _ptr(cu_seqlens), _ptr(gather_idx), _ptr(inv_pos),
                         _ptr(total), _stream(),), _keep, prepare)
 
@@ -175,6 +179,18 @@ def spa_packed_attention_unpack(q, k, v, cu_seqlens, gather_idx, inv_pos, base, 
                      (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(cu_seqlens),
                       _ptr(gather_idx), _ptr(inv_pos), _ptr(base), B, N, H, Dh, dtype_code(y), float(softmax_scale),
                       _ptr(out), _ptr(lse), _ptr(y), _stream(),), _keep, prepare)
+
+
+def spa_linear_packed(x, gather_idx, gate_scores, total, W, bias, out, prepare=False):
+    """out[j] = (sigmoid(score) * x[gather_idx[j]]) W^T + bias for j < *total.  x [*, K] (any leading
+    shape), W [N_out, K], out a [rows, N_out] tensor or column-slice view."""
+    K = x.shape[-1]
+    N_out = W.shape[0]
+    _keep = (x, gather_idx, gate_scores, total, W, bias,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_linear_packed,
+                     (_ptr(x), _ptr(gather_idx), _ptr(gate_scores), _ptr(total), _ptr(W), _ptr(bias), out.shape[0], K,
+                      N_out, dtype_code(x), _ptr(out), _row_stride(out), _stream(),), _keep + (out,), prepare)
 
 
 def spa_unpack(packed_out, inv_pos, base, y, prepare=False):

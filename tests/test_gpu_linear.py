@@ -1,0 +1,101 @@
+"""Projection of packed tokens (gather and gate scaling folded into the operand load) against
+the CPU oracle, and a whole SPA block: gate -> select -> indices -> QKV projection of the
+selected, gated tokens -> per-image attention -> scatter back."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import spa_oracle as orc
+from paper_2410_23608_amd import workloads as wlmod
+from spa_harness import dev, host, tdtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def spa():
+    from paper_2410_23608_amd import spa as mod
+    return mod
+
+
+def _rel(got, ref):
+    return float(np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref)))) if ref.size else 0.0
+
+
+@pytest.mark.parametrize("dtype,B,N,K,No", [("bf16", 3, 100, 64, 96), ("bf16", 8, 196, 384, 1152),
+                                            ("bf16", 2, 777, 96, 288), ("bf16", 4, 129, 32, 8), ("f32", 2, 60, 64, 192)])
+@pytest.mark.parametrize("mode", ["plain", "gather", "gather_scale_bias"])
+def test_linear_packed_matches_oracle(spa, dtype, B, N, K, No, mode):
+    rng = np.random.default_rng(41)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    x = mk(rng.standard_normal((B, N, K)).astype(np.float32))
+    W = mk((rng.standard_normal((No, K)) / np.sqrt(K)).astype(np.float32))
+    bias = mk(rng.standard_normal(No).astype(np.float32)) if mode == "gather_scale_bias" else None
+    s = rng.standard_normal((B, N)).astype(np.float32) if mode == "gather_scale_bias" else None
+    mask = (rng.uniform(size=(B, N)) < 0.55).astype(np.uint8)
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    cap = B * N
+    td = tdtype(dtype)
+    if mode == "plain":
+        rows = np.arange(cap, dtype=np.int32)
+        T_used, gi_d, tot_d = cap, None, None
+    else:
+        rows = gidx
+        T_used = T
+        gi = np.zeros(cap, np.int32)
+        gi[:T] = gidx
+        gi_d, tot_d = dev(gi), dev(np.array([T], np.int32))
+    ref = orc.linear_packed(x, rows, W, bias, s, dtype)
+    out = torch.full((cap, No + 16), float("nan"), dtype=td, device="cuda")     # a column-slice view: row stride > N_out
+    spa.spa_linear_packed(dev(x, dtype), gi_d, None if s is None else dev(s), tot_d, dev(W, dtype),
+                          None if bias is None else dev(bias, dtype), out[:, :No])
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.all(np.isnan(got[:, No:])) and np.all(np.isnan(got[T_used:]))       # nothing outside the result
+    tol = 1e-5 if dtype == "f32" else 1e-2
+    assert _rel(got[:T_used, :No], ref) <= tol
+
+
+def test_spa_block_with_projection(spa):
+    """gate_select -> pack (indices only) -> spa_linear_packed(x gathered and gate-scaled, W_qkv)
+    -> spa_packed_attention_unpack, against the oracle's composition of the same steps."""
+    wl = dataclasses.replace(wlmod.WORKLOADS["vit_s"], B=6)
+    B, N, C, H, Dh = wl.B, wl.N, wl.C, wl.H, wl.Dh
+    bun = wlmod.generate(wl, 9, with_qkv=False)
+    rng = np.random.default_rng(9)
+    Wqkv = wlmod.round_bf16((rng.standard_normal((3 * C, C)) / np.sqrt(C)).astype(np.float32))
+    bqkv = wlmod.round_bf16((rng.standard_normal(3 * C) * 0.1).astype(np.float32))
+    x, w, bias = bun["x"], bun["w"], bun["bias"]
+    # oracle
+    s = orc.gate_scores(x, w, bias)
+    mask, margin = orc.select(s, wl.tau)
+    assert margin > 1e-3
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    qkv_packed = orc.round_to_dtype(orc.linear_packed(x, gidx, Wqkv, bqkv, s.astype(np.float32), "bf16"), "bf16")
+    # the oracle's attention takes un-packed tensors: scatter the packed projections back to [B,N,3C]
+    qkv_full = orc.unpack(qkv_packed, inv, B, N)
+    out_ref, _ = orc.attention_per_image(qkv_full[..., :C], qkv_full[..., C:2 * C], qkv_full[..., 2 * C:], mask, H)
+    y_ref = orc.unpack(out_ref, inv, B, N)
+    # device
+    td, cap = torch.bfloat16, B * N
+    xd, wd = dev(x, "bf16"), dev(w, "bf16")
+    scores = torch.empty(B, N, dtype=torch.float32, device="cuda")
+    mask_d = torch.empty(B, N, dtype=torch.uint8, device="cuda")
+    cu_d = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    gidx_d = torch.zeros(cap, dtype=torch.int32, device="cuda")
+    inv_d = torch.empty(cap, dtype=torch.int32, device="cuda")
+    total = torch.empty(1, dtype=torch.int32, device="cuda")
+    pqkv = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    y = torch.empty(B, N, C, dtype=td, device="cuda")
+    spa.spa_gate_select(xd, wd, bias, None, wl.tau, scores, mask_d)
+    spa.spa_pack(None, mask_d, None, None, 0, None, cu_d, gidx_d, inv_d, total)
+    spa.spa_linear_packed(xd, gidx_d, scores, total, dev(Wqkv, "bf16"), dev(bqkv, "bf16"), pqkv)
+    spa.spa_packed_attention_unpack(pqkv[:, :C], pqkv[:, C:2 * C], pqkv[:, 2 * C:], cu_d, gidx_d, inv_d, None, H, Dh, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(mask_d), mask) and np.array_equal(host(cu_d), cu)
+    assert np.array_equal(host(gidx_d)[:T], gidx) and np.array_equal(host(inv_d), inv)
+    assert _rel(host(pqkv)[:T], qkv_packed) <= 1e-2
+    # the device attention runs on its own (slightly different) bf16 projections
+    assert np.max(np.abs(host(y) - y_ref)) <= 4e-2

@@ -408,3 +408,25 @@ def test_forward_path_on_tiny_workload():
         np.testing.assert_allclose(r["y"][b, sel], ref[0], rtol=1e-12, atol=1e-13)
         unsel = np.flatnonzero(r["mask"][b] == 0)
         assert np.all(r["y"][b, unsel] == 0)
+
+
+def test_linear_packed_matches_library_and_bruteforce():
+    B, N, K, No = 2, 7, 5, 3
+    r = rng(50)
+    x = r.standard_normal((B, N, K))
+    W = r.standard_normal((No, K))
+    bias = r.standard_normal(No)
+    s = r.standard_normal((B, N))
+    mask = _random_mask(51, B, N, 0.6)
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    y = orc.linear_packed(x, gidx, W, bias, s)
+    ref = (scipy.special.expit(s)[:, :, None] * x).reshape(-1, K)[gidx] @ W.T + bias
+    np.testing.assert_allclose(y, ref, rtol=1e-13, atol=1e-13)
+    # brute force, no gate scaling, no bias
+    y0 = orc.linear_packed(x, gidx, W)
+    for j in range(T):
+        for n in range(No):
+            acc = sum(x.reshape(-1, K)[gidx[j], c] * W[n, c] for c in range(K))
+            assert abs(y0[j, n] - acc) < 1e-13
+    # identity weights return the packed rows themselves
+    np.testing.assert_array_equal(orc.linear_packed(x, gidx, np.eye(K)), x.reshape(-1, K)[gidx])
