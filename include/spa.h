@@ -158,9 +158,10 @@ int spa_packed_attention_unpack(const void* q, const void* k, const void* v, int
  * formula, Section 3.2), with the packing gather and the gate scaling optionally folded into
  * the operand load:
  *   a_j     = x[gather_idx[j], :] (or x[j, :] when gather_idx is NULL)
- *   a_j    *= sigmoid(gate_scores[gather_idx[j]]) when gate_scores is given (r_g = Sigmoid(s) . r),
- *             rounded to dtype as a materialised packed r_g would be
- *   out[j,:] = a_j W^T + bias                      for j < min(*total, M_cap)
+ *   s_j      = sigmoid(gate_scores[gather_idx[j]]) when gate_scores is given, else 1
+ *              (r_g = Sigmoid(s) . r; the bf16 kernel applies s_j to the fp32 accumulator,
+ *              one rounding fewer than multiplying a materialised packed r_g)
+ *   out[j,:] = s_j (a_j W^T) + bias                for j < min(*total, M_cap)
  * in:  x [*, K] dtype; gather_idx [>= rows] int32 or NULL; gate_scores fp32 indexed by token
  *      or NULL (needs gather_idx); total [1] int32 (device) or NULL (= M_cap rows);
  *      W [N_out, K] dtype (row n = weights of output n); bias [N_out] dtype or NULL.

@@ -2,15 +2,18 @@
 // formula, Section 3.2): out[j,:] = (s_j * x[row(j),:]) W^T + bias, where row(j) is either j
 // or gather_idx[j] (the token gather of the packing step folded into the A-operand load) and
 // s_j is 1 or sigmoid(score) of the token (the gated representation r_g = Sigmoid(s) . r).
+// The row scale s_j is applied to the fp32 accumulator in the epilogue: (s a) W^T = s (a W^T),
+// one rounding fewer than multiplying a materialised bf16 r_g.
 //
 // bf16 path: MFMA GEMM, C[M,N] = A[M,K] B[N,K]^T with both operands K-contiguous ("NT").
 // Workgroup tile 128 x 128 x 32, four waves in a 2 x 2 grid, each wave a 64 x 64 block
 // (2 x 2 v_mfma_f32_32x32x16_bf16 tiles), A and B tiles double-buffered in LDS with the
 // next tile's rows in flight in registers.  Row stride 40 elements keeps the 16-byte
 // fragment reads bank-conflict free.  The output tile leaves through LDS as whole rows.
-// The 1-D grid walks output tiles M-fastest inside groups of 8 N-tiles... no: tiles are
-// numbered so that consecutive ids (round-robin over the 8 XCDs) on one XCD share the same
-// rows of B (weights), which stay in that XCD's L2.
+// Tiles are numbered so that XCD x (= id % 8) owns the M-tiles x, x+8, x+16, ... and walks
+// the N-tiles of one M-tile consecutively: an A tile is fetched into that XCD's L2 once and
+// reused by all its N-tiles, the weights fit in every L2, and the live M-tiles (the row count
+// is only known on the device) spread evenly over the XCDs.
 // fp32 path (tiny workload): one thread per output element.
 #include "attn_tiles.h"
 #include "spa_common.h"
@@ -32,13 +35,10 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
   __shared__ long a_row[BM];       // source row of every tile row (-1 = past the end)
   __shared__ float a_scale[BM];
 
-  // tile id: xcd = id % 8 owns a contiguous range of N-tiles' worth of work (weights stay in
-  // its L2); inside an XCD the M-tiles of one N-tile are consecutive.
   const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
-  const int per_xcd = (m_tiles * n_tiles + 7) / 8;
-  const int lin = xcd * per_xcd + j;
-  if (j >= per_xcd || lin >= m_tiles * n_tiles) return;
-  const int nt = lin / m_tiles, mt = lin - nt * m_tiles;
+  const int mg = j / n_tiles, nt = j - mg * n_tiles;
+  const int mt = mg * 8 + xcd;
+  if (mt >= m_tiles) return;
   const int M = total != nullptr ? min(total[0], m_cap) : m_cap;
   const int m0 = mt * BM, n0 = nt * BN;
   if (m0 >= M) return;
@@ -59,53 +59,38 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
   }
   __syncthreads();
 
-  // staging: a tile is 128 rows x 4 chunks of 16 bytes = 512 chunks, 2 per thread
-  bf16x8 areg[2], breg[2];
-  auto gload = [&](int k0) {
+  // staging: a tile is 128 rows x BK/8 chunks of 16 bytes, CPT chunks per thread.  The rows
+  // and chunk columns a thread stages never change, so their addresses are computed once.
+  constexpr int CPRW = BK / 8, CPT = BM * CPRW / kGemmThreads;
+  const __bf16* ap[CPT];
+  const __bf16* bp[CPT];
+  int lds_off[CPT];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int i = tid + t * kGemmThreads, r = i >> 2, c = i & 3;
-      areg[t] = zero_bf16x8();
-      breg[t] = zero_bf16x8();
-      const long src = a_row[r];
-      if (src >= 0) {
-        bf16x8 a = *reinterpret_cast<const bf16x8*>(x + src * K + k0 + c * 8);
-        if (kScale) {
-          floatx8 f = bf16x8_to_float(a);
-          const float sc = a_scale[r];
+  for (int t = 0; t < CPT; ++t) {
+    const int i = tid + t * kGemmThreads, r = i / CPRW, c = i % CPRW;
+    const long src = a_row[r];
+    ap[t] = src >= 0 ? x + src * K + c * 8 : nullptr;
+    bp[t] = n0 + r < n_out ? W + (long)(n0 + r) * K + c * 8 : nullptr;
+    lds_off[t] = r * RS + c * 8;
+  }
+  // two tiles in flight in registers (PF = prefetch distance in k-tiles)
+  constexpr int PF = 2;
+  bf16x8 areg[PF][CPT], breg[PF][CPT];
+  auto gload = [&](int slot, int k0) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] *= sc;
-          a = float_to_bf16x8(f);
-        }
-        areg[t] = a;
-      }
-      if (n0 + r < n_out) breg[t] = *reinterpret_cast<const bf16x8*>(W + (long)(n0 + r) * K + k0 + c * 8);
+    for (int t = 0; t < CPT; ++t) {
+      areg[slot][t] = ap[t] != nullptr ? *reinterpret_cast<const bf16x8*>(ap[t] + k0) : zero_bf16x8();
+      breg[slot][t] = bp[t] != nullptr ? *reinterpret_cast<const bf16x8*>(bp[t] + k0) : zero_bf16x8();
     }
   };
-  auto lstore = [&](int buf) {
+  auto lstore = [&](int slot, int buf) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int i = tid + t * kGemmThreads, r = i >> 2, c = i & 3;
-      *reinterpret_cast<bf16x8*>(&As[buf][r * RS + c * 8]) = areg[t];
-      *reinterpret_cast<bf16x8*>(&Bs[buf][r * RS + c * 8]) = breg[t];
+    for (int t = 0; t < CPT; ++t) {
+      *reinterpret_cast<bf16x8*>(&As[buf][lds_off[t]]) = areg[slot][t];
+      *reinterpret_cast<bf16x8*>(&Bs[buf][lds_off[t]]) = breg[slot][t];
     }
   };
-
-  floatx16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
-
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  const int nk = K / BK;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) gload((kt + 1) * BK);
+  auto compute = [&](int buf, floatx16 (&acc)[2][2]) {
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8 af[2], bfr[2];
@@ -123,13 +108,43 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
         for (int jn = 0; jn < 2; ++jn)
           acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[jn], af[i], acc[i][jn], 0, 0, 0);
     }
-    if (kt + 1 < nk) lstore(buf ^ 1);
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
+
+  // software pipeline over k-tiles, unrolled by 2 so that the register slots are static:
+  // tile t is in LDS buffer t&1, tile t+1 in register slot (t+1)&1, tile t+2 being loaded
+  const int nk = K / BK;
+  gload(0, 0);
+  if (nk > 1) gload(1, BK);
+  lstore(0, 0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt += 2) {
+    // even step: LDS buffer 0 holds tile kt; slot 1 holds kt+1; slot 0 is free -> load kt+2
+    if (kt + 2 < nk) gload(0, (kt + 2) * BK);
+    compute(0, acc);
+    if (kt + 1 < nk) lstore(1, 1);
+    __syncthreads();
+    if (kt + 1 >= nk) break;
+    // odd step: buffer 1 holds kt+1; slot 0 holds kt+2; slot 1 is free -> load kt+3
+    if (kt + 3 < nk) gload(1, (kt + 3) * BK);
+    compute(1, acc);
+    if (kt + 2 < nk) lstore(0, 0);
     __syncthreads();
   }
 
   // epilogue: bias, bf16, park the 64 x 64 block of this wave in LDS (its quarter of As/Bs is
   // free after the last barrier), then whole-row stores
   constexpr int ORS = 64 + 8;
+  float row_scale[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) row_scale[i] = a_scale[wm + i * 32 + l32];   // read before the tiles are reused
   __bf16* tile = (wv < 2 ? &As[0][0] : &Bs[0][0]) + (wv & 1) * 64 * ORS;   // 64 rows x 72 per wave
   static_assert(2 * 64 * ORS <= 2 * BM * RS, "output staging fits in the operand buffers");
 #pragma unroll
@@ -140,6 +155,7 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
       for (int g = 0; g < 4; ++g) {
         const int nloc = jn * 32 + 8 * g + 4 * hh;        // 4 consecutive output columns
         floatx4 f = {acc[i][jn][4 * g], acc[i][jn][4 * g + 1], acc[i][jn][4 * g + 2], acc[i][jn][4 * g + 3]};
+        if (kScale) f *= row_scale[i];
         if (bias != nullptr) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
@@ -212,7 +228,7 @@ extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const
   SPA_REQUIRE(aligned16(x) && aligned16(W) && aligned16(out), SPA_ERR_INVALID_ARG, "%s: x / W / out not 16-byte aligned", fn);
   const int m_tiles = (M_cap + kGemmBM - 1) / kGemmBM, n_tiles = (N_out + kGemmBN - 1) / kGemmBN;
   SPA_REQUIRE((long)m_tiles * n_tiles + 8 < 2147483647L / 2, SPA_ERR_INVALID_ARG, "%s: too many tiles", fn);
-  const unsigned grid = (unsigned)(((long)m_tiles * n_tiles + 7) / 8 * 8);
+  const unsigned grid = (unsigned)((long)((m_tiles + 7) / 8) * 8 * n_tiles);
 #define SPA_LIN_BF16(G_, S_)                                                                                  \
   hipLaunchKernelGGL((linear_bf16_kernel<G_, S_>), dim3(grid), dim3(kGemmThreads), 0, st, (const __bf16*)x,  \
                      gather_idx, gate_scores, total, (const __bf16*)W, (const __bf16*)bias, M_cap, K, N_out, \
