@@ -304,6 +304,30 @@ def main():
                              "stage_us": {k_: round(v_, 2) for k_, v_ in tus.items()},
                              "attention_bwd_tflops": round(bwd_flops / tus["packed_attention_bwd"] / 1e6, 2)}
 
+        # the block with its projections: only selected tokens are projected
+        from paper_2410_23608_amd.pipeline import BlockPass
+        g = torch.Generator(device="cpu").manual_seed(args.seed + 17)
+        mkw = lambda r, c: (torch.randn(r, c, generator=g) / c ** 0.5).cuda().to(td)
+        W_qkv, b_qkv, W_o, b_o = mkw(3 * C, C), mkw(1, 3 * C).view(-1), mkw(C, C), mkw(1, C).view(-1)
+        bp = BlockPass(B, N, C, H, wl.dtype, wl.tau, wl.bias)
+        bstages = bp.stages(x, w, W_qkv, b_qkv, W_o, b_o)
+
+        def bstep():
+            for _, fn in bstages:
+                fn()
+
+        for _ in range(5):
+            bstep()
+        torch.cuda.synchronize()
+        bdt = timed(bstep, args.steps, torch)
+        bus = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in bstages}
+        result["block_with_projections"] = {
+            "launches": [n_ for n_, _ in bstages], "value": T * args.steps / bdt, "unit": "selected tokens/s",
+            "ms_per_step": 1e3 * bdt / args.steps, "stage_us": {k_: round(v_, 2) for k_, v_ in bus.items()},
+            "qkv_projection_tflops": round(2.0 * T * C * 3 * C / bus["qkv_projection"] / 1e6, 1),
+            "out_projection_tflops": round(2.0 * T * C * C / bus["out_projection"] / 1e6, 1),
+            "dense_projection_flops_saved": round(1.0 - T / (B * N), 3)}
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_oracle_baseline(wl, bun, args.cpu_seconds)
         result["cpu_baseline"]["gpu_over_cpu"] = round(value / result["cpu_baseline"]["value"], 1)

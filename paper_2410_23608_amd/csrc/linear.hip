@@ -20,21 +20,28 @@
 
 namespace spa {
 
-constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 32, kGemmThreads = 256;
-constexpr int kGemmRS = kGemmBK + 8;   // LDS row stride (elements)
+constexpr int kGemmBN = 128, kGemmThreads = 256;
 
-template <bool kGather, bool kScale>
+// Workgroup tile (64 TM) x 128, four waves as 2 x 2, each wave (32 TM) x 64 of the output held
+// as TM x 2 MFMA tiles.  TM = 2: 128 x 128 tiles (more workgroups for small problems);
+// TM = 4: 256 x 128 tiles (a third less operand traffic per flop).
+template <bool kGather, bool kScale, int BK, int TM>
 __global__ void __launch_bounds__(kGemmThreads)
 linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gather_idx,
                    const float* __restrict__ gate_scores, const int32_t* __restrict__ total,
                    const __bf16* __restrict__ W, const __bf16* __restrict__ bias, int m_cap, int K, int n_out,
                    __bf16* __restrict__ out, long out_stride, int m_tiles, int n_tiles) {
-  constexpr int BM = kGemmBM, BN = kGemmBN, BK = kGemmBK, RS = kGemmRS;
-  __shared__ __attribute__((aligned(16))) __bf16 As[2][BM * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Bs[2][BN * RS];
+  constexpr int BM = 64 * TM, BN = kGemmBN, RS = BK + 8;   // RS = LDS row stride (elements)
+  extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];   // 2 x (A tile, B tile)
+  __bf16(*As)[BM * RS] = reinterpret_cast<__bf16(*)[BM * RS]>(gemm_smem);
+  __bf16(*Bs)[BN * RS] = reinterpret_cast<__bf16(*)[BN * RS]>(gemm_smem + 2 * BM * RS * sizeof(__bf16));
   __shared__ long a_row[BM];       // source row of every tile row (-1 = past the end)
   __shared__ float a_scale[BM];
+  __shared__ float bias_s[BN];     // bias of the tile's output columns (0 past n_out or without bias)
 
+  // m-tiles are dealt round-robin to the XCDs (workgroup id % 8), n fastest within an XCD: the
+  // workgroups that share a block of A rows run on one XCD and find it in that XCD's L2, and
+  // the dead m-tiles past *total spread evenly over the XCDs.
   const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
   const int mg = j / n_tiles, nt = j - mg * n_tiles;
   const int mt = mg * 8 + xcd;
@@ -44,58 +51,74 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
   if (m0 >= M) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
-  const int wm = (wv >> 1) * 64, wn = (wv & 1) * 64;
+  const int wm = (wv >> 1) * 32 * TM, wn = (wv & 1) * 64;
 
-  if (tid < BM) {
-    const int r = m0 + tid;
+  for (int t = tid; t < BM; t += kGemmThreads) {
+    const int r = m0 + t;
     long src = -1;
     float sc = 1.f;
     if (r < M) {
       src = kGather ? (long)gather_idx[r] : (long)r;
       if (kScale) sc = sigmoidf_dev(gate_scores[src]);
     }
-    a_row[tid] = src;
-    a_scale[tid] = sc;
+    a_row[t] = src;
+    a_scale[t] = sc;
   }
+  if (tid < BN) bias_s[tid] = bias != nullptr && n0 + tid < n_out ? static_cast<float>(bias[n0 + tid]) : 0.f;
   __syncthreads();
 
-  // staging: a tile is 128 rows x BK/8 chunks of 16 bytes, CPT chunks per thread.  The rows
-  // and chunk columns a thread stages never change, so their addresses are computed once.
-  constexpr int CPRW = BK / 8, CPT = BM * CPRW / kGemmThreads;
-  const __bf16* ap[CPT];
-  const __bf16* bp[CPT];
-  int lds_off[CPT];
+  // staging: a tile is rows x BK/8 chunks of 16 bytes.  The rows and chunk columns a thread
+  // stages never change, so their addresses are computed once.
+  // Rows past the end of the tile's valid range load a valid row instead of zeros: a row of A
+  // only reaches its own output row and a row of W its own output column, and the epilogue
+  // stores neither.
+  constexpr int CPRW = BK / 8, CA = BM * CPRW / kGemmThreads, CB = BN * CPRW / kGemmThreads;
+  const __bf16* ap[CA];
+  const __bf16* bp[CB];
+  const int st_r = tid / CPRW, st_c = tid % CPRW;           // chunk u of a thread: row st_r + u * (256 / CPRW)
+  constexpr int RSTEP = kGemmThreads / CPRW;
+  const int lds_off = st_r * RS + st_c * 8;
 #pragma unroll
-  for (int t = 0; t < CPT; ++t) {
-    const int i = tid + t * kGemmThreads, r = i / CPRW, c = i % CPRW;
-    const long src = a_row[r];
-    ap[t] = src >= 0 ? x + src * K + c * 8 : nullptr;
-    bp[t] = n0 + r < n_out ? W + (long)(n0 + r) * K + c * 8 : nullptr;
-    lds_off[t] = r * RS + c * 8;
+  for (int u = 0; u < CA; ++u) {
+    const long src = a_row[st_r + u * RSTEP];
+    ap[u] = x + (src >= 0 ? src : 0) * K + st_c * 8;
   }
-  // two tiles in flight in registers (PF = prefetch distance in k-tiles)
-  constexpr int PF = 2;
-  bf16x8 areg[PF][CPT], breg[PF][CPT];
-  auto gload = [&](int slot, int k0) {
 #pragma unroll
-    for (int t = 0; t < CPT; ++t) {
-      areg[slot][t] = ap[t] != nullptr ? *reinterpret_cast<const bf16x8*>(ap[t] + k0) : zero_bf16x8();
-      breg[slot][t] = bp[t] != nullptr ? *reinterpret_cast<const bf16x8*>(bp[t] + k0) : zero_bf16x8();
-    }
+  for (int u = 0; u < CB; ++u) bp[u] = W + (long)min(n0 + st_r + u * RSTEP, n_out - 1) * K + st_c * 8;
+
+  // Two k-tiles in flight in registers.  When K is not a multiple of BK the PARTIAL k-tile comes
+  // first (k in [0, K % BK)), so that only the prologue needs masked loads and every tile the
+  // main loop touches is whole: tile t >= 1 starts at k = k_first + t * BK.
+  constexpr int PF = 2;
+  bf16x8 areg[PF][CA], breg[PF][CB];
+  const int k_tail = K % BK, nk = (K + BK - 1) / BK, k_first = k_tail ? k_tail - BK : 0;
+  auto gload = [&](int slot, int t) {   // whole tile t (t >= 1 when K % BK != 0)
+    const int k0 = k_first + t * BK;
+#pragma unroll
+    for (int u = 0; u < CA; ++u) areg[slot][u] = *reinterpret_cast<const bf16x8*>(ap[u] + k0);
+#pragma unroll
+    for (int u = 0; u < CB; ++u) breg[slot][u] = *reinterpret_cast<const bf16x8*>(bp[u] + k0);
+  };
+  auto gload_first = [&](int slot) {
+    if (k_tail == 0) { gload(slot, 0); return; }
+    const bool in_k = st_c * 8 < k_tail;   // columns past the partial tile are zero in both operands
+#pragma unroll
+    for (int u = 0; u < CA; ++u) areg[slot][u] = in_k ? *reinterpret_cast<const bf16x8*>(ap[u]) : zero_bf16x8();
+#pragma unroll
+    for (int u = 0; u < CB; ++u) breg[slot][u] = in_k ? *reinterpret_cast<const bf16x8*>(bp[u]) : zero_bf16x8();
   };
   auto lstore = [&](int slot, int buf) {
 #pragma unroll
-    for (int t = 0; t < CPT; ++t) {
-      *reinterpret_cast<bf16x8*>(&As[buf][lds_off[t]]) = areg[slot][t];
-      *reinterpret_cast<bf16x8*>(&Bs[buf][lds_off[t]]) = breg[slot][t];
-    }
+    for (int u = 0; u < CA; ++u) *reinterpret_cast<bf16x8*>(&As[buf][lds_off + u * RSTEP * RS]) = areg[slot][u];
+#pragma unroll
+    for (int u = 0; u < CB; ++u) *reinterpret_cast<bf16x8*>(&Bs[buf][lds_off + u * RSTEP * RS]) = breg[slot][u];
   };
-  auto compute = [&](int buf, floatx16 (&acc)[2][2]) {
+  auto compute = [&](int buf, floatx16 (&acc)[TM][2]) {
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[2], bfr[2];
+      bf16x8 af[TM], bfr[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TM; ++i)
         af[i] = *reinterpret_cast<const bf16x8*>(&As[buf][(wm + i * 32 + l32) * RS + kk * 16 + hh * 8]);
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn)
@@ -103,75 +126,77 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
       // C^T tile: rows = output columns n, cols = tokens m, so that a lane's 4 consecutive
       // accumulator registers are 4 consecutive n of one token (8-byte output pieces)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn)
           acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[jn], af[i], acc[i][jn], 0, 0, 0);
     }
   };
 
-  floatx16 acc[2][2];
+  floatx16 acc[TM][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][jn][r] = 0.f;
 
-  // software pipeline over k-tiles, unrolled by 2 so that the register slots are static:
-  // tile t is in LDS buffer t&1, tile t+1 in register slot (t+1)&1, tile t+2 being loaded
-  const int nk = K / BK;
-  gload(0, 0);
-  if (nk > 1) gload(1, BK);
+  // Software pipeline over k-tiles, two per trip so that register slots and LDS buffers are
+  // static.  Entering a trip: LDS buffer 0 holds tile kt, slot 1 holds tile kt+1, slot 0 is free.
+  // Loads past the last tile repeat the last tile and what they bring is never multiplied, which
+  // keeps the loop body free of branches (the compiler then counts outstanding loads exactly).
+  const int last = nk - 1;
+  gload_first(0);
+  if (nk > 1) gload(1, 1);
   lstore(0, 0);
   __syncthreads();
-  for (int kt = 0; kt < nk; kt += 2) {
-    // even step: LDS buffer 0 holds tile kt; slot 1 holds kt+1; slot 0 is free -> load kt+2
-    if (kt + 2 < nk) gload(0, (kt + 2) * BK);
+  for (int kt = 0; kt + 1 < nk; kt += 2) {
+    gload(0, min(kt + 2, last));
     compute(0, acc);
-    if (kt + 1 < nk) lstore(1, 1);
+    lstore(1, 1);        // tile kt+1
     __syncthreads();
-    if (kt + 1 >= nk) break;
-    // odd step: buffer 1 holds kt+1; slot 0 holds kt+2; slot 1 is free -> load kt+3
-    if (kt + 3 < nk) gload(1, (kt + 3) * BK);
+    gload(1, min(kt + 3, last));
     compute(1, acc);
-    if (kt + 2 < nk) lstore(0, 0);
+    lstore(0, 0);        // tile kt+2, or a repeat of the last tile
     __syncthreads();
   }
+  if (nk & 1) {
+    compute(0, acc);
+    __syncthreads();     // the epilogue reuses the operand buffers
+  }
 
-  // epilogue: bias, bf16, park the 64 x 64 block of this wave in LDS (its quarter of As/Bs is
-  // free after the last barrier), then whole-row stores
+  // epilogue: scale, bias, bf16; 64 rows x 64 columns of the wave at a time are parked in LDS
+  // (the operand buffers are free after the last barrier) and leave as whole 16-byte pieces
   constexpr int ORS = 64 + 8;
-  float row_scale[2];
+  static_assert(4 * 64 * ORS <= 2 * (BM + BN) * RS, "output staging fits in the operand buffers");
+  __bf16* tile = reinterpret_cast<__bf16*>(gemm_smem) + wv * 64 * ORS;   // 64 rows x 72 per wave
+  float row_scale[TM];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) row_scale[i] = a_scale[wm + i * 32 + l32];   // read before the tiles are reused
-  __bf16* tile = (wv < 2 ? &As[0][0] : &Bs[0][0]) + (wv & 1) * 64 * ORS;   // 64 rows x 72 per wave
-  static_assert(2 * 64 * ORS <= 2 * BM * RS, "output staging fits in the operand buffers");
+  for (int i = 0; i < TM; ++i) row_scale[i] = a_scale[wm + i * 32 + l32];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int half = 0; half < TM / 2; ++half) {
 #pragma unroll
-    for (int jn = 0; jn < 2; ++jn)
+    for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int nloc = jn * 32 + 8 * g + 4 * hh;        // 4 consecutive output columns
-        floatx4 f = {acc[i][jn][4 * g], acc[i][jn][4 * g + 1], acc[i][jn][4 * g + 2], acc[i][jn][4 * g + 3]};
-        if (kScale) f *= row_scale[i];
-        if (bias != nullptr) {
+      for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int n = n0 + wn + nloc + e;
-            if (n < n_out) f[e] += static_cast<float>(bias[n]);
-          }
+        for (int g = 0; g < 4; ++g) {
+          const int i = half * 2 + ii;
+          const int nloc = jn * 32 + 8 * g + 4 * hh;        // 4 consecutive output columns
+          floatx4 f = {acc[i][jn][4 * g], acc[i][jn][4 * g + 1], acc[i][jn][4 * g + 2], acc[i][jn][4 * g + 3]};
+          if (kScale) f *= row_scale[i];
+          f += *reinterpret_cast<const floatx4*>(&bias_s[wn + nloc]);
+          *reinterpret_cast<bf16x4*>(&tile[(ii * 32 + l32) * ORS + nloc]) = __builtin_convertvector(f, bf16x4);
         }
-        *reinterpret_cast<bf16x4*>(&tile[(i * 32 + l32) * ORS + nloc]) = __builtin_convertvector(f, bf16x4);
-      }
-  __syncthreads();
-  // 64 rows x 8 chunks per wave
-  for (int i = lane; i < 64 * 8; i += 64) {
-    const int r = i >> 3, c = i & 7;
-    const int m = m0 + wm + r, n = n0 + wn + c * 8;
-    if (m < M && n < n_out)
-      *reinterpret_cast<bf16x8*>(out + (long)m * out_stride + n) = *reinterpret_cast<const bf16x8*>(&tile[r * ORS + c * 8]);
+    __syncthreads();
+    // 64 rows x 8 chunks per wave
+    for (int i = lane; i < 64 * 8; i += 64) {
+      const int r = i >> 3, c = i & 7;
+      const int m = m0 + wm + half * 64 + r, n = n0 + wn + c * 8;
+      if (m < M && n < n_out)
+        *reinterpret_cast<bf16x8*>(out + (long)m * out_stride + n) = *reinterpret_cast<const bf16x8*>(&tile[r * ORS + c * 8]);
+    }
+    __syncthreads();
   }
 }
 
@@ -222,18 +247,35 @@ extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const
 #undef SPA_LIN_F32
     return check_launch(fn);
   }
-  SPA_REQUIRE(K % kGemmBK == 0, SPA_ERR_UNSUPPORTED, "%s: K = %d must be a multiple of %d for bf16", fn, K, kGemmBK);
+  SPA_REQUIRE(K % 8 == 0, SPA_ERR_UNSUPPORTED, "%s: K = %d must be a multiple of 8 for bf16", fn, K);
   SPA_REQUIRE(N_out % 8 == 0 && out_row_stride % 8 == 0, SPA_ERR_INVALID_ARG,
               "%s: N_out and out_row_stride must be multiples of 8 for bf16", fn);
   SPA_REQUIRE(aligned16(x) && aligned16(W) && aligned16(out), SPA_ERR_INVALID_ARG, "%s: x / W / out not 16-byte aligned", fn);
-  const int m_tiles = (M_cap + kGemmBM - 1) / kGemmBM, n_tiles = (N_out + kGemmBN - 1) / kGemmBN;
+  // tile shape: 128 x 128 (BK 64) measured faster than 256 x 128 (BK 32) on every projection
+  // shape of the workloads; SPA_GEMM_TM=4 selects the larger tile for experiments
+  static const int cfg_env = [] { const char* e = getenv("SPA_GEMM_TM"); return e ? atoi(e) : 0; }();
+  const int tm = cfg_env == 4 ? 4 : 2;
+  const int bm = 64 * tm;
+  const int m_tiles = (M_cap + bm - 1) / bm, n_tiles = (N_out + kGemmBN - 1) / kGemmBN;
   SPA_REQUIRE((long)m_tiles * n_tiles + 8 < 2147483647L / 2, SPA_ERR_INVALID_ARG, "%s: too many tiles", fn);
   const unsigned grid = (unsigned)((long)((m_tiles + 7) / 8) * 8 * n_tiles);
-#define SPA_LIN_BF16(G_, S_)                                                                                  \
-  hipLaunchKernelGGL((linear_bf16_kernel<G_, S_>), dim3(grid), dim3(kGemmThreads), 0, st, (const __bf16*)x,  \
-                     gather_idx, gate_scores, total, (const __bf16*)W, (const __bf16*)bias, M_cap, K, N_out, \
-                     (__bf16*)out, (long)out_row_stride, m_tiles, n_tiles)
-  if (g && sc) SPA_LIN_BF16(true, true); else if (g) SPA_LIN_BF16(true, false); else SPA_LIN_BF16(false, false);
+#define SPA_LIN_BF16(G_, S_, BK_, TM_)                                                                        \
+  do {                                                                                                        \
+    constexpr size_t smem = (size_t)2 * (64 * TM_ + kGemmBN) * (BK_ + 8) * sizeof(__bf16);                     \
+    const hipError_t attr = hipFuncSetAttribute((const void*)linear_bf16_kernel<G_, S_, BK_, TM_>,            \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);       \
+    SPA_REQUIRE(attr == hipSuccess, SPA_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, smem);            \
+    hipLaunchKernelGGL((linear_bf16_kernel<G_, S_, BK_, TM_>), dim3(grid), dim3(kGemmThreads), smem, st,      \
+                       (const __bf16*)x, gather_idx, gate_scores, total, (const __bf16*)W, (const __bf16*)bias, \
+                       M_cap, K, N_out, (__bf16*)out, (long)out_row_stride, m_tiles, n_tiles);                \
+  } while (0)
+#define SPA_LIN_BF16_CFG(BK_, TM_)                                                                            \
+  do {                                                                                                        \
+    if (g && sc) SPA_LIN_BF16(true, true, BK_, TM_); else if (g) SPA_LIN_BF16(true, false, BK_, TM_);         \
+    else SPA_LIN_BF16(false, false, BK_, TM_);                                                                \
+  } while (0)
+  if (tm == 4) SPA_LIN_BF16_CFG(32, 4); else SPA_LIN_BF16_CFG(64, 2);
+#undef SPA_LIN_BF16_CFG
 #undef SPA_LIN_BF16
   return check_launch(fn);
 }

@@ -144,3 +144,51 @@ class TrainPass:
         for _, fn in self.stages(x, w, qk, labels, dy):
             fn()
         return self.loss
+
+
+class BlockPass:
+    """One SPA attention block with its projections (Section 3.2), six launches:
+
+      gate_select(x) -> pack (indices only) -> QKV projection of the selected, gated tokens
+      (gather and Sigmoid(s) scaling folded into the GEMM's operand load) -> packed attention
+      -> output projection on the packed rows -> scatter back as a residual on x (unselected tokens keep x unchanged).
+
+    Only selected tokens are ever projected, which is where the method saves its FLOPs."""
+
+    def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0):
+        self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
+        self.tau, self.bias = tau, bias
+        td, cap = _td(dtype), B * N
+        dv = dict(device="cuda")
+        self.scores = torch.empty(B, N, dtype=torch.float32, **dv)
+        self.mask = torch.empty(B, N, dtype=torch.uint8, **dv)
+        self.cu_seqlens = torch.zeros(B + 1, dtype=torch.int32, **dv)
+        self.gather_idx = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.inv_pos = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.total = torch.zeros(1, dtype=torch.int32, **dv)
+        self.packed_qkv = torch.zeros(cap, 3 * C, dtype=td, **dv)
+        self.attn = torch.zeros(cap, C, dtype=td, **dv)
+        self.proj = torch.zeros(cap, C, dtype=td, **dv)
+        self.y = torch.empty(B, N, C, dtype=td, **dv)
+
+    def stages(self, x, w, W_qkv, b_qkv, W_o, b_o) -> List[Tuple[str, Callable[[], None]]]:
+        C, p = self.C, self.packed_qkv
+        return [
+            ("gate_select", spa.spa_gate_select(x, w, self.bias, None, self.tau, self.scores, self.mask, None,
+                                                prepare=True)),
+            ("pack_indices", spa.spa_pack(None, self.mask, None, None, 0, None, self.cu_seqlens, self.gather_idx,
+                                          self.inv_pos, self.total, prepare=True)),
+            ("qkv_projection", spa.spa_linear_packed(x, self.gather_idx, self.scores, self.total, W_qkv, b_qkv, p,
+                                                     prepare=True)),
+            ("packed_attention", spa.spa_packed_attention(p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.cu_seqlens,
+                                                          self.B, self.N, self.H, self.Dh, self.attn, None,
+                                                          prepare=True)),
+            ("out_projection", spa.spa_linear_packed(self.attn, None, None, self.total, W_o, b_o, self.proj,
+                                                     prepare=True)),
+            ("unpack", spa.spa_unpack(self.proj, self.inv_pos, x, self.y, prepare=True)),
+        ]
+
+    def run(self, x, w, W_qkv, b_qkv, W_o, b_o):
+        for _, fn in self.stages(x, w, W_qkv, b_qkv, W_o, b_o):
+            fn()
+        return self.y

@@ -25,7 +25,8 @@ def _rel(got, ref):
 
 
 @pytest.mark.parametrize("dtype,B,N,K,No", [("bf16", 3, 100, 64, 96), ("bf16", 8, 196, 384, 1152),
-                                            ("bf16", 2, 777, 96, 288), ("bf16", 4, 129, 32, 8), ("f32", 2, 60, 64, 192)])
+                                            ("bf16", 2, 777, 96, 288), ("bf16", 4, 129, 32, 8), ("bf16", 2, 150, 200, 64), ("bf16", 40, 196, 96, 1280),
+                                            ("f32", 2, 60, 64, 192)])
 @pytest.mark.parametrize("mode", ["plain", "gather", "gather_scale_bias"])
 def test_linear_packed_matches_oracle(spa, dtype, B, N, K, No, mode):
     rng = np.random.default_rng(41)
@@ -99,3 +100,33 @@ def test_spa_block_with_projection(spa):
     assert _rel(host(pqkv)[:T], qkv_packed) <= 1e-2
     # the device attention runs on its own (slightly different) bf16 projections
     assert np.max(np.abs(host(y) - y_ref)) <= 4e-2
+
+
+def test_block_pass_with_both_projections(spa):
+    """BlockPass (six launches: gate, indices, QKV projection, attention, output projection,
+    scatter with x as the bypass) against the oracle's composition of the same steps."""
+    from paper_2410_23608_amd.pipeline import BlockPass
+    wl = dataclasses.replace(wlmod.WORKLOADS["vit_s"], B=5)
+    B, N, C, H = wl.B, wl.N, wl.C, wl.H
+    bun = wlmod.generate(wl, 21, with_qkv=False)
+    rng = np.random.default_rng(21)
+    mkw = lambda *shape: wlmod.round_bf16((rng.standard_normal(shape) / np.sqrt(C)).astype(np.float32))
+    Wqkv, bqkv, Wo, bo = mkw(3 * C, C), mkw(3 * C), mkw(C, C), mkw(C)
+    x, w, bias = bun["x"], bun["w"], bun["bias"]
+    s = orc.gate_scores(x, w, bias)
+    mask, margin = orc.select(s, wl.tau)
+    assert margin > 1e-3
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    qkv_packed = orc.round_to_dtype(orc.linear_packed(x, gidx, Wqkv, bqkv, s.astype(np.float32), "bf16"), "bf16")
+    qkv_full = orc.unpack(qkv_packed, inv, B, N)
+    attn_ref, _ = orc.attention_per_image(qkv_full[..., :C], qkv_full[..., C:2 * C], qkv_full[..., 2 * C:], mask, H)
+    attn_ref = orc.round_to_dtype(attn_ref, "bf16")                       # packed rows, [T, C]
+    proj_ref = orc.linear_packed(attn_ref, np.arange(T), Wo, bo, None, "bf16")
+    y_ref = orc.unpack(proj_ref, inv, B, N, base=x)
+    bp = BlockPass(B, N, C, H, "bf16", wl.tau, bias)
+    y = bp.run(dev(x, "bf16"), dev(w, "bf16"), dev(Wqkv, "bf16"), dev(bqkv, "bf16"), dev(Wo, "bf16"), dev(bo, "bf16"))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(bp.mask), mask) and int(bp.total.item()) == T
+    got = host(y)
+    assert np.array_equal(got[mask == 0], x[mask == 0])                   # bypassing tokens are x, bit for bit
+    assert np.max(np.abs(got - y_ref)) <= 5e-2
