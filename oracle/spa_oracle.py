@@ -113,11 +113,26 @@ def sigmoid(s: np.ndarray) -> np.ndarray:
 
 
 # ---------------------------------------------------------------------------- pack
-def pack_indices(mask: np.ndarray):
+def shift_order(grid_h: int, grid_w: int, shift_h: int, shift_w: int) -> np.ndarray:
+    """Cyclic shift of the feature map (Section 1, the paragraph on shifting the feature maps
+    every two blocks; the amount and direction follow the window shift of the Swin design the
+    paper builds on): the shifted map holds at (r', c') the token that sits at
+    ((r' + shift_h) mod grid_h, (c' + shift_w) mod grid_w) in the original map.
+    Returns order [N] i32: order[p'] = original position of the p'-th token of the shifted map
+    in raster order."""
+    order = np.zeros(grid_h * grid_w, dtype=np.int32)
+    for r in range(grid_h):
+        for c in range(grid_w):
+            order[r * grid_w + c] = ((r + shift_h) % grid_h) * grid_w + (c + shift_w) % grid_w
+    return order
+
+
+def pack_indices(mask: np.ndarray, order: Optional[np.ndarray] = None):
     """Token Packing (Section 3.2): walk images in batch order and tokens in ascending
-    position, appending survivors.  Returns
+    position (of the shifted map when `order` is given, see shift_order), appending
+    survivors.  Returns
       cu_seqlens [B+1] i32 (segment of image b is [cu[b], cu[b+1])),
-      gather_idx [T] i32  (flat token id b*N+n of the j-th packed row),
+      gather_idx [T] i32  (flat token id b*N+n, in the ORIGINAL layout, of the j-th packed row),
       inv_pos [B*N] i32   (packed row of a token, -1 if not selected),
       total T."""
     mask = np.asarray(mask)
@@ -126,12 +141,28 @@ def pack_indices(mask: np.ndarray):
     gather = []
     inv = np.full(B * N, -1, dtype=np.int32)
     for b in range(B):
-        for n in range(N):
+        for p in range(N):
+            n = p if order is None else int(order[p])
             if mask[b, n]:
                 inv[b * N + n] = len(gather)
                 gather.append(b * N + n)
         cu[b + 1] = len(gather)
     return cu, np.asarray(gather, dtype=np.int32), inv, len(gather)
+
+
+def container_segments(cu_seqlens: np.ndarray, container_len: int) -> np.ndarray:
+    """Boundaries of the attention segments when the packed stream is cut into containers of
+    length L (Section 3.2 "Token Packing" and the 2 L^2 C term of the complexity formula): a
+    token attends to the tokens of its own image inside its own container, so a segment ends
+    wherever an image ends or a container ends.  Returns the sorted distinct boundaries
+    [S+1] i32, from 0 to T."""
+    cu = np.asarray(cu_seqlens).astype(np.int64)
+    T = int(cu[-1])
+    cuts = set(int(c) for c in cu)
+    cuts.update(range(0, T, container_len))
+    cuts.add(T)
+    cuts.add(0)
+    return np.asarray(sorted(cuts), dtype=np.int32)
 
 
 def packed_rows(total: int, container_len: int) -> int:
@@ -215,6 +246,70 @@ def attention_per_image(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.nd
             lse[h, row0:row0 + n] = (m + np.log(Z))[:, 0]
         row0 += n
     return out, lse
+
+
+def attention_container_local(qp: np.ndarray, kp: np.ndarray, vp: np.ndarray, cu_seqlens: np.ndarray,
+                              container_len: int, H: int, scale: Optional[float] = None):
+    """Attention over the packed stream [T, C] with the paper's full mask written out
+    (Section 3.2: containers of length L, tokens attend only to tokens of the same image
+    inside their container): row i may attend to row j iff both lie in the same image
+    segment of cu_seqlens and floor(i / L) == floor(j / L).  The T x T score matrix is
+    formed whole, disallowed entries are set to -inf, and softmax(S) V is evaluated.
+    Returns out [T, C] and lse [H, T]."""
+    qp, kp, vp = (np.asarray(a, dtype=F64) for a in (qp, kp, vp))
+    T, C = qp.shape
+    Dh = C // H
+    if scale is None:
+        scale = 1.0 / math.sqrt(Dh)
+    cu = np.asarray(cu_seqlens)
+    image = np.zeros(T, dtype=np.int64)
+    for b in range(len(cu) - 1):
+        image[cu[b]:cu[b + 1]] = b
+    container = np.arange(T) // container_len
+    allowed = (image[:, None] == image[None, :]) & (container[:, None] == container[None, :])
+    out = np.zeros((T, C), dtype=F64)
+    lse = np.zeros((H, T), dtype=F64)
+    for h in range(H):
+        Q, K, V = (a[:, h * Dh:(h + 1) * Dh] for a in (qp, kp, vp))
+        S = np.where(allowed, (Q @ K.T) * scale, -np.inf)
+        m = S.max(axis=1, keepdims=True)
+        E = np.exp(S - m)
+        Z = E.sum(axis=1, keepdims=True)
+        out[:, h * Dh:(h + 1) * Dh] = (E / Z) @ V
+        lse[h] = (m + np.log(Z))[:, 0]
+    return out, lse
+
+
+def attention_container_local_backward(qp, kp, vp, cu_seqlens, container_len: int, dout: np.ndarray, H: int,
+                                       scale: Optional[float] = None):
+    """Gradient of attention_container_local with respect to qp, kp, vp: the textbook
+    softmax-attention calculus on the whole T x T matrices with the same mask
+    (P = 0 where disallowed): dV = P^T dO, dP = dO V^T, dS = P * (dP - rowsum(P * dP)),
+    dQ = dS K * scale, dK = dS^T Q * scale."""
+    qp, kp, vp, dout = (np.asarray(a, dtype=F64) for a in (qp, kp, vp, dout))
+    T, C = qp.shape
+    Dh = C // H
+    if scale is None:
+        scale = 1.0 / math.sqrt(Dh)
+    cu = np.asarray(cu_seqlens)
+    image = np.zeros(T, dtype=np.int64)
+    for b in range(len(cu) - 1):
+        image[cu[b]:cu[b + 1]] = b
+    container = np.arange(T) // container_len
+    allowed = (image[:, None] == image[None, :]) & (container[:, None] == container[None, :])
+    dq, dk, dv = np.zeros_like(qp), np.zeros_like(kp), np.zeros_like(vp)
+    for h in range(H):
+        sl = slice(h * Dh, (h + 1) * Dh)
+        Q, K, V, dO = qp[:, sl], kp[:, sl], vp[:, sl], dout[:, sl]
+        S = np.where(allowed, (Q @ K.T) * scale, -np.inf)
+        E = np.exp(S - S.max(axis=1, keepdims=True))
+        P = E / E.sum(axis=1, keepdims=True)
+        dv[:, sl] = P.T @ dO
+        dP = dO @ V.T
+        dS = P * (dP - (P * dP).sum(axis=1, keepdims=True))
+        dq[:, sl] = dS @ K * scale
+        dk[:, sl] = dS.T @ Q * scale
+    return dq, dk, dv
 
 
 def attention_backward_per_image(q, k, v, mask, dout_packed, H: int,

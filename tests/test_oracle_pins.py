@@ -430,3 +430,152 @@ def test_linear_packed_matches_library_and_bruteforce():
             assert abs(y0[j, n] - acc) < 1e-13
     # identity weights return the packed rows themselves
     np.testing.assert_array_equal(orc.linear_packed(x, gidx, np.eye(K)), x.reshape(-1, K)[gidx])
+
+
+# ------------------------------------------------ cyclic shift and container-local attention
+def test_shift_order_is_a_roll_of_the_index_grid():
+    """The shifted map's raster order equals numpy's roll of the position grid by (-sh, -sw)
+    (the torch.roll convention of the Swin window shift), and zero shift is the identity."""
+    for (gh, gw, sh, sw) in [(3, 4, 1, 1), (7, 7, 3, 3), (5, 9, 0, 4), (6, 2, 5, 1), (4, 4, 0, 0)]:
+        grid = np.arange(gh * gw).reshape(gh, gw)
+        ref = np.roll(grid, shift=(-sh, -sw), axis=(0, 1)).ravel()
+        assert np.array_equal(orc.shift_order(gh, gw, sh, sw), ref)
+    assert np.array_equal(orc.shift_order(4, 5, 0, 0), np.arange(20))
+    # a shift by the full extent is the identity again
+    assert np.array_equal(orc.shift_order(4, 5, 4, 5), np.arange(20))
+
+
+def test_shifted_pack_indices_invariants():
+    rng = np.random.default_rng(3)
+    gh, gw, B = 6, 5, 4
+    mask = (rng.random((B, gh * gw)) < 0.4).astype(np.uint8)
+    order = orc.shift_order(gh, gw, 2, 3)
+    cu, gidx, inv, T = orc.pack_indices(mask, order)
+    cu0, gidx0, inv0, T0 = orc.pack_indices(mask)
+    assert T == T0 and np.array_equal(cu, cu0)                    # a shift moves nothing between images
+    assert sorted(gidx.tolist()) == sorted(gidx0.tolist())        # same tokens, other order
+    assert np.array_equal(inv[gidx], np.arange(T))
+    # inside an image the packed order is the order of the rolled map
+    rank_in_rolled = np.empty(gh * gw, dtype=np.int64)
+    rank_in_rolled[order] = np.arange(gh * gw)
+    for b in range(B):
+        seg = gidx[cu[b]:cu[b + 1]] - b * gh * gw
+        assert np.all(np.diff(rank_in_rolled[seg]) > 0)
+    # rolling the mask itself and packing without an order selects the same tokens in the same sequence
+    rolled = np.stack([np.roll(m.reshape(gh, gw), shift=(-2, -3), axis=(0, 1)).ravel() for m in mask])
+    _, g_rolled, _, _ = orc.pack_indices(rolled)
+    for b in range(B):
+        pos_rolled = g_rolled[cu[b]:cu[b + 1]] - b * gh * gw
+        assert np.array_equal(order[pos_rolled], gidx[cu[b]:cu[b + 1]] - b * gh * gw)
+
+
+def test_container_segments_examples_and_invariants():
+    # worked example: images of 5, 0, 7 and 8 tokens, containers of 7
+    assert orc.container_segments(np.array([0, 5, 5, 12, 20]), 7).tolist() == [0, 5, 7, 12, 14, 20]
+    # containers at least as long as the stream change nothing but drop empty images
+    assert orc.container_segments(np.array([0, 3, 3, 9]), 100).tolist() == [0, 3, 9]
+    # L = 1: every token is its own segment
+    assert orc.container_segments(np.array([0, 2, 4]), 1).tolist() == [0, 1, 2, 3, 4]
+    rng = np.random.default_rng(0)
+    for _ in range(20):
+        lens = rng.integers(0, 30, size=6)
+        cu = np.concatenate([[0], np.cumsum(lens)])
+        L = int(rng.integers(1, 12))
+        seg = orc.container_segments(cu, L)
+        assert seg[0] == 0 and seg[-1] == cu[-1] and np.all(np.diff(seg) > 0) if cu[-1] > 0 else True
+        for a, b in zip(seg[:-1], seg[1:]):
+            assert b - a <= L and a // L == (b - 1) // L                                   # inside one container
+            assert np.searchsorted(cu, a, side="right") == np.searchsorted(cu, b - 1, side="right")  # one image
+
+
+def _packed_qkv(rng, T, C):
+    return tuple(rng.standard_normal((T, C)) for _ in range(3))
+
+
+def test_container_attention_reduces_to_per_image_attention():
+    """With a container longer than the stream the mask is 'same image' alone, which the
+    per-image oracle (written separately, on un-packed tensors) computes."""
+    rng = np.random.default_rng(5)
+    B, N, C, H = 3, 17, 16, 2
+    mask = (rng.random((B, N)) < 0.6).astype(np.uint8)
+    q, k, v = (rng.standard_normal((B, N, C)) for _ in range(3))
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    flat = lambda a: a.reshape(B * N, C)[gidx]
+    out, lse = orc.attention_container_local(flat(q), flat(k), flat(v), cu, 10 ** 6, H)
+    ref, lse_ref = orc.attention_per_image(q, k, v, mask, H)
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(lse, lse_ref, rtol=1e-12, atol=1e-12)
+
+
+def test_container_attention_equals_attention_on_each_piece():
+    """Cutting the stream at the oracle's own segment boundaries and running plain softmax
+    attention (scipy) on each piece gives the same rows; L = 1 returns v itself."""
+    rng = np.random.default_rng(6)
+    C, H, L = 8, 2, 5
+    cu = np.array([0, 7, 7, 18, 21])
+    T, Dh = int(cu[-1]), C // H
+    qp, kp, vp = _packed_qkv(rng, T, C)
+    out, lse = orc.attention_container_local(qp, kp, vp, cu, L, H)
+    seg = orc.container_segments(cu, L)
+    for a, b in zip(seg[:-1], seg[1:]):
+        for h in range(H):
+            sl = slice(h * Dh, (h + 1) * Dh)
+            S = qp[a:b, sl] @ kp[a:b, sl].T / math.sqrt(Dh)
+            P = scipy.special.softmax(S, axis=1)
+            np.testing.assert_allclose(out[a:b, sl], P @ vp[a:b, sl], rtol=1e-12, atol=1e-12)
+            np.testing.assert_allclose(lse[h, a:b], scipy.special.logsumexp(S, axis=1), rtol=1e-12, atol=1e-12)
+    out1, lse1 = orc.attention_container_local(qp, kp, vp, cu, 1, H)
+    np.testing.assert_allclose(out1, vp, rtol=1e-13, atol=1e-13)
+    for h in range(H):
+        sl = slice(h * Dh, (h + 1) * Dh)
+        np.testing.assert_allclose(lse1[h], (qp[:, sl] * kp[:, sl]).sum(1) / math.sqrt(Dh), rtol=1e-12, atol=1e-12)
+
+
+def test_container_attention_no_leakage_across_containers_or_images():
+    rng = np.random.default_rng(7)
+    C, H, L = 8, 2, 4
+    cu = np.array([0, 6, 13])
+    T = 13
+    qp, kp, vp = _packed_qkv(rng, T, C)
+    out, _ = orc.attention_container_local(qp, kp, vp, cu, L, H)
+    # rows 4..5 form the segment (image 0, container 1); changing k, v anywhere else leaves them unchanged
+    k2, v2 = kp.copy(), vp.copy()
+    others = np.r_[0:4, 6:13]
+    k2[others] += rng.standard_normal((len(others), C))
+    v2[others] += rng.standard_normal((len(others), C))
+    out2, _ = orc.attention_container_local(qp, k2, v2, cu, L, H)
+    np.testing.assert_array_equal(out2[4:6], out[4:6])
+    assert not np.allclose(out2[0:4], out[0:4])
+
+
+def test_container_attention_backward_finite_differences_and_reduction():
+    rng = np.random.default_rng(8)
+    C, H, L = 6, 2, 3
+    cu = np.array([0, 4, 9])
+    T = 9
+    qp, kp, vp = _packed_qkv(rng, T, C)
+    dout = rng.standard_normal((T, C))
+    dq, dk, dv = orc.attention_container_local_backward(qp, kp, vp, cu, L, dout, H)
+    f = lambda a, b, c: float((orc.attention_container_local(a, b, c, cu, L, H)[0] * dout).sum())
+    eps = 1e-6
+    for arr, grad, which in ((qp, dq, 0), (kp, dk, 1), (vp, dv, 2)):
+        for idx in [(0, 0), (3, 5), (5, 2), (8, 1)]:
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += eps
+            lo[idx] -= eps
+            args_hi = [qp, kp, vp]
+            args_lo = [qp, kp, vp]
+            args_hi[which], args_lo[which] = hi, lo
+            num = (f(*args_hi) - f(*args_lo)) / (2 * eps)
+            assert abs(num - grad[idx]) <= 1e-6 * max(1.0, abs(num))
+    # one long container: the per-image backward oracle on un-packed tensors
+    B, N = 2, 7
+    mask = (rng.random((B, N)) < 0.7).astype(np.uint8)
+    q, k, v = (rng.standard_normal((B, N, C)) for _ in range(3))
+    cu2, gidx, inv, T2 = orc.pack_indices(mask)
+    flat = lambda a: a.reshape(B * N, C)[gidx]
+    do2 = rng.standard_normal((T2, C))
+    got = orc.attention_container_local_backward(flat(q), flat(k), flat(v), cu2, 10 ** 6, do2, H)
+    ref = orc.attention_backward_per_image(q, k, v, mask, do2, H)
+    for g, r in zip(got, ref):
+        np.testing.assert_allclose(g, r, rtol=1e-11, atol=1e-12)
