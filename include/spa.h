@@ -108,6 +108,41 @@ int spa_pack(const void* x, const uint8_t* mask, const int32_t* counts, const fl
              int32_t* total, void* stream);
 
 /*
+ * Token packing of a cyclically shifted feature map (Section 1: the feature maps are shifted
+ * every two blocks so that the token pairs that share a container vary).  Every image is a
+ * grid_h x grid_w map, N = grid_h*grid_w; the shifted map holds at (r, c) the token that sits
+ * at ((r + shift_h) mod grid_h, (c + shift_w) mod grid_w) of the original (the window-shift
+ * convention of the Swin design the paper builds on).  Tokens are packed in the raster order
+ * of the SHIFTED map; gather_idx and inv_pos keep naming positions of the ORIGINAL layout, so
+ * x is read in place and spa_unpack puts results back unshifted.  Everything else, and every
+ * argument not named here, is as in spa_pack; shift (0, 0) is spa_pack.  shift_h, shift_w:
+ * any integers (reduced modulo the grid).
+ */
+int spa_pack_shifted(const void* x, const uint8_t* mask, const int32_t* counts, const float* gate_scores,
+                     int B, int grid_h, int grid_w, int shift_h, int shift_w, int C, int dtype,
+                     int container_len, void* packed, int32_t* cu_seqlens, int32_t* gather_idx,
+                     int32_t* inv_pos, int32_t* total, void* stream);
+
+/*
+ * Container-local attention segments (Section 3.2 "Token Packing" and the B'(2 L^2 C) term of
+ * the complexity formula): the packed stream is cut into containers of length L and a token
+ * attends to the tokens of its own image inside its own container.  The segment boundaries are
+ * the distinct values among the image boundaries cu_seqlens[0..B] and the multiples of L below
+ * T = cu_seqlens[B]; feeding them to spa_packed_attention / spa_packed_attention_bwd as
+ * cu_seqlens (with B = seg_cap and max_seqlen = min(L, longest image)) evaluates that mask.
+ *   seg_cu_seqlens[0 .. n]       = the boundaries, ascending, seg[0] = 0, seg[n] = T
+ *   seg_cu_seqlens[n+1 .. seg_cap] = T   (empty segments, so that seg_cap can be used as the
+ *                                    segment count without reading n back to the host)
+ * in:  cu_seqlens [B+1] int32 (device); container_len L >= 1; max_total: an upper bound of T
+ *      known to the host (B*N); seg_cap >= spa_container_segments_capacity(B, max_total, L)
+ *      = B + max_total / L, else SPA_ERR_WORKSPACE.
+ * out: seg_cu_seqlens [seg_cap+1] int32 (device); n_segments [1] int32 (device).
+ */
+int64_t spa_container_segments_capacity(int B, int64_t max_total, int container_len);
+int spa_container_segments(const int32_t* cu_seqlens, int B, int container_len, int64_t max_total, int seg_cap,
+                           int32_t* seg_cu_seqlens, int32_t* n_segments, void* stream);
+
+/*
  * Multi-head self-attention on packed tokens in which a token attends only to tokens of
  * its own image (Section 3.2, last paragraph).  For every image b and head h, over packed
  * rows [cu_seqlens[b], cu_seqlens[b+1]):

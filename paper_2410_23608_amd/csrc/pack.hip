@@ -51,11 +51,28 @@ __device__ __forceinline__ int count_bytes_partial(const uint8_t* m, long n) {
   return cnt;
 }
 
-template <typename T, bool kScale>
+// Position in the original map of the p-th token (raster order) of the cyclically shifted map:
+// the shifted map holds at (r, c) the token at ((r + sh) mod gh, (c + sw) mod gw).
+struct Shift {
+  int gh, gw, sh, sw;   // 0 <= sh < gh, 0 <= sw < gw
+  __device__ __forceinline__ int orig(int p) const {
+    int r = p / gw, c = p - r * gw;
+    r += sh;
+    if (r >= gh) r -= gh;
+    c += sw;
+    if (c >= gw) c -= gw;
+    return r * gw + c;
+  }
+};
+
+// kShift: tokens are ranked in the raster order of the shifted map (Section 1: the feature
+// map is shifted so that the token pairs sharing a container vary); gather_idx / inv_pos keep
+// naming ORIGINAL positions, so the scatter back undoes the shift by itself.
+template <typename T, bool kScale, bool kShift>
 __global__ void __launch_bounds__(kPackThreads)
 pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
             const int32_t* __restrict__ counts, const float* __restrict__ gate_scores,
-            int B, int N, int C, int tile, int tiles_per_image, int container_len,
+            int B, int N, int C, int tile, int tiles_per_image, int container_len, Shift shift,
             T* __restrict__ packed, int32_t* __restrict__ cu_seqlens,
             int32_t* __restrict__ gather_idx, int32_t* __restrict__ inv_pos,
             int32_t* __restrict__ total) {
@@ -69,22 +86,25 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
   const int t = blockIdx.x % tiles_per_image;
   const int tile_start = t * tile;
   const int tile_n = min(tile, N - tile_start);
-  const long flat0 = (long)b * N + tile_start;
+  const long img0 = (long)b * N;
 
   // 1. selected tokens before this tile
   int part = 0;
   if (counts != nullptr) {
     for (int i = threadIdx.x; i < b; i += kPackThreads) part += counts[i];
-    part += count_bytes_partial(mask + (long)b * N, tile_start);
+    if (!kShift) part += count_bytes_partial(mask + img0, tile_start);
   } else {
-    part = count_bytes_partial(mask, flat0);
+    part = count_bytes_partial(mask, kShift ? img0 : img0 + tile_start);
   }
+  if (kShift)   // the tile's predecessors inside the image are not contiguous in memory
+    for (int p = threadIdx.x; p < tile_start; p += kPackThreads) part += mask[img0 + shift.orig(p)] != 0;
   const int base = block_sum(part, red);
 
   // 2. rank of each token of the tile among the tile's survivors
   const int tid = threadIdx.x;
   const bool in_tile = tid < tile_n;
-  const bool flag = in_tile && mask[flat0 + tid] != 0;
+  const int src = in_tile ? (kShift ? shift.orig(tile_start + tid) : tile_start + tid) : 0;   // position in the image
+  const bool flag = in_tile && mask[img0 + src] != 0;
   const uint64_t bal = __ballot(flag);
   const int wv = tid / kWave;
   if (lane_id() == 0) wave_cnt[wv] = __popcll(bal);
@@ -97,11 +117,11 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
     nsel += c;
   }
   const int local_rank = wave_off + rank_in_ballot(bal);
-  if (in_tile && inv_pos != nullptr) inv_pos[flat0 + tid] = flag ? base + local_rank : -1;
+  if (in_tile && inv_pos != nullptr) inv_pos[img0 + src] = flag ? base + local_rank : -1;
   if (flag) {
-    if (gather_idx != nullptr) gather_idx[base + local_rank] = (int32_t)(flat0 + tid);
-    sel_src[local_rank] = tid;
-    if (kScale) sel_scale[local_rank] = sigmoidf_dev(gate_scores[flat0 + tid]);
+    if (gather_idx != nullptr) gather_idx[base + local_rank] = (int32_t)(img0 + src);
+    sel_src[local_rank] = src;
+    if (kScale) sel_scale[local_rank] = sigmoidf_dev(gate_scores[img0 + src]);
   }
   if (t == 0 && tid == 0 && cu_seqlens != nullptr) cu_seqlens[b] = base;
   __syncthreads();
@@ -127,7 +147,7 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
   //    independent loads in flight per thread before the first store
   constexpr int U = 8;
   const unsigned work = packed != nullptr ? (unsigned)nsel * (unsigned)chunks : 0u;   // indices only: no rows
-  const T* xt = x + flat0 * (long)C;
+  const T* xt = x + img0 * (long)C;
   T* pt = packed + (long)base * C;
   for (unsigned i0 = tid; i0 < work; i0 += kPackThreads * U) {
     uintx4 v[U];
@@ -299,31 +319,123 @@ static void launch_unpack(const void* src, const int32_t* inv, const void* base,
 
 using namespace spa;
 
+static int pack_common(const char* fn, const void* x, const uint8_t* mask, const int32_t* counts,
+                       const float* gate_scores, int B, int N, int C, int dtype, int container_len,
+                       const Shift& shift, bool shifted, void* packed, int32_t* cu_seqlens,
+                       int32_t* gather_idx, int32_t* inv_pos, int32_t* total, void* stream) {
+  SPA_REQUIRE(mask && ((x != nullptr) == (packed != nullptr)), SPA_ERR_INVALID_ARG,
+              "%s: mask is null, or only one of x / packed is given", fn);
+  if (int rc = check_rows(fn, B, N, C, dtype)) return rc;
+  SPA_REQUIRE(container_len >= 0, SPA_ERR_INVALID_ARG, "%s: container_len must be >= 0", fn);
+  SPA_REQUIRE(aligned16(x) && aligned16(packed), SPA_ERR_INVALID_ARG, "%s: x / packed not 16-byte aligned", fn);
+  const int tile = pick_tile(B, N, counts != nullptr);
+  const int tpi = (N + tile - 1) / tile;
+  SPA_REQUIRE((long)B * tpi < 2147483647L, SPA_ERR_INVALID_ARG, "%s: too many tiles", fn);
+  const dim3 grid((unsigned)((long)B * tpi)), block(kPackThreads);
+  hipStream_t st = as_stream(stream);
+#define SPA_PACK_LAUNCH(T, S, SH)                                                                        \
+  hipLaunchKernelGGL((pack_kernel<T, S, SH>), grid, block, 0, st, static_cast<const T*>(x), mask, counts, \
+                     gate_scores, B, N, C, tile, tpi, container_len, shift, static_cast<T*>(packed),     \
+                     cu_seqlens, gather_idx, inv_pos, total)
+#define SPA_PACK_SCALE(T, SH)                                                                            \
+  do {                                                                                                   \
+    if (gate_scores) SPA_PACK_LAUNCH(T, true, SH); else SPA_PACK_LAUNCH(T, false, SH);                   \
+  } while (0)
+  if (dtype == SPA_F32) {
+    if (shifted) SPA_PACK_SCALE(float, true); else SPA_PACK_SCALE(float, false);
+  } else {
+    if (shifted) SPA_PACK_SCALE(__bf16, true); else SPA_PACK_SCALE(__bf16, false);
+  }
+#undef SPA_PACK_SCALE
+#undef SPA_PACK_LAUNCH
+  return check_launch(fn);
+}
+
 extern "C" int spa_pack(const void* x, const uint8_t* mask, const int32_t* counts,
                         const float* gate_scores, int B, int N, int C, int dtype, int container_len,
                         void* packed, int32_t* cu_seqlens, int32_t* gather_idx, int32_t* inv_pos,
                         int32_t* total, void* stream) {
-  SPA_REQUIRE(mask && ((x != nullptr) == (packed != nullptr)), SPA_ERR_INVALID_ARG,
-              "spa_pack: mask is null, or only one of x / packed is given");
-  if (int rc = check_rows("spa_pack", B, N, C, dtype)) return rc;
-  SPA_REQUIRE(container_len >= 0, SPA_ERR_INVALID_ARG, "spa_pack: container_len must be >= 0");
-  SPA_REQUIRE(aligned16(x) && aligned16(packed), SPA_ERR_INVALID_ARG, "spa_pack: x / packed not 16-byte aligned");
-  const int tile = pick_tile(B, N, counts != nullptr);
-  const int tpi = (N + tile - 1) / tile;
-  SPA_REQUIRE((long)B * tpi < 2147483647L, SPA_ERR_INVALID_ARG, "spa_pack: too many tiles");
-  const dim3 grid((unsigned)((long)B * tpi)), block(kPackThreads);
-  hipStream_t st = as_stream(stream);
-#define SPA_PACK_LAUNCH(T, S)                                                                        \
-  hipLaunchKernelGGL((pack_kernel<T, S>), grid, block, 0, st, static_cast<const T*>(x), mask, counts, \
-                     gate_scores, B, N, C, tile, tpi, container_len, static_cast<T*>(packed),        \
-                     cu_seqlens, gather_idx, inv_pos, total)
-  if (dtype == SPA_F32) {
-    if (gate_scores) SPA_PACK_LAUNCH(float, true); else SPA_PACK_LAUNCH(float, false);
-  } else {
-    if (gate_scores) SPA_PACK_LAUNCH(__bf16, true); else SPA_PACK_LAUNCH(__bf16, false);
+  return pack_common("spa_pack", x, mask, counts, gate_scores, B, N, C, dtype, container_len, Shift{1, 1, 0, 0},
+                     false, packed, cu_seqlens, gather_idx, inv_pos, total, stream);
+}
+
+extern "C" int spa_pack_shifted(const void* x, const uint8_t* mask, const int32_t* counts,
+                                const float* gate_scores, int B, int grid_h, int grid_w, int shift_h,
+                                int shift_w, int C, int dtype, int container_len, void* packed,
+                                int32_t* cu_seqlens, int32_t* gather_idx, int32_t* inv_pos, int32_t* total,
+                                void* stream) {
+  const char* fn = "spa_pack_shifted";
+  SPA_REQUIRE(grid_h >= 1 && grid_w >= 1 && (long)grid_h * grid_w < 2147483647L, SPA_ERR_INVALID_ARG,
+              "%s: grid_h, grid_w must be >= 1 and grid_h*grid_w < 2^31", fn);
+  // any integer shift; reduced to [0, extent)
+  const int sh = ((shift_h % grid_h) + grid_h) % grid_h, sw = ((shift_w % grid_w) + grid_w) % grid_w;
+  return pack_common(fn, x, mask, counts, gate_scores, B, grid_h * grid_w, C, dtype, container_len,
+                     Shift{grid_h, grid_w, sh, sw}, sh != 0 || sw != 0, packed, cu_seqlens, gather_idx, inv_pos,
+                     total, stream);
+}
+
+// Boundaries of the container-local attention segments: a segment ends where an image ends or a
+// container of length L ends.  One workgroup; images are scanned 256 at a time.
+__global__ void __launch_bounds__(256)
+container_segments_kernel(const int32_t* __restrict__ cu_seqlens, int B, int L, int seg_cap,
+                          int32_t* __restrict__ seg_cu, int32_t* __restrict__ n_segments) {
+  __shared__ int wave_sum[4];
+  __shared__ int carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  const int T = cu_seqlens[B];
+  for (int b0 = 0; b0 < B; b0 += 256) {
+    const int b = b0 + tid;
+    int start = 0, end = 0, cnt = 0;
+    if (b < B) {
+      start = cu_seqlens[b];
+      end = cu_seqlens[b + 1];
+      if (end > start) cnt = (end + L - 1) / L - start / L;   // the image's start, then every multiple of L inside it
+    }
+    // exclusive scan of cnt over the 256 images of this round
+    int inc = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += up;
+    }
+    if (lane == 63) wave_sum[wv] = inc;
+    __syncthreads();
+    int off = carry_s;
+    for (int i = 0; i < wv; ++i) off += wave_sum[i];
+    const int first = off + inc - cnt;
+    for (int i = 0; i < cnt; ++i) {
+      const int pos = i == 0 ? start : (start / L + i) * L;
+      if (first + i <= seg_cap) seg_cu[first + i] = pos;
+    }
+    __syncthreads();
+    if (tid == 255) carry_s = off + inc;
+    __syncthreads();
   }
-#undef SPA_PACK_LAUNCH
-  return check_launch("spa_pack");
+  const int n = carry_s;
+  // closing boundary, then empty segments up to the capacity
+  for (int i = n + tid; i <= seg_cap; i += 256) seg_cu[i] = T;
+  if (tid == 0) n_segments[0] = n;
+}
+
+extern "C" int64_t spa_container_segments_capacity(int B, int64_t max_total, int container_len) {
+  if (B < 1 || max_total < 0 || container_len < 1) return -1;
+  return (int64_t)B + max_total / container_len;
+}
+
+extern "C" int spa_container_segments(const int32_t* cu_seqlens, int B, int container_len, int64_t max_total,
+                                      int seg_cap, int32_t* seg_cu_seqlens, int32_t* n_segments, void* stream) {
+  const char* fn = "spa_container_segments";
+  SPA_REQUIRE(cu_seqlens && seg_cu_seqlens && n_segments, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+  SPA_REQUIRE(B >= 1 && container_len >= 1 && max_total >= 0, SPA_ERR_INVALID_ARG,
+              "%s: B, container_len must be >= 1 and max_total >= 0", fn);
+  const int64_t need = spa_container_segments_capacity(B, max_total, container_len);
+  SPA_REQUIRE(seg_cap >= need, SPA_ERR_WORKSPACE, "%s: seg_cap = %d, need %lld for B = %d, max_total = %lld, L = %d", fn,
+              seg_cap, (long long)need, B, (long long)max_total, container_len);
+  hipLaunchKernelGGL(container_segments_kernel, dim3(1), dim3(256), 0, as_stream(stream), cu_seqlens, B,
+                     container_len, seg_cap, seg_cu_seqlens, n_segments);
+  return check_launch(fn);
 }
 
 extern "C" int spa_unpack(const void* packed_out, const int32_t* inv_pos, const void* base,

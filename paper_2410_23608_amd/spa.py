@@ -32,6 +32,10 @@ _SIGNATURES = {
     "spa_gate_select": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, _P, _P, _P, _P]),
     "spa_maxpool2x2": (c_int, [_P, c_int, c_int, c_int, _P, _P]),
     "spa_pack": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, _P, _P, _P, _P, _P, _P]),
+    "spa_pack_shifted": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, _P, _P, _P,
+                                 _P, _P, _P]),
+    "spa_container_segments_capacity": (c_int64, [c_int, c_int64, c_int]),
+    "spa_container_segments": (c_int, [_P, c_int, c_int, c_int64, c_int, _P, _P, _P]),
     "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
     "spa_packed_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
                                             c_int, c_int, c_float, _P, _P, _P, _P]),
@@ -150,6 +154,37 @@ def spa_pack(x, mask, counts, gate_scores, container_len, packed, cu_seqlens, ga
                         dtype_code(x) if x is not None else SPA_BF16,
                         int(container_len), _ptr(packed), _ptr(cu_seqlens), _ptr(gather_idx), _ptr(inv_pos),
                         _ptr(total), _stream(),), _keep, prepare)
+
+
+def spa_pack_shifted(x, mask, counts, gate_scores, grid_h, grid_w, shift_h, shift_w, container_len, packed,
+                     cu_seqlens, gather_idx, inv_pos, total, prepare=False):
+    """spa_pack in the raster order of the feature map cyclically shifted by (shift_h, shift_w);
+    mask [B, grid_h*grid_w].  gather_idx / inv_pos name positions of the original layout."""
+    B, N = mask.shape
+    if N != grid_h * grid_w:
+        raise ValueError("mask.shape[1] != grid_h * grid_w")
+    C = x.shape[2] if x is not None else 8
+    _keep = (x, mask, counts, gate_scores, packed, cu_seqlens, gather_idx, inv_pos, total,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_pack_shifted,
+                     (_ptr(x), _ptr(mask), _ptr(counts), _ptr(gate_scores), B, int(grid_h), int(grid_w), int(shift_h),
+                      int(shift_w), C, dtype_code(x) if x is not None else SPA_BF16, int(container_len), _ptr(packed),
+                      _ptr(cu_seqlens), _ptr(gather_idx), _ptr(inv_pos), _ptr(total), _stream(),), _keep, prepare)
+
+
+def spa_container_segments_capacity(B, max_total, container_len) -> int:
+    return int(lib.spa_container_segments_capacity(int(B), int(max_total), int(container_len)))
+
+
+def spa_container_segments(cu_seqlens, container_len, max_total, seg_cu_seqlens, n_segments, prepare=False):
+    """cu_seqlens [B+1] -> seg_cu_seqlens [seg_cap+1] (boundaries of image x container segments,
+    padded with empty segments), n_segments [1]."""
+    B = cu_seqlens.numel() - 1
+    _keep = (cu_seqlens, seg_cu_seqlens, n_segments,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_container_segments,
+                     (_ptr(cu_seqlens), B, int(container_len), int(max_total), seg_cu_seqlens.numel() - 1,
+                      _ptr(seg_cu_seqlens), _ptr(n_segments), _stream(),), _keep, prepare)
 
 
 def _row_stride(t) -> int:
