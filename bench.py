@@ -328,6 +328,31 @@ def main():
             "out_projection_tflops": round(2.0 * T * C * C / bus["out_projection"] / 1e6, 1),
             "dense_projection_flops_saved": round(1.0 - T / (B * N), 3)}
 
+        # the paper's container mask: containers of L = 7^2 tokens, map shifted by (3, 3)
+        side = int(round(N ** 0.5))
+        if side * side == N:
+            from paper_2410_23608_amd.pipeline import ContainerForwardPass
+            cp = ContainerForwardPass(B, side, side, C, H, wl.dtype, 49, (3, 3), wl.tau, wl.bias)
+            cstages = cp.stages(x, w, qkv)
+
+            def cstep():
+                for _, fn in cstages:
+                    fn()
+
+            for _ in range(5):
+                cstep()
+            torch.cuda.synchronize()
+            cdt = timed(cstep, args.steps, torch)
+            cus = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in cstages}
+            seg = cp.seg_cu_seqlens.cpu().numpy().astype(np.float64)
+            seg_n2 = float((np.diff(seg) ** 2).sum())
+            result["container_local"] = {
+                "container_len": 49, "shift": [3, 3], "segments": int(cp.n_segments.item()),
+                "segment_capacity": cp.seg_cap, "sum_n2": seg_n2, "value": T * args.steps / cdt,
+                "unit": "selected tokens/s", "ms_per_step": 1e3 * cdt / args.steps,
+                "stage_us": {k_: round(v_, 2) for k_, v_ in cus.items()},
+                "attention_tflops": round(4.0 * C * seg_n2 / cus["packed_attention"] / 1e6, 2)}
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_oracle_baseline(wl, bun, args.cpu_seconds)
         result["cpu_baseline"]["gpu_over_cpu"] = round(value / result["cpu_baseline"]["value"], 1)

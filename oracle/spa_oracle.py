@@ -90,6 +90,23 @@ def select(s: np.ndarray, tau: float) -> Tuple[np.ndarray, float]:
     return mask, margin
 
 
+def select_gumbel(s: np.ndarray, noise: np.ndarray, temperature: float, tau: float):
+    """Stochastic hard selection (Eq. r_p = Gumbel-Softmax(s) . r_g, Gumbel-Softmax of the
+    two-class logits [s, 0]): with g1, g2 independent Gumbel(0,1) draws the relaxed weight
+    of the 'select' class is
+        p~_i = exp((s_i + g1)/T) / (exp((s_i + g1)/T) + exp(g2/T)) = sigmoid((s_i + e_i) / T),
+    e_i = g1 - g2 (a Logistic(0,1) variate, passed in as `noise`), and the token is selected
+    when p~_i exceeds the threshold tau, i.e. when s_i + e_i > T * logit(tau) (strict).
+    Returns (mask [B,N] uint8, p~ [B,N], margin = min_i |s_i + e_i - T logit(tau)|)."""
+    s = np.asarray(s, dtype=F64)
+    e = np.asarray(noise, dtype=F64)
+    z = s + e
+    bound = temperature * threshold_logit(tau)
+    mask = (z > bound).astype(np.uint8)
+    margin = float(np.min(np.abs(z - bound))) if s.size else float("inf")
+    return mask, sigmoid(z / temperature), margin
+
+
 def maxpool2x2(s: np.ndarray, h: int, w: int) -> np.ndarray:
     """Up-scale scores resized to the next (2x coarser) stage by 2x2 stride-2 max-pooling
     (Section 3.2: scores from up-scaled features are "adjusted via max-pooling").
@@ -364,7 +381,9 @@ def selection_loss(s: np.ndarray, labels: np.ndarray, loss_scale: float) -> floa
     return float(loss_scale * per.sum())
 
 
-def gate_backward(x, w, bias, s_up, labels, d_rg, gate_scaled: bool, loss_scale: float):
+def gate_backward(x, w, bias, s_up, labels, d_rg, gate_scaled: bool, loss_scale: float,
+                  st_mask: Optional[np.ndarray] = None, st_noise: Optional[np.ndarray] = None,
+                  st_temperature: float = 1.0):
     """Backward of the gate: scores s = Max(x.w + b, s_up); optional gated representation
     r_g = sigmoid(s) . x whose gradient d_rg [B,N,C] arrives from the packed path (zero
     rows for unselected tokens); selection loss = loss_scale * BCE(sigmoid(s), labels).
@@ -373,7 +392,13 @@ def gate_backward(x, w, bias, s_up, labels, d_rg, gate_scaled: bool, loss_scale:
       dx_i = [gate_scaled] p_i * d_rg_i + own_i * ds_i * w
       dw   = sum_i own_i * ds_i * x_i,   db = sum_i own_i * ds_i
     where own_i = 1 when the gate's own logit produced s_i (g_i >= s_up_i) and 0 where the
-    up-scale score won the max.  Returns dict(loss, ds, dx, dw, db)."""
+    up-scale score won the max.  Returns dict(loss, ds, dx, dw, db).
+
+    Straight-through estimator of the hard selection (Gumbel-Softmax with hard samples: the
+    forward pass multiplies r_g by the 0/1 mask m_i, the backward pass differentiates the
+    relaxed weight p~_i = sigmoid((s_i + e_i)/T) in its place).  With st_mask given, selected
+    tokens add   ds_i += <d_rg_i, r_g_i> * p~_i (1 - p~_i) / T,   r_g_i = p_i x_i,
+    where d_rg_i (the gradient that reached r_g through the packed row) equals d r_p_i there."""
     x = np.asarray(x, dtype=F64)
     w = np.asarray(w, dtype=F64)
     B, N, C = x.shape
@@ -393,6 +418,11 @@ def gate_backward(x, w, bias, s_up, labels, d_rg, gate_scaled: bool, loss_scale:
         d_rg = np.asarray(d_rg, dtype=F64)
         ds = ds + p * (1.0 - p) * (d_rg * x).sum(axis=2)
         dx = dx + p[:, :, None] * d_rg
+        if st_mask is not None:
+            e = np.zeros_like(s) if st_noise is None else np.asarray(st_noise, dtype=F64)
+            pt = sigmoid((s + e) / st_temperature)
+            r_g = p[:, :, None] * x
+            ds = ds + np.asarray(st_mask, dtype=F64) * (d_rg * r_g).sum(axis=2) * pt * (1.0 - pt) / st_temperature
     dsg = ds * own
     dx = dx + dsg[:, :, None] * w[None, None, :]
     dw = (dsg[:, :, None] * x).sum(axis=(0, 1))

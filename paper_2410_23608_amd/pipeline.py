@@ -192,3 +192,54 @@ class BlockPass:
         for _, fn in self.stages(x, w, W_qkv, b_qkv, W_o, b_o):
             fn()
         return self.y
+
+
+class ContainerForwardPass:
+    """The forward pass with the paper's container mask (Section 3.2 "Token Packing"): the
+    packed stream is cut into containers of length L and a token attends to the tokens of its
+    own image inside its own container; shift = (sh, sw) packs the cyclically shifted map.
+
+      gate_select(x) -> pack_shifted(qkv) -> container_segments -> packed_attention on the
+      image x container segments -> unpack.  Five launches, no host sync."""
+
+    def __init__(self, B: int, grid_h: int, grid_w: int, C: int, H: int, dtype: str, container_len: int,
+                 shift: Tuple[int, int] = (0, 0), tau: float = 0.5, bias: float = 0.0):
+        N = grid_h * grid_w
+        self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
+        self.grid, self.shift, self.L, self.tau, self.bias = (grid_h, grid_w), shift, container_len, tau, bias
+        td, cap = _td(dtype), B * N
+        dv = dict(device="cuda")
+        self.scores = torch.empty(B, N, dtype=torch.float32, **dv)
+        self.mask = torch.empty(B, N, dtype=torch.uint8, **dv)
+        self.packed_qkv = torch.zeros(cap + container_len - 1, 3 * C, dtype=td, **dv)
+        self.cu_seqlens = torch.zeros(B + 1, dtype=torch.int32, **dv)
+        self.gather_idx = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.inv_pos = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.total = torch.zeros(1, dtype=torch.int32, **dv)
+        self.seg_cap = spa.spa_container_segments_capacity(B, cap, container_len)
+        self.max_seqlen = min(container_len, N)
+        self.seg_cu_seqlens = torch.zeros(self.seg_cap + 1, dtype=torch.int32, **dv)
+        self.n_segments = torch.zeros(1, dtype=torch.int32, **dv)
+        self.out = torch.zeros(cap, C, dtype=td, **dv)
+        self.y = torch.empty(B, N, C, dtype=td, **dv)
+
+    def stages(self, x, w, qkv, base=None) -> List[Tuple[str, Callable[[], None]]]:
+        C, p = self.C, self.packed_qkv
+        return [
+            ("gate_select", spa.spa_gate_select(x, w, self.bias, None, self.tau, self.scores, self.mask, None,
+                                                prepare=True)),
+            ("pack_shifted", spa.spa_pack_shifted(qkv, self.mask, None, None, self.grid[0], self.grid[1],
+                                                  self.shift[0], self.shift[1], self.L, p, self.cu_seqlens,
+                                                  self.gather_idx, self.inv_pos, self.total, prepare=True)),
+            ("container_segments", spa.spa_container_segments(self.cu_seqlens, self.L, self.B * self.N,
+                                                              self.seg_cu_seqlens, self.n_segments, prepare=True)),
+            ("packed_attention", spa.spa_packed_attention(p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.seg_cu_seqlens,
+                                                          self.seg_cap, self.max_seqlen, self.H, self.Dh, self.out,
+                                                          None, prepare=True)),
+            ("unpack", spa.spa_unpack(self.out, self.inv_pos, base, self.y, prepare=True)),
+        ]
+
+    def run(self, x, w, qkv, base=None):
+        for _, fn in self.stages(x, w, qkv, base):
+            fn()
+        return self.y

@@ -579,3 +579,77 @@ def test_container_attention_backward_finite_differences_and_reduction():
     ref = orc.attention_backward_per_image(q, k, v, mask, do2, H)
     for g, r in zip(got, ref):
         np.testing.assert_allclose(g, r, rtol=1e-11, atol=1e-12)
+
+
+# ------------------------------------------------ stochastic selection, straight-through
+def test_select_gumbel_reduces_to_select_without_noise():
+    rng = np.random.default_rng(11)
+    s = rng.standard_normal((3, 50)) * 3
+    for tau in (0.5, 0.01, 0.9):
+        m0, _ = orc.select(s, tau)
+        m1, pt, _ = orc.select_gumbel(s, np.zeros_like(s), 1.0, tau)
+        assert np.array_equal(m0, m1)
+        np.testing.assert_allclose(pt, scipy.special.expit(s), rtol=1e-13)
+        assert np.array_equal(m1, (pt > tau).astype(np.uint8))          # the decision is p~ > tau
+
+
+def test_select_gumbel_is_the_two_class_gumbel_softmax():
+    """p~ equals the first component of softmax(([s, 0] + [g1, g2]) / T) with Gumbel draws,
+    and the frequency of selection under Logistic noise matches sigmoid(s - T logit(tau))."""
+    rng = np.random.default_rng(12)
+    s = rng.standard_normal((2, 40)) * 2
+    g1, g2 = rng.gumbel(size=s.shape), rng.gumbel(size=s.shape)
+    for T in (1.0, 0.5, 2.0):
+        mask, pt, _ = orc.select_gumbel(s, g1 - g2, T, 0.3)
+        logits = np.stack([s + g1, g2], axis=-1) / T
+        ref = scipy.special.softmax(logits, axis=-1)[..., 0]
+        np.testing.assert_allclose(pt, ref, rtol=1e-12, atol=1e-15)
+        assert np.array_equal(mask, (ref > 0.3).astype(np.uint8))
+    # selection frequency: P(s + e > T theta) = sigmoid(s - T theta) for e ~ Logistic(0, 1)
+    n, T, tau = 200000, 0.7, 0.2
+    for s0 in (-1.5, 0.0, 0.8):
+        e = rng.logistic(size=n)
+        mask, _, _ = orc.select_gumbel(np.full(n, s0), e, T, tau)
+        p = scipy.special.expit(s0 - T * scipy.special.logit(tau))
+        assert abs(mask.mean() - p) <= 5 * math.sqrt(p * (1 - p) / n)
+    # a lower threshold selects a superset (the paper lowers the threshold to keep more tokens)
+    e = rng.logistic(size=s.shape)
+    m_lo, _, _ = orc.select_gumbel(s, e, 1.0, 0.01)
+    m_hi, _, _ = orc.select_gumbel(s, e, 1.0, 0.5)
+    assert np.all(m_lo >= m_hi) and m_lo.sum() > m_hi.sum()
+
+
+def test_straight_through_term_is_the_derivative_of_the_relaxed_selection():
+    """Replace the hard mask by the relaxed weight p~(s) in r_p = m . r_g and differentiate
+    numerically with respect to the gate bias: the extra term of gate_backward (db with minus
+    without the flag) equals that derivative restricted to the selected tokens."""
+    rng = np.random.default_rng(13)
+    B, N, C, T = 2, 9, 8, 0.6
+    x = rng.standard_normal((B, N, C))
+    w = rng.standard_normal(C) * 0.5
+    bias = 0.1
+    noise = rng.logistic(size=(B, N))
+    up = rng.standard_normal((B, N, C))                         # d L / d r_p
+    labels = (rng.random((B, N)) < 0.5).astype(np.uint8)
+    s = orc.gate_scores(x, w, bias)
+    mask, _, _ = orc.select_gumbel(s, noise, T, 0.4)
+    d_rg = up * mask[:, :, None]                                # what pack_bwd hands over: zero rows where unselected
+    with_st = orc.gate_backward(x, w, bias, None, labels, d_rg, True, 0.0, st_mask=mask, st_noise=noise, st_temperature=T)
+    without = orc.gate_backward(x, w, bias, None, labels, d_rg, True, 0.0)
+
+    def relaxed_only(b):                                        # sum_i m_i <up_i, p~_i(b) * r_g_i>, r_g held fixed
+        sb = orc.gate_scores(x, w, b)
+        pt = scipy.special.expit((sb + noise) / T)
+        r_g = scipy.special.expit(s)[:, :, None] * x
+        return float((mask[:, :, None] * up * pt[:, :, None] * r_g).sum())
+
+    eps = 1e-6
+    num = (relaxed_only(bias + eps) - relaxed_only(bias - eps)) / (2 * eps)
+    assert abs((with_st["db"] - without["db"]) - num) <= 1e-6 * max(1.0, abs(num))
+    # per token: the term vanishes where the mask is 0 and has the sign of <d_rg, r_g>
+    extra = with_st["ds"] - without["ds"]
+    assert np.all(extra[mask == 0] == 0)
+    dots = (d_rg * scipy.special.expit(s)[:, :, None] * x).sum(axis=2)
+    assert np.all(np.sign(extra[mask == 1]) == np.sign(dots[mask == 1]))
+    # dw picks the same term up through ds
+    np.testing.assert_allclose(with_st["dw"] - without["dw"], (extra[:, :, None] * x).sum(axis=(0, 1)), rtol=1e-10)
