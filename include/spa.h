@@ -75,6 +75,21 @@ int spa_gate_select(const void* x, const void* w, float bias, const float* s_up,
                     float* scores, uint8_t* mask, int32_t* counts, void* stream);
 
 /*
+ * Stochastic selection (Section 3.2, r_p = Gumbel-Softmax(s) . r_g): Gumbel-Softmax of the
+ * two-class logits [s, 0].  With e_i = g1 - g2 the difference of two Gumbel(0,1) draws (a
+ * Logistic(0,1) variate) the relaxed weight of the 'select' class is
+ *   p~_i = sigmoid((scores_i + e_i) / temperature)
+ * and the token is selected when p~_i > tau, decided as scores_i + e_i > temperature*logit(tau)
+ * in fp32 (strict).  The library draws no random numbers: the caller supplies e.
+ * in:  as spa_gate_select, plus noise [B,N] fp32 (e_i) and temperature > 0 (host float).
+ * out: scores [B,N] fp32 (the logits s, WITHOUT the noise); mask; counts as spa_gate_select.
+ * spa_gate_select is the noise-free case e = 0, temperature = 1.
+ */
+int spa_gate_select_gumbel(const void* x, const void* w, float bias, const float* s_up,
+                           const float* noise, float temperature, float tau, int B, int N, int C,
+                           int dtype, float* scores, uint8_t* mask, int32_t* counts, void* stream);
+
+/*
  * 2x2 stride-2 max-pooling of a score map, used to hand the scores of a finer stage to
  * the next one (Section 3.2: up-scale scores "adjusted via max-pooling").
  * in:  s [B, h*w] fp32 (h, w even).   out: pooled [B, (h/2)*(w/2)] fp32.
@@ -273,6 +288,25 @@ int spa_gate_bwd(const void* x, const void* w, float bias, const float* scores,
                  float loss_scale, int B, int N, int C, int dtype,
                  float* loss, void* dx, float* dw, float* db,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * spa_gate_bwd with the straight-through estimator of the hard selection (Section 3.2, the
+ * Gumbel-Softmax with hard samples): the forward pass multiplied r_g by the 0/1 mask, the
+ * backward pass differentiates the relaxed weight p~_i = sigmoid((s_i + e_i)/temperature) in
+ * its place, which adds on selected tokens
+ *   ds_i += <d_rg[i,:], r_g[i,:]> p~_i (1 - p~_i) / temperature,   r_g[i,:] = p_i x[i,:]
+ * to the ds_i of spa_gate_bwd with gate_scaled = 1 (d_rg[i,:] is the gradient of the packed
+ * row there).  Everything else as spa_gate_bwd.
+ * in:  as spa_gate_bwd (d_rg required), plus mask [B,N] uint8 (the selection of the forward
+ *      pass), noise [B,N] fp32 or NULL (the e_i of spa_gate_select_gumbel; NULL = 0),
+ *      temperature > 0.
+ */
+int spa_gate_bwd_straight_through(const void* x, const void* w, float bias, const float* scores,
+                                  const float* s_up, const uint8_t* labels, const void* d_rg,
+                                  float loss_scale, const uint8_t* mask, const float* noise,
+                                  float temperature, int B, int N, int C, int dtype, float* loss,
+                                  void* dx, float* dw, float* db, void* workspace,
+                                  size_t workspace_bytes, void* stream);
 
 /* -------------------------------------------------- comparison baseline -------- */
 

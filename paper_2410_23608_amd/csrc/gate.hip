@@ -49,7 +49,7 @@ __device__ __forceinline__ float group_sum(float v) {
 template <typename T, int G>
 __global__ void __launch_bounds__(kGateThreads)
 gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
-                   const float* __restrict__ s_up, float theta, int ntok, int N, int C,
+                   const float* __restrict__ s_up, const float* __restrict__ noise, float theta, int ntok, int N, int C,
                    float* __restrict__ scores, uint8_t* __restrict__ mask) {
   constexpr int VE = Vec16<T>::kElems;
   extern __shared__ float w_lds[];
@@ -75,7 +75,8 @@ gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
     if (gl == 0) {
       float s = acc + bias;
       if (s_up != nullptr) s = fmaxf(s, s_up[tok]);
-      const bool sel = s > theta;
+      // noise: logistic variate of the two-class Gumbel-Softmax; theta already carries the temperature
+      const bool sel = (noise != nullptr ? s + noise[tok] : s) > theta;
       scores[tok] = s;
       mask[tok] = sel ? 1 : 0;
     }
@@ -116,13 +117,21 @@ __global__ void maxpool2x2_kernel(const float* __restrict__ s, int B, int h, int
 // and d_rg are read once.  dw / db / loss are reduced without atomics: lanes accumulate
 // over their tokens, groups are folded in a fixed order into LDS, every workgroup writes one
 // partial row, and a second kernel adds the partial rows in order.
+// Straight-through estimator of the hard selection: selected tokens differentiate the relaxed
+// weight sigmoid((s + noise) / T) in place of the 0/1 mask.  mask == nullptr: off.
+struct StraightThrough {
+  const uint8_t* mask;
+  const float* noise;   // may be null (noise-free selection)
+  float inv_temperature;
+};
+
 template <typename T, int G, int IT>
 __global__ void __launch_bounds__(kGateThreads)
 gate_bwd_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
                 const float* __restrict__ scores, const float* __restrict__ s_up,
                 const uint8_t* __restrict__ labels, const T* __restrict__ d_rg, int gate_scaled,
-                float loss_scale, int ntok, int C, T* __restrict__ dx, float* __restrict__ partial,
-                int fold_parallel) {
+                float loss_scale, StraightThrough st, int ntok, int C, T* __restrict__ dx,
+                float* __restrict__ partial, int fold_parallel) {
   constexpr int VE = Vec16<T>::kElems;
   constexpr int kGroups = kGateThreads / G;
   extern __shared__ float lds[];
@@ -170,7 +179,14 @@ gate_bwd_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
     const float p = sigmoidf_dev(s);
     const float y = labels[tok] != 0 ? 1.f : 0.f;
     float ds = loss_scale * (p - y);
-    if (scaled) ds = fmaf(p * (1.f - p), dot, ds);
+    if (scaled) {
+      float coef = p * (1.f - p);                      // through r_g = sigmoid(s) . r
+      if (st.mask != nullptr && st.mask[tok] != 0) {   // through the relaxed selection weight: <d_rg, r_g> = p dot
+        const float pt = sigmoidf_dev((s + (st.noise != nullptr ? st.noise[tok] : 0.f)) * st.inv_temperature);
+        coef = fmaf(pt * (1.f - pt) * st.inv_temperature, p, coef);
+      }
+      ds = fmaf(coef, dot, ds);
+    }
     const float dsg = own ? ds : 0.f;
     const float pg = scaled ? p : 0.f;
 #pragma unroll
@@ -275,9 +291,9 @@ static int gate_bwd_parts(long ntok) {
 }
 
 template <typename T>
-static int launch_gate(const void* x, const void* w, float bias, const float* s_up, float theta,
-                       int B, int N, int C, float* scores, uint8_t* mask, int32_t* counts,
-                       hipStream_t st) {
+static int launch_gate(const char* fn, const void* x, const void* w, float bias, const float* s_up,
+                       const float* noise, float theta, int B, int N, int C, float* scores, uint8_t* mask,
+                       int32_t* counts, hipStream_t st) {
   constexpr int VE = Vec16<T>::kElems;
   const int chunks = C / VE;
   const long ntok = (long)B * N;
@@ -288,7 +304,7 @@ static int launch_gate(const void* x, const void* w, float bias, const float* s_
     long wgs = (ntok + per_wg - 1) / per_wg;
     if (wgs > 4096) wgs = 4096;
     hipLaunchKernelGGL((gate_select_kernel<T, G>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
-                       static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, theta,
+                       static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, noise, theta,
                        (int)ntok, N, C, scores, mask);
   };
   if (chunks <= 8) go(std::integral_constant<int, 8>{});
@@ -297,29 +313,48 @@ static int launch_gate(const void* x, const void* w, float bias, const float* s_
   else go(std::integral_constant<int, 64>{});
   if (counts != nullptr)
     hipLaunchKernelGGL(count_selected_kernel, dim3(B), dim3(256), 0, st, mask, N, counts);
-  return check_launch("spa_gate_select");
+  return check_launch(fn);
 }
 
 }  // namespace spa
 
 using namespace spa;
 
+static int gate_select_common(const char* fn, const void* x, const void* w, float bias, const float* s_up,
+                              const float* noise, float temperature, float tau, int B, int N, int C, int dtype,
+                              float* scores, uint8_t* mask, int32_t* counts, void* stream) {
+  SPA_REQUIRE(x && w && scores && mask, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+  SPA_REQUIRE(B >= 1 && N >= 1 && C >= 1, SPA_ERR_INVALID_ARG, "%s: B, N, C must be >= 1", fn);
+  SPA_REQUIRE((long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*N must be < 2^31", fn);
+  SPA_REQUIRE(tau > 0.f && tau < 1.f, SPA_ERR_INVALID_ARG, "%s: tau must lie in (0,1), got %g", fn, (double)tau);
+  SPA_REQUIRE(temperature > 0.f && std::isfinite(temperature), SPA_ERR_INVALID_ARG,
+              "%s: temperature must be positive and finite, got %g", fn, (double)temperature);
+  SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
+  SPA_REQUIRE(((long)C * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG,
+              "%s: row length C*elem = %ld bytes is not a multiple of 16", fn, (long)C * elem_size(dtype));
+  SPA_REQUIRE(aligned16(x), SPA_ERR_INVALID_ARG, "%s: x is not 16-byte aligned", fn);
+  SPA_REQUIRE(C <= kMaxGateC, SPA_ERR_UNSUPPORTED, "%s: C = %d exceeds %d", fn, C, kMaxGateC);
+  // sigmoid((s + e) / T) > tau  <=>  s + e > T * logit(tau)
+  const float theta = (float)((double)temperature * std::log((double)tau / (1.0 - (double)tau)));
+  hipStream_t st = as_stream(stream);
+  if (dtype == SPA_F32)
+    return launch_gate<float>(fn, x, w, bias, s_up, noise, theta, B, N, C, scores, mask, counts, st);
+  return launch_gate<__bf16>(fn, x, w, bias, s_up, noise, theta, B, N, C, scores, mask, counts, st);
+}
+
 extern "C" int spa_gate_select(const void* x, const void* w, float bias, const float* s_up,
                                float tau, int B, int N, int C, int dtype, float* scores,
                                uint8_t* mask, int32_t* counts, void* stream) {
-  SPA_REQUIRE(x && w && scores && mask, SPA_ERR_INVALID_ARG, "spa_gate_select: null pointer");
-  SPA_REQUIRE(B >= 1 && N >= 1 && C >= 1, SPA_ERR_INVALID_ARG, "spa_gate_select: B, N, C must be >= 1");
-  SPA_REQUIRE((long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "spa_gate_select: B*N must be < 2^31");
-  SPA_REQUIRE(tau > 0.f && tau < 1.f, SPA_ERR_INVALID_ARG, "spa_gate_select: tau must lie in (0,1), got %g", (double)tau);
-  SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "spa_gate_select: unknown dtype %d", dtype);
-  SPA_REQUIRE(((long)C * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG,
-              "spa_gate_select: row length C*elem = %ld bytes is not a multiple of 16", (long)C * elem_size(dtype));
-  SPA_REQUIRE(aligned16(x), SPA_ERR_INVALID_ARG, "spa_gate_select: x is not 16-byte aligned");
-  SPA_REQUIRE(C <= kMaxGateC, SPA_ERR_UNSUPPORTED, "spa_gate_select: C = %d exceeds %d", C, kMaxGateC);
-  const float theta = (float)std::log((double)tau / (1.0 - (double)tau));
-  hipStream_t st = as_stream(stream);
-  if (dtype == SPA_F32) return launch_gate<float>(x, w, bias, s_up, theta, B, N, C, scores, mask, counts, st);
-  return launch_gate<__bf16>(x, w, bias, s_up, theta, B, N, C, scores, mask, counts, st);
+  return gate_select_common("spa_gate_select", x, w, bias, s_up, nullptr, 1.f, tau, B, N, C, dtype, scores, mask,
+                            counts, stream);
+}
+
+extern "C" int spa_gate_select_gumbel(const void* x, const void* w, float bias, const float* s_up,
+                                      const float* noise, float temperature, float tau, int B, int N, int C,
+                                      int dtype, float* scores, uint8_t* mask, int32_t* counts, void* stream) {
+  SPA_REQUIRE(noise != nullptr, SPA_ERR_INVALID_ARG, "spa_gate_select_gumbel: noise is null");
+  return gate_select_common("spa_gate_select_gumbel", x, w, bias, s_up, noise, temperature, tau, B, N, C, dtype,
+                            scores, mask, counts, stream);
 }
 
 extern "C" int spa_maxpool2x2(const float* s, int B, int h, int w, float* pooled, void* stream) {
@@ -342,8 +377,8 @@ extern "C" size_t spa_gate_bwd_workspace_bytes(int B, int N, int C, int dtype) {
 template <typename T>
 static int launch_gate_bwd(const void* x, const void* w, float bias, const float* scores, const float* s_up,
                            const uint8_t* labels, const void* d_rg, int gate_scaled, float loss_scale,
-                           long ntok, int C, float* loss, void* dx, float* dw, float* db, float* partial,
-                           hipStream_t st) {
+                           StraightThrough stt, long ntok, int C, float* loss, void* dx, float* dw, float* db,
+                           float* partial, hipStream_t st) {
   constexpr int VE = Vec16<T>::kElems;
   const int chunks = C / VE;
   const int parts = gate_bwd_parts(ntok);
@@ -354,8 +389,8 @@ static int launch_gate_bwd(const void* x, const void* w, float bias, const float
 #define SPA_GB(G, IT)                                                                                         \
   hipLaunchKernelGGL((gate_bwd_kernel<T, G, IT>), dim3(parts), dim3(kGateThreads), lds, st,                  \
                      static_cast<const T*>(x), static_cast<const T*>(w), bias, scores, s_up, labels,         \
-                     static_cast<const T*>(d_rg), gate_scaled, loss_scale, (int)ntok, C, static_cast<T*>(dx), \
-                     partial, fold_parallel)
+                     static_cast<const T*>(d_rg), gate_scaled, loss_scale, stt, (int)ntok, C,                \
+                     static_cast<T*>(dx), partial, fold_parallel)
   if (chunks <= 16) SPA_GB(16, 1);
   else if (chunks <= 32) SPA_GB(16, 2);
   else if (chunks <= 64) SPA_GB(16, 4);
@@ -369,28 +404,52 @@ static int launch_gate_bwd(const void* x, const void* w, float bias, const float
   return check_launch("spa_gate_bwd");
 }
 
+static int gate_bwd_common(const char* fn, const void* x, const void* w, float bias, const float* scores,
+                           const float* s_up, const uint8_t* labels, const void* d_rg, int gate_scaled,
+                           float loss_scale, StraightThrough stt, int B, int N, int C, int dtype, float* loss,
+                           void* dx, float* dw, float* db, void* workspace, size_t workspace_bytes, void* stream) {
+  SPA_REQUIRE(x && w && scores && labels && loss && dx && dw && db, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+  SPA_REQUIRE(B >= 1 && N >= 1 && C >= 1, SPA_ERR_INVALID_ARG, "%s: B, N, C must be >= 1", fn);
+  SPA_REQUIRE((long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*N must be < 2^31", fn);
+  SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
+  SPA_REQUIRE(((long)C * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG,
+              "%s: row length C*elem = %ld bytes is not a multiple of 16", fn, (long)C * elem_size(dtype));
+  SPA_REQUIRE(aligned16(x) && aligned16(dx) && aligned16(d_rg), SPA_ERR_INVALID_ARG,
+              "%s: x / dx / d_rg not 16-byte aligned", fn);
+  SPA_REQUIRE(!(gate_scaled && !d_rg), SPA_ERR_INVALID_ARG, "%s: gate_scaled needs d_rg", fn);
+  SPA_REQUIRE(C <= kMaxGateC, SPA_ERR_UNSUPPORTED, "%s: C = %d exceeds %d", fn, C, kMaxGateC);
+  const size_t need = spa_gate_bwd_workspace_bytes(B, N, C, dtype);
+  SPA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SPA_ERR_WORKSPACE,
+              "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace_bytes);
+  hipStream_t st = as_stream(stream);
+  float* partial = static_cast<float*>(workspace);
+  if (dtype == SPA_F32)
+    return launch_gate_bwd<float>(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, stt, (long)B * N,
+                                  C, loss, dx, dw, db, partial, st);
+  return launch_gate_bwd<__bf16>(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, stt, (long)B * N,
+                                 C, loss, dx, dw, db, partial, st);
+}
+
 extern "C" int spa_gate_bwd(const void* x, const void* w, float bias, const float* scores,
                             const float* s_up, const uint8_t* labels, const void* d_rg, int gate_scaled,
                             float loss_scale, int B, int N, int C, int dtype, float* loss, void* dx,
                             float* dw, float* db, void* workspace, size_t workspace_bytes, void* stream) {
-  SPA_REQUIRE(x && w && scores && labels && loss && dx && dw && db, SPA_ERR_INVALID_ARG, "spa_gate_bwd: null pointer");
-  SPA_REQUIRE(B >= 1 && N >= 1 && C >= 1, SPA_ERR_INVALID_ARG, "spa_gate_bwd: B, N, C must be >= 1");
-  SPA_REQUIRE((long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "spa_gate_bwd: B*N must be < 2^31");
-  SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "spa_gate_bwd: unknown dtype %d", dtype);
-  SPA_REQUIRE(((long)C * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG,
-              "spa_gate_bwd: row length C*elem = %ld bytes is not a multiple of 16", (long)C * elem_size(dtype));
-  SPA_REQUIRE(aligned16(x) && aligned16(dx) && aligned16(d_rg), SPA_ERR_INVALID_ARG,
-              "spa_gate_bwd: x / dx / d_rg not 16-byte aligned");
-  SPA_REQUIRE(!(gate_scaled && !d_rg), SPA_ERR_INVALID_ARG, "spa_gate_bwd: gate_scaled needs d_rg");
-  SPA_REQUIRE(C <= kMaxGateC, SPA_ERR_UNSUPPORTED, "spa_gate_bwd: C = %d exceeds %d", C, kMaxGateC);
-  const size_t need = spa_gate_bwd_workspace_bytes(B, N, C, dtype);
-  SPA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SPA_ERR_WORKSPACE,
-              "spa_gate_bwd: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
-  hipStream_t st = as_stream(stream);
-  float* partial = static_cast<float*>(workspace);
-  if (dtype == SPA_F32)
-    return launch_gate_bwd<float>(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, (long)B * N, C,
-                                  loss, dx, dw, db, partial, st);
-  return launch_gate_bwd<__bf16>(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, (long)B * N, C,
-                                 loss, dx, dw, db, partial, st);
+  return gate_bwd_common("spa_gate_bwd", x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale,
+                         StraightThrough{nullptr, nullptr, 1.f}, B, N, C, dtype, loss, dx, dw, db, workspace,
+                         workspace_bytes, stream);
+}
+
+extern "C" int spa_gate_bwd_straight_through(const void* x, const void* w, float bias, const float* scores,
+                                             const float* s_up, const uint8_t* labels, const void* d_rg,
+                                             float loss_scale, const uint8_t* mask, const float* noise,
+                                             float temperature, int B, int N, int C, int dtype, float* loss,
+                                             void* dx, float* dw, float* db, void* workspace,
+                                             size_t workspace_bytes, void* stream) {
+  const char* fn = "spa_gate_bwd_straight_through";
+  SPA_REQUIRE(mask && d_rg, SPA_ERR_INVALID_ARG, "%s: mask and d_rg are required", fn);
+  SPA_REQUIRE(temperature > 0.f && std::isfinite(temperature), SPA_ERR_INVALID_ARG,
+              "%s: temperature must be positive and finite, got %g", fn, (double)temperature);
+  return gate_bwd_common(fn, x, w, bias, scores, s_up, labels, d_rg, 1, loss_scale,
+                         StraightThrough{mask, noise, 1.f / temperature}, B, N, C, dtype, loss, dx, dw, db, workspace,
+                         workspace_bytes, stream);
 }

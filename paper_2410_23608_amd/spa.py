@@ -30,6 +30,10 @@ _SIGNATURES = {
     "spa_version": (c_int, []),
     "spa_last_error": (c_char_p, []),
     "spa_gate_select": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, _P, _P, _P, _P]),
+    "spa_gate_select_gumbel": (c_int, [_P, _P, c_float, _P, _P, c_float, c_float, c_int, c_int, c_int, c_int, _P, _P,
+                                       _P, _P]),
+    "spa_gate_bwd_straight_through": (c_int, [_P, _P, c_float, _P, _P, _P, _P, c_float, _P, _P, c_float, c_int, c_int,
+                                              c_int, c_int, _P, _P, _P, _P, _P, c_size_t, _P]),
     "spa_maxpool2x2": (c_int, [_P, c_int, c_int, c_int, _P, _P]),
     "spa_pack": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, _P, _P, _P, _P, _P, _P]),
     "spa_pack_shifted": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, _P, _P, _P,
@@ -133,6 +137,17 @@ def spa_gate_select(x, w, bias, s_up, tau, scores, mask, counts=None, prepare=Fa
     _contig(*_keep)
     return _dispatch(lib.spa_gate_select, (_ptr(x), _ptr(w), float(bias), _ptr(s_up), float(tau), B, N, C, dtype_code(x),
                                _ptr(scores), _ptr(mask), _ptr(counts), _stream(),), _keep, prepare)
+
+
+def spa_gate_select_gumbel(x, w, bias, s_up, noise, temperature, tau, scores, mask, counts=None, prepare=False):
+    """spa_gate_select with caller-supplied logistic noise [B,N] f32 and a temperature:
+    selected when sigmoid((s + noise) / temperature) > tau."""
+    B, N, C = x.shape
+    _keep = (x, w, s_up, noise, scores, mask, counts,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_gate_select_gumbel,
+                     (_ptr(x), _ptr(w), float(bias), _ptr(s_up), _ptr(noise), float(temperature), float(tau), B, N, C,
+                      dtype_code(x), _ptr(scores), _ptr(mask), _ptr(counts), _stream(),), _keep, prepare)
 
 
 def spa_maxpool2x2(s, h, w, pooled, prepare=False):
@@ -278,6 +293,18 @@ def spa_gate_bwd(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale
     return _dispatch(lib.spa_gate_bwd, (_ptr(x), _ptr(w), float(bias), _ptr(scores), _ptr(s_up), _ptr(labels), _ptr(d_rg),
                             int(bool(gate_scaled)), float(loss_scale), B, N, C, dtype_code(x), _ptr(loss), _ptr(dx),
                             _ptr(dw), _ptr(db), _ptr(workspace), ws_bytes, _stream(),), _keep, prepare)
+
+
+def spa_gate_bwd_straight_through(x, w, bias, scores, s_up, labels, d_rg, loss_scale, mask, noise, temperature,
+                                  loss, dx, dw, db, workspace, prepare=False):
+    B, N, C = x.shape
+    _keep = (x, w, scores, s_up, labels, d_rg, mask, noise, loss, dx, dw, db, workspace,)
+    _contig(*_keep)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return _dispatch(lib.spa_gate_bwd_straight_through,
+                     (_ptr(x), _ptr(w), float(bias), _ptr(scores), _ptr(s_up), _ptr(labels), _ptr(d_rg),
+                      float(loss_scale), _ptr(mask), _ptr(noise), float(temperature), B, N, C, dtype_code(x),
+                      _ptr(loss), _ptr(dx), _ptr(dw), _ptr(db), _ptr(workspace), ws_bytes, _stream(),), _keep, prepare)
 
 
 def spa_padded_attention(q, k, v, seqlens, B, n_pad, H, Dh, out, softmax_scale=0.0, prepare=False):
