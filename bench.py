@@ -303,6 +303,23 @@ def main():
                              "ms_per_step": 1e3 * tdt / args.steps, "selected_tokens": tT,
                              "stage_us": {k_: round(v_, 2) for k_, v_ in tus.items()},
                              "attention_bwd_tflops": round(bwd_flops / tus["packed_attention_bwd"] / 1e6, 2)}
+        # the same step with stochastic Gumbel-Softmax selection and the straight-through backward
+        gn = torch.from_numpy(np.random.default_rng(args.seed + 5).logistic(size=(twl.B, twl.N)).astype(np.float32)).cuda()
+        gstages = tp.stages(tx, tw, tqk, tlab, tdy, noise=gn, temperature=1.0)
+
+        def gstep():
+            for _, fn in gstages:
+                fn()
+
+        for _ in range(5):
+            gstep()
+        torch.cuda.synchronize()
+        gT = int(tp.total.item())
+        gdt2 = timed(gstep, args.steps, torch)
+        result["fwd_bwd_gumbel"] = {"selected_tokens": gT, "value": gT * args.steps / gdt2, "unit": "selected tokens/s",
+                                    "ms_per_step": 1e3 * gdt2 / args.steps,
+                                    "stage_us": {nme: round(back_to_back_us(fn, args.steps, torch), 2)
+                                                 for nme, fn in (gstages[0], gstages[-1])}}
 
         # the block with its projections: only selected tokens are projected
         from paper_2410_23608_amd.pipeline import BlockPass
@@ -352,6 +369,38 @@ def main():
                 "unit": "selected tokens/s", "ms_per_step": 1e3 * cdt / args.steps,
                 "stage_us": {k_: round(v_, 2) for k_, v_ in cus.items()},
                 "attention_tflops": round(4.0 * C * seg_n2 / cus["packed_attention"] / 1e6, 2)}
+
+        # four-stage hierarchy (batch 16, 56^2 .. 7^2 tokens, C 96 .. 768): 12 launches, eager and as one hipGraph
+        from paper_2410_23608_amd.pipeline import HierarchyPass
+        hb = workloads.generate_hierarchy(args.seed)
+        hcfg = [(b_["workload"].B, *b_["workload"].grid, b_["workload"].C, b_["workload"].H, b_["workload"].dtype,
+                 b_["workload"].tau, b_["bias"]) for b_ in hb]
+        hp = HierarchyPass(hcfg)
+        hx, hw, hq = [up(b_["x"]) for b_ in hb], [up(b_["w"]) for b_ in hb], [up(b_["qkv"]) for b_ in hb]
+        hstages = hp.stages(hx, hw, hq)
+
+        def hstep():
+            for _, fn in hstages:
+                fn()
+
+        for _ in range(5):
+            hstep()
+        torch.cuda.synchronize()
+        hT = [int(p_.total.item()) for p_ in hp.passes]
+        hdt = timed(hstep, args.steps, torch)
+        hres = {"stages": [b_["workload"].name for b_ in hb], "launches": len(hstages), "selected_tokens": hT,
+                "tokens": [c_[0] * c_[1] * c_[2] for c_ in hcfg], "ms_per_chain": 1e3 * hdt / args.steps,
+                "value": sum(hT) * args.steps / hdt, "unit": "selected tokens/s",
+                "stage_us": {nme: round(back_to_back_us(fn, args.steps, torch), 2) for nme, fn in hstages}}
+        try:
+            def make_hstep():
+                st_ = hp.stages(hx, hw, hq)
+                return lambda: [fn() for _, fn in st_]
+            ghdt = graph_replay_s(make_hstep, args.steps, torch)
+            hres["graph_replay_ms_per_chain"] = 1e3 * ghdt / args.steps
+        except Exception as ex:
+            hres["graph_replay_error"] = str(ex)[:200]
+        result["hierarchy"] = hres
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_oracle_baseline(wl, bun, args.cpu_seconds)

@@ -97,6 +97,20 @@ int spa_gate_select_gumbel(const void* x, const void* w, float bias, const float
 int spa_maxpool2x2(const float* s, int B, int h, int w, float* pooled, void* stream);
 
 /*
+ * spa_gate_select with the 2x2 max-pooling of the finer stage's score map folded in
+ * (Section 3.2: s = Max(f_g(r), s_up) with s_up "adjusted via max-pooling"): one launch per
+ * stage of a hierarchy instead of two.  This stage's tokens form a grid_h x grid_w map
+ * (N = grid_h*grid_w); s_fine is the score map of the previous, 2x finer stage.
+ * in:  x [B,N,C], w [C] dtype; bias; s_fine [B, 2*grid_h, 2*grid_w] fp32 (8-byte aligned); tau.
+ * out: scores, mask, counts as spa_gate_select; s_up_pooled [B,N] fp32 or NULL: the pooled
+ *      scores, which spa_gate_bwd takes as s_up.
+ * Results equal spa_maxpool2x2 followed by spa_gate_select bit for bit.
+ */
+int spa_gate_select_pooled(const void* x, const void* w, float bias, const float* s_fine, float tau,
+                           int B, int grid_h, int grid_w, int C, int dtype, float* scores,
+                           uint8_t* mask, int32_t* counts, float* s_up_pooled, void* stream);
+
+/*
  * Token packing (Section 3.2 "Token Packing").  Stable compaction of the selected tokens:
  * images in batch order, tokens in ascending position.
  *   cu_seqlens[b]  = number of selected tokens in images < b    (cu_seqlens[B] = T)

@@ -46,11 +46,19 @@ __device__ __forceinline__ float group_sum(float v) {
 }
 
 // One group of G lanes per token; the group strides over the row's 16-byte chunks.
-template <typename T, int G>
+// kPool: s_up is the score map of the finer stage, [B, 2 gh, 2 gw], and is 2x2 max-pooled on
+// the fly (Section 3.2: up-scale scores adjusted via max-pooling); the pooled value is also
+// written to s_up_pooled when that is given (the backward pass needs it).
+struct PoolGrid {
+  int gh, gw;            // this stage's grid, N = gh * gw
+  float* s_up_pooled;    // [B, N] or null
+};
+
+template <typename T, int G, bool kPool>
 __global__ void __launch_bounds__(kGateThreads)
 gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
                    const float* __restrict__ s_up, const float* __restrict__ noise, float theta, int ntok, int N, int C,
-                   float* __restrict__ scores, uint8_t* __restrict__ mask) {
+                   PoolGrid pool, float* __restrict__ scores, uint8_t* __restrict__ mask) {
   constexpr int VE = Vec16<T>::kElems;
   extern __shared__ float w_lds[];
   for (int c = threadIdx.x; c < C; c += kGateThreads) w_lds[c] = static_cast<float>(w[c]);
@@ -74,7 +82,18 @@ gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
     acc = group_sum<G>(acc);
     if (gl == 0) {
       float s = acc + bias;
-      if (s_up != nullptr) s = fmaxf(s, s_up[tok]);
+      if (kPool) {
+        const int b = (int)(tok / N), n = (int)(tok - (long)b * N);
+        const int oy = n / pool.gw, ox = n - oy * pool.gw;
+        const float* p = s_up + (long)b * N * 4 + (long)(2 * oy) * (2 * pool.gw) + 2 * ox;
+        const float2 top = *reinterpret_cast<const float2*>(p);
+        const float2 bot = *reinterpret_cast<const float2*>(p + 2 * pool.gw);
+        const float up = fmaxf(fmaxf(top.x, top.y), fmaxf(bot.x, bot.y));
+        if (pool.s_up_pooled != nullptr) pool.s_up_pooled[tok] = up;
+        s = fmaxf(s, up);
+      } else if (s_up != nullptr) {
+        s = fmaxf(s, s_up[tok]);
+      }
       // noise: logistic variate of the two-class Gumbel-Softmax; theta already carries the temperature
       const bool sel = (noise != nullptr ? s + noise[tok] : s) > theta;
       scores[tok] = s;
@@ -292,8 +311,8 @@ static int gate_bwd_parts(long ntok) {
 
 template <typename T>
 static int launch_gate(const char* fn, const void* x, const void* w, float bias, const float* s_up,
-                       const float* noise, float theta, int B, int N, int C, float* scores, uint8_t* mask,
-                       int32_t* counts, hipStream_t st) {
+                       const float* noise, float theta, int B, int N, int C, PoolGrid pool, bool pooled,
+                       float* scores, uint8_t* mask, int32_t* counts, hipStream_t st) {
   constexpr int VE = Vec16<T>::kElems;
   const int chunks = C / VE;
   const long ntok = (long)B * N;
@@ -303,9 +322,14 @@ static int launch_gate(const char* fn, const void* x, const void* w, float bias,
     const long per_wg = kGateThreads / G;
     long wgs = (ntok + per_wg - 1) / per_wg;
     if (wgs > 4096) wgs = 4096;
-    hipLaunchKernelGGL((gate_select_kernel<T, G>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
-                       static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, noise, theta,
-                       (int)ntok, N, C, scores, mask);
+    if (pooled)
+      hipLaunchKernelGGL((gate_select_kernel<T, G, true>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
+                         static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, noise, theta,
+                         (int)ntok, N, C, pool, scores, mask);
+    else
+      hipLaunchKernelGGL((gate_select_kernel<T, G, false>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
+                         static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, noise, theta,
+                         (int)ntok, N, C, pool, scores, mask);
   };
   if (chunks <= 8) go(std::integral_constant<int, 8>{});
   else if (chunks <= 64) go(std::integral_constant<int, 16>{});
@@ -322,7 +346,8 @@ using namespace spa;
 
 static int gate_select_common(const char* fn, const void* x, const void* w, float bias, const float* s_up,
                               const float* noise, float temperature, float tau, int B, int N, int C, int dtype,
-                              float* scores, uint8_t* mask, int32_t* counts, void* stream) {
+                              float* scores, uint8_t* mask, int32_t* counts, void* stream,
+                              PoolGrid pool = PoolGrid{0, 0, nullptr}, bool pooled = false) {
   SPA_REQUIRE(x && w && scores && mask, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(B >= 1 && N >= 1 && C >= 1, SPA_ERR_INVALID_ARG, "%s: B, N, C must be >= 1", fn);
   SPA_REQUIRE((long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*N must be < 2^31", fn);
@@ -338,8 +363,8 @@ static int gate_select_common(const char* fn, const void* x, const void* w, floa
   const float theta = (float)((double)temperature * std::log((double)tau / (1.0 - (double)tau)));
   hipStream_t st = as_stream(stream);
   if (dtype == SPA_F32)
-    return launch_gate<float>(fn, x, w, bias, s_up, noise, theta, B, N, C, scores, mask, counts, st);
-  return launch_gate<__bf16>(fn, x, w, bias, s_up, noise, theta, B, N, C, scores, mask, counts, st);
+    return launch_gate<float>(fn, x, w, bias, s_up, noise, theta, B, N, C, pool, pooled, scores, mask, counts, st);
+  return launch_gate<__bf16>(fn, x, w, bias, s_up, noise, theta, B, N, C, pool, pooled, scores, mask, counts, st);
 }
 
 extern "C" int spa_gate_select(const void* x, const void* w, float bias, const float* s_up,
@@ -355,6 +380,18 @@ extern "C" int spa_gate_select_gumbel(const void* x, const void* w, float bias, 
   SPA_REQUIRE(noise != nullptr, SPA_ERR_INVALID_ARG, "spa_gate_select_gumbel: noise is null");
   return gate_select_common("spa_gate_select_gumbel", x, w, bias, s_up, noise, temperature, tau, B, N, C, dtype,
                             scores, mask, counts, stream);
+}
+
+extern "C" int spa_gate_select_pooled(const void* x, const void* w, float bias, const float* s_fine,
+                                      float tau, int B, int grid_h, int grid_w, int C, int dtype, float* scores,
+                                      uint8_t* mask, int32_t* counts, float* s_up_pooled, void* stream) {
+  const char* fn = "spa_gate_select_pooled";
+  SPA_REQUIRE(s_fine != nullptr, SPA_ERR_INVALID_ARG, "%s: s_fine is null", fn);
+  SPA_REQUIRE(grid_h >= 1 && grid_w >= 1 && (long)grid_h * grid_w < 2147483647L / 4, SPA_ERR_INVALID_ARG,
+              "%s: grid_h, grid_w must be >= 1", fn);
+  SPA_REQUIRE((reinterpret_cast<uintptr_t>(s_fine) & 7) == 0, SPA_ERR_INVALID_ARG, "%s: s_fine not 8-byte aligned", fn);
+  return gate_select_common(fn, x, w, bias, s_fine, nullptr, 1.f, tau, B, grid_h * grid_w, C, dtype, scores, mask,
+                            counts, stream, PoolGrid{grid_h, grid_w, s_up_pooled}, true);
 }
 
 extern "C" int spa_maxpool2x2(const float* s, int B, int h, int w, float* pooled, void* stream) {

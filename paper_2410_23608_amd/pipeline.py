@@ -115,7 +115,21 @@ class TrainPass:
                                    dtype=torch.uint8, **dv)
         self.ws_gate = torch.empty(max(spa.spa_gate_bwd_workspace_bytes(B, N, C, code), 256), dtype=torch.uint8, **dv)
 
-    def stages(self, x, w, qk, labels, dy) -> List[Tuple[str, Callable[[], None]]]:
+    def stages(self, x, w, qk, labels, dy, noise=None, temperature: float = 1.0
+               ) -> List[Tuple[str, Callable[[], None]]]:
+        """noise [B,N] f32 (logistic variates) switches the selection to the stochastic
+        Gumbel-Softmax form and the gate backward to its straight-through estimator."""
+        st = self._stages(x, w, qk, labels, dy)
+        if noise is None:
+            return st
+        st[0] = ("gate_select_gumbel", spa.spa_gate_select_gumbel(x, w, self.bias, None, noise, temperature, self.tau,
+                                                                  self.scores, self.mask, None, prepare=True))
+        st[-1] = ("gate_bwd_straight_through", spa.spa_gate_bwd_straight_through(
+            x, w, self.bias, self.scores, None, labels, self.d_rg, self.loss_scale, self.mask, noise, temperature,
+            self.loss, self.dx, self.dw, self.db, self.ws_gate, prepare=True))
+        return st
+
+    def _stages(self, x, w, qk, labels, dy) -> List[Tuple[str, Callable[[], None]]]:
         C = self.C
         pq, pk, pv = self.packed_qk[:, :C], self.packed_qk[:, C:], self.packed_v
         dq, dk = self.dqk_packed[:, :C], self.dqk_packed[:, C:]
@@ -243,3 +257,37 @@ class ContainerForwardPass:
         for _, fn in self.stages(x, w, qkv, base):
             fn()
         return self.y
+
+
+class HierarchyPass:
+    """A multi-stage hierarchy (Section 3.1, Section 3.2 on multi-scale scores): every stage
+    runs gate -> pack -> attention + scatter, and from the second stage on the gate takes the
+    previous (2x finer) stage's score map, max-pooled inside the gate kernel, as s_up.
+    Three launches per stage, no host sync anywhere in the chain."""
+
+    def __init__(self, stages):
+        """stages: one (B, grid_h, grid_w, C, H, dtype, tau, bias) tuple per stage, finest
+        first; consecutive grids halve."""
+        self.cfg = list(stages)
+        for (a, b) in zip(self.cfg[:-1], self.cfg[1:]):
+            if a[1] != 2 * b[1] or a[2] != 2 * b[2] or a[0] != b[0]:
+                raise ValueError("consecutive stages must share B and halve the grid")
+        self.passes = [ForwardPass(B, gh * gw, C, H, dtype, tau, bias) for (B, gh, gw, C, H, dtype, tau, bias) in self.cfg]
+        self.s_up = [None] + [torch.empty(c[0], c[1] * c[2], dtype=torch.float32, device="cuda") for c in self.cfg[1:]]
+
+    def stages(self, xs, ws, qkvs, bases=None) -> List[Tuple[str, Callable[[], None]]]:
+        """xs, ws, qkvs: one tensor per stage.  Returns the chain as named prepared launches."""
+        out = []
+        for i, (fp, cfg) in enumerate(zip(self.passes, self.cfg)):
+            st = fp.stages(xs[i], ws[i], qkvs[i], None, None if bases is None else bases[i])
+            if i > 0:
+                st[0] = ("gate_select_pooled", spa.spa_gate_select_pooled(
+                    xs[i], ws[i], fp.bias, self.passes[i - 1].scores, cfg[1], cfg[2], fp.tau, fp.scores, fp.mask,
+                    None, self.s_up[i], prepare=True))
+            out += [(f"s{i + 1}.{name}", fn) for name, fn in st]
+        return out
+
+    def run(self, xs, ws, qkvs, bases=None):
+        for _, fn in self.stages(xs, ws, qkvs, bases):
+            fn()
+        return [fp.y for fp in self.passes]

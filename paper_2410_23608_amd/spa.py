@@ -30,6 +30,8 @@ _SIGNATURES = {
     "spa_version": (c_int, []),
     "spa_last_error": (c_char_p, []),
     "spa_gate_select": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, _P, _P, _P, _P]),
+    "spa_gate_select_pooled": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, c_int, _P, _P, _P, _P,
+                                       _P]),
     "spa_gate_select_gumbel": (c_int, [_P, _P, c_float, _P, _P, c_float, c_float, c_int, c_int, c_int, c_int, _P, _P,
                                        _P, _P]),
     "spa_gate_bwd_straight_through": (c_int, [_P, _P, c_float, _P, _P, _P, _P, c_float, _P, _P, c_float, c_int, c_int,
@@ -148,6 +150,20 @@ def spa_gate_select_gumbel(x, w, bias, s_up, noise, temperature, tau, scores, ma
     return _dispatch(lib.spa_gate_select_gumbel,
                      (_ptr(x), _ptr(w), float(bias), _ptr(s_up), _ptr(noise), float(temperature), float(tau), B, N, C,
                       dtype_code(x), _ptr(scores), _ptr(mask), _ptr(counts), _stream(),), _keep, prepare)
+
+
+def spa_gate_select_pooled(x, w, bias, s_fine, grid_h, grid_w, tau, scores, mask, counts=None, s_up_pooled=None,
+                           prepare=False):
+    """spa_gate_select whose up-scale scores are the 2x2 max-pool of s_fine [B, 2*grid_h*2*grid_w],
+    pooled inside the kernel."""
+    B, N, C = x.shape
+    if N != grid_h * grid_w or s_fine.numel() != 4 * B * N:
+        raise ValueError("x must be [B, grid_h*grid_w, C] and s_fine [B, 4*grid_h*grid_w]")
+    _keep = (x, w, s_fine, scores, mask, counts, s_up_pooled,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_gate_select_pooled,
+                     (_ptr(x), _ptr(w), float(bias), _ptr(s_fine), float(tau), B, int(grid_h), int(grid_w), C,
+                      dtype_code(x), _ptr(scores), _ptr(mask), _ptr(counts), _ptr(s_up_pooled), _stream(),), _keep, prepare)
 
 
 def spa_maxpool2x2(s, h, w, pooled, prepare=False):

@@ -256,3 +256,55 @@ def test_forward_is_run_to_run_bit_stable(spa, pipeline):
         else:
             for a, b in zip(first, snap):
                 assert np.array_equal(a, b)
+
+
+def test_gate_select_pooled_equals_pool_then_gate(spa):
+    """The gate with the 2x2 max-pool folded in against the oracle's composition
+    (maxpool2x2 then gate_scores / select), and bit for bit against the two separate launches."""
+    rng = np.random.default_rng(41)
+    for dtype, (gh, gw), C in (("bf16", (14, 14), 384), ("f32", (5, 9), 64), ("bf16", (7, 7), 768)):
+        B, N = 3, gh * gw
+        mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+        x = mk(rng.standard_normal((B, N, C)).astype(np.float32))
+        w = mk((rng.standard_normal(C) * 2 / np.sqrt(C)).astype(np.float32))
+        s_fine = (rng.standard_normal((B, 4 * N)) * 1.5).astype(np.float32)
+        s_up = orc.maxpool2x2(s_fine, 2 * gh, 2 * gw)
+        s_ref = orc.gate_scores(x, w, 0.1, s_up)
+        mask_ref, _ = orc.select(s_ref, 0.4)
+        near = np.abs(s_ref - orc.threshold_logit(0.4)) < (1e-3 if dtype == "bf16" else 1e-5)
+        xd, wd = dev(x, dtype), dev(w, dtype)
+        sc = torch.empty(B, N, dtype=torch.float32, device="cuda")
+        m = torch.empty(B, N, dtype=torch.uint8, device="cuda")
+        cnt = torch.empty(B, dtype=torch.int32, device="cuda")
+        pooled = torch.empty(B, N, dtype=torch.float32, device="cuda")
+        spa.spa_gate_select_pooled(xd, wd, 0.1, dev(s_fine), gh, gw, 0.4, sc, m, cnt, pooled)
+        sc2, m2, pooled2 = torch.empty_like(sc), torch.empty_like(m), torch.empty_like(pooled)
+        spa.spa_maxpool2x2(dev(s_fine), 2 * gh, 2 * gw, pooled2)
+        spa.spa_gate_select(xd, wd, 0.1, pooled2, 0.4, sc2, m2)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(pooled), s_up.astype(np.float32))         # a max of fp32 values is exact
+        assert np.max(np.abs(host(sc) - s_ref)) <= (1e-3 if dtype == "bf16" else 1e-5)
+        assert np.array_equal(host(m)[~near], mask_ref[~near])
+        assert torch.equal(sc, sc2) and torch.equal(m, m2) and torch.equal(pooled, pooled2)
+        assert np.array_equal(host(cnt), host(m).sum(1).astype(np.int32))
+
+
+def test_hierarchy_pass_matches_stagewise_oracle(spa, pipeline):
+    """HierarchyPass (three launches per stage, pooling inside the gate) against the oracle run
+    stage by stage with max-pooled up-scale scores."""
+    bundles = wlmod.generate_hierarchy(seed=3, B=2)
+    cfg = [(b["workload"].B, *b["workload"].grid, b["workload"].C, b["workload"].H, b["workload"].dtype,
+            b["workload"].tau, b["bias"]) for b in bundles]
+    hp = pipeline.HierarchyPass(cfg)
+    ys = hp.run([dev(b["x"], "bf16") for b in bundles], [dev(b["w"], "bf16") for b in bundles],
+                [dev(b["qkv"], "bf16") for b in bundles])
+    torch.cuda.synchronize()
+    s_up = None
+    for i, bun in enumerate(bundles):
+        wl = bun["workload"]
+        ref = orc.spa_forward(bun["x"], bun["w"], bun["bias"], bun["qkv"], wl.H, wl.tau, wl.dtype, s_up=s_up)
+        assert ref["margin"] > 1e-3
+        fp = hp.passes[i]
+        assert np.array_equal(host(fp.mask), ref["mask"]) and np.array_equal(host(fp.cu_seqlens), ref["cu_seqlens"])
+        assert np.max(np.abs(host(ys[i]) - ref["y"])) <= 2e-2
+        s_up = orc.maxpool2x2(ref["scores"].astype(np.float32), *wl.grid).astype(np.float32)
