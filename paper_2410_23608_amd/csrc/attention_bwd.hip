@@ -94,7 +94,7 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
       for (int e = 0; e < 8; ++e) dpart = fmaf(of[e], gf[e], dpart);
     }
   }
-  const float D = dpart + __shfl_xor(dpart, 32, kWave);
+  const float D = sum_across_halves(dpart);
   // invalid queries: lse = +inf makes every probability 0
   const float lse2 = q_ok ? lse[h * lse_stride + seg.row0 + qi] * kLog2e : INFINITY;
   if (q_ok && hh == 0) dvec[h * lse_stride + seg.row0 + qi] = D;

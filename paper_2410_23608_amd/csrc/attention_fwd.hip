@@ -111,7 +111,7 @@ __device__ __forceinline__ void fwd_softmax_pv(const floatx16 (&s)[GSB], const _
   for (int sb = 0; sb < GSB; ++sb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+  mx = max_across_halves(mx);
   const float m_new = fmaxf(acc.m, mx * scale_log2);
   if (__ballot(m_new != acc.m) != 0) {       // some query's running max moved: rescale
     const float alpha = __builtin_amdgcn_exp2f(acc.m - m_new);
@@ -179,7 +179,7 @@ __device__ __forceinline__ void fwd_process_tile(const __bf16* kbuf, const __bf1
 template <int DH, int RS>
 __device__ __forceinline__ void fwd_park(FwdAcc<DH>& acc, bool q_ok, bool have_keys, __bf16* tile,
                                          float* lse_ptr, int l32, int hh) {
-  const float l_tot = acc.l + __shfl_xor(acc.l, 32, kWave);
+  const float l_tot = sum_across_halves(acc.l);
   const float inv = have_keys ? 1.0f / l_tot : 0.f;
 #pragma unroll
   for (int d = 0; d < DH / 32; ++d)
@@ -424,7 +424,7 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     for (int sb = 0; sb < NSB; ++sb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    mx = max_across_halves(mx);
     const float m_new = fmaxf(acc.m, mx * scale_log2);
     if (__ballot(m_new != acc.m) != 0) {
       const float alpha = __builtin_amdgcn_exp2f(acc.m - m_new);

@@ -90,6 +90,29 @@ __device__ __forceinline__ bf16x8 transposed_frag_rowmajor(const __bf16* rows, i
 __device__ __forceinline__ constexpr int acc_row(int r, int hh) { return 8 * (r / 4) + 4 * hh + (r % 4); }
 
 // ------------------------------------------------------------------ segments and launch order
+// Exchange between lane l and lane l ^ 32 without the LDS crossbar: v_permlane32_swap of a
+// value with itself leaves (x[l % 32], x[l % 32 + 32]) in every lane (lane layout checked on
+// the GPU), so a reduction over the two halves is one swap and one ALU op, identical in both.
+// (The two results are copied to scalars before the bit cast: casting the vector elements in
+// place made the compiler read element 0 twice.)
+__device__ __forceinline__ void swap_halves(float v, float& lo, float& hi) {
+  const unsigned a = __builtin_bit_cast(unsigned, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+  const unsigned r0 = r[0], r1 = r[1];
+  lo = __builtin_bit_cast(float, r0);
+  hi = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ float max_across_halves(float v) {
+  float lo, hi;
+  swap_halves(v, lo, hi);
+  return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float sum_across_halves(float v) {
+  float lo, hi;
+  swap_halves(v, lo, hi);
+  return lo + hi;
+}
+
 struct Segment {
   long row0;   // first packed row of the segment
   int nq;      // query rows to compute
