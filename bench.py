@@ -181,7 +181,9 @@ def main():
         del src, dst
 
     x, w, qkv = up(bun["x"]), up(bun["w"]), up(bun["qkv"])
-    fp = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias)
+    # forward only: y is the result; the packed attention output and lse (inputs of a backward
+    # pass) are not written
+    fp = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False)
     stages = fp.stages(x, w, qkv)
 
     def step():
@@ -205,27 +207,41 @@ def main():
     ev_overhead = empty_pair_us(stages, args.steps, torch)
     b2b_us = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in stages}
     B, N, C, H = wl.B, wl.N, wl.C, wl.H
-    work = {  # algorithmic bytes / flops per launch
-        "gate_select": ("hbm", B * N * (C * e + 5)),
-        "pack": ("hbm", 2 * T * 3 * C * e + 4 * T + 5 * B * N + 4 * (B + 1)),
-        "packed_attention": ("mfma", 4.0 * C * sum_n2),
-        "packed_attention_unpack": ("mfma", 4.0 * C * sum_n2),   # attention + scatter back in one launch
-        "unpack": ("hbm", T * C * e + 4 * B * N + B * N * C * e),
+    attn_flops = 4.0 * C * sum_n2
+    work = {  # algorithmic (flops, bytes) per launch
+        "gate_select": (0.0, B * N * (C * e + 5)),
+        "pack": (0.0, 2 * T * 3 * C * e + 4 * T + 5 * B * N + 4 * (B + 1)),
+        "packed_attention": (attn_flops, T * 3 * C * e + T * C * e + 4 * H * T + 4 * (B + 1)),
+        # attention + scatter back in one launch: q|k|v rows in, every row of y out, the index arrays
+        "packed_attention_unpack": (attn_flops, T * 3 * C * e + B * N * C * e + 4 * T + 4 * B * N + 4 * (B + 1)
+                                    + (T * C * e + 4 * H * T if fp.keep_packed_out else 0)),
+        "unpack": (0.0, T * C * e + 4 * B * N + B * N * C * e),
     }
     work = {k_: v_ for k_, v_ in work.items() if k_ in st_us}
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else 157.3
+    ridge = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9)     # flop per byte at which the two roofs meet
     kernels = {}
-    for nme, (bound, amount) in work.items():
-        # event pairs around each launch inside K steps of the whole path.  The reading
-        # includes the cost of the two event markers (an empty pair reads ev_overhead), so it
-        # never understates the kernel; rocprofv3's kernel-trace average sits a little below.
-        us = st_us[nme]
-        if bound == "hbm":
-            ach, peak, unit = amount / us / 1e3, HBM_PEAK_GBS, "GB/s"
+    for nme, (flops, nbytes) in work.items():
+        # Two live readings, both with HIP events on the launch stream and both upper bounds of
+        # the kernel's duration: an event pair around each launch inside K steps of the whole
+        # path (includes the cost of the two markers; an empty pair reads ev_overhead) and K
+        # back-to-back launches of the kernel between one pair (includes the dispatch gap).
+        # The smaller one is used; rocprofv3's kernel-trace average sits a little below it.
+        us = min(st_us[nme], b2b_us[nme])
+        intensity = flops / nbytes
+        # the roof that bounds the kernel: below the ridge the HBM roof is the lower one
+        if intensity < ridge:
+            bound, ach, peak, unit = "hbm", nbytes / us / 1e3, HBM_PEAK_GBS, "GB/s"
         else:
-            ach, peak, unit = amount / us / 1e6, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+            bound, ach, peak, unit = "mfma" if wl.dtype == "bf16" else "alu", flops / us / 1e6, mfma_peak, "TFLOP/s"
         kernels[nme] = {"bound": bound, "event_us": round(st_us[nme], 2), "kernel_us": round(us, 2),
                         "back_to_back_us": round(b2b_us[nme], 2),
-                        "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)}
+                        "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
+                        "algorithmic_bytes": int(nbytes), "algorithmic_flops": flops,
+                        "flop_per_byte": round(intensity, 1), "ridge_flop_per_byte": round(ridge, 1)}
+        if flops > 0:
+            kernels[nme]["tflops"] = round(flops / us / 1e6, 2)
+            kernels[nme]["mfma_frac"] = round(flops / us / 1e6 / mfma_peak, 4)
     dom = max(kernels, key=lambda k_: kernels[k_]["kernel_us"])
     kd = kernels[dom]
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
@@ -234,8 +250,9 @@ def main():
                 "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
                 "avg_launch_us": kd["kernel_us"],
                 "event_pair_overhead_us": round(ev_overhead, 2)}
-    if wl.dtype == "f32" and dom.startswith("packed_attention"):
-        roofline.update({"bound": "alu", "peak": 157.3, "frac": round(kd["achieved"] / 157.3, 4)})
+    if "tflops" in kd:
+        roofline.update({"flop_per_byte": kd["flop_per_byte"], "ridge_flop_per_byte": kd["ridge_flop_per_byte"],
+                         "tflops": kd["tflops"], "mfma_frac": kd["mfma_frac"]})
 
     result = {
         "metric": "selected tokens/sec (SPA fwd) at 1 GPU", "value": value, "unit": "selected tokens/s",

@@ -28,10 +28,13 @@ class ForwardPass:
     fills the bypassing rows); the results are bit-identical to the two separate calls."""
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
-                 container_len: int = 0, fused_unpack: bool = True):
+                 container_len: int = 0, fused_unpack: bool = True, keep_packed_out: bool = True):
+        """keep_packed_out=False (fused form only): the packed attention output and the
+        log-sum-exp rows, which only a backward pass reads, are not written; y is the result."""
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
         self.tau, self.bias, self.container_len = tau, bias, container_len
         self.fused_unpack = fused_unpack
+        self.keep_packed_out = keep_packed_out or not fused_unpack
         td, cap = _td(dtype), B * N
         dv = dict(device="cuda")
         self.scores = torch.empty(B, N, dtype=torch.float32, **dv)
@@ -60,7 +63,8 @@ class ForwardPass:
             return head + [
                 ("packed_attention_unpack", spa.spa_packed_attention_unpack(
                     q, k, v, self.cu_seqlens, self.gather_idx, self.inv_pos, base, self.H, self.Dh, self.y,
-                    self.out, self.lse, prepare=True)),
+                    self.out if self.keep_packed_out else None, self.lse if self.keep_packed_out else None,
+                    prepare=True)),
             ]
         return head + [
             ("packed_attention", spa.spa_packed_attention(q, k, v, self.cu_seqlens, self.B, self.N, self.H,
