@@ -6,14 +6,14 @@
 // one rounding fewer than multiplying a materialised bf16 r_g.
 //
 // bf16 path: MFMA GEMM, C[M,N] = A[M,K] B[N,K]^T with both operands K-contiguous ("NT").
-// Workgroup tile 128 x 128 x 32, four waves in a 2 x 2 grid, each wave a 64 x 64 block
-// (2 x 2 v_mfma_f32_32x32x16_bf16 tiles), A and B tiles double-buffered in LDS with the
-// next tile's rows in flight in registers.  Row stride 40 elements keeps the 16-byte
+// Workgroup tile 128 x 128 x 64, four waves in a 2 x 2 grid, each wave a 64 x 64 block
+// (2 x 2 v_mfma_f32_32x32x16_bf16 tiles), A and B tiles double-buffered in LDS with two
+// k-tiles of rows in flight in registers.  Row stride 72 elements keeps the 16-byte
 // fragment reads bank-conflict free.  The output tile leaves through LDS as whole rows.
-// Tiles are numbered so that XCD x (= id % 8) owns the M-tiles x, x+8, x+16, ... and walks
-// the N-tiles of one M-tile consecutively: an A tile is fetched into that XCD's L2 once and
-// reused by all its N-tiles, the weights fit in every L2, and the live M-tiles (the row count
-// is only known on the device) spread evenly over the XCDs.
+// The live tiles (the row count is only known on the device) are numbered m-major and cut
+// into 8 equal contiguous ranges, one per XCD (workgroup id % 8): the workgroups that share a
+// block of A rows run on one XCD's L2 and every XCD gets the same number of tiles.
+// Large problems with long k-loops take the 256 x 256 x 64 kernel of linear_big.hip.
 // fp32 path (tiny workload): one thread per output element.
 #include "attn_tiles.h"
 #include "spa_common.h"
@@ -21,6 +21,11 @@
 namespace spa {
 
 constexpr int kGemmBN = 128, kGemmThreads = 256;
+
+// 256 x 256 x 64 tiles (linear_big.hip)
+hipError_t launch_linear_bf16_big(bool gather, bool scale, const void* x, const int32_t* gather_idx,
+                                  const float* gate_scores, const int32_t* total, const void* W, const void* bias,
+                                  int M_cap, int K, int N_out, void* out, long out_row_stride, hipStream_t st);
 
 // Workgroup tile (64 TM) x 128, four waves as 2 x 2, each wave (32 TM) x 64 of the output held
 // as TM x 2 MFMA tiles.  TM = 2: 128 x 128 tiles (more workgroups for small problems);
@@ -39,16 +44,16 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
   __shared__ float a_scale[BM];
   __shared__ float bias_s[BN];     // bias of the tile's output columns (0 past n_out or without bias)
 
-  // m-tiles are dealt round-robin to the XCDs (workgroup id % 8), n fastest within an XCD: the
-  // workgroups that share a block of A rows run on one XCD and find it in that XCD's L2, and
-  // the dead m-tiles past *total spread evenly over the XCDs.
-  const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
-  const int mg = j / n_tiles, nt = j - mg * n_tiles;
-  const int mt = mg * 8 + xcd;
-  if (mt >= m_tiles) return;
+  // Tile order.  Workgroup ids go to the 8 XCDs round-robin (id % 8) and each XCD has its own
+  // L2.  The LIVE tiles (the row count is only known here, on the device) are numbered m-major
+  // and cut into 8 equal contiguous ranges, one per XCD: the workgroups that share a block of A
+  // rows run on one XCD, and every XCD gets the same number of tiles.
   const int M = total != nullptr ? min(total[0], m_cap) : m_cap;
+  const int live_tiles = ((M + BM - 1) / BM) * n_tiles, per_xcd = (live_tiles + 7) >> 3;
+  const int xcd = blockIdx.x & 7, jx = blockIdx.x >> 3, tile_id = xcd * per_xcd + jx;
+  if (jx >= per_xcd || tile_id >= live_tiles) return;
+  const int mt = tile_id / n_tiles, nt = tile_id - mt * n_tiles;
   const int m0 = mt * BM, n0 = nt * BN;
-  if (m0 >= M) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
   const int wm = (wv >> 1) * 32 * TM, wn = (wv & 1) * 64;
@@ -251,9 +256,19 @@ extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const
   SPA_REQUIRE(N_out % 8 == 0 && out_row_stride % 8 == 0, SPA_ERR_INVALID_ARG,
               "%s: N_out and out_row_stride must be multiples of 8 for bf16", fn);
   SPA_REQUIRE(aligned16(x) && aligned16(W) && aligned16(out), SPA_ERR_INVALID_ARG, "%s: x / W / out not 16-byte aligned", fn);
-  // tile shape: 128 x 128 (BK 64) measured faster than 256 x 128 (BK 32) on every projection
-  // shape of the workloads; SPA_GEMM_TM=4 selects the larger tile for experiments
+  // tile shape: 256 x 256 x 64 only where it measured faster than 128 x 128 x 64: long k-loops
+  // and enough tiles that the live ones (about half of the capacity for a packed stream) still
+  // cover most CUs.  SPA_GEMM_TM = 2 | 4 | 8 forces 128 x 128, 256 x 128 or 256 x 256 (tuning aid).
   static const int cfg_env = [] { const char* e = getenv("SPA_GEMM_TM"); return e ? atoi(e) : 0; }();
+  const long tiles_big = (long)((M_cap + 255) / 256) * ((N_out + 255) / 256);
+  const bool big = cfg_env == 8 || (cfg_env == 0 && tiles_big >= 384 && K >= 512);
+  if (big) {
+    const hipError_t e = launch_linear_bf16_big(g, sc, x, gather_idx, gate_scores, total, W, bias, M_cap, K, N_out,
+                                                out, (long)out_row_stride, st);
+    SPA_REQUIRE(e == hipSuccess, SPA_ERR_HIP, "%s: cannot reserve LDS for the 256 x 256 tile: %s", fn,
+                hipGetErrorString(e));
+    return check_launch(fn);
+  }
   const int tm = cfg_env == 4 ? 4 : 2;
   const int bm = 64 * tm;
   const int m_tiles = (M_cap + bm - 1) / bm, n_tiles = (N_out + kGemmBN - 1) / kGemmBN;
