@@ -417,6 +417,25 @@ def main():
             hres["graph_replay_ms_per_chain"] = 1e3 * ghdt / args.steps
         except Exception as ex:
             hres["graph_replay_error"] = str(ex)[:200]
+        # the same hierarchy forward + backward (36 launches)
+        from paper_2410_23608_amd.pipeline import HierarchyTrainPass
+        htp = HierarchyTrainPass(hcfg)
+        hqk = [up(b_["qkv"][:, :, :2 * b_["workload"].C]) for b_ in hb]
+        hlab = [torch.from_numpy(b_["labels"]).cuda() for b_ in hb]
+        hdy = [up(b_["dy"]) for b_ in hb]
+        htstages = htp.stages(hx, hw, hqk, hlab, hdy)
+
+        def htstep():
+            for _, fn in htstages:
+                fn()
+
+        for _ in range(5):
+            htstep()
+        torch.cuda.synchronize()
+        htT = [int(p_.total.item()) for p_ in htp.passes]
+        htdt = timed(htstep, args.steps, torch)
+        hres["fwd_bwd"] = {"launches": len(htstages), "selected_tokens": htT, "ms_per_chain": 1e3 * htdt / args.steps,
+                           "value": sum(htT) * args.steps / htdt, "unit": "selected tokens/s"}
         result["hierarchy"] = hres
 
     if not args.no_cpu_baseline:

@@ -119,11 +119,25 @@ class TrainPass:
                                    dtype=torch.uint8, **dv)
         self.ws_gate = torch.empty(max(spa.spa_gate_bwd_workspace_bytes(B, N, C, code), 256), dtype=torch.uint8, **dv)
 
-    def stages(self, x, w, qk, labels, dy, noise=None, temperature: float = 1.0
+    def stages(self, x, w, qk, labels, dy, noise=None, temperature: float = 1.0, s_fine=None, grid=None
                ) -> List[Tuple[str, Callable[[], None]]]:
         """noise [B,N] f32 (logistic variates) switches the selection to the stochastic
-        Gumbel-Softmax form and the gate backward to its straight-through estimator."""
+        Gumbel-Softmax form and the gate backward to its straight-through estimator.
+        s_fine [B, 4N] f32 with grid = (grid_h, grid_w): the score map of the 2x finer stage of a
+        hierarchy; it is max-pooled inside the gate kernel and the pooled map is the s_up of the
+        gate backward (no gradient to this stage's gate where the up-scale score won)."""
         st = self._stages(x, w, qk, labels, dy)
+        if s_fine is not None:
+            if noise is not None:
+                raise ValueError("s_fine and noise together are not wired up")
+            self.s_up = torch.empty(self.B, self.N, dtype=torch.float32, device="cuda")
+            st[0] = ("gate_select_pooled", spa.spa_gate_select_pooled(
+                x, w, self.bias, s_fine, grid[0], grid[1], self.tau, self.scores, self.mask, None, self.s_up,
+                prepare=True))
+            st[-1] = ("gate_bwd", spa.spa_gate_bwd(x, w, self.bias, self.scores, self.s_up, labels, self.d_rg, True,
+                                                   self.loss_scale, self.loss, self.dx, self.dw, self.db, self.ws_gate,
+                                                   prepare=True))
+            return st
         if noise is None:
             return st
         st[0] = ("gate_select_gumbel", spa.spa_gate_select_gumbel(x, w, self.bias, None, noise, temperature, self.tau,
@@ -295,3 +309,29 @@ class HierarchyPass:
         for _, fn in self.stages(xs, ws, qkvs, bases):
             fn()
         return [fp.y for fp in self.passes]
+
+
+class HierarchyTrainPass:
+    """Forward + backward of every stage of a hierarchy (TrainPass per stage); from the second
+    stage on the gate takes the finer stage's score map (pooled in the gate kernel).  All
+    forwards run first (a stage's gate needs the finer stage's scores), then all backwards.
+    The score map handed down is treated as a constant by the coarser stage's backward."""
+
+    def __init__(self, stages):
+        self.cfg = list(stages)
+        self.passes = [TrainPass(B, gh * gw, C, H, dtype, tau, bias) for (B, gh, gw, C, H, dtype, tau, bias) in self.cfg]
+
+    def stages(self, xs, ws, qks, labels, dys) -> List[Tuple[str, Callable[[], None]]]:
+        fwd, bwd = [], []
+        for i, (tp, cfg) in enumerate(zip(self.passes, self.cfg)):
+            st = tp.stages(xs[i], ws[i], qks[i], labels[i], dys[i],
+                           s_fine=self.passes[i - 1].scores if i > 0 else None, grid=(cfg[1], cfg[2]))
+            n_fwd = 4      # gate, pack_qk, pack_rg, attention + scatter
+            fwd += [(f"s{i + 1}.{n}", f) for n, f in st[:n_fwd]]
+            bwd += [(f"s{i + 1}.{n}", f) for n, f in st[n_fwd:]]
+        return fwd + bwd
+
+    def run(self, xs, ws, qks, labels, dys):
+        for _, fn in self.stages(xs, ws, qks, labels, dys):
+            fn()
+        return [tp.loss for tp in self.passes]

@@ -308,3 +308,43 @@ def test_hierarchy_pass_matches_stagewise_oracle(spa, pipeline):
         assert np.array_equal(host(fp.mask), ref["mask"]) and np.array_equal(host(fp.cu_seqlens), ref["cu_seqlens"])
         assert np.max(np.abs(host(ys[i]) - ref["y"])) <= 2e-2
         s_up = orc.maxpool2x2(ref["scores"].astype(np.float32), *wl.grid).astype(np.float32)
+
+
+def test_hierarchy_training_chain_matches_stagewise_oracle(spa, pipeline):
+    """Forward + backward over the four stages (reduced batch) through HierarchyTrainPass:
+    every stage's selection, attention gradients and gate gradients against the oracle run stage
+    by stage with max-pooled up-scale scores."""
+    bundles = wlmod.generate_hierarchy(seed=4, B=2)
+    cfg = [(b["workload"].B, *b["workload"].grid, b["workload"].C, b["workload"].H, b["workload"].dtype,
+            b["workload"].tau, b["bias"]) for b in bundles]
+    hp = pipeline.HierarchyTrainPass(cfg)
+    qks = [b["qkv"][:, :, :2 * b["workload"].C] for b in bundles]
+    hp.run([dev(b["x"], "bf16") for b in bundles], [dev(b["w"], "bf16") for b in bundles],
+           [dev(q, "bf16") for q in qks], [dev(b["labels"]) for b in bundles], [dev(b["dy"], "bf16") for b in bundles])
+    torch.cuda.synchronize()
+
+    def rel(got, ref):
+        return float(np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref))))
+
+    s_up = None
+    for i, bun in enumerate(bundles):
+        wl, tp = bun["workload"], hp.passes[i]
+        B, N, C, H = wl.B, wl.N, wl.C, wl.H
+        x, w, bias, qk = bun["x"], bun["w"], bun["bias"], qks[i]
+        s = orc.gate_scores(x, w, bias, s_up)
+        mask, margin = orc.select(s, wl.tau)
+        assert margin > 1e-3
+        cu, gidx, inv, T = orc.pack_indices(mask)
+        assert np.array_equal(host(tp.mask), mask) and np.array_equal(host(tp.cu_seqlens), cu)
+        rg = orc.round_to_dtype(orc.sigmoid(s.astype(np.float32).astype(np.float64))[:, :, None] * x, "bf16")
+        dO = bun["dy"].reshape(-1, C)[gidx]
+        rdq, rdk, rdv = orc.attention_backward_per_image(qk[:, :, :C], qk[:, :, C:], rg, mask, dO, H)
+        dqk = host(tp.dqk_packed)
+        assert rel(dqk[:T, :C], rdq) <= 2e-2 and rel(dqk[:T, C:], rdk) <= 2e-2
+        assert rel(host(tp.dv_packed)[:T], rdv) <= 2e-2
+        if s_up is not None:
+            assert np.min(np.abs(orc.gate_only(x, w, bias) - s_up)) > 1e-4      # which side won the max is unambiguous
+        g = orc.gate_backward(x, w, bias, s_up, bun["labels"], orc.unpack(rdv, inv, B, N), True, tp.loss_scale)
+        assert rel(host(tp.dx), g["dx"]) <= 2e-2 and rel(host(tp.dw), g["dw"]) <= 2e-2
+        assert abs(float(host(tp.loss)[0]) - g["loss"]) <= 1e-3 * abs(g["loss"])
+        s_up = orc.maxpool2x2(s.astype(np.float32), *wl.grid).astype(np.float32)
