@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="vit_s", choices=["tiny", "vit_s", "vit_b_train", "det"])
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--streams", type=int, default=3,
+                    help="independent batches in flight, one HIP stream each (1 = one stream, steps back to back)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip graph / padded / training measurements")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -197,8 +199,40 @@ def main():
     n = np.diff(fp.cu_seqlens.cpu().numpy()).astype(np.float64)
     sum_n2 = float((n * n).sum())
 
-    # ---- the timed region: exactly K steps
-    dt = timed(step, args.steps, torch)
+    # ---- one stream, steps back to back: the latency of a step
+    dt1 = timed(step, args.steps, torch)
+    single = {"ms_per_step": 1e3 * dt1 / args.steps, "value": T * args.steps / dt1, "unit": "selected tokens/s"}
+
+    # ---- the timed region: exactly K steps.  The batches of a data-parallel job are independent,
+    # so S of them are kept in flight: S HIP streams (default priority), each with its own copy
+    # of the inputs and its own buffers; steps are dealt round-robin and the launches of a step
+    # stay in order on their stream.
+    S = max(1, args.streams)
+    if S == 1:
+        dt = dt1
+    else:
+        streams = [torch.cuda.Stream() for _ in range(S)]
+        sets = []
+        for s_ in streams:
+            with torch.cuda.stream(s_):
+                fp_s = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False)
+                sets.append((fp_s, fp_s.stages(x.clone(), w.clone(), qkv.clone())))
+        torch.cuda.synchronize()
+        turn = [0]
+
+        def sstep():
+            for _, fn in sets[turn[0] % S][1]:
+                fn()
+            turn[0] += 1
+
+        for _ in range(max(args.warmup, S)):
+            sstep()
+        torch.cuda.synchronize()
+        turn[0] = 0
+        dt = timed(sstep, args.steps, torch)
+        if not all(torch.equal(fs.y, fp.y) and int(fs.total.item()) == T for fs, _ in sets):
+            print("bench.py: a stream's result differs from the single-stream result", file=sys.stderr)
+            sys.exit(1)
     ms_per_step = 1e3 * dt / args.steps
     value = T * args.steps / dt
 
@@ -260,7 +294,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={B} N={N} C={C} H={H} Dh={wl.Dh} {wl.dtype}, selected fraction "
                                f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward select+pack+attention+unpack",
-                   "selected_tokens": T, "sum_n2": sum_n2, "seed": args.seed, "launch": f"eager, {len(stages)} launches per step ({' + '.join(n_ for n_, _ in stages)})"},
+                   "selected_tokens": T, "sum_n2": sum_n2, "seed": args.seed,
+                   "launch": f"eager, {len(stages)} launches per step ({' + '.join(n_ for n_, _ in stages)}); "
+                             f"{S} independent batches in flight on {S} HIP stream(s)", "streams": S},
+        "single_stream": single,
         "roofline": roofline, "kernels": kernels,
     }
 
@@ -320,6 +357,29 @@ def main():
                              "ms_per_step": 1e3 * tdt / args.steps, "selected_tokens": tT,
                              "stage_us": {k_: round(v_, 2) for k_, v_ in tus.items()},
                              "attention_bwd_tflops": round(bwd_flops / tus["packed_attention_bwd"] / 1e6, 2)}
+        if S > 1:   # the training step with S batches in flight, like the forward headline
+            tsets = []
+            for s_ in streams:
+                with torch.cuda.stream(s_):
+                    tp_s = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias)
+                    tsets.append((tp_s, tp_s.stages(tx.clone(), tw.clone(), tqk.clone(), tlab.clone(), tdy.clone())))
+            torch.cuda.synchronize()
+            turn[0] = 0
+
+            def tsstep():
+                for _, fn in tsets[turn[0] % S][1]:
+                    fn()
+                turn[0] += 1
+
+            for _ in range(2 * S):
+                tsstep()
+            torch.cuda.synchronize()
+            turn[0] = 0
+            tsdt = timed(tsstep, args.steps, torch)
+            same = all(torch.equal(ts.dx, tp.dx) and torch.equal(ts.dw, tp.dw) for ts, _ in tsets)
+            result["fwd_bwd"]["batches_in_flight"] = {"streams": S, "value": tT * args.steps / tsdt,
+                                                      "ms_per_step": 1e3 * tsdt / args.steps,
+                                                      "gradients_equal_single_stream": bool(same)}
         # the same step with stochastic Gumbel-Softmax selection and the straight-through backward
         gn = torch.from_numpy(np.random.default_rng(args.seed + 5).logistic(size=(twl.B, twl.N)).astype(np.float32)).cuda()
         gstages = tp.stages(tx, tw, tqk, tlab, tdy, noise=gn, temperature=1.0)
