@@ -130,3 +130,32 @@ def test_block_pass_with_both_projections(spa):
     got = host(y)
     assert np.array_equal(got[mask == 0], x[mask == 0])                   # bypassing tokens are x, bit for bit
     assert np.max(np.abs(got - y_ref)) <= 5e-2
+
+
+def test_linear_packed_empty_and_capped_totals(spa):
+    """*total = 0 writes nothing; *total above the capacity is clamped to it."""
+    rng = np.random.default_rng(5)
+    cap, K, No = 300, 64, 128
+    x = wlmod.round_bf16(rng.standard_normal((cap, K)).astype(np.float32))
+    W = wlmod.round_bf16((rng.standard_normal((No, K)) / 8).astype(np.float32))
+    gi = torch.arange(cap, dtype=torch.int32, device="cuda")
+    for tot, rows in ((0, 0), (10 ** 6, cap), (1, 1), (129, 129)):
+        out = torch.full((cap, No), float("nan"), dtype=torch.bfloat16, device="cuda")
+        spa.spa_linear_packed(dev(x, "bf16"), gi, None, dev(np.array([tot], np.int32)), dev(W, "bf16"), None, out)
+        torch.cuda.synchronize()
+        got = host(out)
+        assert np.all(np.isnan(got[rows:])) and not np.any(np.isnan(got[:rows]))
+        if rows:
+            ref = orc.linear_packed(x, np.arange(rows), W)
+            assert _rel(got[:rows], ref) <= 1e-2
+
+
+def test_linear_packed_rejects_bad_arguments(spa):
+    x = torch.zeros(16, 64, dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros(32, 64, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(16, 32, dtype=torch.bfloat16, device="cuda")
+    sc = torch.zeros(16, device="cuda")
+    with pytest.raises(spa.SpaError):
+        spa.spa_linear_packed(x, None, sc, None, W, None, out)                      # scores without gather_idx
+    with pytest.raises(spa.SpaError):
+        spa.spa_linear_packed(x[:, :60].contiguous(), None, None, None, W[:, :60].contiguous(), None, out)   # K % 8 != 0
