@@ -421,6 +421,22 @@ def main():
             "qkv_projection_tflops": round(2.0 * T * C * 3 * C / bus["qkv_projection"] / 1e6, 1),
             "out_projection_tflops": round(2.0 * T * C * C / bus["out_projection"] / 1e6, 1),
             "dense_projection_flops_saved": round(1.0 - T / (B * N), 3)}
+        # five-launch form: the output projection scatters its rows (plus the residual) itself
+        bp5 = BlockPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, fused_scatter=True)
+        b5 = bp5.stages(x, w, W_qkv, b_qkv, W_o, b_o)
+
+        def b5step():
+            for _, fn in b5:
+                fn()
+
+        for _ in range(5):
+            b5step()
+        torch.cuda.synchronize()
+        b5dt = timed(b5step, args.steps, torch)
+        result["block_with_projections"]["fused_scatter"] = {
+            "outputs_equal_six_launch_form": bool(torch.equal(bp5.y, bp.y)),
+            "launches": [n_ for n_, _ in b5], "ms_per_step": 1e3 * b5dt / args.steps,
+            "out_projection_scatter_us": round(back_to_back_us(b5[-1][1], args.steps, torch), 2)}
 
         # the paper's container mask: containers of L = 7^2 tokens, map shifted by (3, 3)
         side = int(round(N ** 0.5))

@@ -229,12 +229,29 @@ int spa_packed_attention_unpack(const void* q, const void* k, const void* v, int
  * in:  x [*, K] dtype; gather_idx [>= rows] int32 or NULL; gate_scores fp32 indexed by token
  *      or NULL (needs gather_idx); total [1] int32 (device) or NULL (= M_cap rows);
  *      W [N_out, K] dtype (row n = weights of output n); bias [N_out] dtype or NULL.
- *      bf16: K a multiple of 32, N_out and out_row_stride multiples of 8.
+ *      bf16: K, N_out and out_row_stride multiples of 8.
  * out: out[j*out_row_stride + n] dtype; rows >= min(*total, M_cap) are not written.
  */
 int spa_linear_packed(const void* x, const int32_t* gather_idx, const float* gate_scores,
                       const int32_t* total, const void* W, const void* bias, int M_cap, int K,
                       int N_out, int dtype, void* out, int64_t out_row_stride, void* stream);
+
+/*
+ * Output projection of the packed rows with the scatter back and the residual add folded into
+ * the store (Section 3.2: unselected tokens bypass the block; selected tokens receive the
+ * block's output at their original position):
+ *   y[scatter_idx[j], :] = residual[scatter_idx[j], :] + (x[j, :] W^T + bias)   for j < min(*total, M_cap)
+ * Rows of y that no j names are not touched, so with y == residual (the residual stream updated
+ * in place) the bypassing tokens keep their values without any copy.  The bf16 kernel rounds the
+ * projection to bf16 before the residual is added (two roundings, as a separate unpack would).
+ * in:  x [M_cap, K] dtype (packed rows); total [1] int32 (device) or NULL; W [N_out, K], bias
+ *      [N_out] or NULL; scatter_idx [>= rows] int32 (gather_idx of spa_pack: distinct rows);
+ *      residual: same layout as y, or NULL (then y[scatter_idx[j]] = projection only).
+ * out: y[row*y_row_stride + n] dtype; y may alias residual.
+ */
+int spa_linear_packed_scatter(const void* x, const int32_t* total, const void* W, const void* bias,
+                              int M_cap, int K, int N_out, int dtype, const int32_t* scatter_idx,
+                              const void* residual, void* y, int64_t y_row_stride, void* stream);
 
 /* ----------------------------------------------------------------- training ---- */
 

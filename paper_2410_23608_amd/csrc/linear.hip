@@ -35,7 +35,8 @@ __global__ void __launch_bounds__(kGemmThreads)
 linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gather_idx,
                    const float* __restrict__ gate_scores, const int32_t* __restrict__ total,
                    const __bf16* __restrict__ W, const __bf16* __restrict__ bias, int m_cap, int K, int n_out,
-                   __bf16* __restrict__ out, long out_stride, int m_tiles, int n_tiles) {
+                   __bf16* out, long out_stride, int m_tiles, int n_tiles,
+                   const int32_t* __restrict__ scatter_idx, const __bf16* residual) {
   constexpr int BM = 64 * TM, BN = kGemmBN, RS = BK + 8;   // RS = LDS row stride (elements)
   extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];   // 2 x (A tile, B tile)
   __bf16(*As)[BM * RS] = reinterpret_cast<__bf16(*)[BM * RS]>(gemm_smem);
@@ -43,6 +44,7 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
   __shared__ long a_row[BM];       // source row of every tile row (-1 = past the end)
   __shared__ float a_scale[BM];
   __shared__ float bias_s[BN];     // bias of the tile's output columns (0 past n_out or without bias)
+  __shared__ int o_row[BM];        // output row of every tile row when the result is scattered
 
   // Tile order.  Workgroup ids go to the 8 XCDs round-robin (id % 8) and each XCD has its own
   // L2.  The LIVE tiles (the row count is only known here, on the device) are numbered m-major
@@ -68,6 +70,7 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
     }
     a_row[t] = src;
     a_scale[t] = sc;
+    o_row[t] = scatter_idx != nullptr && r < M ? scatter_idx[r] : r;
   }
   if (tid < BN) bias_s[tid] = bias != nullptr && n0 + tid < n_out ? static_cast<float>(bias[n0 + tid]) : 0.f;
   __syncthreads();
@@ -198,8 +201,13 @@ linear_bf16_kernel(const __bf16* __restrict__ x, const int32_t* __restrict__ gat
     for (int i = lane; i < 64 * 8; i += 64) {
       const int r = i >> 3, c = i & 7;
       const int m = m0 + wm + half * 64 + r, n = n0 + wn + c * 8;
-      if (m < M && n < n_out)
-        *reinterpret_cast<bf16x8*>(out + (long)m * out_stride + n) = *reinterpret_cast<const bf16x8*>(&tile[r * ORS + c * 8]);
+      if (m < M && n < n_out) {
+        const long off = (long)o_row[wm + half * 64 + r] * out_stride + n;
+        bf16x8 val = *reinterpret_cast<const bf16x8*>(&tile[r * ORS + c * 8]);
+        if (residual != nullptr)
+          val = float_to_bf16x8(bf16x8_to_float(val) + bf16x8_to_float(*reinterpret_cast<const bf16x8*>(residual + off)));
+        *reinterpret_cast<bf16x8*>(out + off) = val;
+      }
     }
     __syncthreads();
   }
@@ -210,7 +218,7 @@ __global__ void __launch_bounds__(256)
 linear_f32_kernel(const float* __restrict__ x, const int32_t* __restrict__ gather_idx,
                   const float* __restrict__ gate_scores, const int32_t* __restrict__ total,
                   const float* __restrict__ W, const float* __restrict__ bias, int m_cap, int K, int n_out,
-                  float* __restrict__ out, long out_stride) {
+                  float* out, long out_stride, const int32_t* __restrict__ scatter_idx, const float* residual) {
   const int M = total != nullptr ? min(total[0], m_cap) : m_cap;
   const long work = (long)M * n_out;
   for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < work; i += (long)gridDim.x * blockDim.x) {
@@ -221,7 +229,8 @@ linear_f32_kernel(const float* __restrict__ x, const int32_t* __restrict__ gathe
     const float* wr = W + (long)n * K;
     float a = 0.f;
     for (int kq = 0; kq < K; ++kq) a = fmaf(sc * xr[kq], wr[kq], a);
-    out[(long)m * out_stride + n] = a + (bias != nullptr ? bias[n] : 0.f);
+    const long off = (long)(scatter_idx != nullptr ? scatter_idx[m] : m) * out_stride + n;
+    out[off] = a + (bias != nullptr ? bias[n] : 0.f) + (residual != nullptr ? residual[off] : 0.f);
   }
 }
 
@@ -229,10 +238,10 @@ linear_f32_kernel(const float* __restrict__ x, const int32_t* __restrict__ gathe
 
 using namespace spa;
 
-extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const float* gate_scores,
-                                 const int32_t* total, const void* W, const void* bias, int M_cap, int K,
-                                 int N_out, int dtype, void* out, int64_t out_row_stride, void* stream) {
-  const char* fn = "spa_linear_packed";
+static int linear_common(const char* fn, const void* x, const int32_t* gather_idx, const float* gate_scores,
+                         const int32_t* total, const void* W, const void* bias, int M_cap, int K, int N_out,
+                         int dtype, void* out, int64_t out_row_stride, const int32_t* scatter_idx,
+                         const void* residual, void* stream) {
   SPA_REQUIRE(x && W && out, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(M_cap >= 1 && K >= 1 && N_out >= 1, SPA_ERR_INVALID_ARG, "%s: M_cap, K, N_out must be >= 1", fn);
   SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
@@ -247,7 +256,7 @@ extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const
 #define SPA_LIN_F32(G_, S_)                                                                                   \
   hipLaunchKernelGGL((linear_f32_kernel<G_, S_>), dim3((unsigned)wgs), dim3(256), 0, st, (const float*)x,    \
                      gather_idx, gate_scores, total, (const float*)W, (const float*)bias, M_cap, K, N_out,   \
-                     (float*)out, (long)out_row_stride)
+                     (float*)out, (long)out_row_stride, scatter_idx, (const float*)residual)
     if (g && sc) SPA_LIN_F32(true, true); else if (g) SPA_LIN_F32(true, false); else SPA_LIN_F32(false, false);
 #undef SPA_LIN_F32
     return check_launch(fn);
@@ -261,7 +270,8 @@ extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const
   // cover most CUs.  SPA_GEMM_TM = 2 | 4 | 8 forces 128 x 128, 256 x 128 or 256 x 256 (tuning aid).
   static const int cfg_env = [] { const char* e = getenv("SPA_GEMM_TM"); return e ? atoi(e) : 0; }();
   const long tiles_big = (long)((M_cap + 255) / 256) * ((N_out + 255) / 256);
-  const bool big = cfg_env == 8 || (cfg_env == 0 && tiles_big >= 384 && K >= 512);
+  const bool plain_out = scatter_idx == nullptr && residual == nullptr;
+  const bool big = plain_out && (cfg_env == 8 || (cfg_env == 0 && tiles_big >= 384 && K >= 512));
   if (big) {
     const hipError_t e = launch_linear_bf16_big(g, sc, x, gather_idx, gate_scores, total, W, bias, M_cap, K, N_out,
                                                 out, (long)out_row_stride, st);
@@ -282,7 +292,8 @@ extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const
     SPA_REQUIRE(attr == hipSuccess, SPA_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, smem);            \
     hipLaunchKernelGGL((linear_bf16_kernel<G_, S_, BK_, TM_>), dim3(grid), dim3(kGemmThreads), smem, st,      \
                        (const __bf16*)x, gather_idx, gate_scores, total, (const __bf16*)W, (const __bf16*)bias, \
-                       M_cap, K, N_out, (__bf16*)out, (long)out_row_stride, m_tiles, n_tiles);                \
+                       M_cap, K, N_out, (__bf16*)out, (long)out_row_stride, m_tiles, n_tiles, scatter_idx,     \
+                       (const __bf16*)residual);                                                              \
   } while (0)
 #define SPA_LIN_BF16_CFG(BK_, TM_)                                                                            \
   do {                                                                                                        \
@@ -293,4 +304,21 @@ extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const
 #undef SPA_LIN_BF16_CFG
 #undef SPA_LIN_BF16
   return check_launch(fn);
+}
+
+extern "C" int spa_linear_packed(const void* x, const int32_t* gather_idx, const float* gate_scores,
+                                 const int32_t* total, const void* W, const void* bias, int M_cap, int K,
+                                 int N_out, int dtype, void* out, int64_t out_row_stride, void* stream) {
+  return linear_common("spa_linear_packed", x, gather_idx, gate_scores, total, W, bias, M_cap, K, N_out, dtype, out,
+                       out_row_stride, nullptr, nullptr, stream);
+}
+
+extern "C" int spa_linear_packed_scatter(const void* x, const int32_t* total, const void* W, const void* bias,
+                                         int M_cap, int K, int N_out, int dtype, const int32_t* scatter_idx,
+                                         const void* residual, void* y, int64_t y_row_stride, void* stream) {
+  const char* fn = "spa_linear_packed_scatter";
+  SPA_REQUIRE(scatter_idx != nullptr, SPA_ERR_INVALID_ARG, "%s: scatter_idx is null", fn);
+  SPA_REQUIRE(aligned16(residual), SPA_ERR_INVALID_ARG, "%s: residual not 16-byte aligned", fn);
+  return linear_common(fn, x, nullptr, nullptr, total, W, bias, M_cap, K, N_out, dtype, y, y_row_stride, scatter_idx,
+                       residual, stream);
 }

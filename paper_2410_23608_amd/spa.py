@@ -46,6 +46,7 @@ _SIGNATURES = {
     "spa_packed_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
                                             c_int, c_int, c_float, _P, _P, _P, _P]),
     "spa_linear_packed": (c_int, [_P, _P, _P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, c_int64, _P]),
+    "spa_linear_packed_scatter": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, _P, _P, c_int64, _P]),
     "spa_unpack": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_unpack_bwd": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_pack_bwd": (c_int, [_P, _P, c_int, c_int, c_int, c_int, _P, _P]),
@@ -257,6 +258,19 @@ def spa_linear_packed(x, gather_idx, gate_scores, total, W, bias, out, prepare=F
     return _dispatch(lib.spa_linear_packed,
                      (_ptr(x), _ptr(gather_idx), _ptr(gate_scores), _ptr(total), _ptr(W), _ptr(bias), out.shape[0], K,
                       N_out, dtype_code(x), _ptr(out), _row_stride(out), _stream(),), _keep + (out,), prepare)
+
+
+def spa_linear_packed_scatter(x, total, W, bias, scatter_idx, residual, y, prepare=False):
+    """y[scatter_idx[j]] = residual[scatter_idx[j]] + x[j] W^T + bias for j < *total.  x [rows, K] packed,
+    y / residual [*, N_out] (any leading shape, contiguous); y may be residual itself."""
+    K, N_out = x.shape[-1], W.shape[0]
+    if y.shape[-1] != N_out or (residual is not None and residual.shape != y.shape):
+        raise ValueError("y (and residual) must be [..., N_out]")
+    _keep = (x, total, W, bias, scatter_idx, residual, y,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_linear_packed_scatter,
+                     (_ptr(x), _ptr(total), _ptr(W), _ptr(bias), x.shape[0], K, N_out, dtype_code(x), _ptr(scatter_idx),
+                      _ptr(residual), _ptr(y), N_out, _stream(),), _keep, prepare)
 
 
 def spa_unpack(packed_out, inv_pos, base, y, prepare=False):

@@ -159,3 +159,62 @@ def test_linear_packed_rejects_bad_arguments(spa):
         spa.spa_linear_packed(x, None, sc, None, W, None, out)                      # scores without gather_idx
     with pytest.raises(spa.SpaError):
         spa.spa_linear_packed(x[:, :60].contiguous(), None, None, None, W[:, :60].contiguous(), None, out)   # K % 8 != 0
+
+
+@pytest.mark.parametrize("dtype,K,No", [("bf16", 384, 384), ("bf16", 96, 200), ("f32", 64, 48)])
+@pytest.mark.parametrize("with_residual", [False, True])
+def test_linear_packed_scatter_matches_oracle(spa, dtype, K, No, with_residual):
+    """y[scatter_idx[j]] = residual[...] + x[j] W^T + bias against the oracle's projection followed
+    by its scatter back; rows that no j names stay as they were."""
+    rng = np.random.default_rng(K + No)
+    B, N = 3, 150
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    mask = (rng.random((B, N)) < 0.5).astype(np.uint8)
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    cap = B * N
+    xp = mk(rng.standard_normal((cap, K)).astype(np.float32))                 # packed rows (first T used)
+    W = mk((rng.standard_normal((No, K)) / np.sqrt(K)).astype(np.float32))
+    b = mk((rng.standard_normal(No) * 0.1).astype(np.float32))
+    res = mk(rng.standard_normal((B, N, No)).astype(np.float32))
+    proj = orc.linear_packed(xp, np.arange(T), W, b)
+    if dtype == "bf16":
+        proj = orc.round_to_dtype(proj, "bf16")                               # the kernel rounds before the add
+    y_ref = orc.unpack(proj, inv, B, N, base=res if with_residual else None)
+    td = tdtype(dtype)
+    gi = torch.zeros(cap, dtype=torch.int32, device="cuda")
+    gi[:T] = dev(gidx)
+    tot = dev(np.array([T], np.int32))
+    canary = 123.0
+    y = torch.full((B, N, No), canary, dtype=td, device="cuda")
+    spa.spa_linear_packed_scatter(dev(xp, dtype), tot, dev(W, dtype), dev(b, dtype), gi,
+                                  dev(res, dtype) if with_residual else None, y)
+    torch.cuda.synchronize()
+    got = host(y)
+    sel = mask.astype(bool)
+    assert np.all(got[~sel] == canary)                                        # untouched rows
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    assert np.max(np.abs(got[sel] - y_ref[sel])) <= tol * max(1.0, np.max(np.abs(y_ref)))
+    if with_residual:                                                         # in place on the residual stream
+        y2 = dev(res, dtype).clone()
+        spa.spa_linear_packed_scatter(dev(xp, dtype), tot, dev(W, dtype), dev(b, dtype), gi, y2, y2)
+        torch.cuda.synchronize()
+        g2 = host(y2)
+        assert np.array_equal(g2[sel], got[sel]) and np.array_equal(g2[~sel], res[~sel])
+
+
+def test_block_pass_in_place_equals_six_launch_form(spa):
+    """BlockPass(in_place=True) (output projection scatters into the residual stream) gives the
+    same bits as the six-launch form with its separate scatter."""
+    from paper_2410_23608_amd.pipeline import BlockPass
+    wl = dataclasses.replace(wlmod.WORKLOADS["vit_s"], B=7)
+    B, N, C, H = wl.B, wl.N, wl.C, wl.H
+    bun = wlmod.generate(wl, 33, with_qkv=False)
+    rng = np.random.default_rng(33)
+    mkw = lambda *shape: wlmod.round_bf16((rng.standard_normal(shape) / np.sqrt(C)).astype(np.float32))
+    Wqkv, bqkv, Wo, bo = (dev(a, "bf16") for a in (mkw(3 * C, C), mkw(3 * C), mkw(C, C), mkw(C)))
+    x, w = dev(bun["x"], "bf16"), dev(bun["w"], "bf16")
+    y6 = BlockPass(B, N, C, H, "bf16", wl.tau, bun["bias"]).run(x, w, Wqkv, bqkv, Wo, bo).clone()
+    x5 = x.clone()
+    y5 = BlockPass(B, N, C, H, "bf16", wl.tau, bun["bias"], in_place=True).run(x5, w, Wqkv, bqkv, Wo, bo)
+    torch.cuda.synchronize()
+    assert y5.data_ptr() == x5.data_ptr() and torch.equal(y5, y6)
