@@ -276,8 +276,10 @@ __device__ __forceinline__ void load_q_frags(const __bf16* qrow, bool q_ok, int 
 // LDS in tiles of BN keys, double-buffered: while a tile is consumed the next one is already
 // in flight from global memory into registers, and is written to the other LDS buffer
 // before the single barrier that ends the iteration.
+// Head dim 32 is compiled for three waves per SIMD (168 registers, no spills): with several
+// batches in flight the third wave fills the softmax stalls of the other two.
 template <int DH, int NW, int BN>
-__global__ void __launch_bounds__(64 * NW)
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(DH == 32 ? 3 : 2)))
 attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                            const __bf16* __restrict__ v, long qs, long ks, long vs,
                            const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
