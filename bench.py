@@ -65,15 +65,17 @@ def timed(fn, steps, torch):
     return time.perf_counter() - t0
 
 
-def per_stage_us(stages, steps, torch):
+def per_stage_us(stage_sets, steps, torch):
     """Average duration of every stage, from event pairs recorded on the launch stream
-    around each launch of the timed steps."""
-    names = [n for n, _ in stages]
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in stages]
+    around each launch of the timed steps.  stage_sets: one list of (name, launch) per
+    independent copy of the inputs and buffers; step i runs on copy i % len(stage_sets), so
+    with enough copies every launch finds its inputs out of the last-level cache."""
+    names = [n for n, _ in stage_sets[0]]
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in names]
           for _ in range(steps)]
     torch.cuda.synchronize()
     for s in range(steps):
-        for i, (_, fn) in enumerate(stages):
+        for i, (_, fn) in enumerate(stage_sets[s % len(stage_sets)]):
             a, b = ev[s][i]
             a.record()
             fn()
@@ -85,7 +87,7 @@ def per_stage_us(stages, steps, torch):
     return out
 
 
-def empty_pair_us(stages, steps, torch):
+def empty_pair_us(stages, steps, torch):  # noqa: D401
     """What an event pair reads with NO launch between its two records, measured in the same
     position (inside steps of the whole path): the part of a per-launch reading that is not
     kernel time."""
@@ -103,15 +105,46 @@ def empty_pair_us(stages, steps, torch):
 
 def back_to_back_us(fn, steps, torch):
     """Average duration of one launch when the same kernel is enqueued `steps` times between
-    two events (no per-launch event overhead)."""
+    two events (no per-launch event overhead).  fn may be a list of launches of the same kernel
+    on independent copies of its data, used round-robin."""
+    fns = fn if isinstance(fn, (list, tuple)) else [fn]
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     a.record()
-    for _ in range(steps):
-        fn()
+    for i in range(steps):
+        fns[i % len(fns)]()
     b.record()
     torch.cuda.synchronize()
     return 1e3 * a.elapsed_time(b) / steps
+
+
+def ceilings(spa, torch):
+    """Achievable ceilings measured on this machine with the library's yardstick kernels: a plain
+    streaming copy whose buffers rotate through 1 GiB (every launch misses the last-level cache)
+    and an MFMA-only loop."""
+    nbuf, nbytes = 8, 64 << 20
+    src = [torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1) for _ in range(nbuf)]
+    dst = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(nbuf)]
+    copies = [spa.spa_ceiling_copy(a, b, prepare=True) for a, b in zip(src, dst)]
+    for c in copies:
+        c()
+    us = back_to_back_us(copies, 64, torch)
+    copy_gbs = 2.0 * nbytes / us / 1e3
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    best = 0.0
+    for wps in (1, 2):
+        flops = spa.spa_ceiling_mfma(sink, wps, 4096)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            spa.spa_ceiling_mfma(sink, wps, 4096)
+        b.record()
+        torch.cuda.synchronize()
+        best = max(best, 5 * flops / (a.elapsed_time(b) * 1e-3) / 1e12)
+    del src, dst
+    return {"copy_GBs": round(copy_gbs, 1), "copy": "64 MiB read + 64 MiB written per launch, 8 buffer pairs in rotation",
+            "mfma_bf16_TFLOPs": round(best, 1), "mfma": "v_mfma_f32_32x32x16_bf16 only, 4 chains per wave, best of 1 and 2 waves per SIMD"}
 
 
 def graph_replay_s(make_step, steps, torch):
@@ -199,47 +232,55 @@ def main():
     n = np.diff(fp.cu_seqlens.cpu().numpy()).astype(np.float64)
     sum_n2 = float((n * n).sum())
 
-    # ---- one stream, steps back to back: the latency of a step
+    # ---- one stream, steps back to back on ONE copy of the batch (everything stays in the
+    # 256 MB last-level cache): the latency of a step
     dt1 = timed(step, args.steps, torch)
-    single = {"ms_per_step": 1e3 * dt1 / args.steps, "value": T * args.steps / dt1, "unit": "selected tokens/s"}
+    single = {"ms_per_step": 1e3 * dt1 / args.steps, "value": T * args.steps / dt1, "unit": "selected tokens/s",
+              "cache": "warm (one copy of the batch, reused every step)"}
 
     # ---- the timed region: exactly K steps.  The batches of a data-parallel job are independent,
-    # so S of them are kept in flight: S HIP streams (default priority), each with its own copy
-    # of the inputs and its own buffers; steps are dealt round-robin and the launches of a step
-    # stay in order on their stream.
+    # so S of them are kept in flight: S HIP streams (default priority), steps dealt round-robin,
+    # the launches of a step in order on their stream.  Every step works on its own copy of the
+    # inputs and its own buffers, and there are enough copies (> 512 MB in total) that no step
+    # finds its inputs or a previous step's buffers in the last-level cache.
     S = max(1, args.streams)
-    if S == 1:
-        dt = dt1
-    else:
-        streams = [torch.cuda.Stream() for _ in range(S)]
-        sets = []
-        for s_ in streams:
-            with torch.cuda.stream(s_):
-                fp_s = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False)
-                sets.append((fp_s, fp_s.stages(x.clone(), w.clone(), qkv.clone())))
-        torch.cuda.synchronize()
-        turn = [0]
+    set_bytes = (x.numel() + qkv.numel() + fp.packed_qkv.numel() + fp.y.numel()) * e
+    n_sets = S * max(2, -(-(512 << 20) // (S * set_bytes)))
+    streams = [torch.cuda.Stream() for _ in range(S)] if S > 1 else [torch.cuda.current_stream()]
+    sets = []
+    for i in range(n_sets):
+        with torch.cuda.stream(streams[i % S]):
+            fp_s = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False)
+            ins = (x.clone(), w.clone(), qkv.clone())
+            sets.append((fp_s, fp_s.stages(*ins), ins))
+    torch.cuda.synchronize()
+    turn = [0]
 
-        def sstep():
-            for _, fn in sets[turn[0] % S][1]:
-                fn()
-            turn[0] += 1
+    def sstep():   # step i -> copy i % n_sets, which lives on stream i % S
+        for _, fn in sets[turn[0] % n_sets][1]:
+            fn()
+        turn[0] += 1
 
-        for _ in range(max(args.warmup, S)):
-            sstep()
-        torch.cuda.synchronize()
-        turn[0] = 0
-        dt = timed(sstep, args.steps, torch)
-        if not all(torch.equal(fs.y, fp.y) and int(fs.total.item()) == T for fs, _ in sets):
-            print("bench.py: a stream's result differs from the single-stream result", file=sys.stderr)
-            sys.exit(1)
+    for _ in range(max(args.warmup, n_sets)):
+        sstep()
+    torch.cuda.synchronize()
+    turn[0] = 0
+    dt = timed(sstep, args.steps, torch)
+    if not all(torch.equal(fs.y, fp.y) and int(fs.total.item()) == T for fs, _, _ in sets):
+        print("bench.py: a copy's result differs from the single-stream result", file=sys.stderr)
+        sys.exit(1)
     ms_per_step = 1e3 * dt / args.steps
     value = T * args.steps / dt
 
-    # ---- per-kernel durations, live, events on the launch stream
-    st_us = per_stage_us(stages, args.steps, torch)
+    # ---- per-kernel durations, live, events on the launch stream, the kernel running alone.
+    # cold: the copies of the timed region on ONE stream, in rotation; warm: one copy reused.
+    cold_sets = [fs.stages(*ins) for fs, _, ins in sets]   # the same launches, prepared on this stream
+    st_us = per_stage_us(cold_sets, args.steps, torch)
+    b2b_us = {nme: back_to_back_us([cs[i][1] for cs in cold_sets], args.steps, torch)
+              for i, (nme, _) in enumerate(stages)}
+    warm_us = {nme: min(v_, back_to_back_us(fn, args.steps, torch))
+               for (nme, fn), v_ in zip(stages, per_stage_us([stages], args.steps, torch).values())}
     ev_overhead = empty_pair_us(stages, args.steps, torch)
-    b2b_us = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in stages}
     B, N, C, H = wl.B, wl.N, wl.C, wl.H
     attn_flops = 4.0 * C * sum_n2
     work = {  # algorithmic (flops, bytes) per launch
@@ -268,8 +309,8 @@ def main():
             bound, ach, peak, unit = "hbm", nbytes / us / 1e3, HBM_PEAK_GBS, "GB/s"
         else:
             bound, ach, peak, unit = "mfma" if wl.dtype == "bf16" else "alu", flops / us / 1e6, mfma_peak, "TFLOP/s"
-        kernels[nme] = {"bound": bound, "event_us": round(st_us[nme], 2), "kernel_us": round(us, 2),
-                        "back_to_back_us": round(b2b_us[nme], 2),
+        kernels[nme] = {"bound": bound, "cache": "cold", "event_us": round(st_us[nme], 2), "kernel_us": round(us, 2),
+                        "back_to_back_us": round(b2b_us[nme], 2), "warm_cache_us": round(warm_us[nme], 2),
                         "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
                         "algorithmic_bytes": int(nbytes), "algorithmic_flops": flops,
                         "flop_per_byte": round(intensity, 1), "ridge_flop_per_byte": round(ridge, 1)}
@@ -278,8 +319,14 @@ def main():
             kernels[nme]["mfma_frac"] = round(flops / us / 1e6 / mfma_peak, 4)
     dom = max(kernels, key=lambda k_: kernels[k_]["kernel_us"])
     kd = kernels[dom]
+    ceil_ = ceilings(spa, torch)
+    measured_ceiling = ceil_["copy_GBs"] if kd["bound"] == "hbm" else ceil_["mfma_bf16_TFLOPs"]
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
                 "unit": kd["unit"], "frac": kd["frac"],
+                "cache": f"cold: {n_sets} copies of the batch and its buffers in rotation ({n_sets * set_bytes >> 20} MB)",
+                "warm_cache_frac": round(kd["frac"] * kd["kernel_us"] / kd["warm_cache_us"], 4),
+                "measured_ceiling": measured_ceiling,
+                "frac_of_measured_ceiling": round(kd["achieved"] / measured_ceiling, 4) if kd["bound"] != "alu" else None,
                 "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)) if args.seed == 0 else None,
                 "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
                 "avg_launch_us": kd["kernel_us"],
@@ -296,9 +343,11 @@ def main():
                                f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward select+pack+attention+unpack",
                    "selected_tokens": T, "sum_n2": sum_n2, "seed": args.seed,
                    "launch": f"eager, {len(stages)} launches per step ({' + '.join(n_ for n_, _ in stages)}); "
-                             f"{S} independent batches in flight on {S} HIP stream(s)", "streams": S},
+                             f"{S} independent batches in flight on {S} HIP stream(s); {n_sets} copies of the "
+                             f"inputs and buffers in rotation ({n_sets * set_bytes >> 20} MB, cold last-level cache)",
+                   "streams": S, "copies": n_sets},
         "single_stream": single,
-        "roofline": roofline, "kernels": kernels,
+        "roofline": roofline, "ceilings": ceil_, "kernels": kernels,
     }
 
     if not args.no_extras:

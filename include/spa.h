@@ -352,6 +352,18 @@ int spa_padded_attention(const void* q, const void* k, const void* v, int64_t ro
                          const int32_t* seqlens, int B, int n_pad, int H, int Dh, int dtype,
                          float softmax_scale, void* out, void* stream);
 
+/*
+ * Measurement aids (not part of the method): the yardstick kernels bench.py times on the box to
+ * report achievable ceilings beside the published peaks.
+ * spa_ceiling_copy: dst[0..bytes) = src[0..bytes) with 16-byte accesses (device pointers,
+ * 16-byte aligned, bytes a multiple of 16).
+ * spa_ceiling_mfma: an MFMA-only loop (four independent v_mfma_f32_32x32x16_bf16 chains per
+ * wave, `iters` rounds, `waves_per_simd` waves on every SIMD of 256 CUs); sink [1] fp32 device
+ * (never written).  Returns the flops the launch issues, or -1 on a bad argument.
+ */
+int spa_ceiling_copy(const void* src, void* dst, size_t bytes, void* stream);
+double spa_ceiling_mfma(float* sink, int waves_per_simd, int iters, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import c_char_p, c_float, c_int, c_int64, c_size_t, c_void_p
+from ctypes import c_char_p, c_double, c_float, c_int, c_int64, c_size_t, c_void_p
 from typing import Optional
 
 import torch
@@ -45,6 +45,8 @@ _SIGNATURES = {
     "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
     "spa_packed_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
                                             c_int, c_int, c_float, _P, _P, _P, _P]),
+    "spa_ceiling_copy": (c_int, [_P, _P, c_size_t, _P]),
+    "spa_ceiling_mfma": (c_double, [_P, c_int, c_int, _P]),
     "spa_linear_packed": (c_int, [_P, _P, _P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, c_int64, _P]),
     "spa_linear_packed_scatter": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, _P, _P, c_int64, _P]),
     "spa_unpack": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
@@ -271,6 +273,22 @@ def spa_linear_packed_scatter(x, total, W, bias, scatter_idx, residual, y, prepa
     return _dispatch(lib.spa_linear_packed_scatter,
                      (_ptr(x), _ptr(total), _ptr(W), _ptr(bias), x.shape[0], K, N_out, dtype_code(x), _ptr(scatter_idx),
                       _ptr(residual), _ptr(y), N_out, _stream(),), _keep, prepare)
+
+
+def spa_ceiling_copy(src, dst, prepare=False):
+    """Yardstick: dst = src with the library's plain copy kernel (uint8 / any dtype tensors of equal byte size)."""
+    nbytes = src.numel() * src.element_size()
+    _keep = (src, dst,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_ceiling_copy, (_ptr(src), _ptr(dst), nbytes, _stream(),), _keep, prepare)
+
+
+def spa_ceiling_mfma(sink, waves_per_simd, iters) -> float:
+    """Yardstick: launches the MFMA-only loop; returns the flops issued."""
+    fl = float(lib.spa_ceiling_mfma(_ptr(sink), int(waves_per_simd), int(iters), _stream()))
+    if fl < 0:
+        raise SpaError(-1, lib.spa_last_error().decode())
+    return fl
 
 
 def spa_unpack(packed_out, inv_pos, base, y, prepare=False):
