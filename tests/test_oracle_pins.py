@@ -653,3 +653,26 @@ def test_straight_through_term_is_the_derivative_of_the_relaxed_selection():
     assert np.all(np.sign(extra[mask == 1]) == np.sign(dots[mask == 1]))
     # dw picks the same term up through ds
     np.testing.assert_allclose(with_st["dw"] - without["dw"], (extra[:, :, None] * x).sum(axis=(0, 1)), rtol=1e-10)
+
+
+def test_attention_work_matches_the_papers_complexity_terms():
+    """The score counts that the segment boundaries imply reproduce the attention terms of the
+    paper's complexity formulas on the hand-evaluated example in tests/golden: container
+    segments -> B' 2 L^2 C, all tokens selected with per-image segments -> B 2 N^2 C."""
+    import os
+    golden = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "complexity_worked_example.txt")) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                golden[k] = int(v)
+    C, L = 64, 49
+    cu = np.array([0, 98, 196])                      # two images with 98 selected tokens each: 4 full containers
+    seg = orc.container_segments(cu, L)
+    assert len(seg) - 1 == 4
+    assert int((np.diff(seg).astype(np.int64) ** 2).sum()) * 2 * C == golden["spa_attention_macs"]
+    mask = np.ones((2, 196), np.uint8)               # everything selected: ordinary self-attention per image
+    cu_all, _, _, _ = orc.pack_indices(mask)
+    assert int((np.diff(cu_all).astype(np.int64) ** 2).sum()) * 2 * C == golden["msa_attention_macs"]
+    # bench.py's algorithmic flop count, 4 C sum n^2, is two flops per multiply-accumulate of these terms
+    assert 4 * C * int((np.diff(cu_all).astype(np.int64) ** 2).sum()) == 2 * golden["msa_attention_macs"]
