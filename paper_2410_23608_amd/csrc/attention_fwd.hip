@@ -672,7 +672,8 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
     }
     const char* short_env = std::getenv("SPA_ATTN_FWD_SHORT");      // "whole" | "wave" (tuning aid)
     const bool use_whole = short_env != nullptr && short_env[0] == 'w' && short_env[1] == 'h';
-    if (NW == 0 && n_max <= 256 && !use_whole) {
+    static const int wave_max = [] { const char* e = std::getenv("SPA_ATTN_FWD_WAVE_MAX"); return e ? std::atoi(e) : 256; }();
+    if (NW == 0 && n_max <= wave_max && !use_whole) {
       // short segments: one wave per (image, head, 32 queries)
       const int nqb = (n_max + 31) / 32;
       const dim3 grid(xcd_grid(nqb, H, B));
