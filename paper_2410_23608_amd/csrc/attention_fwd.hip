@@ -348,7 +348,7 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
 
 // Short segments, wave-autonomous.  ONE wave per (image, head, 32-query block), no
 // workgroup barriers, no shared state between waves: the wave streams its segment's K and V
-// rows in steps of 64 keys through a private LDS tile (coalesced 16-byte row loads, the next
+// rows in steps of STEP keys through a private LDS tile (coalesced 16-byte row loads, the next
 // step's rows already in flight in registers), reads K fragments back as MFMA A operands
 // and V fragments through the transposing LDS read, and keeps the online softmax state in
 // registers.  Work units are small (<= n/32 steps each), so the load spreads over all SIMDs

@@ -22,38 +22,6 @@ __device__ __forceinline__ bf16x8 zero_bf16x8() {
   return z;
 }
 
-// Stage `ROWS` rows (row r = global row row0 + r, zero beyond n_valid) of a [*, stride]
-// tensor's head slice into LDS: row-major into `rm` (if kRowMajor) and/or transposed into
-// `tr` (if kTransposed).  Called by all THREADS threads of the workgroup.
-template <int DH, int ROWS, int THREADS, bool kRowMajor, bool kTransposed>
-__device__ __forceinline__ void stage_tile(const __bf16* __restrict__ src, long row0, int n_valid,
-                                           long stride, __bf16* rm, __bf16* tr) {
-  constexpr int CPR = DH / 8;
-  constexpr int RS = DH + 8;
-  constexpr int TS = transposed_stride(ROWS);
-  // one task = one 16-byte chunk column of a PAIR of rows, so that transposed stores are
-  // 4 bytes (two tokens of one head-dim column)
-  constexpr int TASKS = (ROWS / 2) * CPR;
-  for (int i = threadIdx.x; i < TASKS; i += THREADS) {
-    const int c = i % CPR, g = i / CPR;
-    const int r0 = 2 * g;
-    bf16x8 a = zero_bf16x8(), b = zero_bf16x8();
-    if (r0 < n_valid) a = *reinterpret_cast<const bf16x8*>(src + (row0 + r0) * stride + c * 8);
-    if (r0 + 1 < n_valid) b = *reinterpret_cast<const bf16x8*>(src + (row0 + r0 + 1) * stride + c * 8);
-    if (kRowMajor) {
-      *reinterpret_cast<bf16x8*>(&rm[r0 * RS + c * 8]) = a;
-      *reinterpret_cast<bf16x8*>(&rm[(r0 + 1) * RS + c * 8]) = b;
-    }
-    if (kTransposed) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        bf16x2 pr = {a[e], b[e]};
-        *reinterpret_cast<bf16x2*>(&tr[(c * 8 + e) * TS + r0]) = pr;
-      }
-    }
-  }
-}
-
 // A-operand fragment from a transposed tile: head-dim row `d`, the 8 token slots that pair
 // with accumulator registers 8*mf .. 8*mf+7 of a 32x32 tile whose rows are tokens
 // (token = 16*mf + 8*(j/4) + 4*hh + j%4 for slot j of half hh).
