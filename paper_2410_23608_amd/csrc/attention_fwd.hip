@@ -535,13 +535,17 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
 }
 
 // ------------------------------------------------------------------------------- fp32
+// G lanes share one query: lane g takes the keys j = g (mod G) of every tile with its own
+// online-softmax state, the G partial states are merged with a butterfly of shuffles at the
+// end, and every lane writes DH / G of the query's output elements.
 template <int DH>
 __global__ void __launch_bounds__(128)
 attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
                     const float* __restrict__ v, long qs, long ks, long vs, const int32_t* __restrict__ cu,
                     const int32_t* __restrict__ key_lens, int n_pad, int H, float scale,
                     float* __restrict__ out, float* __restrict__ lse, long lse_stride, Scatter sc) {
-  constexpr int BM = 128, BN = 32;
+  constexpr int THREADS = 128, G = 8, BM = THREADS / G, BN = 32, JPL = BN / G, EPL = DH / G;
+  static_assert(EPL % 4 == 0, "every lane writes whole 16-byte pieces");
   __shared__ __attribute__((aligned(16))) float Ks[BN * DH];
   __shared__ __attribute__((aligned(16))) float Vs[BN * DH];
 
@@ -551,12 +555,12 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
   if (sc.y != nullptr) {
     const int per = (sc.N + gridDim.x - 1) / gridDim.x;
     scatter_fill<float, DH>(sc, blockIdx.z, min(sc.N, (int)blockIdx.x * per), min(sc.N, ((int)blockIdx.x + 1) * per), h, C,
-                            threadIdx.x, BM);
+                            threadIdx.x, THREADS);
   }
   const int q0 = blockIdx.x * BM;
   if (q0 >= seg.nq) return;
-  const int tid = threadIdx.x;
-  const int qi = q0 + tid;
+  const int tid = threadIdx.x, g = tid % G;
+  const int qi = q0 + tid / G;
   const bool q_ok = qi < seg.nq;
 
   float qr[DH], o[DH];
@@ -574,7 +578,7 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
 
   for (int kt = 0; kt < seg.nk; kt += BN) {
     __syncthreads();
-    for (int i = tid; i < BN * DH / 4; i += BM) {
+    for (int i = tid; i < BN * DH / 4; i += THREADS) {
       const int r = i / (DH / 4), c = i % (DH / 4);
       floatx4 kv = {0.f, 0.f, 0.f, 0.f}, vv = kv;
       if (kt + r < seg.nk) {
@@ -586,28 +590,56 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
     }
     __syncthreads();
     const int kn = min(BN, seg.nk - kt);
-    float s[BN];
+    float s[JPL];
     float mx = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < BN; ++j) {
-      float acc = 0.f;
+    for (int jj = 0; jj < JPL; ++jj) {
+      const int j = jj * G + g;
+      float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll
-      for (int d = 0; d < DH; ++d) acc = fmaf(qr[d], Ks[j * DH + d], acc);
-      s[j] = j < kn ? acc : -INFINITY;
-      mx = fmaxf(mx, s[j]);
+      for (int d = 0; d < DH; d += 4) {
+        const floatx4 kv = *reinterpret_cast<const floatx4*>(&Ks[j * DH + d]);
+        a0 = fmaf(qr[d], kv[0], a0);
+        a1 = fmaf(qr[d + 1], kv[1], a1);
+        a2 = fmaf(qr[d + 2], kv[2], a2);
+        a3 = fmaf(qr[d + 3], kv[3], a3);
+      }
+      s[jj] = j < kn ? (a0 + a1) + (a2 + a3) : -INFINITY;
+      mx = fmaxf(mx, s[jj]);
     }
     const float m_new = fmaxf(m, mx);
-    const float alpha = expf(m - m_new);
-    l *= alpha;
+    if (m_new > -INFINITY) {          // this lane has seen at least one key
+      const float alpha = expf(m - m_new);
+      l *= alpha;
 #pragma unroll
-    for (int d = 0; d < DH; ++d) o[d] *= alpha;
+      for (int d = 0; d < DH; ++d) o[d] *= alpha;
 #pragma unroll
-    for (int j = 0; j < BN; ++j) {
-      const float p = expf(s[j] - m_new);
-      l += p;
+      for (int jj = 0; jj < JPL; ++jj) {
+        const int j = jj * G + g;
+        const float p = expf(s[jj] - m_new);
+        l += p;
 #pragma unroll
-      for (int d = 0; d < DH; ++d) o[d] = fmaf(p, Vs[j * DH + d], o[d]);
+        for (int d = 0; d < DH; d += 4) {
+          const floatx4 vv = *reinterpret_cast<const floatx4*>(&Vs[j * DH + d]);
+          o[d] = fmaf(p, vv[0], o[d]);
+          o[d + 1] = fmaf(p, vv[1], o[d + 1]);
+          o[d + 2] = fmaf(p, vv[2], o[d + 2]);
+          o[d + 3] = fmaf(p, vv[3], o[d + 3]);
+        }
+      }
+      m = m_new;
     }
+  }
+  // merge the G partial states of the query (all G lanes end with the merged state)
+#pragma unroll
+  for (int off = G / 2; off > 0; off >>= 1) {
+    const float m_o = __shfl_xor(m, off, kWave), l_o = __shfl_xor(l, off, kWave);
+    const float m_new = fmaxf(m, m_o);
+    const float a = m > -INFINITY ? expf(m - m_new) : 0.f;
+    const float b = m_o > -INFINITY ? expf(m_o - m_new) : 0.f;
+    l = l * a + l_o * b;
+#pragma unroll
+    for (int d = 0; d < DH; ++d) o[d] = o[d] * a + __shfl_xor(o[d], off, kWave) * b;
     m = m_new;
   }
   if (!q_ok) return;
@@ -615,15 +647,16 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
   float* op = out != nullptr ? out + (seg.row0 + qi) * C + h * DH : nullptr;
   const long yoff = sc.y != nullptr ? (long)sc.gather_idx[seg.row0 + qi] * C + h * DH : 0;
 #pragma unroll
-  for (int d = 0; d < DH; d += 4) {
-    floatx4 t = {o[d] * inv, o[d + 1] * inv, o[d + 2] * inv, o[d + 3] * inv};
-    if (op != nullptr) *reinterpret_cast<floatx4*>(op + d) = t;
+  for (int d0 = 0; d0 < DH; d0 += 4) {
+    if (d0 / EPL != g) continue;      // this lane's share of the row
+    floatx4 t = {o[d0] * inv, o[d0 + 1] * inv, o[d0 + 2] * inv, o[d0 + 3] * inv};
+    if (op != nullptr) *reinterpret_cast<floatx4*>(op + d0) = t;
     if (sc.y != nullptr) {
-      if (sc.base != nullptr) t += *reinterpret_cast<const floatx4*>(static_cast<const float*>(sc.base) + yoff + d);
-      *reinterpret_cast<floatx4*>(static_cast<float*>(sc.y) + yoff + d) = t;
+      if (sc.base != nullptr) t += *reinterpret_cast<const floatx4*>(static_cast<const float*>(sc.base) + yoff + d0);
+      *reinterpret_cast<floatx4*>(static_cast<float*>(sc.y) + yoff + d0) = t;
     }
   }
-  if (lse != nullptr) lse[h * lse_stride + seg.row0 + qi] = seg.nk > 0 ? m + logf(l) : -INFINITY;
+  if (lse != nullptr && g == 0) lse[h * lse_stride + seg.row0 + qi] = seg.nk > 0 ? m + logf(l) : -INFINITY;
 }
 
 // ------------------------------------------------------------------------------- host
@@ -652,7 +685,7 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
   const long lse_stride = (long)B * n_max;
   hipStream_t st = as_stream(stream);
   if (dtype == SPA_F32) {
-    const dim3 grid((n_max + 127) / 128, H, B), block(128);
+    const dim3 grid((n_max + 15) / 16, H, B), block(128);   // 16 queries per workgroup, 8 lanes each
 #define SPA_F32_LAUNCH(D)                                                                                \
   hipLaunchKernelGGL((attn_fwd_f32_kernel<D>), grid, block, 0, st, (const float*)q, (const float*)k,    \
                      (const float*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu, key_lens, n_max, H, scale, (float*)out, lse, \
