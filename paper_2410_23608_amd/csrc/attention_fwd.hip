@@ -10,8 +10,8 @@
 // in the B-operand layout of the second product O^T = V^T P^T — no trip through LDS.
 // K tiles sit in LDS row-major (A operand: 16-byte reads), V tiles are stored transposed.
 //
-// fp32 path (reference-grade, used by the small fp32 workload): one thread per query,
-// K/V tiles broadcast from LDS, plain fp32 FMA.
+// fp32 path (reference-grade, used by the small fp32 workload): eight lanes per query,
+// K/V tiles read from LDS, plain fp32 FMA.
 #include <cmath>
 
 #include <cstdio>
