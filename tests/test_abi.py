@@ -66,3 +66,53 @@ def test_product_package_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle\b|oracle/|spa_oracle", text, flags=re.M), f
+
+
+def test_validation_of_the_wider_entry_points_without_gpu(lib):
+    """Argument checks of the entry points beyond the four hot-path calls answer before any
+    launch (no GPU needed): bad grids, capacities, temperatures, missing index arrays."""
+    lib.spa_last_error.restype = ctypes.c_char_p
+    P, I, F, L = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_int64
+    fake = ctypes.c_void_p(4096)
+
+    lib.spa_pack_shifted.restype = I
+    lib.spa_pack_shifted.argtypes = [P, P, P, P] + [I] * 8 + [P] * 6
+    assert lib.spa_pack_shifted(None, fake, None, None, 1, 0, 4, 1, 1, 8, 1, 0, None, fake, fake, fake, fake, None) == -1
+    assert b"grid_h" in lib.spa_last_error()
+
+    lib.spa_container_segments_capacity.restype = L
+    lib.spa_container_segments_capacity.argtypes = [I, L, I]
+    assert lib.spa_container_segments_capacity(64, 12544, 49) == 64 + 12544 // 49
+    assert lib.spa_container_segments_capacity(0, 10, 4) == -1
+    lib.spa_container_segments.restype = I
+    lib.spa_container_segments.argtypes = [P, I, I, L, I, P, P, P]
+    assert lib.spa_container_segments(fake, 4, 7, 100, 4 + 100 // 7 - 1, fake, fake, None) == -3     # one short
+    assert b"seg_cap" in lib.spa_last_error()
+    assert lib.spa_container_segments(fake, 4, 0, 100, 64, fake, fake, None) == -1
+
+    lib.spa_gate_select_gumbel.restype = I
+    lib.spa_gate_select_gumbel.argtypes = [P, P, F, P, P, F, F] + [I] * 4 + [P] * 4
+    assert lib.spa_gate_select_gumbel(fake, fake, 0.0, None, None, 1.0, 0.5, 1, 1, 8, 0, fake, fake, None, None) == -1
+    assert b"noise" in lib.spa_last_error()
+    assert lib.spa_gate_select_gumbel(fake, fake, 0.0, None, fake, -1.0, 0.5, 1, 1, 8, 0, fake, fake, None, None) == -1
+    assert b"temperature" in lib.spa_last_error()
+
+    lib.spa_gate_select_pooled.restype = I
+    lib.spa_gate_select_pooled.argtypes = [P, P, F, P, F] + [I] * 5 + [P] * 5
+    assert lib.spa_gate_select_pooled(fake, fake, 0.0, None, 0.5, 1, 2, 2, 8, 0, fake, fake, None, None, None) == -1
+    assert b"s_fine" in lib.spa_last_error()
+
+    lib.spa_linear_packed.restype = I
+    lib.spa_linear_packed.argtypes = [P] * 6 + [I] * 4 + [P, L, P]
+    assert lib.spa_linear_packed(fake, None, fake, None, fake, None, 8, 64, 64, 1, fake, 64, None) == -1
+    assert b"gather_idx" in lib.spa_last_error()
+    assert lib.spa_linear_packed(fake, None, None, None, fake, None, 8, 60, 64, 1, fake, 64, None) == -2
+    assert b"multiple of 8" in lib.spa_last_error()
+    lib.spa_linear_packed_scatter.restype = I
+    lib.spa_linear_packed_scatter.argtypes = [P] * 4 + [I] * 4 + [P, P, P, L, P]
+    assert lib.spa_linear_packed_scatter(fake, None, fake, None, 8, 64, 64, 1, None, None, fake, 64, None) == -1
+    assert b"scatter_idx" in lib.spa_last_error()
+
+    lib.spa_ceiling_mfma.restype = ctypes.c_double
+    lib.spa_ceiling_mfma.argtypes = [P, I, I, P]
+    assert lib.spa_ceiling_mfma(None, 1, 1, None) == -1.0
