@@ -524,7 +524,21 @@ def main():
                 "segment_capacity": cp.seg_cap, "sum_n2": seg_n2, "value": T * args.steps / cdt,
                 "unit": "selected tokens/s", "ms_per_step": 1e3 * cdt / args.steps,
                 "stage_us": {k_: round(v_, 2) for k_, v_ in cus.items()},
-                "attention_tflops": round(4.0 * C * seg_n2 / cus["packed_attention"] / 1e6, 2)}
+                "attention_tflops": round(4.0 * C * seg_n2 / cus["segment_attention_unpack"] / 1e6, 2)}
+            cp2 = ContainerForwardPass(B, side, side, C, H, wl.dtype, 49, (3, 3), wl.tau, wl.bias, fused_unpack=False)
+            c2 = cp2.stages(x, w, qkv)
+
+            def c2step():
+                for _, fn in c2:
+                    fn()
+
+            for _ in range(5):
+                c2step()
+            torch.cuda.synchronize()
+            c2dt = timed(c2step, args.steps, torch)
+            result["container_local"]["separate_unpack"] = {
+                "outputs_equal": bool(torch.equal(cp2.y, cp.y)), "ms_per_step": 1e3 * c2dt / args.steps,
+                "launches": [n_ for n_, _ in c2]}
 
         # four-stage hierarchy (batch 16, 56^2 .. 7^2 tokens, C 96 .. 768): 12 launches, eager and as one hipGraph
         from paper_2410_23608_amd.pipeline import HierarchyPass

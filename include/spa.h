@@ -218,6 +218,25 @@ int spa_packed_attention_unpack(const void* q, const void* k, const void* v, int
                                 void* stream);
 
 /*
+ * spa_packed_attention_unpack for segments that are not whole images (the container-local
+ * segments of spa_container_segments): attention inside every segment of seg_cu_seqlens and,
+ * in the same launch, the scatter back to y with the fill of the bypassing rows.  Results equal
+ * spa_packed_attention on the segments followed by spa_unpack, bit for bit.
+ * in:  q, k, v, strides, softmax_scale as in spa_packed_attention; seg_cu_seqlens
+ *      [n_segments + 1] int32 (empty segments allowed); max_seqlen >= every segment length;
+ *      gather_idx, inv_pos [rows] int32 from spa_pack / spa_pack_shifted; base [rows, H*Dh]
+ *      dtype or NULL; rows = B*N, the rows of y.
+ * out: y [rows, H*Dh] dtype; out [>= T, H*Dh] dtype or NULL; lse [H, n_segments*max_seqlen]
+ *      fp32 or NULL.  y may alias base.
+ */
+int spa_segment_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                 int64_t k_row_stride, int64_t v_row_stride,
+                                 const int32_t* seg_cu_seqlens, int n_segments, int max_seqlen,
+                                 const int32_t* gather_idx, const int32_t* inv_pos, const void* base,
+                                 int64_t rows, int H, int Dh, int dtype, float softmax_scale, void* out,
+                                 float* lse, void* y, void* stream);
+
+/*
  * Linear projection of packed tokens (the 3 L C^2 / N C^2 terms of the SPA complexity
  * formula, Section 3.2), with the packing gather and the gate scaling optionally folded into
  * the operand load:

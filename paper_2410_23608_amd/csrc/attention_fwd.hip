@@ -32,8 +32,33 @@ struct Scatter {
   const int32_t* inv_pos;      // [B*N] flat token -> packed row or -1
   const void* base;            // [B*N, C] residual or nullptr
   void* y;                     // [B*N, C]
-  int N;                       // tokens per image
+  int N;                       // tokens per image; in flat mode all rows of y (B*N)
+  int flat;                    // 0: segment s fills the bypassing rows of image s (segments are images)
+                               // 1: segments are not images (containers): the rows of y are dealt
+                               //    evenly to all (segment, part) work units
 };
+
+// The rows whose bypass fill falls to work unit (segment `seg` of `nseg`, part `part` of `nparts`):
+// tokens [t0, t1) of image b (flat mode: b = 0 and the range is over all rows of y).
+struct FillRange {
+  int b, t0, t1;
+};
+__device__ __forceinline__ FillRange fill_range(const Scatter& sc, int seg, int nseg, int part, int nparts) {
+  FillRange f = {0, 0, 0};
+  if (sc.y == nullptr) return f;
+  if (!sc.flat) {
+    const int per = (sc.N + nparts - 1) / nparts;
+    f.b = seg;
+    f.t0 = min(sc.N, part * per);
+    f.t1 = min(sc.N, (part + 1) * per);
+  } else {
+    const long units = (long)nseg * nparts, u = (long)seg * nparts + part;
+    const long per = (sc.N + units - 1) / units;
+    f.t0 = (int)min((long)sc.N, u * per);
+    f.t1 = (int)min((long)sc.N, (u + 1) * per);
+  }
+  return f;
+}
 
 // Fill the head slice [h*DH, (h+1)*DH) of the bypassing rows among tokens [t0, t1) of image b.
 // Shared by `nthreads` threads, this one being number `tid` of them.
@@ -299,12 +324,11 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   const long C = (long)H * DH;
   // this workgroup's share of the image's bypassing tokens: filled right away by a
   // workgroup that has no queries, after the main loop by one that has
-  const int fill_per = sc.y != nullptr ? (sc.N + nqb - 1) / nqb : 0;
   const int fill_img = key_lens == nullptr && B > 1 && B <= kLptMaxB ? s_pick : tile_id.rank;
-  const int fill_t0 = min(sc.N, tile_id.qb * fill_per), fill_t1 = min(sc.N, (tile_id.qb + 1) * fill_per);
+  const FillRange fr = fill_range(sc, fill_img, B, tile_id.qb, nqb);
   const int q0 = tile_id.qb * (32 * NW);
   if (q0 >= seg.nq) {
-    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fill_img, fill_t0, fill_t1, h, C, threadIdx.x, 64 * NW);
+    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64 * NW);
     return;
   }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -343,7 +367,7 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   __syncthreads();
   if (wave_live)
     fwd_flush<DH, RS>(tile, out, sc, seg.row0 + q0 + wv * 32, h, C, min(32, seg.nq - q0 - wv * 32), lane);
-  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fill_img, fill_t0, fill_t1, h, C, threadIdx.x, 64 * NW);
+  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64 * NW);
 }
 
 // Short segments, wave-autonomous.  ONE wave per (image, head, 32-query block), no
@@ -372,11 +396,10 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   const Segment seg = segment_of(img, cu, key_lens, n_pad);
   const long C = (long)H * DH;
   // this wave's share of the image's bypassing tokens: at once if it has no queries, else last
-  const int fill_per = sc.y != nullptr ? (sc.N + nqb - 1) / nqb : 0;
-  const int fill_t0 = min(sc.N, tile_id.qb * fill_per), fill_t1 = min(sc.N, (tile_id.qb + 1) * fill_per);
+  const FillRange fr = fill_range(sc, img, B, tile_id.qb, nqb);
   const int q0 = tile_id.qb * 32;
   if (q0 >= seg.nq) {
-    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, img, fill_t0, fill_t1, h, C, threadIdx.x, 64);
+    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64);
     return;
   }
   const int lane = threadIdx.x, l32 = lane & 31, hh = lane >> 5;
@@ -468,7 +491,7 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   fwd_park<DH, RS>(acc, q_ok, seg.nk > 0, Ks, lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr, l32,
                    hh);
   fwd_flush<DH, RS>(Ks, out, sc, seg.row0 + q0, h, C, min(32, seg.nq - q0), lane);
-  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, img, fill_t0, fill_t1, h, C, threadIdx.x, 64);
+  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64);
 }
 
 // Short segments (every segment <= NKMAX keys).  ONE workgroup per (image, head): all K / V
@@ -494,8 +517,9 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   seg.nq = min(seg.nq, NKMAX);   // never index past the LDS tile, whatever cu_seqlens holds
   seg.nk = min(seg.nk, NKMAX);
   const long C = (long)H * DH;
+  const FillRange fr = fill_range(sc, blockIdx.y, gridDim.y, 0, 1);
   if (seg.nq <= 0) {
-    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, blockIdx.y, 0, sc.N, h, C, threadIdx.x, THREADS);
+    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, THREADS);
     return;
   }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -515,7 +539,7 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   // others compute; if every wave has queries (few rows bypass then) all do it at the end
   const int live_threads = ((seg.nq + 31) / 32) * 64;
   if (!wave_live && sc.y != nullptr)
-    scatter_fill<__bf16, DH>(sc, blockIdx.y, 0, sc.N, h, C, threadIdx.x - live_threads, THREADS - live_threads);
+    scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x - live_threads, THREADS - live_threads);
   if (wave_live) {
     for (int kt = 0; kt < seg.nk; kt += TILE) {
       const int rem = seg.nk - kt;
@@ -531,7 +555,7 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   __syncthreads();
   if (wave_live) fwd_flush<DH, RS>(tile, out, sc, seg.row0 + wv * 32, h, C, min(32, seg.nq - wv * 32), lane);
   if (sc.y != nullptr && live_threads >= THREADS)
-    scatter_fill<__bf16, DH>(sc, blockIdx.y, 0, sc.N, h, C, threadIdx.x, THREADS);
+    scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, THREADS);
 }
 
 // ------------------------------------------------------------------------------- fp32
@@ -553,9 +577,8 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
   const Segment seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
   const long C = (long)H * DH;
   if (sc.y != nullptr) {
-    const int per = (sc.N + gridDim.x - 1) / gridDim.x;
-    scatter_fill<float, DH>(sc, blockIdx.z, min(sc.N, (int)blockIdx.x * per), min(sc.N, ((int)blockIdx.x + 1) * per), h, C,
-                            threadIdx.x, THREADS);
+    const FillRange fr = fill_range(sc, blockIdx.z, gridDim.z, blockIdx.x, gridDim.x);
+    scatter_fill<float, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, THREADS);
   }
   const int q0 = blockIdx.x * BM;
   if (q0 >= seg.nq) return;
@@ -782,7 +805,22 @@ extern "C" int spa_packed_attention_unpack(const void* q, const void* k, const v
               "spa_packed_attention_unpack: null pointer");
   SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG,
               "spa_packed_attention_unpack: y / base not 16-byte aligned");
-  const Scatter sc = {gather_idx, inv_pos, base, y, N};
+  const Scatter sc = {gather_idx, inv_pos, base, y, N, 0};
   return attention_common("spa_packed_attention_unpack", q, k, v, q_row_stride, k_row_stride, v_row_stride,
                           cu_seqlens, nullptr, B, N, H, Dh, dtype, softmax_scale, out, lse, sc, stream);
+}
+
+extern "C" int spa_segment_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                            int64_t k_row_stride, int64_t v_row_stride,
+                                            const int32_t* seg_cu_seqlens, int n_segments, int max_seqlen,
+                                            const int32_t* gather_idx, const int32_t* inv_pos, const void* base,
+                                            int64_t rows, int H, int Dh, int dtype, float softmax_scale,
+                                            void* out, float* lse, void* y, void* stream) {
+  const char* fn = "spa_segment_attention_unpack";
+  SPA_REQUIRE(seg_cu_seqlens && gather_idx && inv_pos && y, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+  SPA_REQUIRE(rows >= 1 && rows < 2147483647L, SPA_ERR_INVALID_ARG, "%s: rows must be in [1, 2^31)", fn);
+  SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG, "%s: y / base not 16-byte aligned", fn);
+  const Scatter sc = {gather_idx, inv_pos, base, y, (int)rows, 1};
+  return attention_common(fn, q, k, v, q_row_stride, k_row_stride, v_row_stride, seg_cu_seqlens, nullptr, n_segments,
+                          max_seqlen, H, Dh, dtype, softmax_scale, out, lse, sc, stream);
 }

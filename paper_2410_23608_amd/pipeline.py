@@ -249,11 +249,12 @@ class ContainerForwardPass:
     packed stream is cut into containers of length L and a token attends to the tokens of its
     own image inside its own container; shift = (sh, sw) packs the cyclically shifted map.
 
-      gate_select(x) -> pack_shifted(qkv) -> container_segments -> packed_attention on the
-      image x container segments -> unpack.  Five launches, no host sync."""
+      gate_select(x) -> pack_shifted(qkv) -> container_segments -> attention on the image x
+      container segments + scatter back (one launch; fused_unpack=False: two).  No host sync."""
 
     def __init__(self, B: int, grid_h: int, grid_w: int, C: int, H: int, dtype: str, container_len: int,
-                 shift: Tuple[int, int] = (0, 0), tau: float = 0.5, bias: float = 0.0):
+                 shift: Tuple[int, int] = (0, 0), tau: float = 0.5, bias: float = 0.0, fused_unpack: bool = True):
+        self.fused_unpack = fused_unpack
         N = grid_h * grid_w
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
         self.grid, self.shift, self.L, self.tau, self.bias = (grid_h, grid_w), shift, container_len, tau, bias
@@ -283,11 +284,16 @@ class ContainerForwardPass:
                                                   self.gather_idx, self.inv_pos, self.total, prepare=True)),
             ("container_segments", spa.spa_container_segments(self.cu_seqlens, self.L, self.B * self.N,
                                                               self.seg_cu_seqlens, self.n_segments, prepare=True)),
+        ] + ([
+            ("segment_attention_unpack", spa.spa_segment_attention_unpack(
+                p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.seg_cu_seqlens, self.max_seqlen, self.gather_idx,
+                self.inv_pos, base, self.H, self.Dh, self.y, None, None, prepare=True)),
+        ] if self.fused_unpack else [
             ("packed_attention", spa.spa_packed_attention(p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.seg_cu_seqlens,
                                                           self.seg_cap, self.max_seqlen, self.H, self.Dh, self.out,
                                                           None, prepare=True)),
             ("unpack", spa.spa_unpack(self.out, self.inv_pos, base, self.y, prepare=True)),
-        ]
+        ])
 
     def run(self, x, w, qkv, base=None):
         for _, fn in self.stages(x, w, qkv, base):

@@ -45,6 +45,8 @@ _SIGNATURES = {
     "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
     "spa_packed_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
                                             c_int, c_int, c_float, _P, _P, _P, _P]),
+    "spa_segment_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, _P, _P, _P, c_int64,
+                                             c_int, c_int, c_int, c_float, _P, _P, _P, _P]),
     "spa_ceiling_copy": (c_int, [_P, _P, c_size_t, _P]),
     "spa_ceiling_mfma": (c_double, [_P, c_int, c_int, _P]),
     "spa_linear_packed": (c_int, [_P, _P, _P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, c_int64, _P]),
@@ -248,6 +250,20 @@ def spa_packed_attention_unpack(q, k, v, cu_seqlens, gather_idx, inv_pos, base, 
                      (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(cu_seqlens),
                       _ptr(gather_idx), _ptr(inv_pos), _ptr(base), B, N, H, Dh, dtype_code(y), float(softmax_scale),
                       _ptr(out), _ptr(lse), _ptr(y), _stream(),), _keep, prepare)
+
+
+def spa_segment_attention_unpack(q, k, v, seg_cu_seqlens, max_seqlen, gather_idx, inv_pos, base, H, Dh, y, out=None,
+                                 lse=None, softmax_scale=0.0, prepare=False):
+    """Attention inside the segments of seg_cu_seqlens (not necessarily whole images) + scatter
+    back to y [B,N,C] in one launch."""
+    rows = y.numel() // y.shape[-1]
+    n_segments = seg_cu_seqlens.numel() - 1
+    _keep = (seg_cu_seqlens, gather_idx, inv_pos, base, y, out, lse,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_segment_attention_unpack,
+                     (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(seg_cu_seqlens),
+                      n_segments, int(max_seqlen), _ptr(gather_idx), _ptr(inv_pos), _ptr(base), rows, H, Dh,
+                      dtype_code(y), float(softmax_scale), _ptr(out), _ptr(lse), _ptr(y), _stream(),), _keep, prepare)
 
 
 def spa_linear_packed(x, gather_idx, gate_scores, total, W, bias, out, prepare=False):

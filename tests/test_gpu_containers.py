@@ -196,3 +196,42 @@ def test_shift_changes_container_partners_but_not_membership(spa):
     sel = np.flatnonzero(inv0[:N] >= 0)
     pairs = [(a, b) for a in sel[:40] for b in sel[:40] if a < b]
     assert any(same_container(inv0, a, b) != same_container(inv1, a, b) for a, b in pairs)
+
+
+@pytest.mark.parametrize("dtype,B,gh,gw,C,H,L", [("bf16", 6, 14, 14, 384, 6, 49), ("bf16", 2, 20, 30, 256, 8, 49),
+                                                 ("f32", 3, 6, 7, 64, 2, 9), ("bf16", 2, 30, 30, 64, 2, 400)])
+@pytest.mark.parametrize("with_base", [False, True])
+def test_segment_attention_unpack_equals_two_calls(spa, dtype, B, gh, gw, C, H, L, with_base):
+    """Attention on container segments + scatter back in one launch gives the bits of
+    spa_packed_attention on the segments followed by spa_unpack."""
+    rng = np.random.default_rng(L + C + B)
+    N, Dh, cap = gh * gw, C // H, B * gh * gw
+    mk = (lambda a: wlmod.round_bf16(a.astype(np.float32))) if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    qkv = dev(mk(rng.standard_normal((B, N, 3 * C))), dtype)
+    base = dev(mk(rng.standard_normal((B, N, C))), dtype) if with_base else None
+    mask = (rng.random((B, N)) < rng.uniform(0.1, 0.9, size=(B, 1))).astype(np.uint8)
+    mask[0] = 0
+    td = tdtype(dtype)
+    cu_d, g_d, inv_d, tot = _ints(B + 1), _ints(cap), _ints(cap), _ints(1)
+    packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    seg_cap = spa.spa_container_segments_capacity(B, cap, L)
+    seg, nseg = _ints(seg_cap + 1), _ints(1)
+    n_max = min(L, N)
+    spa.spa_pack_shifted(qkv, dev(mask), None, None, gh, gw, 2, 1, 0, packed, cu_d, g_d, inv_d, tot)
+    spa.spa_container_segments(cu_d, L, cap, seg, nseg)
+    q, k, v = packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:]
+    out2 = torch.zeros(cap, C, dtype=td, device="cuda")
+    lse2 = torch.zeros(H, seg_cap * n_max, dtype=torch.float32, device="cuda")
+    y2 = torch.empty(B, N, C, dtype=td, device="cuda")
+    spa.spa_packed_attention(q, k, v, seg, seg_cap, n_max, H, Dh, out2, lse2)
+    spa.spa_unpack(out2, inv_d, base, y2)
+    out1, lse1 = torch.zeros_like(out2), torch.zeros_like(lse2)
+    y1 = torch.full((B, N, C), float("nan"), dtype=td, device="cuda")
+    spa.spa_segment_attention_unpack(q, k, v, seg, n_max, g_d, inv_d, base, H, Dh, y1, out1, lse1)
+    torch.cuda.synchronize()
+    T = int(tot.item())
+    assert torch.equal(y1, y2) and torch.equal(out1[:T], out2[:T]) and torch.equal(lse1, lse2)
+    y3 = torch.full((B, N, C), float("nan"), dtype=td, device="cuda")
+    spa.spa_segment_attention_unpack(q, k, v, seg, n_max, g_d, inv_d, base, H, Dh, y3)      # y only
+    torch.cuda.synchronize()
+    assert torch.equal(y3, y2)
