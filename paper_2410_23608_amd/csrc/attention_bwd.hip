@@ -44,19 +44,20 @@ __device__ __forceinline__ Seg seg_of(int b, const int32_t* cu) {
 
 // --------------------------------------------------------------------------- dQ (bf16)
 template <int DH, int NW, int BT, bool LPT>
-__global__ void __launch_bounds__(64 * NW)
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 3 : 2)))
 attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                         const __bf16* __restrict__ v, long qs, long ks, long vs,
                         const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                         const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
                         float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B,
                         int nqb) {
-  constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW;
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][BT * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[2][BT * RS];
+  // a one-wave workgroup stores the next tile only after its own reads of the current one: one buffer
+  constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW, NBUF = NW == 1 ? 1 : 2;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[NBUF][BT * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[NBUF][BT * RS];
   __shared__ int s_cu[LPT ? 2 * kLptMaxB + 1 : 1];
   __shared__ int s_pick;
-  static_assert(2 * BT >= 32 * NW, "the K buffers double as the output staging tile");
+  static_assert(NBUF * BT >= 32 * NW, "the K buffers double as the output staging tile");
 
   const TileId tile_id = xcd_tile(nqb, H, B);
   if (!tile_id.valid) return;
@@ -110,7 +111,7 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   __syncthreads();
   const int nt = (seg.nk + BT - 1) / BT;
   for (int t = 0; t < nt; ++t) {
-    const int buf = t & 1, kt = t * BT;
+    const int buf = t & (NBUF - 1), nbuf = (t + 1) & (NBUF - 1), kt = t * BT;
     if (t + 1 < nt) {
       kst.load(kh, seg.row0 + kt + BT, seg.nk - kt - BT, ks);
       vst.load(vh, seg.row0 + kt + BT, seg.nk - kt - BT, vs);
@@ -152,8 +153,8 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
       }
     }
     if (t + 1 < nt) {
-      kst.store(Ks[buf ^ 1]);
-      vst.store(Vs[buf ^ 1]);
+      kst.store(Ks[nbuf]);
+      vst.store(Vs[nbuf]);
     }
     __syncthreads();
   }
@@ -174,14 +175,14 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           const float* __restrict__ dvec, long lse_stride, const int32_t* __restrict__ cu, int H,
                           float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs,
                           int B, int nkb) {
-  constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW;
-  __shared__ __attribute__((aligned(16))) __bf16 Qs[2][BT * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Gs[2][BT * RS];     // dO rows
-  __shared__ __attribute__((aligned(16))) float lse2s[2][BT];
-  __shared__ __attribute__((aligned(16))) float Ds[2][BT];
+  constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW, NBUF = NW == 1 ? 1 : 2;
+  __shared__ __attribute__((aligned(16))) __bf16 Qs[NBUF][BT * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Gs[NBUF][BT * RS];     // dO rows
+  __shared__ __attribute__((aligned(16))) float lse2s[NBUF][BT];
+  __shared__ __attribute__((aligned(16))) float Ds[NBUF][BT];
   __shared__ int s_cu[LPT ? 2 * kLptMaxB + 1 : 1];
   __shared__ int s_pick;
-  static_assert(2 * BT >= 32 * NW, "the Q / dO buffers double as the output staging tiles");
+  static_assert(NBUF * BT >= 32 * NW, "the Q / dO buffers double as the output staging tiles");
 
   const TileId tile_id = xcd_tile(nkb, H, B);
   if (!tile_id.valid) return;
@@ -243,7 +244,7 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   __syncthreads();
   const int nt = (seg.nq + BT - 1) / BT;
   for (int t = 0; t < nt; ++t) {
-    const int buf = t & 1, qt = t * BT;
+    const int buf = t & (NBUF - 1), nbuf = (t + 1) & (NBUF - 1), qt = t * BT;
     if (t + 1 < nt) {
       qst.load(qh, seg.row0 + qt + BT, seg.nq - qt - BT, qs);
       gst.load(gh, seg.row0 + qt + BT, seg.nq - qt - BT, C);
@@ -293,9 +294,9 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
       }
     }
     if (t + 1 < nt) {
-      qst.store(Qs[buf ^ 1]);
-      gst.store(Gs[buf ^ 1]);
-      store_stats(buf ^ 1);
+      qst.store(Qs[nbuf]);
+      gst.store(Gs[nbuf]);
+      store_stats(nbuf);
     }
     __syncthreads();
   }
@@ -311,6 +312,243 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     flush_tile<DH, RS>(ktile, dk + (seg.row0 + k0 + wv * 32) * dks + h * DH, dks, nrows, lane);
     flush_tile<DH, RS>(vtile, dv + (seg.row0 + k0 + wv * 32) * dvs + h * DH, dvs, nrows, lane);
   }
+}
+
+// ------------------------------------------------- dQ, dK, dV in one kernel (short segments)
+// One workgroup per (image, head); wave j owns the segment's keys 32j .. 32j+31 (K_j, V_j as
+// register operands, dK_j / dV_j in its accumulators).  Q and dO of the whole segment sit in
+// LDS, so every operand is read from memory once and S, dP are computed once (5 GEMM shapes).
+// In round r wave j works on query tile t = (j + r) mod nw: S = Q_t K_j^T, dP = dO_t V_j^T,
+// P, dS; dV_j^T += dO_t^T P, dK_j^T += Q_t^T dS; dS goes through a wave-private LDS tile to
+// come back transposed as the B operand of dQ_t^T += K_j^T dS^T, whose fp32 accumulator tile
+// lives in LDS and is read-modify-written by exactly one wave per round (a barrier between
+// rounds).  Tile t therefore receives its nw contributions in the fixed order j = t, t-1, ...:
+// no atomics, run-to-run bit-stable.
+// Dynamic LDS, rows = 32 * nw:  Q [rows][DH+8] | dO [rows][DH+8] | dQ accumulators [nw] tiles
+// of DH*32 fp32 in register layout | dS tiles [nw][32][40] bf16 | lse*log2(e) [rows] | D [rows].
+template <int DH>
+__host__ __device__ constexpr size_t bwd_fused_lds_bytes(int nw) {
+  return (size_t)nw * (2 * 32 * (DH + 8) * 2 + DH * 32 * 4 + 32 * 40 * 2 + 2 * 32 * 4);
+}
+
+template <int DH>
+__global__ void __launch_bounds__(512)
+attn_bwd_fused_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                           const __bf16* __restrict__ v, long qs, long ks, long vs,
+                           const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
+                           const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
+                           float scale, __bf16* __restrict__ dq, long dqs, __bf16* __restrict__ dk, long dks,
+                           __bf16* __restrict__ dv, long dvs, int B) {
+  constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, CPR = DH / 8, SS = 40, PER = CPR / 2;
+  constexpr int ACC = DH * 32;                       // floats of one dQ accumulator tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char bwd_smem[];
+  __shared__ int s_pick;
+  const int threads = blockDim.x, nw = threads >> 6, rows_cap = 32 * nw;
+  __bf16* Qs = reinterpret_cast<__bf16*>(bwd_smem);
+  __bf16* Gs = Qs + rows_cap * RS;
+  float* dqacc = reinterpret_cast<float*>(Gs + rows_cap * RS);
+  __bf16* scr = reinterpret_cast<__bf16*>(dqacc + nw * ACC);
+  float* lse2s = reinterpret_cast<float*>(scr + nw * 32 * SS);
+  float* Ds = lse2s + rows_cap;
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int h = blockIdx.x % H, rank = blockIdx.x / H;
+  // longest image first (work per segment grows like n^2); the ranking borrows the dS tiles
+  int img = rank;
+  if (B > 1 && B <= 512 && B * (int)sizeof(int) <= nw * 32 * SS * 2) {
+    int* s_len = reinterpret_cast<int*>(scr);
+    for (int b = tid; b < B; b += threads) s_len[b] = cu[b + 1] - cu[b];
+    __syncthreads();
+    for (int b = tid; b < B; b += threads) {
+      const int nb = s_len[b];
+      int r = 0;
+#pragma unroll 8
+      for (int j = 0; j < B; ++j) {
+        const int nj = s_len[j];
+        r += (nj > nb) | ((nj == nb) & (j < b));
+      }
+      if (r == rank) s_pick = b;
+    }
+    __syncthreads();
+    img = s_pick;
+  }
+  const long row0 = cu[img];
+  const int n = min(cu[img + 1] - cu[img], rows_cap);
+  if (n <= 0) return;
+  const int nws = (n + 31) >> 5;                     // waves with keys = query tiles = rounds
+  const long C = (long)H * DH;
+  const float scale_log2 = scale * kLog2e;
+
+  // ---- stage Q, dO (every thread PER chunks of each), D_i = <dO_i, O_i>, lse_i; wave j: K_j, V_j
+  bf16x8 qreg[PER], greg[PER], oreg[PER], kreg[PER], vf[KK];
+  float lreg[PER];
+#pragma unroll
+  for (int t = 0; t < PER; ++t) {
+    const int i = tid + t * threads, r = i / CPR, c = i % CPR;
+    qreg[t] = zero_bf16x8(); greg[t] = zero_bf16x8(); oreg[t] = zero_bf16x8();
+    lreg[t] = INFINITY;                              // rows past the segment: probability 0
+    if (r < n) {
+      qreg[t] = *reinterpret_cast<const bf16x8*>(q + (row0 + r) * qs + h * DH + c * 8);
+      greg[t] = *reinterpret_cast<const bf16x8*>(dout + (row0 + r) * C + h * DH + c * 8);
+      oreg[t] = *reinterpret_cast<const bf16x8*>(out + (row0 + r) * C + h * DH + c * 8);
+      if (c == 0) lreg[t] = lse[h * lse_stride + row0 + r] * kLog2e;
+    }
+  }
+  const int ki = wv * 32 + l32;
+  const bool k_ok = ki < n;
+#pragma unroll
+  for (int t = 0; t < PER; ++t) {
+    const int i = lane + t * 64, r = i / CPR, c = i % CPR;
+    kreg[t] = zero_bf16x8();
+    if (wv * 32 + r < n) kreg[t] = *reinterpret_cast<const bf16x8*>(k + (row0 + wv * 32 + r) * ks + h * DH + c * 8);
+  }
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    vf[kk] = zero_bf16x8();
+    if (k_ok) vf[kk] = *reinterpret_cast<const bf16x8*>(v + (row0 + ki) * vs + h * DH + kk * 16 + hh * 8);
+  }
+#pragma unroll
+  for (int t = 0; t < PER; ++t) {
+    const int i = tid + t * threads, r = i / CPR, c = i % CPR;
+    *reinterpret_cast<bf16x8*>(&Qs[r * RS + c * 8]) = qreg[t];
+    *reinterpret_cast<bf16x8*>(&Gs[r * RS + c * 8]) = greg[t];
+    const floatx8 gf = bf16x8_to_float(greg[t]), of = bf16x8_to_float(oreg[t]);
+    float d = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d = fmaf(of[e], gf[e], d);
+#pragma unroll
+    for (int o = 1; o < CPR; o <<= 1) d += __shfl_xor(d, o, kWave);     // the CPR chunks of a row: adjacent lanes
+    if (c == 0) {
+      Ds[r] = d;
+      lse2s[r] = lreg[t];
+    }
+  }
+  // K_j: through this wave's (still unused) dQ accumulator tile to get both operand forms
+  bf16x8 kf[KK], ktf[DB][2];
+  {
+    __bf16* kt = reinterpret_cast<__bf16*>(dqacc + wv * ACC);
+#pragma unroll
+    for (int t = 0; t < PER; ++t) {
+      const int i = lane + t * 64, r = i / CPR, c = i % CPR;
+      *reinterpret_cast<bf16x8*>(&kt[r * RS + c * 8]) = kreg[t];
+    }
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const bf16x8*>(&kt[l32 * RS + kk * 16 + hh * 8]);
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int mf = 0; mf < 2; ++mf) ktf[d][mf] = transposed_frag_rowmajor<RS>(kt, d, 0, mf, lane);   // K_j^T
+  }
+  floatx16 dka[DB], dva[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dka[d][r] = 0.f; dva[d][r] = 0.f; }
+  __syncthreads();
+
+  const bool live = wv < nws;
+  const bool ragged = live && wv == nws - 1 && (n & 31) != 0;      // this wave's key block has empty lanes
+  __bf16* sc = scr + wv * 32 * SS;
+  for (int r = 0; r < nws; ++r) {
+    if (live) {
+      int t = wv + r;
+      if (t >= nws) t -= nws;
+      const __bf16* Qt = Qs + t * 32 * RS;
+      const __bf16* Gt = Gs + t * 32 * RS;
+      floatx16 s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 qa = *reinterpret_cast<const bf16x8*>(&Qt[l32 * RS + kk * 16 + hh * 8]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
+        const bf16x8 ga = *reinterpret_cast<const bf16x8*>(&Gt[l32 * RS + kk * 16 + hh * 8]);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vf[kk], dp, 0, 0, 0);
+      }
+      float p[16], ds[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const floatx4 l4 = *reinterpret_cast<const floatx4*>(&lse2s[t * 32 + 8 * g + 4 * hh]);
+        const floatx4 d4 = *reinterpret_cast<const floatx4*>(&Ds[t * 32 + 8 * g + 4 * hh]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * g + e;
+          p[i] = __builtin_amdgcn_exp2f(fmaf(s[i], scale_log2, -l4[e]));
+          ds[i] = p[i] * (dp[i] - d4[e]);
+        }
+      }
+      if (ragged) {                                  // keys past the segment must not reach dQ
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ds[i] = k_ok ? ds[i] : 0.f;
+      }
+#pragma unroll
+      for (int mf = 0; mf < 2; ++mf) {
+        floatx8 fp, fd;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { fp[j] = p[8 * mf + j]; fd[j] = ds[8 * mf + j]; }
+        const bf16x8 pb = float_to_bf16x8(fp), dsb = float_to_bf16x8(fd);
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+          const bf16x8 ga = transposed_frag_rowmajor<RS>(Gt, d, 0, mf, lane);   // dO_t^T
+          dva[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, pb, dva[d], 0, 0, 0);
+          const bf16x8 qa = transposed_frag_rowmajor<RS>(Qt, d, 0, mf, lane);   // Q_t^T
+          dka[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, dsb, dka[d], 0, 0, 0);
+        }
+        // dS tile, [key][query]: registers 8mf .. 8mf+7 are queries 16mf + 4hh + {0..3, 8..11}
+        *reinterpret_cast<bf16x4*>(&sc[l32 * SS + 16 * mf + 4 * hh]) = __builtin_shufflevector(dsb, dsb, 0, 1, 2, 3);
+        *reinterpret_cast<bf16x4*>(&sc[l32 * SS + 16 * mf + 8 + 4 * hh]) = __builtin_shufflevector(dsb, dsb, 4, 5, 6, 7);
+      }
+      // dQ_t^T += K_j^T dS^T on the tile's fp32 accumulators in LDS
+      floatx4* at = reinterpret_cast<floatx4*>(dqacc + t * ACC);
+      floatx16 acc[DB];
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          floatx4 a4 = {0.f, 0.f, 0.f, 0.f};
+          if (r > 0) a4 = at[(d * 4 + g) * 64 + lane];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[d][4 * g + e] = a4[e];
+        }
+#pragma unroll
+      for (int mf = 0; mf < 2; ++mf) {
+        const bf16x8 dst = transposed_frag_rowmajor<SS>(sc, 0, 0, mf, lane);     // dS^T: lane = query
+#pragma unroll
+        for (int d = 0; d < DB; ++d) acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[d][mf], dst, acc[d], 0, 0, 0);
+      }
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const floatx4 a4 = {acc[d][4 * g], acc[d][4 * g + 1], acc[d][4 * g + 2], acc[d][4 * g + 3]};
+          at[(d * 4 + g) * 64 + lane] = a4;
+        }
+    }
+    __syncthreads();
+  }
+  if (!live) return;
+  // gradients: dK_j, dV_j from the registers, dQ tile j from LDS; parked as bf16 rows, written whole
+  __bf16* ktile = Qs + wv * 32 * RS;
+  __bf16* vtile = Gs + wv * 32 * RS;
+  park_tile<DH, RS>(dka, scale, ktile, l32, hh);
+  park_tile<DH, RS>(dva, 1.0f, vtile, l32, hh);
+  floatx16 acc[DB];
+  const floatx4* at = reinterpret_cast<const floatx4*>(dqacc + wv * ACC);
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const floatx4 a4 = at[(d * 4 + g) * 64 + lane];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[d][4 * g + e] = a4[e];
+    }
+  __bf16* qtile = reinterpret_cast<__bf16*>(dqacc + wv * ACC);
+  // (LDS operations of one wave complete in order: the reads above precede the stores below)
+  park_tile<DH, RS>(acc, scale, qtile, l32, hh);
+  const int nrows = min(32, n - wv * 32);
+  flush_tile<DH, RS>(qtile, dq + (row0 + wv * 32) * dqs + h * DH, dqs, nrows, lane);
+  flush_tile<DH, RS>(ktile, dk + (row0 + wv * 32) * dks + h * DH, dks, nrows, lane);
+  flush_tile<DH, RS>(vtile, dv + (row0 + wv * 32) * dvs + h * DH, dvs, nrows, lane);
 }
 
 // ------------------------------------------------------------------------------- fp32
@@ -476,8 +714,29 @@ extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void
   (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_row_stride, (long)k_row_stride,               \
       (long)v_row_stride, (const __bf16*)dout, lse, dvec, ls, cu_seqlens, H, scale, (__bf16*)dk,              \
       (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride, B, nblk
-    const char* env = std::getenv("SPA_ATTN_BWD_SHORT");                 // "tiled" forces the 4-wave kernels
+    // short segments: the one-kernel form.  SPA_ATTN_BWD_SHORT = "split" keeps the two one-wave
+    // kernels, "tiled" forces the 4-wave kernels (tuning aids).
+    const char* env = std::getenv("SPA_ATTN_BWD_SHORT");
     const bool short_seg = max_seqlen <= 256 && !(env != nullptr && env[0] == 't');
+    if (short_seg && !(env != nullptr && env[0] == 's')) {
+      const int nw = (max_seqlen + 31) / 32;
+      SPA_REQUIRE((long)B * H < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H must be < 2^31", fn);
+#define SPA_BWD_FUSED(D)                                                                                        \
+  do {                                                                                                          \
+    const size_t smem = bwd_fused_lds_bytes<D>(nw);                                                             \
+    const hipError_t attr = hipFuncSetAttribute((const void*)attn_bwd_fused_bf16_kernel<D>,                     \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);         \
+    SPA_REQUIRE(attr == hipSuccess, SPA_ERR_HIP, "%s: cannot reserve %zu bytes of LDS", fn, smem);              \
+    hipLaunchKernelGGL((attn_bwd_fused_bf16_kernel<D>), dim3((unsigned)(B * H)), dim3(64 * nw), smem, st,       \
+                       (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_row_stride,                \
+                       (long)k_row_stride, (long)v_row_stride, (const __bf16*)out, (const __bf16*)dout, lse, ls, \
+                       cu_seqlens, H, scale, (__bf16*)dq, (long)dq_row_stride, (__bf16*)dk, (long)dk_row_stride, \
+                       (__bf16*)dv, (long)dv_row_stride, B);                                                    \
+  } while (0)
+      if (Dh == 32) SPA_BWD_FUSED(32); else SPA_BWD_FUSED(64);
+#undef SPA_BWD_FUSED
+      return check_launch(fn);
+    }
     const int rows_per_block = short_seg ? 32 : 128;
     const int nblk = (max_seqlen + rows_per_block - 1) / rows_per_block;
     SPA_REQUIRE(((long)H * B + 8) * nblk < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H*blocks must be < 2^31", fn);
