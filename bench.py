@@ -419,7 +419,24 @@ def main():
                              "value": tT * args.steps / tdt, "unit": "selected tokens/s",
                              "ms_per_step": 1e3 * tdt / args.steps, "selected_tokens": tT,
                              "stage_us": {k_: round(v_, 2) for k_, v_ in tus.items()},
-                             "attention_bwd_tflops": round(bwd_flops / tus["packed_attention_bwd"] / 1e6, 2)}
+                             "attention_bwd_tflops": round(bwd_flops / tus["packed_attention_bwd_tokens"] / 1e6, 2)}
+        # the same step with the gather of dy and the scatters of dq, dk, dv as separate launches (9 launches)
+        tp9 = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias, fused_bwd=False)
+        t9 = tp9.stages(tx, tw, tqk, tlab, tdy)
+
+        def t9step():
+            for _, fn in t9:
+                fn()
+
+        for _ in range(5):
+            t9step()
+        torch.cuda.synchronize()
+        t9dt = timed(t9step, args.steps, torch)
+        t9us = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in t9}
+        result["fwd_bwd"]["separate_gather_scatter"] = {
+            "ms_per_step": 1e3 * t9dt / args.steps, "launches": len(t9),
+            "gradients_equal": bool(torch.equal(tp9.dx, tp.dx) and torch.equal(tp9.dqk, tp.dqk) and torch.equal(tp9.dw, tp.dw)),
+            "stage_us": {k_: round(t9us[k_], 2) for k_ in ("unpack_bwd", "packed_attention_bwd", "pack_bwd_v", "pack_bwd_qk")}}
         if S > 1:   # the training step with S batches in flight, like the forward headline
             tsets = []
             for s_ in streams:

@@ -326,6 +326,29 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 // no atomics, run-to-run bit-stable.
 // Dynamic LDS, rows = 32 * nw:  Q [rows][DH+8] | dO [rows][DH+8] | dQ accumulators [nw] tiles
 // of DH*32 fp32 in register layout | dS tiles [nw][32][40] bf16 | lse*log2(e) [rows] | D [rows].
+// Token-position I/O folded into the kernel (gather_idx == nullptr: packed I/O): the upstream
+// gradient row of packed token j is dy[gather_idx[j]], the gradients of packed token j go to
+// row gather_idx[j] of dq / dk / dv, and the rows of unselected tokens (inv_pos < 0) are zeroed:
+// the workgroup of (launch rank, head) clears that head's columns of an even share of the rows.
+struct TokenIO {
+  const int32_t* gather_idx;
+  const int32_t* inv_pos;
+  long rows;               // B * N
+};
+
+template <int DH, int RS>
+__device__ __forceinline__ void flush_tile_rows(const __bf16* tile, __bf16* dst, long row_stride, int nrows, int lane,
+                                                const int32_t* row_index) {
+  constexpr int CPR = DH / 8;
+#pragma unroll
+  for (int i = lane; i < 32 * CPR; i += 64) {
+    const int r = i / CPR, c = i % CPR;
+    if (r < nrows)
+      *reinterpret_cast<bf16x8*>(dst + (long)row_index[r] * row_stride + c * 8) =
+          *reinterpret_cast<const bf16x8*>(&tile[r * RS + c * 8]);
+  }
+}
+
 template <int DH>
 __host__ __device__ constexpr size_t bwd_fused_lds_bytes(int nw) {
   return (size_t)nw * (2 * 32 * (DH + 8) * 2 + DH * 32 * 4 + 32 * 40 * 2 + 2 * 32 * 4);
@@ -338,7 +361,7 @@ attn_bwd_fused_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restric
                            const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                            const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
                            float scale, __bf16* __restrict__ dq, long dqs, __bf16* __restrict__ dk, long dks,
-                           __bf16* __restrict__ dv, long dvs, int B) {
+                           __bf16* __restrict__ dv, long dvs, int B, TokenIO tok) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, CPR = DH / 8, SS = 40, PER = CPR / 2;
   constexpr int ACC = DH * 32;                       // floats of one dQ accumulator tile
   extern __shared__ __attribute__((aligned(16))) unsigned char bwd_smem[];
@@ -353,6 +376,23 @@ attn_bwd_fused_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restric
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
   const int h = blockIdx.x % H, rank = blockIdx.x / H;
+  const bool at_tokens = tok.gather_idx != nullptr;
+  // zero this head's columns of the unselected rows of this workgroup's share; every thread
+  // runs it as its last step, so nothing it computes with waits behind these stores
+  auto zero_unselected = [&]() {
+    if (!at_tokens) return;
+    const long per = (tok.rows + B - 1) / B, i0 = rank * per, i1 = min(tok.rows, i0 + per);
+    const bf16x8 z = zero_bf16x8();
+    for (long i = i0 * CPR + tid; i < i1 * CPR; i += threads) {
+      const long row = i / CPR;
+      const int c = (int)(i % CPR);
+      if (tok.inv_pos[row] < 0) {
+        *reinterpret_cast<bf16x8*>(dq + row * dqs + h * DH + c * 8) = z;
+        *reinterpret_cast<bf16x8*>(dk + row * dks + h * DH + c * 8) = z;
+        *reinterpret_cast<bf16x8*>(dv + row * dvs + h * DH + c * 8) = z;
+      }
+    }
+  };
   // longest image first (work per segment grows like n^2); the ranking borrows the dS tiles
   int img = rank;
   if (B > 1 && B <= 512 && B * (int)sizeof(int) <= nw * 32 * SS * 2) {
@@ -374,7 +414,10 @@ attn_bwd_fused_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   }
   const long row0 = cu[img];
   const int n = min(cu[img + 1] - cu[img], rows_cap);
-  if (n <= 0) return;
+  if (n <= 0) {
+    zero_unselected();
+    return;
+  }
   const int nws = (n + 31) >> 5;                     // waves with keys = query tiles = rounds
   const long C = (long)H * DH;
   const float scale_log2 = scale * kLog2e;
@@ -388,8 +431,9 @@ attn_bwd_fused_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restric
     qreg[t] = zero_bf16x8(); greg[t] = zero_bf16x8(); oreg[t] = zero_bf16x8();
     lreg[t] = INFINITY;                              // rows past the segment: probability 0
     if (r < n) {
+      const long grow = at_tokens ? (long)tok.gather_idx[row0 + r] : row0 + r;
       qreg[t] = *reinterpret_cast<const bf16x8*>(q + (row0 + r) * qs + h * DH + c * 8);
-      greg[t] = *reinterpret_cast<const bf16x8*>(dout + (row0 + r) * C + h * DH + c * 8);
+      greg[t] = *reinterpret_cast<const bf16x8*>(dout + grow * C + h * DH + c * 8);
       oreg[t] = *reinterpret_cast<const bf16x8*>(out + (row0 + r) * C + h * DH + c * 8);
       if (c == 0) lreg[t] = lse[h * lse_stride + row0 + r] * kLog2e;
     }
@@ -526,7 +570,10 @@ attn_bwd_fused_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restric
     }
     __syncthreads();
   }
-  if (!live) return;
+  if (!live) {
+    zero_unselected();
+    return;
+  }
   // gradients: dK_j, dV_j from the registers, dQ tile j from LDS; parked as bf16 rows, written whole
   __bf16* ktile = Qs + wv * 32 * RS;
   __bf16* vtile = Gs + wv * 32 * RS;
@@ -546,9 +593,17 @@ attn_bwd_fused_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   // (LDS operations of one wave complete in order: the reads above precede the stores below)
   park_tile<DH, RS>(acc, scale, qtile, l32, hh);
   const int nrows = min(32, n - wv * 32);
-  flush_tile<DH, RS>(qtile, dq + (row0 + wv * 32) * dqs + h * DH, dqs, nrows, lane);
-  flush_tile<DH, RS>(ktile, dk + (row0 + wv * 32) * dks + h * DH, dks, nrows, lane);
-  flush_tile<DH, RS>(vtile, dv + (row0 + wv * 32) * dvs + h * DH, dvs, nrows, lane);
+  if (at_tokens) {
+    const int32_t* ri = tok.gather_idx + row0 + wv * 32;
+    flush_tile_rows<DH, RS>(qtile, dq + h * DH, dqs, nrows, lane, ri);
+    flush_tile_rows<DH, RS>(ktile, dk + h * DH, dks, nrows, lane, ri);
+    flush_tile_rows<DH, RS>(vtile, dv + h * DH, dvs, nrows, lane, ri);
+  } else {
+    flush_tile<DH, RS>(qtile, dq + (row0 + wv * 32) * dqs + h * DH, dqs, nrows, lane);
+    flush_tile<DH, RS>(ktile, dk + (row0 + wv * 32) * dks + h * DH, dks, nrows, lane);
+    flush_tile<DH, RS>(vtile, dv + (row0 + wv * 32) * dvs + h * DH, dvs, nrows, lane);
+  }
+  zero_unselected();
 }
 
 // ------------------------------------------------------------------------------- fp32
@@ -660,14 +715,14 @@ extern "C" size_t spa_attention_bwd_workspace_bytes(int B, int max_seqlen, int H
   return (size_t)H * (size_t)B * (size_t)max_seqlen * sizeof(float);   // D_i for every (head, row)
 }
 
-extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
-                                        int64_t k_row_stride, int64_t v_row_stride, const void* out,
-                                        const void* dout, const float* lse, const int32_t* cu_seqlens, int B,
-                                        int max_seqlen, int H, int Dh, int dtype, float softmax_scale,
-                                        void* dq, void* dk, void* dv, int64_t dq_row_stride,
-                                        int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
-                                        size_t workspace_bytes, void* stream) {
-  const char* fn = "spa_packed_attention_bwd";
+// tok.gather_idx != nullptr: gradients in and out at token positions (one-kernel form only).
+static int attention_bwd_common(const char* fn, const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                int64_t k_row_stride, int64_t v_row_stride, const void* out, const void* dout,
+                                const float* lse, const int32_t* cu_seqlens, int B, int max_seqlen, int H, int Dh,
+                                int dtype, float softmax_scale, void* dq, void* dk, void* dv,
+                                int64_t dq_row_stride, int64_t dk_row_stride, int64_t dv_row_stride,
+                                void* workspace, size_t workspace_bytes, TokenIO tok, void* stream) {
+  const bool at_tokens = tok.gather_idx != nullptr;
   SPA_REQUIRE(q && k && v && out && dout && lse && cu_seqlens && dq && dk && dv, SPA_ERR_INVALID_ARG,
               "%s: null pointer", fn);
   SPA_REQUIRE(B >= 1 && max_seqlen >= 1 && H >= 1, SPA_ERR_INVALID_ARG, "%s: B, max_seqlen, H must be >= 1", fn);
@@ -685,9 +740,11 @@ extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void
               SPA_ERR_INVALID_ARG, "%s: tensors not 16-byte aligned", fn);
   SPA_REQUIRE(softmax_scale >= 0.f && std::isfinite(softmax_scale), SPA_ERR_INVALID_ARG,
               "%s: softmax_scale must be finite and >= 0", fn);
-  const size_t need = spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype);
-  SPA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SPA_ERR_WORKSPACE,
+  const size_t need = at_tokens ? 0 : spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype);
+  SPA_REQUIRE(at_tokens || (workspace != nullptr && workspace_bytes >= need), SPA_ERR_WORKSPACE,
               "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace_bytes);
+  SPA_REQUIRE(!at_tokens || (dtype == SPA_BF16 && max_seqlen <= 256), SPA_ERR_UNSUPPORTED,
+              "%s: bf16 and max_seqlen <= 256 only (else spa_unpack_bwd, spa_packed_attention_bwd, spa_pack_bwd)", fn);
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)Dh);
   const long ls = (long)B * max_seqlen;
   float* dvec = static_cast<float*>(workspace);
@@ -718,7 +775,7 @@ extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void
     // kernels, "tiled" forces the 4-wave kernels (tuning aids).
     const char* env = std::getenv("SPA_ATTN_BWD_SHORT");
     const bool short_seg = max_seqlen <= 256 && !(env != nullptr && env[0] == 't');
-    if (short_seg && !(env != nullptr && env[0] == 's')) {
+    if (at_tokens || (short_seg && !(env != nullptr && env[0] == 's'))) {
       const int nw = (max_seqlen + 31) / 32;
       SPA_REQUIRE((long)B * H < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H must be < 2^31", fn);
 #define SPA_BWD_FUSED(D)                                                                                        \
@@ -731,7 +788,7 @@ extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void
                        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_row_stride,                \
                        (long)k_row_stride, (long)v_row_stride, (const __bf16*)out, (const __bf16*)dout, lse, ls, \
                        cu_seqlens, H, scale, (__bf16*)dq, (long)dq_row_stride, (__bf16*)dk, (long)dk_row_stride, \
-                       (__bf16*)dv, (long)dv_row_stride, B);                                                    \
+                       (__bf16*)dv, (long)dv_row_stride, B, tok);                                               \
   } while (0)
       if (Dh == 32) SPA_BWD_FUSED(32); else SPA_BWD_FUSED(64);
 #undef SPA_BWD_FUSED
@@ -757,4 +814,32 @@ extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void
 #undef SPA_BWD_ARGS_DKDV
   }
   return check_launch(fn);
+}
+
+extern "C" int spa_packed_attention_bwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                        int64_t k_row_stride, int64_t v_row_stride, const void* out,
+                                        const void* dout, const float* lse, const int32_t* cu_seqlens, int B,
+                                        int max_seqlen, int H, int Dh, int dtype, float softmax_scale,
+                                        void* dq, void* dk, void* dv, int64_t dq_row_stride,
+                                        int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  return attention_bwd_common("spa_packed_attention_bwd", q, k, v, q_row_stride, k_row_stride, v_row_stride, out,
+                              dout, lse, cu_seqlens, B, max_seqlen, H, Dh, dtype, softmax_scale, dq, dk, dv,
+                              dq_row_stride, dk_row_stride, dv_row_stride, workspace, workspace_bytes,
+                              TokenIO{nullptr, nullptr, 0}, stream);
+}
+
+extern "C" int spa_packed_attention_bwd_tokens(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                               int64_t k_row_stride, int64_t v_row_stride, const void* out,
+                                               const void* dy, const float* lse, const int32_t* cu_seqlens, int B,
+                                               int max_seqlen, int H, int Dh, int dtype, float softmax_scale,
+                                               const int32_t* gather_idx, const int32_t* inv_pos, int64_t rows,
+                                               void* dq, void* dk, void* dv, int64_t dq_row_stride,
+                                               int64_t dk_row_stride, int64_t dv_row_stride, void* stream) {
+  const char* fn = "spa_packed_attention_bwd_tokens";
+  SPA_REQUIRE(gather_idx && inv_pos, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+  SPA_REQUIRE(rows >= 1 && rows < 2147483647L, SPA_ERR_INVALID_ARG, "%s: rows must be in [1, 2^31)", fn);
+  return attention_bwd_common(fn, q, k, v, q_row_stride, k_row_stride, v_row_stride, out, dy, lse, cu_seqlens, B,
+                              max_seqlen, H, Dh, dtype, softmax_scale, dq, dk, dv, dq_row_stride, dk_row_stride,
+                              dv_row_stride, nullptr, 0, TokenIO{gather_idx, inv_pos, (long)rows}, stream);
 }

@@ -73,6 +73,47 @@ def test_attention_backward_matches_oracle(spa, dtype, Dh, N):
         assert _rel(got[:T], ref) <= tol, (name, _rel(got[:T], ref))
 
 
+@pytest.mark.parametrize("Dh,H,N", [(64, 2, 256), (64, 3, 196), (32, 4, 100), (32, 2, 40)])
+def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N):
+    """spa_packed_attention_bwd_tokens = unpack_bwd + attention backward + pack_bwd (x3): same bits at the
+    selected tokens, zeros elsewhere, nothing else written."""
+    C = H * Dh
+    lens = [n for n in [0, 1, 31, 33, 64, 97, 130, 200] if n < N] + [N, 0]
+    B, cap = len(lens), len(lens) * N
+    rng = np.random.default_rng(N + Dh)
+    qkv = wlmod.round_bf16(rng.standard_normal((B, N, 3 * C)).astype(np.float32))
+    mask = np.zeros((B, N), np.uint8)
+    for b, n in enumerate(lens):
+        mask[b, rng.permutation(N)[:n]] = 1
+    dy = dev(wlmod.round_bf16(rng.standard_normal((B, N, C)).astype(np.float32)), "bf16")
+    td = torch.bfloat16
+    packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    gidx = torch.empty(cap, dtype=torch.int32, device="cuda")
+    inv = torch.empty(cap, dtype=torch.int32, device="cuda")
+    tot = torch.empty(1, dtype=torch.int32, device="cuda")
+    spa.spa_pack(dev(qkv, "bf16"), dev(mask), None, None, 0, packed, cu, gidx, inv, tot)
+    pq, pk, pv = packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:]
+    out = torch.zeros(cap, C, dtype=td, device="cuda")
+    lse = torch.zeros(H, cap, dtype=torch.float32, device="cuda")
+    spa.spa_packed_attention(pq, pk, pv, cu, B, N, H, Dh, out, lse)
+    # three calls
+    dout = torch.zeros(cap, C, dtype=td, device="cuda")
+    gp = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    ws = torch.empty(spa.spa_attention_bwd_workspace_bytes(B, N, H, Dh, spa.SPA_BF16), dtype=torch.uint8, device="cuda")
+    ref = torch.full((B, N, 3 * C), float("nan"), dtype=td, device="cuda")
+    spa.spa_unpack_bwd(dy, gidx, tot, dout)
+    spa.spa_packed_attention_bwd(pq, pk, pv, out, dout, lse, cu, B, N, H, Dh, gp[:, :C], gp[:, C:2 * C], gp[:, 2 * C:], ws)
+    spa.spa_pack_bwd(gp, inv, ref)
+    # one call, into a wider buffer whose extra columns must stay untouched
+    got = torch.full((cap, 3 * C + 8), float("nan"), dtype=td, device="cuda")
+    spa.spa_packed_attention_bwd_tokens(pq, pk, pv, out, dy, lse, cu, B, N, H, Dh, gidx, inv,
+                                        got[:, :C], got[:, C:2 * C], got[:, 2 * C:3 * C])
+    torch.cuda.synchronize()
+    assert torch.equal(got[:, :3 * C], ref.view(cap, 3 * C))
+    assert bool(torch.isnan(got[:, 3 * C:]).all())
+
+
 @pytest.mark.parametrize("N", [300, 190])
 def test_attention_backward_is_bit_stable(spa, N):
     B, H, Dh = 4, 2, 64

@@ -78,12 +78,17 @@ def test_full_size_forward_as_benchmarked(spa, pipeline, name):
     assert np.array_equal(y[gidx], out[:T]) and np.all(y[inv < 0] == 0)
 
 
-def test_full_size_training_step_as_benchmarked(spa, pipeline):
-    """ViT-B-shaped forward+backward step at full batch through pipeline.TrainPass."""
+@pytest.mark.parametrize("fused_bwd", [True, False])
+def test_full_size_training_step_as_benchmarked(spa, pipeline, fused_bwd):
+    """ViT-B-shaped forward+backward step at full batch through pipeline.TrainPass, with the
+    gather / scatter of the gradients inside the attention backward (as benchmarked) and as
+    separate launches."""
     wl = wlmod.WORKLOADS["vit_b_train"]
     B, N, C, H = wl.B, wl.N, wl.C, wl.H
     bun = wlmod.generate(wl, 0)
-    tp = pipeline.TrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias)
+    tp = pipeline.TrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, fused_bwd=fused_bwd)
+    tp.dqk.fill_(float("nan"))
+    tp.d_rg.fill_(float("nan"))
     qk = bun["qkv"][:, :, :2 * C]
     tp.run(dev(bun["x"], "bf16"), dev(bun["w"], "bf16"), dev(qk, "bf16"), dev(bun["labels"]), dev(bun["dy"], "bf16"))
     torch.cuda.synchronize()
@@ -102,16 +107,19 @@ def test_full_size_training_step_as_benchmarked(spa, pipeline):
     def rel(got, ref):
         return float(np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref))))
 
-    dqk = host(tp.dqk_packed)
-    assert rel(dqk[:T, :C], rdq) <= 2e-2 and rel(dqk[:T, C:], rdk) <= 2e-2
-    assert rel(host(tp.dv_packed)[:T], rdv) <= 2e-2
+    # gradients w.r.t. the un-packed q|k and r_g: at the selected positions, zero elsewhere
+    dqk_full = host(tp.dqk).reshape(-1, 2 * C)
+    d_rg = host(tp.d_rg).reshape(-1, C)
+    assert rel(dqk_full[gidx][:, :C], rdq) <= 2e-2 and rel(dqk_full[gidx][:, C:], rdk) <= 2e-2
+    assert rel(d_rg[gidx], rdv) <= 2e-2
+    assert np.all(dqk_full[inv < 0] == 0) and np.all(d_rg[inv < 0] == 0)
+    if not fused_bwd:
+        dqk = host(tp.dqk_packed)
+        assert np.array_equal(dqk_full[gidx], dqk[:T]) and np.array_equal(d_rg[gidx], host(tp.dv_packed)[:T])
     g = orc.gate_backward(x, w, bias, None, bun["labels"], orc.unpack(rdv, inv, B, N), True, tp.loss_scale)
     assert rel(host(tp.dx), g["dx"]) <= 2e-2
     assert rel(host(tp.dw), g["dw"]) <= 2e-2
     assert abs(float(host(tp.loss)[0]) - g["loss"]) <= 1e-3 * abs(g["loss"])
-    # gradient w.r.t. the un-packed q|k: packed gradients at selected positions, zero elsewhere
-    dqk_full = host(tp.dqk).reshape(-1, 2 * C)
-    assert np.array_equal(dqk_full[gidx], dqk[:T]) and np.all(dqk_full[inv < 0] == 0)
 
 
 def test_maxpool_matches_oracle(spa):
@@ -339,9 +347,10 @@ def test_hierarchy_training_chain_matches_stagewise_oracle(spa, pipeline):
         rg = orc.round_to_dtype(orc.sigmoid(s.astype(np.float32).astype(np.float64))[:, :, None] * x, "bf16")
         dO = bun["dy"].reshape(-1, C)[gidx]
         rdq, rdk, rdv = orc.attention_backward_per_image(qk[:, :, :C], qk[:, :, C:], rg, mask, dO, H)
-        dqk = host(tp.dqk_packed)
-        assert rel(dqk[:T, :C], rdq) <= 2e-2 and rel(dqk[:T, C:], rdk) <= 2e-2
-        assert rel(host(tp.dv_packed)[:T], rdv) <= 2e-2
+        dqk, d_rg = host(tp.dqk).reshape(-1, 2 * C), host(tp.d_rg).reshape(-1, C)     # at token positions
+        assert rel(dqk[gidx][:, :C], rdq) <= 2e-2 and rel(dqk[gidx][:, C:], rdk) <= 2e-2
+        assert rel(d_rg[gidx], rdv) <= 2e-2
+        assert np.all(dqk[inv < 0] == 0) and np.all(d_rg[inv < 0] == 0)
         if s_up is not None:
             assert np.min(np.abs(orc.gate_only(x, w, bias) - s_up)) > 1e-4      # which side won the max is unambiguous
         g = orc.gate_backward(x, w, bias, s_up, bun["labels"], orc.unpack(rdv, inv, B, N), True, tp.loss_scale)
