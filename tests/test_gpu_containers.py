@@ -151,6 +151,16 @@ def _container_case(spa, dtype, B, gh, gw, C, H, L, shift, seed, frac=(0.2, 0.9)
     for name, g, r in (("dq", got[:, :C], dq_ref), ("dk", got[:, C:2 * C], dk_ref), ("dv", got[:, 2 * C:], dv_ref)):
         err = np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-30)
         assert err <= (1e-4 if dtype == "f32" else 2e-2), (name, err)
+    if dtype == "bf16":
+        # the same backward with the gradients at token positions (shifted packing order included)
+        dy = torch.zeros(cap, C, dtype=td, device="cuda")
+        dy[g_d[:T].long()] = dout_d[:T]
+        tok = torch.full((cap, 3 * C), float("nan"), dtype=td, device="cuda")
+        spa.spa_packed_attention_bwd_tokens(q, k, v, out, dy.view(B, N, C), lse, seg, seg_cap, n_max, H, Dh, g_d, inv_d,
+                                            tok[:, :C], tok[:, C:2 * C], tok[:, 2 * C:])
+        torch.cuda.synchronize()
+        assert torch.equal(tok[g_d[:T].long()], dqkv[:T])
+        assert bool((tok[inv_d < 0] == 0).all())
 
 
 @pytest.mark.parametrize("dtype,B,gh,gw,C,H,L,shift", [
