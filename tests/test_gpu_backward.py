@@ -114,6 +114,41 @@ def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N)
     assert bool(torch.isnan(got[:, 3 * C:]).all())
 
 
+@pytest.mark.parametrize("fill", [0, 1])
+def test_attention_backward_at_token_positions_degenerate_masks(spa, fill):
+    """Nothing selected: all gradients zero.  Everything selected: the plain backward, row for row."""
+    B, N, H, Dh = 3, 70, 2, 32
+    C, cap = H * Dh, B * N
+    rng = np.random.default_rng(5)
+    qkv = dev(wlmod.round_bf16(rng.standard_normal((B, N, 3 * C)).astype(np.float32)), "bf16")
+    dy = dev(wlmod.round_bf16(rng.standard_normal((B, N, C)).astype(np.float32)), "bf16")
+    mask = torch.full((B, N), fill, dtype=torch.uint8, device="cuda")
+    td = torch.bfloat16
+    packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    gidx = torch.zeros(cap, dtype=torch.int32, device="cuda")
+    inv = torch.empty(cap, dtype=torch.int32, device="cuda")
+    tot = torch.empty(1, dtype=torch.int32, device="cuda")
+    spa.spa_pack(qkv, mask, None, None, 0, packed, cu, gidx, inv, tot)
+    pq, pk, pv = packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:]
+    out = torch.zeros(cap, C, dtype=td, device="cuda")
+    lse = torch.zeros(H, cap, dtype=torch.float32, device="cuda")
+    spa.spa_packed_attention(pq, pk, pv, cu, B, N, H, Dh, out, lse)
+    got = torch.full((cap, 3 * C), float("nan"), dtype=td, device="cuda")
+    spa.spa_packed_attention_bwd_tokens(pq, pk, pv, out, dy, lse, cu, B, N, H, Dh, gidx, inv,
+                                        got[:, :C], got[:, C:2 * C], got[:, 2 * C:])
+    torch.cuda.synchronize()
+    if fill == 0:
+        assert int(tot.item()) == 0 and bool((got == 0).all())
+    else:
+        ref = torch.full((cap, 3 * C), float("nan"), dtype=td, device="cuda")
+        ws = torch.empty(spa.spa_attention_bwd_workspace_bytes(B, N, H, Dh, spa.SPA_BF16), dtype=torch.uint8, device="cuda")
+        spa.spa_packed_attention_bwd(pq, pk, pv, out, dy.view(cap, C), lse, cu, B, N, H, Dh,
+                                     ref[:, :C], ref[:, C:2 * C], ref[:, 2 * C:], ws)
+        torch.cuda.synchronize()
+        assert int(tot.item()) == cap and torch.equal(got, ref)
+
+
 @pytest.mark.parametrize("N", [300, 190])
 def test_attention_backward_is_bit_stable(spa, N):
     B, H, Dh = 4, 2, 64
