@@ -10,6 +10,7 @@
 //                 dP = dO V^T un-transposed (lane = key), so P and dS are the B operands of
 //                 dV^T += dO^T P and dK^T += Q^T dS.
 // S and dP are recomputed in both (7 GEMM shapes instead of 5) in exchange for determinism.
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 
@@ -43,23 +44,36 @@ __device__ __forceinline__ Seg seg_of(int b, const int32_t* cu) {
 // row-major tiles, so nothing is staged twice.
 
 // --------------------------------------------------------------------------- dQ (bf16)
+// LDS of the two long-segment kernels: two row-major operand tiles (double-buffered unless the
+// workgroup is one wave, which stores the next tile only after its own reads of the current
+// one), the per-query statistics of the dkdv side, and the longest-first ranking.
 template <int DH, int NW, int BT, bool LPT>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 3 : 2)))
-attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                        const __bf16* __restrict__ v, long qs, long ks, long vs,
-                        const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
-                        const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
-                        float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B,
-                        int nqb) {
-  // a one-wave workgroup stores the next tile only after its own reads of the current one: one buffer
+struct BwdLds {
+  static constexpr int RS = DH + 8, NBUF = NW == 1 ? 1 : 2;
+  __attribute__((aligned(16))) __bf16 A[NBUF][BT * RS];     // K (dq) | Q (dkdv)
+  __attribute__((aligned(16))) __bf16 Bm[NBUF][BT * RS];    // V (dq) | dO (dkdv)
+  __attribute__((aligned(16))) float lse2s[NBUF][BT];
+  __attribute__((aligned(16))) float Ds[NBUF][BT];
+  int s_cu[LPT ? 2 * kLptMaxB + 1 : 1];
+  int s_pick;
+};
+
+// kHaveD: D_i = <dO_i, O_i> was computed by an earlier launch and is read from dvec; else this
+// kernel computes it and writes dvec for the dkdv kernel that follows.
+template <int DH, int NW, int BT, bool LPT, bool kHaveD>
+__device__ __forceinline__ void
+attn_bwd_dq_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __bf16* __restrict__ q,
+                 const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs,
+                 const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
+                 const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
+                 float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW, NBUF = NW == 1 ? 1 : 2;
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[NBUF][BT * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[NBUF][BT * RS];
-  __shared__ int s_cu[LPT ? 2 * kLptMaxB + 1 : 1];
-  __shared__ int s_pick;
+  auto& Ks = lds.A;
+  auto& Vs = lds.Bm;
+  int* s_cu = lds.s_cu;
+  int& s_pick = lds.s_pick;
   static_assert(NBUF * BT >= 32 * NW, "the K buffers double as the output staging tile");
 
-  const TileId tile_id = xcd_tile(nqb, H, B);
   if (!tile_id.valid) return;
   const int h = tile_id.h;
   const Segment seg = LPT ? lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick)
@@ -89,16 +103,23 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
       const int col = h * DH + kk * 16 + hh * 8;
       qf[kk] = *reinterpret_cast<const bf16x8*>(q + (seg.row0 + qi) * qs + col);
       dof[kk] = *reinterpret_cast<const bf16x8*>(dout + (seg.row0 + qi) * C + col);
-      const floatx8 of = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(out + (seg.row0 + qi) * C + col));
-      const floatx8 gf = bf16x8_to_float(dof[kk]);
+      if (!kHaveD) {
+        const floatx8 of = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(out + (seg.row0 + qi) * C + col));
+        const floatx8 gf = bf16x8_to_float(dof[kk]);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dpart = fmaf(of[e], gf[e], dpart);
+        for (int e = 0; e < 8; ++e) dpart = fmaf(of[e], gf[e], dpart);
+      }
     }
   }
-  const float D = sum_across_halves(dpart);
+  float D;
+  if (kHaveD) {
+    D = q_ok ? dvec[h * lse_stride + seg.row0 + qi] : 0.f;
+  } else {
+    D = sum_across_halves(dpart);
+    if (q_ok && hh == 0) dvec[h * lse_stride + seg.row0 + qi] = D;
+  }
   // invalid queries: lse = +inf makes every probability 0
   const float lse2 = q_ok ? lse[h * lse_stride + seg.row0 + qi] * kLog2e : INFINITY;
-  if (q_ok && hh == 0) dvec[h * lse_stride + seg.row0 + qi] = D;
 
   floatx16 acc[DB];
 #pragma unroll
@@ -166,25 +187,36 @@ attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
                        min(32, seg.nq - q0 - wv * 32), lane);
 }
 
+template <int DH, int NW, int BT, bool LPT>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 3 : 2)))
+attn_bwd_dq_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                        const __bf16* __restrict__ v, long qs, long ks, long vs,
+                        const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
+                        const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
+                        float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B,
+                        int nqb) {
+  __shared__ BwdLds<DH, NW, BT, LPT> lds;
+  attn_bwd_dq_body<DH, NW, BT, LPT, false>(lds, xcd_tile(nqb, H, B), q, k, v, qs, ks, vs, out, dout, lse, lse_stride,
+                                           cu, H, scale, dq, gstride, dvec, B);
+}
+
 // ------------------------------------------------------------------------ dK, dV (bf16)
 template <int DH, int NW, int BT, bool LPT>
-__global__ void __launch_bounds__(64 * NW)
-attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                          const __bf16* __restrict__ v, long qs, long ks, long vs,
-                          const __bf16* __restrict__ dout, const float* __restrict__ lse,
-                          const float* __restrict__ dvec, long lse_stride, const int32_t* __restrict__ cu, int H,
-                          float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs,
-                          int B, int nkb) {
+__device__ __forceinline__ void
+attn_bwd_dkdv_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __bf16* __restrict__ q,
+                   const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs,
+                   const __bf16* __restrict__ dout, const float* __restrict__ lse,
+                   const float* __restrict__ dvec, long lse_stride, const int32_t* __restrict__ cu, int H,
+                   float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs, int B) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW, NBUF = NW == 1 ? 1 : 2;
-  __shared__ __attribute__((aligned(16))) __bf16 Qs[NBUF][BT * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Gs[NBUF][BT * RS];     // dO rows
-  __shared__ __attribute__((aligned(16))) float lse2s[NBUF][BT];
-  __shared__ __attribute__((aligned(16))) float Ds[NBUF][BT];
-  __shared__ int s_cu[LPT ? 2 * kLptMaxB + 1 : 1];
-  __shared__ int s_pick;
+  auto& Qs = lds.A;
+  auto& Gs = lds.Bm;                  // dO rows
+  auto& lse2s = lds.lse2s;
+  auto& Ds = lds.Ds;
+  int* s_cu = lds.s_cu;
+  int& s_pick = lds.s_pick;
   static_assert(NBUF * BT >= 32 * NW, "the Q / dO buffers double as the output staging tiles");
 
-  const TileId tile_id = xcd_tile(nkb, H, B);
   if (!tile_id.valid) return;
   const int h = tile_id.h;
   const Segment seg = LPT ? lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick)
@@ -311,6 +343,70 @@ attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     const int nrows = min(32, seg.nk - k0 - wv * 32);
     flush_tile<DH, RS>(ktile, dk + (seg.row0 + k0 + wv * 32) * dks + h * DH, dks, nrows, lane);
     flush_tile<DH, RS>(vtile, dv + (seg.row0 + k0 + wv * 32) * dvs + h * DH, dvs, nrows, lane);
+  }
+}
+
+template <int DH, int NW, int BT, bool LPT>
+__global__ void __launch_bounds__(64 * NW)
+attn_bwd_dkdv_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                          const __bf16* __restrict__ v, long qs, long ks, long vs,
+                          const __bf16* __restrict__ dout, const float* __restrict__ lse,
+                          const float* __restrict__ dvec, long lse_stride, const int32_t* __restrict__ cu, int H,
+                          float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs,
+                          int B, int nkb) {
+  __shared__ BwdLds<DH, NW, BT, LPT> lds;
+  attn_bwd_dkdv_body<DH, NW, BT, LPT>(lds, xcd_tile(nkb, H, B), q, k, v, qs, ks, vs, dout, lse, dvec, lse_stride, cu,
+                                      H, scale, dk, dks, dv, dvs, B);
+}
+
+// Long segments, one launch for both sides.  Each of the two kernels above is bound by the
+// chain of its longest workgroup (a wave walks all tokens of its image) with one to two
+// workgroups per compute unit; launched together, the two chains run side by side.  Workgroup
+// -> (xcd = id % 8, role = (id / 8) % 2, j = id / 16): the dq block and the dkdv block of a
+// tile number sit on the same XCD (they read the same rows).  D_i = <dO_i, O_i> comes from
+// the small kernel below, launched first.
+template <int DH, int NW, int BT>
+__global__ void __launch_bounds__(64 * NW)
+attn_bwd_both_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                          const __bf16* __restrict__ v, long qs, long ks, long vs,
+                          const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
+                          const float* __restrict__ lse, float* __restrict__ dvec, long lse_stride,
+                          const int32_t* __restrict__ cu, int H, float scale, __bf16* __restrict__ dq, long dqs,
+                          __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs, int B, int nblk) {
+  __shared__ BwdLds<DH, NW, BT, true> lds;
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+  const TileId tile_id = xcd_tile_at(xcd, jj >> 1, nblk, H, B);
+  if (jj & 1)
+    attn_bwd_dkdv_body<DH, NW, BT, true>(lds, tile_id, q, k, v, qs, ks, vs, dout, lse, dvec, lse_stride, cu, H, scale,
+                                         dk, dks, dv, dvs, B);
+  else
+    attn_bwd_dq_body<DH, NW, BT, true, true>(lds, tile_id, q, k, v, qs, ks, vs, out, dout, lse, lse_stride, cu, H,
+                                             scale, dq, dqs, dvec, B);
+}
+
+// D[h][j] = <dO_j, O_j> over head h's columns, for the packed rows j < cu[B]: DH / 8 adjacent
+// lanes share a (row, head).
+template <int DH>
+__global__ void __launch_bounds__(256)
+attn_bwd_dvec_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout, const int32_t* __restrict__ cu,
+                     int B, int H, long lse_stride, float* __restrict__ dvec) {
+  constexpr int CPR = DH / 8;
+  const long C = (long)H * DH, total = (long)cu[B] * H * CPR;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < ((total + 63) & ~63L); i += (long)gridDim.x * 256) {
+    const long rh = i / CPR;
+    const int c = (int)(i % CPR);
+    const long row = rh / H;
+    const int h = (int)(rh % H);
+    float d = 0.f;
+    if (i < total) {
+      const floatx8 of = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(out + row * C + h * DH + c * 8));
+      const floatx8 gf = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(dout + row * C + h * DH + c * 8));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d = fmaf(of[e], gf[e], d);
+    }
+#pragma unroll
+    for (int o = 1; o < CPR; o <<= 1) d += __shfl_xor(d, o, kWave);
+    if (i < total && c == 0) dvec[h * lse_stride + row] = d;
   }
 }
 
@@ -808,7 +904,27 @@ static int attention_bwd_common(const char* fn, const void* q, const void* k, co
       hipLaunchKernelGGL((attn_bwd_dkdv_bf16_kernel<D, 4, 64, true>), grid, dim3(256), 0, st, SPA_BWD_ARGS_DKDV); \
     }                                                                                                            \
   } while (0)
-    if (Dh == 32) SPA_BWD_BF16(32); else SPA_BWD_BF16(64);
+    // long segments: D first, then both sides in one launch (SPA_ATTN_BWD_LONG=two keeps two launches)
+    const char* lenv = std::getenv("SPA_ATTN_BWD_LONG");
+    if (!short_seg && !(lenv != nullptr && lenv[0] == 't')) {
+      SPA_REQUIRE(2L * grid.x < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H*blocks must be < 2^30", fn);
+      const long rows_cap = (long)B * max_seqlen;
+      const unsigned dgrid = (unsigned)std::min<long>((rows_cap * H * (Dh / 8) + 255) / 256, 4096L);
+#define SPA_BWD_BOTH(D)                                                                                          \
+  do {                                                                                                           \
+    hipLaunchKernelGGL((attn_bwd_dvec_kernel<D>), dim3(dgrid), dim3(256), 0, st, (const __bf16*)out,             \
+                       (const __bf16*)dout, cu_seqlens, B, H, ls, dvec);                                         \
+    hipLaunchKernelGGL((attn_bwd_both_bf16_kernel<D, 4, 64>), dim3(2 * grid.x), dim3(256), 0, st,                \
+                       (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_row_stride,                 \
+                       (long)k_row_stride, (long)v_row_stride, (const __bf16*)out, (const __bf16*)dout, lse,     \
+                       dvec, ls, cu_seqlens, H, scale, (__bf16*)dq, (long)dq_row_stride, (__bf16*)dk,            \
+                       (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride, B, nblk);                          \
+  } while (0)
+      if (Dh == 32) SPA_BWD_BOTH(32); else SPA_BWD_BOTH(64);
+#undef SPA_BWD_BOTH
+    } else {
+      if (Dh == 32) SPA_BWD_BF16(32); else SPA_BWD_BF16(64);
+    }
 #undef SPA_BWD_BF16
 #undef SPA_BWD_ARGS_DQ
 #undef SPA_BWD_ARGS_DKDV

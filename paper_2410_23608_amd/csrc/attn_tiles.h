@@ -114,8 +114,8 @@ struct TileId {
   int qb, h, rank;
   bool valid;
 };
-__device__ __forceinline__ TileId xcd_tile(int nqb, int H, int B) {
-  const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
+// (xcd, j): the workgroup's XCD and its number inside the XCD
+__device__ __forceinline__ TileId xcd_tile_at(int xcd, int j, int nqb, int H, int B) {
   const int pl = j / nqb;
   TileId t;
   t.qb = j - pl * nqb;
@@ -124,6 +124,9 @@ __device__ __forceinline__ TileId xcd_tile(int nqb, int H, int B) {
   t.h = pair % H;
   t.rank = pair / H;
   return t;
+}
+__device__ __forceinline__ TileId xcd_tile(int nqb, int H, int B) {
+  return xcd_tile_at(blockIdx.x & 7, blockIdx.x >> 3, nqb, H, B);
 }
 static unsigned xcd_grid(int nqb, int H, int B) {
   const long pairs8 = ((long)H * B + 7) / 8;
