@@ -377,31 +377,18 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
 // and V fragments through the transposing LDS read, and keeps the online softmax state in
 // registers.  Work units are small (<= n/32 steps each), so the load spreads over all SIMDs
 // instead of concentrating a heavy (image, head) on one compute unit.
+// The wave's work on queries [q0, q0 + 32) of head h of segment seg (q0 < seg.nq): Ks, Vs are
+// its private LDS tiles of STEP rows.
 template <int DH, int STEP>
-__global__ void __launch_bounds__(64)
-attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                          const __bf16* __restrict__ v, long qs, long ks, long vs,
-                          const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
-                          int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
-                          long lse_stride, Scatter sc, int B, int nqb) {
+__device__ __forceinline__ void
+wave_attention(__bf16* Ks, __bf16* Vs, const Segment seg, int h, int q0, const __bf16* __restrict__ q,
+               const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs, int H,
+               float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse, long lse_stride,
+               const Scatter& sc) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, CPR = DH / 8;
   constexpr int NSB = STEP / 32;                 // 32-key sub-tiles per step (one softmax update)
   constexpr int LPL = STEP * CPR / 64;           // 16-byte loads per lane per tensor per step
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[STEP * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[STEP * RS];
-
-  const TileId tile_id = xcd_tile(nqb, H, B);
-  if (!tile_id.valid) return;
-  const int h = tile_id.h, img = tile_id.rank;
-  const Segment seg = segment_of(img, cu, key_lens, n_pad);
   const long C = (long)H * DH;
-  // this wave's share of the image's bypassing tokens: at once if it has no queries, else last
-  const FillRange fr = fill_range(sc, img, B, tile_id.qb, nqb);
-  const int q0 = tile_id.qb * 32;
-  if (q0 >= seg.nq) {
-    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64);
-    return;
-  }
   const int lane = threadIdx.x, l32 = lane & 31, hh = lane >> 5;
   const int qi = q0 + l32;
   const bool q_ok = qi < seg.nq;
@@ -491,7 +478,136 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   fwd_park<DH, RS>(acc, q_ok, seg.nk > 0, Ks, lse != nullptr ? lse + h * lse_stride + seg.row0 + qi : nullptr, l32,
                    hh);
   fwd_flush<DH, RS>(Ks, out, sc, seg.row0 + q0, h, C, min(32, seg.nq - q0), lane);
+}
+
+template <int DH, int STEP>
+__global__ void __launch_bounds__(64)
+attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                          const __bf16* __restrict__ v, long qs, long ks, long vs,
+                          const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
+                          int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
+                          long lse_stride, Scatter sc, int B, int nqb) {
+  constexpr int RS = DH + 8;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[STEP * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[STEP * RS];
+
+  const TileId tile_id = xcd_tile(nqb, H, B);
+  if (!tile_id.valid) return;
+  const int h = tile_id.h, img = tile_id.rank;
+  const Segment seg = segment_of(img, cu, key_lens, n_pad);
+  const long C = (long)H * DH;
+  // this wave's share of the image's bypassing tokens: at once if it has no queries, else last
+  const FillRange fr = fill_range(sc, img, B, tile_id.qb, nqb);
+  const int q0 = tile_id.qb * 32;
+  if (q0 < seg.nq)
+    wave_attention<DH, STEP>(Ks, Vs, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
   if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64);
+}
+
+// The same work units, dealt to the compute units by weight (batches of up to 64 images, one
+// per lane).  All one-wave workgroups of the launch are resident at once and workgroup j of
+// an XCD runs on compute unit j % 32 (the hardware id register says so), so which units get
+// the long segments is decided by the numbering alone; numbered blindly, the unluckiest SIMDs
+// end a third later than the median.  Here every wave ranks the images by their number of
+// 32-key steps (9 classes, one ballot each; images of a class in index order), the (image,
+// head) pairs of that ranking are dealt to the XCDs in snake order (an XCD's L2 still holds
+// all blocks of its pairs), the XCD's live query blocks are listed heaviest first, and the
+// m-th workgroup of a unit takes block r = 32 m + (unit, or 31 - unit for odd m).  Workgroups
+// past the live blocks only fill; the bypassing rows of y are shared evenly by all.
+template <typename T, int DH>
+__device__ __forceinline__ void scatter_fill_rows(const Scatter& sc, long r0, long r1, long C, int tid, int nthreads) {
+  constexpr int VE = 16 / sizeof(T);
+  const long cpr = C / VE;
+  for (long i = r0 * cpr + tid; i < r1 * cpr; i += nthreads) {
+    const long row = i / cpr, c = i % cpr;
+    if (sc.inv_pos[row] < 0) {
+      const long off = row * C + c * VE;
+      uintx4 val = {0u, 0u, 0u, 0u};
+      if (sc.base != nullptr) val = *reinterpret_cast<const uintx4*>(static_cast<const T*>(sc.base) + off);
+      *reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off) = val;
+    }
+  }
+}
+
+// No tables are needed: with the pairs sorted by
+// class, class c holds the ranked images [A_c, A_c + n_c) (n_c from one ballot), hence the
+// pairs [A_c H, (A_c + n_c) H), of which this XCD owns a count with a closed form; every pair
+// of class c has exactly c live blocks.  Walking the 9 classes with scalar arithmetic finds
+// the class, the pair and the block of number r; the image is the k-th set bit of the class
+// ballot and its bounds come by readlane.
+__device__ __forceinline__ int pairs_below(int X, int x) {        // XCD x's pairs with index < X
+  const int g = X >> 3, s = (g & 1) ? 7 - x : x;
+  return g + (s < (X & 7) ? 1 : 0);
+}
+__device__ __forceinline__ int kth_set_bit(uint64_t mask, int kth) {   // kth < popcount(mask)
+  int pos = 0;
+#pragma unroll
+  for (int sh = 32; sh >= 1; sh >>= 1) {
+    const int cnt = __popcll((mask >> pos) & ((1ull << sh) - 1ull));
+    if (kth >= cnt) {
+      kth -= cnt;
+      pos += sh;
+    }
+  }
+  return pos;
+}
+
+template <int DH, int STEP>
+__global__ void __launch_bounds__(64)
+attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                                const __bf16* __restrict__ v, long qs, long ks, long vs,
+                                const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
+                                int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
+                                long lse_stride, Scatter sc, int B, int nqb) {
+  constexpr int RS = DH + 8;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[STEP * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[STEP * RS];
+  const int lane = threadIdx.x;
+  const int x = blockIdx.x & 7, j = blockIdx.x >> 3, unit = j & 31, m = j >> 5;
+  const bool padded = key_lens != nullptr;
+  int start = 0, len = 0, cls = -1;
+  if (lane < B) {
+    if (padded) {
+      start = lane * n_pad;
+      len = min(max(key_lens[lane], 0), n_pad);
+    } else {
+      start = cu[lane];
+      len = cu[lane + 1] - start;
+    }
+    cls = min((max(len, 0) + 31) >> 5, 8);
+  }
+  const int r = m * 32 + ((m & 1) ? 31 - unit : unit);
+  Segment seg = {0, 0, 0};
+  int h = 0, q0 = 0;
+  int ranked = 0, tiles = 0, g0 = 0;             // images, live blocks, this XCD's pairs of the heavier classes
+  for (int c = 8; c >= 0; --c) {
+    const uint64_t bal = __ballot(cls == c);
+    const int n_c = __popcll(bal);
+    const int per_pair = padded ? nqb : min(c, nqb);
+    const int pairs_c = pairs_below((ranked + n_c) * H, x) - pairs_below(ranked * H, x);
+    const int tiles_c = pairs_c * per_pair;
+    if (r < tiles + tiles_c) {
+      const int idx = r - tiles, g = g0 + idx / per_pair;
+      const int p = 8 * g + ((g & 1) ? 7 - x : x);
+      const int img = kth_set_bit(bal, p / H - ranked);
+      h = p % H;
+      q0 = (idx % per_pair) * 32;
+      seg.row0 = __builtin_amdgcn_readlane(start, img);
+      seg.nk = __builtin_amdgcn_readlane(len, img);
+      seg.nq = padded ? n_pad : seg.nk;
+      break;
+    }
+    tiles += tiles_c;
+    g0 += pairs_c;
+    ranked += n_c;
+  }
+  if (q0 < seg.nq)
+    wave_attention<DH, STEP>(Ks, Vs, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
+  if (sc.y != nullptr) {
+    const long rows = sc.flat ? (long)sc.N : (long)B * sc.N, per = (rows + gridDim.x - 1) / gridDim.x;
+    const long r0 = min(rows, blockIdx.x * per), r1 = min(rows, r0 + per);
+    scatter_fill_rows<__bf16, DH>(sc, r0, r1, (long)H * DH, lane, 64);
+  }
 }
 
 // Short segments (every segment <= NKMAX keys).  ONE workgroup per (image, head): all K / V
@@ -734,7 +850,14 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
       const int nqb = (n_max + 31) / 32;
       const dim3 grid(xcd_grid(nqb, H, B));
       const bool step64 = short_env != nullptr && std::strstr(short_env, "64") != nullptr;
-      if (Dh == 32) {
+      // default: blocks dealt to the compute units by weight ("plain" in SPA_ATTN_FWD_SHORT: numbered blindly)
+      const bool plain = short_env != nullptr && std::strstr(short_env, "plain") != nullptr;
+      if (!step64 && !plain && B <= kWave) {
+        const long g8 = ((long)B * H + 7) / 8;
+        const dim3 lgrid((unsigned)(8 * 32 * ((g8 * nqb + 31) / 32)));
+        if (Dh == 32) hipLaunchKernelGGL((attn_fwd_bf16_wave_lpt64_kernel<32, 32>), lgrid, dim3(64), 0, st, SPA_ARGS, B, nqb);
+        else hipLaunchKernelGGL((attn_fwd_bf16_wave_lpt64_kernel<64, 32>), lgrid, dim3(64), 0, st, SPA_ARGS, B, nqb);
+      } else if (Dh == 32) {
         if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 64>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
         else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 32>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
       } else {

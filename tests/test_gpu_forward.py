@@ -267,12 +267,13 @@ def test_argument_validation_returns_errors_before_launch(spa):
 
 
 @pytest.mark.parametrize("dtype,Dh,N,short", [("f32", 32, 150, ""), ("bf16", 64, 196, ""), ("bf16", 64, 196, "wave"),
+                                              ("bf16", 64, 196, "wave plain"), ("bf16", 32, 250, "wave"),
                                               ("bf16", 32, 49, ""), ("bf16", 32, 700, ""), ("bf16", 64, 300, "")])
 @pytest.mark.parametrize("with_base,keep_out", [(False, True), (True, False)])
 def test_fused_attention_unpack_equals_separate_calls(spa, monkeypatch, dtype, Dh, N, short, with_base, keep_out):
     """spa_packed_attention_unpack == spa_packed_attention followed by spa_unpack, bit for bit,
-    for the short-segment kernels (whole / wave), the tiled kernel and the fp32 kernel; and
-    both equal the oracle within tolerance."""
+    for the short-segment kernels (whole / wave with blocks numbered by weight / wave numbered
+    blindly), the tiled kernel and the fp32 kernel; and both equal the oracle within tolerance."""
     if short:
         monkeypatch.setenv("SPA_ATTN_FWD_SHORT", short)
     else:
@@ -312,3 +313,34 @@ def test_fused_attention_unpack_equals_separate_calls(spa, monkeypatch, dtype, D
     ref_y = orc.unpack(ref_out, orc.pack_indices(mask)[2], B, N, base)
     tol = TOL[dtype] * (2 if with_base and dtype == "bf16" else 1)
     assert np.max(np.abs(host(y2) - ref_y)) <= tol
+
+
+@pytest.mark.parametrize("B", [64, 70])
+def test_short_segments_many_images(spa, B):
+    """The one-wave kernel with as many images as lanes (blocks numbered by weight) and with
+    more (numbered blindly): same results as the oracle, fused scatter equal to separate calls."""
+    N, H, Dh = 40, 3, 32
+    C, cap = H * Dh, B * N
+    rng = np.random.default_rng(B)
+    qkv = wlmod.round_bf16(rng.standard_normal((B, N, 3 * C)).astype(np.float32))
+    mask = (rng.uniform(size=(B, N)) < rng.uniform(0.0, 1.0, size=(B, 1))).astype(np.uint8)
+    mask[3] = 0
+    mask[B - 1] = 1
+    td = torch.bfloat16
+    packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    gidx = torch.zeros(cap, dtype=torch.int32, device="cuda")
+    inv = torch.empty(cap, dtype=torch.int32, device="cuda")
+    spa.spa_pack(dev(qkv, "bf16"), dev(mask), None, None, 0, packed, cu, gidx, inv, None)
+    pq, pk, pv = packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:]
+    out1 = torch.zeros(cap, C, dtype=td, device="cuda")
+    y1 = torch.full((B, N, C), float("nan"), dtype=td, device="cuda")
+    y2 = torch.full((B, N, C), float("nan"), dtype=td, device="cuda")
+    spa.spa_packed_attention(pq, pk, pv, cu, B, N, H, Dh, out1, None)
+    spa.spa_unpack(out1, inv, None, y1)
+    spa.spa_packed_attention_unpack(pq, pk, pv, cu, gidx, inv, None, H, Dh, y2, None, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(y1), host(y2))
+    ref_out, _ = orc.attention_per_image(qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], mask, H)
+    T = int(mask.sum())
+    assert np.max(np.abs(host(out1)[:T] - ref_out)) <= TOL["bf16"]
