@@ -514,17 +514,23 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 // all blocks of its pairs), the XCD's live query blocks are listed heaviest first, and the
 // m-th workgroup of a unit takes block r = 32 m + (unit, or 31 - unit for odd m).  Workgroups
 // past the live blocks only fill; the bypassing rows of y are shared evenly by all.
-template <typename T, int DH>
-__device__ __forceinline__ void scatter_fill_rows(const Scatter& sc, long r0, long r1, long C, int tid, int nthreads) {
+// One wave fills the bypassing rows among rows [r0, r1) of y: the lanes test 64 rows at a time
+// (one load each), then the wave writes the rows that need it, a lane per 16-byte chunk.
+template <typename T>
+__device__ __forceinline__ void scatter_fill_rows(const Scatter& sc, long r0, long r1, long C, int lane) {
   constexpr int VE = 16 / sizeof(T);
-  const long cpr = C / VE;
-  for (long i = r0 * cpr + tid; i < r1 * cpr; i += nthreads) {
-    const long row = i / cpr, c = i % cpr;
-    if (sc.inv_pos[row] < 0) {
-      const long off = row * C + c * VE;
-      uintx4 val = {0u, 0u, 0u, 0u};
-      if (sc.base != nullptr) val = *reinterpret_cast<const uintx4*>(static_cast<const T*>(sc.base) + off);
-      *reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off) = val;
+  const int cpr = (int)(C / VE);
+  for (long rb = r0; rb < r1; rb += kWave) {
+    const long row = rb + lane;
+    uint64_t todo = __ballot(row < r1 && sc.inv_pos[row] < 0);
+    while (todo != 0) {
+      const long off0 = (rb + __ffsll((unsigned long long)todo) - 1) * C;
+      todo &= todo - 1;
+      for (int c = lane; c < cpr; c += kWave) {
+        uintx4 val = {0u, 0u, 0u, 0u};
+        if (sc.base != nullptr) val = *reinterpret_cast<const uintx4*>(static_cast<const T*>(sc.base) + off0 + c * VE);
+        *reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off0 + c * VE) = val;
+      }
     }
   }
 }
@@ -606,7 +612,7 @@ attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __re
   if (sc.y != nullptr) {
     const long rows = sc.flat ? (long)sc.N : (long)B * sc.N, per = (rows + gridDim.x - 1) / gridDim.x;
     const long r0 = min(rows, blockIdx.x * per), r1 = min(rows, r0 + per);
-    scatter_fill_rows<__bf16, DH>(sc, r0, r1, (long)H * DH, lane, 64);
+    scatter_fill_rows<__bf16>(sc, r0, r1, (long)H * DH, lane);
   }
 }
 
