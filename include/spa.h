@@ -318,8 +318,9 @@ int spa_packed_attention_bwd(const void* q, const void* k, const void* v, int64_
  * spa_unpack_bwd, spa_packed_attention_bwd and spa_pack_bwd (of dq, dk and dv) in one launch:
  * the upstream gradient is read at the token positions and the gradients are written at the
  * token positions (the transposes of the scatter and gather of Section 3.2 folded into the
- * attention backward).  bf16 with max_seqlen <= 256 only; SPA_ERR_UNSUPPORTED otherwise (use
- * the three separate calls).
+ * attention backward).  bf16 only; fp32 returns SPA_ERR_UNSUPPORTED (use the three separate
+ * calls).  workspace as for spa_packed_attention_bwd; with max_seqlen <= 256 none is needed
+ * and NULL may be passed.
  * in:  q, k, v, out, lse, cu_seqlens as in spa_packed_attention_bwd; dy [rows, H*Dh] dtype
  *      contiguous, the gradient of the spa_unpack output; gather_idx, inv_pos [rows] int32
  *      from spa_pack; rows = B*N.
@@ -334,7 +335,8 @@ int spa_packed_attention_bwd_tokens(const void* q, const void* k, const void* v,
                                     int dtype, float softmax_scale, const int32_t* gather_idx,
                                     const int32_t* inv_pos, int64_t rows,
                                     void* dq, void* dk, void* dv, int64_t dq_row_stride,
-                                    int64_t dk_row_stride, int64_t dv_row_stride, void* stream);
+                                    int64_t dk_row_stride, int64_t dv_row_stride,
+                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace spa_gate_bwd needs. Host. */
 size_t spa_gate_bwd_workspace_bytes(int B, int N, int C, int dtype);

@@ -34,6 +34,45 @@ __device__ __forceinline__ Seg seg_of(int b, const int32_t* cu) {
 }
 
 
+// Token-position I/O folded into the kernel (gather_idx == nullptr: packed I/O): the upstream
+// gradient row of packed token j is dy[gather_idx[j]], the gradients of packed token j go to
+// row gather_idx[j] of dq / dk / dv, and the rows of unselected tokens (inv_pos < 0) are zeroed,
+// every workgroup of the launch clearing an even share (one-kernel form: its head's columns).
+struct TokenIO {
+  const int32_t* gather_idx;
+  const int32_t* inv_pos;
+  long rows;               // B * N
+};
+
+template <int DH, int RS>
+__device__ __forceinline__ void flush_tile_rows(const __bf16* tile, __bf16* dst, long row_stride, int nrows, int lane,
+                                                const int32_t* row_index) {
+  constexpr int CPR = DH / 8;
+#pragma unroll
+  for (int i = lane; i < 32 * CPR; i += 64) {
+    const int r = i / CPR, c = i % CPR;
+    if (r < nrows)
+      *reinterpret_cast<bf16x8*>(dst + (long)row_index[r] * row_stride + c * 8) =
+          *reinterpret_cast<const bf16x8*>(&tile[r * RS + c * 8]);
+  }
+}
+
+// One wave zeroes columns [0, C) of the unselected rows among rows [r0, r1): the lanes test 64
+// rows at a time, then the wave writes the rows that need it, a lane per 16-byte chunk.
+__device__ __forceinline__ void zero_unselected_rows(__bf16* dst, long row_stride, int C, const int32_t* inv_pos, long r0,
+                                                     long r1, int lane) {
+  const bf16x8 z = zero_bf16x8();
+  for (long rb = r0; rb < r1; rb += kWave) {
+    const long row = rb + lane;
+    uint64_t todo = __ballot(row < r1 && inv_pos[row] < 0);
+    while (todo != 0) {
+      __bf16* p = dst + (rb + __ffsll((unsigned long long)todo) - 1) * row_stride;
+      todo &= todo - 1;
+      for (int c = lane; c < C / 8; c += kWave) *reinterpret_cast<bf16x8*>(p + c * 8) = z;
+    }
+  }
+}
+
 // Both bf16 kernels use the forward's launch scheme: 1-D XCD-aware grid (the blocks that
 // share one (image, head)'s rows sit on one L2), longest image first, 4 waves x 32 rows per
 // workgroup, the other side of the product streaming through double-buffered row-major LDS
@@ -66,8 +105,10 @@ attn_bwd_dq_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __bf1
                  const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs,
                  const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                  const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
-                 float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B) {
+                 float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B,
+                 const TokenIO tok = TokenIO{nullptr, nullptr, 0}) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW, NBUF = NW == 1 ? 1 : 2;
+  const bool at_tokens = tok.gather_idx != nullptr;
   auto& Ks = lds.A;
   auto& Vs = lds.Bm;
   int* s_cu = lds.s_cu;
@@ -101,8 +142,9 @@ attn_bwd_dq_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __bf1
     dof[kk] = zero_bf16x8();
     if (q_ok) {
       const int col = h * DH + kk * 16 + hh * 8;
+      const long grow = at_tokens ? (long)tok.gather_idx[seg.row0 + qi] : seg.row0 + qi;
       qf[kk] = *reinterpret_cast<const bf16x8*>(q + (seg.row0 + qi) * qs + col);
-      dof[kk] = *reinterpret_cast<const bf16x8*>(dout + (seg.row0 + qi) * C + col);
+      dof[kk] = *reinterpret_cast<const bf16x8*>(dout + grow * C + col);
       if (!kHaveD) {
         const floatx8 of = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(out + (seg.row0 + qi) * C + col));
         const floatx8 gf = bf16x8_to_float(dof[kk]);
@@ -182,9 +224,13 @@ attn_bwd_dq_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __bf1
   __bf16* tile = &Ks[0][0] + wv * 32 * RS;
   if (wave_live) park_tile<DH, RS>(acc, scale, tile, l32, hh);
   __syncthreads();
-  if (wave_live)
-    flush_tile<DH, RS>(tile, dq + (seg.row0 + q0 + wv * 32) * gstride + h * DH, gstride,
-                       min(32, seg.nq - q0 - wv * 32), lane);
+  if (wave_live) {
+    const int nrows = min(32, seg.nq - q0 - wv * 32);
+    if (at_tokens)
+      flush_tile_rows<DH, RS>(tile, dq + h * DH, gstride, nrows, lane, tok.gather_idx + seg.row0 + q0 + wv * 32);
+    else
+      flush_tile<DH, RS>(tile, dq + (seg.row0 + q0 + wv * 32) * gstride + h * DH, gstride, nrows, lane);
+  }
 }
 
 template <int DH, int NW, int BT, bool LPT>
@@ -207,8 +253,10 @@ attn_bwd_dkdv_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __b
                    const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs,
                    const __bf16* __restrict__ dout, const float* __restrict__ lse,
                    const float* __restrict__ dvec, long lse_stride, const int32_t* __restrict__ cu, int H,
-                   float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs, int B) {
+                   float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs, int B,
+                   const TokenIO tok = TokenIO{nullptr, nullptr, 0}) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW, NBUF = NW == 1 ? 1 : 2;
+  const bool at_tokens = tok.gather_idx != nullptr;
   auto& Qs = lds.A;
   auto& Gs = lds.Bm;                  // dO rows
   auto& lse2s = lds.lse2s;
@@ -250,7 +298,8 @@ attn_bwd_dkdv_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __b
     }
   };
   qst.load(qh, seg.row0, seg.nq, qs);
-  gst.load(gh, seg.row0, seg.nq, C);
+  if (at_tokens) gst.load_rows(gh, tok.gather_idx + seg.row0, seg.nq, C);
+  else gst.load(gh, seg.row0, seg.nq, C);
   load_stats(0);
 
   bf16x8 kf[KK], vf[KK];
@@ -279,7 +328,8 @@ attn_bwd_dkdv_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __b
     const int buf = t & (NBUF - 1), nbuf = (t + 1) & (NBUF - 1), qt = t * BT;
     if (t + 1 < nt) {
       qst.load(qh, seg.row0 + qt + BT, seg.nq - qt - BT, qs);
-      gst.load(gh, seg.row0 + qt + BT, seg.nq - qt - BT, C);
+      if (at_tokens) gst.load_rows(gh, tok.gather_idx + seg.row0 + qt + BT, seg.nq - qt - BT, C);
+      else gst.load(gh, seg.row0 + qt + BT, seg.nq - qt - BT, C);
       load_stats(qt + BT);
     }
     if (wave_live) {
@@ -341,8 +391,14 @@ attn_bwd_dkdv_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __b
   __syncthreads();
   if (wave_live) {
     const int nrows = min(32, seg.nk - k0 - wv * 32);
-    flush_tile<DH, RS>(ktile, dk + (seg.row0 + k0 + wv * 32) * dks + h * DH, dks, nrows, lane);
-    flush_tile<DH, RS>(vtile, dv + (seg.row0 + k0 + wv * 32) * dvs + h * DH, dvs, nrows, lane);
+    if (at_tokens) {
+      const int32_t* ri = tok.gather_idx + seg.row0 + k0 + wv * 32;
+      flush_tile_rows<DH, RS>(ktile, dk + h * DH, dks, nrows, lane, ri);
+      flush_tile_rows<DH, RS>(vtile, dv + h * DH, dvs, nrows, lane, ri);
+    } else {
+      flush_tile<DH, RS>(ktile, dk + (seg.row0 + k0 + wv * 32) * dks + h * DH, dks, nrows, lane);
+      flush_tile<DH, RS>(vtile, dv + (seg.row0 + k0 + wv * 32) * dvs + h * DH, dvs, nrows, lane);
+    }
   }
 }
 
@@ -372,16 +428,30 @@ attn_bwd_both_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                           const float* __restrict__ lse, float* __restrict__ dvec, long lse_stride,
                           const int32_t* __restrict__ cu, int H, float scale, __bf16* __restrict__ dq, long dqs,
-                          __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs, int B, int nblk) {
+                          __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs, int B, int nblk,
+                          TokenIO tok) {
   __shared__ BwdLds<DH, NW, BT, true> lds;
   const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
   const TileId tile_id = xcd_tile_at(xcd, jj >> 1, nblk, H, B);
   if (jj & 1)
     attn_bwd_dkdv_body<DH, NW, BT, true>(lds, tile_id, q, k, v, qs, ks, vs, dout, lse, dvec, lse_stride, cu, H, scale,
-                                         dk, dks, dv, dvs, B);
+                                         dk, dks, dv, dvs, B, tok);
   else
     attn_bwd_dq_body<DH, NW, BT, true, true>(lds, tile_id, q, k, v, qs, ks, vs, out, dout, lse, lse_stride, cu, H,
-                                             scale, dq, dqs, dvec, B);
+                                             scale, dq, dqs, dvec, B, tok);
+  if (tok.gather_idx != nullptr) {
+    // gradients of the unselected tokens: every workgroup of a role (with or without a tile) zeroes an
+    // even share of the rows, a quarter per wave: the dq role in dq, the dkdv role in dk and dv
+    const long units = (long)(gridDim.x >> 1) * NW, u = ((long)xcd + 8 * (jj >> 1)) * NW + (threadIdx.x >> 6);
+    const long per = (tok.rows + units - 1) / units, r0 = min(tok.rows, u * per), r1 = min(tok.rows, r0 + per);
+    const int lane = threadIdx.x & 63;
+    if (jj & 1) {
+      zero_unselected_rows(dk, dks, H * DH, tok.inv_pos, r0, r1, lane);
+      zero_unselected_rows(dv, dvs, H * DH, tok.inv_pos, r0, r1, lane);
+    } else {
+      zero_unselected_rows(dq, dqs, H * DH, tok.inv_pos, r0, r1, lane);
+    }
+  }
 }
 
 // D[h][j] = <dO_j, O_j> over head h's columns, for the packed rows j < cu[B]: DH / 8 adjacent
@@ -389,7 +459,7 @@ attn_bwd_both_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 template <int DH>
 __global__ void __launch_bounds__(256)
 attn_bwd_dvec_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout, const int32_t* __restrict__ cu,
-                     int B, int H, long lse_stride, float* __restrict__ dvec) {
+                     int B, int H, long lse_stride, float* __restrict__ dvec, const int32_t* __restrict__ gather_idx) {
   constexpr int CPR = DH / 8;
   const long C = (long)H * DH, total = (long)cu[B] * H * CPR;
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < ((total + 63) & ~63L); i += (long)gridDim.x * 256) {
@@ -400,7 +470,8 @@ attn_bwd_dvec_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ 
     float d = 0.f;
     if (i < total) {
       const floatx8 of = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(out + row * C + h * DH + c * 8));
-      const floatx8 gf = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(dout + row * C + h * DH + c * 8));
+      const long grow = gather_idx != nullptr ? (long)gather_idx[row] : row;
+      const floatx8 gf = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(dout + grow * C + h * DH + c * 8));
 #pragma unroll
       for (int e = 0; e < 8; ++e) d = fmaf(of[e], gf[e], d);
     }
@@ -422,29 +493,6 @@ attn_bwd_dvec_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ 
 // no atomics, run-to-run bit-stable.
 // Dynamic LDS, rows = 32 * nw:  Q [rows][DH+8] | dO [rows][DH+8] | dQ accumulators [nw] tiles
 // of DH*32 fp32 in register layout | dS tiles [nw][32][40] bf16 | lse*log2(e) [rows] | D [rows].
-// Token-position I/O folded into the kernel (gather_idx == nullptr: packed I/O): the upstream
-// gradient row of packed token j is dy[gather_idx[j]], the gradients of packed token j go to
-// row gather_idx[j] of dq / dk / dv, and the rows of unselected tokens (inv_pos < 0) are zeroed:
-// the workgroup of (launch rank, head) clears that head's columns of an even share of the rows.
-struct TokenIO {
-  const int32_t* gather_idx;
-  const int32_t* inv_pos;
-  long rows;               // B * N
-};
-
-template <int DH, int RS>
-__device__ __forceinline__ void flush_tile_rows(const __bf16* tile, __bf16* dst, long row_stride, int nrows, int lane,
-                                                const int32_t* row_index) {
-  constexpr int CPR = DH / 8;
-#pragma unroll
-  for (int i = lane; i < 32 * CPR; i += 64) {
-    const int r = i / CPR, c = i % CPR;
-    if (r < nrows)
-      *reinterpret_cast<bf16x8*>(dst + (long)row_index[r] * row_stride + c * 8) =
-          *reinterpret_cast<const bf16x8*>(&tile[r * RS + c * 8]);
-  }
-}
-
 template <int DH>
 __host__ __device__ constexpr size_t bwd_fused_lds_bytes(int nw) {
   return (size_t)nw * (2 * 32 * (DH + 8) * 2 + DH * 32 * 4 + 32 * 40 * 2 + 2 * 32 * 4);
@@ -836,11 +884,16 @@ static int attention_bwd_common(const char* fn, const void* q, const void* k, co
               SPA_ERR_INVALID_ARG, "%s: tensors not 16-byte aligned", fn);
   SPA_REQUIRE(softmax_scale >= 0.f && std::isfinite(softmax_scale), SPA_ERR_INVALID_ARG,
               "%s: softmax_scale must be finite and >= 0", fn);
-  const size_t need = at_tokens ? 0 : spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype);
-  SPA_REQUIRE(at_tokens || (workspace != nullptr && workspace_bytes >= need), SPA_ERR_WORKSPACE,
+  SPA_REQUIRE(!at_tokens || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED,
+              "%s: bf16 only (fp32: spa_unpack_bwd, spa_packed_attention_bwd, spa_pack_bwd)", fn);
+  // short segments: the one-kernel form.  SPA_ATTN_BWD_SHORT = "split" keeps the two one-wave
+  // kernels, "tiled" forces the long-segment kernels (tuning aids).
+  const char* env = std::getenv("SPA_ATTN_BWD_SHORT");
+  const bool short_seg = max_seqlen <= 256 && !(env != nullptr && env[0] == 't');
+  const bool one_kernel = dtype == SPA_BF16 && short_seg && (at_tokens || !(env != nullptr && env[0] == 's'));
+  const size_t need = one_kernel ? 0 : spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype);
+  SPA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SPA_ERR_WORKSPACE,
               "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace_bytes);
-  SPA_REQUIRE(!at_tokens || (dtype == SPA_BF16 && max_seqlen <= 256), SPA_ERR_UNSUPPORTED,
-              "%s: bf16 and max_seqlen <= 256 only (else spa_unpack_bwd, spa_packed_attention_bwd, spa_pack_bwd)", fn);
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)Dh);
   const long ls = (long)B * max_seqlen;
   float* dvec = static_cast<float*>(workspace);
@@ -867,11 +920,7 @@ static int attention_bwd_common(const char* fn, const void* q, const void* k, co
   (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_row_stride, (long)k_row_stride,               \
       (long)v_row_stride, (const __bf16*)dout, lse, dvec, ls, cu_seqlens, H, scale, (__bf16*)dk,              \
       (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride, B, nblk
-    // short segments: the one-kernel form.  SPA_ATTN_BWD_SHORT = "split" keeps the two one-wave
-    // kernels, "tiled" forces the 4-wave kernels (tuning aids).
-    const char* env = std::getenv("SPA_ATTN_BWD_SHORT");
-    const bool short_seg = max_seqlen <= 256 && !(env != nullptr && env[0] == 't');
-    if (at_tokens || (short_seg && !(env != nullptr && env[0] == 's'))) {
+    if (one_kernel) {
       const int nw = (max_seqlen + 31) / 32;
       SPA_REQUIRE((long)B * H < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H must be < 2^31", fn);
 #define SPA_BWD_FUSED(D)                                                                                        \
@@ -906,19 +955,19 @@ static int attention_bwd_common(const char* fn, const void* q, const void* k, co
   } while (0)
     // long segments: D first, then both sides in one launch (SPA_ATTN_BWD_LONG=two keeps two launches)
     const char* lenv = std::getenv("SPA_ATTN_BWD_LONG");
-    if (!short_seg && !(lenv != nullptr && lenv[0] == 't')) {
+    if (!short_seg && (at_tokens || !(lenv != nullptr && lenv[0] == 't'))) {
       SPA_REQUIRE(2L * grid.x < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H*blocks must be < 2^30", fn);
       const long rows_cap = (long)B * max_seqlen;
       const unsigned dgrid = (unsigned)std::min<long>((rows_cap * H * (Dh / 8) + 255) / 256, 4096L);
 #define SPA_BWD_BOTH(D)                                                                                          \
   do {                                                                                                           \
     hipLaunchKernelGGL((attn_bwd_dvec_kernel<D>), dim3(dgrid), dim3(256), 0, st, (const __bf16*)out,             \
-                       (const __bf16*)dout, cu_seqlens, B, H, ls, dvec);                                         \
+                       (const __bf16*)dout, cu_seqlens, B, H, ls, dvec, tok.gather_idx);                         \
     hipLaunchKernelGGL((attn_bwd_both_bf16_kernel<D, 4, 64>), dim3(2 * grid.x), dim3(256), 0, st,                \
                        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_row_stride,                 \
                        (long)k_row_stride, (long)v_row_stride, (const __bf16*)out, (const __bf16*)dout, lse,     \
                        dvec, ls, cu_seqlens, H, scale, (__bf16*)dq, (long)dq_row_stride, (__bf16*)dk,            \
-                       (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride, B, nblk);                          \
+                       (long)dk_row_stride, (__bf16*)dv, (long)dv_row_stride, B, nblk, tok);                     \
   } while (0)
       if (Dh == 32) SPA_BWD_BOTH(32); else SPA_BWD_BOTH(64);
 #undef SPA_BWD_BOTH
@@ -951,11 +1000,13 @@ extern "C" int spa_packed_attention_bwd_tokens(const void* q, const void* k, con
                                                int max_seqlen, int H, int Dh, int dtype, float softmax_scale,
                                                const int32_t* gather_idx, const int32_t* inv_pos, int64_t rows,
                                                void* dq, void* dk, void* dv, int64_t dq_row_stride,
-                                               int64_t dk_row_stride, int64_t dv_row_stride, void* stream) {
+                                               int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
+                                               size_t workspace_bytes, void* stream) {
   const char* fn = "spa_packed_attention_bwd_tokens";
   SPA_REQUIRE(gather_idx && inv_pos, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(rows >= 1 && rows < 2147483647L, SPA_ERR_INVALID_ARG, "%s: rows must be in [1, 2^31)", fn);
   return attention_bwd_common(fn, q, k, v, q_row_stride, k_row_stride, v_row_stride, out, dy, lse, cu_seqlens, B,
                               max_seqlen, H, Dh, dtype, softmax_scale, dq, dk, dv, dq_row_stride, dk_row_stride,
-                              dv_row_stride, nullptr, 0, TokenIO{gather_idx, inv_pos, (long)rows}, stream);
+                              dv_row_stride, workspace, workspace_bytes, TokenIO{gather_idx, inv_pos, (long)rows},
+                              stream);
 }

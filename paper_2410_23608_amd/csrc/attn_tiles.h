@@ -201,6 +201,16 @@ struct RowStage {
       if (i < CHUNKS && r < nrows) reg[t] = *reinterpret_cast<const bf16x8*>(src + (base + r) * stride + c * 8);
     }
   }
+  // the same with row r taken at src + row_index[r] * stride (rows gathered through an index)
+  __device__ __forceinline__ void load_rows(const __bf16* src, const int32_t* row_index, int nrows, long stride) {
+#pragma unroll
+    for (int t = 0; t < CPT; ++t) {
+      const int i = threadIdx.x + t * THREADS, r = i / CPR, c = i % CPR;
+      reg[t] = zero_bf16x8();
+      if (i < CHUNKS && r < nrows)
+        reg[t] = *reinterpret_cast<const bf16x8*>(src + (long)row_index[r] * stride + c * 8);
+    }
+  }
   __device__ __forceinline__ void store(__bf16* rows) const {
 #pragma unroll
     for (int t = 0; t < CPT; ++t) {

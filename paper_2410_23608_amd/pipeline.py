@@ -85,14 +85,14 @@ class TrainPass:
     representation r_g = Sigmoid(s) . r, so the gate receives the attention's gradient:
       fwd: gate_select(x) -> pack(qk) -> pack(x, scaled by sigmoid(s)) -> attention + unpack (one launch)
       bwd: unpack_bwd(dy) -> attention_bwd -> pack_bwd(dv) [-> pack_bwd(dq|dk)] -> gate_bwd
-    fused_bwd (default: where the library supports it, bf16 and N <= 256): the gather of dy and
-    the scatters of dq, dk, dv run inside the attention backward, 6 launches instead of 9.
+    fused_bwd (default: where the library supports it, bf16): the gather of dy and the scatters
+    of dq, dk, dv run inside the attention backward, 6 calls instead of 9.
     """
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
                  loss_scale: Optional[float] = None, fused_bwd: Optional[bool] = None):
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
-        self.fused_bwd = (dtype == "bf16" and N <= 256) if fused_bwd is None else fused_bwd
+        self.fused_bwd = (dtype == "bf16") if fused_bwd is None else fused_bwd
         self.tau, self.bias = tau, bias
         self.loss_scale = 0.01 / (B * N) if loss_scale is None else loss_scale
         td, cap = _td(dtype), B * N
@@ -159,7 +159,7 @@ class TrainPass:
             dqk_tok = self.dqk.view(B * N, 2 * C)
             attention_bwd = [("packed_attention_bwd_tokens", spa.spa_packed_attention_bwd_tokens(
                 pq, pk, pv, self.out, dy, self.lse, self.cu_seqlens, B, N, H, Dh, self.gather_idx, self.inv_pos,
-                dqk_tok[:, :C], dqk_tok[:, C:], self.d_rg.view(B * N, C), prepare=True))]
+                dqk_tok[:, :C], dqk_tok[:, C:], self.d_rg.view(B * N, C), self.ws_attn, prepare=True))]
         else:
             attention_bwd = [
                 ("unpack_bwd", spa.spa_unpack_bwd(dy, self.gather_idx, self.total, self.dout, prepare=True)),

@@ -60,7 +60,7 @@ _SIGNATURES = {
                                          c_size_t, _P]),
     "spa_packed_attention_bwd_tokens": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int,
                                                 c_int, c_int, c_int, c_float, _P, _P, c_int64, _P, _P, _P, c_int64,
-                                                c_int64, c_int64, _P]),
+                                                c_int64, c_int64, _P, c_size_t, _P]),
     "spa_gate_bwd_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int]),
     "spa_gate_bwd": (c_int, [_P, _P, c_float, _P, _P, _P, _P, c_int, c_float, c_int, c_int, c_int, c_int,
                              _P, _P, _P, _P, _P, c_size_t, _P]),
@@ -348,16 +348,18 @@ def spa_packed_attention_bwd(q, k, v, out, dout, lse, cu_seqlens, B, max_seqlen,
 
 
 def spa_packed_attention_bwd_tokens(q, k, v, out, dy, lse, cu_seqlens, B, max_seqlen, H, Dh, gather_idx, inv_pos,
-                                    dq, dk, dv, softmax_scale=0.0, prepare=False):
-    """unpack_bwd + attention backward + pack_bwd in one launch: dy and dq, dk, dv at token positions."""
+                                    dq, dk, dv, workspace=None, softmax_scale=0.0, prepare=False):
+    """unpack_bwd + attention backward + pack_bwd in one call: dy and dq, dk, dv at token positions
+    (workspace: only for max_seqlen > 256)."""
     rows = dy.numel() // dy.shape[-1]
-    _keep = (out, dy, lse, cu_seqlens, gather_idx, inv_pos,)
+    _keep = (out, dy, lse, cu_seqlens, gather_idx, inv_pos, workspace,)
     _contig(*_keep)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     return _dispatch(lib.spa_packed_attention_bwd_tokens,
                      (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(out), _ptr(dy),
                       _ptr(lse), _ptr(cu_seqlens), B, max_seqlen, H, Dh, dtype_code(out), float(softmax_scale),
                       _ptr(gather_idx), _ptr(inv_pos), rows, _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq),
-                      _row_stride(dk), _row_stride(dv), _stream(),), _keep, prepare)
+                      _row_stride(dk), _row_stride(dv), _ptr(workspace), ws_bytes, _stream(),), _keep, prepare)
 
 
 def spa_gate_bwd_workspace_bytes(B, N, C, dtype) -> int:

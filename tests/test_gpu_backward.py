@@ -73,12 +73,12 @@ def test_attention_backward_matches_oracle(spa, dtype, Dh, N):
         assert _rel(got[:T], ref) <= tol, (name, _rel(got[:T], ref))
 
 
-@pytest.mark.parametrize("Dh,H,N", [(64, 2, 256), (64, 3, 196), (32, 4, 100), (32, 2, 40)])
+@pytest.mark.parametrize("Dh,H,N", [(64, 2, 256), (64, 3, 196), (32, 4, 100), (32, 2, 40), (32, 3, 700), (64, 2, 300)])
 def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N):
     """spa_packed_attention_bwd_tokens = unpack_bwd + attention backward + pack_bwd (x3): same bits at the
     selected tokens, zeros elsewhere, nothing else written."""
     C = H * Dh
-    lens = [n for n in [0, 1, 31, 33, 64, 97, 130, 200] if n < N] + [N, 0]
+    lens = [n for n in [0, 1, 31, 33, 64, 97, 130, 200, 257, 513] if n < N] + [N, 0]
     B, cap = len(lens), len(lens) * N
     rng = np.random.default_rng(N + Dh)
     qkv = wlmod.round_bf16(rng.standard_normal((B, N, 3 * C)).astype(np.float32))
@@ -108,7 +108,7 @@ def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N)
     # one call, into a wider buffer whose extra columns must stay untouched
     got = torch.full((cap, 3 * C + 8), float("nan"), dtype=td, device="cuda")
     spa.spa_packed_attention_bwd_tokens(pq, pk, pv, out, dy, lse, cu, B, N, H, Dh, gidx, inv,
-                                        got[:, :C], got[:, C:2 * C], got[:, 2 * C:3 * C])
+                                        got[:, :C], got[:, C:2 * C], got[:, 2 * C:3 * C], ws if N > 256 else None)
     torch.cuda.synchronize()
     assert torch.equal(got[:, :3 * C], ref.view(cap, 3 * C))
     assert bool(torch.isnan(got[:, 3 * C:]).all())
