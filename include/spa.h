@@ -318,9 +318,8 @@ int spa_packed_attention_bwd(const void* q, const void* k, const void* v, int64_
  * spa_unpack_bwd, spa_packed_attention_bwd and spa_pack_bwd (of dq, dk and dv) in one launch:
  * the upstream gradient is read at the token positions and the gradients are written at the
  * token positions (the transposes of the scatter and gather of Section 3.2 folded into the
- * attention backward).  bf16 only; fp32 returns SPA_ERR_UNSUPPORTED (use the three separate
- * calls).  workspace as for spa_packed_attention_bwd; with max_seqlen <= 256 none is needed
- * and NULL may be passed.
+ * attention backward).  workspace as for spa_packed_attention_bwd; bf16 with max_seqlen <= 256
+ * needs none and NULL may be passed.
  * in:  q, k, v, out, lse, cu_seqlens as in spa_packed_attention_bwd; dy [rows, H*Dh] dtype
  *      contiguous, the gradient of the spa_unpack output; gather_idx, inv_pos [rows] int32
  *      from spa_pack; rows = B*N.

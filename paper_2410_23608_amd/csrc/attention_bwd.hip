@@ -759,7 +759,7 @@ attn_bwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k, co
                     long qs, long ks, long vs, const float* __restrict__ out, const float* __restrict__ dout,
                     const float* __restrict__ lse, float* __restrict__ dvec, long lse_stride,
                     const int32_t* __restrict__ cu, int H, float scale, float* __restrict__ g0, long g0s,
-                    float* __restrict__ g1, long g1s) {
+                    float* __restrict__ g1, long g1s, TokenIO tok) {
   constexpr int BM = 128, BN = 32;
   __shared__ __attribute__((aligned(16))) float As[BN * DH];   // K (query side) or Q (key side)
   __shared__ __attribute__((aligned(16))) float Bs[BN * DH];   // V (query side) or dO (key side)
@@ -768,12 +768,27 @@ attn_bwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k, co
   const int h = blockIdx.y;
   const Seg seg = seg_of(blockIdx.z, cu);
   const int r0 = blockIdx.x * BM;
-  if (r0 >= seg.n) return;
   const int tid = threadIdx.x;
+  const bool at_tokens = tok.gather_idx != nullptr;
+  if (at_tokens) {   // gradients of the unselected tokens: this head's columns of an even share of the rows
+    const long units = (long)gridDim.x * gridDim.z, u = (long)blockIdx.z * gridDim.x + blockIdx.x;
+    const long per = (tok.rows + units - 1) / units, i0 = min(tok.rows, u * per), i1 = min(tok.rows, i0 + per);
+    const floatx4 z = {0.f, 0.f, 0.f, 0.f};
+    for (long i = i0 * (DH / 4) + tid; i < i1 * (DH / 4); i += BM) {
+      const long row = i / (DH / 4);
+      const int c = (int)(i % (DH / 4));
+      if (tok.inv_pos[row] < 0) {
+        *reinterpret_cast<floatx4*>(g0 + row * g0s + h * DH + c * 4) = z;
+        if (kKeySide) *reinterpret_cast<floatx4*>(g1 + row * g1s + h * DH + c * 4) = z;
+      }
+    }
+  }
+  if (r0 >= seg.n) return;
   const int ri = r0 + tid;
   const bool ok = ri < seg.n;
   const long C = (long)H * DH;
   const long grow = seg.row0 + ri;
+  const long trow = ok && at_tokens ? (long)tok.gather_idx[grow] : grow;   // where this row's gradients live
 
   float a[DH], b[DH], acc0[DH], acc1[DH];
 #pragma unroll
@@ -785,7 +800,7 @@ attn_bwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k, co
 #pragma unroll
       for (int d = 0; d < DH; ++d) {
         a[d] = q[grow * qs + h * DH + d];
-        b[d] = dout[grow * C + h * DH + d];
+        b[d] = dout[trow * C + h * DH + d];
         dsum = fmaf(b[d], out[grow * C + h * DH + d], dsum);
       }
       my_D = dsum;
@@ -810,8 +825,10 @@ attn_bwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k, co
       const int r = i / (DH / 4), c = i % (DH / 4);
       floatx4 x = {0.f, 0.f, 0.f, 0.f}, y = x;
       if (t + r < seg.n) {
-        x = *reinterpret_cast<const floatx4*>(sa + (seg.row0 + t + r) * sa_stride + h * DH + c * 4);
-        y = *reinterpret_cast<const floatx4*>(sb + (seg.row0 + t + r) * sb_stride + h * DH + c * 4);
+        const long prow = seg.row0 + t + r;
+        const long brow = kKeySide && at_tokens ? (long)tok.gather_idx[prow] : prow;   // dO rows sit at the tokens
+        x = *reinterpret_cast<const floatx4*>(sa + prow * sa_stride + h * DH + c * 4);
+        y = *reinterpret_cast<const floatx4*>(sb + brow * sb_stride + h * DH + c * 4);
       }
       *reinterpret_cast<floatx4*>(&As[r * DH + c * 4]) = x;
       *reinterpret_cast<floatx4*>(&Bs[r * DH + c * 4]) = y;
@@ -844,8 +861,8 @@ attn_bwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k, co
   if (!ok) return;
 #pragma unroll
   for (int d = 0; d < DH; ++d) {
-    g0[grow * g0s + h * DH + d] = acc0[d];
-    if (kKeySide) g1[grow * g1s + h * DH + d] = acc1[d];
+    g0[trow * g0s + h * DH + d] = acc0[d];
+    if (kKeySide) g1[trow * g1s + h * DH + d] = acc1[d];
   }
 }
 
@@ -884,8 +901,6 @@ static int attention_bwd_common(const char* fn, const void* q, const void* k, co
               SPA_ERR_INVALID_ARG, "%s: tensors not 16-byte aligned", fn);
   SPA_REQUIRE(softmax_scale >= 0.f && std::isfinite(softmax_scale), SPA_ERR_INVALID_ARG,
               "%s: softmax_scale must be finite and >= 0", fn);
-  SPA_REQUIRE(!at_tokens || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED,
-              "%s: bf16 only (fp32: spa_unpack_bwd, spa_packed_attention_bwd, spa_pack_bwd)", fn);
   // short segments: the one-kernel form.  SPA_ATTN_BWD_SHORT = "split" keeps the two one-wave
   // kernels, "tiled" forces the long-segment kernels (tuning aids).
   const char* env = std::getenv("SPA_ATTN_BWD_SHORT");
@@ -904,11 +919,11 @@ static int attention_bwd_common(const char* fn, const void* q, const void* k, co
   hipLaunchKernelGGL((attn_bwd_f32_kernel<D, false>), grid, block, 0, st, (const float*)q, (const float*)k,   \
                      (const float*)v, (long)q_row_stride, (long)k_row_stride, (long)v_row_stride,             \
                      (const float*)out, (const float*)dout, lse, dvec, ls, cu_seqlens, H, scale, (float*)dq,  \
-                     (long)dq_row_stride, (float*)nullptr, 0L);                                               \
+                     (long)dq_row_stride, (float*)nullptr, 0L, tok);                                          \
   hipLaunchKernelGGL((attn_bwd_f32_kernel<D, true>), grid, block, 0, st, (const float*)q, (const float*)k,    \
                      (const float*)v, (long)q_row_stride, (long)k_row_stride, (long)v_row_stride,             \
                      (const float*)out, (const float*)dout, lse, dvec, ls, cu_seqlens, H, scale, (float*)dk,  \
-                     (long)dk_row_stride, (float*)dv, (long)dv_row_stride)
+                     (long)dk_row_stride, (float*)dv, (long)dv_row_stride, tok)
     if (Dh == 32) { SPA_BWD_F32(32); } else { SPA_BWD_F32(64); }
 #undef SPA_BWD_F32
   } else {

@@ -85,14 +85,14 @@ class TrainPass:
     representation r_g = Sigmoid(s) . r, so the gate receives the attention's gradient:
       fwd: gate_select(x) -> pack(qk) -> pack(x, scaled by sigmoid(s)) -> attention + unpack (one launch)
       bwd: unpack_bwd(dy) -> attention_bwd -> pack_bwd(dv) [-> pack_bwd(dq|dk)] -> gate_bwd
-    fused_bwd (default: where the library supports it, bf16): the gather of dy and the scatters
-    of dq, dk, dv run inside the attention backward, 6 calls instead of 9.
+    fused_bwd (default): the gather of dy and the scatters of dq, dk, dv run inside the
+    attention backward, 6 calls instead of 9.
     """
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
                  loss_scale: Optional[float] = None, fused_bwd: Optional[bool] = None):
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
-        self.fused_bwd = (dtype == "bf16") if fused_bwd is None else fused_bwd
+        self.fused_bwd = True if fused_bwd is None else fused_bwd
         self.tau, self.bias = tau, bias
         self.loss_scale = 0.01 / (B * N) if loss_scale is None else loss_scale
         td, cap = _td(dtype), B * N

@@ -119,8 +119,7 @@ def test_validation_of_the_wider_entry_points_without_gpu(lib):
     tok_args = lambda dtype, n_max, gidx: (fake, fake, fake, 64, 64, 64, fake, fake, fake, fake, 2, n_max, 1, 64, dtype,
                                            0.0, gidx, fake, 2 * n_max, fake, fake, fake, 64, 64, 64, None, 0, None)
     assert lib.spa_packed_attention_bwd_tokens(*tok_args(1, 64, None)) == -1
-    assert lib.spa_packed_attention_bwd_tokens(*tok_args(0, 64, fake)) == -2          # fp32: separate calls
-    assert b"bf16 only" in lib.spa_last_error()
+    assert lib.spa_packed_attention_bwd_tokens(*tok_args(0, 64, fake)) == -3          # fp32 needs the workspace
     assert lib.spa_packed_attention_bwd_tokens(*tok_args(1, 257, fake)) == -3         # long segments need the workspace
     assert b"workspace" in lib.spa_last_error()
 

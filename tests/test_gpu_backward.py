@@ -73,8 +73,9 @@ def test_attention_backward_matches_oracle(spa, dtype, Dh, N):
         assert _rel(got[:T], ref) <= tol, (name, _rel(got[:T], ref))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("Dh,H,N", [(64, 2, 256), (64, 3, 196), (32, 4, 100), (32, 2, 40), (32, 3, 700), (64, 2, 300)])
-def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N):
+def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N, dtype):
     """spa_packed_attention_bwd_tokens = unpack_bwd + attention backward + pack_bwd (x3): same bits at the
     selected tokens, zeros elsewhere, nothing else written."""
     C = H * Dh
@@ -85,14 +86,14 @@ def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N)
     mask = np.zeros((B, N), np.uint8)
     for b, n in enumerate(lens):
         mask[b, rng.permutation(N)[:n]] = 1
-    dy = dev(wlmod.round_bf16(rng.standard_normal((B, N, C)).astype(np.float32)), "bf16")
-    td = torch.bfloat16
+    dy = dev(wlmod.round_bf16(rng.standard_normal((B, N, C)).astype(np.float32)), dtype)
+    td = tdtype(dtype)
     packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
     cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
     gidx = torch.empty(cap, dtype=torch.int32, device="cuda")
     inv = torch.empty(cap, dtype=torch.int32, device="cuda")
     tot = torch.empty(1, dtype=torch.int32, device="cuda")
-    spa.spa_pack(dev(qkv, "bf16"), dev(mask), None, None, 0, packed, cu, gidx, inv, tot)
+    spa.spa_pack(dev(qkv, dtype), dev(mask), None, None, 0, packed, cu, gidx, inv, tot)
     pq, pk, pv = packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:]
     out = torch.zeros(cap, C, dtype=td, device="cuda")
     lse = torch.zeros(H, cap, dtype=torch.float32, device="cuda")
@@ -100,7 +101,8 @@ def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N)
     # three calls
     dout = torch.zeros(cap, C, dtype=td, device="cuda")
     gp = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
-    ws = torch.empty(spa.spa_attention_bwd_workspace_bytes(B, N, H, Dh, spa.SPA_BF16), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(spa.spa_attention_bwd_workspace_bytes(B, N, H, Dh, spa.dtype_code(out)), dtype=torch.uint8,
+                     device="cuda")
     ref = torch.full((B, N, 3 * C), float("nan"), dtype=td, device="cuda")
     spa.spa_unpack_bwd(dy, gidx, tot, dout)
     spa.spa_packed_attention_bwd(pq, pk, pv, out, dout, lse, cu, B, N, H, Dh, gp[:, :C], gp[:, C:2 * C], gp[:, 2 * C:], ws)
@@ -108,7 +110,8 @@ def test_attention_backward_at_token_positions_equals_three_calls(spa, Dh, H, N)
     # one call, into a wider buffer whose extra columns must stay untouched
     got = torch.full((cap, 3 * C + 8), float("nan"), dtype=td, device="cuda")
     spa.spa_packed_attention_bwd_tokens(pq, pk, pv, out, dy, lse, cu, B, N, H, Dh, gidx, inv,
-                                        got[:, :C], got[:, C:2 * C], got[:, 2 * C:3 * C], ws if N > 256 else None)
+                                        got[:, :C], got[:, C:2 * C], got[:, 2 * C:3 * C],
+                                        ws if N > 256 or dtype == "f32" else None)
     torch.cuda.synchronize()
     assert torch.equal(got[:, :3 * C], ref.view(cap, 3 * C))
     assert bool(torch.isnan(got[:, 3 * C:]).all())
