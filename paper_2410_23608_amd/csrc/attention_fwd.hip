@@ -303,34 +303,25 @@ __device__ __forceinline__ void load_q_frags(const __bf16* qrow, bool q_ok, int 
 // before the single barrier that ends the iteration.
 // Head dim 32 is compiled for three waves per SIMD (168 registers, no spills): with several
 // batches in flight the third wave fills the softmax stalls of the other two.
-template <int DH, int NW, int BN>
-__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(DH == 32 ? 3 : 2)))
-attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                           const __bf16* __restrict__ v, long qs, long ks, long vs,
-                           const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
-                           int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
-                           long lse_stride, Scatter sc, int B, int nqb) {
-  constexpr int RS = DH + 8, TS = transposed_stride(BN), NSB = BN / 32;
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][BN * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vt[2][DH * TS];
-  __shared__ int s_cu[2 * kLptMaxB + 1];
-  __shared__ int s_pick;
-  static_assert(2 * BN >= 32 * NW, "the K buffers double as the output staging tile");
+template <int DH, int BN>
+struct TiledLds {
+  static constexpr int RS = DH + 8, TS = transposed_stride(BN);
+  __attribute__((aligned(16))) __bf16 Ks[2][BN * RS];
+  __attribute__((aligned(16))) __bf16 Vt[2][DH * TS];
+};
 
-  const TileId tile_id = xcd_tile(nqb, H, B);
-  if (!tile_id.valid) return;
-  const int h = tile_id.h;
-  const Segment seg = lpt_segment<64 * NW>(tile_id.rank, B, cu, key_lens, n_pad, s_cu, &s_pick);
+// The workgroup's work on queries [q0, q0 + 32 NW) of head h of segment seg (q0 < seg.nq).
+template <int DH, int NW, int BN>
+__device__ __forceinline__ void
+tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const __bf16* __restrict__ q,
+                const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs, int H,
+                float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse, long lse_stride,
+                const Scatter& sc) {
+  constexpr int RS = DH + 8, TS = transposed_stride(BN), NSB = BN / 32;
+  auto& Ks = lds.Ks;
+  auto& Vt = lds.Vt;
+  static_assert(2 * BN >= 32 * NW, "the K buffers double as the output staging tile");
   const long C = (long)H * DH;
-  // this workgroup's share of the image's bypassing tokens: filled right away by a
-  // workgroup that has no queries, after the main loop by one that has
-  const int fill_img = key_lens == nullptr && B > 1 && B <= kLptMaxB ? s_pick : tile_id.rank;
-  const FillRange fr = fill_range(sc, fill_img, B, tile_id.qb, nqb);
-  const int q0 = tile_id.qb * (32 * NW);
-  if (q0 >= seg.nq) {
-    if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64 * NW);
-    return;
-  }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
   const int qi = q0 + wv * 32 + l32;
   const bool wave_live = q0 + wv * 32 < seg.nq;
@@ -367,6 +358,31 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   __syncthreads();
   if (wave_live)
     fwd_flush<DH, RS>(tile, out, sc, seg.row0 + q0 + wv * 32, h, C, min(32, seg.nq - q0 - wv * 32), lane);
+}
+
+template <int DH, int NW, int BN>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(DH == 32 ? 3 : 2)))
+attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                           const __bf16* __restrict__ v, long qs, long ks, long vs,
+                           const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
+                           int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
+                           long lse_stride, Scatter sc, int B, int nqb) {
+  __shared__ TiledLds<DH, BN> lds;
+  __shared__ int s_cu[2 * kLptMaxB + 1];
+  __shared__ int s_pick;
+
+  const TileId tile_id = xcd_tile(nqb, H, B);
+  if (!tile_id.valid) return;
+  const int h = tile_id.h;
+  const Segment seg = lpt_segment<64 * NW>(tile_id.rank, B, cu, key_lens, n_pad, s_cu, &s_pick);
+  const long C = (long)H * DH;
+  // this workgroup's share of the image's bypassing tokens: filled right away by a
+  // workgroup that has no queries, after the main loop by one that has
+  const int fill_img = key_lens == nullptr && B > 1 && B <= kLptMaxB ? s_pick : tile_id.rank;
+  const FillRange fr = fill_range(sc, fill_img, B, tile_id.qb, nqb);
+  const int q0 = tile_id.qb * (32 * NW);
+  if (q0 < seg.nq)
+    tiled_attention<DH, NW, BN>(lds, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
   if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64 * NW);
 }
 
@@ -558,18 +574,18 @@ __device__ __forceinline__ int kth_set_bit(uint64_t mask, int kth) {   // kth < 
   return pos;
 }
 
-template <int DH, int STEP>
-__global__ void __launch_bounds__(64)
-attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                                const __bf16* __restrict__ v, long qs, long ks, long vs,
-                                const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
-                                int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
-                                long lse_stride, Scatter sc, int B, int nqb) {
-  constexpr int RS = DH + 8;
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[STEP * RS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[STEP * RS];
-  const int lane = threadIdx.x;
-  const int x = blockIdx.x & 7, j = blockIdx.x >> 3, unit = j & 31, m = j >> 5;
+// Block number r of XCD x -> its segment, head and first query (live = false: past the live
+// blocks).  QB = queries per block; a segment's class is its number of blocks.  Every wave of
+// the workgroup computes the same answer from its own ballots.
+struct LptBlock {
+  Segment seg;
+  int h, q0;
+  bool live;
+};
+template <int QB>
+__device__ __forceinline__ LptBlock lpt64_block(const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens,
+                                                int n_pad, int B, int H, int nqb, int x, int r) {
+  const int lane = threadIdx.x & 63;
   const bool padded = key_lens != nullptr;
   int start = 0, len = 0, cls = -1;
   if (lane < B) {
@@ -580,39 +596,59 @@ attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __re
       start = cu[lane];
       len = cu[lane + 1] - start;
     }
-    cls = min((max(len, 0) + 31) >> 5, 8);
+    cls = min((max(len, 0) + QB - 1) / QB, nqb);
   }
-  const int r = m * 32 + ((m & 1) ? 31 - unit : unit);
-  Segment seg = {0, 0, 0};
-  int h = 0, q0 = 0;
+  LptBlock blk = {{0, 0, 0}, 0, 0, false};
   int ranked = 0, tiles = 0, g0 = 0;             // images, live blocks, this XCD's pairs of the heavier classes
-  for (int c = 8; c >= 0; --c) {
+  for (int c = nqb; c >= 0; --c) {
     const uint64_t bal = __ballot(cls == c);
     const int n_c = __popcll(bal);
-    const int per_pair = padded ? nqb : min(c, nqb);
+    const int per_pair = padded ? nqb : c;
     const int pairs_c = pairs_below((ranked + n_c) * H, x) - pairs_below(ranked * H, x);
     const int tiles_c = pairs_c * per_pair;
     if (r < tiles + tiles_c) {
       const int idx = r - tiles, g = g0 + idx / per_pair;
       const int p = 8 * g + ((g & 1) ? 7 - x : x);
       const int img = kth_set_bit(bal, p / H - ranked);
-      h = p % H;
-      q0 = (idx % per_pair) * 32;
-      seg.row0 = __builtin_amdgcn_readlane(start, img);
-      seg.nk = __builtin_amdgcn_readlane(len, img);
-      seg.nq = padded ? n_pad : seg.nk;
+      blk.h = p % H;
+      blk.q0 = (idx % per_pair) * QB;
+      blk.seg.row0 = __builtin_amdgcn_readlane(start, img);
+      blk.seg.nk = __builtin_amdgcn_readlane(len, img);
+      blk.seg.nq = padded ? n_pad : blk.seg.nk;
+      blk.live = blk.q0 < blk.seg.nq;
       break;
     }
     tiles += tiles_c;
     g0 += pairs_c;
     ranked += n_c;
   }
-  if (q0 < seg.nq)
-    wave_attention<DH, STEP>(Ks, Vs, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
+  return blk;
+}
+// the grid of such a launch: 8 XCDs x 32 units x enough rounds for all blocks of the XCD with most pairs
+static unsigned lpt64_grid(int B, int H, int nqb) {
+  const long g8 = ((long)B * H + 7) / 8;
+  return (unsigned)(8 * 32 * ((g8 * nqb + 31) / 32));
+}
+
+template <int DH, int STEP>
+__global__ void __launch_bounds__(64)
+attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                                const __bf16* __restrict__ v, long qs, long ks, long vs,
+                                const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
+                                int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
+                                long lse_stride, Scatter sc, int B, int nqb) {
+  constexpr int RS = DH + 8;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[STEP * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[STEP * RS];
+  const int x = blockIdx.x & 7, j = blockIdx.x >> 3, unit = j & 31, m = j >> 5;
+  const LptBlock blk = lpt64_block<32>(cu, key_lens, n_pad, B, H, nqb, x, m * 32 + ((m & 1) ? 31 - unit : unit));
+  if (blk.live)
+    wave_attention<DH, STEP>(Ks, Vs, blk.seg, blk.h, blk.q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride,
+                             sc);
   if (sc.y != nullptr) {
     const long rows = sc.flat ? (long)sc.N : (long)B * sc.N, per = (rows + gridDim.x - 1) / gridDim.x;
     const long r0 = min(rows, blockIdx.x * per), r1 = min(rows, r0 + per);
-    scatter_fill_rows<__bf16>(sc, r0, r1, (long)H * DH, lane);
+    scatter_fill_rows<__bf16>(sc, r0, r1, (long)H * DH, threadIdx.x);
   }
 }
 
@@ -859,8 +895,7 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
       // default: blocks dealt to the compute units by weight ("plain" in SPA_ATTN_FWD_SHORT: numbered blindly)
       const bool plain = short_env != nullptr && std::strstr(short_env, "plain") != nullptr;
       if (!step64 && !plain && B <= kWave) {
-        const long g8 = ((long)B * H + 7) / 8;
-        const dim3 lgrid((unsigned)(8 * 32 * ((g8 * nqb + 31) / 32)));
+        const dim3 lgrid(lpt64_grid(B, H, nqb));
         if (Dh == 32) hipLaunchKernelGGL((attn_fwd_bf16_wave_lpt64_kernel<32, 32>), lgrid, dim3(64), 0, st, SPA_ARGS, B, nqb);
         else hipLaunchKernelGGL((attn_fwd_bf16_wave_lpt64_kernel<64, 32>), lgrid, dim3(64), 0, st, SPA_ARGS, B, nqb);
       } else if (Dh == 32) {
