@@ -351,6 +351,34 @@ def main():
     }
 
     if not args.no_extras:
+        # the hot path as its four calls (gate_select, pack, packed_attention, unpack), the last two NOT
+        # fused: warm back-to-back launch times and the roofline fraction of each kernel on its own
+        fp4 = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, fused_unpack=False)
+        st4 = fp4.stages(x, w, qkv)
+
+        def step4():
+            for _, fn in st4:
+                fn()
+
+        for _ in range(5):
+            step4()
+        torch.cuda.synchronize()
+        dt4 = timed(step4, args.steps, torch)
+        us4 = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in st4}
+        all_work = {"gate_select": (0.0, B * N * (C * e + 5)),
+                    "pack": (0.0, 2 * T * 3 * C * e + 4 * T + 5 * B * N + 4 * (B + 1)),
+                    "packed_attention": (attn_flops, T * 3 * C * e + T * C * e + 4 * H * T + 4 * (B + 1)),
+                    "unpack": (0.0, T * C * e + 4 * B * N + B * N * C * e)}
+        four = {}
+        for nme, us_ in us4.items():
+            fl, by = all_work[nme]
+            four[nme] = {"us": round(us_, 2), "GB/s": round(by / us_ / 1e3, 1), "hbm_frac": round(by / us_ / 1e3 / HBM_PEAK_GBS, 4)}
+            if fl > 0:
+                four[nme].update({"tflops": round(fl / us_ / 1e6, 2), "mfma_frac": round(fl / us_ / 1e6 / mfma_peak, 4)})
+        result["four_call_form"] = {"ms_per_step": 1e3 * dt4 / args.steps, "value": T * args.steps / dt4,
+                                    "cache": "warm (one copy of the batch, one stream)",
+                                    "y_equals_fused_form": bool(torch.equal(fp4.y, fp.y)), "kernels": four}
+
         # the same step replayed as a hipGraph
         try:
             def make_step():
