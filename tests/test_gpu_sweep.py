@@ -79,3 +79,88 @@ def test_seeded_shape_sweep(spa, seed):
             for i, r in enumerate(refs):
                 err = np.max(np.abs(g[:, i * C:(i + 1) * C] - r)) / max(1.0, np.max(np.abs(r)))
                 assert err <= (2e-2 if dtype == "bf16" else 2e-5), (what, i, err)
+
+
+def _ints(n):
+    return torch.zeros(n, dtype=torch.int32, device="cuda")
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_seeded_sweep_of_the_bandwidth_bound_calls(spa, seed):
+    """gate_select (with / without up-scale scores, counts), pack (shift, containers, gate scale,
+    counts), unpack with a residual, gate backward: random grids, channel counts and thresholds."""
+    rng = np.random.default_rng(2000 + seed)
+    for case in range(12):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        ve = 8 if dtype == "bf16" else 4
+        C = max(int(rng.choice([8, 16, 64, 96, 200, 384, 768, 1040])) // ve * ve, ve)
+        gh, gw = int(rng.integers(1, 15)), int(rng.integers(1, 15))
+        N, B = gh * gw, int(rng.choice([1, 2, 3, 7, 40]))
+        tau = float(rng.choice([0.5, 0.3, 0.01, 0.9]))
+        mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+        x = mk(rng.standard_normal((B, N, C)).astype(np.float32))
+        w = mk((rng.standard_normal(C) / np.sqrt(C)).astype(np.float32))
+        bias = float(rng.normal())
+        s_up = (rng.standard_normal((B, N)) * 1.5).astype(np.float32) if rng.random() < 0.4 else None
+        what = f"seed {seed} case {case}: {dtype} B={B} grid={gh}x{gw} C={C} tau={tau} s_up={s_up is not None}"
+        td, cap = tdtype(dtype), B * N
+        xd, wd = dev(x, dtype), dev(w, dtype)
+        scores = torch.empty(B, N, dtype=torch.float32, device="cuda")
+        mask = torch.empty(B, N, dtype=torch.uint8, device="cuda")
+        counts = _ints(B)
+        spa.spa_gate_select(xd, wd, bias, None if s_up is None else dev(s_up), tau, scores, mask, counts)
+        torch.cuda.synchronize()
+        s_ref = orc.gate_scores(x, w, bias, s_up)
+        assert np.max(np.abs(host(scores) - s_ref) / (1 + np.abs(s_ref))) <= (1e-5 if dtype == "f32" else 1e-3), what
+        m_ref, _ = orc.select(s_ref, tau)
+        m_gpu, theta = host(mask), orc.threshold_logit(tau)
+        off = m_gpu != m_ref                      # random logits may sit on the threshold: only there may the sides differ
+        assert np.all(np.abs(s_ref[off] - theta) < 1e-2 * (1 + abs(theta))), what
+        assert np.array_equal(host(counts), m_gpu.sum(axis=1)), what
+        sh, sw, L = int(rng.integers(0, gh)), int(rng.integers(0, gw)), int(rng.choice([0, 0, 4, 9, 49]))
+        scale, use_counts = rng.random() < 0.5, rng.random() < 0.5
+        packed = torch.full((cap + max(L - 1, 0), C), float("nan"), dtype=td, device="cuda")
+        cu, gidx, inv, tot = _ints(B + 1), _ints(cap), _ints(cap), _ints(1)
+        spa.spa_pack_shifted(xd, mask, counts if use_counts else None, scores if scale else None, gh, gw, sh, sw, L,
+                             packed, cu, gidx, inv, tot)
+        torch.cuda.synchronize()
+        cu_r, g_r, inv_r, T = orc.pack_indices(m_gpu, orc.shift_order(gh, gw, sh, sw))
+        assert np.array_equal(host(cu), cu_r) and np.array_equal(host(gidx)[:T], g_r), what
+        assert np.array_equal(host(inv), inv_r) and int(tot.item()) == T, what
+        pk = host(packed)
+        if not scale:
+            assert np.array_equal(pk[:T], x.reshape(cap, C)[g_r]), what
+        elif T:
+            ref = orc.sigmoid(host(scores).astype(np.float64)).reshape(cap, 1)[g_r] * x.reshape(cap, C)[g_r]
+            assert np.max(np.abs(pk[:T] - ref)) <= (1e-5 if dtype == "f32" else 2e-2) * max(1, np.max(np.abs(ref))), what
+        if L:
+            t_pad = orc.packed_rows(T, L)
+            assert np.all(pk[T:t_pad] == 0) and np.all(np.isnan(pk[t_pad:])), what
+        base = mk(rng.standard_normal((B, N, C)).astype(np.float32))
+        y = torch.empty(B, N, C, dtype=td, device="cuda")
+        spa.spa_unpack(packed, inv, dev(base, dtype), y)
+        torch.cuda.synchronize()
+        y_ref = orc.unpack(pk[:T].astype(np.float64), inv_r, B, N, base)
+        assert np.max(np.abs(host(y) - y_ref)) <= (1e-5 if dtype == "f32" else 4e-2) * max(1, np.max(np.abs(y_ref))), what
+        if s_up is not None and np.min(np.abs(orc.gate_only(x, w, bias) - s_up)) <= 1e-3:
+            continue                              # which side won the max must be unambiguous for the backward
+        labels = (rng.uniform(size=(B, N)) < 0.4).astype(np.uint8)
+        d_rg = mk((rng.standard_normal((B, N, C)) * (rng.uniform(size=(B, N, 1)) < 0.5)).astype(np.float32))
+        lam = 0.01 / (B * N)
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        dx = torch.empty(B, N, C, dtype=td, device="cuda")
+        dw = torch.empty(C, dtype=torch.float32, device="cuda")
+        db = torch.empty(1, dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(spa.spa_gate_bwd_workspace_bytes(B, N, C, spa.dtype_code(xd)), 256), dtype=torch.uint8,
+                         device="cuda")
+        spa.spa_gate_bwd(xd, wd, bias, scores, None if s_up is None else dev(s_up), dev(labels), dev(d_rg, dtype), True,
+                         lam, loss, dx, dw, db, ws)
+        torch.cuda.synchronize()
+        g = orc.gate_backward(x, w, bias, s_up, labels, d_rg, True, lam)
+
+        def rel(a, b):
+            return float(np.max(np.abs(a - b)) / max(1.0, np.max(np.abs(b))))
+
+        t = 2e-2 if dtype == "bf16" else 2e-5
+        assert rel(host(dx), g["dx"]) <= t and rel(host(dw), g["dw"]) <= max(t, 1e-3), what
+        assert abs(float(host(loss)[0]) - g["loss"]) <= 1e-3 * abs(g["loss"]) + 1e-7, what
