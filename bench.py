@@ -615,7 +615,7 @@ def main():
             hres["graph_replay_ms_per_chain"] = 1e3 * ghdt / args.steps
         except Exception as ex:
             hres["graph_replay_error"] = str(ex)[:200]
-        # the same hierarchy forward + backward (36 launches)
+        # the same hierarchy forward + backward (24 calls)
         from paper_2410_23608_amd.pipeline import HierarchyTrainPass
         htp = HierarchyTrainPass(hcfg)
         hqk = [up(b_["qkv"][:, :, :2 * b_["workload"].C]) for b_ in hb]
