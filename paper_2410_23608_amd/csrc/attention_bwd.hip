@@ -1,15 +1,20 @@
 // Backward of the packed, per-image attention: for every (image, head) segment
 //   P = exp(S - lse), dV = P^T dO, dP = dO V^T, D_i = sum_d dO_id O_id,
 //   dS = P * (dP - D), dQ = dS K * scale, dK = dS^T Q * scale.
-// Two kernels, no atomics, run-to-run bit-stable:
-//   dq kernel   : a wave owns 32 queries and walks the segment's keys.  Like the forward it
-//                 works on transposed tiles (S^T = K Q^T, dP^T = V dO^T) so lse_i and D_i are
-//                 one scalar per lane and dS^T is already the B operand of
-//                 dQ^T += K^T dS^T.  It also writes D_i for the second kernel.
-//   dkdv kernel : a wave owns 32 keys and walks the segment's queries with S = Q K^T and
-//                 dP = dO V^T un-transposed (lane = key), so P and dS are the B operands of
-//                 dV^T += dO^T P and dK^T += Q^T dS.
-// S and dP are recomputed in both (7 GEMM shapes instead of 5) in exchange for determinism.
+// No atomics anywhere; results are run-to-run bit-stable.
+// Segments of up to 256 tokens (bf16): ONE kernel, a workgroup per (image, head), S and dP
+// computed once (5 GEMM shapes); see attn_bwd_fused_bf16_kernel.
+// Longer segments (bf16): two roles in one launch, after a small kernel that writes D_i:
+//   dq role   : a wave owns 32 queries and walks the segment's keys.  Like the forward it
+//               works on transposed tiles (S^T = K Q^T, dP^T = V dO^T) so lse_i and D_i are
+//               one scalar per lane and dS^T is already the B operand of dQ^T += K^T dS^T.
+//   dkdv role : a wave owns 32 keys and walks the segment's queries with S = Q K^T and
+//               dP = dO V^T un-transposed (lane = key), so P and dS are the B operands of
+//               dV^T += dO^T P and dK^T += Q^T dS.
+//   S and dP are recomputed in both roles (7 GEMM shapes instead of 5) in exchange for
+//   determinism.
+// fp32: a thread per row (query side, then key side), the other side streaming through LDS.
+// Every form can read the upstream gradient and write dq, dk, dv at token positions (TokenIO).
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
