@@ -630,8 +630,10 @@ static unsigned lpt64_grid(int B, int H, int nqb) {
   return (unsigned)(8 * 32 * ((g8 * nqb + 31) / 32));
 }
 
+// Compiled for three waves per SIMD (168 registers at head dim 64, no spills): a ViT-B-shaped
+// batch has ~2800 live waves for 1024 SIMDs and then runs in one round instead of two.
 template <int DH, int STEP>
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(3)))
 attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                                 const __bf16* __restrict__ v, long qs, long ks, long vs,
                                 const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
