@@ -497,7 +497,7 @@ wave_attention(__bf16* Ks, __bf16* Vs, const Segment seg, int h, int q0, const _
 }
 
 template <int DH, int STEP>
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(STEP == 32 ? 3 : 1)))
 attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                           const __bf16* __restrict__ v, long qs, long ks, long vs,
                           const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
