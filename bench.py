@@ -41,8 +41,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="vit_s", choices=["tiny", "vit_s", "vit_b_train", "det"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--streams", type=int, default=3,
