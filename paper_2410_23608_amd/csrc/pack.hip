@@ -143,9 +143,10 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
     }
   }
 
-  // 4. copy the survivors' rows: consecutive threads take consecutive 16-byte chunks, four
-  //    independent loads in flight per thread before the first store
-  constexpr int U = 8;
+  // 4. copy the survivors' rows: consecutive threads take consecutive 16-byte chunks, up to
+  //    twelve independent loads in flight per thread before the first store (a 16-token tile of
+  //    q|k|v rows of a 384-wide model is nine per thread: one pass, one memory latency)
+  constexpr int U = 12;
   const unsigned work = packed != nullptr ? (unsigned)nsel * (unsigned)chunks : 0u;   // indices only: no rows
   const T* xt = x + img0 * (long)C;
   T* pt = packed + (long)base * C;
