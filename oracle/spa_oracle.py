@@ -446,6 +446,26 @@ def linear_packed(x, gather_idx, W, bias=None, scores=None, dtype: Optional[str]
     return y
 
 
+def linear_packed_backward(dout, x, gather_idx, W, scores=None, dout_idx=None, dtype: Optional[str] = None):
+    """Gradients of the projection out_j = r_j W^T + bias, with r_j = x[gather_idx[j]]
+    (times sigmoid(score) of that token when scores are given: the gated row of Eq.
+    r_g = Sigmoid(s) . r), for an upstream gradient whose row j is dout[dout_idx[j]]
+    (dout[j] without dout_idx).  The chain rule of a linear map, written out:
+      d_rows[j,:] = dout_j W           gradient with respect to the row r_j that was multiplied
+      dW          = sum_j dout_j^T r_j
+      dbias       = sum_j dout_j
+    When scores are given r_j is the gated row, so d_rows is the gradient of r_g (what the
+    gate backward takes), not of x.  dtype: the gated rows are rounded to it first, as in
+    linear_packed.  x [..., K], W [N_out, K], dout [*, N_out]."""
+    gather_idx = np.asarray(gather_idx)
+    rows = pack_rows(np.asarray(x, dtype=F64).reshape(-1, np.shape(x)[-1])[None], gather_idx,
+                     None if scores is None else np.asarray(scores, dtype=F64).reshape(1, -1), 0,
+                     dtype if scores is not None else None)
+    g = np.asarray(dout, dtype=F64).reshape(-1, np.shape(dout)[-1])
+    g = g[np.asarray(dout_idx)] if dout_idx is not None else g[:len(gather_idx)]
+    return {"d_rows": g @ np.asarray(W, dtype=F64), "dW": g.T @ rows, "dbias": g.sum(axis=0)}
+
+
 # ------------------------------------------------------------------------ whole path
 def spa_forward(x, w, bias, qkv, H: int, tau: float, dtype: str,
                 s_up: Optional[np.ndarray] = None, container_len: int = 0,

@@ -432,6 +432,64 @@ def test_linear_packed_matches_library_and_bruteforce():
     np.testing.assert_array_equal(orc.linear_packed(x, gidx, np.eye(K)), x.reshape(-1, K)[gidx])
 
 
+def test_linear_packed_backward_matches_finite_differences_and_bruteforce():
+    """The projection is linear in W, bias and the rows, so central differences of the scalar
+    L = sum_j <g_j, out_j> through linear_packed (the forward oracle) are exact up to rounding;
+    with scores, the chain through r_g = Sigmoid(s) . r fixes what d_rows is the gradient of."""
+    B, N, K, No = 2, 6, 5, 3
+    r = rng(60)
+    x = r.standard_normal((B, N, K))
+    W = r.standard_normal((No, K))
+    bias = r.standard_normal(No)
+    s = r.standard_normal((B, N))
+    mask = _random_mask(61, B, N, 0.6)
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    assert 2 <= T < B * N
+    dy = r.standard_normal((B * N, No))           # upstream gradient at token positions
+    didx = gidx[::-1].copy()                      # row j of the gradient is dy[didx[j]] (any index map)
+    g = dy[didx]
+    eps = 1e-6
+
+    def L(x_=x, W_=W, b_=bias, s_=None):
+        return float((g * orc.linear_packed(x_, gidx, W_, b_, s_)).sum())
+
+    for scores in (None, s):
+        bw = orc.linear_packed_backward(dy, x, gidx, W, scores, didx)
+        for n in range(No):
+            e = np.zeros(No); e[n] = eps
+            assert abs((L(b_=bias + e, s_=scores) - L(b_=bias - e, s_=scores)) / (2 * eps) - bw["dbias"][n]) < 1e-8
+            for c in range(K):
+                E = np.zeros((No, K)); E[n, c] = eps
+                fd = (L(W_=W + E, s_=scores) - L(W_=W - E, s_=scores)) / (2 * eps)
+                assert abs(fd - bw["dW"][n, c]) < 1e-8
+        p = scipy.special.expit(s).reshape(-1)
+        for j in range(T):
+            tok = gidx[j]
+            scale = 1.0 if scores is None else p[tok]
+            for c in range(K):
+                E = np.zeros((B * N, K)); E[tok, c] = eps
+                fd = (L(x_=(x.reshape(-1, K) + E).reshape(B, N, K), s_=scores) -
+                      L(x_=(x.reshape(-1, K) - E).reshape(B, N, K), s_=scores)) / (2 * eps)
+                assert abs(fd - scale * bw["d_rows"][j, c]) < 1e-8           # dL/dx = Sigmoid(s) dL/dr_g
+            if scores is not None:
+                E = np.zeros(B * N); E[tok] = eps
+                fd = (L(s_=(s.reshape(-1) + E).reshape(B, N)) - L(s_=(s.reshape(-1) - E).reshape(B, N))) / (2 * eps)
+                assert abs(fd - p[tok] * (1 - p[tok]) * float(bw["d_rows"][j] @ x.reshape(-1, K)[tok])) < 1e-8
+    # brute force with explicit loops, no scores, rows of dout taken in order
+    bw = orc.linear_packed_backward(dy, x, gidx, W)
+    xf = x.reshape(-1, K)
+    for n in range(No):
+        assert abs(bw["dbias"][n] - sum(dy[j, n] for j in range(T))) < 1e-13
+        for c in range(K):
+            assert abs(bw["dW"][n, c] - sum(dy[j, n] * xf[gidx[j], c] for j in range(T))) < 1e-12
+    for j in range(T):
+        for c in range(K):
+            assert abs(bw["d_rows"][j, c] - sum(dy[j, n] * W[n, c] for n in range(No))) < 1e-12
+    # identity weights hand the gradient through unchanged
+    dyk = r.standard_normal((B * N, K))
+    np.testing.assert_array_equal(orc.linear_packed_backward(dyk, x, gidx, np.eye(K))["d_rows"], dyk[:T])
+
+
 # ------------------------------------------------ cyclic shift and container-local attention
 def test_shift_order_is_a_roll_of_the_index_grid():
     """The shifted map's raster order equals numpy's roll of the position grid by (-sh, -sw)
