@@ -275,6 +275,48 @@ int spa_linear_packed_scatter(const void* x, const int32_t* total, const void* W
 /* ----------------------------------------------------------------- training ---- */
 
 /*
+ * Backward of the projections with respect to the rows that were multiplied (the 3 L C^2 /
+ * N C^2 terms of Section 3.2; chain rule of out_j = r_j W^T + bias):
+ *   g_j             = dout[dout_idx[j], :]  (dout[j, :] when dout_idx is NULL)
+ *   dx[o(j), :]     = g_j W                 for j < min(*total, M_cap), o(j) = dx_idx[j] or j
+ * For spa_linear_packed with gate_scores, r_j is the gated row Sigmoid(s) . r, so the result is
+ * the gradient of r_g (the d_rg of spa_gate_bwd, which applies the sigmoid factor), written at
+ * the token positions when dx_idx = gather_idx.  For spa_linear_packed_scatter, dout is the
+ * gradient at token positions and dout_idx = scatter_idx gathers it.
+ * in:  dout [*, N_out] dtype, row stride dout_row_stride; dout_idx [>= rows used] int32 or NULL;
+ *      total [1] int32 (device) or NULL (= M_cap rows); W [N_out, K] dtype; dx_idx int32
+ *      (distinct rows) or NULL; inv_pos [rows] int32 or NULL: when given (needs dx_idx), every
+ *      row i < rows of dx with inv_pos[i] < 0 is set to zero (the rows of unselected tokens).
+ *      bf16: K, N_out and both row strides multiples of 8.
+ * out: dx[o(j)*dx_row_stride + k] dtype; other rows untouched unless inv_pos is given.
+ */
+int spa_linear_packed_bwd_input(const void* dout, const int32_t* dout_idx, int64_t dout_row_stride,
+                                const int32_t* total, const void* W, int M_cap, int K, int N_out,
+                                int dtype, const int32_t* dx_idx, const int32_t* inv_pos, int64_t rows,
+                                void* dx, int64_t dx_row_stride, void* stream);
+
+/* Bytes of workspace spa_linear_packed_bwd_weight needs (0 for fp32). Host. */
+size_t spa_linear_bwd_weight_workspace_bytes(int M_cap, int K, int N_out, int dtype);
+
+/*
+ * Backward of the projections with respect to the weights and the bias (same chain rule):
+ *   r_j   = s_j x[x_idx[j], :]  (x[j, :] when x_idx is NULL), s_j = sigmoid(gate_scores[x_idx[j]])
+ *           when gate_scores is given, else 1 (bf16: r_j is rounded to bf16, as a packed r_g is)
+ *   dW    = sum_j g_j^T r_j,  dbias = sum_j g_j      over j < min(*total, M_cap), g_j as above
+ * in:  dout, dout_idx, dout_row_stride, total as in spa_linear_packed_bwd_input; x [*, K] dtype
+ *      contiguous rows; x_idx int32 or NULL; gate_scores fp32 indexed by token or NULL (needs
+ *      x_idx); workspace (device, 256-byte aligned) of at least
+ *      spa_linear_bwd_weight_workspace_bytes bytes (bf16).
+ * out: dW [N_out, K] fp32; dbias [N_out] fp32 or NULL.  Sums run in a fixed order: run-to-run
+ *      bit-stable.  With no rows (*total = 0) both are zero.
+ */
+int spa_linear_packed_bwd_weight(const void* dout, const int32_t* dout_idx, int64_t dout_row_stride,
+                                 const void* x, const int32_t* x_idx, const float* gate_scores,
+                                 const int32_t* total, int M_cap, int K, int N_out, int dtype,
+                                 float* dW, float* dbias, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
+/*
  * Transpose of spa_unpack: dout[j,:] = dy[gather_idx[j],:] for j < total.
  * in:  dy [B,N,C] dtype; gather_idx [B*N] int32; total [1] int32 (device).
  * out: dout [B*N, C] dtype (rows >= T untouched).

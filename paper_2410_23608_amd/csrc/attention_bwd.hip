@@ -62,22 +62,6 @@ __device__ __forceinline__ void flush_tile_rows(const __bf16* tile, __bf16* dst,
   }
 }
 
-// One wave zeroes columns [0, C) of the unselected rows among rows [r0, r1): the lanes test 64
-// rows at a time, then the wave writes the rows that need it, a lane per 16-byte chunk.
-__device__ __forceinline__ void zero_unselected_rows(__bf16* dst, long row_stride, int C, const int32_t* inv_pos, long r0,
-                                                     long r1, int lane) {
-  const bf16x8 z = zero_bf16x8();
-  for (long rb = r0; rb < r1; rb += kWave) {
-    const long row = rb + lane;
-    uint64_t todo = __ballot(row < r1 && inv_pos[row] < 0);
-    while (todo != 0) {
-      __bf16* p = dst + (rb + __ffsll((unsigned long long)todo) - 1) * row_stride;
-      todo &= todo - 1;
-      for (int c = lane; c < C / 8; c += kWave) *reinterpret_cast<bf16x8*>(p + c * 8) = z;
-    }
-  }
-}
-
 // Both bf16 kernels use the forward's launch scheme: 1-D XCD-aware grid (the blocks that
 // share one (image, head)'s rows sit on one L2), longest image first, 4 waves x 32 rows per
 // workgroup, the other side of the product streaming through double-buffered row-major LDS

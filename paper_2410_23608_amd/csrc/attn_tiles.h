@@ -54,6 +54,22 @@ __device__ __forceinline__ bf16x8 transposed_frag_rowmajor(const __bf16* rows, i
   return __builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// One wave zeroes columns [0, C) of the unselected rows among rows [r0, r1): the lanes test 64
+// rows at a time, then the wave writes the rows that need it, a lane per 16-byte chunk.
+__device__ __forceinline__ void zero_unselected_rows(__bf16* dst, long row_stride, int C, const int32_t* inv_pos, long r0,
+                                                     long r1, int lane) {
+  const bf16x8 z = zero_bf16x8();
+  for (long rb = r0; rb < r1; rb += kWave) {
+    const long row = rb + lane;
+    uint64_t todo = __ballot(row < r1 && inv_pos[row] < 0);
+    while (todo != 0) {
+      __bf16* p = dst + (rb + __ffsll((unsigned long long)todo) - 1) * row_stride;
+      todo &= todo - 1;
+      for (int c = lane; c < C / 8; c += kWave) *reinterpret_cast<bf16x8*>(p + c * 8) = z;
+    }
+  }
+}
+
 // Row of a 32x32 fp32 accumulator tile held in register r of a lane in half hh.
 __device__ __forceinline__ constexpr int acc_row(int r, int hh) { return 8 * (r / 4) + 4 * hh + (r % 4); }
 

@@ -51,6 +51,11 @@ _SIGNATURES = {
     "spa_ceiling_mfma": (c_double, [_P, c_int, c_int, _P]),
     "spa_linear_packed": (c_int, [_P, _P, _P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, c_int64, _P]),
     "spa_linear_packed_scatter": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, _P, _P, c_int64, _P]),
+    "spa_linear_packed_bwd_input": (c_int, [_P, _P, c_int64, _P, _P, c_int, c_int, c_int, c_int, _P, _P, c_int64, _P,
+                                            c_int64, _P]),
+    "spa_linear_bwd_weight_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int]),
+    "spa_linear_packed_bwd_weight": (c_int, [_P, _P, c_int64, _P, _P, _P, _P, c_int, c_int, c_int, c_int, _P, _P, _P,
+                                             c_size_t, _P]),
     "spa_unpack": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_unpack_bwd": (c_int, [_P, _P, _P, c_int, c_int, c_int, c_int, _P, _P]),
     "spa_pack_bwd": (c_int, [_P, _P, c_int, c_int, c_int, c_int, _P, _P]),
@@ -292,6 +297,39 @@ def spa_linear_packed_scatter(x, total, W, bias, scatter_idx, residual, y, prepa
     return _dispatch(lib.spa_linear_packed_scatter,
                      (_ptr(x), _ptr(total), _ptr(W), _ptr(bias), x.shape[0], K, N_out, dtype_code(x), _ptr(scatter_idx),
                       _ptr(residual), _ptr(y), N_out, _stream(),), _keep, prepare)
+
+
+def spa_linear_packed_bwd_input(dout, dout_idx, total, W, M_cap, dx_idx, inv_pos, dx, prepare=False):
+    """dx[dx_idx[j] or j] = dout[dout_idx[j] or j] W for j < min(*total, M_cap).  dout [*, N_out] and dx
+    [*, K] may be column-slice views; W [N_out, K].  inv_pos given: the rows of dx (all of its leading
+    shape) that no packed row maps to are zeroed."""
+    N_out, K = W.shape
+    rows = dx.numel() // dx.shape[-1] if inv_pos is not None else 0
+    _keep = (dout_idx, total, W, dx_idx, inv_pos,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_linear_packed_bwd_input,
+                     (_ptr(dout), _ptr(dout_idx), _row_stride(dout), _ptr(total), _ptr(W), int(M_cap), K, N_out,
+                      dtype_code(W), _ptr(dx_idx), _ptr(inv_pos), rows, _ptr(dx), _row_stride(dx), _stream(),),
+                     _keep + (dout, dx,), prepare)
+
+
+def spa_linear_bwd_weight_workspace_bytes(M_cap, K, N_out, dtype) -> int:
+    return int(lib.spa_linear_bwd_weight_workspace_bytes(int(M_cap), int(K), int(N_out),
+                                                          SPA_F32 if dtype in (torch.float32, "f32") else SPA_BF16))
+
+
+def spa_linear_packed_bwd_weight(dout, dout_idx, x, x_idx, gate_scores, total, M_cap, dW, dbias, workspace=None,
+                                 prepare=False):
+    """dW [N_out, K] f32 = sum_j dout[dout_idx[j] or j]^T (sigmoid(score) x[x_idx[j] or j]), dbias [N_out] f32 =
+    sum_j dout[...] over j < min(*total, M_cap).  dout may be a column-slice view; x [*, K] contiguous."""
+    N_out, K = dW.shape
+    _keep = (dout_idx, x, x_idx, gate_scores, total, dW, dbias, workspace,)
+    _contig(*_keep)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return _dispatch(lib.spa_linear_packed_bwd_weight,
+                     (_ptr(dout), _ptr(dout_idx), _row_stride(dout), _ptr(x), _ptr(x_idx), _ptr(gate_scores), _ptr(total),
+                      int(M_cap), K, N_out, dtype_code(x), _ptr(dW), _ptr(dbias), _ptr(workspace), ws_bytes, _stream(),),
+                     _keep + (dout,), prepare)
 
 
 def spa_ceiling_copy(src, dst, prepare=False):

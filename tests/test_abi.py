@@ -123,6 +123,23 @@ def test_validation_of_the_wider_entry_points_without_gpu(lib):
     assert lib.spa_packed_attention_bwd_tokens(*tok_args(1, 257, fake)) == -3         # long segments need the workspace
     assert b"workspace" in lib.spa_last_error()
 
+    lib.spa_linear_packed_bwd_input.restype = I
+    lib.spa_linear_packed_bwd_input.argtypes = [P, P, L, P, P, I, I, I, I, P, P, L, P, L, P]
+    assert lib.spa_linear_packed_bwd_input(fake, None, 64, None, fake, 8, 64, 64, 1, None, fake, 8, fake, 64, None) == -1
+    assert b"dx_idx" in lib.spa_last_error()
+    assert lib.spa_linear_packed_bwd_input(fake, None, 64, None, fake, 8, 60, 64, 1, None, None, 0, fake, 64, None) == -2
+    lib.spa_linear_bwd_weight_workspace_bytes.restype = ctypes.c_size_t
+    lib.spa_linear_bwd_weight_workspace_bytes.argtypes = [I] * 4
+    need = lib.spa_linear_bwd_weight_workspace_bytes(12544, 384, 1152, 1)
+    assert need >= (384 * 1152 + 1152) * 4 and need % 256 == 0
+    assert lib.spa_linear_bwd_weight_workspace_bytes(12544, 384, 1152, 0) == 0          # fp32 needs none
+    lib.spa_linear_packed_bwd_weight.restype = I
+    lib.spa_linear_packed_bwd_weight.argtypes = [P, P, L, P, P, P, P, I, I, I, I, P, P, P, ctypes.c_size_t, P]
+    assert lib.spa_linear_packed_bwd_weight(fake, None, 64, fake, None, None, None, 8, 64, 64, 1, fake, None, None, 0, None) == -3
+    assert b"workspace" in lib.spa_last_error()
+    assert lib.spa_linear_packed_bwd_weight(fake, None, 64, fake, None, fake, None, 8, 64, 64, 1, fake, None, None, 0, None) == -1
+    assert b"x_idx" in lib.spa_last_error()
+
     lib.spa_ceiling_mfma.restype = ctypes.c_double
     lib.spa_ceiling_mfma.argtypes = [P, I, I, P]
     assert lib.spa_ceiling_mfma(None, 1, 1, None) == -1.0

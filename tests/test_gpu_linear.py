@@ -218,3 +218,140 @@ def test_block_pass_in_place_equals_six_launch_form(spa):
     y5 = BlockPass(B, N, C, H, "bf16", wl.tau, bun["bias"], in_place=True).run(x5, w, Wqkv, bqkv, Wo, bo)
     torch.cuda.synchronize()
     assert y5.data_ptr() == x5.data_ptr() and torch.equal(y5, y6)
+
+
+# ----------------------------------------------------------------------------- backward
+def _bwd_case(dtype, B, N, K, No, mode, seed=43, select=0.55):
+    rng = np.random.default_rng(seed)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    cap = B * N
+    x_tok = mk(rng.standard_normal((B, N, K)).astype(np.float32))
+    W = mk((rng.standard_normal((No, K)) / np.sqrt(K)).astype(np.float32))
+    s = rng.standard_normal((B, N)).astype(np.float32)
+    mask = (rng.uniform(size=(B, N)) < select).astype(np.uint8)
+    cu, gidx, inv, T = orc.pack_indices(mask)
+    g_rows = mk(rng.standard_normal((cap, No)).astype(np.float32))
+    return dict(x_tok=x_tok, W=W, s=s, gidx=gidx, inv=inv, T=T, g_rows=g_rows, cap=cap)
+
+
+@pytest.mark.parametrize("dtype,B,N,K,No", [("bf16", 3, 100, 64, 96), ("bf16", 8, 196, 384, 1152),
+                                            ("bf16", 2, 777, 96, 288), ("bf16", 4, 129, 32, 8), ("bf16", 2, 150, 200, 72),
+                                            ("bf16", 40, 196, 96, 1280), ("bf16", 2, 300, 136, 264),
+                                            ("f32", 2, 60, 64, 192)])
+@pytest.mark.parametrize("mode", ["plain", "qkv", "out_proj"])
+def test_linear_backward_matches_oracle(spa, dtype, B, N, K, No, mode):
+    """plain: rows in order, no index arrays, no row count on the device.
+    qkv: the backward of spa_linear_packed(x, gather_idx, scores): upstream rows packed (a
+    column-slice view), x read at token positions and gate-scaled, d_rg written at token
+    positions with the unselected rows cleared.
+    out_proj: the backward of spa_linear_packed_scatter: upstream gradient gathered from token
+    positions, x and dx packed."""
+    c = _bwd_case(dtype, B, N, K, No, mode)
+    cap, T, gidx, td = c["cap"], c["T"], c["gidx"], tdtype(dtype)
+    gi = np.zeros(cap, np.int32)
+    gi[:T] = gidx
+    gi_d, tot_d, inv_d = dev(gi), dev(np.array([T], np.int32)), dev(c["inv"])
+    x_flat = c["x_tok"].reshape(cap, K)
+    W_d = dev(c["W"], dtype)
+    dW = torch.full((No, K), float("nan"), dtype=torch.float32, device="cuda")
+    db = torch.full((No,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(spa.spa_linear_bwd_weight_workspace_bytes(cap, K, No, dtype), 256), dtype=torch.uint8, device="cuda")
+    if mode == "plain":
+        M = cap
+        ref = orc.linear_packed_backward(c["g_rows"], x_flat, np.arange(cap), c["W"])
+        g_d = dev(c["g_rows"], dtype)
+        dx = torch.full((cap, K), float("nan"), dtype=td, device="cuda")
+        spa.spa_linear_packed_bwd_input(g_d, None, None, W_d, cap, None, None, dx)
+        spa.spa_linear_packed_bwd_weight(g_d, None, dev(x_flat, dtype), None, None, None, cap, dW, db, ws)
+        dx_rows = host(dx)
+    elif mode == "qkv":
+        M = T
+        ref = orc.linear_packed_backward(c["g_rows"], x_flat, gidx, c["W"], c["s"], None, dtype)
+        wide = torch.full((cap, No + 24), float("nan"), dtype=td, device="cuda")
+        wide[:, 8:8 + No] = dev(c["g_rows"], dtype)
+        g_d = wide[:, 8:8 + No]                                   # row stride No + 24, offset 8 columns
+        dx = torch.full((cap, K), float("nan"), dtype=td, device="cuda")
+        spa.spa_linear_packed_bwd_input(g_d, None, tot_d, W_d, cap, gi_d, inv_d, dx)
+        spa.spa_linear_packed_bwd_weight(g_d, None, dev(x_flat, dtype), gi_d, dev(c["s"]), tot_d, cap, dW, db, ws)
+        got = host(dx)
+        assert not np.any(np.isnan(got))                          # every row written: a result or zero
+        assert np.all(got[c["inv"] < 0] == 0)
+        dx_rows = got[gidx]
+    else:
+        M = T
+        packed_x = np.zeros((cap, K), np.float32)
+        packed_x[:T] = x_flat[gidx]                               # any packed rows will do as the forward input
+        ref = orc.linear_packed_backward(c["g_rows"], packed_x, np.arange(T), c["W"], None, gidx)
+        g_d = dev(c["g_rows"], dtype)
+        dx = torch.full((cap, K), float("nan"), dtype=td, device="cuda")
+        spa.spa_linear_packed_bwd_input(g_d, gi_d, tot_d, W_d, cap, None, None, dx)
+        spa.spa_linear_packed_bwd_weight(g_d, gi_d, dev(packed_x, dtype), None, None, tot_d, cap, dW, db, ws)
+        got = host(dx)
+        assert np.all(np.isnan(got[T:]))                          # rows past the total untouched
+        dx_rows = got[:T]
+    torch.cuda.synchronize()
+    tol_x, tol_w = (1e-5, 1e-5) if dtype == "f32" else (1e-2, 2e-3)
+    assert _rel(dx_rows[:M], ref["d_rows"]) <= tol_x
+    assert _rel(host(dW), ref["dW"]) <= tol_w
+    assert _rel(host(db), ref["dbias"]) <= tol_w
+    # the sums run in a fixed order
+    dW2, db2 = torch.empty_like(dW), torch.empty_like(db)
+    if mode == "plain":
+        spa.spa_linear_packed_bwd_weight(g_d, None, dev(x_flat, dtype), None, None, None, cap, dW2, db2, ws)
+    elif mode == "qkv":
+        spa.spa_linear_packed_bwd_weight(g_d, None, dev(x_flat, dtype), gi_d, dev(c["s"]), tot_d, cap, dW2, db2, ws)
+    else:
+        spa.spa_linear_packed_bwd_weight(g_d, gi_d, dev(packed_x, dtype), None, None, tot_d, cap, dW2, db2, ws)
+    assert torch.equal(dW, dW2) and torch.equal(db, db2)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T", [0, 1, 63, 65])
+def test_linear_backward_few_or_no_rows(spa, dtype, T):
+    """No selected token: dW and dbias are zero and d_rg is all zeros; a handful of rows: one
+    ragged contraction step on the weight side, one ragged tile on the input side."""
+    B, N, K, No = 2, 96, 72, 40
+    rng = np.random.default_rng(47)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    cap, td = B * N, tdtype(dtype)
+    x = mk(rng.standard_normal((cap, K)).astype(np.float32))
+    W = mk((rng.standard_normal((No, K)) / np.sqrt(K)).astype(np.float32))
+    g = mk(rng.standard_normal((cap, No)).astype(np.float32))
+    mask = np.zeros(cap, np.uint8)
+    mask[rng.permutation(cap)[:T]] = 1
+    cu, gidx, inv, T_ = orc.pack_indices(mask.reshape(B, N))
+    assert T_ == T
+    gi = np.zeros(cap, np.int32)
+    gi[:T] = gidx
+    ref = orc.linear_packed_backward(g, x, gidx, W)
+    dx = torch.full((cap, K), float("nan"), dtype=td, device="cuda")
+    dW = torch.full((No, K), float("nan"), dtype=torch.float32, device="cuda")
+    db = torch.full((No,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(spa.spa_linear_bwd_weight_workspace_bytes(cap, K, No, dtype), 256), dtype=torch.uint8, device="cuda")
+    tot = dev(np.array([T], np.int32))
+    spa.spa_linear_packed_bwd_input(dev(g, dtype), None, tot, dev(W, dtype), cap, dev(gi), dev(inv), dx)
+    spa.spa_linear_packed_bwd_weight(dev(g, dtype), None, dev(x, dtype), dev(gi), None, tot, cap, dW, db, ws)
+    torch.cuda.synchronize()
+    got = host(dx)
+    assert np.all(got[inv < 0] == 0) and not np.any(np.isnan(got))
+    tol_x, tol_w = (1e-5, 1e-5) if dtype == "f32" else (1e-2, 2e-3)
+    if T == 0:
+        assert np.all(host(dW) == 0) and np.all(host(db) == 0)
+    else:
+        assert _rel(got[gidx], ref["d_rows"]) <= tol_x
+        assert _rel(host(dW), ref["dW"]) <= tol_w and _rel(host(db), ref["dbias"]) <= tol_w
+
+
+def test_linear_backward_rejects_bad_arguments(spa):
+    x = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros(32, 64, dtype=torch.bfloat16, device="cuda")
+    g = torch.zeros(64, 32, dtype=torch.bfloat16, device="cuda")
+    dW = torch.zeros(32, 64, dtype=torch.float32, device="cuda")
+    inv = torch.zeros(64, dtype=torch.int32, device="cuda")
+    sc = torch.zeros(64, dtype=torch.float32, device="cuda")
+    with pytest.raises(spa.SpaError, match="dx_idx"):
+        spa.spa_linear_packed_bwd_input(g, None, None, W, 64, None, inv, x)              # zero fill without dx_idx
+    with pytest.raises(spa.SpaError, match="workspace"):
+        spa.spa_linear_packed_bwd_weight(g, None, x, None, None, None, 64, dW, None, None)
+    with pytest.raises(spa.SpaError, match="x_idx"):
+        spa.spa_linear_packed_bwd_weight(g, None, x, None, sc, None, 64, dW, None, torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
