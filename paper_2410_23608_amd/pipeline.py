@@ -256,6 +256,93 @@ class BlockPass:
         return x if self.in_place else self.y
 
 
+class BlockTrainPass:
+    """Forward + backward of one SPA attention block WITH its projections (Section 3.2) and the
+    selection loss (Section 3.3), eleven launches:
+
+      fwd: gate_select(x) -> pack (indices only) -> QKV projection of the selected, gated tokens
+           -> packed attention -> output projection scattering y[token] = x[token] + projection
+      bwd: (dy at token positions) -> input side and weight side of the output projection (dy
+           gathered inside the GEMMs) -> attention backward on the packed rows -> input side of
+           the QKV projection, scattering d_rg to token positions with the unselected rows
+           cleared, and its weight side (x gathered and gate-scaled inside the GEMM) -> gate
+           backward with the selection loss.
+    Results: dW_qkv, db_qkv, dW_o, db_o, dw, db (fp32), loss, and dx = the gradient that reaches x
+    through the gate and the gated representation; the residual path adds dy itself to it, which
+    is left to the caller (it is the upstream gradient, unchanged)."""
+
+    def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
+                 loss_scale: Optional[float] = None):
+        self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
+        self.tau, self.bias = tau, bias
+        self.loss_scale = 0.01 / (B * N) if loss_scale is None else loss_scale
+        td, cap = _td(dtype), B * N
+        code = spa.SPA_BF16 if dtype == "bf16" else spa.SPA_F32
+        dv = dict(device="cuda")
+        f32 = dict(dtype=torch.float32, device="cuda")
+        self.scores = torch.empty(B, N, **f32)
+        self.mask = torch.empty(B, N, dtype=torch.uint8, **dv)
+        self.cu_seqlens = torch.zeros(B + 1, dtype=torch.int32, **dv)
+        self.gather_idx = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.inv_pos = torch.zeros(cap, dtype=torch.int32, **dv)
+        self.total = torch.zeros(1, dtype=torch.int32, **dv)
+        self.packed_qkv = torch.zeros(cap, 3 * C, dtype=td, **dv)
+        self.attn = torch.zeros(cap, C, dtype=td, **dv)
+        self.lse = torch.zeros(H, cap, **f32)
+        self.y = torch.empty(B, N, C, dtype=td, **dv)
+        self.d_attn = torch.zeros(cap, C, dtype=td, **dv)
+        self.d_qkv = torch.zeros(cap, 3 * C, dtype=td, **dv)
+        self.d_rg = torch.empty(B, N, C, dtype=td, **dv)
+        self.dx = torch.empty(B, N, C, dtype=td, **dv)
+        self.dW_qkv, self.db_qkv = torch.empty(3 * C, C, **f32), torch.empty(3 * C, **f32)
+        self.dW_o, self.db_o = torch.empty(C, C, **f32), torch.empty(C, **f32)
+        self.dw, self.db, self.loss = torch.empty(C, **f32), torch.empty(1, **f32), torch.empty(1, **f32)
+        u8 = lambda n: torch.empty(max(n, 256), dtype=torch.uint8, **dv)
+        self.ws_attn = u8(spa.spa_attention_bwd_workspace_bytes(B, N, H, self.Dh, code))
+        self.ws_gate = u8(spa.spa_gate_bwd_workspace_bytes(B, N, C, code))
+        self.ws_qkv = u8(spa.spa_linear_bwd_weight_workspace_bytes(cap, C, 3 * C, dtype))
+        self.ws_o = u8(spa.spa_linear_bwd_weight_workspace_bytes(cap, C, C, dtype))
+
+    def stages(self, x, w, W_qkv, b_qkv, W_o, b_o, labels, dy) -> List[Tuple[str, Callable[[], None]]]:
+        B, N, C, H, Dh = self.B, self.N, self.C, self.H, self.Dh
+        cap, p, dp = B * N, self.packed_qkv, self.d_qkv
+        dy2 = dy.view(cap, C)
+        self.y.copy_(x)                                    # the bypassing rows of y, set once
+        return [
+            ("gate_select", spa.spa_gate_select(x, w, self.bias, None, self.tau, self.scores, self.mask, None,
+                                                prepare=True)),
+            ("pack_indices", spa.spa_pack(None, self.mask, None, None, 0, None, self.cu_seqlens, self.gather_idx,
+                                          self.inv_pos, self.total, prepare=True)),
+            ("qkv_projection", spa.spa_linear_packed(x, self.gather_idx, self.scores, self.total, W_qkv, b_qkv, p,
+                                                     prepare=True)),
+            ("packed_attention", spa.spa_packed_attention(p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.cu_seqlens, B, N,
+                                                          H, Dh, self.attn, self.lse, prepare=True)),
+            ("out_projection_scatter", spa.spa_linear_packed_scatter(self.attn, self.total, W_o, b_o, self.gather_idx,
+                                                                     x, self.y, prepare=True)),
+            ("out_projection_bwd_input", spa.spa_linear_packed_bwd_input(dy2, self.gather_idx, self.total, W_o, cap,
+                                                                         None, None, self.d_attn, prepare=True)),
+            ("out_projection_bwd_weight", spa.spa_linear_packed_bwd_weight(dy2, self.gather_idx, self.attn, None, None,
+                                                                           self.total, cap, self.dW_o, self.db_o,
+                                                                           self.ws_o, prepare=True)),
+            ("packed_attention_bwd", spa.spa_packed_attention_bwd(
+                p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.attn, self.d_attn, self.lse, self.cu_seqlens, B, N, H, Dh,
+                dp[:, :C], dp[:, C:2 * C], dp[:, 2 * C:], self.ws_attn, prepare=True)),
+            ("qkv_projection_bwd_input", spa.spa_linear_packed_bwd_input(dp, None, self.total, W_qkv, cap,
+                                                                         self.gather_idx, self.inv_pos,
+                                                                         self.d_rg.view(cap, C), prepare=True)),
+            ("qkv_projection_bwd_weight", spa.spa_linear_packed_bwd_weight(dp, None, x, self.gather_idx, self.scores,
+                                                                           self.total, cap, self.dW_qkv, self.db_qkv,
+                                                                           self.ws_qkv, prepare=True)),
+            ("gate_bwd", spa.spa_gate_bwd(x, w, self.bias, self.scores, None, labels, self.d_rg, True, self.loss_scale,
+                                          self.loss, self.dx, self.dw, self.db, self.ws_gate, prepare=True)),
+        ]
+
+    def run(self, x, w, W_qkv, b_qkv, W_o, b_o, labels, dy):
+        for _, fn in self.stages(x, w, W_qkv, b_qkv, W_o, b_o, labels, dy):
+            fn()
+        return self.loss
+
+
 class ContainerForwardPass:
     """The forward pass with the paper's container mask (Section 3.2 "Token Packing"): the
     packed stream is cut into containers of length L and a token attends to the tokens of its
