@@ -31,10 +31,11 @@ namespace spa {
 constexpr int kLbThreads = 256;
 constexpr int kLbT = 128;          // output tile edge
 constexpr int kLbK = 64;           // contraction step
-constexpr int kLbRS = kLbT + 32;   // row stride (elements) of a [contraction][128] tile: 80 dwords = 16 mod 64,
+constexpr int kLbRS = kLbT + 16;   // row stride (elements) of a [contraction][128] tile: 72 dwords = 8 mod 64,
                                    // the 4 rows x 32 bytes a 16-lane block reads fall on distinct banks
 constexpr int kLbRSA = kLbK + 8;   // row stride of a [128][contraction] tile (16-byte fragment reads)
 constexpr size_t kLbInputLds = (size_t)2 * (kLbT * kLbRSA + kLbK * kLbRS) * sizeof(__bf16);
+constexpr int kLbRows = 512;       // rows of a chunk whose sources are tabled in LDS at a time
 constexpr size_t kLbWeightLds = (size_t)2 * 2 * kLbK * kLbRS * sizeof(__bf16);
 
 // MFMA operand fragment taken DOWN the columns of a row-major tile whose rows are the
@@ -256,6 +257,9 @@ linear_bwd_weight_bf16_kernel(const __bf16* __restrict__ dout, const int32_t* __
   extern __shared__ __attribute__((aligned(16))) unsigned char lb_smem[];
   __bf16(*Gs)[BK * RS] = reinterpret_cast<__bf16(*)[BK * RS]>(lb_smem);
   __bf16(*Xs)[BK * RS] = reinterpret_cast<__bf16(*)[BK * RS]>(lb_smem + 2 * BK * RS * sizeof(__bf16));
+  __shared__ int g_src[kLbRows];       // row of dout (-1: past the end of the chunk), of x, and the
+  __shared__ int x_src[kLbRows];       // gate scale of every row of the current block
+  __shared__ float x_scale[kLbRows];
 
   const int M = total != nullptr ? min(total[0], m_cap) : m_cap;
   const TokenSplit ts = token_split(M, splits);
@@ -266,7 +270,6 @@ linear_bwd_weight_bf16_kernel(const __bf16* __restrict__ dout, const int32_t* __
   const int nt = tile_id / k_tiles, kt_ = tile_id - nt * k_tiles;
   const int n0 = nt * BT, k0 = kt_ * BT;
   const int m_begin = split * ts.chunk, m_end = min(M, m_begin + ts.chunk);
-  const int nsteps = (m_end - m_begin + BK - 1) / BK;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
   const int wn = (wv >> 1) * 64, wk = (wv & 1) * 64;
@@ -279,36 +282,21 @@ linear_bwd_weight_bf16_kernel(const __bf16* __restrict__ dout, const int32_t* __
   const __bf16* gcol = dout + (n0 + s_c * 8 < n_out ? n0 + s_c * 8 : n0);
   const __bf16* xcol = x + (k0 + s_c * 8 < K ? k0 + s_c * 8 : k0);
 
-  // The rows of a step are found two steps before they are loaded (index, then score, then row
-  // would otherwise be three dependent trips to memory inside one step).
-  struct Where {
-    int g[NU], x[NU];
-    float sc[NU];
-    bool ok[NU];
-  };
   struct Data {
     bf16x8 g[NU], x[NU];
     float sc[NU];
     bool ok[NU];
   };
-  auto locate = [&](Where& w, int t) {
+  // rows of step t of the current block of tabled rows
+  auto gload = [&](Data& d, int t) {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      const int m = m_begin + t * BK + s_r + u * 16;
-      const int mc = min(m, m_end - 1);
-      w.ok[u] = m < m_end;
-      w.g[u] = dout_idx != nullptr ? dout_idx[mc] : mc;
-      w.x[u] = x_idx != nullptr ? x_idx[mc] : mc;
-      w.sc[u] = kScale ? sigmoidf_dev(gate_scores[w.x[u]]) : 1.f;
-    }
-  };
-  auto gload = [&](Data& d, const Where& w) {
-#pragma unroll
-    for (int u = 0; u < NU; ++u) {
-      d.g[u] = *reinterpret_cast<const bf16x8*>(gcol + (long)w.g[u] * ldd);
-      d.x[u] = *reinterpret_cast<const bf16x8*>(xcol + (long)w.x[u] * K);
-      d.sc[u] = w.sc[u];
-      d.ok[u] = w.ok[u];
+      const int r = t * BK + s_r + u * 16;
+      const int gi = g_src[r];
+      d.ok[u] = gi >= 0;
+      d.sc[u] = x_scale[r];
+      d.g[u] = *reinterpret_cast<const bf16x8*>(gcol + (long)max(gi, 0) * ldd);
+      d.x[u] = *reinterpret_cast<const bf16x8*>(xcol + (long)x_src[r] * K);
     }
   };
   auto lstore = [&](const Data& d, int buf) {
@@ -357,33 +345,57 @@ linear_bwd_weight_bf16_kernel(const __bf16* __restrict__ dout, const int32_t* __
     }
   };
 
-  // Entering a trip: LDS buffer 0 holds step kt, d1 holds step kt + 1, w0 / w1 know where the
-  // rows of steps kt + 2 / kt + 3 are.  Steps past the end repeat the chunk's last row.
-  Where w0, w1;
-  Data d0, d1;
-  locate(w0, 0);
-  locate(w1, 1);
-  gload(d0, w0);
-  locate(w0, 2);
-  gload(d1, w1);
-  locate(w1, 3);
-  lstore(d0, 0);
-  __syncthreads();
-  for (int kt = 0; kt + 1 < nsteps; kt += 2) {
-    gload(d0, w0);
-    locate(w0, kt + 4);
-    compute(0);
-    lstore(d1, 1);
+  // The chunk is walked in blocks of kLbRows rows.  Where a block's rows lie (index arrays) and
+  // their gate scale are tabled in LDS first, so the row loads of the pipelined loop depend on
+  // LDS reads only, not on other loads still in flight (index -> score -> row would be three
+  // dependent trips to memory per step).
+  for (int blk0 = m_begin; blk0 < m_end; blk0 += kLbRows) {
+    const int blk_rows = min(kLbRows, m_end - blk0), steps = (blk_rows + BK - 1) / BK;
+    // all index loads first, then all score loads: two trips to memory for the whole table
+    constexpr int NF = kLbRows / kLbThreads;
+    int gi[NF], xi[NF];
+    float sv[NF];
+#pragma unroll
+    for (int u = 0; u < NF; ++u) {
+      const int m = min(blk0 + tid + u * kLbThreads, m_end - 1);
+      gi[u] = dout_idx != nullptr ? dout_idx[m] : m;
+      xi[u] = x_idx != nullptr ? x_idx[m] : m;
+    }
+#pragma unroll
+    for (int u = 0; u < NF; ++u) sv[u] = kScale ? gate_scores[xi[u]] : 0.f;
+#pragma unroll
+    for (int u = 0; u < NF; ++u) {
+      const int r = tid + u * kLbThreads;
+      const bool valid = r < blk_rows;
+      if (r < steps * BK) {
+        g_src[r] = valid ? gi[u] : -1;
+        x_src[r] = valid ? xi[u] : 0;
+        x_scale[r] = valid ? (kScale ? sigmoidf_dev(sv[u]) : 1.f) : 0.f;
+      }
+    }
     __syncthreads();
-    gload(d1, w1);
-    locate(w1, kt + 5);
-    compute(1);
+    // Entering a trip: LDS buffer 0 holds step kt, d1 holds step kt + 1, d0 is free.  Loads
+    // past the last step repeat it; what they bring is stored but never multiplied.
+    const int last = steps - 1;
+    Data d0, d1;
+    gload(d0, 0);
+    if (steps > 1) gload(d1, 1);
     lstore(d0, 0);
     __syncthreads();
-  }
-  if (nsteps & 1) {
-    compute(0);
-    __syncthreads();     // the epilogue reuses the operand buffers
+    for (int kt = 0; kt + 1 < steps; kt += 2) {
+      gload(d0, min(kt + 2, last));
+      compute(0);
+      lstore(d1, 1);
+      __syncthreads();
+      gload(d1, min(kt + 3, last));
+      compute(1);
+      lstore(d0, 0);
+      __syncthreads();
+    }
+    if (steps & 1) {
+      compute(0);
+      __syncthreads();     // the next block's tables and the epilogue reuse LDS
+    }
   }
 
   // epilogue: the wave's 64 (n) x 64 (k) block is parked in LDS as fp32 and leaves as 16-byte
@@ -464,16 +476,18 @@ linear_bwd_weight_f32_kernel(const float* __restrict__ dout, const int32_t* __re
   }
 }
 
-// Number of token chunks of the weight-side kernel: enough (chunk, tile) workgroups for two per
-// compute unit, chunks of at least 256 rows at full capacity.  SPA_GEMM_SPLITS overrides it
-// (tuning aid).
+// Number of token chunks of the weight-side kernel: (chunk, tile) workgroups for about three per
+// compute unit (two are resident at a time), at most 16 chunks (the partial tiles are written
+// and read once per chunk), chunks of at least 256 rows at full capacity.  SPA_GEMM_SPLITS
+// overrides it (tuning aid).
 static int weight_splits(int M_cap, int K, int N_out) {
   static const int env = [] { const char* e = getenv("SPA_GEMM_SPLITS"); return e ? atoi(e) : 0; }();
   if (env > 0) return env;
   const long tiles = (long)((N_out + kLbT - 1) / kLbT) * ((K + kLbT - 1) / kLbT);
-  long s = (512 + tiles - 1) / tiles;
+  long s = (768 + tiles - 1) / tiles;
   const long by_rows = M_cap / 256 > 0 ? M_cap / 256 : 1;
   if (s > by_rows) s = by_rows;
+  if (s > 16) s = 16;
   return (int)(s < 1 ? 1 : s);
 }
 
@@ -581,3 +595,4 @@ extern "C" int spa_linear_packed_bwd_weight(const void* dout, const int32_t* dou
                      splits, nk, N_out, dW, dbias);
   return check_launch(fn);
 }
+

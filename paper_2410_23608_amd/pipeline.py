@@ -269,10 +269,17 @@ class BlockTrainPass:
            backward with the selection loss.
     Results: dW_qkv, db_qkv, dW_o, db_o, dw, db (fp32), loss, and dx = the gradient that reaches x
     through the gate and the gated representation; the residual path adds dy itself to it, which
-    is left to the caller (it is the upstream gradient, unchanged)."""
+    is left to the caller (it is the upstream gradient, unchanged).
+
+    overlap_weight_grads (default): nothing downstream in the step reads dW / dbias, so the two
+    weight-side GEMMs are enqueued on a second HIP stream (default priority) and run beside the
+    attention backward, the input-side GEMM and the gate backward; events order them after
+    their inputs and the step's last stage joins the streams."""
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
-                 loss_scale: Optional[float] = None):
+                 loss_scale: Optional[float] = None, overlap_weight_grads: bool = True):
+        self.overlap = overlap_weight_grads
+        self.side = torch.cuda.Stream() if overlap_weight_grads else None
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
         self.tau, self.bias = tau, bias
         self.loss_scale = 0.01 / (B * N) if loss_scale is None else loss_scale
@@ -308,6 +315,33 @@ class BlockTrainPass:
         cap, p, dp = B * N, self.packed_qkv, self.d_qkv
         dy2 = dy.view(cap, C)
         self.y.copy_(x)                                    # the bypassing rows of y, set once
+        main = torch.cuda.current_stream()
+
+        def weight_side():
+            return (spa.spa_linear_packed_bwd_weight(dy2, self.gather_idx, self.attn, None, None, self.total, cap,
+                                                     self.dW_o, self.db_o, self.ws_o, prepare=True),
+                    spa.spa_linear_packed_bwd_weight(dp, None, x, self.gather_idx, self.scores, self.total, cap,
+                                                     self.dW_qkv, self.db_qkv, self.ws_qkv, prepare=True))
+
+        if self.overlap:
+            with torch.cuda.stream(self.side):             # the prepared calls keep the stream they were made on
+                w_o, w_qkv = weight_side()
+            events = [torch.cuda.Event() for _ in range(3)]
+
+            def on_side(ev, call):
+                def go():
+                    ev.record(main)                        # inputs of the GEMM are complete on the main stream
+                    self.side.wait_event(ev)
+                    call()
+                return go
+
+            def join():
+                events[2].record(self.side)
+                main.wait_event(events[2])
+
+            w_o, w_qkv = on_side(events[0], w_o), on_side(events[1], w_qkv)
+        else:
+            w_o, w_qkv = weight_side()
         return [
             ("gate_select", spa.spa_gate_select(x, w, self.bias, None, self.tau, self.scores, self.mask, None,
                                                 prepare=True)),
@@ -319,23 +353,19 @@ class BlockTrainPass:
                                                           H, Dh, self.attn, self.lse, prepare=True)),
             ("out_projection_scatter", spa.spa_linear_packed_scatter(self.attn, self.total, W_o, b_o, self.gather_idx,
                                                                      x, self.y, prepare=True)),
+            ("out_projection_bwd_weight", w_o),
             ("out_projection_bwd_input", spa.spa_linear_packed_bwd_input(dy2, self.gather_idx, self.total, W_o, cap,
                                                                          None, None, self.d_attn, prepare=True)),
-            ("out_projection_bwd_weight", spa.spa_linear_packed_bwd_weight(dy2, self.gather_idx, self.attn, None, None,
-                                                                           self.total, cap, self.dW_o, self.db_o,
-                                                                           self.ws_o, prepare=True)),
             ("packed_attention_bwd", spa.spa_packed_attention_bwd(
                 p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.attn, self.d_attn, self.lse, self.cu_seqlens, B, N, H, Dh,
                 dp[:, :C], dp[:, C:2 * C], dp[:, 2 * C:], self.ws_attn, prepare=True)),
+            ("qkv_projection_bwd_weight", w_qkv),
             ("qkv_projection_bwd_input", spa.spa_linear_packed_bwd_input(dp, None, self.total, W_qkv, cap,
                                                                          self.gather_idx, self.inv_pos,
                                                                          self.d_rg.view(cap, C), prepare=True)),
-            ("qkv_projection_bwd_weight", spa.spa_linear_packed_bwd_weight(dp, None, x, self.gather_idx, self.scores,
-                                                                           self.total, cap, self.dW_qkv, self.db_qkv,
-                                                                           self.ws_qkv, prepare=True)),
             ("gate_bwd", spa.spa_gate_bwd(x, w, self.bias, self.scores, None, labels, self.d_rg, True, self.loss_scale,
                                           self.loss, self.dx, self.dw, self.db, self.ws_gate, prepare=True)),
-        ]
+        ] + ([("join_streams", join)] if self.overlap else [])
 
     def run(self, x, w, W_qkv, b_qkv, W_o, b_o, labels, dy):
         for _, fn in self.stages(x, w, W_qkv, b_qkv, W_o, b_o, labels, dy):

@@ -357,11 +357,13 @@ def test_linear_backward_rejects_bad_arguments(spa):
         spa.spa_linear_packed_bwd_weight(g, None, x, None, sc, None, 64, dW, None, torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
 
 
-def test_block_train_pass_with_both_projections(spa):
+@pytest.mark.parametrize("overlap", [True, False])
+def test_block_train_pass_with_both_projections(spa, overlap):
     """BlockTrainPass (forward + backward of the block with its projections and the selection
     loss) against the oracle.  Every backward stage is checked against the oracle applied to the
     device's own inputs of that stage (so each link of the chain is held to a tight bound), and
-    the end of the chain against the oracle's own chain."""
+    the end of the chain against the oracle's own chain.  overlap: the weight-side GEMMs on a
+    second stream (as benchmarked) or everything on one stream."""
     from paper_2410_23608_amd.pipeline import BlockTrainPass
     wl = dataclasses.replace(wlmod.WORKLOADS["vit_s"], B=6)
     B, N, C, H = wl.B, wl.N, wl.C, wl.H
@@ -372,7 +374,7 @@ def test_block_train_pass_with_both_projections(spa):
     Wqkv, bqkv, Wo, bo = mkw(3 * C, C), mkw(3 * C), mkw(C, C), mkw(C)
     x, w, bias, labels = bun["x"], bun["w"], bun["bias"], bun["labels"]
     dy = wlmod.round_bf16(rng.standard_normal((B, N, C)).astype(np.float32))
-    tp = BlockTrainPass(B, N, C, H, "bf16", wl.tau, bias)
+    tp = BlockTrainPass(B, N, C, H, "bf16", wl.tau, bias, overlap_weight_grads=overlap)
     tp.d_rg.fill_(float("nan"))
     tp.run(dev(x, "bf16"), dev(w, "bf16"), dev(Wqkv, "bf16"), dev(bqkv, "bf16"), dev(Wo, "bf16"), dev(bo, "bf16"),
            dev(labels), dev(dy, "bf16"))
