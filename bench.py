@@ -546,6 +546,35 @@ def main():
             "launches": [n_ for n_, _ in b5], "ms_per_step": 1e3 * b5dt / args.steps,
             "out_projection_scatter_us": round(back_to_back_us(b5[-1][1], args.steps, torch), 2)}
 
+        # the block forward + backward with its projections (input-side and weight-side GEMMs of both
+        # projections, attention backward, gate backward with the selection loss)
+        from paper_2410_23608_amd.pipeline import BlockTrainPass
+        dy_blk = torch.randn(B, N, C, generator=g).cuda().to(td)
+        lab_blk = torch.from_numpy(bun["labels"]).cuda()
+        blk_train = {}
+        for key, ov in (("two_streams", True), ("one_stream", False)):
+            btp = BlockTrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, overlap_weight_grads=ov)
+            tst = btp.stages(x, w, W_qkv, b_qkv, W_o, b_o, lab_blk, dy_blk)
+
+            def tstep():
+                for _, fn in tst:
+                    fn()
+
+            for _ in range(5):
+                tstep()
+            torch.cuda.synchronize()
+            tdt = timed(tstep, args.steps, torch)
+            blk_train[key] = {"ms_per_step": 1e3 * tdt / args.steps, "value": T * args.steps / tdt,
+                              "unit": "selected tokens/s"}
+            if not ov:
+                tus = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in tst}
+                gemm = {"qkv_projection_bwd_input": 3, "qkv_projection_bwd_weight": 3, "out_projection_bwd_input": 1,
+                        "out_projection_bwd_weight": 1}
+                blk_train[key]["launches"] = [n_ for n_, _ in tst]
+                blk_train[key]["stage_us"] = {k_: round(v_, 2) for k_, v_ in tus.items()}
+                blk_train[key]["gemm_tflops"] = {k_: round(2.0 * T * C * m_ * C / tus[k_] / 1e6, 1) for k_, m_ in gemm.items()}
+        result["block_with_projections"]["fwd_bwd"] = blk_train
+
         # the paper's container mask: containers of L = 7^2 tokens, map shifted by (3, 3)
         side = int(round(N ** 0.5))
         if side * side == N:
