@@ -164,3 +164,53 @@ def test_seeded_sweep_of_the_bandwidth_bound_calls(spa, seed):
         t = 2e-2 if dtype == "bf16" else 2e-5
         assert rel(host(dx), g["dx"]) <= t and rel(host(dw), g["dw"]) <= max(t, 1e-3), what
         assert abs(float(host(loss)[0]) - g["loss"]) <= 1e-3 * abs(g["loss"]) + 1e-7, what
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_seeded_sweep_of_the_projections_and_their_backward(spa, seed):
+    """Random widths (multiples of 8, ragged against the 64-wide contraction steps and the
+    128-wide tiles), row counts, selection densities and index maps: forward projection, input
+    side and weight side of its backward, against the oracle."""
+    rng = np.random.default_rng(3000 + seed)
+    rel = lambda got, ref: float(np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref)))) if ref.size else 0.0
+    for case in range(12):
+        dtype = "bf16" if rng.random() < 0.85 else "f32"
+        K = 8 * int(rng.integers(1, 50 if dtype == "bf16" else 12))
+        No = 8 * int(rng.integers(1, 60 if dtype == "bf16" else 12))
+        cap = int(rng.choice([1, 40, 129, 600, 2500, 5000] if dtype == "bf16" else [1, 40, 129]))
+        dens = float(rng.choice([0.0, 0.02, 0.5, 1.0]))
+        scale, bias_on = bool(rng.random() < 0.5), bool(rng.random() < 0.5)
+        mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+        x = mk(rng.standard_normal((cap, K)).astype(np.float32))
+        W = mk((rng.standard_normal((No, K)) / np.sqrt(K)).astype(np.float32))
+        bias = mk(rng.standard_normal(No).astype(np.float32)) if bias_on else None
+        s = rng.standard_normal(cap).astype(np.float32) if scale else None
+        g = mk(rng.standard_normal((cap, No)).astype(np.float32))
+        mask = (rng.uniform(size=(1, cap)) < dens).astype(np.uint8)
+        cu, gidx, inv, T = orc.pack_indices(mask)
+        what = f"seed {seed} case {case}: {dtype} cap={cap} T={T} K={K} N_out={No} scale={scale} bias={bias_on}"
+        td = tdtype(dtype)
+        gi = np.zeros(cap, np.int32)
+        gi[:T] = gidx
+        gi_d, tot_d, inv_d = dev(gi), dev(np.array([T], np.int32)), dev(inv)
+        xd, Wd, gd = dev(x, dtype), dev(W, dtype), dev(g, dtype)
+        sd = None if s is None else dev(s)
+        out = torch.full((cap, No), float("nan"), dtype=td, device="cuda")
+        spa.spa_linear_packed(xd, gi_d, sd, tot_d, Wd, None if bias is None else dev(bias, dtype), out)
+        dx = torch.full((cap, K), float("nan"), dtype=td, device="cuda")
+        dW = torch.full((No, K), float("nan"), dtype=torch.float32, device="cuda")
+        db = torch.full((No,), float("nan"), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(spa.spa_linear_bwd_weight_workspace_bytes(cap, K, No, dtype), 256), dtype=torch.uint8, device="cuda")
+        spa.spa_linear_packed_bwd_input(gd, None, tot_d, Wd, cap, gi_d, inv_d, dx)
+        spa.spa_linear_packed_bwd_weight(gd, None, xd, gi_d, sd, tot_d, cap, dW, db, ws)
+        torch.cuda.synchronize()
+        tol, tol_w = (1e-5, 1e-5) if dtype == "f32" else (1e-2, 2e-3)
+        ref = orc.linear_packed(x, gidx, W, bias, s, dtype)
+        got = host(out)
+        assert np.all(np.isnan(got[T:])), what
+        assert rel(got[:T], ref) <= tol, what
+        bw = orc.linear_packed_backward(g, x, gidx, W, s, None, dtype)
+        gx = host(dx)
+        assert not np.any(np.isnan(gx)) and np.all(gx[inv < 0] == 0), what
+        assert rel(gx[gidx], bw["d_rows"]) <= tol, what
+        assert rel(host(dW), bw["dW"]) <= tol_w and rel(host(db), bw["dbias"]) <= tol_w, what
