@@ -237,6 +237,7 @@ def _bwd_case(dtype, B, N, K, No, mode, seed=43, select=0.55):
 @pytest.mark.parametrize("dtype,B,N,K,No", [("bf16", 3, 100, 64, 96), ("bf16", 8, 196, 384, 1152),
                                             ("bf16", 2, 777, 96, 288), ("bf16", 4, 129, 32, 8), ("bf16", 2, 150, 200, 72),
                                             ("bf16", 40, 196, 96, 1280), ("bf16", 2, 300, 136, 264),
+                                            ("bf16", 64, 196, 64, 96),      # token chunks longer than one LDS table of rows
                                             ("f32", 2, 60, 64, 192)])
 @pytest.mark.parametrize("mode", ["plain", "qkv", "out_proj"])
 def test_linear_backward_matches_oracle(spa, dtype, B, N, K, No, mode):
