@@ -264,12 +264,12 @@ def main():
         turn[0] += 1
 
     # Which HIP streams end up sharing one of the process's hardware queues (4 here) is the
-    # runtime's business, and two batches on one queue run one after the other.  So two groups of
-    # S streams are tried for a few hundred untimed steps each and the faster group is kept.
+    # runtime's business, and two batches on one queue run one after the other.  So three groups of
+    # S streams are tried for a few hundred untimed steps each and the fastest group is kept.
     stream_groups = {}
     if S > 1:
         best = None
-        for gi_ in range(2):
+        for gi_ in range(3):
             cand = [torch.cuda.Stream() for _ in range(S)]
             sets = build_sets(cand)
             for _ in range(n_sets):
