@@ -689,6 +689,21 @@ def main():
         htdt = timed(htstep, args.steps, torch)
         hres["fwd_bwd"] = {"launches": len(htstages), "selected_tokens": htT, "ms_per_chain": 1e3 * htdt / args.steps,
                            "value": sum(htT) * args.steps / htdt, "unit": "selected tokens/s"}
+        htpc = HierarchyTrainPass(hcfg, concurrent=True)
+        htcstages = htpc.stages(hx, hw, hqk, hlab, hdy)
+
+        def htcstep():
+            for _, fn in htcstages:
+                fn()
+
+        for _ in range(5):
+            htcstep()
+        torch.cuda.synchronize()
+        htcdt = timed(htcstep, args.steps, torch)
+        hres["fwd_bwd"]["stream_per_stage"] = {
+            "ms_per_chain": 1e3 * htcdt / args.steps, "value": sum(htT) * args.steps / htcdt,
+            "gradients_equal_one_stream": bool(all(torch.equal(a_.dx, b_.dx) and torch.equal(a_.dw, b_.dw)
+                                                   for a_, b_ in zip(htpc.passes, htp.passes)))}
         result["hierarchy"] = hres
 
     if not args.no_cpu_baseline:

@@ -318,14 +318,15 @@ def test_hierarchy_pass_matches_stagewise_oracle(spa, pipeline):
         s_up = orc.maxpool2x2(ref["scores"].astype(np.float32), *wl.grid).astype(np.float32)
 
 
-def test_hierarchy_training_chain_matches_stagewise_oracle(spa, pipeline):
+@pytest.mark.parametrize("concurrent", [False, True])
+def test_hierarchy_training_chain_matches_stagewise_oracle(spa, pipeline, concurrent):
     """Forward + backward over the four stages (reduced batch) through HierarchyTrainPass:
     every stage's selection, attention gradients and gate gradients against the oracle run stage
-    by stage with max-pooled up-scale scores."""
+    by stage with max-pooled up-scale scores; on one stream and with a stream per stage."""
     bundles = wlmod.generate_hierarchy(seed=4, B=2)
     cfg = [(b["workload"].B, *b["workload"].grid, b["workload"].C, b["workload"].H, b["workload"].dtype,
             b["workload"].tau, b["bias"]) for b in bundles]
-    hp = pipeline.HierarchyTrainPass(cfg)
+    hp = pipeline.HierarchyTrainPass(cfg, concurrent=concurrent)
     qks = [b["qkv"][:, :, :2 * b["workload"].C] for b in bundles]
     hp.run([dev(b["x"], "bf16") for b in bundles], [dev(b["w"], "bf16") for b in bundles],
            [dev(q, "bf16") for q in qks], [dev(b["labels"]) for b in bundles], [dev(b["dy"], "bf16") for b in bundles])
