@@ -197,7 +197,9 @@ def test_seeded_sweep_of_the_projections_and_their_backward(spa, seed):
         sd = None if s is None else dev(s)
         out = torch.full((cap, No), float("nan"), dtype=td, device="cuda")
         spa.spa_linear_packed(xd, gi_d, sd, tot_d, Wd, None if bias is None else dev(bias, dtype), out)
-        dx = torch.full((cap, K), float("nan"), dtype=td, device="cuda")
+        pad = 8 * int(rng.integers(0, 3))                           # dx as a column slice of a wider buffer
+        dx_wide = torch.full((cap, K + 2 * pad), float("nan"), dtype=td, device="cuda")
+        dx = dx_wide[:, pad:pad + K]
         dW = torch.full((No, K), float("nan"), dtype=torch.float32, device="cuda")
         db = torch.full((No,), float("nan"), dtype=torch.float32, device="cuda")
         ws = torch.empty(max(spa.spa_linear_bwd_weight_workspace_bytes(cap, K, No, dtype), 256), dtype=torch.uint8, device="cuda")
@@ -212,5 +214,8 @@ def test_seeded_sweep_of_the_projections_and_their_backward(spa, seed):
         bw = orc.linear_packed_backward(g, x, gidx, W, s, None, dtype)
         gx = host(dx)
         assert not np.any(np.isnan(gx)) and np.all(gx[inv < 0] == 0), what
+        if pad:
+            wide = host(dx_wide)
+            assert np.all(np.isnan(wide[:, :pad])) and np.all(np.isnan(wide[:, pad + K:])), what   # nothing outside the slice
         assert rel(gx[gidx], bw["d_rows"]) <= tol, what
         assert rel(host(dW), bw["dW"]) <= tol_w and rel(host(db), bw["dbias"]) <= tol_w, what

@@ -358,3 +358,33 @@ def test_hierarchy_training_chain_matches_stagewise_oracle(spa, pipeline, concur
         assert rel(host(tp.dx), g["dx"]) <= 2e-2 and rel(host(tp.dw), g["dw"]) <= 2e-2
         assert abs(float(host(tp.loss)[0]) - g["loss"]) <= 1e-3 * abs(g["loss"])
         s_up = orc.maxpool2x2(s.astype(np.float32), *wl.grid).astype(np.float32)
+
+
+def test_independent_batches_on_four_streams_match_their_own_results(spa, pipeline):
+    """Four different batches in flight on four HIP streams (as the benchmark runs the forward
+    chain): every batch's outputs equal, bit for bit, what the same batch gives alone on one
+    stream, so the calls share no hidden state."""
+    wl = dataclasses.replace(wlmod.WORKLOADS["vit_s"], B=16)
+    bundles = [wlmod.generate(wl, seed) for seed in (11, 12, 13, 14)]
+    ins = [(dev(b["x"], "bf16"), dev(b["w"], "bf16"), dev(b["qkv"], "bf16")) for b in bundles]
+    alone = []
+    for (x, w, qkv), b in zip(ins, bundles):
+        fp = pipeline.ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, b["bias"], keep_packed_out=False)
+        alone.append((fp.run(x, w, qkv).clone(), fp.gather_idx.clone(), int(fp.total.item())))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in bundles]
+    passes, chains = [], []
+    for st, (x, w, qkv), b in zip(streams, ins, bundles):
+        with torch.cuda.stream(st):
+            fp = pipeline.ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, b["bias"], keep_packed_out=False)
+            passes.append(fp)
+            chains.append([fn for _, fn in fp.stages(x, w, qkv)])
+    torch.cuda.synchronize()
+    for _ in range(20):                      # steps dealt round-robin to the streams, launches interleaved
+        for k in range(3):
+            for chain in chains:
+                chain[k]()
+    torch.cuda.synchronize()
+    for fp, (y, gidx, T) in zip(passes, alone):
+        assert int(fp.total.item()) == T
+        assert torch.equal(fp.gather_idx[:T], gidx[:T]) and torch.equal(fp.y, y)
