@@ -599,6 +599,30 @@ def main():
                 blk_train[key]["launches"] = [n_ for n_, _ in tst]
                 blk_train[key]["stage_us"] = {k_: round(v_, 2) for k_, v_ in tus.items()}
                 blk_train[key]["gemm_tflops"] = {k_: round(2.0 * T * C * m_ * C / tus[k_] / 1e6, 1) for k_, m_ in gemm.items()}
+        if S > 1:   # independent batches in flight, one stream each, like the forward headline
+            bsets = []
+            for s_ in streams:
+                with torch.cuda.stream(s_):
+                    b_s = BlockTrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, overlap_weight_grads=False)
+                    bsets.append((b_s, b_s.stages(x.clone(), w.clone(), W_qkv.clone(), b_qkv.clone(), W_o.clone(),
+                                                  b_o.clone(), lab_blk.clone(), dy_blk.clone())))
+            torch.cuda.synchronize()
+            turn[0] = 0
+
+            def bsstep():
+                for _, fn in bsets[turn[0] % S][1]:
+                    fn()
+                turn[0] += 1
+
+            for _ in range(2 * S):
+                bsstep()
+            torch.cuda.synchronize()
+            turn[0] = 0
+            bsdt = timed(bsstep, args.steps, torch)
+            blk_train["batches_in_flight"] = {
+                "streams": S, "ms_per_step": 1e3 * bsdt / args.steps, "value": T * args.steps / bsdt,
+                "gradients_equal_single_stream": bool(all(torch.equal(b_.dW_qkv, btp.dW_qkv) and torch.equal(b_.dx, btp.dx)
+                                                          for b_, _ in bsets))}
         result["block_with_projections"]["fwd_bwd"] = blk_train
 
         # the paper's container mask: containers of L = 7^2 tokens, map shifted by (3, 3)
