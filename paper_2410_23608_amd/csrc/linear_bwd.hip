@@ -35,7 +35,8 @@ constexpr int kLbRS = kLbT + 16;   // row stride (elements) of a [contraction][1
                                    // the 4 rows x 32 bytes a 16-lane block reads fall on distinct banks
 constexpr int kLbRSA = kLbK + 8;   // row stride of a [128][contraction] tile (16-byte fragment reads)
 constexpr size_t kLbInputLds = (size_t)2 * (kLbT * kLbRSA + kLbK * kLbRS) * sizeof(__bf16);
-constexpr int kLbRows = 512;       // rows of a chunk whose sources are tabled in LDS at a time
+constexpr int kLbRows = 512;       // rows of a chunk whose sources are tabled in LDS at a time (6 KB: with the
+                                   // operand stages 78 KB per workgroup, two workgroups per compute unit)
 constexpr size_t kLbWeightLds = (size_t)2 * 2 * kLbK * kLbRS * sizeof(__bf16);
 
 // MFMA operand fragment taken DOWN the columns of a row-major tile whose rows are the
