@@ -734,3 +734,65 @@ def test_attention_work_matches_the_papers_complexity_terms():
     assert int((np.diff(cu_all).astype(np.int64) ** 2).sum()) * 2 * C == golden["msa_attention_macs"]
     # bench.py's algorithmic flop count, 4 C sum n^2, is two flops per multiply-accumulate of these terms
     assert 4 * C * int((np.diff(cu_all).astype(np.int64) ** 2).sum()) == 2 * golden["msa_attention_macs"]
+
+
+# ------------------------------------------------------------ the block with its projections
+def test_block_chain_of_oracle_steps_matches_finite_differences():
+    """The backward of a whole block, assembled from the oracle's steps in the order the GPU
+    pipeline runs them (output projection -> attention -> QKV projection of the gated rows ->
+    gate with the selection loss), against central differences of the block's forward value
+    L = sum(dy * y) + loss_scale * BCE.  The hard mask is a constant (perturbations are far
+    smaller than the selection margin).  Pins the composition itself: which gradient feeds which
+    step, and that the gradient reaching x is dy (residual and bypass) plus the gate's dx."""
+    B, N, C, H = 2, 6, 4, 2
+    r = rng(70)
+    x = r.standard_normal((B, N, C))
+    w = r.standard_normal(C)
+    bias = 0.1
+    Wqkv, bqkv = r.standard_normal((3 * C, C)) / 2, r.standard_normal(3 * C) / 4
+    Wo, bo = r.standard_normal((C, C)) / 2, r.standard_normal(C) / 4
+    labels = (r.uniform(size=(B, N)) < 0.5).astype(np.uint8)
+    dy = r.standard_normal((B, N, C))
+    lam = 0.3
+    s0 = orc.gate_scores(x, w, bias)
+    mask, margin = orc.select(s0, 0.5)
+    assert margin > 1e-3 and 2 <= mask.sum() < B * N
+    cu, gidx, inv, T = orc.pack_indices(mask)
+
+    def forward(x_=x, w_=w, Wqkv_=Wqkv, bqkv_=bqkv, Wo_=Wo, bo_=bo):
+        s = orc.gate_scores(x_, w_, bias)
+        qkv = orc.unpack(orc.linear_packed(x_, gidx, Wqkv_, bqkv_, s), inv, B, N)
+        attn, _ = orc.attention_per_image(qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], mask, H)
+        y = orc.unpack(orc.linear_packed(attn, np.arange(T), Wo_, bo_), inv, B, N, base=x_)
+        return float((dy * y).sum()) + orc.selection_loss(s, labels, lam), (s, qkv, attn)
+
+    _, (s, qkv, attn) = forward()
+    # backward, step by step
+    g_o = orc.linear_packed_backward(dy.reshape(-1, C), attn, np.arange(T), Wo, None, gidx)
+    dq, dk, dv = orc.attention_backward_per_image(qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], mask,
+                                                  g_o["d_rows"], H)
+    g_q = orc.linear_packed_backward(np.concatenate([dq, dk, dv], axis=1), x, gidx, Wqkv, s)
+    g_g = orc.gate_backward(x, w, bias, None, labels, orc.unpack(g_q["d_rows"], inv, B, N), True, lam)
+    dx_total = dy + g_g["dx"]
+
+    eps = 1e-6
+
+    def fd(name, arr, idx):
+        e = np.zeros_like(arr)
+        e[idx] = eps
+        return (forward(**{name: arr + e})[0] - forward(**{name: arr - e})[0]) / (2 * eps)
+
+    for idx in [(0, 0), (5, 3), (11, 2)]:
+        assert abs(fd("Wqkv_", Wqkv, idx) - g_q["dW"][idx]) < 1e-6
+    for idx in [(0,), (7,)]:
+        assert abs(fd("bqkv_", bqkv, idx) - g_q["dbias"][idx]) < 1e-6
+    for idx in [(0, 0), (3, 1)]:
+        assert abs(fd("Wo_", Wo, idx) - g_o["dW"][idx]) < 1e-6
+    assert abs(fd("bo_", bo, (2,)) - g_o["dbias"][2]) < 1e-6
+    for c in range(C):
+        assert abs(fd("w_", w, (c,)) - g_g["dw"][c]) < 1e-6
+    sel = np.argwhere(mask == 1)[0]
+    uns = np.argwhere(mask == 0)[0]
+    for b, n in (sel, uns):
+        for c in range(C):
+            assert abs(fd("x_", x, (b, n, c)) - dx_total[b, n, c]) < 1e-6
