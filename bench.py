@@ -475,7 +475,7 @@ def main():
                              "stage_us": {k_: round(v_, 2) for k_, v_ in tus.items()},
                              "attention_bwd_tflops": round(bwd_flops / tus["packed_attention_bwd_tokens"] / 1e6, 2)}
         # the same step with the gather of dy and the scatters of dq, dk, dv as separate launches (9 launches)
-        tp9 = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias, fused_bwd=False)
+        tp9 = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias, fused_bwd=False, pack_pair=False)
         t9 = tp9.stages(tx, tw, tqk, tlab, tdy)
 
         def t9step():
@@ -694,7 +694,7 @@ def main():
             hres["graph_replay_ms_per_chain"] = 1e3 * ghdt / args.steps
         except Exception as ex:
             hres["graph_replay_error"] = str(ex)[:200]
-        # the same hierarchy forward + backward (24 calls)
+        # the same hierarchy forward + backward (20 calls)
         from paper_2410_23608_amd.pipeline import HierarchyTrainPass
         htp = HierarchyTrainPass(hcfg)
         hqk = [up(b_["qkv"][:, :, :2 * b_["workload"].C]) for b_ in hb]

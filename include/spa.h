@@ -137,6 +137,22 @@ int spa_pack(const void* x, const uint8_t* mask, const int32_t* counts, const fl
              int32_t* total, void* stream);
 
 /*
+ * spa_pack of TWO tensors of the same tokens in one launch (Section 3.2 "Token Packing": the
+ * same selection, the same packed order): the rows of x go to packed as they are, the rows of
+ * x2, multiplied by sigmoid(gate_scores) when gate_scores is given (Eq. r_g = Sigmoid(s) . r),
+ * go to packed2.  Equal, bit for bit, to spa_pack(x, gate_scores = NULL) followed by
+ * spa_pack(x2, gate_scores); the survivors are counted and ranked once.
+ * in:  x [B,N,C], x2 [B,N,C2] dtype (C*elem, C2*elem multiples of 16 bytes); mask, counts,
+ *      gate_scores as in spa_pack.  No container padding.
+ * out: packed [B*N, C], packed2 [B*N, C2] dtype; cu_seqlens, gather_idx, inv_pos, total as in
+ *      spa_pack (each may be NULL).
+ */
+int spa_pack_pair(const void* x, int C, const void* x2, int C2, const uint8_t* mask,
+                  const int32_t* counts, const float* gate_scores, int B, int N, int dtype,
+                  void* packed, void* packed2, int32_t* cu_seqlens, int32_t* gather_idx,
+                  int32_t* inv_pos, int32_t* total, void* stream);
+
+/*
  * Token packing of a cyclically shifted feature map (Section 1: the feature maps are shifted
  * every two blocks so that the token pairs that share a container vary).  Every image is a
  * grid_h x grid_w map, N = grid_h*grid_w; the shifted map holds at (r, c) the token that sits

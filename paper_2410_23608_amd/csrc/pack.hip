@@ -65,17 +65,64 @@ struct Shift {
   }
 };
 
+// Copy of a tile's selected rows (sel_src[r] = position in the image of the r-th survivor) to
+// consecutive packed rows: consecutive threads take consecutive 16-byte chunks, up to twelve
+// independent loads in flight per thread before the first store (a 16-token tile of q|k|v rows
+// of a 384-wide model is nine per thread: one pass, one memory latency).
+template <typename T, bool kScale>
+__device__ __forceinline__ void copy_selected_rows(const T* __restrict__ xt, T* __restrict__ pt, int C, int nsel,
+                                                   const int* sel_src, const float* sel_scale, int tid) {
+  constexpr int VE = 16 / sizeof(T);
+  constexpr int U = 12;
+  const int chunks = C / VE;
+  const unsigned work = (unsigned)nsel * (unsigned)chunks;
+  for (unsigned i0 = tid; i0 < work; i0 += kPackThreads * U) {
+    uintx4 v[U];
+    unsigned dst_off[U];
+    float sc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned i = i0 + u * kPackThreads;
+      if (i < work) {
+        const unsigned r = i / (unsigned)chunks;
+        const unsigned ch = i - r * (unsigned)chunks;
+        v[u] = *reinterpret_cast<const uintx4*>(xt + (long)sel_src[r] * C + ch * VE);
+        dst_off[u] = r * (unsigned)C + ch * VE;
+        if (kScale) sc[u] = sel_scale[r];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned i = i0 + u * kPackThreads;
+      if (i < work) {
+        uintx4 o = v[u];
+        if (kScale) {
+          if constexpr (sizeof(T) == 2) {
+            floatx8 f = bf16x8_to_float(__builtin_bit_cast(bf16x8, o));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] *= sc[u];
+            o = __builtin_bit_cast(uintx4, float_to_bf16x8(f));
+          } else {
+            o = __builtin_bit_cast(uintx4, __builtin_bit_cast(floatx4, o) * sc[u]);
+          }
+        }
+        *reinterpret_cast<uintx4*>(pt + dst_off[u]) = o;
+      }
+    }
+  }
+}
+
 // kShift: tokens are ranked in the raster order of the shifted map (Section 1: the feature
 // map is shifted so that the token pairs sharing a container vary); gather_idx / inv_pos keep
 // naming ORIGINAL positions, so the scatter back undoes the shift by itself.
-template <typename T, bool kScale, bool kShift>
+template <typename T, bool kScale, bool kShift, bool kPair>
 __global__ void __launch_bounds__(kPackThreads)
 pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
             const int32_t* __restrict__ counts, const float* __restrict__ gate_scores,
             int B, int N, int C, int tile, int tiles_per_image, int container_len, Shift shift,
             T* __restrict__ packed, int32_t* __restrict__ cu_seqlens,
             int32_t* __restrict__ gather_idx, int32_t* __restrict__ inv_pos,
-            int32_t* __restrict__ total) {
+            int32_t* __restrict__ total, const T* __restrict__ x2, int C2, T* __restrict__ packed2) {
   constexpr int VE = 16 / sizeof(T);
   __shared__ int red[kPackWaves];
   __shared__ int wave_cnt[kPackWaves];
@@ -143,47 +190,14 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
     }
   }
 
-  // 4. copy the survivors' rows: consecutive threads take consecutive 16-byte chunks, up to
-  //    twelve independent loads in flight per thread before the first store (a 16-token tile of
-  //    q|k|v rows of a 384-wide model is nine per thread: one pass, one memory latency)
-  constexpr int U = 12;
-  const unsigned work = packed != nullptr ? (unsigned)nsel * (unsigned)chunks : 0u;   // indices only: no rows
-  const T* xt = x + img0 * (long)C;
-  T* pt = packed + (long)base * C;
-  for (unsigned i0 = tid; i0 < work; i0 += kPackThreads * U) {
-    uintx4 v[U];
-    unsigned dst_off[U];
-    float sc[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const unsigned i = i0 + u * kPackThreads;
-      if (i < work) {
-        const unsigned r = i / (unsigned)chunks;
-        const unsigned ch = i - r * (unsigned)chunks;
-        v[u] = *reinterpret_cast<const uintx4*>(xt + (long)sel_src[r] * C + ch * VE);
-        dst_off[u] = r * (unsigned)C + ch * VE;
-        if (kScale) sc[u] = sel_scale[r];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const unsigned i = i0 + u * kPackThreads;
-      if (i < work) {
-        uintx4 o = v[u];
-        if (kScale) {
-          if constexpr (sizeof(T) == 2) {
-            floatx8 f = bf16x8_to_float(__builtin_bit_cast(bf16x8, o));
-#pragma unroll
-            for (int e = 0; e < 8; ++e) f[e] *= sc[u];
-            o = __builtin_bit_cast(uintx4, float_to_bf16x8(f));
-          } else {
-            o = __builtin_bit_cast(uintx4, __builtin_bit_cast(floatx4, o) * sc[u]);
-          }
-        }
-        *reinterpret_cast<uintx4*>(pt + dst_off[u]) = o;
-      }
-    }
-  }
+  // 4. copy the survivors' rows.  kPair: the rows of x go to packed as they are, and the rows
+  //    of a second tensor x2 (width C2) of the same tokens, multiplied by Sigmoid(s) when scores
+  //    are given, go to packed2, in the same launch (one copy after the other: one list of chunks
+  //    over both tensors, with all loads in flight together, measured slower, 13.6 against 12.3 us).
+  if (packed != nullptr)
+    copy_selected_rows<T, kScale && !kPair>(x + img0 * (long)C, packed + (long)base * C, C, nsel, sel_src, sel_scale, tid);
+  if (kPair)
+    copy_selected_rows<T, kScale>(x2 + img0 * (long)C2, packed2 + (long)base * C2, C2, nsel, sel_src, sel_scale, tid);
 }
 
 // y[i] = base[i] (+ src[inv[i]]) or src[inv[i]] or 0.  A block owns `rpb` consecutive output
@@ -335,9 +349,10 @@ static int pack_common(const char* fn, const void* x, const uint8_t* mask, const
   const dim3 grid((unsigned)((long)B * tpi)), block(kPackThreads);
   hipStream_t st = as_stream(stream);
 #define SPA_PACK_LAUNCH(T, S, SH)                                                                        \
-  hipLaunchKernelGGL((pack_kernel<T, S, SH>), grid, block, 0, st, static_cast<const T*>(x), mask, counts, \
+  hipLaunchKernelGGL((pack_kernel<T, S, SH, false>), grid, block, 0, st, static_cast<const T*>(x), mask, counts, \
                      gate_scores, B, N, C, tile, tpi, container_len, shift, static_cast<T*>(packed),     \
-                     cu_seqlens, gather_idx, inv_pos, total)
+                     cu_seqlens, gather_idx, inv_pos, total, static_cast<const T*>(nullptr), 0,          \
+                     static_cast<T*>(nullptr))
 #define SPA_PACK_SCALE(T, SH)                                                                            \
   do {                                                                                                   \
     if (gate_scores) SPA_PACK_LAUNCH(T, true, SH); else SPA_PACK_LAUNCH(T, false, SH);                   \
@@ -358,6 +373,35 @@ extern "C" int spa_pack(const void* x, const uint8_t* mask, const int32_t* count
                         int32_t* total, void* stream) {
   return pack_common("spa_pack", x, mask, counts, gate_scores, B, N, C, dtype, container_len, Shift{1, 1, 0, 0},
                      false, packed, cu_seqlens, gather_idx, inv_pos, total, stream);
+}
+
+extern "C" int spa_pack_pair(const void* x, int C, const void* x2, int C2, const uint8_t* mask, const int32_t* counts,
+                             const float* gate_scores, int B, int N, int dtype, void* packed, void* packed2,
+                             int32_t* cu_seqlens, int32_t* gather_idx, int32_t* inv_pos, int32_t* total,
+                             void* stream) {
+  const char* fn = "spa_pack_pair";
+  SPA_REQUIRE(mask && x && x2 && packed && packed2, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+  if (int rc = check_rows(fn, B, N, C, dtype)) return rc;
+  if (int rc = check_rows(fn, B, N, C2, dtype)) return rc;
+  SPA_REQUIRE(aligned16(x) && aligned16(packed) && aligned16(x2) && aligned16(packed2), SPA_ERR_INVALID_ARG,
+              "%s: buffers not 16-byte aligned", fn);
+  const int tile = pick_tile(B, N, counts != nullptr);
+  const int tpi = (N + tile - 1) / tile;
+  SPA_REQUIRE((long)B * tpi < 2147483647L, SPA_ERR_INVALID_ARG, "%s: too many tiles", fn);
+  const dim3 grid((unsigned)((long)B * tpi)), block(kPackThreads);
+  hipStream_t st = as_stream(stream);
+  const Shift shift{1, 1, 0, 0};
+#define SPA_PACK_PAIR(T, S)                                                                                    \
+  hipLaunchKernelGGL((pack_kernel<T, S, false, true>), grid, block, 0, st, static_cast<const T*>(x), mask, counts, \
+                     gate_scores, B, N, C, tile, tpi, 0, shift, static_cast<T*>(packed), cu_seqlens, gather_idx, \
+                     inv_pos, total, static_cast<const T*>(x2), C2, static_cast<T*>(packed2))
+  if (dtype == SPA_F32) {
+    if (gate_scores) SPA_PACK_PAIR(float, true); else SPA_PACK_PAIR(float, false);
+  } else {
+    if (gate_scores) SPA_PACK_PAIR(__bf16, true); else SPA_PACK_PAIR(__bf16, false);
+  }
+#undef SPA_PACK_PAIR
+  return check_launch(fn);
 }
 
 extern "C" int spa_pack_shifted(const void* x, const uint8_t* mask, const int32_t* counts,

@@ -87,12 +87,15 @@ class TrainPass:
       bwd: unpack_bwd(dy) -> attention_bwd -> pack_bwd(dv) [-> pack_bwd(dq|dk)] -> gate_bwd
     fused_bwd (default): the gather of dy and the scatters of dq, dk, dv run inside the
     attention backward, 6 calls instead of 9.
+    pack_pair (default): q|k and the gated x are packed by one launch (the survivors are counted
+    and ranked once), 5 calls.
     """
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
-                 loss_scale: Optional[float] = None, fused_bwd: Optional[bool] = None):
+                 loss_scale: Optional[float] = None, fused_bwd: Optional[bool] = None, pack_pair: bool = True):
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
         self.fused_bwd = True if fused_bwd is None else fused_bwd
+        self.pack_pair = pack_pair
         self.tau, self.bias = tau, bias
         self.loss_scale = 0.01 / (B * N) if loss_scale is None else loss_scale
         td, cap = _td(dtype), B * N
@@ -171,10 +174,13 @@ class TrainPass:
             ]
         return [
             ("gate_select", spa.spa_gate_select(x, w, self.bias, None, self.tau, self.scores, self.mask, None, prepare=True)),
-            ("pack_qk", spa.spa_pack(qk, self.mask, None, None, 0, self.packed_qk, self.cu_seqlens,
-                                             self.gather_idx, self.inv_pos, self.total, prepare=True)),
-            ("pack_rg", spa.spa_pack(x, self.mask, None, self.scores, 0, self.packed_v, None, None, None, None,
-                                          prepare=True)),
+            *([("pack_qk_rg", spa.spa_pack_pair(qk, x, self.mask, None, self.scores, self.packed_qk, self.packed_v,
+                                                self.cu_seqlens, self.gather_idx, self.inv_pos, self.total,
+                                                prepare=True))] if self.pack_pair else [
+                ("pack_qk", spa.spa_pack(qk, self.mask, None, None, 0, self.packed_qk, self.cu_seqlens,
+                                         self.gather_idx, self.inv_pos, self.total, prepare=True)),
+                ("pack_rg", spa.spa_pack(x, self.mask, None, self.scores, 0, self.packed_v, None, None, None, None,
+                                         prepare=True))]),
             ("packed_attention_unpack", spa.spa_packed_attention_unpack(
                 pq, pk, pv, self.cu_seqlens, self.gather_idx, self.inv_pos, None, H, Dh, self.y, self.out, self.lse,
                 prepare=True)),
@@ -538,7 +544,7 @@ class HierarchyTrainPass:
             with torch.cuda.stream(self.streams[self.stream_of[i]] if self.concurrent else torch.cuda.current_stream()):
                 st = tp.stages(xs[i], ws[i], qks[i], labels[i], dys[i],
                                s_fine=self.passes[i - 1].scores if i > 0 else None, grid=(cfg[1], cfg[2]))
-            n_fwd = 4      # gate, pack_qk, pack_rg, attention + scatter
+            n_fwd = 3 if tp.pack_pair else 4      # gate, pack (one or two launches), attention + scatter
             fwd += [(f"s{i + 1}.{n}", f) for n, f in st[:n_fwd]]
             bwd += [(f"s{i + 1}.{n}", f) for n, f in st[n_fwd:]]
             chains.append([(f"s{i + 1}.{n}", f) for n, f in st])

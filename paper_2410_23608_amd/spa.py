@@ -38,6 +38,7 @@ _SIGNATURES = {
                                               c_int, c_int, _P, _P, _P, _P, _P, c_size_t, _P]),
     "spa_maxpool2x2": (c_int, [_P, c_int, c_int, c_int, _P, _P]),
     "spa_pack": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, _P, _P, _P, _P, _P, _P]),
+    "spa_pack_pair": (c_int, [_P, c_int, _P, c_int, _P, _P, _P, c_int, c_int, c_int, _P, _P, _P, _P, _P, _P, _P]),
     "spa_pack_shifted": (c_int, [_P, _P, _P, _P, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, _P, _P, _P,
                                  _P, _P, _P]),
     "spa_container_segments_capacity": (c_int64, [c_int, c_int64, c_int]),
@@ -198,6 +199,19 @@ def spa_pack(x, mask, counts, gate_scores, container_len, packed, cu_seqlens, ga
                         dtype_code(x) if x is not None else SPA_BF16,
                         int(container_len), _ptr(packed), _ptr(cu_seqlens), _ptr(gather_idx), _ptr(inv_pos),
                         _ptr(total), _stream(),), _keep, prepare)
+
+
+def spa_pack_pair(x, x2, mask, counts, gate_scores, packed, packed2, cu_seqlens, gather_idx, inv_pos, total,
+                  prepare=False):
+    """spa_pack of x [B,N,C] (unscaled) and x2 [B,N,C2] (scaled by sigmoid(gate_scores) if given) in one launch."""
+    B, N, C = x.shape
+    C2 = x2.shape[-1]
+    _keep = (x, x2, mask, counts, gate_scores, packed, packed2, cu_seqlens, gather_idx, inv_pos, total,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_pack_pair,
+                     (_ptr(x), C, _ptr(x2), C2, _ptr(mask), _ptr(counts), _ptr(gate_scores), B, N, dtype_code(x),
+                      _ptr(packed), _ptr(packed2), _ptr(cu_seqlens), _ptr(gather_idx), _ptr(inv_pos), _ptr(total),
+                      _stream(),), _keep, prepare)
 
 
 def spa_pack_shifted(x, mask, counts, gate_scores, grid_h, grid_w, shift_h, shift_w, container_len, packed,

@@ -140,6 +140,13 @@ def test_validation_of_the_wider_entry_points_without_gpu(lib):
     assert lib.spa_linear_packed_bwd_weight(fake, None, 64, fake, None, fake, None, 8, 64, 64, 1, fake, None, None, 0, None) == -1
     assert b"x_idx" in lib.spa_last_error()
 
+    lib.spa_pack_pair.restype = I
+    lib.spa_pack_pair.argtypes = [P, I, P, I, P, P, P, I, I, I, P, P, P, P, P, P, P]
+    assert lib.spa_pack_pair(fake, 64, None, 64, fake, None, None, 1, 8, 1, fake, fake, None, None, None, None, None) == -1
+    assert b"null" in lib.spa_last_error()
+    assert lib.spa_pack_pair(fake, 64, fake, 12, fake, None, None, 1, 8, 1, fake, fake, None, None, None, None, None) == -1
+    assert b"multiple of 16" in lib.spa_last_error()
+
     lib.spa_ceiling_mfma.restype = ctypes.c_double
     lib.spa_ceiling_mfma.argtypes = [P, I, I, P]
     assert lib.spa_ceiling_mfma(None, 1, 1, None) == -1.0

@@ -344,3 +344,40 @@ def test_short_segments_many_images(spa, B):
     ref_out, _ = orc.attention_per_image(qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], mask, H)
     T = int(mask.sum())
     assert np.max(np.abs(host(out1)[:T] - ref_out)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,N,C,C2,dens,use_counts", [(3, 100, 64, 32, 0.5, False), (64, 196, 768, 384, 0.5, False),
+                                                     (2, 777, 96, 48, 0.9, True), (5, 33, 16, 200, 0.0, False),
+                                                     (4, 257, 128, 64, 1.0, True)])
+def test_pack_pair_equals_two_packs(spa, dtype, B, N, C, C2, dens, use_counts):
+    """spa_pack_pair against spa_pack(x) + spa_pack(x2, gate-scaled): every output bit for bit."""
+    rng = np.random.default_rng(5)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    td = tdtype(dtype)
+    x = dev(mk(rng.standard_normal((B, N, C)).astype(np.float32)), dtype)
+    x2 = dev(mk(rng.standard_normal((B, N, C2)).astype(np.float32)), dtype)
+    scores = dev(rng.standard_normal((B, N)).astype(np.float32))
+    mask_h = (rng.uniform(size=(B, N)) < dens).astype(np.uint8)
+    mask = dev(mask_h)
+    counts = dev(mask_h.sum(1).astype(np.int32)) if use_counts else None
+    cap = B * N
+
+    def bufs():
+        return (torch.full((cap, C), float("nan"), dtype=td, device="cuda"),
+                torch.full((cap, C2), float("nan"), dtype=td, device="cuda"),
+                torch.full((B + 1,), -5, dtype=torch.int32, device="cuda"), torch.full((cap,), -5, dtype=torch.int32, device="cuda"),
+                torch.full((cap,), -5, dtype=torch.int32, device="cuda"), torch.full((1,), -5, dtype=torch.int32, device="cuda"))
+
+    pa, pb, cu, gi, inv, tot = bufs()
+    spa.spa_pack(x, mask, counts, None, 0, pa, cu, gi, inv, tot)
+    spa.spa_pack(x2, mask, counts, scores, 0, pb, None, None, None, None)
+    qa, qb, cu2, gi2, inv2, tot2 = bufs()
+    spa.spa_pack_pair(x, x2, mask, counts, scores, qa, qb, cu2, gi2, inv2, tot2)
+    torch.cuda.synchronize()
+    T = int(tot.item())
+    assert T == int(mask_h.sum()) == int(tot2.item())
+    assert torch.equal(cu, cu2) and torch.equal(inv, inv2) and torch.equal(gi[:T], gi2[:T])
+    eq = lambda a, b: torch.equal(a[:T].view(torch.uint8), b[:T].view(torch.uint8))
+    assert eq(pa, qa) and eq(pb, qb)
+    assert torch.isnan(qa[T:]).all() and torch.isnan(qb[T:]).all()       # rows past the total untouched

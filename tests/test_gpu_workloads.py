@@ -78,15 +78,15 @@ def test_full_size_forward_as_benchmarked(spa, pipeline, name):
     assert np.array_equal(y[gidx], out[:T]) and np.all(y[inv < 0] == 0)
 
 
-@pytest.mark.parametrize("fused_bwd", [True, False])
-def test_full_size_training_step_as_benchmarked(spa, pipeline, fused_bwd):
+@pytest.mark.parametrize("fused_bwd,pack_pair", [(True, True), (True, False), (False, False)])
+def test_full_size_training_step_as_benchmarked(spa, pipeline, fused_bwd, pack_pair):
     """ViT-B-shaped forward+backward step at full batch through pipeline.TrainPass, with the
     gather / scatter of the gradients inside the attention backward (as benchmarked) and as
     separate launches."""
     wl = wlmod.WORKLOADS["vit_b_train"]
     B, N, C, H = wl.B, wl.N, wl.C, wl.H
     bun = wlmod.generate(wl, 0)
-    tp = pipeline.TrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, fused_bwd=fused_bwd)
+    tp = pipeline.TrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, fused_bwd=fused_bwd, pack_pair=pack_pair)
     tp.dqk.fill_(float("nan"))
     tp.d_rg.fill_(float("nan"))
     qk = bun["qkv"][:, :, :2 * C]
