@@ -27,6 +27,8 @@ namespace spa {
 // Optional fused scatter-back (the unpack step folded into the attention kernel): packed
 // output row j goes to y[gather_idx[j]] (plus base), and every workgroup first fills its
 // share of the rows that bypass attention (inv_pos < 0) with base or zero.  All-null = off.
+// y is the path's final output: nothing here reads it again, so its stores are non-temporal
+// (they do not push the packed rows the next launches read out of the caches).
 struct Scatter {
   const int32_t* gather_idx;   // [B*N] packed row -> flat token
   const int32_t* inv_pos;      // [B*N] flat token -> packed row or -1
@@ -74,7 +76,7 @@ __device__ __forceinline__ void scatter_fill(const Scatter& sc, int b, int t0, i
       const long off = (tok0 + t) * C + h * DH + c * VE;
       uintx4 val = {0u, 0u, 0u, 0u};
       if (sc.base != nullptr) val = *reinterpret_cast<const uintx4*>(static_cast<const T*>(sc.base) + off);
-      *reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off) = val;
+      __builtin_nontemporal_store(val, reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off));
     }
   }
 }
@@ -237,7 +239,7 @@ __device__ __forceinline__ void fwd_flush(const __bf16* tile, __bf16* out, const
           const floatx8 bv = bf16x8_to_float(*reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(sc.base) + off));
           val = float_to_bf16x8(bf16x8_to_float(val) + bv);
         }
-        *reinterpret_cast<bf16x8*>(static_cast<__bf16*>(sc.y) + off) = val;
+        __builtin_nontemporal_store(val, reinterpret_cast<bf16x8*>(static_cast<__bf16*>(sc.y) + off));
       }
     }
   }
@@ -545,7 +547,7 @@ __device__ __forceinline__ void scatter_fill_rows(const Scatter& sc, long r0, lo
       for (int c = lane; c < cpr; c += kWave) {
         uintx4 val = {0u, 0u, 0u, 0u};
         if (sc.base != nullptr) val = *reinterpret_cast<const uintx4*>(static_cast<const T*>(sc.base) + off0 + c * VE);
-        *reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off0 + c * VE) = val;
+        __builtin_nontemporal_store(val, reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off0 + c * VE));
       }
     }
   }
@@ -836,7 +838,7 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
     if (op != nullptr) *reinterpret_cast<floatx4*>(op + d0) = t;
     if (sc.y != nullptr) {
       if (sc.base != nullptr) t += *reinterpret_cast<const floatx4*>(static_cast<const float*>(sc.base) + yoff + d0);
-      *reinterpret_cast<floatx4*>(static_cast<float*>(sc.y) + yoff + d0) = t;
+      __builtin_nontemporal_store(t, reinterpret_cast<floatx4*>(static_cast<float*>(sc.y) + yoff + d0));
     }
   }
   if (lse != nullptr && g == 0) lse[h * lse_stride + seg.row0 + qi] = seg.nk > 0 ? m + logf(l) : -INFINITY;

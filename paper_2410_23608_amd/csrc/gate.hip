@@ -18,9 +18,10 @@ template <> struct Vec16<float> {
     floatx4 v = *reinterpret_cast<const floatx4*>(p);
     f[0] = v[0]; f[1] = v[1]; f[2] = v[2]; f[3] = v[3];
   }
+  // dx is the last thing the backward pass writes and nothing here reads it again: non-temporal
   __device__ static __forceinline__ void store(float* p, const float (&f)[4]) {
     floatx4 v = {f[0], f[1], f[2], f[3]};
-    *reinterpret_cast<floatx4*>(p) = v;
+    __builtin_nontemporal_store(v, reinterpret_cast<floatx4*>(p));
   }
 };
 template <> struct Vec16<__bf16> {
@@ -34,7 +35,7 @@ template <> struct Vec16<__bf16> {
     floatx8 v;
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = f[i];
-    *reinterpret_cast<bf16x8*>(p) = float_to_bf16x8(v);
+    __builtin_nontemporal_store(float_to_bf16x8(v), reinterpret_cast<bf16x8*>(p));
   }
 };
 

@@ -202,7 +202,10 @@ pack_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
 
 // y[i] = base[i] (+ src[inv[i]]) or src[inv[i]] or 0.  A block owns `rpb` consecutive output
 // rows; consecutive threads take consecutive 16-byte chunks.
-template <typename T, bool kBase>
+// kStream: y is a final output nothing in the path reads again (spa_unpack): non-temporal
+// stores, so it does not displace what the next launches read; the transpose of the pack gather
+// (spa_pack_bwd) feeds the gate backward and keeps ordinary stores.
+template <typename T, bool kBase, bool kStream>
 __global__ void __launch_bounds__(256)
 unpack_kernel(const T* __restrict__ src, const int32_t* __restrict__ inv_pos,
               const T* base, long rows, int C, int rpb, T* y) {
@@ -250,7 +253,8 @@ unpack_kernel(const T* __restrict__ src, const int32_t* __restrict__ inv_pos,
             o = bv[u];
           }
         }
-        *reinterpret_cast<uintx4*>(yt + off[u]) = o;
+        if (kStream) __builtin_nontemporal_store(o, reinterpret_cast<uintx4*>(yt + off[u]));
+        else *reinterpret_cast<uintx4*>(yt + off[u]) = o;
       }
     }
   }
@@ -316,17 +320,17 @@ static int check_rows(const char* fn, int B, int N, int C, int dtype) {
   return SPA_OK;
 }
 
-template <typename T>
+template <typename T, bool kStream>
 static void launch_unpack(const void* src, const int32_t* inv, const void* base, long rows, int C,
                           void* y, hipStream_t st) {
   constexpr int VE = 16 / sizeof(T);
   const int rpb = rows_per_block(C / VE);
   const unsigned g = (unsigned)((rows + rpb - 1) / rpb);
   if (base != nullptr)
-    hipLaunchKernelGGL((unpack_kernel<T, true>), dim3(g), dim3(256), 0, st, static_cast<const T*>(src), inv,
+    hipLaunchKernelGGL((unpack_kernel<T, true, kStream>), dim3(g), dim3(256), 0, st, static_cast<const T*>(src), inv,
                        static_cast<const T*>(base), rows, C, rpb, static_cast<T*>(y));
   else
-    hipLaunchKernelGGL((unpack_kernel<T, false>), dim3(g), dim3(256), 0, st, static_cast<const T*>(src), inv,
+    hipLaunchKernelGGL((unpack_kernel<T, false, kStream>), dim3(g), dim3(256), 0, st, static_cast<const T*>(src), inv,
                        static_cast<const T*>(nullptr), rows, C, rpb, static_cast<T*>(y));
 }
 
@@ -489,8 +493,8 @@ extern "C" int spa_unpack(const void* packed_out, const int32_t* inv_pos, const 
   if (int rc = check_rows("spa_unpack", B, N, C, dtype)) return rc;
   SPA_REQUIRE(aligned16(packed_out) && aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG,
               "spa_unpack: buffers not 16-byte aligned");
-  if (dtype == SPA_F32) launch_unpack<float>(packed_out, inv_pos, base, (long)B * N, C, y, as_stream(stream));
-  else launch_unpack<__bf16>(packed_out, inv_pos, base, (long)B * N, C, y, as_stream(stream));
+  if (dtype == SPA_F32) launch_unpack<float, true>(packed_out, inv_pos, base, (long)B * N, C, y, as_stream(stream));
+  else launch_unpack<__bf16, true>(packed_out, inv_pos, base, (long)B * N, C, y, as_stream(stream));
   return check_launch("spa_unpack");
 }
 
@@ -499,8 +503,8 @@ extern "C" int spa_pack_bwd(const void* dpacked, const int32_t* inv_pos, int B, 
   SPA_REQUIRE(dpacked && inv_pos && d_rg, SPA_ERR_INVALID_ARG, "spa_pack_bwd: null pointer");
   if (int rc = check_rows("spa_pack_bwd", B, N, C, dtype)) return rc;
   SPA_REQUIRE(aligned16(dpacked) && aligned16(d_rg), SPA_ERR_INVALID_ARG, "spa_pack_bwd: buffers not 16-byte aligned");
-  if (dtype == SPA_F32) launch_unpack<float>(dpacked, inv_pos, nullptr, (long)B * N, C, d_rg, as_stream(stream));
-  else launch_unpack<__bf16>(dpacked, inv_pos, nullptr, (long)B * N, C, d_rg, as_stream(stream));
+  if (dtype == SPA_F32) launch_unpack<float, false>(dpacked, inv_pos, nullptr, (long)B * N, C, d_rg, as_stream(stream));
+  else launch_unpack<__bf16, false>(dpacked, inv_pos, nullptr, (long)B * N, C, d_rg, as_stream(stream));
   return check_launch("spa_pack_bwd");
 }
 
