@@ -376,7 +376,13 @@ def main():
         "roofline": roofline, "ceilings": ceil_, "kernels": kernels,
     }
 
-    if not args.no_extras:
+    # The extras (graph replay, padded baseline, training steps, projections, containers, hierarchy)
+    # are measured on the bf16 workloads only.  `--workload tiny` (fp32) with the extras ended in a
+    # GPU memory fault the one time that combination was run; its cause has not been found, so that
+    # combination stays switched off (every fp32 kernel passes its parity tests one by one).
+    if not args.no_extras and wl.dtype != "bf16":
+        result["extras"] = "not run for the fp32 workload"
+    if not args.no_extras and wl.dtype == "bf16":
         # the hot path as its four calls (gate_select, pack, packed_attention, unpack), the last two NOT
         # fused: warm back-to-back launch times and the roofline fraction of each kernel on its own
         fp4 = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, fused_unpack=False)
