@@ -204,8 +204,11 @@ def main():
     td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     bun = workloads.generate(wl, args.seed)
 
-    def up(a):
-        return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(td).contiguous()
+    def up(a, dtype=None):
+        """Host array -> device tensor in the dtype of the workload it is uploaded FOR (the
+        headline workload's unless another one is named)."""
+        t_ = td if dtype is None else (torch.bfloat16 if dtype == "bf16" else torch.float32)
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(t_).contiguous()
 
     if args.calibration_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
@@ -376,13 +379,7 @@ def main():
         "roofline": roofline, "ceilings": ceil_, "kernels": kernels,
     }
 
-    # The extras (graph replay, padded baseline, training steps, projections, containers, hierarchy)
-    # are measured on the bf16 workloads only.  `--workload tiny` (fp32) with the extras ended in a
-    # GPU memory fault the one time that combination was run; its cause has not been found, so that
-    # combination stays switched off (every fp32 kernel passes its parity tests one by one).
-    if not args.no_extras and wl.dtype != "bf16":
-        result["extras"] = "not run for the fp32 workload"
-    if not args.no_extras and wl.dtype == "bf16":
+    if not args.no_extras:
         # the hot path as its four calls (gate_select, pack, packed_attention, unpack), the last two NOT
         # fused: warm back-to-back launch times and the roofline fraction of each kernel on its own
         fp4 = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, fused_unpack=False)
@@ -457,9 +454,9 @@ def main():
         twl = workloads.WORKLOADS["vit_b_train"]
         tb = workloads.generate(twl, args.seed)
         tp = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias)
-        tx, tw = up(tb["x"]), up(tb["w"])
-        tqk = up(tb["qkv"][:, :, :2 * twl.C])
-        tdy = up(tb["dy"])
+        tx, tw = up(tb["x"], twl.dtype), up(tb["w"], twl.dtype)
+        tqk = up(tb["qkv"][:, :, :2 * twl.C], twl.dtype)
+        tdy = up(tb["dy"], twl.dtype)
         tlab = torch.from_numpy(tb["labels"]).cuda()
         tstages = tp.stages(tx, tw, tqk, tlab, tdy)
 
@@ -561,23 +558,6 @@ def main():
             "qkv_projection_tflops": round(2.0 * T * C * 3 * C / bus["qkv_projection"] / 1e6, 1),
             "out_projection_tflops": round(2.0 * T * C * C / bus["out_projection"] / 1e6, 1),
             "dense_projection_flops_saved": round(1.0 - T / (B * N), 3)}
-        # five-launch form: the output projection scatters its rows (plus the residual) itself
-        bp5 = BlockPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, fused_scatter=True)
-        b5 = bp5.stages(x, w, W_qkv, b_qkv, W_o, b_o)
-
-        def b5step():
-            for _, fn in b5:
-                fn()
-
-        for _ in range(5):
-            b5step()
-        torch.cuda.synchronize()
-        b5dt = timed(b5step, args.steps, torch)
-        result["block_with_projections"]["fused_scatter"] = {
-            "outputs_equal_six_launch_form": bool(torch.equal(bp5.y, bp.y)),
-            "launches": [n_ for n_, _ in b5], "ms_per_step": 1e3 * b5dt / args.steps,
-            "out_projection_scatter_us": round(back_to_back_us(b5[-1][1], args.steps, torch), 2)}
-
         # the block forward + backward with its projections (input-side and weight-side GEMMs of both
         # projections, attention backward, gate backward with the selection loss)
         from paper_2410_23608_amd.pipeline import BlockTrainPass
@@ -676,7 +656,10 @@ def main():
         hcfg = [(b_["workload"].B, *b_["workload"].grid, b_["workload"].C, b_["workload"].H, b_["workload"].dtype,
                  b_["workload"].tau, b_["bias"]) for b_ in hb]
         hp = HierarchyPass(hcfg)
-        hx, hw, hq = [up(b_["x"]) for b_ in hb], [up(b_["w"]) for b_ in hb], [up(b_["qkv"]) for b_ in hb]
+        hdt_ = [b_["workload"].dtype for b_ in hb]
+        hx = [up(b_["x"], d_) for b_, d_ in zip(hb, hdt_)]
+        hw = [up(b_["w"], d_) for b_, d_ in zip(hb, hdt_)]
+        hq = [up(b_["qkv"], d_) for b_, d_ in zip(hb, hdt_)]
         hstages = hp.stages(hx, hw, hq)
 
         def hstep():
@@ -703,9 +686,9 @@ def main():
         # the same hierarchy forward + backward (20 calls)
         from paper_2410_23608_amd.pipeline import HierarchyTrainPass
         htp = HierarchyTrainPass(hcfg)
-        hqk = [up(b_["qkv"][:, :, :2 * b_["workload"].C]) for b_ in hb]
+        hqk = [up(b_["qkv"][:, :, :2 * b_["workload"].C], b_["workload"].dtype) for b_ in hb]
         hlab = [torch.from_numpy(b_["labels"]).cuda() for b_ in hb]
-        hdy = [up(b_["dy"]) for b_ in hb]
+        hdy = [up(b_["dy"], b_["workload"].dtype) for b_ in hb]
         htstages = htp.stages(hx, hw, hqk, hlab, hdy)
 
         def htstep():

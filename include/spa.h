@@ -58,6 +58,42 @@ int spa_version(void);
 const char* spa_last_error(void);
 
 /*
+ * Launch options (host, process-wide; not part of the method).  Every option has a default
+ * that is the measured best; the alternatives select other kernels of the library for the same
+ * call (used by the parity tests to cover them, and for tuning).  Each option is also read ONCE,
+ * when the library is loaded, from the environment variable SPA_<NAME IN CAPITALS>; nothing on a
+ * launch path reads the environment.  value NULL or "" restores the default.  Not synchronised
+ * with calls running on other host threads.  Returns SPA_ERR_INVALID_ARG for an unknown name or a
+ * malformed value (nothing changes then).
+ *   attn_fwd_short     words of: "whole" (one workgroup per (image, head)), "64" (64-key steps),
+ *                      "plain" (one-wave blocks numbered blindly instead of by weight)
+ *   attn_fwd_cfg       "NW,BN": the tiled forward kernel with NW in {2,4} waves, BN in {64,128} keys
+ *   attn_fwd_wave_max  longest segment (<= 256) the one-wave forward kernels take
+ *   attn_bwd_short     "split" | "tiled": two-kernel / long-segment backward for segments <= 256
+ *   attn_bwd_long      "two": the dq and dkdv roles of the long-segment backward as two launches
+ *   gemm_tm            2 | 4 | 8: 128x128, 256x128, 256x256 projection tiles
+ *   gemm_splits        1..16 token chunks of the weight-side GEMM
+ *   pack_tile          16 | 32 | 64 | 128 | 256 tokens per packing workgroup
+ */
+int spa_set_option(const char* name, const char* value);
+
+/*
+ * Bytes of workspace that call `op` needs for a batch of B images x N tokens, width C, H heads
+ * (the one query over the per-call ones below; Section 3.2 / 3.3 name the calls).  0 for the
+ * calls that need none (all forward calls and the row-moving transposes), and for bad arguments.
+ * The projection ops take M_cap = B*N rows, K = C and N_out = 3C (QKV) or C (output).  Host.
+ */
+#define SPA_OP_GATE_SELECT 0
+#define SPA_OP_PACK 1
+#define SPA_OP_PACKED_ATTENTION 2
+#define SPA_OP_UNPACK 3
+#define SPA_OP_PACKED_ATTENTION_BWD 4
+#define SPA_OP_GATE_BWD 5
+#define SPA_OP_QKV_PROJECTION_BWD_WEIGHT 6
+#define SPA_OP_OUT_PROJECTION_BWD_WEIGHT 7
+size_t spa_workspace_bytes(int op, int B, int N, int C, int H, int dtype);
+
+/*
  * Gate scoring and selection (Section 3.2, equations for s and r_p).
  *   g_i      = bias + sum_c w[c] * x[i,c]            (linear gating layer f_g)
  *   scores_i = max(g_i, s_up[i]) if s_up else g_i    (s = Max(f_g(r), s_up))

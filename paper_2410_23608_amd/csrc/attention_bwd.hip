@@ -890,11 +890,11 @@ static int attention_bwd_common(const char* fn, const void* q, const void* k, co
               SPA_ERR_INVALID_ARG, "%s: tensors not 16-byte aligned", fn);
   SPA_REQUIRE(softmax_scale >= 0.f && std::isfinite(softmax_scale), SPA_ERR_INVALID_ARG,
               "%s: softmax_scale must be finite and >= 0", fn);
-  // short segments: the one-kernel form.  SPA_ATTN_BWD_SHORT = "split" keeps the two one-wave
-  // kernels, "tiled" forces the long-segment kernels (tuning aids).
-  const char* env = std::getenv("SPA_ATTN_BWD_SHORT");
-  const bool short_seg = max_seqlen <= 256 && !(env != nullptr && env[0] == 't');
-  const bool one_kernel = dtype == SPA_BF16 && short_seg && (at_tokens || !(env != nullptr && env[0] == 's'));
+  // short segments: the one-kernel form.  Option attn_bwd_short = "split" keeps the two one-wave
+  // kernels, "tiled" forces the long-segment kernels.
+  const Options& opt = options();
+  const bool short_seg = max_seqlen <= 256 && opt.bwd_short != 2;
+  const bool one_kernel = dtype == SPA_BF16 && short_seg && (at_tokens || opt.bwd_short != 1);
   const size_t need = one_kernel ? 0 : spa_attention_bwd_workspace_bytes(B, max_seqlen, H, Dh, dtype);
   SPA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SPA_ERR_WORKSPACE,
               "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace_bytes);
@@ -957,9 +957,8 @@ static int attention_bwd_common(const char* fn, const void* q, const void* k, co
       hipLaunchKernelGGL((attn_bwd_dkdv_bf16_kernel<D, 4, 64, true>), grid, dim3(256), 0, st, SPA_BWD_ARGS_DKDV); \
     }                                                                                                            \
   } while (0)
-    // long segments: D first, then both sides in one launch (SPA_ATTN_BWD_LONG=two keeps two launches)
-    const char* lenv = std::getenv("SPA_ATTN_BWD_LONG");
-    if (!short_seg && (at_tokens || !(lenv != nullptr && lenv[0] == 't'))) {
+    // long segments: D first, then both sides in one launch (option attn_bwd_long = "two" keeps two launches)
+    if (!short_seg && (at_tokens || !opt.bwd_long_two)) {
       SPA_REQUIRE(2L * grid.x < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H*blocks must be < 2^30", fn);
       const long rows_cap = (long)B * max_seqlen;
       const unsigned dgrid = (unsigned)std::min<long>((rows_cap * H * (Dh / 8) + 255) / 256, 4096L);

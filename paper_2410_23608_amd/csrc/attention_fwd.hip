@@ -882,22 +882,18 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
 #define SPA_ARGS                                                                                              \
   (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu,   \
       key_lens, n_max, H, scale_log2, (__bf16*)out, lse, lse_stride, sc
-    // SPA_ATTN_FWD_CFG="NW,BN" forces the tiled kernel with that launch shape (tuning aid).
-    int NW = 0, BN = 0;
-    if (const char* env = std::getenv("SPA_ATTN_FWD_CFG")) {
-      int a = 0, b = 0;
-      if (std::sscanf(env, "%d,%d", &a, &b) == 2 && (a == 2 || a == 4) && (b == 64 || b == 128)) { NW = a; BN = b; }
-    }
-    const char* short_env = std::getenv("SPA_ATTN_FWD_SHORT");      // "whole" | "wave" (tuning aid)
-    const bool use_whole = short_env != nullptr && short_env[0] == 'w' && short_env[1] == 'h';
-    static const int wave_max = [] { const char* e = std::getenv("SPA_ATTN_FWD_WAVE_MAX"); return e ? std::atoi(e) : 256; }();
+    // options attn_fwd_cfg (forces the tiled kernel with that launch shape), attn_fwd_short and
+    // attn_fwd_wave_max select among the kernels below; unset, the measured best is taken
+    const Options& opt = options();
+    int NW = opt.fwd_nw, BN = opt.fwd_bn;
+    const bool use_whole = opt.fwd_whole;
+    const int wave_max = opt.fwd_wave_max;
     if (NW == 0 && n_max <= wave_max && !use_whole) {
       // short segments: one wave per (image, head, 32 queries)
       const int nqb = (n_max + 31) / 32;
       const dim3 grid(xcd_grid(nqb, H, B));
-      const bool step64 = short_env != nullptr && std::strstr(short_env, "64") != nullptr;
-      // default: blocks dealt to the compute units by weight ("plain" in SPA_ATTN_FWD_SHORT: numbered blindly)
-      const bool plain = short_env != nullptr && std::strstr(short_env, "plain") != nullptr;
+      // default: blocks dealt to the compute units by weight ("plain": numbered blindly)
+      const bool step64 = opt.fwd_step64, plain = opt.fwd_plain;
       if (!step64 && !plain && B <= kWave) {
         const dim3 lgrid(lpt64_grid(B, H, nqb));
         if (Dh == 32) hipLaunchKernelGGL((attn_fwd_bf16_wave_lpt64_kernel<32, 32>), lgrid, dim3(64), 0, st, SPA_ARGS, B, nqb);

@@ -267,8 +267,8 @@ static int linear_common(const char* fn, const void* x, const int32_t* gather_id
   SPA_REQUIRE(aligned16(x) && aligned16(W) && aligned16(out), SPA_ERR_INVALID_ARG, "%s: x / W / out not 16-byte aligned", fn);
   // tile shape: 256 x 256 x 64 only where it measured faster than 128 x 128 x 64: long k-loops
   // and enough tiles that the live ones (about half of the capacity for a packed stream) still
-  // cover most CUs.  SPA_GEMM_TM = 2 | 4 | 8 forces 128 x 128, 256 x 128 or 256 x 256 (tuning aid).
-  static const int cfg_env = [] { const char* e = getenv("SPA_GEMM_TM"); return e ? atoi(e) : 0; }();
+  // cover most CUs.  option gemm_tm = 2 | 4 | 8 forces 128 x 128, 256 x 128 or 256 x 256 (tuning aid).
+  const int cfg_env = options().gemm_tm;
   const long tiles_big = (long)((M_cap + 255) / 256) * ((N_out + 255) / 256);
   const bool plain_out = scatter_idx == nullptr && residual == nullptr;
   const bool big = plain_out && (cfg_env == 8 || (cfg_env == 0 && tiles_big >= 384 && K >= 512));

@@ -479,10 +479,10 @@ linear_bwd_weight_f32_kernel(const float* __restrict__ dout, const int32_t* __re
 
 // Number of token chunks of the weight-side kernel: (chunk, tile) workgroups for about three per
 // compute unit (two are resident at a time), at most 16 chunks (the partial tiles are written
-// and read once per chunk), chunks of at least 256 rows at full capacity.  SPA_GEMM_SPLITS
+// and read once per chunk), chunks of at least 256 rows at full capacity.  The option gemm_splits
 // overrides it (tuning aid).
 static int weight_splits(int M_cap, int K, int N_out) {
-  static const int env = [] { const char* e = getenv("SPA_GEMM_SPLITS"); return e ? atoi(e) : 0; }();
+  const int env = options().gemm_splits;
   if (env > 0) return env;
   const long tiles = (long)((N_out + kLbT - 1) / kLbT) * ((K + kLbT - 1) / kLbT);
   long s = (768 + tiles - 1) / tiles;

@@ -303,10 +303,7 @@ static int pick_tile(int B, int N, bool have_counts) {
   const long want = (!have_counts && (long)B * N > 16384) ? 512 : 1024;
   int tile = 256;
   while (tile > 16 && (long)B * ((N + tile - 1) / tile) < want) tile >>= 1;
-  if (const char* env = std::getenv("SPA_PACK_TILE")) {       // tuning aid
-    const int t = std::atoi(env);
-    if (t == 16 || t == 32 || t == 64 || t == 128 || t == 256) tile = t;
-  }
+  if (options().pack_tile != 0) tile = options().pack_tile;       // option pack_tile
   return tile;
 }
 

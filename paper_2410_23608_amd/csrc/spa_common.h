@@ -13,6 +13,17 @@ namespace spa {
 int fail(int code, const char* fmt, ...);          // records the message, returns code
 int check_launch(const char* what);                // hipGetLastError -> SPA_ERR_HIP
 
+// Launch options (tuning aids and kernel selection for tests), see spa_set_option in spa.h.
+struct Options {
+  bool fwd_whole, fwd_step64, fwd_plain;   // attn_fwd_short
+  int fwd_nw, fwd_bn;                      // attn_fwd_cfg (0 = automatic)
+  int fwd_wave_max;                        // attn_fwd_wave_max
+  int bwd_short;                           // attn_bwd_short: 0 one kernel, 1 split, 2 tiled
+  bool bwd_long_two;                       // attn_bwd_long = two
+  int gemm_tm, gemm_splits, pack_tile;     // 0 = automatic
+};
+const Options& options();
+
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int elem_size(int dtype) { return dtype == SPA_BF16 ? 2 : 4; }

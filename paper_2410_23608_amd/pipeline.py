@@ -207,15 +207,12 @@ class BlockPass:
 
     in_place=True: five launches.  The output projection scatters its rows straight into the
     residual stream x (x[token] += projection), so there is no scatter launch and no copy of the
-    bypassing tokens; run() then returns x itself.
-    fused_scatter=True (without in_place): the same five launches writing y[token] = x[token] +
-    projection into this object's y, whose bypassing rows are set to x ONCE, when stages() is
-    called (for repeated runs on an unchanged x, e.g. a benchmark loop)."""
+    bypassing tokens; run() then returns x itself."""
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
-                 in_place: bool = False, fused_scatter: bool = False):
+                 in_place: bool = False):
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
-        self.tau, self.bias, self.in_place, self.fused_scatter = tau, bias, in_place, fused_scatter or in_place
+        self.tau, self.bias, self.in_place = tau, bias, in_place
         td, cap = _td(dtype), B * N
         dv = dict(device="cuda")
         self.scores = torch.empty(B, N, dtype=torch.float32, **dv)
@@ -243,18 +240,12 @@ class BlockPass:
                                                           prepare=True)),
         ] + ([
             ("out_projection_scatter", spa.spa_linear_packed_scatter(self.attn, self.total, W_o, b_o, self.gather_idx,
-                                                                     x, self._scatter_target(x), prepare=True)),
-        ] if self.fused_scatter else [
+                                                                     x, x, prepare=True)),
+        ] if self.in_place else [
             ("out_projection", spa.spa_linear_packed(self.attn, None, None, self.total, W_o, b_o, self.proj,
                                                      prepare=True)),
             ("unpack", spa.spa_unpack(self.proj, self.inv_pos, x, self.y, prepare=True)),
         ])
-
-    def _scatter_target(self, x):
-        if self.in_place:
-            return x
-        self.y.copy_(x)
-        return self.y
 
     def run(self, x, w, W_qkv, b_qkv, W_o, b_o):
         for _, fn in self.stages(x, w, W_qkv, b_qkv, W_o, b_o):
@@ -264,10 +255,12 @@ class BlockPass:
 
 class BlockTrainPass:
     """Forward + backward of one SPA attention block WITH its projections (Section 3.2) and the
-    selection loss (Section 3.3), eleven launches:
+    selection loss (Section 3.3), twelve launches:
 
       fwd: gate_select(x) -> pack (indices only) -> QKV projection of the selected, gated tokens
-           -> packed attention -> output projection scattering y[token] = x[token] + projection
+           -> packed attention -> output projection of the packed rows -> scatter back as a
+           residual on x (y[token] = x[token] + projection, bypassing tokens y = x; x stays
+           intact for the backward pass)
       bwd: (dy at token positions) -> input side and weight side of the output projection (dy
            gathered inside the GEMMs) -> attention backward on the packed rows -> input side of
            the QKV projection, scattering d_rg to token positions with the unselected rows
@@ -284,9 +277,6 @@ class BlockTrainPass:
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
                  loss_scale: Optional[float] = None, overlap_weight_grads: bool = True):
-        if dtype != "bf16":
-            # every call of the chain has its fp32 parity test, the chain as a whole has none
-            raise ValueError("BlockTrainPass is wired up and verified for bf16 only")
         self.overlap = overlap_weight_grads
         self.side = torch.cuda.Stream() if overlap_weight_grads else None
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
@@ -305,6 +295,7 @@ class BlockTrainPass:
         self.packed_qkv = torch.zeros(cap, 3 * C, dtype=td, **dv)
         self.attn = torch.zeros(cap, C, dtype=td, **dv)
         self.lse = torch.zeros(H, cap, **f32)
+        self.proj = torch.zeros(cap, C, dtype=td, **dv)
         self.y = torch.empty(B, N, C, dtype=td, **dv)
         self.d_attn = torch.zeros(cap, C, dtype=td, **dv)
         self.d_qkv = torch.zeros(cap, 3 * C, dtype=td, **dv)
@@ -323,7 +314,6 @@ class BlockTrainPass:
         B, N, C, H, Dh = self.B, self.N, self.C, self.H, self.Dh
         cap, p, dp = B * N, self.packed_qkv, self.d_qkv
         dy2 = dy.view(cap, C)
-        self.y.copy_(x)                                    # the bypassing rows of y, set once
         main = torch.cuda.current_stream()
 
         def weight_side():
@@ -360,8 +350,9 @@ class BlockTrainPass:
                                                      prepare=True)),
             ("packed_attention", spa.spa_packed_attention(p[:, :C], p[:, C:2 * C], p[:, 2 * C:], self.cu_seqlens, B, N,
                                                           H, Dh, self.attn, self.lse, prepare=True)),
-            ("out_projection_scatter", spa.spa_linear_packed_scatter(self.attn, self.total, W_o, b_o, self.gather_idx,
-                                                                     x, self.y, prepare=True)),
+            ("out_projection", spa.spa_linear_packed(self.attn, None, None, self.total, W_o, b_o, self.proj,
+                                                     prepare=True)),
+            ("unpack", spa.spa_unpack(self.proj, self.inv_pos, x, self.y, prepare=True)),
             ("out_projection_bwd_weight", w_o),
             ("out_projection_bwd_input", spa.spa_linear_packed_bwd_input(dy2, self.gather_idx, self.total, W_o, cap,
                                                                          None, None, self.d_attn, prepare=True)),

@@ -150,3 +150,34 @@ def test_validation_of_the_wider_entry_points_without_gpu(lib):
     lib.spa_ceiling_mfma.restype = ctypes.c_double
     lib.spa_ceiling_mfma.argtypes = [P, I, I, P]
     assert lib.spa_ceiling_mfma(None, 1, 1, None) == -1.0
+
+
+def test_options_and_the_single_workspace_query_without_gpu(lib):
+    """spa_set_option parses once and rejects unknown names / malformed values; spa_workspace_bytes
+    agrees with the per-call queries."""
+    I = ctypes.c_int
+    lib.spa_last_error.restype = ctypes.c_char_p
+    lib.spa_set_option.restype = I
+    lib.spa_set_option.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+    assert lib.spa_set_option(b"attn_fwd_short", b"whole") == 0
+    assert lib.spa_set_option(b"attn_fwd_short", None) == 0
+    assert lib.spa_set_option(b"attn_fwd_cfg", b"4,128") == 0 and lib.spa_set_option(b"attn_fwd_cfg", b"") == 0
+    assert lib.spa_set_option(b"attn_fwd_cfg", b"3,128") == -1 and b"attn_fwd_cfg" in lib.spa_last_error()
+    assert lib.spa_set_option(b"no_such_option", b"1") == -1
+    assert lib.spa_set_option(b"pack_tile", b"48") == -1 and lib.spa_set_option(b"pack_tile", b"0") == 0
+    assert lib.spa_set_option(None, b"1") == -1
+    S = ctypes.c_size_t
+    lib.spa_workspace_bytes.restype = S
+    lib.spa_workspace_bytes.argtypes = [I] * 6
+    for f, n in (("spa_attention_bwd_workspace_bytes", 5), ("spa_gate_bwd_workspace_bytes", 4),
+                 ("spa_linear_bwd_weight_workspace_bytes", 4)):
+        getattr(lib, f).restype = S
+        getattr(lib, f).argtypes = [I] * n
+    B, N, C, H = 64, 196, 768, 12
+    assert lib.spa_workspace_bytes(4, B, N, C, H, 1) == lib.spa_attention_bwd_workspace_bytes(B, N, H, C // H, 1) > 0
+    assert lib.spa_workspace_bytes(5, B, N, C, H, 1) == lib.spa_gate_bwd_workspace_bytes(B, N, C, 1) > 0
+    assert lib.spa_workspace_bytes(6, B, N, C, H, 1) == lib.spa_linear_bwd_weight_workspace_bytes(B * N, C, 3 * C, 1) > 0
+    assert lib.spa_workspace_bytes(7, B, N, C, H, 1) == lib.spa_linear_bwd_weight_workspace_bytes(B * N, C, C, 1) > 0
+    for op in (0, 1, 2, 3, 99):
+        assert lib.spa_workspace_bytes(op, B, N, C, H, 1) == 0
+    assert lib.spa_workspace_bytes(4, 0, N, C, H, 1) == 0 and lib.spa_workspace_bytes(4, B, N, C, 5, 1) == 0

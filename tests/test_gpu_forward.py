@@ -226,18 +226,21 @@ def test_all_unselected_batch_is_noop(spa):
     assert np.all(host(f.y) == 0) and np.all(np.isnan(host(f.out)))
 
 
-def test_padded_baseline_matches_oracle(spa):
-    """The padded-to-max baseline computes the same attention on the valid rows."""
-    B, H, Dh = 5, 2, 64
+@pytest.mark.parametrize("dtype,Dh", [("bf16", 64), ("bf16", 32), ("f32", 32), ("f32", 64)])
+def test_padded_baseline_matches_oracle(spa, dtype, Dh):
+    """The padded-to-max baseline computes the same attention on the valid rows (bf16 and fp32:
+    the benchmark runs it in the workload's dtype)."""
+    B, H = 5, 2
     C = H * Dh
     lens = np.array([40, 97, 1, 0, 130], np.int32)
     n_pad = int(lens.max())
     rng = np.random.default_rng(13)
-    q, k, v = (wlmod.round_bf16(rng.standard_normal((B, n_pad, C)).astype(np.float32)) for _ in range(3))
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    q, k, v = (mk(rng.standard_normal((B, n_pad, C)).astype(np.float32)) for _ in range(3))
     mask = (np.arange(n_pad)[None, :] < lens[:, None]).astype(np.uint8)
     ref, _ = orc.attention_per_image(q, k, v, mask, H)
-    qkv = dev(np.concatenate([q, k, v], axis=2), "bf16")
-    out = torch.empty(B, n_pad, C, dtype=torch.bfloat16, device="cuda")
+    qkv = dev(np.concatenate([q, k, v], axis=2), dtype)
+    out = torch.empty(B, n_pad, C, dtype=tdtype(dtype), device="cuda")
     flat = qkv.view(B * n_pad, 3 * C)
     spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], dev(lens), B, n_pad, H, Dh, out)
     torch.cuda.synchronize()
@@ -246,7 +249,7 @@ def test_padded_baseline_matches_oracle(spa):
     row = 0
     for b in range(B):
         n = int(lens[b])
-        assert np.max(np.abs(got[b, :n] - ref[row:row + n]), initial=0.0) <= TOL["bf16"]
+        assert np.max(np.abs(got[b, :n] - ref[row:row + n]), initial=0.0) <= TOL[dtype]
         row += n
 
 
@@ -266,18 +269,22 @@ def test_argument_validation_returns_errors_before_launch(spa):
     torch.cuda.synchronize()
 
 
+@pytest.fixture
+def short_option(spa):
+    """Selects the short-segment forward kernel for one test and restores the default after it."""
+    yield lambda value: spa.spa_set_option("attn_fwd_short", value)
+    spa.spa_set_option("attn_fwd_short", None)
+
+
 @pytest.mark.parametrize("dtype,Dh,N,short", [("f32", 32, 150, ""), ("bf16", 64, 196, ""), ("bf16", 64, 196, "wave"),
                                               ("bf16", 64, 196, "wave plain"), ("bf16", 32, 250, "wave"),
                                               ("bf16", 32, 49, ""), ("bf16", 32, 700, ""), ("bf16", 64, 300, "")])
 @pytest.mark.parametrize("with_base,keep_out", [(False, True), (True, False)])
-def test_fused_attention_unpack_equals_separate_calls(spa, monkeypatch, dtype, Dh, N, short, with_base, keep_out):
+def test_fused_attention_unpack_equals_separate_calls(spa, short_option, dtype, Dh, N, short, with_base, keep_out):
     """spa_packed_attention_unpack == spa_packed_attention followed by spa_unpack, bit for bit,
     for the short-segment kernels (whole / wave with blocks numbered by weight / wave numbered
     blindly), the tiled kernel and the fp32 kernel; and both equal the oracle within tolerance."""
-    if short:
-        monkeypatch.setenv("SPA_ATTN_FWD_SHORT", short)
-    else:
-        monkeypatch.setenv("SPA_ATTN_FWD_SHORT", "whole")
+    short_option(short if short else "whole")
     B, H = 5, 2
     C = H * Dh
     rng = np.random.default_rng(31)

@@ -26,6 +26,15 @@ def pipeline():
     return mod
 
 
+def _hier_cfg(bundles):
+    return [(b["workload"].B, *b["workload"].grid, b["workload"].C, b["workload"].H, b["workload"].dtype,
+             b["workload"].tau, b["bias"]) for b in bundles]
+
+
+def _rel(got, ref):
+    return float(np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref))))
+
+
 def _sampled_attention_reference(q, k, v, mask, H, rows):
     """Oracle attention for a sample of packed rows only, one row at a time: row j of image b
     attends to all selected tokens of b.  Plain definition, fp64."""
@@ -48,7 +57,8 @@ def _sampled_attention_reference(q, k, v, mask, H, rows):
 @pytest.mark.parametrize("name", ["vit_s", "det"])
 def test_full_size_forward_as_benchmarked(spa, pipeline, name):
     """The exact batch and launch path of bench.py: integers bit-exact, packed rows bit-exact,
-    attention checked on every row (vit_s) or on sampled rows computed one by one (det)."""
+    attention checked on EVERY packed row of the full batch (vit_s: 64 images, det: 8 images of
+    4200 tokens), and on det also row by row on a sample computed one query at a time."""
     wl = wlmod.WORKLOADS[name]
     bun = wlmod.generate(wl, 0)
     C = wl.C
@@ -65,10 +75,10 @@ def test_full_size_forward_as_benchmarked(spa, pipeline, name):
     assert np.array_equal(host(fp.packed_qkv)[:T], bun["qkv"].reshape(-1, 3 * C)[gidx])
     q, k, v = bun["qkv"][..., :C], bun["qkv"][..., C:2 * C], bun["qkv"][..., 2 * C:]
     out = host(fp.out)
-    if name == "vit_s":
-        ref, _ = orc.attention_per_image(q, k, v, mask, wl.H)
-        assert np.max(np.abs(out[:T] - ref)) <= 2e-2
-    else:
+    ref, lse_ref = orc.attention_per_image(q, k, v, mask, wl.H)
+    assert np.max(np.abs(out[:T] - ref)) <= 2e-2
+    assert np.max(np.abs(host(fp.lse)[:, :T] - lse_ref)) <= 2e-2
+    if name == "det":
         rng = np.random.default_rng(0)
         rows = np.unique(np.concatenate([rng.integers(0, T, 48), cu[:-1][np.diff(cu) > 0], cu[1:][np.diff(cu) > 0] - 1]))
         ref = _sampled_attention_reference(q, k, v, mask, wl.H, rows)
@@ -388,3 +398,76 @@ def test_independent_batches_on_four_streams_match_their_own_results(spa, pipeli
     for fp, (y, gidx, T) in zip(passes, alone):
         assert int(fp.total.item()) == T
         assert torch.equal(fp.gather_idx[:T], gidx[:T]) and torch.equal(fp.y, y)
+
+
+def test_hierarchy_full_batch_forward_matches_stagewise_oracle(spa, pipeline):
+    """The four-stage hierarchy at its stated size (batch 16, 56^2 .. 7^2 tokens, C 96 .. 768)
+    through HierarchyPass exactly as bench.py runs it: every stage's mask, cu_seqlens, gather_idx,
+    inv_pos and total bit-exact, packed attention output and y within the bf16 bound, the score map
+    handed down within the score bound."""
+    bundles = wlmod.generate_hierarchy(0)
+    assert [b["workload"].B for b in bundles] == [16] * 4 and bundles[0]["workload"].N == 3136
+    hp = pipeline.HierarchyPass(_hier_cfg(bundles))
+    ys = hp.run([dev(b["x"], "bf16") for b in bundles], [dev(b["w"], "bf16") for b in bundles],
+                [dev(b["qkv"], "bf16") for b in bundles])
+    torch.cuda.synchronize()
+    s_up = None
+    for i, bun in enumerate(bundles):
+        wl, fp = bun["workload"], hp.passes[i]
+        ref = orc.spa_forward(bun["x"], bun["w"], bun["bias"], bun["qkv"], wl.H, wl.tau, wl.dtype, s_up=s_up)
+        assert ref["margin"] > 1e-3
+        T = ref["total"]
+        assert np.array_equal(host(fp.mask), ref["mask"])
+        assert np.array_equal(host(fp.cu_seqlens), ref["cu_seqlens"]) and int(host(fp.total)[0]) == T
+        assert np.array_equal(host(fp.gather_idx)[:T], ref["gather_idx"])
+        assert np.array_equal(host(fp.inv_pos), ref["inv_pos"])
+        assert np.max(np.abs(host(fp.scores) - ref["scores"])) <= 1e-3 * (1 + np.abs(ref["scores"]).max())
+        assert np.max(np.abs(host(fp.out)[:T] - ref["out"])) <= 2e-2
+        assert np.max(np.abs(host(ys[i]) - ref["y"])) <= 2e-2
+        if i > 0:      # the pooled score map the gate kernel handed to the backward pass
+            assert np.max(np.abs(host(hp.s_up[i]) - s_up)) <= 1e-3 * (1 + np.abs(s_up).max())
+        s_up = orc.maxpool2x2(ref["scores"].astype(np.float32), *wl.grid).astype(np.float32)
+
+
+@pytest.mark.parametrize("concurrent", [False, True])
+def test_hierarchy_full_batch_training_chain_matches_stagewise_oracle(spa, pipeline, concurrent):
+    """Forward + backward of the four-stage hierarchy at its stated size (batch 16) through
+    HierarchyTrainPass as bench.py runs it (one stream, and a stream per stage): every stage's
+    integers bit-exact; y, dq | dk, d_rg, dx, dw, db and the loss against the oracle run stage by
+    stage with the max-pooled up-scale scores."""
+    bundles = wlmod.generate_hierarchy(0)
+    hp = pipeline.HierarchyTrainPass(_hier_cfg(bundles), concurrent=concurrent)
+    qks = [b["qkv"][:, :, :2 * b["workload"].C] for b in bundles]
+    hp.run([dev(b["x"], "bf16") for b in bundles], [dev(b["w"], "bf16") for b in bundles],
+           [dev(q, "bf16") for q in qks], [dev(b["labels"]) for b in bundles], [dev(b["dy"], "bf16") for b in bundles])
+    torch.cuda.synchronize()
+    s_up = None
+    for i, bun in enumerate(bundles):
+        wl, tp = bun["workload"], hp.passes[i]
+        B, N, C, H = wl.B, wl.N, wl.C, wl.H
+        assert B == 16
+        x, w, bias, qk = bun["x"], bun["w"], bun["bias"], qks[i]
+        s = orc.gate_scores(x, w, bias, s_up)
+        mask, margin = orc.select(s, wl.tau)
+        assert margin > 1e-3
+        cu, gidx, inv, T = orc.pack_indices(mask)
+        assert np.array_equal(host(tp.mask), mask) and np.array_equal(host(tp.cu_seqlens), cu)
+        assert np.array_equal(host(tp.gather_idx)[:T], gidx) and np.array_equal(host(tp.inv_pos), inv)
+        assert int(host(tp.total)[0]) == T
+        rg = orc.round_to_dtype(orc.sigmoid(s.astype(np.float32).astype(np.float64))[:, :, None] * x, "bf16")
+        out_ref, _ = orc.attention_per_image(qk[:, :, :C], qk[:, :, C:], rg, mask, H)
+        assert np.max(np.abs(host(tp.out)[:T] - out_ref)) <= 2e-2
+        assert np.max(np.abs(host(tp.y) - orc.unpack(out_ref, inv, B, N))) <= 2e-2
+        dO = bun["dy"].reshape(-1, C)[gidx]
+        rdq, rdk, rdv = orc.attention_backward_per_image(qk[:, :, :C], qk[:, :, C:], rg, mask, dO, H)
+        dqk, d_rg = host(tp.dqk).reshape(-1, 2 * C), host(tp.d_rg).reshape(-1, C)     # at token positions
+        assert _rel(dqk[gidx][:, :C], rdq) <= 2e-2 and _rel(dqk[gidx][:, C:], rdk) <= 2e-2
+        assert _rel(d_rg[gidx], rdv) <= 2e-2
+        assert np.all(dqk[inv < 0] == 0) and np.all(d_rg[inv < 0] == 0)
+        if s_up is not None:
+            assert np.min(np.abs(orc.gate_only(x, w, bias) - s_up)) > 1e-4      # which side won the max is unambiguous
+        g = orc.gate_backward(x, w, bias, s_up, bun["labels"], orc.unpack(rdv, inv, B, N), True, tp.loss_scale)
+        assert _rel(host(tp.dx), g["dx"]) <= 2e-2 and _rel(host(tp.dw), g["dw"]) <= 2e-2
+        assert abs(float(host(tp.db)[0]) - g["db"]) <= 2e-2 * max(1.0, abs(g["db"]))
+        assert abs(float(host(tp.loss)[0]) - g["loss"]) <= 1e-3 * abs(g["loss"])
+        s_up = orc.maxpool2x2(s.astype(np.float32), *wl.grid).astype(np.float32)
