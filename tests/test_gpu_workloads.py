@@ -2,6 +2,7 @@
 paper_2410_23608_amd.pipeline), the multi-stage hierarchy with up-scale scores, property
 tests over random shapes, and run-to-run determinism."""
 import dataclasses
+import itertools
 
 import numpy as np
 import pytest
@@ -33,6 +34,26 @@ def _hier_cfg(bundles):
 
 def _rel(got, ref):
     return float(np.max(np.abs(got - ref)) / max(1.0, np.max(np.abs(ref))))
+
+
+def _gate_backward_candidates(x, w, bias, s_up, labels, d_rg, loss_scale):
+    """The oracle's gate backward for every admissible reading of near-ties between the gate's own
+    score and the up-scale score.  Which of the two wins the max decides whether the token's score
+    gradient reaches (w, b); the kernel takes that decision on its fp32 sum, the oracle on its fp64
+    sum, so for a token whose two scores lie within 1e-4 of each other (far above the fp32
+    reassociation error, far below anything that matters to the values) both outcomes are valid.
+    Yields the oracle result with each such token forced to either side."""
+    if s_up is None:
+        yield orc.gate_backward(x, w, bias, None, labels, d_rg, True, loss_scale)
+        return
+    g = orc.gate_only(x, w, bias)
+    near = np.argwhere(np.abs(g - s_up) < 1e-4)
+    assert len(near) <= 4, "too many near-ties for an exhaustive check"
+    for signs in itertools.product((-1.0, 1.0), repeat=len(near)):
+        su = s_up.astype(np.float64).copy()
+        for (b, n), sg in zip(near, signs):
+            su[b, n] = g[b, n] + sg * 2e-4
+        yield orc.gate_backward(x, w, bias, su, labels, d_rg, True, loss_scale)
 
 
 def _sampled_attention_reference(q, k, v, mask, H, rows):
@@ -464,10 +485,11 @@ def test_hierarchy_full_batch_training_chain_matches_stagewise_oracle(spa, pipel
         assert _rel(dqk[gidx][:, :C], rdq) <= 2e-2 and _rel(dqk[gidx][:, C:], rdk) <= 2e-2
         assert _rel(d_rg[gidx], rdv) <= 2e-2
         assert np.all(dqk[inv < 0] == 0) and np.all(d_rg[inv < 0] == 0)
-        if s_up is not None:
-            assert np.min(np.abs(orc.gate_only(x, w, bias) - s_up)) > 1e-4      # which side won the max is unambiguous
-        g = orc.gate_backward(x, w, bias, s_up, bun["labels"], orc.unpack(rdv, inv, B, N), True, tp.loss_scale)
-        assert _rel(host(tp.dx), g["dx"]) <= 2e-2 and _rel(host(tp.dw), g["dw"]) <= 2e-2
-        assert abs(float(host(tp.db)[0]) - g["db"]) <= 2e-2 * max(1.0, abs(g["db"]))
-        assert abs(float(host(tp.loss)[0]) - g["loss"]) <= 1e-3 * abs(g["loss"])
+        dx_d, dw_d, db_d, loss_d = host(tp.dx), host(tp.dw), float(host(tp.db)[0]), float(host(tp.loss)[0])
+        ok = [(_rel(dx_d, g["dx"]) <= 2e-2 and _rel(dw_d, g["dw"]) <= 2e-2
+               and abs(db_d - g["db"]) <= 2e-2 * max(1.0, abs(g["db"]))
+               and abs(loss_d - g["loss"]) <= 1e-3 * abs(g["loss"]))
+              for g in _gate_backward_candidates(x, w, bias, s_up, bun["labels"], orc.unpack(rdv, inv, B, N),
+                                                 tp.loss_scale)]
+        assert any(ok), f"stage {i + 1}: gate backward matches no admissible reading of the near-ties"
         s_up = orc.maxpool2x2(s.astype(np.float32), *wl.grid).astype(np.float32)
