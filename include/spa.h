@@ -457,6 +457,23 @@ int spa_gate_bwd(const void* x, const void* w, float bias, const float* scores,
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * spa_gate_bwd for callers that cannot allocate device memory or hand in a workspace: code under
+ * HIP graph capture, tight serving / training loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results (bit for bit) as spa_gate_bwd, but the partial rows of the
+ * dw / db / loss reduction live in a device array built into the library (2.1 MB per GPU, held
+ * until the process ends; its address on the current device is looked up on the first call on
+ * that device).  The call allocates and frees nothing.
+ * Limits: C <= 1024 (any B, N); beyond that SPA_ERR_WORKSPACE and nothing is launched.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on the same GPU
+ * (different streams, different threads) race; calls on one stream, or ordered by events, do not.
+ * Nothing in the array needs clearing between calls (every row read is written first).
+ */
+int spa_gate_bwd_static(const void* x, const void* w, float bias, const float* scores,
+                        const float* s_up, const uint8_t* labels, const void* d_rg, int gate_scaled,
+                        float loss_scale, int B, int N, int C, int dtype,
+                        float* loss, void* dx, float* dw, float* db, void* stream);
+
+/*
  * spa_gate_bwd with the straight-through estimator of the hard selection (Section 3.2, the
  * Gumbel-Softmax with hard samples): the forward pass multiplied r_g by the 0/1 mask, the
  * backward pass differentiates the relaxed weight p~_i = sigmoid((s_i + e_i)/temperature) in

@@ -3,6 +3,7 @@
 // (Section 3.3).  All kernels are bandwidth-bound: every feature row is read once with
 // 16-byte loads, a group of G lanes per token, fp32 accumulation.
 #include <cmath>
+#include <mutex>
 
 #include "spa_common.h"
 
@@ -475,6 +476,57 @@ extern "C" int spa_gate_bwd(const void* x, const void* w, float bias, const floa
   return gate_bwd_common("spa_gate_bwd", x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale,
                          StraightThrough{nullptr, nullptr, 1.f}, B, N, C, dtype, loss, dx, dw, db, workspace,
                          workspace_bytes, stream);
+}
+
+// ---- the gate backward for callers that cannot allocate --------------------------------
+// The partial rows of the two-stage reduction live in a file-scope device array instead of a
+// caller workspace.  The array's name is a host-side stand-in, not a device address: its
+// address on the current device is looked up once per device with hipGetSymbolAddress and that
+// pointer is what the kernels get.
+namespace spa {
+constexpr int kNoAllocMaxC = 1024;
+constexpr int kNoAllocMaxDevices = 64;
+static __device__ __align__(256) float scratch[(size_t)kGateBwdMaxParts * (kNoAllocMaxC + 2)];
+static float* g_scratch_ptr[kNoAllocMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+static int scratch_on_current_device(const char* fn, float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(SPA_ERR_HIP, "%s: hipGetDevice: %s", fn, hipGetErrorString(e));
+  SPA_REQUIRE(dev >= 0 && dev < kNoAllocMaxDevices, SPA_ERR_UNSUPPORTED, "%s: device %d beyond %d", fn, dev,
+              kNoAllocMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr)
+      return fail(SPA_ERR_HIP, "%s: hipGetSymbolAddress(scratch): %s", fn, hipGetErrorString(e));
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return SPA_OK;
+}
+}  // namespace spa
+
+extern "C" int spa_gate_bwd_static(const void* x, const void* w, float bias, const float* scores,
+                                   const float* s_up, const uint8_t* labels, const void* d_rg, int gate_scaled,
+                                   float loss_scale, int B, int N, int C, int dtype, float* loss, void* dx,
+                                   float* dw, float* db, void* stream) {
+  const char* fn = "spa_gate_bwd_static";
+  SPA_REQUIRE(C >= 1 && C <= kNoAllocMaxC, SPA_ERR_WORKSPACE,
+              "%s: C = %d exceeds the built-in scratch (C <= %d); use spa_gate_bwd with a workspace", fn, C,
+              kNoAllocMaxC);
+  SPA_REQUIRE(B >= 1 && N >= 1, SPA_ERR_INVALID_ARG, "%s: B, N must be >= 1", fn);
+  const size_t need = spa_gate_bwd_workspace_bytes(B, N, C, dtype);
+  SPA_REQUIRE(need <= sizeof(float) * (size_t)kGateBwdMaxParts * (kNoAllocMaxC + 2), SPA_ERR_WORKSPACE,
+              "%s: %zu bytes of scratch needed, more than the built-in array holds", fn, need);
+  float* ptr = nullptr;
+  if (int rc = scratch_on_current_device(fn, &ptr)) return rc;
+  // every partial row the reduction reads is written by this call's first kernel: nothing to clear
+  return gate_bwd_common(fn, x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale,
+                         StraightThrough{nullptr, nullptr, 1.f}, B, N, C, dtype, loss, dx, dw, db, ptr, need, stream);
 }
 
 extern "C" int spa_gate_bwd_straight_through(const void* x, const void* w, float bias, const float* scores,

@@ -72,6 +72,8 @@ _SIGNATURES = {
     "spa_gate_bwd_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int]),
     "spa_gate_bwd": (c_int, [_P, _P, c_float, _P, _P, _P, _P, c_int, c_float, c_int, c_int, c_int, c_int,
                              _P, _P, _P, _P, _P, c_size_t, _P]),
+    "spa_gate_bwd_static": (c_int, [_P, _P, c_float, _P, _P, _P, _P, c_int, c_float, c_int, c_int, c_int, c_int,
+                                    _P, _P, _P, _P, _P]),
     "spa_padded_attention": (c_int, [_P, _P, _P, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P]),
 }
 for _name, (_res, _args) in _SIGNATURES.items():
@@ -617,6 +619,20 @@ def spa_gate_bwd(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale
     return _dispatch(lib.spa_gate_bwd, (_ptr(x), _ptr(w), float(bias), _ptr(scores), _ptr(s_up), _ptr(labels), _ptr(d_rg),
                             int(bool(gate_scaled)), float(loss_scale), B, N, C, code, _ptr(loss), _ptr(dx),
                             _ptr(dw), _ptr(db), _ptr(workspace), ws_bytes, _stream(),), _keep, prepare)
+
+
+def spa_gate_bwd_static(x, w, bias, scores, s_up, labels, d_rg, gate_scaled, loss_scale, loss, dx, dw, db,
+                        prepare=False):
+    """spa_gate_bwd without a workspace argument: the reduction's scratch is a device array built
+    into the library (C <= 1024); the call allocates nothing."""
+    B, N, C, code = _gate_bwd_checks("spa_gate_bwd_static", x, w, scores, s_up, labels, d_rg, None, None, loss, dx,
+                                     dw, db)
+    _keep = (x, w, scores, s_up, labels, d_rg, loss, dx, dw, db,)
+    _contig(*_keep)
+    return _dispatch(lib.spa_gate_bwd_static,
+                     (_ptr(x), _ptr(w), float(bias), _ptr(scores), _ptr(s_up), _ptr(labels), _ptr(d_rg),
+                      int(bool(gate_scaled)), float(loss_scale), B, N, C, code, _ptr(loss), _ptr(dx), _ptr(dw),
+                      _ptr(db), _stream(),), _keep, prepare)
 
 
 def spa_gate_bwd_straight_through(x, w, bias, scores, s_up, labels, d_rg, loss_scale, mask, noise, temperature,
