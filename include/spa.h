@@ -270,6 +270,24 @@ int spa_packed_attention_unpack(const void* q, const void* k, const void* v, int
                                 void* stream);
 
 /*
+ * spa_packed_attention_unpack on rows that were never copied (Section 3.2 "Token Packing": packing
+ * re-arranges tokens, it computes nothing): q, k, v stay where the projections wrote them, at the
+ * token positions, and the kernel fetches the row of packed position j from row gather_idx[j].
+ * Together with the index-only spa_pack (x = packed = NULL) the forward pass moves no row twice.
+ * Results equal spa_pack of q|k|v followed by spa_packed_attention_unpack, bit for bit.
+ * in:  q, k, v: element (i, h, d) of q at q[i*q_row_stride + h*Dh + d] for TOKEN i = b*N + n
+ *      (likewise k, v; e.g. three column slices of one [B*N, 3*H*Dh] tensor); every other
+ *      argument, and every output, as in spa_packed_attention_unpack (out and lse are in packed
+ *      order).
+ */
+int spa_gathered_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                  int64_t k_row_stride, int64_t v_row_stride,
+                                  const int32_t* cu_seqlens, const int32_t* gather_idx,
+                                  const int32_t* inv_pos, const void* base, int B, int N, int H, int Dh,
+                                  int dtype, float softmax_scale, void* out, float* lse, void* y,
+                                  void* stream);
+
+/*
  * spa_packed_attention_unpack for segments that are not whole images (the container-local
  * segments of spa_container_segments): attention inside every segment of seg_cu_seqlens and,
  * in the same launch, the scatter back to y with the fill of the bypassing rows.  Results equal

@@ -38,7 +38,19 @@ struct Scatter {
   int flat;                    // 0: segment s fills the bypassing rows of image s (segments are images)
                                // 1: segments are not images (containers): the rows of y are dealt
                                //    evenly to all (segment, part) work units
+  int gathered;                // 1: q, k, v are NOT packed: the row of packed position j is row
+                               //    gather_idx[j] of q, k, v (token positions); packing then only
+                               //    builds the index and no row is copied before the attention
 };
+
+// Row of q / k / v that holds packed position j of a segment starting at packed row row0:
+// gi = gather_idx + row0 when the rows are gathered through the index, else null.
+__device__ __forceinline__ const int32_t* gather_base(const Scatter& sc, long row0) {
+  return sc.gathered ? sc.gather_idx + row0 : nullptr;
+}
+__device__ __forceinline__ long source_row(const int32_t* gi, long row0, int j) {
+  return gi != nullptr ? (long)gi[j] : row0 + j;
+}
 
 // The rows whose bypass fill falls to work unit (segment `seg` of `nseg`, part `part` of `nparts`):
 // tokens [t0, t1) of image b (flat mode: b = 0 and the range is over all rows of y).
@@ -253,19 +265,33 @@ struct KvStage {
   static constexpr int TPT = (TASKS + THREADS - 1) / THREADS;
   bf16x8 kreg[TPT][2], vreg[TPT][2];
 
-  // rows are relative to row `base` of the segment; rows >= nrows read as zero
-  __device__ __forceinline__ void load(const __bf16* kh, const __bf16* vh, long base, int nrows, long ks, long vs) {
+  int rows[TPT][2];   // source rows of the next load (-1: past the segment)
+
+  // Step 1: the rows of q / k / v that hold keys [kt, kt + tile) of the segment (gi: see
+  // gather_base; an index load when the rows are gathered, arithmetic otherwise).  Issued one
+  // tile ahead of load(), so the row loads never wait for an index.
+  __device__ __forceinline__ void index(const int32_t* gi, long row0, int kt, int nk) {
 #pragma unroll
     for (int t = 0; t < TPT; ++t) {
       const int i = threadIdx.x + t * THREADS;
-      const int c = i % CPR, r0 = 2 * (i / CPR);
+      const int r0 = kt + 2 * (i / CPR);
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        rows[t][u] = (i < TASKS && r0 + u < nk) ? (int)source_row(gi, row0, r0 + u) : -1;
+    }
+  }
+  // Step 2: the row loads; rows past the segment read as zero
+  __device__ __forceinline__ void load(const __bf16* kh, const __bf16* vh, long ks, long vs) {
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) {
+      const int c = (threadIdx.x + t * THREADS) % CPR;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         kreg[t][u] = zero_bf16x8();
         vreg[t][u] = zero_bf16x8();
-        if (i < TASKS && r0 + u < nrows) {
-          kreg[t][u] = *reinterpret_cast<const bf16x8*>(kh + (base + r0 + u) * ks + c * 8);
-          vreg[t][u] = *reinterpret_cast<const bf16x8*>(vh + (base + r0 + u) * vs + c * 8);
+        if (rows[t][u] >= 0) {
+          kreg[t][u] = *reinterpret_cast<const bf16x8*>(kh + (long)rows[t][u] * ks + c * 8);
+          vreg[t][u] = *reinterpret_cast<const bf16x8*>(vh + (long)rows[t][u] * vs + c * 8);
         }
       }
     }
@@ -331,10 +357,13 @@ tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const _
   const __bf16* kh = k + h * DH;
   const __bf16* vh = v + h * DH;
 
+  const int32_t* gi = gather_base(sc, seg.row0);
   KvStage<DH, 64 * NW, (BN / 2) * (DH / 8)> stage;
-  stage.load(kh, vh, seg.row0, seg.nk, ks, vs);
+  stage.index(gi, seg.row0, 0, seg.nk);
+  stage.load(kh, vh, ks, vs);
+  stage.index(gi, seg.row0, BN, seg.nk);
   bf16x8 qf[DH / 16];
-  load_q_frags<DH>(q + (seg.row0 + qi) * qs + h * DH, q_ok, hh, qf);
+  load_q_frags<DH>(q + (q_ok ? source_row(gi, seg.row0, qi) : 0) * qs + h * DH, q_ok, hh, qf);
   FwdAcc<DH> acc;
   acc.init();
   stage.template store<RS, TS>(Ks[0], Vt[0], 0);
@@ -343,7 +372,10 @@ tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const _
   const int nt = (seg.nk + BN - 1) / BN;
   for (int t = 0; t < nt; ++t) {
     const int buf = t & 1, kt = t * BN;
-    if (t + 1 < nt) stage.load(kh, vh, seg.row0 + kt + BN, seg.nk - kt - BN, ks, vs);
+    if (t + 1 < nt) {
+      stage.load(kh, vh, ks, vs);                           // tile t + 1, whose rows were indexed a tile ago
+      stage.index(gi, seg.row0, kt + 2 * BN, seg.nk);
+    }
     if (wave_live) {
       const int rem = seg.nk - kt;               // valid keys from this tile on (may exceed BN)
       if (rem >= BN) fwd_process_tile<DH, RS, TS, NSB, true>(Ks[buf], Vt[buf], 0, BN, qf, acc, scale_log2, l32, hh);
@@ -415,15 +447,24 @@ wave_attention(__bf16* Ks, __bf16* Vs, const Segment seg, int h, int q0, const _
 
   // lane -> (row, chunk) of the step's tile: 8 (Dh 64) or 4 (Dh 32) lanes cover one row
   bf16x8 kreg[LPL], vreg[LPL];
-  auto gload = [&](int kt) {
+  const int32_t* gi = gather_base(sc, seg.row0);
+  int rows[LPL];                                  // source rows of the next gload (-1: past the segment)
+  auto iload = [&](int kt) {                      // issued one step ahead of the row loads that use it
 #pragma unroll
     for (int t = 0; t < LPL; ++t) {
-      const int i = lane + 64 * t, r = i / CPR, c = i % CPR;
+      const int r = kt + (lane + 64 * t) / CPR;
+      rows[t] = r < seg.nk ? (int)source_row(gi, seg.row0, r) : -1;
+    }
+  };
+  auto gload = [&]() {
+#pragma unroll
+    for (int t = 0; t < LPL; ++t) {
+      const int c = (lane + 64 * t) % CPR;
       kreg[t] = zero_bf16x8();
       vreg[t] = zero_bf16x8();
-      if (kt + r < seg.nk) {
-        kreg[t] = *reinterpret_cast<const bf16x8*>(kh + (seg.row0 + kt + r) * ks + c * 8);
-        vreg[t] = *reinterpret_cast<const bf16x8*>(vh + (seg.row0 + kt + r) * vs + c * 8);
+      if (rows[t] >= 0) {
+        kreg[t] = *reinterpret_cast<const bf16x8*>(kh + (long)rows[t] * ks + c * 8);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(vh + (long)rows[t] * vs + c * 8);
       }
     }
   };
@@ -436,15 +477,20 @@ wave_attention(__bf16* Ks, __bf16* Vs, const Segment seg, int h, int q0, const _
     }
   };
 
-  gload(0);
+  iload(0);
+  gload();
+  iload(STEP);
   bf16x8 qf[KK];
-  load_q_frags<DH>(q + (seg.row0 + qi) * qs + h * DH, q_ok, hh, qf);
+  load_q_frags<DH>(q + (q_ok ? source_row(gi, seg.row0, qi) : 0) * qs + h * DH, q_ok, hh, qf);
   FwdAcc<DH> acc;
   acc.init();
 
   for (int kt = 0; kt < seg.nk; kt += STEP) {
     lstore();                                     // this step's rows: registers -> LDS
-    if (kt + STEP < seg.nk) gload(kt + STEP);     // next step's rows: in flight during the math
+    if (kt + STEP < seg.nk) {
+      gload();                                    // next step's rows: in flight during the math
+      iload(kt + 2 * STEP);
+    }
     const int rem = seg.nk - kt;
     // scores of the step: S^T = K Q^T, NSB 32-key sub-tiles, one softmax update for all
     floatx16 s[NSB];
@@ -689,10 +735,12 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   const bool wave_live = wv * 32 < seg.nq;
   const bool q_ok = qi < seg.nq;
 
+  const int32_t* gi = gather_base(sc, seg.row0);
   KvStage<DH, THREADS, (NKMAX / 2) * (DH / 8)> stage;
-  stage.load(k + h * DH, v + h * DH, seg.row0, seg.nk, ks, vs);
+  stage.index(gi, seg.row0, 0, seg.nk);
+  stage.load(k + h * DH, v + h * DH, ks, vs);
   bf16x8 qf[DH / 16];
-  load_q_frags<DH>(q + (seg.row0 + qi) * qs + h * DH, q_ok, hh, qf);
+  load_q_frags<DH>(q + (q_ok ? source_row(gi, seg.row0, qi) : 0) * qs + h * DH, q_ok, hh, qf);
   FwdAcc<DH> acc;
   acc.init();
   stage.template store<RS, TS>(Ks, Vt, 0);
@@ -751,8 +799,9 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
   float qr[DH], o[DH];
 #pragma unroll
   for (int d = 0; d < DH; ++d) { qr[d] = 0.f; o[d] = 0.f; }
+  const int32_t* gi = gather_base(sc, seg.row0);
   if (q_ok) {
-    const float* qp = q + (seg.row0 + qi) * qs + h * DH;
+    const float* qp = q + source_row(gi, seg.row0, qi) * qs + h * DH;
 #pragma unroll
     for (int d = 0; d < DH; d += 4) {
       const floatx4 t = *reinterpret_cast<const floatx4*>(qp + d);
@@ -767,8 +816,9 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
       const int r = i / (DH / 4), c = i % (DH / 4);
       floatx4 kv = {0.f, 0.f, 0.f, 0.f}, vv = kv;
       if (kt + r < seg.nk) {
-        kv = *reinterpret_cast<const floatx4*>(k + (seg.row0 + kt + r) * ks + h * DH + c * 4);
-        vv = *reinterpret_cast<const floatx4*>(v + (seg.row0 + kt + r) * vs + h * DH + c * 4);
+        const long src = source_row(gi, seg.row0, kt + r);
+        kv = *reinterpret_cast<const floatx4*>(k + src * ks + h * DH + c * 4);
+        vv = *reinterpret_cast<const floatx4*>(v + src * vs + h * DH + c * 4);
       }
       *reinterpret_cast<floatx4*>(&Ks[r * DH + c * 4]) = kv;
       *reinterpret_cast<floatx4*>(&Vs[r * DH + c * 4]) = vv;
@@ -944,7 +994,7 @@ extern "C" int spa_packed_attention(const void* q, const void* k, const void* v,
                                     int dtype, float softmax_scale, void* out, float* lse, void* stream) {
   SPA_REQUIRE(cu_seqlens, SPA_ERR_INVALID_ARG, "spa_packed_attention: cu_seqlens is null");
   SPA_REQUIRE(out, SPA_ERR_INVALID_ARG, "spa_packed_attention: out is null");
-  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0};
+  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
   return attention_common("spa_packed_attention", q, k, v, q_row_stride, k_row_stride, v_row_stride, cu_seqlens, nullptr, B, max_seqlen,
                           H, Dh, dtype, softmax_scale, out, lse, none, stream);
 }
@@ -954,7 +1004,7 @@ extern "C" int spa_padded_attention(const void* q, const void* k, const void* v,
                                     float softmax_scale, void* out, void* stream) {
   SPA_REQUIRE(seqlens, SPA_ERR_INVALID_ARG, "spa_padded_attention: seqlens is null");
   SPA_REQUIRE(out, SPA_ERR_INVALID_ARG, "spa_padded_attention: out is null");
-  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0};
+  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
   return attention_common("spa_padded_attention", q, k, v, row_stride, row_stride, row_stride, nullptr, seqlens, B, n_pad, H, Dh,
                           dtype, softmax_scale, out, nullptr, none, stream);
 }
@@ -969,9 +1019,23 @@ extern "C" int spa_packed_attention_unpack(const void* q, const void* k, const v
               "spa_packed_attention_unpack: null pointer");
   SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG,
               "spa_packed_attention_unpack: y / base not 16-byte aligned");
-  const Scatter sc = {gather_idx, inv_pos, base, y, N, 0};
+  const Scatter sc = {gather_idx, inv_pos, base, y, N, 0, 0};
   return attention_common("spa_packed_attention_unpack", q, k, v, q_row_stride, k_row_stride, v_row_stride,
                           cu_seqlens, nullptr, B, N, H, Dh, dtype, softmax_scale, out, lse, sc, stream);
+}
+
+extern "C" int spa_gathered_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                             int64_t k_row_stride, int64_t v_row_stride,
+                                             const int32_t* cu_seqlens, const int32_t* gather_idx,
+                                             const int32_t* inv_pos, const void* base, int B, int N, int H, int Dh,
+                                             int dtype, float softmax_scale, void* out, float* lse, void* y,
+                                             void* stream) {
+  const char* fn = "spa_gathered_attention_unpack";
+  SPA_REQUIRE(cu_seqlens && gather_idx && inv_pos && y, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+  SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG, "%s: y / base not 16-byte aligned", fn);
+  const Scatter sc = {gather_idx, inv_pos, base, y, N, 0, 1};
+  return attention_common(fn, q, k, v, q_row_stride, k_row_stride, v_row_stride, cu_seqlens, nullptr, B, N, H, Dh,
+                          dtype, softmax_scale, out, lse, sc, stream);
 }
 
 extern "C" int spa_segment_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
@@ -984,7 +1048,7 @@ extern "C" int spa_segment_attention_unpack(const void* q, const void* k, const 
   SPA_REQUIRE(seg_cu_seqlens && gather_idx && inv_pos && y, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(rows >= 1 && rows < 2147483647L, SPA_ERR_INVALID_ARG, "%s: rows must be in [1, 2^31)", fn);
   SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG, "%s: y / base not 16-byte aligned", fn);
-  const Scatter sc = {gather_idx, inv_pos, base, y, (int)rows, 1};
+  const Scatter sc = {gather_idx, inv_pos, base, y, (int)rows, 1, 0};
   return attention_common(fn, q, k, v, q_row_stride, k_row_stride, v_row_stride, seg_cu_seqlens, nullptr, n_segments,
                           max_seqlen, H, Dh, dtype, softmax_scale, out, lse, sc, stream);
 }

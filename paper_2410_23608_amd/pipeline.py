@@ -25,12 +25,19 @@ class ForwardPass:
 
     fused_unpack=True (default) issues the last two steps as ONE launch
     (spa_packed_attention_unpack: the attention kernel scatters its rows back itself and
-    fills the bypassing rows); the results are bit-identical to the two separate calls."""
+    fills the bypassing rows); the results are bit-identical to the two separate calls.
+    gathered=True (fused form only): packing builds the index only and the attention kernel
+    fetches the q | k | v rows through gather_idx from where they lie, so no row is copied
+    (spa_pack with x = NULL, then spa_gathered_attention_unpack); same results, bit for bit."""
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
-                 container_len: int = 0, fused_unpack: bool = True, keep_packed_out: bool = True):
+                 container_len: int = 0, fused_unpack: bool = True, keep_packed_out: bool = True,
+                 gathered: bool = False):
         """keep_packed_out=False (fused form only): the packed attention output and the
         log-sum-exp rows, which only a backward pass reads, are not written; y is the result."""
+        if gathered and (not fused_unpack or container_len):
+            raise ValueError("gathered=True needs the fused form and no container padding")
+        self.gathered = gathered
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
         self.tau, self.bias, self.container_len = tau, bias, container_len
         self.fused_unpack = fused_unpack
@@ -39,19 +46,30 @@ class ForwardPass:
         dv = dict(device="cuda")
         self.scores = torch.empty(B, N, dtype=torch.float32, **dv)
         self.mask = torch.empty(B, N, dtype=torch.uint8, **dv)
-        self.packed_qkv = torch.zeros(cap + max(container_len - 1, 0), 3 * C, dtype=td, **dv)
+        self.packed_qkv = None if gathered else torch.zeros(cap + max(container_len - 1, 0), 3 * C, dtype=td, **dv)
         self.cu_seqlens = torch.zeros(B + 1, dtype=torch.int32, **dv)
         self.gather_idx = torch.zeros(cap, dtype=torch.int32, **dv)
         self.inv_pos = torch.zeros(cap, dtype=torch.int32, **dv)
         self.total = torch.zeros(1, dtype=torch.int32, **dv)
-        self.out = torch.zeros(cap, C, dtype=td, **dv)
-        self.lse = torch.zeros(H, cap, dtype=torch.float32, **dv)
+        self.out = torch.zeros(cap, C, dtype=td, **dv) if self.keep_packed_out else None
+        self.lse = torch.zeros(H, cap, dtype=torch.float32, **dv) if self.keep_packed_out else None
         self.y = torch.empty(B, N, C, dtype=td, **dv)
 
     def stages(self, x, w, qkv, s_up=None, base=None) -> List[Tuple[str, Callable[[], None]]]:
         """The pass as named, prepared launches (bound to the stream that is current now), so a
         caller can time each of them or replay them with no marshalling cost."""
         C, p = self.C, self.packed_qkv
+        if self.gathered:
+            t = qkv.view(self.B * self.N, 3 * C)
+            return [
+                ("gate_select", spa.spa_gate_select(x, w, self.bias, s_up, self.tau, self.scores, self.mask, None,
+                                                    prepare=True)),
+                ("pack_indices", spa.spa_pack(None, self.mask, None, None, 0, None, self.cu_seqlens, self.gather_idx,
+                                              self.inv_pos, self.total, prepare=True)),
+                ("gathered_attention_unpack", spa.spa_gathered_attention_unpack(
+                    t[:, :C], t[:, C:2 * C], t[:, 2 * C:], self.cu_seqlens, self.gather_idx, self.inv_pos, base,
+                    self.H, self.Dh, self.y, self.out, self.lse, prepare=True)),
+            ]
         q, k, v = p[:, :C], p[:, C:2 * C], p[:, 2 * C:]
         head = [
             ("gate_select", spa.spa_gate_select(x, w, self.bias, s_up, self.tau, self.scores, self.mask, None,

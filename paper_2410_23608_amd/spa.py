@@ -48,6 +48,8 @@ _SIGNATURES = {
     "spa_packed_attention": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, c_int, c_int, c_int, c_float, _P, _P, _P]),
     "spa_packed_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
                                             c_int, c_int, c_float, _P, _P, _P, _P]),
+    "spa_gathered_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
+                                              c_int, c_int, c_float, _P, _P, _P, _P]),
     "spa_segment_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, _P, _P, _P, c_int64,
                                              c_int, c_int, c_int, c_float, _P, _P, _P, _P]),
     "spa_ceiling_copy": (c_int, [_P, _P, c_size_t, _P]),
@@ -390,6 +392,22 @@ def spa_packed_attention_unpack(q, k, v, cu_seqlens, gather_idx, inv_pos, base, 
     _keep = (q, k, v, cu_seqlens, gather_idx, inv_pos, base, y, out, lse,)
     _contig(cu_seqlens, gather_idx, inv_pos, base, y, out, lse)
     return _dispatch(lib.spa_packed_attention_unpack,
+                     (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(cu_seqlens),
+                      _ptr(gather_idx), _ptr(inv_pos), _ptr(base), B, N, H, Dh, code, float(softmax_scale),
+                      _ptr(out), _ptr(lse), _ptr(y), _stream(),), _keep, prepare)
+
+
+def spa_gathered_attention_unpack(q, k, v, cu_seqlens, gather_idx, inv_pos, base, H, Dh, y, out=None, lse=None,
+                                  softmax_scale=0.0, prepare=False):
+    """spa_packed_attention_unpack on un-packed q, k, v ([B*N, H*Dh] tensors or column-slice views at
+    token positions): the kernel fetches packed row j from row gather_idx[j]."""
+    fn = "spa_gathered_attention_unpack"
+    B, N, C = y.shape
+    _, code = _scatter_checks(fn, q, k, v, cu_seqlens, B, N, gather_idx, inv_pos, base, H, Dh, y, out, lse)
+    _rows(fn, C, q=(q, B * N), k=(k, B * N), v=(v, B * N))
+    _keep = (q, k, v, cu_seqlens, gather_idx, inv_pos, base, y, out, lse,)
+    _contig(cu_seqlens, gather_idx, inv_pos, base, y, out, lse)
+    return _dispatch(lib.spa_gathered_attention_unpack,
                      (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(cu_seqlens),
                       _ptr(gather_idx), _ptr(inv_pos), _ptr(base), B, N, H, Dh, code, float(softmax_scale),
                       _ptr(out), _ptr(lse), _ptr(y), _stream(),), _keep, prepare)

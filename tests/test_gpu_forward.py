@@ -322,6 +322,60 @@ def test_fused_attention_unpack_equals_separate_calls(spa, short_option, dtype, 
     assert np.max(np.abs(host(y2) - ref_y)) <= tol
 
 
+@pytest.mark.parametrize("dtype,Dh,N,short", [("f32", 32, 150, ""), ("f32", 64, 77, ""), ("bf16", 64, 196, ""),
+                                              ("bf16", 64, 196, "plain"), ("bf16", 64, 196, "whole"),
+                                              ("bf16", 32, 250, "64"), ("bf16", 32, 49, ""), ("bf16", 32, 700, ""),
+                                              ("bf16", 64, 300, ""), ("bf16", 32, 1337, "")])
+@pytest.mark.parametrize("with_base,keep_out", [(False, True), (True, False)])
+def test_gathered_attention_equals_packed_form(spa, short_option, dtype, Dh, N, short, with_base, keep_out):
+    """spa_gathered_attention_unpack (rows fetched through gather_idx from the un-packed q | k | v,
+    index-only packing) == spa_pack of the rows + spa_packed_attention_unpack, bit for bit, for
+    every forward kernel (one-wave numbered by weight / blindly / 64-key steps, whole-segment,
+    tiled, fp32), and both equal the oracle within tolerance."""
+    short_option(short)
+    B, H = 5, 2
+    C = H * Dh
+    rng = np.random.default_rng(77)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    qkv = mk(rng.standard_normal((B, N, 3 * C)).astype(np.float32))
+    base = mk(rng.standard_normal((B, N, C)).astype(np.float32)) if with_base else None
+    mask = (rng.uniform(size=(B, N)) < rng.uniform(0.1, 0.9, size=(B, 1))).astype(np.uint8)
+    mask[1] = 0                                   # an image with nothing selected
+    mask[2] = 1                                   # an image with everything selected
+    td, cap = tdtype(dtype), B * N
+    qkv_d, mask_d = dev(qkv, dtype), dev(mask)
+    base_d = None if base is None else dev(base, dtype)
+    new = lambda *shape, t=td: torch.full(shape, float("nan"), dtype=t, device="cuda")
+    ints = lambda n: torch.full((n,), -9, dtype=torch.int32, device="cuda")
+    # packed form: rows copied, then attention + scatter
+    packed = torch.zeros(cap, 3 * C, dtype=td, device="cuda")
+    cu1, g1, inv1 = ints(B + 1), ints(cap), ints(cap)
+    spa.spa_pack(qkv_d, mask_d, None, None, 0, packed, cu1, g1, inv1, None)
+    out1, lse1, y1 = new(cap, C), new(H, cap, t=torch.float32), new(B, N, C)
+    spa.spa_packed_attention_unpack(packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:], cu1, g1, inv1, base_d, H, Dh,
+                                    y1, out1, lse1)
+    # gathered form: indices only, rows fetched where they lie
+    cu2, g2, inv2, tot2 = ints(B + 1), ints(cap), ints(cap), ints(1)
+    spa.spa_pack(None, mask_d, None, None, 0, None, cu2, g2, inv2, tot2)
+    flat = qkv_d.view(cap, 3 * C)
+    out2 = new(cap, C) if keep_out else None
+    lse2 = new(H, cap, t=torch.float32) if keep_out else None
+    y2 = new(B, N, C)
+    spa.spa_gathered_attention_unpack(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], cu2, g2, inv2, base_d, H, Dh, y2,
+                                      out2, lse2)
+    torch.cuda.synchronize()
+    T = int(mask.sum())
+    assert int(host(tot2)[0]) == T and torch.equal(cu1, cu2) and torch.equal(g1[:T], g2[:T]) and torch.equal(inv1, inv2)
+    assert np.array_equal(host(y1), host(y2)) and not np.any(np.isnan(host(y2)))
+    if keep_out:
+        assert np.array_equal(host(out1)[:T], host(out2)[:T]) and np.array_equal(host(lse1)[:, :T], host(lse2)[:, :T])
+        assert np.all(np.isnan(host(out2)[T:]))                  # rows past T untouched
+    ref_out, _ = orc.attention_per_image(qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], mask, H)
+    ref_y = orc.unpack(ref_out, orc.pack_indices(mask)[2], B, N, base)
+    tol = TOL[dtype] * (2 if with_base and dtype == "bf16" else 1)
+    assert np.max(np.abs(host(y2) - ref_y)) <= tol
+
+
 @pytest.mark.parametrize("B", [64, 70])
 def test_short_segments_many_images(spa, B):
     """The one-wave kernel with as many images as lanes (blocks numbered by weight) and with

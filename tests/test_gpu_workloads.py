@@ -493,3 +493,25 @@ def test_hierarchy_full_batch_training_chain_matches_stagewise_oracle(spa, pipel
                                                  tp.loss_scale)]
         assert any(ok), f"stage {i + 1}: gate backward matches no admissible reading of the near-ties"
         s_up = orc.maxpool2x2(s.astype(np.float32), *wl.grid).astype(np.float32)
+
+
+@pytest.mark.parametrize("name", ["tiny", "vit_s", "det"])
+def test_full_size_gathered_forward_as_benchmarked(spa, pipeline, name):
+    """The forward step bench.py times (gate_select, index-only pack, attention on gathered rows
+    + scatter) on the full batch: integers bit-exact, y against the oracle on every row, and
+    bit-equal to the form that copies the rows first."""
+    wl = wlmod.WORKLOADS[name]
+    bun = wlmod.generate(wl, 0)
+    ins = (dev(bun["x"], wl.dtype), dev(bun["w"], wl.dtype), dev(bun["qkv"], wl.dtype))
+    fg = pipeline.ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, gathered=True, keep_packed_out=False)
+    fp = pipeline.ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False)
+    yg, yp = fg.run(*ins), fp.run(*ins)
+    torch.cuda.synchronize()
+    ref = orc.spa_forward(bun["x"], bun["w"], bun["bias"], bun["qkv"], wl.H, wl.tau, wl.dtype)
+    assert ref["margin"] > 1e-3
+    T = ref["total"]
+    assert np.array_equal(host(fg.mask), ref["mask"]) and np.array_equal(host(fg.cu_seqlens), ref["cu_seqlens"])
+    assert np.array_equal(host(fg.gather_idx)[:T], ref["gather_idx"]) and np.array_equal(host(fg.inv_pos), ref["inv_pos"])
+    assert int(host(fg.total)[0]) == T
+    assert torch.equal(yg, yp)
+    assert np.max(np.abs(host(yg) - ref["y"])) <= (1e-5 if wl.dtype == "f32" else 2e-2)
