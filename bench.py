@@ -1,16 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the SPA hot path on one MI355X.
 
-A step is one pass of the whole forward path (gate score + selection, pack, per-image
-attention on the packed tokens, scatter back — the last two in one launch) over one seeded
-synthetic batch that is already resident in HBM.  The default workload is the ViT-S-shaped classification batch
-(64 images x 196 tokens, dim 384, 6 heads, bf16, per-image selected fraction U[0.1, 0.9]).
+A step is one pass of the whole forward path (gate score + selection, index-only packing,
+per-image attention on the selected tokens fetched through the index, scatter back - the last
+two in one launch) over one seeded synthetic batch that is already resident in HBM.  The
+headline workload is the detection-shaped batch, the largest single-GPU configuration (8
+images x 4200 tokens, dim 256, 8 heads of 32, bf16, 5-40 % of the tokens selected per image):
+it is the one whose attention sits above the ridge of the roofline, so its matrix-pipe fraction
+means something.
 
-Prints ONE JSON line: whole-path throughput in selected tokens/s, the roofline of the
-dominant kernel (durations measured live with events on the launch stream), the CPU
-oracle timed on this machine's host cores, and secondary measurements (per-kernel table,
-hipGraph replay, the padded-to-max attention baseline, the forward+backward training
-step of the ViT-B-shaped workload).
+Prints ONE JSON line: whole-path throughput in selected tokens/s (median over R repeats of the
+timed K-step region), the roofline of the dominant kernel (durations measured live with events
+on the launch stream), the CPU oracle timed on this machine's host cores, and a `configs` block
+with the same measurements for every configuration: ViT-S-shaped forward, detection-shaped
+forward, ViT-B-shaped forward + backward, four-stage hierarchy forward + backward.
 """
 from __future__ import annotations
 
@@ -25,36 +28,39 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
-
-# HBM bytes per launch (fetch + write) of each stage, seed 0, from two `rocprofv3 --pmc` runs of
-# this script (FETCH_SIZE, then WRITE_SIZE; `--calibration-copy --steps 20 --warmup 5`), each
-# counter scaled by what it reads for the plain 256 MiB device copy of the same run
-# (factors 2.000 and 1.000).  Re-measure after any change to a kernel's access pattern.
-MEASURED_TRAFFIC_BYTES = {
-    ("vit_s", "gate_select"): 9.76e6, ("vit_s", "pack"): 29.45e6, ("vit_s", "packed_attention_unpack"): 24.86e6,
-    ("det", "gate_select"): 17.46e6, ("det", "pack"): 26.64e6, ("det", "packed_attention_unpack"): 44.85e6,
-}
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.txt")
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--workload", default="vit_s", choices=["tiny", "vit_s", "vit_b_train", "det"])
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--repeats", type=int, default=15,
+                    help="the K-step region is timed this many times; median and min are reported")
+    ap.add_argument("--workload", default="det", choices=["tiny", "vit_s", "det"], help="headline forward workload")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--streams", type=int, default=4,
                     help="independent batches in flight, one HIP stream each (1 = one stream, steps back to back)")
+    ap.add_argument("--only", default=None, choices=["forward", "vit_s", "det", "vit_b_train", "hierarchy"],
+                    help="measure one chain only (profiling runs): forward = the headline workload's forward chain")
+    ap.add_argument("--form", default="fused", choices=["fused", "gathered", "packed"],
+                    help="forward step: gate + packing index in one launch, attention on gathered rows (default, 2 "
+                         "launches); gate, index-only pack, attention on gathered rows (3); gate, pack of the rows, "
+                         "attention on the packed rows (3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip graph / padded / training measurements")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the four-call form, graph replay, padded baseline, widened rows")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
+# ------------------------------------------------------------------------------- timing
 def timed(fn, steps, torch):
     """K calls bracketed by synchronize on both sides -> seconds."""
     torch.cuda.synchronize()
@@ -65,11 +71,18 @@ def timed(fn, steps, torch):
     return time.perf_counter() - t0
 
 
+def timed_regions(fn, steps, repeats, torch):
+    """The K-step region, timed `repeats` times (a 20-step region of a 20 us step lasts 0.4 ms
+    and one reading of it carries the host's jitter): seconds per step, median and min."""
+    per = [timed(fn, steps, torch) / steps for _ in range(max(1, repeats))]
+    return float(np.median(per)), float(np.min(per))
+
+
 def per_stage_us(stage_sets, steps, torch):
-    """Average duration of every stage, from event pairs recorded on the launch stream
-    around each launch of the timed steps.  stage_sets: one list of (name, launch) per
-    independent copy of the inputs and buffers; step i runs on copy i % len(stage_sets), so
-    with enough copies every launch finds its inputs out of the last-level cache."""
+    """Average duration of every stage, from event pairs recorded on the launch stream around
+    each launch of the timed steps.  stage_sets: one list of (name, launch) per independent copy
+    of the inputs and buffers; step i runs on copy i % len(stage_sets), so with enough copies every
+    launch finds its inputs out of the last-level cache."""
     names = [n for n, _ in stage_sets[0]]
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in names]
           for _ in range(steps)]
@@ -81,32 +94,14 @@ def per_stage_us(stage_sets, steps, torch):
             fn()
             b.record()
     torch.cuda.synchronize()
-    out = {}
-    for i, n in enumerate(names):
-        out[n] = 1e3 * float(np.mean([ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)]))
-    return out
-
-
-def empty_pair_us(stages, steps, torch):  # noqa: D401
-    """What an event pair reads with NO launch between its two records, measured in the same
-    position (inside steps of the whole path): the part of a per-launch reading that is not
-    kernel time."""
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    torch.cuda.synchronize()
-    for s in range(steps):
-        for i, (_, fn) in enumerate(stages):
-            fn()
-            if i == 1:
-                ev[s][0].record()
-                ev[s][1].record()
-    torch.cuda.synchronize()
-    return 1e3 * float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    return {n: 1e3 * float(np.mean([ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)]))
+            for i, n in enumerate(names)}
 
 
 def back_to_back_us(fn, steps, torch):
-    """Average duration of one launch when the same kernel is enqueued `steps` times between
-    two events (no per-launch event overhead).  fn may be a list of launches of the same kernel
-    on independent copies of its data, used round-robin."""
+    """Average duration of one launch when the same kernel is enqueued `steps` times between two
+    events (no per-launch event overhead).  fn may be a list of launches of the same kernel on
+    independent copies of its data, used round-robin."""
     fns = fn if isinstance(fn, (list, tuple)) else [fn]
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -116,6 +111,20 @@ def back_to_back_us(fn, steps, torch):
     b.record()
     torch.cuda.synchronize()
     return 1e3 * a.elapsed_time(b) / steps
+
+
+def kernel_times_us(stage_sets, steps, torch):
+    """Per launch, the kernel running alone on one stream: two live readings with HIP events on the
+    launch stream, both upper bounds of the kernel's duration (an event pair around each launch
+    inside steps of the whole chain, and back-to-back launches between one pair); the smaller."""
+    steps = max(20, min(steps, 200))
+    ev = per_stage_us(stage_sets, steps, torch)
+    out = {}
+    for i, (name, _) in enumerate(stage_sets[0]):
+        b2b = back_to_back_us([cs[i][1] for cs in stage_sets], steps, torch)
+        out[name] = {"event_us": round(ev[name], 2), "back_to_back_us": round(b2b, 2),
+                     "kernel_us": round(min(ev[name], b2b), 2)}
+    return out
 
 
 def ceilings(spa, torch):
@@ -144,7 +153,8 @@ def ceilings(spa, torch):
         best = max(best, 5 * flops / (a.elapsed_time(b) * 1e-3) / 1e12)
     del src, dst
     return {"copy_GBs": round(copy_gbs, 1), "copy": "64 MiB read + 64 MiB written per launch, 8 buffer pairs in rotation",
-            "mfma_bf16_TFLOPs": round(best, 1), "mfma": "v_mfma_f32_32x32x16_bf16 only, 4 chains per wave, best of 1 and 2 waves per SIMD"}
+            "mfma_bf16_TFLOPs": round(best, 1),
+            "mfma": "v_mfma_f32_32x32x16_bf16 only, 4 chains per wave, best of 1 and 2 waves per SIMD"}
 
 
 def graph_replay_s(make_step, steps, torch):
@@ -162,6 +172,474 @@ def graph_replay_s(make_step, steps, torch):
     for _ in range(3):
         g.replay()
     return timed(g.replay, steps, torch)
+
+
+# ----------------------------------------------------------------------------- rooflines
+def load_traffic_table():
+    """HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs, as the committed table
+    under profiles/ holds them (written by `python -m paper_2410_23608_amd.profiling`)."""
+    table = {}
+    if os.path.exists(TRAFFIC_TABLE):
+        for line in open(TRAFFIC_TABLE):
+            f = line.split()
+            if len(f) >= 3 and not line.startswith("#"):
+                table[(f[0], f[1])] = float(f[2])
+    return table
+
+
+def roofline_entry(name, us, flops, nbytes, dtype, traffic):
+    """The roof that bounds a launch, chosen by operational intensity: below the ridge (peak flop
+    rate / peak bandwidth) the HBM roof is the lower one."""
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if dtype == "bf16" else FP32_VECTOR_PEAK_TFLOPS
+    ridge = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9)
+    intensity = flops / nbytes
+    if intensity < ridge:
+        bound, ach, peak, unit = "hbm", nbytes / us / 1e3, HBM_PEAK_GBS, "GB/s"
+    else:
+        bound, ach, peak, unit = ("mfma" if dtype == "bf16" else "alu"), flops / us / 1e6, mfma_peak, "TFLOP/s"
+    r = {"kernel": name, "bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit,
+         "frac": round(ach / peak, 4), "avg_launch_us": us, "algorithmic_bytes": int(nbytes),
+         "algorithmic_flops": flops, "flop_per_byte": round(intensity, 1), "ridge_flop_per_byte": round(ridge, 1),
+         "traffic": traffic,
+         "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated; from "
+                         "profiles/hbm_traffic_table.txt)"}
+    if flops > 0:
+        r["tflops"] = round(flops / us / 1e6, 2)
+        r["mfma_frac"] = round(flops / us / 1e6 / mfma_peak, 4)
+        r["hbm_frac"] = round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)
+    return r
+
+
+def kernels_block(times, work, dtype, wl_name, traffic_table, seed):
+    """times: name -> {kernel_us, ...}; work: name -> (flops, bytes).  Returns the per-kernel table
+    and the roofline of the dominant (longest) kernel."""
+    out = {}
+    for name, t in times.items():
+        if name not in work:
+            out[name] = t
+            continue
+        fl, by = work[name]
+        traffic = traffic_table.get((wl_name, name)) if seed == 0 else None
+        r = roofline_entry(name, t["kernel_us"], fl, by, dtype, traffic)
+        r.update(t)
+        out[name] = r
+    scored = [n for n in out if "frac" in out[n]]
+    dom = max(scored, key=lambda n: out[n]["kernel_us"])
+    return out, dict(out[dom])
+
+
+# ------------------------------------------------------------------------ forward chain
+def forward_work(wl, T, sum_n2, keep_out=False):
+    """Algorithmic (flops, bytes) per launch of the forward kernels."""
+    B, N, C, H = wl.B, wl.N, wl.C, wl.H
+    e = 2 if wl.dtype == "bf16" else 4
+    attn = (4.0 * C * sum_n2, T * 3 * C * e + B * N * C * e + 4 * T + 4 * B * N + 4 * (B + 1)
+            + (T * C * e + 4 * H * T if keep_out else 0))
+    return {
+        "gate_select": (0.0, B * N * (C * e + 5)),
+        "gate_select_index": (0.0, B * N * (C * e + 5) + 4 * T + 5 * B * N + 4 * (B + 1)),
+        "pack": (0.0, 2 * T * 3 * C * e + 4 * T + 5 * B * N + 4 * (B + 1)),
+        "pack_indices": (0.0, 4 * T + 5 * B * N + 4 * (B + 1)),
+        "packed_attention_unpack": attn, "gathered_attention_unpack": attn,
+        "packed_attention": (4.0 * C * sum_n2, T * 3 * C * e + T * C * e + 4 * H * T + 4 * (B + 1)),
+        "unpack": (0.0, T * C * e + 4 * B * N + B * N * C * e),
+    }
+
+
+def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, streams_cache):
+    """Forward chain of one workload: S batches in flight (cold rotation), one stream, per kernel."""
+    td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    e = 2 if wl.dtype == "bf16" else 4
+    bun = workloads.generate(wl, args.seed)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(td).contiguous()
+    x, w, qkv = up(bun["x"]), up(bun["w"]), up(bun["qkv"])
+    gathered = args.form in ("gathered", "fused")
+    mk = lambda: ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False,
+                             gathered=gathered, fused_index=args.form == "fused")
+    fp = mk()
+    stages = fp.stages(x, w, qkv)
+
+    def step():
+        for _, fn in stages:
+            fn()
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    T = int(fp.total.item())
+    n = np.diff(fp.cu_seqlens.cpu().numpy()).astype(np.float64)
+    sum_n2 = float((n * n).sum())
+
+    # one stream, steps back to back on ONE copy of the batch (warm last-level cache): the latency of a step
+    s_med, s_min = timed_regions(step, args.steps, args.repeats, torch)
+    single = {"ms_per_step": 1e3 * s_med, "ms_per_step_min": 1e3 * s_min, "value": T / s_med,
+              "unit": "selected tokens/s", "cache": "warm (one copy of the batch, reused every step)"}
+
+    # S independent batches in flight: S HIP streams (default priority), steps dealt round-robin, the
+    # launches of a step in order on their stream; every step works on its own copy of the inputs and
+    # buffers, enough copies (> 512 MB in total) that no step finds anything in the last-level cache
+    S = max(1, args.streams)
+    set_bytes = (x.numel() + qkv.numel() + (0 if gathered else fp.packed_qkv.numel()) + fp.y.numel()) * e
+    n_sets = S * max(2, -(-(512 << 20) // (S * set_bytes)))
+    turn = [0]
+    holder = {}
+
+    def build_sets(streams_):
+        made = []
+        for i in range(n_sets):
+            with torch.cuda.stream(streams_[i % S]):
+                fp_s = mk()
+                ins = (x.clone(), w.clone(), qkv.clone())
+                made.append((fp_s, fp_s.stages(*ins), ins))
+        torch.cuda.synchronize()
+        return made
+
+    def sstep():   # step i -> copy i % n_sets, which lives on stream i % S
+        for _, fn in holder["sets"][turn[0] % n_sets][1]:
+            fn()
+        turn[0] += 1
+
+    # Which HIP streams end up sharing one of the process's hardware queues (4 here) is the runtime's
+    # business, and two batches on one queue run one after the other: three groups of S streams are
+    # tried for a few hundred untimed steps each and the fastest group is kept (once per process).
+    calib = {}
+    if S > 1 and "streams" not in streams_cache:
+        best = None
+        for gi_ in range(3):
+            cand = [torch.cuda.Stream() for _ in range(S)]
+            holder["sets"] = build_sets(cand)
+            for _ in range(n_sets):
+                sstep()
+            torch.cuda.synchronize()
+            turn[0] = 0
+            probe = timed(sstep, 300, torch) / 300
+            calib[f"group_{gi_}_us_per_step"] = round(1e6 * probe, 2)
+            if best is None or probe < best[0]:
+                best = (probe, cand)
+            holder["sets"] = None
+        streams_cache["streams"] = best[1]
+    streams = streams_cache["streams"] if S > 1 else [torch.cuda.current_stream()]
+    sets = holder["sets"] = build_sets(streams)
+    for _ in range(max(args.warmup, n_sets)):
+        sstep()
+    torch.cuda.synchronize()
+    turn[0] = 0
+    med, mn = timed_regions(sstep, args.steps, args.repeats, torch)
+    if not all(torch.equal(fs.y, fp.y) and int(fs.total.item()) == T for fs, _, _ in sets):
+        print("bench.py: a copy's result differs from the single-stream result", file=sys.stderr)
+        sys.exit(1)
+
+    # per-kernel durations: the copies of the timed region on ONE stream, in rotation (cold)
+    cold_sets = [fs.stages(*ins) for fs, _, ins in sets]
+    times = kernel_times_us(cold_sets, args.steps, torch)
+    warm = {nme: back_to_back_us(fn, max(20, min(args.steps, 200)), torch) for nme, fn in stages}
+    for nme in times:
+        times[nme]["warm_cache_us"] = round(warm[nme], 2)
+    kernels, roof = kernels_block(times, forward_work(wl, T, sum_n2), wl.dtype, wl.name, traffic_table, args.seed)
+    roof["cache"] = f"cold: {n_sets} copies of the batch and its buffers in rotation ({n_sets * set_bytes >> 20} MB)"
+    res = {
+        "workload": f"{wl.name}: B={wl.B} N={wl.N} C={wl.C} H={wl.H} Dh={wl.Dh} {wl.dtype}, selected fraction "
+                    f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward select+pack+attention+unpack",
+        "selected_tokens": T, "sum_n2": sum_n2, "value": T / med, "unit": "selected tokens/s",
+        "ms_per_step": 1e3 * med, "ms_per_step_min": 1e3 * mn, "regions": args.repeats,
+        "launch": f"eager, {len(stages)} launches per step ({' + '.join(n_ for n_, _ in stages)}); {S} independent "
+                  f"batches in flight on {S} HIP stream(s); {n_sets} copies of the inputs and buffers in rotation "
+                  f"({n_sets * set_bytes >> 20} MB, cold last-level cache)",
+        "streams": S, "copies": n_sets, "single_stream": single, "kernels": kernels, "roofline": roof,
+    }
+    if calib:
+        res["stream_group_calibration"] = calib
+    del sets, cold_sets
+    holder["sets"] = None
+    return res, dict(bun=bun, x=x, w=w, qkv=qkv, fp=fp, stages=stages, T=T, n=n, sum_n2=sum_n2, streams=streams)
+
+
+# ------------------------------------------------------------------- forward + backward
+def train_work(B, N, C, H, T, sum_n2, prefix="", bwd_executed_over_algorithmic=1.0):
+    e = 2
+    return {
+        prefix + "gate_select": (0.0, B * N * (C * e + 5)),
+        prefix + "gate_select_pooled": (0.0, B * N * (C * e + 5 + 16)),
+        prefix + "pack_qk_rg": (0.0, 2 * T * 3 * C * e + 8 * T + 5 * B * N + 4 * (B + 1)),
+        prefix + "packed_attention_unpack": (4.0 * C * sum_n2, T * 3 * C * e + B * N * C * e + 4 * T + 4 * B * N
+                                             + 4 * (B + 1) + T * C * e + 4 * H * T),
+        # reads q, k, v, out rows and dy at the selected positions; writes dq | dk and d_rg at ALL token positions
+        prefix + "packed_attention_bwd_tokens": (10.0 * C * sum_n2, 5 * T * C * e + 3 * B * N * C * e + 4 * H * T
+                                                 + 8 * B * N),
+        prefix + "gate_bwd": (0.0, B * N * (3 * C * e + 9) + 8 * C),
+    }
+
+
+def measure_train(args, torch, workloads, TrainPass, traffic_table, streams):
+    """ViT-B-shaped training step: forward + backward with the selection loss, 5 calls."""
+    wl = workloads.WORKLOADS["vit_b_train"]
+    B, N, C, H = wl.B, wl.N, wl.C, wl.H
+    td = torch.bfloat16
+    tb = workloads.generate(wl, args.seed)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(td).contiguous()
+    tx, tw, tqk, tdy = up(tb["x"]), up(tb["w"]), up(tb["qkv"][:, :, :2 * C]), up(tb["dy"])
+    tlab = torch.from_numpy(tb["labels"]).cuda()
+    tp = TrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias)
+    stages = tp.stages(tx, tw, tqk, tlab, tdy)
+
+    def step():
+        for _, fn in stages:
+            fn()
+
+    for _ in range(max(5, args.warmup // 4)):
+        step()
+    torch.cuda.synchronize()
+    T = int(tp.total.item())
+    n = np.diff(tp.cu_seqlens.cpu().numpy()).astype(np.float64)
+    sum_n2 = float((n * n).sum())
+    med, mn = timed_regions(step, args.steps, args.repeats, torch)
+    times = kernel_times_us([stages], args.steps, torch)
+    kernels, roof = kernels_block(times, train_work(B, N, C, H, T, sum_n2), wl.dtype, wl.name, traffic_table, args.seed)
+    res = {"workload": f"vit_b_train: B={B} N={N} C={C} H={H} Dh={wl.Dh} bf16, selected fraction "
+                       f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward + backward with the selection loss",
+           "selected_tokens": T, "sum_n2": sum_n2, "value": T / med, "unit": "selected tokens/s",
+           "ms_per_step": 1e3 * med, "ms_per_step_min": 1e3 * mn, "regions": args.repeats,
+           "launch": f"eager, one stream, {len(stages)} calls per step ({' + '.join(n_ for n_, _ in stages)}), warm cache",
+           "kernels": kernels, "roofline": roof,
+           "attention_bwd_tflops": kernels["packed_attention_bwd_tokens"].get("tflops")}
+    S = len(streams)
+    if S > 1:   # the training step with S batches in flight, like the forward headline
+        tsets = []
+        for s_ in streams:
+            with torch.cuda.stream(s_):
+                tp_s = TrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias)
+                tsets.append((tp_s, tp_s.stages(tx.clone(), tw.clone(), tqk.clone(), tlab.clone(), tdy.clone())))
+        torch.cuda.synchronize()
+        turn = [0]
+
+        def tsstep():
+            for _, fn in tsets[turn[0] % S][1]:
+                fn()
+            turn[0] += 1
+
+        for _ in range(2 * S):
+            tsstep()
+        torch.cuda.synchronize()
+        turn[0] = 0
+        smed, smin = timed_regions(tsstep, args.steps, args.repeats, torch)
+        same = all(torch.equal(ts.dx, tp.dx) and torch.equal(ts.dw, tp.dw) for ts, _ in tsets)
+        res["batches_in_flight"] = {"streams": S, "value": T / smed, "ms_per_step": 1e3 * smed,
+                                    "ms_per_step_min": 1e3 * smin, "gradients_equal_single_stream": bool(same)}
+    return res
+
+
+def measure_hierarchy(args, torch, workloads, HierarchyPass, HierarchyTrainPass, traffic_table):
+    """Four-stage hierarchy (batch 16, 56^2 .. 7^2 tokens, C 96 .. 768): forward chain (12 launches)
+    and forward + backward chain (20 calls); per-kernel rooflines, dominant = the finest stage's."""
+    hb = workloads.generate_hierarchy(args.seed)
+    td = torch.bfloat16
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(td).contiguous()
+    hcfg = [(b_["workload"].B, *b_["workload"].grid, b_["workload"].C, b_["workload"].H, b_["workload"].dtype,
+             b_["workload"].tau, b_["bias"]) for b_ in hb]
+    hx, hw, hq = [up(b_["x"]) for b_ in hb], [up(b_["w"]) for b_ in hb], [up(b_["qkv"]) for b_ in hb]
+    hp = HierarchyPass(hcfg)
+    hstages = hp.stages(hx, hw, hq)
+
+    def hstep():
+        for _, fn in hstages:
+            fn()
+
+    for _ in range(5):
+        hstep()
+    torch.cuda.synchronize()
+    hT = [int(p_.total.item()) for p_ in hp.passes]
+    fmed, fmin = timed_regions(hstep, args.steps, args.repeats, torch)
+    res = {"workload": "hierarchy: B=16, stages of 56^2/28^2/14^2/7^2 tokens, C=96/192/384/768, heads 3/6/12/24 of 32, "
+                       "bf16, every stage's gate takes the finer stage's score map (max-pooled in the gate kernel)",
+           "stages": [b_["workload"].name for b_ in hb], "tokens": [c_[0] * c_[1] * c_[2] for c_ in hcfg],
+           "forward": {"launches": len(hstages), "selected_tokens": hT, "value": sum(hT) / fmed,
+                       "unit": "selected tokens/s", "ms_per_step": 1e3 * fmed, "ms_per_step_min": 1e3 * fmin,
+                       "stage_us": {nme: round(back_to_back_us(fn, max(20, min(args.steps, 100)), torch), 2)
+                                    for nme, fn in hstages}}}
+    htp = HierarchyTrainPass(hcfg)
+    hqk = [up(b_["qkv"][:, :, :2 * b_["workload"].C]) for b_ in hb]
+    hlab = [torch.from_numpy(b_["labels"]).cuda() for b_ in hb]
+    hdy = [up(b_["dy"]) for b_ in hb]
+    htstages = htp.stages(hx, hw, hqk, hlab, hdy)
+
+    def htstep():
+        for _, fn in htstages:
+            fn()
+
+    for _ in range(5):
+        htstep()
+    torch.cuda.synchronize()
+    htT = [int(p_.total.item()) for p_ in htp.passes]
+    med, mn = timed_regions(htstep, args.steps, args.repeats, torch)
+    times = kernel_times_us([htstages], args.steps, torch)
+    work, sum_n2s = {}, []
+    for i, (b_, tp_) in enumerate(zip(hb, htp.passes)):
+        wl_ = b_["workload"]
+        n = np.diff(tp_.cu_seqlens.cpu().numpy()).astype(np.float64)
+        sum_n2s.append(float((n * n).sum()))
+        work.update(train_work(wl_.B, wl_.N, wl_.C, wl_.H, htT[i], sum_n2s[-1], prefix=f"s{i + 1}."))
+    kernels, roof = kernels_block(times, work, "bf16", "hierarchy", traffic_table, args.seed)
+    res.update({"selected_tokens": htT, "sum_n2": sum_n2s, "value": sum(htT) / med, "unit": "selected tokens/s",
+                "ms_per_step": 1e3 * med, "ms_per_step_min": 1e3 * mn, "regions": args.repeats,
+                "launch": f"eager, one stream, {len(htstages)} calls per forward + backward chain, warm cache",
+                "kernels": kernels, "roofline": roof})
+    htpc = HierarchyTrainPass(hcfg, concurrent=True)
+    htcstages = htpc.stages(hx, hw, hqk, hlab, hdy)
+
+    def htcstep():
+        for _, fn in htcstages:
+            fn()
+
+    for _ in range(5):
+        htcstep()
+    torch.cuda.synchronize()
+    cmed, cmin = timed_regions(htcstep, args.steps, args.repeats, torch)
+    res["stream_per_stage"] = {
+        "ms_per_step": 1e3 * cmed, "ms_per_step_min": 1e3 * cmin, "value": sum(htT) / cmed,
+        "gradients_equal_one_stream": bool(all(torch.equal(a_.dx, b_.dx) and torch.equal(a_.dw, b_.dw)
+                                               for a_, b_ in zip(htpc.passes, htp.passes)))}
+    return res
+
+
+# ------------------------------------------------------------------------------- extras
+def measure_extras(wl, ctx, args, torch, spa, workloads, pipeline):
+    """On the headline workload: the four-call form of the boundary, the other forward form, hipGraph
+    replay, the padded-to-max baseline; on the ViT-S-shaped batch the widened rows (block with
+    projections forward and forward + backward, container-local attention)."""
+    out = {}
+    td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    B, N, C, H = wl.B, wl.N, wl.C, wl.H
+    x, w, qkv, fp, T, n, sum_n2 = ctx["x"], ctx["w"], ctx["qkv"], ctx["fp"], ctx["T"], ctx["n"], ctx["sum_n2"]
+    steps = max(20, min(args.steps, 200))
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else FP32_VECTOR_PEAK_TFLOPS
+
+    def run_chain(stages_):
+        def go():
+            for _, fn in stages_:
+                fn()
+        for _ in range(5):
+            go()
+        torch.cuda.synchronize()
+        return timed_regions(go, steps, 5, torch)[0]
+
+    # the hot path as its four calls (gate_select, pack of the rows, packed_attention, unpack), nothing fused
+    fp4 = pipeline.ForwardPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, fused_unpack=False)
+    st4 = fp4.stages(x, w, qkv)
+    med4 = run_chain(st4)
+    work4 = forward_work(wl, T, sum_n2)
+    four = {}
+    for nme, fn in st4:
+        us_ = back_to_back_us(fn, steps, torch)
+        fl, by = work4[nme]
+        four[nme] = {"us": round(us_, 2), "GB/s": round(by / us_ / 1e3, 1),
+                     "hbm_frac": round(by / us_ / 1e3 / HBM_PEAK_GBS, 4)}
+        if fl > 0:
+            four[nme].update({"tflops": round(fl / us_ / 1e6, 2), "mfma_frac": round(fl / us_ / 1e6 / mfma_peak, 4)})
+    out["four_call_form"] = {"ms_per_step": 1e3 * med4, "value": T / med4,
+                             "cache": "warm (one copy of the batch, one stream)",
+                             "y_equals_headline_form": bool(torch.equal(fp4.y, fp.y)), "kernels": four}
+    # the other forward forms (rows copied by the pack launch / fetched through the index / index built by the gate launch)
+    for other in ("fused", "gathered", "packed"):
+        if other == args.form:
+            continue
+        fpo = pipeline.ForwardPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False,
+                                   gathered=other != "packed", fused_index=other == "fused")
+        sto = fpo.stages(x, w, qkv)
+        medo = run_chain(sto)
+        out[f"{other}_form"] = {"ms_per_step": 1e3 * medo, "value": T / medo, "cache": "warm, one stream",
+                                "launches": [n_ for n_, _ in sto], "y_equals_headline_form": bool(torch.equal(fpo.y, fp.y)),
+                                "stage_us": {nme: round(back_to_back_us(fn, steps, torch), 2) for nme, fn in sto}}
+    # the headline step replayed as a hipGraph
+    try:
+        def make_step():
+            st = fp.stages(x, w, qkv)
+            return lambda: [fn() for _, fn in st]
+        gdt = graph_replay_s(make_step, steps, torch)
+        out["graph_replay"] = {"ms_per_step": 1e3 * gdt / steps, "value": T * steps / gdt}
+    except Exception as ex:  # capture refused: report, do not hide
+        out["graph_replay"] = {"error": str(ex)[:200]}
+    # padded-to-max masked attention on the same selected tokens
+    n_max = int(n.max())
+    cu = fp.cu_seqlens.cpu().numpy()
+    gidx = fp.gather_idx.cpu().numpy()
+    flat_qkv = qkv.view(B * N, 3 * C)
+    packed = flat_qkv[torch.from_numpy(gidx[:T].astype(np.int64)).cuda()].contiguous()   # setup of the padded inputs only
+    pad = torch.zeros(B, n_max, 3 * C, dtype=td, device="cuda")
+    for b in range(B):
+        pad[b, :cu[b + 1] - cu[b]] = packed[cu[b]:cu[b + 1]]
+    lens = torch.from_numpy(np.diff(cu).astype(np.int32)).cuda()
+    pout = torch.empty(B, n_max, C, dtype=td, device="cuda")
+    flat = pad.view(B * n_max, 3 * C)
+    pfn = spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], lens, B, n_max, H, wl.Dh, pout,
+                                   prepare=True)
+    lens_full = torch.full((B,), n_max, dtype=torch.int32, device="cuda")
+    dfn = spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], lens_full, B, n_max, H, wl.Dh, pout,
+                                   prepare=True)
+    aout = torch.empty(B * N, C, dtype=td, device="cuda")
+    afn = spa.spa_packed_attention(packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:], fp.cu_seqlens, B, N, H, wl.Dh,
+                                   aout, None, prepare=True)
+    for f_ in (pfn, dfn, afn):
+        f_()
+    pus, dus, aus = (back_to_back_us(f_, steps, torch) for f_ in (pfn, dfn, afn))
+    out["padded_baseline"] = {
+        "n_max": n_max, "packed_attention_us": round(aus, 2),
+        "padded_dense_us": round(dus, 2), "speedup_over_padded_dense": round(dus / aus, 3),
+        "padded_dense": "every image padded to n_max queries AND n_max keys (B n_max^2 scores): what padding to the "
+                        "batch maximum costs",
+        "work_ratio_B_nmax2_over_sum_n2": round(B * n_max * n_max / sum_n2, 3),
+        "padded_skipping_masked_keys_us": round(pus, 2), "speedup_over_padded_skipping": round(pus / aus, 3),
+        "padded_skipping_masked_keys": "n_max queries per image, but keys past the image's length are skipped instead "
+                                       "of masked (sum n_max n_b scores): a length-aware padded kernel",
+        "work_ratio_nmax_sum_n_over_sum_n2": round(n_max * float(n.sum()) / sum_n2, 3)}
+    if wl.dtype != "bf16":
+        return out
+
+    # widened rows, on the ViT-S-shaped batch (their shapes are the classification ones)
+    vwl = workloads.WORKLOADS["vit_s"]
+    vb = workloads.generate(vwl, args.seed)
+    vup = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(torch.bfloat16).contiguous()
+    vx, vw, vqkv = vup(vb["x"]), vup(vb["w"]), vup(vb["qkv"])
+    VB, VN, VC, VH = vwl.B, vwl.N, vwl.C, vwl.H
+    g = torch.Generator(device="cpu").manual_seed(args.seed + 17)
+    mkw = lambda r, c: (torch.randn(r, c, generator=g) / c ** 0.5).cuda().to(torch.bfloat16)
+    W_qkv, b_qkv, W_o, b_o = mkw(3 * VC, VC), mkw(1, 3 * VC).view(-1), mkw(VC, VC), mkw(1, VC).view(-1)
+    bp = pipeline.BlockPass(VB, VN, VC, VH, "bf16", vwl.tau, vwl.bias)
+    bstages = bp.stages(vx, vw, W_qkv, b_qkv, W_o, b_o)
+    bmed = run_chain(bstages)
+    vT = int(bp.total.item())
+    bus = {nme: back_to_back_us(fn, steps, torch) for nme, fn in bstages}
+    out["block_with_projections"] = {
+        "workload": "vit_s", "launches": [n_ for n_, _ in bstages], "value": vT / bmed, "unit": "selected tokens/s",
+        "ms_per_step": 1e3 * bmed, "stage_us": {k_: round(v_, 2) for k_, v_ in bus.items()},
+        "qkv_projection_tflops": round(2.0 * vT * VC * 3 * VC / bus["qkv_projection"] / 1e6, 1),
+        "out_projection_tflops": round(2.0 * vT * VC * VC / bus["out_projection"] / 1e6, 1),
+        "dense_projection_flops_saved": round(1.0 - vT / (VB * VN), 3)}
+    dy_blk = torch.randn(VB, VN, VC, generator=g).cuda().to(torch.bfloat16)
+    lab_blk = torch.from_numpy(vb["labels"]).cuda()
+    blk_train = {}
+    for key, ov in (("two_streams", True), ("one_stream", False)):
+        btp = pipeline.BlockTrainPass(VB, VN, VC, VH, "bf16", vwl.tau, vwl.bias, overlap_weight_grads=ov)
+        tst = btp.stages(vx, vw, W_qkv, b_qkv, W_o, b_o, lab_blk, dy_blk)
+        tmed = run_chain(tst)
+        blk_train[key] = {"ms_per_step": 1e3 * tmed, "value": vT / tmed, "unit": "selected tokens/s"}
+        if not ov:
+            blk_train[key]["launches"] = [n_ for n_, _ in tst]
+            blk_train[key]["stage_us"] = {nme: round(back_to_back_us(fn, steps, torch), 2) for nme, fn in tst}
+    out["block_with_projections"]["fwd_bwd"] = blk_train
+    # the paper's container mask: containers of L = 7^2 tokens, map shifted by (3, 3)
+    side = int(round(VN ** 0.5))
+    cp = pipeline.ContainerForwardPass(VB, side, side, VC, VH, "bf16", 49, (3, 3), vwl.tau, vwl.bias)
+    cstages = cp.stages(vx, vw, vqkv)
+    cmed = run_chain(cstages)
+    cus = {nme: back_to_back_us(fn, steps, torch) for nme, fn in cstages}
+    seg = cp.seg_cu_seqlens.cpu().numpy().astype(np.float64)
+    seg_n2 = float((np.diff(seg) ** 2).sum())
+    out["container_local"] = {
+        "workload": "vit_s", "container_len": 49, "shift": [3, 3], "segments": int(cp.n_segments.item()),
+        "segment_capacity": cp.seg_cap, "sum_n2": seg_n2, "value": vT / cmed, "unit": "selected tokens/s",
+        "ms_per_step": 1e3 * cmed, "stage_us": {k_: round(v_, 2) for k_, v_ in cus.items()},
+        "attention_tflops": round(4.0 * VC * seg_n2 / cus["segment_attention_unpack"] / 1e6, 2)}
+    return out
 
 
 def cpu_oracle_baseline(wl, bundle, seconds):
@@ -192,24 +670,12 @@ def main():
               file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2410_23608_amd import spa, workloads
-    from paper_2410_23608_amd.pipeline import ForwardPass, TrainPass
+    from paper_2410_23608_amd import pipeline, spa, workloads
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    wl = workloads.WORKLOADS[args.workload]
-    e = 2 if wl.dtype == "bf16" else 4
-    td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
-    bun = workloads.generate(wl, args.seed)
-
-    def up(a, dtype=None):
-        """Host array -> device tensor in the dtype of the workload it is uploaded FOR (the
-        headline workload's unless another one is named)."""
-        t_ = td if dtype is None else (torch.bfloat16 if dtype == "bf16" else torch.float32)
-        return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(t_).contiguous()
-
     if args.calibration_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -218,511 +684,53 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    x, w, qkv = up(bun["x"]), up(bun["w"]), up(bun["qkv"])
-    # forward only: y is the result; the packed attention output and lse (inputs of a backward
-    # pass) are not written
-    fp = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False)
-    stages = fp.stages(x, w, qkv)
-
-    def step():
-        for _, fn in stages:
-            fn()
-
-    for _ in range(max(args.warmup, 1)):
-        step()
-    torch.cuda.synchronize()
-    T = int(fp.total.item())
-    n = np.diff(fp.cu_seqlens.cpu().numpy()).astype(np.float64)
-    sum_n2 = float((n * n).sum())
-
-    # ---- one stream, steps back to back on ONE copy of the batch (everything stays in the
-    # 256 MB last-level cache): the latency of a step
-    dt1 = timed(step, args.steps, torch)
-    single = {"ms_per_step": 1e3 * dt1 / args.steps, "value": T * args.steps / dt1, "unit": "selected tokens/s",
-              "cache": "warm (one copy of the batch, reused every step)"}
-
-    # ---- the timed region: exactly K steps.  The batches of a data-parallel job are independent,
-    # so S of them are kept in flight: S HIP streams (default priority), steps dealt round-robin,
-    # the launches of a step in order on their stream.  Every step works on its own copy of the
-    # inputs and its own buffers, and there are enough copies (> 512 MB in total) that no step
-    # finds its inputs or a previous step's buffers in the last-level cache.
-    S = max(1, args.streams)
-    set_bytes = (x.numel() + qkv.numel() + fp.packed_qkv.numel() + fp.y.numel()) * e
-    n_sets = S * max(2, -(-(512 << 20) // (S * set_bytes)))
-    turn = [0]
-
-    def build_sets(streams_):
-        made = []
-        for i in range(n_sets):
-            with torch.cuda.stream(streams_[i % S]):
-                fp_s = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False)
-                ins = (x.clone(), w.clone(), qkv.clone())
-                made.append((fp_s, fp_s.stages(*ins), ins))
-        torch.cuda.synchronize()
-        return made
-
-    def sstep():   # step i -> copy i % n_sets, which lives on stream i % S
-        for _, fn in sets[turn[0] % n_sets][1]:
-            fn()
-        turn[0] += 1
-
-    # Which HIP streams end up sharing one of the process's hardware queues (4 here) is the
-    # runtime's business, and two batches on one queue run one after the other.  So three groups of
-    # S streams are tried for a few hundred untimed steps each and the fastest group is kept.
-    stream_groups = {}
-    if S > 1:
-        best = None
-        for gi_ in range(3):
-            cand = [torch.cuda.Stream() for _ in range(S)]
-            sets = build_sets(cand)
-            for _ in range(n_sets):
-                sstep()
-            torch.cuda.synchronize()
-            turn[0] = 0
-            probe = timed(sstep, 300, torch) / 300
-            stream_groups[f"group_{gi_}_us_per_step"] = round(1e6 * probe, 2)
-            if best is None or probe < best[0]:
-                best = (probe, cand, sets)
-            del sets
-        _, streams, sets = best
-        del best
-    else:
-        streams = [torch.cuda.current_stream()]
-        sets = build_sets(streams)
-
-    for _ in range(max(args.warmup, n_sets)):
-        sstep()
-    torch.cuda.synchronize()
-    turn[0] = 0
-    dt = timed(sstep, args.steps, torch)
-    if not all(torch.equal(fs.y, fp.y) and int(fs.total.item()) == T for fs, _, _ in sets):
-        print("bench.py: a copy's result differs from the single-stream result", file=sys.stderr)
-        sys.exit(1)
-    ms_per_step = 1e3 * dt / args.steps
-    value = T * args.steps / dt
-
-    # ---- per-kernel durations, live, events on the launch stream, the kernel running alone.
-    # cold: the copies of the timed region on ONE stream, in rotation; warm: one copy reused.
-    cold_sets = [fs.stages(*ins) for fs, _, ins in sets]   # the same launches, prepared on this stream
-    st_us = per_stage_us(cold_sets, args.steps, torch)
-    b2b_us = {nme: back_to_back_us([cs[i][1] for cs in cold_sets], args.steps, torch)
-              for i, (nme, _) in enumerate(stages)}
-    warm_us = {nme: min(v_, back_to_back_us(fn, args.steps, torch))
-               for (nme, fn), v_ in zip(stages, per_stage_us([stages], args.steps, torch).values())}
-    ev_overhead = empty_pair_us(stages, args.steps, torch)
-    B, N, C, H = wl.B, wl.N, wl.C, wl.H
-    attn_flops = 4.0 * C * sum_n2
-    work = {  # algorithmic (flops, bytes) per launch
-        "gate_select": (0.0, B * N * (C * e + 5)),
-        "pack": (0.0, 2 * T * 3 * C * e + 4 * T + 5 * B * N + 4 * (B + 1)),
-        "packed_attention": (attn_flops, T * 3 * C * e + T * C * e + 4 * H * T + 4 * (B + 1)),
-        # attention + scatter back in one launch: q|k|v rows in, every row of y out, the index arrays
-        "packed_attention_unpack": (attn_flops, T * 3 * C * e + B * N * C * e + 4 * T + 4 * B * N + 4 * (B + 1)
-                                    + (T * C * e + 4 * H * T if fp.keep_packed_out else 0)),
-        "unpack": (0.0, T * C * e + 4 * B * N + B * N * C * e),
-    }
-    work = {k_: v_ for k_, v_ in work.items() if k_ in st_us}
-    mfma_peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else 157.3
-    ridge = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9)     # flop per byte at which the two roofs meet
-    kernels = {}
-    for nme, (flops, nbytes) in work.items():
-        # Two live readings, both with HIP events on the launch stream and both upper bounds of
-        # the kernel's duration: an event pair around each launch inside K steps of the whole
-        # path (includes the cost of the two markers; an empty pair reads ev_overhead) and K
-        # back-to-back launches of the kernel between one pair (includes the dispatch gap).
-        # The smaller one is used; rocprofv3's kernel-trace average sits a little below it.
-        us = min(st_us[nme], b2b_us[nme])
-        intensity = flops / nbytes
-        # the roof that bounds the kernel: below the ridge the HBM roof is the lower one
-        if intensity < ridge:
-            bound, ach, peak, unit = "hbm", nbytes / us / 1e3, HBM_PEAK_GBS, "GB/s"
+    traffic_table = load_traffic_table()
+    streams_cache = {}
+    fwd = lambda name: measure_forward(workloads.WORKLOADS[name], args, torch, workloads, pipeline.ForwardPass,
+                                       traffic_table, streams_cache)
+    if args.only is not None:      # one chain only (profiling runs): a short line, same fields
+        if args.only in ("forward", "vit_s", "det"):
+            res, _ = fwd(args.workload if args.only == "forward" else args.only)
+        elif args.only == "vit_b_train":
+            res = measure_train(args, torch, workloads, pipeline.TrainPass, traffic_table, [torch.cuda.current_stream()])
         else:
-            bound, ach, peak, unit = "mfma" if wl.dtype == "bf16" else "alu", flops / us / 1e6, mfma_peak, "TFLOP/s"
-        kernels[nme] = {"bound": bound, "cache": "cold", "event_us": round(st_us[nme], 2), "kernel_us": round(us, 2),
-                        "back_to_back_us": round(b2b_us[nme], 2), "warm_cache_us": round(warm_us[nme], 2),
-                        "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
-                        "algorithmic_bytes": int(nbytes), "algorithmic_flops": flops,
-                        "flop_per_byte": round(intensity, 1), "ridge_flop_per_byte": round(ridge, 1)}
-        if flops > 0:
-            kernels[nme]["tflops"] = round(flops / us / 1e6, 2)
-            kernels[nme]["mfma_frac"] = round(flops / us / 1e6 / mfma_peak, 4)
-    dom = max(kernels, key=lambda k_: kernels[k_]["kernel_us"])
-    kd = kernels[dom]
+            res = measure_hierarchy(args, torch, workloads, pipeline.HierarchyPass, pipeline.HierarchyTrainPass,
+                                    traffic_table)
+        print(json.dumps({"only": args.only, **res}))
+        return
+
+    wl = workloads.WORKLOADS[args.workload]
+    head, ctx = fwd(args.workload)
+    configs = {args.workload: head}
+    if wl.dtype == "bf16":
+        for name in ("vit_s", "det"):
+            if name not in configs:
+                configs[name], _ = fwd(name)
+        configs["vit_b_train"] = measure_train(args, torch, workloads, pipeline.TrainPass, traffic_table, ctx["streams"])
+        configs["hierarchy"] = measure_hierarchy(args, torch, workloads, pipeline.HierarchyPass,
+                                                 pipeline.HierarchyTrainPass, traffic_table)
     ceil_ = ceilings(spa, torch)
-    measured_ceiling = ceil_["copy_GBs"] if kd["bound"] == "hbm" else ceil_["mfma_bf16_TFLOPs"]
-    roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
-                "unit": kd["unit"], "frac": kd["frac"],
-                "cache": f"cold: {n_sets} copies of the batch and its buffers in rotation ({n_sets * set_bytes >> 20} MB)",
-                "warm_cache_frac": round(kd["frac"] * kd["kernel_us"] / kd["warm_cache_us"], 4),
-                "measured_ceiling": measured_ceiling,
-                "frac_of_measured_ceiling": round(kd["achieved"] / measured_ceiling, 4) if kd["bound"] != "alu" else None,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)) if args.seed == 0 else None,
-                "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
-                "avg_launch_us": kd["kernel_us"],
-                "event_pair_overhead_us": round(ev_overhead, 2)}
-    if "tflops" in kd:
-        roofline.update({"flop_per_byte": kd["flop_per_byte"], "ridge_flop_per_byte": kd["ridge_flop_per_byte"],
-                         "tflops": kd["tflops"], "mfma_frac": kd["mfma_frac"]})
+    roof = dict(head["roofline"])
+    measured = ceil_["copy_GBs"] if roof["bound"] == "hbm" else ceil_["mfma_bf16_TFLOPs"]
+    roof["measured_ceiling"] = measured
+    roof["frac_of_measured_ceiling"] = round(roof["achieved"] / measured, 4) if roof["bound"] != "alu" else None
 
     result = {
-        "metric": "selected tokens/sec (SPA fwd) at 1 GPU", "value": value, "unit": "selected tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "selected tokens/sec (SPA fwd) at 1 GPU", "value": head["value"], "unit": "selected tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: B={B} N={N} C={C} H={H} Dh={wl.Dh} {wl.dtype}, selected fraction "
-                               f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward select+pack+attention+unpack",
-                   "selected_tokens": T, "sum_n2": sum_n2, "seed": args.seed,
-                   "launch": f"eager, {len(stages)} launches per step ({' + '.join(n_ for n_, _ in stages)}); "
-                             f"{S} independent batches in flight on {S} HIP stream(s); {n_sets} copies of the "
-                             f"inputs and buffers in rotation ({n_sets * set_bytes >> 20} MB, cold last-level cache)",
-                   "streams": S, "copies": n_sets, "stream_group_calibration": stream_groups},
-        "single_stream": single,
-        "roofline": roofline, "ceilings": ceil_, "kernels": kernels,
+        "config": {"workload": head["workload"], "selected_tokens": head["selected_tokens"], "sum_n2": head["sum_n2"],
+                   "seed": args.seed, "launch": head["launch"], "streams": head["streams"], "copies": head["copies"],
+                   "timing": f"median over {args.repeats} repeats of the {args.steps}-step region (min: "
+                             f"{head['ms_per_step_min'] * 1e3:.2f} us per step)"},
+        "ms_per_step_min": head["ms_per_step_min"], "single_stream": head["single_stream"],
+        "roofline": roof, "ceilings": ceil_, "kernels": head["kernels"], "configs": configs,
     }
-
     if not args.no_extras:
-        # the hot path as its four calls (gate_select, pack, packed_attention, unpack), the last two NOT
-        # fused: warm back-to-back launch times and the roofline fraction of each kernel on its own
-        fp4 = ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, fused_unpack=False)
-        st4 = fp4.stages(x, w, qkv)
-
-        def step4():
-            for _, fn in st4:
-                fn()
-
-        for _ in range(5):
-            step4()
-        torch.cuda.synchronize()
-        dt4 = timed(step4, args.steps, torch)
-        us4 = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in st4}
-        all_work = {"gate_select": (0.0, B * N * (C * e + 5)),
-                    "pack": (0.0, 2 * T * 3 * C * e + 4 * T + 5 * B * N + 4 * (B + 1)),
-                    "packed_attention": (attn_flops, T * 3 * C * e + T * C * e + 4 * H * T + 4 * (B + 1)),
-                    "unpack": (0.0, T * C * e + 4 * B * N + B * N * C * e)}
-        four = {}
-        for nme, us_ in us4.items():
-            fl, by = all_work[nme]
-            four[nme] = {"us": round(us_, 2), "GB/s": round(by / us_ / 1e3, 1), "hbm_frac": round(by / us_ / 1e3 / HBM_PEAK_GBS, 4)}
-            if fl > 0:
-                four[nme].update({"tflops": round(fl / us_ / 1e6, 2), "mfma_frac": round(fl / us_ / 1e6 / mfma_peak, 4)})
-        result["four_call_form"] = {"ms_per_step": 1e3 * dt4 / args.steps, "value": T * args.steps / dt4,
-                                    "cache": "warm (one copy of the batch, one stream)",
-                                    "y_equals_fused_form": bool(torch.equal(fp4.y, fp.y)), "kernels": four}
-
-        # the same step replayed as a hipGraph
-        try:
-            def make_step():
-                st = fp.stages(x, w, qkv)
-                return lambda: [fn() for _, fn in st]
-            gdt = graph_replay_s(make_step, args.steps, torch)
-            result["graph_replay"] = {"ms_per_step": 1e3 * gdt / args.steps, "value": T * args.steps / gdt}
-        except Exception as ex:  # capture refused: report, do not hide
-            result["graph_replay"] = {"error": str(ex)[:200]}
-        # padded-to-max masked attention on the same selected tokens
-        n_max = int(n.max())
-        pad = torch.zeros(B, n_max, 3 * C, dtype=td, device="cuda")
-        cu = fp.cu_seqlens.cpu().numpy()
-        for b in range(B):
-            pad[b, :cu[b + 1] - cu[b]] = fp.packed_qkv[cu[b]:cu[b + 1]]
-        lens = torch.from_numpy(np.diff(cu).astype(np.int32)).cuda()
-        pout = torch.empty(B, n_max, C, dtype=td, device="cuda")
-        flat = pad.view(B * n_max, 3 * C)
-        pfn = spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], lens, B, n_max, H, wl.Dh, pout,
-                                       prepare=True)
-        # the cost of padding itself: every image carries n_max keys (timing only: the mask of a
-        # dense masked kernel adds a compare/select per score on top of this)
-        lens_full = torch.full((B,), n_max, dtype=torch.int32, device="cuda")
-        dfn = spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], lens_full, B, n_max, H, wl.Dh,
-                                       pout, prepare=True)
-        pfn()
-        dfn()
-        pus = back_to_back_us(pfn, args.steps, torch)
-        dus = back_to_back_us(dfn, args.steps, torch)
-        afn = spa.spa_packed_attention(fp.packed_qkv[:, :C], fp.packed_qkv[:, C:2 * C], fp.packed_qkv[:, 2 * C:],
-                                       fp.cu_seqlens, B, N, H, wl.Dh, fp.out, None, prepare=True)
-        aus = back_to_back_us(afn, args.steps, torch)
-        result["padded_baseline"] = {
-            "n_max": n_max, "packed_attention_us": round(aus, 2),
-            "padded_dense_us": round(dus, 2), "speedup_over_padded_dense": round(dus / aus, 3),
-            "padded_dense": "every image padded to n_max queries AND n_max keys (B n_max^2 scores): what padding to "
-                            "the batch maximum costs",
-            "work_ratio_B_nmax2_over_sum_n2": round(B * n_max * n_max / sum_n2, 3),
-            "padded_skipping_masked_keys_us": round(pus, 2), "speedup_over_padded_skipping": round(pus / aus, 3),
-            "padded_skipping_masked_keys": "n_max queries per image, but keys past the image's length are skipped "
-                                           "instead of masked (sum n_max n_b scores): a length-aware padded kernel",
-            "work_ratio_nmax_sum_n_over_sum_n2": round(n_max * float(n.sum()) / sum_n2, 3)}
-        # forward + backward training step, ViT-B-shaped
-        twl = workloads.WORKLOADS["vit_b_train"]
-        tb = workloads.generate(twl, args.seed)
-        tp = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias)
-        tx, tw = up(tb["x"], twl.dtype), up(tb["w"], twl.dtype)
-        tqk = up(tb["qkv"][:, :, :2 * twl.C], twl.dtype)
-        tdy = up(tb["dy"], twl.dtype)
-        tlab = torch.from_numpy(tb["labels"]).cuda()
-        tstages = tp.stages(tx, tw, tqk, tlab, tdy)
-
-        def tstep():
-            for _, fn in tstages:
-                fn()
-
-        for _ in range(5):
-            tstep()
-        torch.cuda.synchronize()
-        tT = int(tp.total.item())
-        tn = np.diff(tp.cu_seqlens.cpu().numpy()).astype(np.float64)
-        tdt = timed(tstep, args.steps, torch)
-        tus = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in tstages}
-        bwd_flops = 10.0 * twl.C * float((tn * tn).sum())
-        result["fwd_bwd"] = {"workload": "vit_b_train: B=64 N=196 C=768 H=12 bf16, fwd+bwd with selection loss",
-                             "value": tT * args.steps / tdt, "unit": "selected tokens/s",
-                             "ms_per_step": 1e3 * tdt / args.steps, "selected_tokens": tT,
-                             "stage_us": {k_: round(v_, 2) for k_, v_ in tus.items()},
-                             "attention_bwd_tflops": round(bwd_flops / tus["packed_attention_bwd_tokens"] / 1e6, 2)}
-        # the same step with the gather of dy and the scatters of dq, dk, dv as separate launches (9 launches)
-        tp9 = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias, fused_bwd=False, pack_pair=False)
-        t9 = tp9.stages(tx, tw, tqk, tlab, tdy)
-
-        def t9step():
-            for _, fn in t9:
-                fn()
-
-        for _ in range(5):
-            t9step()
-        torch.cuda.synchronize()
-        t9dt = timed(t9step, args.steps, torch)
-        t9us = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in t9}
-        result["fwd_bwd"]["separate_gather_scatter"] = {
-            "ms_per_step": 1e3 * t9dt / args.steps, "launches": len(t9),
-            "gradients_equal": bool(torch.equal(tp9.dx, tp.dx) and torch.equal(tp9.dqk, tp.dqk) and torch.equal(tp9.dw, tp.dw)),
-            "stage_us": {k_: round(t9us[k_], 2) for k_ in ("unpack_bwd", "packed_attention_bwd", "pack_bwd_v", "pack_bwd_qk")}}
-        if S > 1:   # the training step with S batches in flight, like the forward headline
-            tsets = []
-            for s_ in streams:
-                with torch.cuda.stream(s_):
-                    tp_s = TrainPass(twl.B, twl.N, twl.C, twl.H, twl.dtype, twl.tau, twl.bias)
-                    tsets.append((tp_s, tp_s.stages(tx.clone(), tw.clone(), tqk.clone(), tlab.clone(), tdy.clone())))
-            torch.cuda.synchronize()
-            turn[0] = 0
-
-            def tsstep():
-                for _, fn in tsets[turn[0] % S][1]:
-                    fn()
-                turn[0] += 1
-
-            for _ in range(2 * S):
-                tsstep()
-            torch.cuda.synchronize()
-            turn[0] = 0
-            tsdt = timed(tsstep, args.steps, torch)
-            same = all(torch.equal(ts.dx, tp.dx) and torch.equal(ts.dw, tp.dw) for ts, _ in tsets)
-            result["fwd_bwd"]["batches_in_flight"] = {"streams": S, "value": tT * args.steps / tsdt,
-                                                      "ms_per_step": 1e3 * tsdt / args.steps,
-                                                      "gradients_equal_single_stream": bool(same)}
-        # the same step with stochastic Gumbel-Softmax selection and the straight-through backward
-        gn = torch.from_numpy(np.random.default_rng(args.seed + 5).logistic(size=(twl.B, twl.N)).astype(np.float32)).cuda()
-        gstages = tp.stages(tx, tw, tqk, tlab, tdy, noise=gn, temperature=1.0)
-
-        def gstep():
-            for _, fn in gstages:
-                fn()
-
-        for _ in range(5):
-            gstep()
-        torch.cuda.synchronize()
-        gT = int(tp.total.item())
-        gdt2 = timed(gstep, args.steps, torch)
-        result["fwd_bwd_gumbel"] = {"selected_tokens": gT, "value": gT * args.steps / gdt2, "unit": "selected tokens/s",
-                                    "ms_per_step": 1e3 * gdt2 / args.steps,
-                                    "stage_us": {nme: round(back_to_back_us(fn, args.steps, torch), 2)
-                                                 for nme, fn in (gstages[0], gstages[-1])}}
-
-        # the block with its projections: only selected tokens are projected
-        from paper_2410_23608_amd.pipeline import BlockPass
-        g = torch.Generator(device="cpu").manual_seed(args.seed + 17)
-        mkw = lambda r, c: (torch.randn(r, c, generator=g) / c ** 0.5).cuda().to(td)
-        W_qkv, b_qkv, W_o, b_o = mkw(3 * C, C), mkw(1, 3 * C).view(-1), mkw(C, C), mkw(1, C).view(-1)
-        bp = BlockPass(B, N, C, H, wl.dtype, wl.tau, wl.bias)
-        bstages = bp.stages(x, w, W_qkv, b_qkv, W_o, b_o)
-
-        def bstep():
-            for _, fn in bstages:
-                fn()
-
-        for _ in range(5):
-            bstep()
-        torch.cuda.synchronize()
-        bdt = timed(bstep, args.steps, torch)
-        bus = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in bstages}
-        result["block_with_projections"] = {
-            "launches": [n_ for n_, _ in bstages], "value": T * args.steps / bdt, "unit": "selected tokens/s",
-            "ms_per_step": 1e3 * bdt / args.steps, "stage_us": {k_: round(v_, 2) for k_, v_ in bus.items()},
-            "qkv_projection_tflops": round(2.0 * T * C * 3 * C / bus["qkv_projection"] / 1e6, 1),
-            "out_projection_tflops": round(2.0 * T * C * C / bus["out_projection"] / 1e6, 1),
-            "dense_projection_flops_saved": round(1.0 - T / (B * N), 3)}
-        # the block forward + backward with its projections (input-side and weight-side GEMMs of both
-        # projections, attention backward, gate backward with the selection loss)
-        from paper_2410_23608_amd.pipeline import BlockTrainPass
-        dy_blk = torch.randn(B, N, C, generator=g).cuda().to(td)
-        lab_blk = torch.from_numpy(bun["labels"]).cuda()
-        blk_train = {}
-        for key, ov in (("two_streams", True), ("one_stream", False)):
-            btp = BlockTrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, overlap_weight_grads=ov)
-            tst = btp.stages(x, w, W_qkv, b_qkv, W_o, b_o, lab_blk, dy_blk)
-
-            def tstep():
-                for _, fn in tst:
-                    fn()
-
-            for _ in range(5):
-                tstep()
-            torch.cuda.synchronize()
-            tdt = timed(tstep, args.steps, torch)
-            blk_train[key] = {"ms_per_step": 1e3 * tdt / args.steps, "value": T * args.steps / tdt,
-                              "unit": "selected tokens/s"}
-            if not ov:
-                tus = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in tst}
-                gemm = {"qkv_projection_bwd_input": 3, "qkv_projection_bwd_weight": 3, "out_projection_bwd_input": 1,
-                        "out_projection_bwd_weight": 1}
-                blk_train[key]["launches"] = [n_ for n_, _ in tst]
-                blk_train[key]["stage_us"] = {k_: round(v_, 2) for k_, v_ in tus.items()}
-                blk_train[key]["gemm_tflops"] = {k_: round(2.0 * T * C * m_ * C / tus[k_] / 1e6, 1) for k_, m_ in gemm.items()}
-        if S > 1:   # independent batches in flight, one stream each, like the forward headline
-            bsets = []
-            for s_ in streams:
-                with torch.cuda.stream(s_):
-                    b_s = BlockTrainPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, overlap_weight_grads=False)
-                    bsets.append((b_s, b_s.stages(x.clone(), w.clone(), W_qkv.clone(), b_qkv.clone(), W_o.clone(),
-                                                  b_o.clone(), lab_blk.clone(), dy_blk.clone())))
-            torch.cuda.synchronize()
-            turn[0] = 0
-
-            def bsstep():
-                for _, fn in bsets[turn[0] % S][1]:
-                    fn()
-                turn[0] += 1
-
-            for _ in range(2 * S):
-                bsstep()
-            torch.cuda.synchronize()
-            turn[0] = 0
-            bsdt = timed(bsstep, args.steps, torch)
-            blk_train["batches_in_flight"] = {
-                "streams": S, "ms_per_step": 1e3 * bsdt / args.steps, "value": T * args.steps / bsdt,
-                "gradients_equal_single_stream": bool(all(torch.equal(b_.dW_qkv, btp.dW_qkv) and torch.equal(b_.dx, btp.dx)
-                                                          for b_, _ in bsets))}
-        result["block_with_projections"]["fwd_bwd"] = blk_train
-
-        # the paper's container mask: containers of L = 7^2 tokens, map shifted by (3, 3)
-        side = int(round(N ** 0.5))
-        if side * side == N:
-            from paper_2410_23608_amd.pipeline import ContainerForwardPass
-            cp = ContainerForwardPass(B, side, side, C, H, wl.dtype, 49, (3, 3), wl.tau, wl.bias)
-            cstages = cp.stages(x, w, qkv)
-
-            def cstep():
-                for _, fn in cstages:
-                    fn()
-
-            for _ in range(5):
-                cstep()
-            torch.cuda.synchronize()
-            cdt = timed(cstep, args.steps, torch)
-            cus = {nme: back_to_back_us(fn, args.steps, torch) for nme, fn in cstages}
-            seg = cp.seg_cu_seqlens.cpu().numpy().astype(np.float64)
-            seg_n2 = float((np.diff(seg) ** 2).sum())
-            result["container_local"] = {
-                "container_len": 49, "shift": [3, 3], "segments": int(cp.n_segments.item()),
-                "segment_capacity": cp.seg_cap, "sum_n2": seg_n2, "value": T * args.steps / cdt,
-                "unit": "selected tokens/s", "ms_per_step": 1e3 * cdt / args.steps,
-                "stage_us": {k_: round(v_, 2) for k_, v_ in cus.items()},
-                "attention_tflops": round(4.0 * C * seg_n2 / cus["segment_attention_unpack"] / 1e6, 2)}
-            cp2 = ContainerForwardPass(B, side, side, C, H, wl.dtype, 49, (3, 3), wl.tau, wl.bias, fused_unpack=False)
-            c2 = cp2.stages(x, w, qkv)
-
-            def c2step():
-                for _, fn in c2:
-                    fn()
-
-            for _ in range(5):
-                c2step()
-            torch.cuda.synchronize()
-            c2dt = timed(c2step, args.steps, torch)
-            result["container_local"]["separate_unpack"] = {
-                "outputs_equal": bool(torch.equal(cp2.y, cp.y)), "ms_per_step": 1e3 * c2dt / args.steps,
-                "launches": [n_ for n_, _ in c2]}
-
-        # four-stage hierarchy (batch 16, 56^2 .. 7^2 tokens, C 96 .. 768): 12 launches, eager and as one hipGraph
-        from paper_2410_23608_amd.pipeline import HierarchyPass
-        hb = workloads.generate_hierarchy(args.seed)
-        hcfg = [(b_["workload"].B, *b_["workload"].grid, b_["workload"].C, b_["workload"].H, b_["workload"].dtype,
-                 b_["workload"].tau, b_["bias"]) for b_ in hb]
-        hp = HierarchyPass(hcfg)
-        hdt_ = [b_["workload"].dtype for b_ in hb]
-        hx = [up(b_["x"], d_) for b_, d_ in zip(hb, hdt_)]
-        hw = [up(b_["w"], d_) for b_, d_ in zip(hb, hdt_)]
-        hq = [up(b_["qkv"], d_) for b_, d_ in zip(hb, hdt_)]
-        hstages = hp.stages(hx, hw, hq)
-
-        def hstep():
-            for _, fn in hstages:
-                fn()
-
-        for _ in range(5):
-            hstep()
-        torch.cuda.synchronize()
-        hT = [int(p_.total.item()) for p_ in hp.passes]
-        hdt = timed(hstep, args.steps, torch)
-        hres = {"stages": [b_["workload"].name for b_ in hb], "launches": len(hstages), "selected_tokens": hT,
-                "tokens": [c_[0] * c_[1] * c_[2] for c_ in hcfg], "ms_per_chain": 1e3 * hdt / args.steps,
-                "value": sum(hT) * args.steps / hdt, "unit": "selected tokens/s",
-                "stage_us": {nme: round(back_to_back_us(fn, args.steps, torch), 2) for nme, fn in hstages}}
-        try:
-            def make_hstep():
-                st_ = hp.stages(hx, hw, hq)
-                return lambda: [fn() for _, fn in st_]
-            ghdt = graph_replay_s(make_hstep, args.steps, torch)
-            hres["graph_replay_ms_per_chain"] = 1e3 * ghdt / args.steps
-        except Exception as ex:
-            hres["graph_replay_error"] = str(ex)[:200]
-        # the same hierarchy forward + backward (20 calls)
-        from paper_2410_23608_amd.pipeline import HierarchyTrainPass
-        htp = HierarchyTrainPass(hcfg)
-        hqk = [up(b_["qkv"][:, :, :2 * b_["workload"].C], b_["workload"].dtype) for b_ in hb]
-        hlab = [torch.from_numpy(b_["labels"]).cuda() for b_ in hb]
-        hdy = [up(b_["dy"], b_["workload"].dtype) for b_ in hb]
-        htstages = htp.stages(hx, hw, hqk, hlab, hdy)
-
-        def htstep():
-            for _, fn in htstages:
-                fn()
-
-        for _ in range(5):
-            htstep()
-        torch.cuda.synchronize()
-        htT = [int(p_.total.item()) for p_ in htp.passes]
-        htdt = timed(htstep, args.steps, torch)
-        hres["fwd_bwd"] = {"launches": len(htstages), "selected_tokens": htT, "ms_per_chain": 1e3 * htdt / args.steps,
-                           "value": sum(htT) * args.steps / htdt, "unit": "selected tokens/s"}
-        htpc = HierarchyTrainPass(hcfg, concurrent=True)
-        htcstages = htpc.stages(hx, hw, hqk, hlab, hdy)
-
-        def htcstep():
-            for _, fn in htcstages:
-                fn()
-
-        for _ in range(5):
-            htcstep()
-        torch.cuda.synchronize()
-        htcdt = timed(htcstep, args.steps, torch)
-        hres["fwd_bwd"]["stream_per_stage"] = {
-            "ms_per_chain": 1e3 * htcdt / args.steps, "value": sum(htT) * args.steps / htcdt,
-            "gradients_equal_one_stream": bool(all(torch.equal(a_.dx, b_.dx) and torch.equal(a_.dw, b_.dw)
-                                                   for a_, b_ in zip(htpc.passes, htp.passes)))}
-        result["hierarchy"] = hres
-
+        result["extras"] = measure_extras(wl, ctx, args, torch, spa, workloads, pipeline)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_oracle_baseline(wl, bun, args.cpu_seconds)
-        result["cpu_baseline"]["gpu_over_cpu"] = round(value / result["cpu_baseline"]["value"], 1)
-
+        result["cpu_baseline"] = cpu_oracle_baseline(wl, ctx["bun"], args.cpu_seconds)
+        result["cpu_baseline"]["gpu_over_cpu"] = round(head["value"] / result["cpu_baseline"]["value"], 1)
     print(json.dumps(result))
 
 

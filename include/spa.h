@@ -111,6 +111,22 @@ int spa_gate_select(const void* x, const void* w, float bias, const float* s_up,
                     float* scores, uint8_t* mask, int32_t* counts, void* stream);
 
 /*
+ * spa_gate_select and the index-only spa_pack in ONE launch (Section 3.2: scores s, hard selection,
+ * and the order in which "Token Packing" lines the survivors up): the workgroup of the gate kernel
+ * that finishes last walks the finished mask once and writes the packing index.  There is no
+ * waiting between workgroups; one arrival counter in `workspace` tells which workgroup is last.
+ * in:  as spa_gate_select (mask and inv_pos 16-byte aligned); workspace: at least 73984 bytes of
+ *      device memory, 4-byte aligned, ZERO before the first call; every call leaves it zero, so
+ *      consecutive calls on one stream may share it (calls that overlap in time must not).
+ * out: scores, mask, counts (or NULL) as spa_gate_select; cu_seqlens [B+1], gather_idx [B*N],
+ *      inv_pos [B*N], total [1] (or NULL) exactly as spa_pack writes them (bit for bit).
+ */
+int spa_gate_select_index(const void* x, const void* w, float bias, const float* s_up, float tau,
+                          int B, int N, int C, int dtype, float* scores, uint8_t* mask, int32_t* counts,
+                          int32_t* cu_seqlens, int32_t* gather_idx, int32_t* inv_pos, int32_t* total,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Stochastic selection (Section 3.2, r_p = Gumbel-Softmax(s) . r_g): Gumbel-Softmax of the
  * two-class logits [s, 0].  With e_i = g1 - g2 the difference of two Gumbel(0,1) draws (a
  * Logistic(0,1) variate) the relaxed weight of the 'select' class is

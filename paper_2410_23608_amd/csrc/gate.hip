@@ -56,11 +56,132 @@ struct PoolGrid {
   float* s_up_pooled;    // [B, N] or null
 };
 
-template <typename T, int G, bool kPool>
+// Packing index built by the gate launch itself (Section 3.2 "Token Packing" needs nothing but the
+// selection): the workgroup that finishes LAST (one arrival counter, no waiting anywhere) walks
+// the mask once and writes cu_seqlens, gather_idx, inv_pos, total (and counts), exactly what
+// spa_pack writes.  arrive == nullptr: off.
+struct IndexOut {
+  int32_t* cu_seqlens;   // [B+1]
+  int32_t* gather_idx;   // [B*N]
+  int32_t* inv_pos;      // [B*N]
+  int32_t* total;        // [1] or null
+  int32_t* counts;       // [B] or null
+  unsigned* arrive;      // kArriveWords words, zero before the launch, zero again after it
+};
+// Arrival is counted in two levels, 16 group counters and a root: atomics on ONE address are served
+// one after the other (about 25 ns each here, 50 us for the 2100 workgroups of a 33600-token
+// batch), and so are atomics on neighbouring lines (they meet in one memory channel), so the
+// counters lie 4352 bytes apart.
+constexpr int kArriveGroups = 16, kArriveStride = 1088;             // words between counters (4352 bytes)
+constexpr int kArriveWords = (kArriveGroups + 1) * kArriveStride;
+
+// number of non-zero bytes in a 32-bit word
+__device__ __forceinline__ int nonzero_bytes_u32(uint32_t w) {
+  const uint32_t t = (((w & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | w) & 0x80808080u;
+  return __popc(t);
+}
+
+// One workgroup of kGateThreads threads: stable compaction index of mask[0 .. ntok) (tokens of image b
+// are [b*N, (b+1)*N)).  In a round, thread t owns the 16 consecutive tokens [4096 r + 16 t, + 16)
+// (consecutive threads, consecutive groups: the index stores of a wave are contiguous); the
+// mask words of up to kRounds rounds are fetched first, as independent 32-bit agent-scope loads (the
+// mask is 16-byte aligned; other XCDs wrote these bytes in this same launch), so 32768 tokens cost
+// one trip to memory, then every round is one scan over the workgroup and a walk of 16 tokens.
+__device__ __forceinline__ void build_pack_index(const uint8_t* mask, int ntok, int N, int B, const IndexOut& idx) {
+  constexpr int kWaves = kGateThreads / kWave;
+  constexpr int kRounds = 8, kPerRound = kGateThreads * 16;
+  __shared__ int s_wave[2][kWaves];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+  int carry = 0;                                       // selected tokens before the round (the same in every thread)
+  const int tail = ntok & ~3;                          // start of the one partial word at the end of the mask
+  for (int t_super = 0; t_super < ntok; t_super += kRounds * kPerRound) {
+    uint32_t m[kRounds][4];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        m[r][k] = 0u;
+        const int tk = t_super + r * kPerRound + tid * 16 + 4 * k;
+        if (tk + 4 <= ntok)
+          m[r][k] = __hip_atomic_load(reinterpret_cast<const uint32_t*>(mask + tk), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    if (tail < ntok) {                                 // the partial word, by the thread that owns it
+#pragma unroll
+      for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (t_super + r * kPerRound + tid * 16 + 4 * k == tail) {
+            uint32_t word = 0u;
+            for (int j = 0; j < ntok - tail; ++j)
+              word |= (uint32_t)__hip_atomic_load(mask + tail + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) << (8 * j);
+            m[r][k] = word;
+          }
+    }
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      const int t0 = t_super + r * kPerRound + tid * 16;
+      if (t_super + r * kPerRound >= ntok) break;      // uniform
+      const int cnt = nonzero_bytes_u32(m[r][0]) + nonzero_bytes_u32(m[r][1]) + nonzero_bytes_u32(m[r][2]) +
+                      nonzero_bytes_u32(m[r][3]);
+      int inc = cnt;                                   // inclusive scan over the wave
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += up;
+      }
+      if (lane == kWave - 1) s_wave[r & 1][wv] = inc;
+      __syncthreads();                                 // one barrier per round: the wave totals alternate between two rows
+      int run = carry + inc - cnt, total = 0;          // selected tokens before this thread's first token
+#pragma unroll
+      for (int i = 0; i < kWaves; ++i) {
+        const int c = s_wave[r & 1][i];
+        if (i < wv) run += c;
+        total += c;
+      }
+      carry += total;
+      if (t0 < ntok) {
+        int b = t0 / N, rr = t0 - b * N;
+        int inv[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          const int tok = t0 + k;
+          const bool sel = ((m[r][k >> 2] >> (8 * (k & 3))) & 0xFFu) != 0u;   // bytes past ntok are zero: never selected
+          if (tok < ntok && rr == 0) idx.cu_seqlens[b] = run;
+          inv[k] = -1;
+          if (sel) {
+            idx.gather_idx[run] = tok;
+            inv[k] = run;
+            ++run;
+          }
+          if (++rr == N) { rr = 0; ++b; }
+        }
+        if (t0 + 16 <= ntok) {
+#pragma unroll
+          for (int k = 0; k < 16; k += 4) {
+            const uintx4 v = {(uint32_t)inv[k], (uint32_t)inv[k + 1], (uint32_t)inv[k + 2], (uint32_t)inv[k + 3]};
+            *reinterpret_cast<uintx4*>(idx.inv_pos + t0 + k) = v;
+          }
+        } else {
+          for (int k = 0; k < ntok - t0; ++k) idx.inv_pos[t0 + k] = inv[k];
+        }
+      }
+    }
+  }
+  if (tid == 0) {
+    idx.cu_seqlens[B] = carry;
+    if (idx.total != nullptr) idx.total[0] = carry;
+  }
+  if (idx.counts != nullptr) {                       // counts[b] = cu[b+1] - cu[b], from this workgroup's own writes
+    __syncthreads();
+    for (int b = tid; b < B; b += kGateThreads) idx.counts[b] = idx.cu_seqlens[b + 1] - idx.cu_seqlens[b];
+  }
+}
+
+template <typename T, int G, bool kPool, bool kIndex>
 __global__ void __launch_bounds__(kGateThreads)
 gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
                    const float* __restrict__ s_up, const float* __restrict__ noise, float theta, int ntok, int N, int C,
-                   PoolGrid pool, float* __restrict__ scores, uint8_t* __restrict__ mask) {
+                   PoolGrid pool, float* __restrict__ scores, uint8_t* __restrict__ mask, IndexOut idx) {
   constexpr int VE = Vec16<T>::kElems;
   extern __shared__ float w_lds[];
   for (int c = threadIdx.x; c < C; c += kGateThreads) w_lds[c] = static_cast<float>(w[c]);
@@ -70,19 +191,24 @@ gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
   const int grp = threadIdx.x / G;
   const int gl = threadIdx.x % G;
   const int chunks = C / VE;
-  for (long tok = (long)blockIdx.x * kGroups + grp; tok < ntok; tok += (long)gridDim.x * kGroups) {
-    const T* row = x + tok * (long)C;
+  static_assert(kGroups % 4 == 0, "a pass of the workgroup covers whole 4-token words of the mask");
+  __shared__ uint8_t s_sel[kGroups];
+  for (long base = (long)blockIdx.x * kGroups; base < ntok; base += (long)gridDim.x * kGroups) {
+    const long tok = base + grp;
     float acc = 0.f;
+    if (tok < ntok) {
+      const T* row = x + tok * (long)C;
 #pragma unroll 4
-    for (int ch = gl; ch < chunks; ch += G) {
-      float f[VE];
-      Vec16<T>::load(row + ch * VE, f);
-      const float* wp = w_lds + ch * VE;
+      for (int ch = gl; ch < chunks; ch += G) {
+        float f[VE];
+        Vec16<T>::load(row + ch * VE, f);
+        const float* wp = w_lds + ch * VE;
 #pragma unroll
-      for (int i = 0; i < VE; ++i) acc = fmaf(f[i], wp[i], acc);
+        for (int i = 0; i < VE; ++i) acc = fmaf(f[i], wp[i], acc);
+      }
     }
     acc = group_sum<G>(acc);
-    if (gl == 0) {
+    if (gl == 0 && tok < ntok) {
       float s = acc + bias;
       if (kPool) {
         const int b = (int)(tok / N), n = (int)(tok - (long)b * N);
@@ -99,8 +225,53 @@ gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
       // noise: logistic variate of the two-class Gumbel-Softmax; theta already carries the temperature
       const bool sel = (noise != nullptr ? s + noise[tok] : s) > theta;
       scores[tok] = s;
-      mask[tok] = sel ? 1 : 0;
+      if (kIndex) s_sel[grp] = sel ? 1 : 0;
+      else mask[tok] = sel ? 1 : 0;
     }
+    if (kIndex) {
+      // With the index built in this launch the mask is written with agent-scope stores, whole
+      // 4-token words (byte stores past the caches cost a partial write to memory each): such a
+      // store goes through the XCD's write-back L2, so that the last workgroup, on whatever XCD it
+      // runs, reads the bytes without any workgroup having to flush its L2.  The pass covers tokens
+      // [base, base + kGroups), base a multiple of 4; the mask is 16-byte aligned.
+      __syncthreads();
+      if (threadIdx.x < kGroups / 4) {
+        const long t4 = base + 4 * threadIdx.x;
+        if (t4 + 4 <= ntok) {
+          const uint32_t word = (uint32_t)s_sel[4 * threadIdx.x] | ((uint32_t)s_sel[4 * threadIdx.x + 1] << 8) |
+                                ((uint32_t)s_sel[4 * threadIdx.x + 2] << 16) | ((uint32_t)s_sel[4 * threadIdx.x + 3] << 24);
+          __hip_atomic_store(reinterpret_cast<uint32_t*>(mask + t4), word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+          for (long t = t4; t < ntok; ++t)
+            __hip_atomic_store(mask + t, s_sel[t - base], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __builtin_amdgcn_s_waitcnt(0);               // the stores have completed before this thread goes on
+      }
+      __syncthreads();
+    }
+  }
+  if (kIndex) {
+    // sign off: this workgroup's mask stores have completed (see above; the barrier that ends the
+    // last pass orders them before what follows) before its arrival is counted; the workgroup whose
+    // arrival completes the count reads the mask with agent-scope loads and builds the index.  No
+    // workgroup waits for another.
+    __shared__ int s_last;
+    if (threadIdx.x == 0) {
+      const unsigned g = blockIdx.x % kArriveGroups, groups = min((unsigned)kArriveGroups, gridDim.x);
+      const unsigned members = (gridDim.x - g + kArriveGroups - 1) / kArriveGroups;      // workgroups of group g
+      unsigned* mine = idx.arrive + (1 + g) * kArriveStride;
+      int last = 0;
+      if (atomicAdd(mine, 1u) == members - 1) {      // last of its group: nobody touches this counter again
+        __hip_atomic_store(mine, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (atomicAdd(idx.arrive, 1u) == groups - 1) {
+          __hip_atomic_store(idx.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // counters left as found
+          last = 1;
+        }
+      }
+      s_last = last;
+    }
+    __syncthreads();
+    if (s_last) build_pack_index(mask, ntok, N, ntok / N, idx);
   }
 }
 
@@ -314,7 +485,8 @@ static int gate_bwd_parts(long ntok) {
 template <typename T>
 static int launch_gate(const char* fn, const void* x, const void* w, float bias, const float* s_up,
                        const float* noise, float theta, int B, int N, int C, PoolGrid pool, bool pooled,
-                       float* scores, uint8_t* mask, int32_t* counts, hipStream_t st) {
+                       float* scores, uint8_t* mask, int32_t* counts, hipStream_t st,
+                       IndexOut idx = IndexOut{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr}) {
   constexpr int VE = Vec16<T>::kElems;
   const int chunks = C / VE;
   const long ntok = (long)B * N;
@@ -325,19 +497,23 @@ static int launch_gate(const char* fn, const void* x, const void* w, float bias,
     long wgs = (ntok + per_wg - 1) / per_wg;
     if (wgs > 4096) wgs = 4096;
     if (pooled)
-      hipLaunchKernelGGL((gate_select_kernel<T, G, true>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
+      hipLaunchKernelGGL((gate_select_kernel<T, G, true, false>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
                          static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, noise, theta,
-                         (int)ntok, N, C, pool, scores, mask);
+                         (int)ntok, N, C, pool, scores, mask, idx);
+    else if (idx.arrive != nullptr)
+      hipLaunchKernelGGL((gate_select_kernel<T, G, false, true>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
+                         static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, noise, theta,
+                         (int)ntok, N, C, pool, scores, mask, idx);
     else
-      hipLaunchKernelGGL((gate_select_kernel<T, G, false>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
+      hipLaunchKernelGGL((gate_select_kernel<T, G, false, false>), dim3((unsigned)wgs), dim3(kGateThreads), lds, st,
                          static_cast<const T*>(x), static_cast<const T*>(w), bias, s_up, noise, theta,
-                         (int)ntok, N, C, pool, scores, mask);
+                         (int)ntok, N, C, pool, scores, mask, idx);
   };
   if (chunks <= 8) go(std::integral_constant<int, 8>{});
   else if (chunks <= 64) go(std::integral_constant<int, 16>{});
   else if (chunks <= 256) go(std::integral_constant<int, 32>{});
   else go(std::integral_constant<int, 64>{});
-  if (counts != nullptr)
+  if (counts != nullptr && idx.arrive == nullptr)
     hipLaunchKernelGGL(count_selected_kernel, dim3(B), dim3(256), 0, st, mask, N, counts);
   return check_launch(fn);
 }
@@ -349,7 +525,8 @@ using namespace spa;
 static int gate_select_common(const char* fn, const void* x, const void* w, float bias, const float* s_up,
                               const float* noise, float temperature, float tau, int B, int N, int C, int dtype,
                               float* scores, uint8_t* mask, int32_t* counts, void* stream,
-                              PoolGrid pool = PoolGrid{0, 0, nullptr}, bool pooled = false) {
+                              PoolGrid pool = PoolGrid{0, 0, nullptr}, bool pooled = false,
+                              IndexOut idx = IndexOut{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr}) {
   SPA_REQUIRE(x && w && scores && mask, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(B >= 1 && N >= 1 && C >= 1, SPA_ERR_INVALID_ARG, "%s: B, N, C must be >= 1", fn);
   SPA_REQUIRE((long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*N must be < 2^31", fn);
@@ -365,8 +542,8 @@ static int gate_select_common(const char* fn, const void* x, const void* w, floa
   const float theta = (float)((double)temperature * std::log((double)tau / (1.0 - (double)tau)));
   hipStream_t st = as_stream(stream);
   if (dtype == SPA_F32)
-    return launch_gate<float>(fn, x, w, bias, s_up, noise, theta, B, N, C, pool, pooled, scores, mask, counts, st);
-  return launch_gate<__bf16>(fn, x, w, bias, s_up, noise, theta, B, N, C, pool, pooled, scores, mask, counts, st);
+    return launch_gate<float>(fn, x, w, bias, s_up, noise, theta, B, N, C, pool, pooled, scores, mask, counts, st, idx);
+  return launch_gate<__bf16>(fn, x, w, bias, s_up, noise, theta, B, N, C, pool, pooled, scores, mask, counts, st, idx);
 }
 
 extern "C" int spa_gate_select(const void* x, const void* w, float bias, const float* s_up,
@@ -374,6 +551,22 @@ extern "C" int spa_gate_select(const void* x, const void* w, float bias, const f
                                uint8_t* mask, int32_t* counts, void* stream) {
   return gate_select_common("spa_gate_select", x, w, bias, s_up, nullptr, 1.f, tau, B, N, C, dtype, scores, mask,
                             counts, stream);
+}
+
+extern "C" int spa_gate_select_index(const void* x, const void* w, float bias, const float* s_up, float tau, int B,
+                                     int N, int C, int dtype, float* scores, uint8_t* mask, int32_t* counts,
+                                     int32_t* cu_seqlens, int32_t* gather_idx, int32_t* inv_pos, int32_t* total,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  const char* fn = "spa_gate_select_index";
+  SPA_REQUIRE(cu_seqlens && gather_idx && inv_pos, SPA_ERR_INVALID_ARG, "%s: null index pointer", fn);
+  SPA_REQUIRE(workspace != nullptr && workspace_bytes >= kArriveWords * sizeof(unsigned), SPA_ERR_WORKSPACE,
+              "%s: workspace of %zu bytes needed (zero-filled once, left zero by every call), %zu given", fn,
+              kArriveWords * sizeof(unsigned), workspace_bytes);
+  SPA_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 3u) == 0 && aligned16(mask) && aligned16(inv_pos),
+              SPA_ERR_INVALID_ARG, "%s: mask / inv_pos not 16-byte aligned or workspace not 4-byte aligned", fn);
+  const IndexOut idx = {cu_seqlens, gather_idx, inv_pos, total, counts, static_cast<unsigned*>(workspace)};
+  return gate_select_common(fn, x, w, bias, s_up, nullptr, 1.f, tau, B, N, C, dtype, scores, mask, counts, stream,
+                            PoolGrid{0, 0, nullptr}, false, idx);
 }
 
 extern "C" int spa_gate_select_gumbel(const void* x, const void* w, float bias, const float* s_up,

@@ -32,12 +32,17 @@ class ForwardPass:
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
                  container_len: int = 0, fused_unpack: bool = True, keep_packed_out: bool = True,
-                 gathered: bool = False):
+                 gathered: bool = False, fused_index: bool = False):
         """keep_packed_out=False (fused form only): the packed attention output and the
-        log-sum-exp rows, which only a backward pass reads, are not written; y is the result."""
+        log-sum-exp rows, which only a backward pass reads, are not written; y is the result.
+        fused_index=True (with gathered): the gate launch builds the packing index itself
+        (spa_gate_select_index), two launches per step."""
         if gathered and (not fused_unpack or container_len):
             raise ValueError("gathered=True needs the fused form and no container padding")
-        self.gathered = gathered
+        if fused_index and not gathered:
+            raise ValueError("fused_index=True needs gathered=True")
+        self.gathered, self.fused_index = gathered, fused_index
+        self.ws_index = torch.zeros(17 * 1088, dtype=torch.int32, device="cuda") if fused_index else None
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
         self.tau, self.bias, self.container_len = tau, bias, container_len
         self.fused_unpack = fused_unpack
@@ -61,11 +66,17 @@ class ForwardPass:
         C, p = self.C, self.packed_qkv
         if self.gathered:
             t = qkv.view(self.B * self.N, 3 * C)
-            return [
+            head = [
+                ("gate_select_index", spa.spa_gate_select_index(x, w, self.bias, s_up, self.tau, self.scores, self.mask,
+                                                                None, self.cu_seqlens, self.gather_idx, self.inv_pos,
+                                                                self.total, self.ws_index, prepare=True)),
+            ] if self.fused_index else [
                 ("gate_select", spa.spa_gate_select(x, w, self.bias, s_up, self.tau, self.scores, self.mask, None,
                                                     prepare=True)),
                 ("pack_indices", spa.spa_pack(None, self.mask, None, None, 0, None, self.cu_seqlens, self.gather_idx,
                                               self.inv_pos, self.total, prepare=True)),
+            ]
+            return head + [
                 ("gathered_attention_unpack", spa.spa_gathered_attention_unpack(
                     t[:, :C], t[:, C:2 * C], t[:, 2 * C:], self.cu_seqlens, self.gather_idx, self.inv_pos, base,
                     self.H, self.Dh, self.y, self.out, self.lse, prepare=True)),

@@ -32,6 +32,8 @@ _SIGNATURES = {
     "spa_set_option": (c_int, [c_char_p, c_char_p]),
     "spa_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int, c_int, c_int]),
     "spa_gate_select": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, _P, _P, _P, _P]),
+    "spa_gate_select_index": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, _P, _P, _P, _P, _P, _P, _P,
+                                      _P, c_size_t, _P]),
     "spa_gate_select_pooled": (c_int, [_P, _P, c_float, _P, c_float, c_int, c_int, c_int, c_int, c_int, _P, _P, _P, _P,
                                        _P]),
     "spa_gate_select_gumbel": (c_int, [_P, _P, c_float, _P, _P, c_float, c_float, c_int, c_int, c_int, c_int, _P, _P,
@@ -229,6 +231,23 @@ def spa_gate_select(x, w, bias, s_up, tau, scores, mask, counts=None, prepare=Fa
     _contig(*_keep)
     return _dispatch(lib.spa_gate_select, (_ptr(x), _ptr(w), float(bias), _ptr(s_up), float(tau), B, N, C, code,
                                _ptr(scores), _ptr(mask), _ptr(counts), _stream(),), _keep, prepare)
+
+
+def spa_gate_select_index(x, w, bias, s_up, tau, scores, mask, counts, cu_seqlens, gather_idx, inv_pos, total, workspace,
+                          prepare=False):
+    """spa_gate_select + the index-only spa_pack in one launch.  workspace: >= 73984 bytes, zero before the
+    first call (every call leaves it zero)."""
+    fn = "spa_gate_select_index"
+    B, N, C, code = _gate_select_checks(fn, x, w, s_up, None, scores, mask, counts)
+    _typed(fn, torch.int32, cu_seqlens=cu_seqlens, gather_idx=gather_idx, inv_pos=inv_pos, total=total)
+    _holds(fn, cu_seqlens=(cu_seqlens, B + 1), gather_idx=(gather_idx, B * N), inv_pos=(inv_pos, B * N), total=(total, 1))
+    _keep = (x, w, s_up, scores, mask, counts, cu_seqlens, gather_idx, inv_pos, total, workspace,)
+    _contig(*_keep)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return _dispatch(lib.spa_gate_select_index,
+                     (_ptr(x), _ptr(w), float(bias), _ptr(s_up), float(tau), B, N, C, code, _ptr(scores), _ptr(mask),
+                      _ptr(counts), _ptr(cu_seqlens), _ptr(gather_idx), _ptr(inv_pos), _ptr(total), _ptr(workspace),
+                      ws_bytes, _stream(),), _keep, prepare)
 
 
 def spa_gate_select_gumbel(x, w, bias, s_up, noise, temperature, tau, scores, mask, counts=None, prepare=False):

@@ -376,6 +376,52 @@ def test_gathered_attention_equals_packed_form(spa, short_option, dtype, Dh, N, 
     assert np.max(np.abs(host(y2) - ref_y)) <= tol
 
 
+@pytest.mark.parametrize("dtype,B,N,C", [("bf16", 64, 196, 384), ("bf16", 8, 4200, 256), ("f32", 2, 196, 64),
+                                         ("bf16", 3, 37, 64), ("f32", 1, 1, 8), ("bf16", 5, 4099, 96),
+                                         ("bf16", 16, 3136, 96), ("f32", 7, 16, 32)])
+def test_gate_select_index_equals_gate_then_pack(spa, dtype, B, N, C):
+    """spa_gate_select_index (the gate launch builds the packing index itself) against the oracle's
+    indices, and bit for bit against spa_gate_select followed by the index-only spa_pack; shapes
+    whose token count is and is not a multiple of the 16-token groups the index builder reads, an
+    empty and a full image, up-scale scores; three calls in a row on one arrival counter."""
+    rng = np.random.default_rng(B * 1000 + N)
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    x = mk(rng.standard_normal((B, N, C)).astype(np.float32))
+    w = mk((rng.standard_normal(C) * 3 / np.sqrt(C)).astype(np.float32))
+    s_up = (rng.standard_normal((B, N)) * 2 - 1).astype(np.float32)
+    if B > 2:
+        s_up[1] = -50.0
+        x[1] = 0                                   # an image with nothing selected (bias below the threshold)
+        s_up[2] = 50.0                             # an image with everything selected
+    bias = -0.25
+    xd, wd, sd = dev(x, dtype), dev(w, dtype), dev(s_up)
+    cap = B * N
+    ints = lambda n: torch.full((n,), -9, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(17 * 1088, dtype=torch.int32, device="cuda")
+    for call, sup in enumerate((sd, None, sd)):
+        sc1, m1 = torch.empty(B, N, device="cuda"), torch.empty(B, N, dtype=torch.uint8, device="cuda")
+        cnt1, cu1, g1, inv1, tot1 = ints(B), ints(B + 1), ints(cap), ints(cap), ints(1)
+        spa.spa_gate_select_index(xd, wd, bias, sup, 0.5, sc1, m1, cnt1, cu1, g1, inv1, tot1, ws)
+        sc2, m2 = torch.empty(B, N, device="cuda"), torch.empty(B, N, dtype=torch.uint8, device="cuda")
+        cnt2, cu2, g2, inv2, tot2 = ints(B), ints(B + 1), ints(cap), ints(cap), ints(1)
+        spa.spa_gate_select(xd, wd, bias, sup, 0.5, sc2, m2, cnt2)
+        spa.spa_pack(None, m2, None, None, 0, None, cu2, g2, inv2, tot2)
+        torch.cuda.synchronize()
+        assert not host(ws).any()                                   # the arrival counters are left zero
+        T = int(host(tot1)[0])
+        assert torch.equal(sc1, sc2) and torch.equal(m1, m2) and torch.equal(cnt1, cnt2)
+        assert torch.equal(cu1, cu2) and T == int(host(tot2)[0]) and torch.equal(inv1, inv2)
+        assert torch.equal(g1[:T], g2[:T]) and bool((g1[T:] == -9).all())
+        # against the oracle, from the device's own mask (near-ties of the threshold aside)
+        ref_cu, ref_g, ref_inv, ref_T = orc.pack_indices(host(m1))
+        assert np.array_equal(host(cu1), ref_cu) and T == ref_T
+        assert np.array_equal(host(g1)[:T], ref_g) and np.array_equal(host(inv1), ref_inv)
+        s_ref = orc.gate_scores(x, w, bias, s_up if sup is not None else None)
+        mask_ref, _ = orc.select(s_ref, 0.5)
+        near = np.abs(s_ref) < (1e-3 if dtype == "bf16" else 1e-5)
+        assert np.array_equal(host(m1)[~near], mask_ref[~near])
+
+
 @pytest.mark.parametrize("B", [64, 70])
 def test_short_segments_many_images(spa, B):
     """The one-wave kernel with as many images as lanes (blocks numbered by weight) and with

@@ -495,18 +495,21 @@ def test_hierarchy_full_batch_training_chain_matches_stagewise_oracle(spa, pipel
         s_up = orc.maxpool2x2(s.astype(np.float32), *wl.grid).astype(np.float32)
 
 
+@pytest.mark.parametrize("fused_index", [False, True])
 @pytest.mark.parametrize("name", ["tiny", "vit_s", "det"])
-def test_full_size_gathered_forward_as_benchmarked(spa, pipeline, name):
-    """The forward step bench.py times (gate_select, index-only pack, attention on gathered rows
-    + scatter) on the full batch: integers bit-exact, y against the oracle on every row, and
+def test_full_size_gathered_forward_as_benchmarked(spa, pipeline, name, fused_index):
+    """The forward step bench.py times (gate_select [+ index in the same launch | index-only pack],
+    attention on gathered rows + scatter) on the full batch: integers bit-exact, y against the oracle on every row, and
     bit-equal to the form that copies the rows first."""
     wl = wlmod.WORKLOADS[name]
     bun = wlmod.generate(wl, 0)
     ins = (dev(bun["x"], wl.dtype), dev(bun["w"], wl.dtype), dev(bun["qkv"], wl.dtype))
-    fg = pipeline.ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, gathered=True, keep_packed_out=False)
+    fg = pipeline.ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, gathered=True, keep_packed_out=False,
+                              fused_index=fused_index)
     fp = pipeline.ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False)
     yg, yp = fg.run(*ins), fp.run(*ins)
     torch.cuda.synchronize()
+    assert len(fg.stages(*ins)) == (2 if fused_index else 3)
     ref = orc.spa_forward(bun["x"], bun["w"], bun["bias"], bun["qkv"], wl.H, wl.tau, wl.dtype)
     assert ref["margin"] > 1e-3
     T = ref["total"]
