@@ -47,10 +47,10 @@ def parse_args():
                     help="independent batches in flight, one HIP stream each (1 = one stream, steps back to back)")
     ap.add_argument("--only", default=None, choices=["forward", "vit_s", "det", "vit_b_train", "hierarchy"],
                     help="measure one chain only (profiling runs): forward = the headline workload's forward chain")
-    ap.add_argument("--form", default="fused", choices=["fused", "gathered", "packed"],
-                    help="forward step: gate + packing index in one launch, attention on gathered rows (default, 2 "
-                         "launches); gate, index-only pack, attention on gathered rows (3); gate, pack of the rows, "
-                         "attention on the packed rows (3)")
+    ap.add_argument("--form", default="gathered", choices=["fused", "gathered", "packed"],
+                    help="forward step: gate, index-only pack, attention on gathered rows (default, 3 launches); "
+                         "gate + packing index in one launch, attention on gathered rows (2 launches); gate, pack of "
+                         "the rows, attention on the packed rows (3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the four-call form, graph replay, padded baseline, widened rows")

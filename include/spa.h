@@ -67,7 +67,9 @@ const char* spa_last_error(void);
  * malformed value (nothing changes then).
  *   attn_fwd_short     words of: "whole" (one workgroup per (image, head)), "64" (64-key steps),
  *                      "plain" (one-wave blocks numbered blindly instead of by weight)
- *   attn_fwd_cfg       "NW,BN": the tiled forward kernel with NW in {2,4} waves, BN in {64,128} keys
+ *   attn_fwd_long      "two": the long-segment forward kernel with two chains of 32 queries per wave
+ *                      sharing every K / V fragment (default: one chain per wave)
+ *   attn_fwd_cfg       "NW,BN": the one-chain tiled forward kernel with NW in {2,4} waves, BN in {64,128} keys
  *   attn_fwd_wave_max  longest segment (<= 256) the one-wave forward kernels take
  *   attn_bwd_short     "split" | "tiled": two-kernel / long-segment backward for segments <= 256
  *   attn_bwd_long      "two": the dq and dkdv roles of the long-segment backward as two launches

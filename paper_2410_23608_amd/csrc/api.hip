@@ -34,6 +34,8 @@ static bool parse_option(Options& o, const char* name, const char* value) {
     o.fwd_whole = std::strstr(v, "whole") != nullptr;
     o.fwd_step64 = std::strstr(v, "64") != nullptr;
     o.fwd_plain = std::strstr(v, "plain") != nullptr;
+  } else if (!std::strcmp(name, "attn_fwd_long")) {    // "" (one query chain per wave) | "two"
+    o.fwd_long_two = v[0] == 't';
   } else if (!std::strcmp(name, "attn_fwd_cfg")) {     // "" | "NW,BN" with NW in {2,4}, BN in {64,128}
     int a = 0, b = 0;
     o.fwd_nw = o.fwd_bn = 0;
@@ -68,7 +70,7 @@ static bool parse_option(Options& o, const char* name, const char* value) {
   return true;
 }
 
-static const char* const kOptionNames[] = {"attn_fwd_short", "attn_fwd_cfg", "attn_fwd_wave_max", "attn_bwd_short",
+static const char* const kOptionNames[] = {"attn_fwd_short", "attn_fwd_long", "attn_fwd_cfg", "attn_fwd_wave_max", "attn_bwd_short",
                                            "attn_bwd_long",  "gemm_tm",      "gemm_splits",       "pack_tile"};
 
 static Options load_options() {

@@ -45,11 +45,20 @@ struct Scatter {
 
 // Row of q / k / v that holds packed position j of a segment starting at packed row row0:
 // gi = gather_idx + row0 when the rows are gathered through the index, else null.
+// GATHER is a compile-time property of every bf16 kernel: with packed rows the index is known to be
+// absent and the row addresses stay affine in the loop counters (pointer increments), with gathered
+// rows every row address is a multiply on a loaded index.
+template <bool GATHER>
 __device__ __forceinline__ const int32_t* gather_base(const Scatter& sc, long row0) {
-  return sc.gathered ? sc.gather_idx + row0 : nullptr;
+  return GATHER ? sc.gather_idx + row0 : nullptr;
 }
 __device__ __forceinline__ long source_row(const int32_t* gi, long row0, int j) {
   return gi != nullptr ? (long)gi[j] : row0 + j;
+}
+// Element offset of a gathered row: one 32 x 32 -> 64 bit multiply (the host checks that rows and
+// strides are below 2^31).
+__device__ __forceinline__ long row_offset(int row, long stride) {
+  return (long)((unsigned long)(uint32_t)row * (uint32_t)stride);
 }
 
 // The rows whose bypass fill falls to work unit (segment `seg` of `nseg`, part `part` of `nparts`):
@@ -259,39 +268,60 @@ __device__ __forceinline__ void fwd_flush(const __bf16* tile, __bf16* out, const
 
 // Register staging of key/value rows on their way to LDS: task i = 16-byte chunk column
 // c = i % CPR of the row pair (2*(i / CPR), +1); K goes row-major, V transposed.
-template <int DH, int THREADS, int TASKS>
+template <int DH, int THREADS, int TASKS, bool GATHER>
 struct KvStage {
   static constexpr int CPR = DH / 8;
   static constexpr int TPT = (TASKS + THREADS - 1) / THREADS;
+  static constexpr int RPP = 2 * THREADS / CPR;   // rows one pass of the workgroup covers
+  static_assert(THREADS % CPR == 0, "a thread keeps its chunk column over the passes");
   bf16x8 kreg[TPT][2], vreg[TPT][2];
 
-  int rows[TPT][2];   // source rows of the next load (-1: past the segment)
+  // The rows the next load() fetches: keys [kt_, kt_ + tile) of a segment of nk_ keys whose packed rows
+  // start at row0_.  Packed rows need no per-lane address arithmetic: the address is a uniform base
+  // (segment, tile, pass) plus a 32-bit per-lane offset that never changes.  Gathered rows have their
+  // token rows loaded here, one tile ahead of load(), so the row loads never wait for an index.
+  int tok_rows[TPT][2];
+  long row0_;
+  int kt_, nk_;
 
-  // Step 1: the rows of q / k / v that hold keys [kt, kt + tile) of the segment (gi: see
-  // gather_base; an index load when the rows are gathered, arithmetic otherwise).  Issued one
-  // tile ahead of load(), so the row loads never wait for an index.
+  __device__ __forceinline__ bool valid(int t, int u) const {
+    const int i = threadIdx.x + t * THREADS;
+    return i < TASKS && kt_ + 2 * (i / CPR) + u < nk_;
+  }
   __device__ __forceinline__ void index(const int32_t* gi, long row0, int kt, int nk) {
+    row0_ = row0;
+    kt_ = kt;
+    nk_ = nk;
+    if (GATHER) {
 #pragma unroll
-    for (int t = 0; t < TPT; ++t) {
-      const int i = threadIdx.x + t * THREADS;
-      const int r0 = kt + 2 * (i / CPR);
+      for (int t = 0; t < TPT; ++t)
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
-        rows[t][u] = (i < TASKS && r0 + u < nk) ? (int)source_row(gi, row0, r0 + u) : -1;
+        for (int u = 0; u < 2; ++u)
+          if (valid(t, u)) tok_rows[t][u] = gi[kt + 2 * ((threadIdx.x + t * THREADS) / CPR) + u];
     }
   }
-  // Step 2: the row loads; rows past the segment read as zero
+  // The row loads; rows past the segment read as zero
   __device__ __forceinline__ void load(const __bf16* kh, const __bf16* vh, long ks, long vs) {
+    const int c = threadIdx.x % CPR, lrow = 2 * (threadIdx.x / CPR);
+    const uint32_t koff = (uint32_t)lrow * (uint32_t)ks + c * 8, voff = (uint32_t)lrow * (uint32_t)vs + c * 8;
 #pragma unroll
     for (int t = 0; t < TPT; ++t) {
-      const int c = (threadIdx.x + t * THREADS) % CPR;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         kreg[t][u] = zero_bf16x8();
         vreg[t][u] = zero_bf16x8();
-        if (rows[t][u] >= 0) {
-          kreg[t][u] = *reinterpret_cast<const bf16x8*>(kh + (long)rows[t][u] * ks + c * 8);
-          vreg[t][u] = *reinterpret_cast<const bf16x8*>(vh + (long)rows[t][u] * vs + c * 8);
+        if (valid(t, u)) {
+          const __bf16 *kp, *vp;
+          if (GATHER) {
+            kp = kh + row_offset(tok_rows[t][u], ks) + c * 8;
+            vp = vh + row_offset(tok_rows[t][u], vs) + c * 8;
+          } else {
+            const long r = row0_ + kt_ + t * RPP + u;     // uniform
+            kp = kh + r * ks + koff;
+            vp = vh + r * vs + voff;
+          }
+          kreg[t][u] = *reinterpret_cast<const bf16x8*>(kp);
+          vreg[t][u] = *reinterpret_cast<const bf16x8*>(vp);
         }
       }
     }
@@ -339,7 +369,7 @@ struct TiledLds {
 };
 
 // The workgroup's work on queries [q0, q0 + 32 NW) of head h of segment seg (q0 < seg.nq).
-template <int DH, int NW, int BN>
+template <int DH, int NW, int BN, bool GATHER>
 __device__ __forceinline__ void
 tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const __bf16* __restrict__ q,
                 const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs, int H,
@@ -357,13 +387,14 @@ tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const _
   const __bf16* kh = k + h * DH;
   const __bf16* vh = v + h * DH;
 
-  const int32_t* gi = gather_base(sc, seg.row0);
-  KvStage<DH, 64 * NW, (BN / 2) * (DH / 8)> stage;
+  const int32_t* gi = gather_base<GATHER>(sc, seg.row0);
+  const long q_src = q_ok ? source_row(gi, seg.row0, qi) : 0;   // (gathered: an index load, issued first)
+  KvStage<DH, 64 * NW, (BN / 2) * (DH / 8), GATHER> stage;
   stage.index(gi, seg.row0, 0, seg.nk);
   stage.load(kh, vh, ks, vs);
   stage.index(gi, seg.row0, BN, seg.nk);
   bf16x8 qf[DH / 16];
-  load_q_frags<DH>(q + (q_ok ? source_row(gi, seg.row0, qi) : 0) * qs + h * DH, q_ok, hh, qf);
+  load_q_frags<DH>(q + q_src * qs + h * DH, q_ok, hh, qf);
   FwdAcc<DH> acc;
   acc.init();
   stage.template store<RS, TS>(Ks[0], Vt[0], 0);
@@ -394,7 +425,7 @@ tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const _
     fwd_flush<DH, RS>(tile, out, sc, seg.row0 + q0 + wv * 32, h, C, min(32, seg.nq - q0 - wv * 32), lane);
 }
 
-template <int DH, int NW, int BN>
+template <int DH, int NW, int BN, bool GATHER>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(DH == 32 ? 3 : 2)))
 attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                            const __bf16* __restrict__ v, long qs, long ks, long vs,
@@ -416,7 +447,284 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   const FillRange fr = fill_range(sc, fill_img, B, tile_id.qb, nqb);
   const int q0 = tile_id.qb * (32 * NW);
   if (q0 < seg.nq)
-    tiled_attention<DH, NW, BN>(lds, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
+    tiled_attention<DH, NW, BN, GATHER>(lds, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
+  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64 * NW);
+}
+
+// Long segments, two query sub-tiles per wave.  A wave owns 64 queries as two independent
+// 32-query chains that share every K and V fragment it reads from LDS: half the LDS operand
+// reads per MFMA of the one-chain kernel above, and two independent dependency chains in one
+// instruction stream, so the score and P V MFMAs of one chain run under the softmax vector
+// work of the other even when the wave has its SIMD to itself (the long-segment launches of
+// this path keep one to two waves per SIMD resident, too few to hide a single chain's stalls).
+// K and V tiles sit row-major in LDS; V^T fragments come from the transposing LDS read, so
+// staging is plain 16-byte copies.  One softmax update per 32 keys and chain.
+template <int DH, int BN>
+struct Tiled2Lds {
+  static constexpr int RS = DH + 8;
+  __attribute__((aligned(16))) __bf16 Ks[2][BN * RS];
+  __attribute__((aligned(16))) __bf16 Vs[2][BN * RS];
+};
+
+// Register staging of BN key and value rows on their way to LDS (both row-major): chunk i =
+// 16-byte piece i % CPR of row i / CPR; index() runs one tile ahead of load() (see KvStage).
+template <int DH, int THREADS, int BN, bool GATHER>
+struct KvRowStage {
+  static constexpr int CPR = DH / 8, CHUNKS = BN * CPR, CPT = (CHUNKS + THREADS - 1) / THREADS;
+  static constexpr int RPP = THREADS / CPR;
+  static_assert(THREADS % CPR == 0, "a thread keeps its chunk column over the passes");
+  bf16x8 kreg[CPT], vreg[CPT];
+  int tok_rows[CPT];                   // gathered rows only: see KvStage
+  long row0_;
+  int kt_, nk_;
+  __device__ __forceinline__ bool valid(int t) const {
+    const int i = threadIdx.x + t * THREADS;
+    return i < CHUNKS && kt_ + i / CPR < nk_;
+  }
+  __device__ __forceinline__ void index(const int32_t* gi, long row0, int kt, int nk) {
+    row0_ = row0;
+    kt_ = kt;
+    nk_ = nk;
+    if (GATHER) {
+#pragma unroll
+      for (int t = 0; t < CPT; ++t)
+        if (valid(t)) tok_rows[t] = gi[kt + (threadIdx.x + t * THREADS) / CPR];
+    }
+  }
+  __device__ __forceinline__ void load(const __bf16* kh, const __bf16* vh, long ks, long vs) {
+    const int c = threadIdx.x % CPR, lrow = threadIdx.x / CPR;
+    const uint32_t koff = (uint32_t)lrow * (uint32_t)ks + c * 8, voff = (uint32_t)lrow * (uint32_t)vs + c * 8;
+#pragma unroll
+    for (int t = 0; t < CPT; ++t) {
+      kreg[t] = zero_bf16x8();
+      vreg[t] = zero_bf16x8();
+      if (valid(t)) {
+        const __bf16 *kp, *vp;
+        if (GATHER) {
+          kp = kh + row_offset(tok_rows[t], ks) + c * 8;
+          vp = vh + row_offset(tok_rows[t], vs) + c * 8;
+        } else {
+          const long r = row0_ + kt_ + t * RPP;           // uniform
+          kp = kh + r * ks + koff;
+          vp = vh + r * vs + voff;
+        }
+        kreg[t] = *reinterpret_cast<const bf16x8*>(kp);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(vp);
+      }
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* kbuf, __bf16* vbuf) const {
+#pragma unroll
+    for (int t = 0; t < CPT; ++t) {
+      const int i = threadIdx.x + t * THREADS, r = i / CPR, c = i % CPR;
+      if (i < CHUNKS) {
+        *reinterpret_cast<bf16x8*>(&kbuf[r * (DH + 8) + c * 8]) = kreg[t];
+        *reinterpret_cast<bf16x8*>(&vbuf[r * (DH + 8) + c * 8]) = vreg[t];
+      }
+    }
+  }
+};
+
+// Online-softmax update of one chain over one 32-key sub-tile whose first key is k0 of the tile
+// (rem = valid keys of the tile): masks keys past the segment, moves the running max, rescales
+// the chain's accumulators when some query's max moved, and leaves the bf16 probabilities in
+// the B-operand layout of the P V product.
+template <int DH, bool FULL>
+__device__ __forceinline__ void chain_softmax(floatx16& s, int k0, int rem, FwdAcc<DH>& acc, float scale_log2,
+                                              bf16x8 (&pb)[2], int hh) {
+  if (!FULL && rem - k0 < 32) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (k0 + acc_row(r, hh) >= rem) s[r] = -INFINITY;
+  }
+  float mx = s[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+  mx = max_across_halves(mx);
+  // The rescale is unconditional (alpha = 1 when no max moved): skipping it takes a branch per
+  // chain and sub-tile, and every branch ends a scheduling region, which is what keeps the two
+  // chains, the fragment reads and the MFMAs from overlapping.  The first sub-tile of a tile always
+  // holds a valid key, so m_new is finite and alpha well defined.
+  const float m_new = fmaxf(acc.m, mx * scale_log2);
+  const float alpha = __builtin_amdgcn_exp2f(acc.m - m_new);
+  acc.m = m_new;
+#pragma unroll
+  for (int d = 0; d < DH / 32; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc.o[d][r] *= alpha;
+  float p[16], psum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -m_new));
+    psum += p[r];
+  }
+  acc.l = fmaf(acc.l, alpha, psum);
+#pragma unroll
+  for (int mf = 0; mf < 2; ++mf) {
+    floatx8 pf;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pf[j] = p[8 * mf + j];
+    pb[mf] = float_to_bf16x8(pf);
+  }
+}
+
+// One tile of NSB*32 keys in LDS (K rows at kbuf, V rows at vbuf, both row stride RS) against
+// the wave's NC query chains.  The score MFMAs of sub-tile sb + 1 are issued before the softmax of
+// sub-tile sb.  FULL = every key of the tile is valid; otherwise keys >= rem are masked (their K and
+// V rows in LDS are zero): all sub-tiles are computed, there is no control flow in the tile.
+template <int DH, int RS, int NSB, bool FULL, int NC>
+__device__ __forceinline__ void fwd_tile_chains(const __bf16* kbuf, const __bf16* vbuf, int rem,
+                                                const bf16x8 (&qf)[NC][DH / 16], FwdAcc<DH> (&acc)[NC],
+                                                float scale_log2, int lane) {
+  constexpr int KK = DH / 16, DB = DH / 32;
+  const int l32 = lane & 31, hh = lane >> 5;
+  floatx16 s[2][NC];
+  auto scores = [&](int sb, floatx16 (&dst)[NC]) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dst[c][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&kbuf[(sb * 32 + l32) * RS + kk * 16 + hh * 8]);
+#pragma unroll
+      for (int c = 0; c < NC; ++c) dst[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c][kk], dst[c], 0, 0, 0);
+    }
+  };
+  scores(0, s[0]);
+#pragma unroll
+  for (int sb = 0; sb < NSB; ++sb) {
+    const int k0 = sb * 32;
+    if (sb + 1 < NSB) scores(sb + 1, s[(sb + 1) & 1]);
+    bf16x8 vf[2][DB];                                  // V^T fragments of the sub-tile: read before the softmax needs them
+#pragma unroll
+    for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+      for (int d = 0; d < DB; ++d) vf[mf][d] = transposed_frag_rowmajor<RS>(vbuf, d, k0, mf, lane);
+    bf16x8 pb[NC][2];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) chain_softmax<DH, FULL>(s[sb & 1][c], k0, rem, acc[c], scale_log2, pb[c], hh);
+#pragma unroll
+    for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+          acc[c].o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mf][d], pb[c][mf], acc[c].o[d], 0, 0, 0);
+  }
+}
+
+// The key loop of one wave with NC live query chains (NC = 0: a wave without queries, which only
+// helps to stage the tiles).  Every instantiation runs the same sequence of barriers.
+template <int DH, int NW, int BN, int NC, bool GATHER>
+__device__ __forceinline__ void
+tiled2_wave(Tiled2Lds<DH, BN>& lds, KvRowStage<DH, 64 * NW, BN, GATHER>& stage, const Segment& seg, const int32_t* gi,
+            const __bf16* kh, const __bf16* vh, long ks, long vs, const bf16x8 (&qf)[2][DH / 16], FwdAcc<DH> (&acc2)[2],
+            float scale_log2, int lane) {
+  constexpr int RS = DH + 8, NSB = BN / 32, KK = DH / 16, NCA = NC > 0 ? NC : 1;
+  bf16x8 q[NCA][KK];
+  FwdAcc<DH> acc[NCA];
+#pragma unroll
+  for (int c = 0; c < NCA; ++c) {
+    acc[c].init();
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) q[c][kk] = qf[c][kk];
+  }
+  const int nt = (seg.nk + BN - 1) / BN;
+  for (int t = 0; t + 1 < nt; ++t) {                  // all tiles but the last are full
+    const int buf = t & 1;
+    stage.load(kh, vh, ks, vs);                        // tile t + 1, whose rows were indexed a tile ago
+    stage.index(gi, seg.row0, (t + 2) * BN, seg.nk);
+    if (NC > 0) fwd_tile_chains<DH, RS, NSB, true, NCA>(lds.Ks[buf], lds.Vs[buf], BN, q, acc, scale_log2, lane);
+    stage.store(lds.Ks[buf ^ 1], lds.Vs[buf ^ 1]);
+    __syncthreads();
+  }
+  if (nt > 0) {
+    const int buf = (nt - 1) & 1;
+    if (NC > 0)
+      fwd_tile_chains<DH, RS, NSB, false, NCA>(lds.Ks[buf], lds.Vs[buf], seg.nk - (nt - 1) * BN, q, acc, scale_log2, lane);
+  }
+  __syncthreads();                                     // every wave is past its last read of the K buffers
+#pragma unroll
+  for (int c = 0; c < NCA; ++c)
+    if (NC > 0) acc2[c] = acc[c];
+}
+
+// The workgroup's work on queries [q0, q0 + 64 NW) of head h of segment seg (q0 < seg.nq).
+template <int DH, int NW, int BN, bool GATHER>
+__device__ __forceinline__ void
+tiled2_attention(Tiled2Lds<DH, BN>& lds, const Segment seg, int h, int q0, const __bf16* __restrict__ q,
+                 const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs, int H,
+                 float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse, long lse_stride,
+                 const Scatter& sc) {
+  constexpr int RS = DH + 8, KK = DH / 16;
+  static_assert(2 * BN >= 64 * NW, "the K buffers double as the output staging tile");
+  const long C = (long)H * DH;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int qw = q0 + wv * 64;                         // the wave's first query
+  const int nc = qw >= seg.nq ? 0 : (qw + 32 < seg.nq ? 2 : 1);      // live chains of this wave
+  const __bf16* kh = k + h * DH;
+  const __bf16* vh = v + h * DH;
+  const int32_t* gi = gather_base<GATHER>(sc, seg.row0);
+
+  bool q_ok[2];
+  long q_src[2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const int qi = qw + 32 * c + l32;
+    q_ok[c] = qi < seg.nq;
+    q_src[c] = q_ok[c] ? source_row(gi, seg.row0, qi) : 0;     // (gathered: an index load, issued first)
+  }
+  KvRowStage<DH, 64 * NW, BN, GATHER> stage;
+  stage.index(gi, seg.row0, 0, seg.nk);
+  stage.load(kh, vh, ks, vs);
+  stage.index(gi, seg.row0, BN, seg.nk);
+  bf16x8 qf[2][KK];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) load_q_frags<DH>(q + q_src[c] * qs + h * DH, q_ok[c], hh, qf[c]);
+  FwdAcc<DH> acc[2];
+  acc[0].init();
+  acc[1].init();
+  stage.store(lds.Ks[0], lds.Vs[0]);
+  __syncthreads();
+  if (nc == 2) tiled2_wave<DH, NW, BN, 2, GATHER>(lds, stage, seg, gi, kh, vh, ks, vs, qf, acc, scale_log2, lane);
+  else if (nc == 1) tiled2_wave<DH, NW, BN, 1, GATHER>(lds, stage, seg, gi, kh, vh, ks, vs, qf, acc, scale_log2, lane);
+  else tiled2_wave<DH, NW, BN, 0, GATHER>(lds, stage, seg, gi, kh, vh, ks, vs, qf, acc, scale_log2, lane);
+
+  __bf16* tile = &lds.Ks[0][0] + wv * 64 * RS;
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+    if (c < nc)
+      fwd_park<DH, RS>(acc[c], q_ok[c], seg.nk > 0, tile + c * 32 * RS,
+                       lse != nullptr ? lse + h * lse_stride + seg.row0 + qw + 32 * c + l32 : nullptr, l32, hh);
+  __syncthreads();
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+    if (c < nc)
+      fwd_flush<DH, RS>(tile + c * 32 * RS, out, sc, seg.row0 + qw + 32 * c, h, C, min(32, seg.nq - qw - 32 * c), lane);
+}
+
+template <int DH, int NW, int BN, bool GATHER>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2)))
+attn_fwd_bf16_tiled2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                            const __bf16* __restrict__ v, long qs, long ks, long vs,
+                            const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int n_pad,
+                            int H, float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse,
+                            long lse_stride, Scatter sc, int B, int nqb) {
+  __shared__ Tiled2Lds<DH, BN> lds;
+  __shared__ int s_cu[2 * kLptMaxB + 1];
+  __shared__ int s_pick;
+
+  const TileId tile_id = xcd_tile(nqb, H, B);
+  if (!tile_id.valid) return;
+  const int h = tile_id.h;
+  const Segment seg = lpt_segment<64 * NW>(tile_id.rank, B, cu, key_lens, n_pad, s_cu, &s_pick);
+  const long C = (long)H * DH;
+  const int fill_img = key_lens == nullptr && B > 1 && B <= kLptMaxB ? s_pick : tile_id.rank;
+  const FillRange fr = fill_range(sc, fill_img, B, tile_id.qb, nqb);
+  const int q0 = tile_id.qb * (64 * NW);
+  if (q0 < seg.nq)
+    tiled2_attention<DH, NW, BN, GATHER>(lds, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
   if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64 * NW);
 }
 
@@ -429,7 +737,7 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
 // instead of concentrating a heavy (image, head) on one compute unit.
 // The wave's work on queries [q0, q0 + 32) of head h of segment seg (q0 < seg.nq): Ks, Vs are
 // its private LDS tiles of STEP rows.
-template <int DH, int STEP>
+template <int DH, int STEP, bool GATHER>
 __device__ __forceinline__ void
 wave_attention(__bf16* Ks, __bf16* Vs, const Segment seg, int h, int q0, const __bf16* __restrict__ q,
                const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs, int H,
@@ -447,24 +755,38 @@ wave_attention(__bf16* Ks, __bf16* Vs, const Segment seg, int h, int q0, const _
 
   // lane -> (row, chunk) of the step's tile: 8 (Dh 64) or 4 (Dh 32) lanes cover one row
   bf16x8 kreg[LPL], vreg[LPL];
-  const int32_t* gi = gather_base(sc, seg.row0);
-  int rows[LPL];                                  // source rows of the next gload (-1: past the segment)
+  const int32_t* gi = gather_base<GATHER>(sc, seg.row0);
+  int tok_rows[LPL];                              // gathered rows only: token rows of the next gload
+  int kt_next = 0;                                // first key of the step the next gload fetches
+  const int c = lane % CPR, lrow = lane / CPR;
+  const uint32_t koff = (uint32_t)lrow * (uint32_t)ks + c * 8, voff = (uint32_t)lrow * (uint32_t)vs + c * 8;
   auto iload = [&](int kt) {                      // issued one step ahead of the row loads that use it
+    kt_next = kt;
+    if (GATHER) {
 #pragma unroll
-    for (int t = 0; t < LPL; ++t) {
-      const int r = kt + (lane + 64 * t) / CPR;
-      rows[t] = r < seg.nk ? (int)source_row(gi, seg.row0, r) : -1;
+      for (int t = 0; t < LPL; ++t) {
+        const int r = kt + lrow + t * (64 / CPR);
+        if (r < seg.nk) tok_rows[t] = gi[r];
+      }
     }
   };
-  auto gload = [&]() {
+  auto gload = [&]() {                            // rows past the segment read as zero
 #pragma unroll
     for (int t = 0; t < LPL; ++t) {
-      const int c = (lane + 64 * t) % CPR;
       kreg[t] = zero_bf16x8();
       vreg[t] = zero_bf16x8();
-      if (rows[t] >= 0) {
-        kreg[t] = *reinterpret_cast<const bf16x8*>(kh + (long)rows[t] * ks + c * 8);
-        vreg[t] = *reinterpret_cast<const bf16x8*>(vh + (long)rows[t] * vs + c * 8);
+      if (kt_next + lrow + t * (64 / CPR) < seg.nk) {
+        const __bf16 *kp, *vp;
+        if (GATHER) {
+          kp = kh + row_offset(tok_rows[t], ks) + c * 8;
+          vp = vh + row_offset(tok_rows[t], vs) + c * 8;
+        } else {
+          const long r = seg.row0 + kt_next + t * (64 / CPR);    // uniform: the lane's part is koff / voff
+          kp = kh + r * ks + koff;
+          vp = vh + r * vs + voff;
+        }
+        kreg[t] = *reinterpret_cast<const bf16x8*>(kp);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(vp);
       }
     }
   };
@@ -477,11 +799,12 @@ wave_attention(__bf16* Ks, __bf16* Vs, const Segment seg, int h, int q0, const _
     }
   };
 
-  iload(0);
+  const long q_src = q_ok ? source_row(gi, seg.row0, qi) : 0;   // (gathered: an index load, issued first, so that
+  iload(0);                                                      // its wait is the one the first row loads need anyway)
   gload();
   iload(STEP);
   bf16x8 qf[KK];
-  load_q_frags<DH>(q + (q_ok ? source_row(gi, seg.row0, qi) : 0) * qs + h * DH, q_ok, hh, qf);
+  load_q_frags<DH>(q + q_src * qs + h * DH, q_ok, hh, qf);
   FwdAcc<DH> acc;
   acc.init();
 
@@ -544,7 +867,7 @@ wave_attention(__bf16* Ks, __bf16* Vs, const Segment seg, int h, int q0, const _
   fwd_flush<DH, RS>(Ks, out, sc, seg.row0 + q0, h, C, min(32, seg.nq - q0), lane);
 }
 
-template <int DH, int STEP>
+template <int DH, int STEP, bool GATHER>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(STEP == 32 ? 3 : 1)))
 attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                           const __bf16* __restrict__ v, long qs, long ks, long vs,
@@ -564,7 +887,7 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   const FillRange fr = fill_range(sc, img, B, tile_id.qb, nqb);
   const int q0 = tile_id.qb * 32;
   if (q0 < seg.nq)
-    wave_attention<DH, STEP>(Ks, Vs, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
+    wave_attention<DH, STEP, GATHER>(Ks, Vs, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
   if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64);
 }
 
@@ -680,7 +1003,7 @@ static unsigned lpt64_grid(int B, int H, int nqb) {
 
 // Compiled for three waves per SIMD (168 registers at head dim 64, no spills): a ViT-B-shaped
 // batch has ~2800 live waves for 1024 SIMDs and then runs in one round instead of two.
-template <int DH, int STEP>
+template <int DH, int STEP, bool GATHER>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(3)))
 attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                                 const __bf16* __restrict__ v, long qs, long ks, long vs,
@@ -693,7 +1016,7 @@ attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __re
   const int x = blockIdx.x & 7, j = blockIdx.x >> 3, unit = j & 31, m = j >> 5;
   const LptBlock blk = lpt64_block<32>(cu, key_lens, n_pad, B, H, nqb, x, m * 32 + ((m & 1) ? 31 - unit : unit));
   if (blk.live)
-    wave_attention<DH, STEP>(Ks, Vs, blk.seg, blk.h, blk.q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride,
+    wave_attention<DH, STEP, GATHER>(Ks, Vs, blk.seg, blk.h, blk.q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride,
                              sc);
   if (sc.y != nullptr) {
     const long rows = sc.flat ? (long)sc.N : (long)B * sc.N, per = (rows + gridDim.x - 1) / gridDim.x;
@@ -706,7 +1029,7 @@ attn_fwd_bf16_wave_lpt64_kernel(const __bf16* __restrict__ q, const __bf16* __re
 // rows of the segment are staged once (each element is read from memory exactly once per
 // head), one barrier, then wave w owns queries [32w, 32w+32) and walks the keys in LDS with
 // no further synchronisation.  No workgroup is launched for nothing.
-template <int DH, int NKMAX>
+template <int DH, int NKMAX, bool GATHER>
 __global__ void __launch_bounds__(2 * NKMAX)
 attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                            const __bf16* __restrict__ v, long qs, long ks, long vs,
@@ -735,8 +1058,8 @@ attn_fwd_bf16_whole_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   const bool wave_live = wv * 32 < seg.nq;
   const bool q_ok = qi < seg.nq;
 
-  const int32_t* gi = gather_base(sc, seg.row0);
-  KvStage<DH, THREADS, (NKMAX / 2) * (DH / 8)> stage;
+  const int32_t* gi = gather_base<GATHER>(sc, seg.row0);
+  KvStage<DH, THREADS, (NKMAX / 2) * (DH / 8), GATHER> stage;
   stage.index(gi, seg.row0, 0, seg.nk);
   stage.load(k + h * DH, v + h * DH, ks, vs);
   bf16x8 qf[DH / 16];
@@ -799,7 +1122,7 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
   float qr[DH], o[DH];
 #pragma unroll
   for (int d = 0; d < DH; ++d) { qr[d] = 0.f; o[d] = 0.f; }
-  const int32_t* gi = gather_base(sc, seg.row0);
+  const int32_t* gi = sc.gathered ? sc.gather_idx + seg.row0 : nullptr;
   if (q_ok) {
     const float* qp = q + source_row(gi, seg.row0, qi) * qs + h * DH;
 #pragma unroll
@@ -910,6 +1233,8 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
   const int64_t strides[3] = {q_stride, k_stride, v_stride};
   for (int64_t rs : strides) {
     SPA_REQUIRE(rs >= (int64_t)H * Dh, SPA_ERR_INVALID_ARG, "%s: row stride %ld < H*Dh", fn, (long)rs);
+    // the kernels keep a lane's offset inside a tile (up to 128 rows) in 32 bits
+    SPA_REQUIRE(rs < (1 << 24), SPA_ERR_INVALID_ARG, "%s: row stride %ld must be < 2^24 elements", fn, (long)rs);
     SPA_REQUIRE((rs * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG, "%s: row stride is not a multiple of 16 bytes", fn);
   }
   SPA_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(out), SPA_ERR_INVALID_ARG,
@@ -929,6 +1254,13 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
 #undef SPA_F32_LAUNCH
   } else {
     const float scale_log2 = scale * 1.4426950408889634f;
+#define SPA_ARGS_PLAIN SPA_ARGS
+#define SPA_ARGS_BN SPA_ARGS, B, nqb
+#define SPA_LAUNCH(KERNEL, GRID, BLOCK, ARGS, ...)                                                            \
+  do {                                                                                                        \
+    if (sc.gathered) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, true>), GRID, BLOCK, 0, st, ARGS);               \
+    else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, false>), GRID, BLOCK, 0, st, ARGS);                          \
+  } while (0)
 #define SPA_ARGS                                                                                              \
   (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (long)q_stride, (long)k_stride, (long)v_stride, cu,   \
       key_lens, n_max, H, scale_log2, (__bf16*)out, lse, lse_stride, sc
@@ -946,41 +1278,50 @@ static int attention_common(const char* fn, const void* q, const void* k, const 
       const bool step64 = opt.fwd_step64, plain = opt.fwd_plain;
       if (!step64 && !plain && B <= kWave) {
         const dim3 lgrid(lpt64_grid(B, H, nqb));
-        if (Dh == 32) hipLaunchKernelGGL((attn_fwd_bf16_wave_lpt64_kernel<32, 32>), lgrid, dim3(64), 0, st, SPA_ARGS, B, nqb);
-        else hipLaunchKernelGGL((attn_fwd_bf16_wave_lpt64_kernel<64, 32>), lgrid, dim3(64), 0, st, SPA_ARGS, B, nqb);
+        if (Dh == 32) SPA_LAUNCH(attn_fwd_bf16_wave_lpt64_kernel, lgrid, dim3(64), SPA_ARGS_BN, 32, 32);
+        else SPA_LAUNCH(attn_fwd_bf16_wave_lpt64_kernel, lgrid, dim3(64), SPA_ARGS_BN, 64, 32);
       } else if (Dh == 32) {
-        if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 64>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
-        else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<32, 32>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
+        if (step64) SPA_LAUNCH(attn_fwd_bf16_wave_kernel, grid, dim3(64), SPA_ARGS_BN, 32, 64);
+        else SPA_LAUNCH(attn_fwd_bf16_wave_kernel, grid, dim3(64), SPA_ARGS_BN, 32, 32);
       } else {
-        if (step64) hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<64, 64>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
-        else hipLaunchKernelGGL((attn_fwd_bf16_wave_kernel<64, 32>), grid, dim3(64), 0, st, SPA_ARGS, B, nqb);
+        if (step64) SPA_LAUNCH(attn_fwd_bf16_wave_kernel, grid, dim3(64), SPA_ARGS_BN, 64, 64);
+        else SPA_LAUNCH(attn_fwd_bf16_wave_kernel, grid, dim3(64), SPA_ARGS_BN, 64, 32);
       }
     } else if (NW == 0 && n_max <= 256) {
       // short segments: one workgroup per (image, head), whole segment in LDS
       const dim3 grid(H, B);
 #define SPA_WHOLE(D)                                                                                          \
   do {                                                                                                        \
-    if (n_max <= 64) hipLaunchKernelGGL((attn_fwd_bf16_whole_kernel<D, 64>), grid, dim3(128), 0, st, SPA_ARGS);       \
-    else if (n_max <= 128) hipLaunchKernelGGL((attn_fwd_bf16_whole_kernel<D, 128>), grid, dim3(256), 0, st, SPA_ARGS); \
-    else hipLaunchKernelGGL((attn_fwd_bf16_whole_kernel<D, 256>), grid, dim3(512), 0, st, SPA_ARGS);          \
+    if (n_max <= 64) SPA_LAUNCH(attn_fwd_bf16_whole_kernel, grid, dim3(128), SPA_ARGS_PLAIN, D, 64);       \
+    else if (n_max <= 128) SPA_LAUNCH(attn_fwd_bf16_whole_kernel, grid, dim3(256), SPA_ARGS_PLAIN, D, 128); \
+    else SPA_LAUNCH(attn_fwd_bf16_whole_kernel, grid, dim3(512), SPA_ARGS_PLAIN, D, 256);          \
   } while (0)
       if (Dh == 32) SPA_WHOLE(32); else SPA_WHOLE(64);
 #undef SPA_WHOLE
+    } else if (NW == 0 && opt.fwd_long_two) {
+      // long segments: two query chains per wave, 2 waves x 64 queries per workgroup, 64-key tiles
+      const int nqb = (n_max + 127) / 128;
+      const dim3 grid(xcd_grid(nqb, H, B)), block(128);
+      if (Dh == 32) SPA_LAUNCH(attn_fwd_bf16_tiled2_kernel, grid, block, SPA_ARGS_BN, 32, 2, 64);
+      else SPA_LAUNCH(attn_fwd_bf16_tiled2_kernel, grid, block, SPA_ARGS_BN, 64, 2, 64);
     } else {
       if (NW == 0) { NW = 4; BN = 128; }
       const int nqb = (n_max + 32 * NW - 1) / (32 * NW);
       const dim3 grid(xcd_grid(nqb, H, B)), block(64 * NW);
 #define SPA_TILED(D)                                                                                          \
   do {                                                                                                        \
-    if (NW == 2 && BN == 64) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 2, 64>), grid, block, 0, st, SPA_ARGS, B, nqb);        \
-    else if (NW == 2) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 2, 128>), grid, block, 0, st, SPA_ARGS, B, nqb);              \
-    else if (BN == 64) hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 4, 64>), grid, block, 0, st, SPA_ARGS, B, nqb);              \
-    else hipLaunchKernelGGL((attn_fwd_bf16_tiled_kernel<D, 4, 128>), grid, block, 0, st, SPA_ARGS, B, nqb);           \
+    if (NW == 2 && BN == 64) SPA_LAUNCH(attn_fwd_bf16_tiled_kernel, grid, block, SPA_ARGS_BN, D, 2, 64);        \
+    else if (NW == 2) SPA_LAUNCH(attn_fwd_bf16_tiled_kernel, grid, block, SPA_ARGS_BN, D, 2, 128);              \
+    else if (BN == 64) SPA_LAUNCH(attn_fwd_bf16_tiled_kernel, grid, block, SPA_ARGS_BN, D, 4, 64);              \
+    else SPA_LAUNCH(attn_fwd_bf16_tiled_kernel, grid, block, SPA_ARGS_BN, D, 4, 128);           \
   } while (0)
       if (Dh == 32) SPA_TILED(32); else SPA_TILED(64);
 #undef SPA_TILED
     }
 #undef SPA_ARGS
+#undef SPA_ARGS_PLAIN
+#undef SPA_ARGS_BN
+#undef SPA_LAUNCH
   }
   return check_launch(fn);
 }

@@ -16,6 +16,7 @@ int check_launch(const char* what);                // hipGetLastError -> SPA_ERR
 // Launch options (tuning aids and kernel selection for tests), see spa_set_option in spa.h.
 struct Options {
   bool fwd_whole, fwd_step64, fwd_plain;   // attn_fwd_short
+  bool fwd_long_two;                       // attn_fwd_long = two (two query chains per wave)
   int fwd_nw, fwd_bn;                      // attn_fwd_cfg (0 = automatic)
   int fwd_wave_max;                        // attn_fwd_wave_max
   int bwd_short;                           // attn_bwd_short: 0 one kernel, 1 split, 2 tiled
