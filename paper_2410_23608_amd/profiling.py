@@ -38,10 +38,30 @@ CHAINS = {
 CHAINS["hierarchy"] = CHAINS["train"]
 
 
+def template_args(mangled: str) -> str:
+    """'DF16bLi16ELb0E' -> 'bf16, 16, false' (the few forms libspa's kernel templates use)."""
+    out, i = [], 0
+    while i < len(mangled):
+        if mangled.startswith("DF16b", i):
+            out.append("bf16")
+            i += 5
+        elif mangled[i] == "f":
+            out.append("float")
+            i += 1
+        elif mangled[i] == "L" and (m := re.match(r"L([ib])(n?\d+)E", mangled[i:])):
+            v = m.group(2).replace("n", "-")
+            out.append(v if m.group(1) == "i" else ("true" if v != "0" else "false"))
+            i += m.end()
+        else:
+            return mangled
+    return ", ".join(out)
+
+
 def short(name: str) -> str:
     m = re.match(r"_ZN3spa\d+([a-z_0-9]+?_kernel)I(.*?)E+v", name)      # names the profiler left mangled
     if m:
-        return m.group(1) + "<" + m.group(2) + ">"
+        args = m.group(2)                      # (the pattern's E+ may have eaten the last literal's closing E)
+        return m.group(1) + "<" + template_args(args if re.search(r"L[ib]n?\d+$", args) is None else args + "E") + ">"
     name = re.sub(r"\(.*", "", name).replace("void ", "").replace("spa::", "")
     return name.strip()
 
@@ -81,16 +101,19 @@ def stage_labels(groups, chain):
     kernel shares a name; other chains: the call itself."""
     if chain != "hierarchy":
         return {g: g[1] for g in groups}
-    by_kernel = defaultdict(list)
+    by_family = defaultdict(list)                 # instances of one kernel template differ by stage (lanes per token)
     for g in groups:
-        by_kernel[g[0]].append(g)
+        by_family[(g[1], g[0].split("<")[0])].append(g)
     labels = {}
-    for kname, gs in by_kernel.items():
-        gs.sort(key=lambda g: -g[2])
+    for (_, family), gs in by_family.items():
+        # a stage = a distinct grid size; the gate backward picks its instance (tokens per workgroup) by the
+        # stage's C and two of them launch the same grid, so there the instance tells the stages apart
+        key = lambda g: (-g[2], g[0] if family == "gate_bwd_kernel" else "")
+        ranks = sorted({key(g) for g in gs})
         # kernels of the long-segment forms serve the two finest stages, the short forms the two coarsest
-        first = 3 if (("wave" in kname or "fused" in kname) and len(gs) <= 2) else 1
-        for i, g in enumerate(gs):
-            labels[g] = f"s{first + i}.{g[1]}"
+        first = 3 if (("wave" in family or "fused" in family) and len(ranks) <= 2) else 1
+        for g in gs:
+            labels[g] = f"s{first + ranks.index(key(g))}.{g[1]}"
     return labels
 
 
