@@ -526,27 +526,36 @@ attn_bwd_fused_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restric
       }
     }
   };
-  // longest image first (work per segment grows like n^2); the ranking borrows the dS tiles
-  int img = rank;
-  if (B > 1 && B <= 512 && B * (int)sizeof(int) <= nw * 32 * SS * 2) {
-    int* s_len = reinterpret_cast<int*>(scr);
-    for (int b = tid; b < B; b += threads) s_len[b] = cu[b + 1] - cu[b];
-    __syncthreads();
-    for (int b = tid; b < B; b += threads) {
-      const int nb = s_len[b];
-      int r = 0;
+  // heaviest image first (work per segment grows like n^2)
+  int img = rank, start = 0, len = 0;
+  if (B > 1 && B <= kWave) {                         // every wave ranks on its own: no LDS, no barrier
+    const RankedSegment rs = ranked_segment_wave(rank, B, cu, nw);
+    img = rs.img;
+    start = rs.row0;
+    len = rs.len;
+  } else {
+    if (B > 1 && B <= 512 && B * (int)sizeof(int) <= nw * 32 * SS * 2) {     // the ranking borrows the dS tiles
+      int* s_len = reinterpret_cast<int*>(scr);
+      for (int b = tid; b < B; b += threads) s_len[b] = cu[b + 1] - cu[b];
+      __syncthreads();
+      for (int b = tid; b < B; b += threads) {
+        const int nb = s_len[b];
+        int r = 0;
 #pragma unroll 8
-      for (int j = 0; j < B; ++j) {
-        const int nj = s_len[j];
-        r += (nj > nb) | ((nj == nb) & (j < b));
+        for (int j = 0; j < B; ++j) {
+          const int nj = s_len[j];
+          r += (nj > nb) | ((nj == nb) & (j < b));
+        }
+        if (r == rank) s_pick = b;
       }
-      if (r == rank) s_pick = b;
+      __syncthreads();
+      img = s_pick;
     }
-    __syncthreads();
-    img = s_pick;
+    start = cu[img];
+    len = cu[img + 1] - start;
   }
-  const long row0 = cu[img];
-  const int n = min(cu[img + 1] - cu[img], rows_cap);
+  const long row0 = start;
+  const int n = min(len, rows_cap);
   if (n <= 0) {
     zero_unselected();
     return;

@@ -932,19 +932,6 @@ __device__ __forceinline__ int pairs_below(int X, int x) {        // XCD x's pai
   const int g = X >> 3, s = (g & 1) ? 7 - x : x;
   return g + (s < (X & 7) ? 1 : 0);
 }
-__device__ __forceinline__ int kth_set_bit(uint64_t mask, int kth) {   // kth < popcount(mask)
-  int pos = 0;
-#pragma unroll
-  for (int sh = 32; sh >= 1; sh >>= 1) {
-    const int cnt = __popcll((mask >> pos) & ((1ull << sh) - 1ull));
-    if (kth >= cnt) {
-      kth -= cnt;
-      pos += sh;
-    }
-  }
-  return pos;
-}
-
 // Block number r of XCD x -> its segment, head and first query (live = false: past the live
 // blocks).  QB = queries per block; a segment's class is its number of blocks.  Every wave of
 // the workgroup computes the same answer from its own ballots.

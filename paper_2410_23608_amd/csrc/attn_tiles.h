@@ -149,6 +149,48 @@ static unsigned xcd_grid(int nqb, int H, int B) {
   return (unsigned)(pairs8 * 8 * nqb);
 }
 
+// Position of the kth set bit of mask (kth < popcount(mask)): binary search on popcounts.
+__device__ __forceinline__ int kth_set_bit(uint64_t mask, int kth) {
+  int pos = 0;
+#pragma unroll
+  for (int sh = 32; sh >= 1; sh >>= 1) {
+    const int cnt = __popcll((mask >> pos) & ((1ull << sh) - 1ull));
+    if (kth >= cnt) {
+      kth -= cnt;
+      pos += sh;
+    }
+  }
+  return pos;
+}
+
+// Heaviest-class-first launch order for up to 64 segments, computed by every wave on its own (no
+// LDS, no barrier): lane b holds segment b's bounds, a segment's class is its number of 32-row
+// tiles (<= ncls), launch rank r is the (r - #heavier)th segment of its class in index order.
+// Returns the segment of launch rank `rank` (< B) with its length.
+struct RankedSegment {
+  int img, row0, len;
+};
+__device__ __forceinline__ RankedSegment ranked_segment_wave(int rank, int B, const int32_t* __restrict__ cu, int ncls) {
+  const int lane = threadIdx.x & 63;
+  int start = 0, len = 0, cls = -1;
+  if (lane < B) {
+    start = cu[lane];
+    len = cu[lane + 1] - start;
+    cls = min((max(len, 0) + 31) >> 5, ncls);
+  }
+  int img = 0, ranked = 0;
+  for (int c = ncls; c >= 0; --c) {
+    const uint64_t bal = __ballot(cls == c);
+    const int n_c = __popcll(bal);
+    if (rank < ranked + n_c) {
+      img = kth_set_bit(bal, rank - ranked);
+      break;
+    }
+    ranked += n_c;
+  }
+  return {img, __builtin_amdgcn_readlane(start, img), __builtin_amdgcn_readlane(len, img)};
+}
+
 // Longest-segment-first launch order.  Work per segment grows like n^2 and workgroups are
 // handed to compute units in launch order, so the heaviest images should start first.  Maps
 // launch rank -> image by ranking the segment lengths (ties by index) and returns that
