@@ -703,7 +703,7 @@ def main():
     head, ctx = fwd(args.workload)
     configs = {args.workload: head}
     if wl.dtype == "bf16":
-        for name in ("vit_s", "det"):
+        for name in ("tiny", "vit_s", "det"):
             if name not in configs:
                 configs[name], _ = fwd(name)
         configs["vit_b_train"] = measure_train(args, torch, workloads, pipeline.TrainPass, traffic_table, ctx["streams"])

@@ -1,7 +1,10 @@
 """Builds libspa.so (gfx950 only) from csrc/*.hip with hipcc.
 
-Usage: python -m paper_2410_23608_amd.build [--force]
+Usage: python -m paper_2410_23608_amd.build [--sanitize-host]
 The shared library is written next to this file so that it travels with the source tree.
+--sanitize-host builds _build_asan/libspa_asan.so instead: the HOST side of every source under
+AddressSanitizer and UndefinedBehaviorSanitizer (device code unchanged), for the host-only checks
+of tests/test_host_sanitizers.py; it is never loaded by the binding.
 """
 from __future__ import annotations
 
@@ -38,9 +41,16 @@ def sources():
 AGPR_SOURCES = {"linear_big.hip"}
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
-    flags = list(FLAGS)
+SAN_DIR = os.path.join(HERE, "_build_asan")
+SAN_LIB_PATH = os.path.join(SAN_DIR, "libspa_asan.so")
+# sanitizers on the host pass only: every -fsanitize= directly after -Xarch_host
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-omit-frame-pointer", "-g"]
+
+
+def _compile(src: str, sanitize: bool = False) -> str:
+    obj = os.path.join(SAN_DIR if sanitize else OBJ_DIR, os.path.basename(src)[:-4] + ".o")
+    flags = list(FLAGS) + (SAN_FLAGS if sanitize else [])
     if os.path.basename(src) in AGPR_SOURCES:
         i = flags.index("-amdgpu-mfma-vgpr-form=1")
         del flags[i - 1:i + 1]
@@ -51,22 +61,36 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    os.makedirs(OBJ_DIR, exist_ok=True)
+def build(verbose: bool = True, sanitize: bool = False) -> str:
+    os.makedirs(SAN_DIR if sanitize else OBJ_DIR, exist_ok=True)
     srcs = sources()
+    lib = SAN_LIB_PATH if sanitize else LIB_PATH
     if verbose:
-        print(f"[build] compiling {len(srcs)} HIP sources for gfx950", flush=True)
+        print(f"[build] compiling {len(srcs)} HIP sources for gfx950" + (" (host side sanitized)" if sanitize else ""),
+              flush=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(_compile, srcs))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+        objs = list(ex.map(lambda s_: _compile(s_, sanitize), srcs))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
+    if sanitize:   # (a link line has no -Xarch_ option: the device side is kept out explicitly)
+        cmd += ["-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
     if verbose:
-        print(f"[build] wrote {LIB_PATH}", flush=True)
-    return LIB_PATH
+        print(f"[build] wrote {lib}", flush=True)
+    return lib
+
+
+def sanitized_is_current() -> bool:
+    """True when _build_asan/libspa_asan.so is newer than every source and header it is built from."""
+    if not os.path.exists(SAN_LIB_PATH):
+        return False
+    t = os.path.getmtime(SAN_LIB_PATH)
+    deps = sources() + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    deps += [os.path.join(ROOT, "include", "spa.h"), os.path.abspath(__file__)]
+    return all(os.path.getmtime(d) <= t for d in deps)
 
 
 if __name__ == "__main__":
-    build()
+    build(sanitize="--sanitize-host" in sys.argv[1:])
     sys.exit(0)
