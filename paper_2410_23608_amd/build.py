@@ -2,7 +2,7 @@
 
 Usage: python -m paper_2410_23608_amd.build [--sanitize-host]
 The shared library is written next to this file so that it travels with the source tree.
---sanitize-host builds _build_asan/libspa_asan.so instead: the HOST side of every source under
+--sanitize-host builds libspa_asan.so in <tmp>/spa_build_asan instead: the HOST side of every source under
 AddressSanitizer and UndefinedBehaviorSanitizer (device code unchanged), for the host-only checks
 of tests/test_host_sanitizers.py; it is never loaded by the binding.
 """
@@ -12,6 +12,7 @@ import concurrent.futures
 import os
 import subprocess
 import sys
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -41,7 +42,8 @@ def sources():
 AGPR_SOURCES = {"linear_big.hip"}
 
 
-SAN_DIR = os.path.join(HERE, "_build_asan")
+# kept out of the source tree: nothing but the host-only sanitizer test reads it
+SAN_DIR = os.path.join(tempfile.gettempdir(), "spa_build_asan")
 SAN_LIB_PATH = os.path.join(SAN_DIR, "libspa_asan.so")
 # sanitizers on the host pass only: every -fsanitize= directly after -Xarch_host
 SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
@@ -82,7 +84,7 @@ def build(verbose: bool = True, sanitize: bool = False) -> str:
 
 
 def sanitized_is_current() -> bool:
-    """True when _build_asan/libspa_asan.so is newer than every source and header it is built from."""
+    """True when the sanitized library is newer than every source and header it is built from."""
     if not os.path.exists(SAN_LIB_PATH):
         return False
     t = os.path.getmtime(SAN_LIB_PATH)
