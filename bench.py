@@ -337,6 +337,12 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
         times[nme]["warm_cache_us"] = round(warm[nme], 2)
     kernels, roof = kernels_block(times, forward_work(wl, T, sum_n2), wl.dtype, wl.name, traffic_table, args.seed)
     roof["cache"] = f"cold: {n_sets} copies of the batch and its buffers in rotation ({n_sets * set_bytes >> 20} MB)"
+    # context beside `achieved` (the launch alone on one stream): the same algorithmic work over the
+    # whole step of the timed region, where the launches of S batches share the GPU
+    if roof.get("algorithmic_flops", 0) > 0:
+        peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else FP32_VECTOR_PEAK_TFLOPS
+        roof["tflops_over_step"] = round(roof["algorithmic_flops"] / med / 1e12, 2)
+        roof["mfma_frac_over_step"] = round(roof["algorithmic_flops"] / med / 1e12 / peak, 4)
     res = {
         "workload": f"{wl.name}: B={wl.B} N={wl.N} C={wl.C} H={wl.H} Dh={wl.Dh} {wl.dtype}, selected fraction "
                     f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward select+pack+attention+unpack",
