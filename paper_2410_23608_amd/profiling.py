@@ -36,6 +36,11 @@ CHAINS = {
               ("attn_bwd", "packed_attention_bwd_tokens"), ("gate_bwd", "gate_bwd")],
 }
 CHAINS["hierarchy"] = CHAINS["train"]
+# a whole bench.py run (every configuration and the extras): calls named by kind only
+CHAINS["all"] = [("gate_select_kernel", "gate"), ("count_selected", "gate"), ("pack_kernel", "pack"), ("unpack_kernel", "unpack"),
+                 ("gather_rows", "unpack / pack backward"), ("attn_fwd", "attention forward"), ("attn_bwd", "attention backward"),
+                 ("gate_bwd", "gate backward"), ("linear_bwd", "projection backward"), ("linear", "projection"),
+                 ("container_segments", "container segments"), ("maxpool", "max-pool"), ("ceiling", "yardstick")]
 
 
 def template_args(mangled: str) -> str:
@@ -127,15 +132,21 @@ def cmd_kernels(a):
     out = [f"# rocprofv3 kernel trace: {a.title or a.chain + ', ' + a.workload}, one stream (every kernel runs alone)", "",
            "Command (MI355X box):", "", f"    {PRE}{a.command}", "",
            "libspa kernels of that run, by kernel and grid size (the run holds the warm-up, the timed steps, the "
-           "event-instrumented steps and the back-to-back launches of bench.py):", "",
+           "event-instrumented steps and the back-to-back launches of bench.py):" if a.chain != "all" else
+           "libspa kernels of that run, by kernel and grid size.  The run holds every configuration and the extras; a "
+           "kernel's launches are partly overlapped with the launches of other batches in flight (the timed regions of "
+           "the forward and training steps) and partly alone (the per-kernel timing passes), so min and median "
+           "describe the launch alone and avg / max the launches under overlap:", "",
            "| call | kernel | grid (threads) | launches | avg us | median us | min us | max us |", "|---|---|---|---|---|---|---|---|"]
+    if a.chain == "all":
+        out[0] = f"# rocprofv3 kernel trace: {a.title or 'a whole bench.py run'} (the 60 kernel / grid pairs with the most GPU time)"
     for g in sorted(groups, key=lambda g: -sum(groups[g])):
         d = groups[g]
         out.append(f"| {labels[g]} | {g[0]} | {g[2]} | {len(d)} | {statistics.mean(d):.2f} | {statistics.median(d):.2f} | "
                    f"{min(d):.2f} | {max(d):.2f} |")
     if a.note:
         out += ["", a.note]
-    write(f"kernels_{a.workload}.md", out)
+    write(f"kernels_{a.workload}.md", out[:10 + 60] if a.chain == "all" else out)
 
 
 def counters(d: str):
