@@ -47,10 +47,12 @@ def parse_args():
                     help="independent batches in flight, one HIP stream each (1 = one stream, steps back to back)")
     ap.add_argument("--only", default=None, choices=["forward", "vit_s", "det", "vit_b_train", "hierarchy"],
                     help="measure one chain only (profiling runs): forward = the headline workload's forward chain")
-    ap.add_argument("--form", default="gathered", choices=["fused", "gathered", "packed"],
-                    help="forward step: gate, index-only pack, attention on gathered rows (default, 3 launches); "
-                         "gate + packing index in one launch, attention on gathered rows (2 launches); gate, pack of "
-                         "the rows, attention on the packed rows (3)")
+    ap.add_argument("--form", default="auto", choices=["auto", "selected", "fused", "gathered", "packed"],
+                    help="forward step.  gathered: gate, index-only pack, attention on gathered rows (3 launches); "
+                         "selected: gate, attention that takes the packing order from the mask itself (2 launches; "
+                         "images of at most 256 tokens, bf16); auto (default): selected where it applies, else gathered; "
+                         "fused: gate + packing index in one launch, attention on gathered rows (2 launches); packed: "
+                         "gate, pack of the rows, attention on the packed rows (3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the four-call form, graph replay, padded baseline, widened rows")
@@ -241,9 +243,21 @@ def forward_work(wl, T, sum_n2, keep_out=False):
         "pack": (0.0, 2 * T * 3 * C * e + 4 * T + 5 * B * N + 4 * (B + 1)),
         "pack_indices": (0.0, 4 * T + 5 * B * N + 4 * (B + 1)),
         "packed_attention_unpack": attn, "gathered_attention_unpack": attn,
+        # no index arrays: the mask bytes are read instead (once per query block and head; counted once)
+        "selected_attention_unpack": (attn[0], attn[1] - 4 * T - 4 * B * N - 4 * (B + 1) + B * N),
         "packed_attention": (4.0 * C * sum_n2, T * 3 * C * e + T * C * e + 4 * H * T + 4 * (B + 1)),
         "unpack": (0.0, T * C * e + 4 * B * N + B * N * C * e),
     }
+
+
+def forward_form(requested, wl):
+    """The form a forward workload is timed in: `selected` needs images of at most 256 tokens and bf16."""
+    fits = wl.N <= 256 and wl.dtype == "bf16"
+    if requested == "auto":
+        return "selected" if fits else "gathered"
+    if requested == "selected" and not fits:
+        return "gathered"
+    return requested
 
 
 def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, streams_cache):
@@ -253,9 +267,10 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
     bun = workloads.generate(wl, args.seed)
     up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(td).contiguous()
     x, w, qkv = up(bun["x"]), up(bun["w"]), up(bun["qkv"])
-    gathered = args.form in ("gathered", "fused")
+    form = forward_form(args.form, wl)
+    gathered = form in ("gathered", "fused", "selected")
     mk = lambda: ForwardPass(wl.B, wl.N, wl.C, wl.H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False,
-                             gathered=gathered, fused_index=args.form == "fused")
+                             gathered=gathered, fused_index=form == "fused", from_mask=form == "selected")
     fp = mk()
     stages = fp.stages(x, w, qkv)
 
@@ -266,8 +281,8 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
     for _ in range(max(args.warmup, 1)):
         step()
     torch.cuda.synchronize()
-    T = int(fp.total.item())
-    n = np.diff(fp.cu_seqlens.cpu().numpy()).astype(np.float64)
+    n = fp.mask.sum(dim=1).cpu().numpy().astype(np.float64)      # (the selected form writes no cu_seqlens / total)
+    T = int(n.sum())
     sum_n2 = float((n * n).sum())
 
     # one stream, steps back to back on ONE copy of the batch (warm last-level cache): the latency of a step
@@ -325,7 +340,7 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
     torch.cuda.synchronize()
     turn[0] = 0
     med, mn = timed_regions(sstep, args.steps, args.repeats, torch)
-    if not all(torch.equal(fs.y, fp.y) and int(fs.total.item()) == T for fs, _, _ in sets):
+    if not all(torch.equal(fs.y, fp.y) and int(fs.mask.sum().item()) == T for fs, _, _ in sets):
         print("bench.py: a copy's result differs from the single-stream result", file=sys.stderr)
         sys.exit(1)
 
@@ -545,11 +560,13 @@ def measure_extras(wl, ctx, args, torch, spa, workloads, pipeline):
                              "cache": "warm (one copy of the batch, one stream)",
                              "y_equals_headline_form": bool(torch.equal(fp4.y, fp.y)), "kernels": four}
     # the other forward forms (rows copied by the pack launch / fetched through the index / index built by the gate launch)
-    for other in ("fused", "gathered", "packed"):
-        if other == args.form:
+    timed_form = forward_form(args.form, wl)
+    for other in ("selected", "fused", "gathered", "packed"):
+        if other == timed_form or forward_form(other, wl) != other:
             continue
         fpo = pipeline.ForwardPass(B, N, C, H, wl.dtype, wl.tau, wl.bias, keep_packed_out=False,
-                                   gathered=other != "packed", fused_index=other == "fused")
+                                   gathered=other != "packed", fused_index=other == "fused",
+                                   from_mask=other == "selected")
         sto = fpo.stages(x, w, qkv)
         medo = run_chain(sto)
         out[f"{other}_form"] = {"ms_per_step": 1e3 * medo, "value": T / medo, "cache": "warm, one stream",
@@ -566,8 +583,8 @@ def measure_extras(wl, ctx, args, torch, spa, workloads, pipeline):
         out["graph_replay"] = {"error": str(ex)[:200]}
     # padded-to-max masked attention on the same selected tokens
     n_max = int(n.max())
-    cu = fp.cu_seqlens.cpu().numpy()
-    gidx = fp.gather_idx.cpu().numpy()
+    cu = fp4.cu_seqlens.cpu().numpy()                     # (the four-call pass above always builds the index)
+    gidx = fp4.gather_idx.cpu().numpy()
     flat_qkv = qkv.view(B * N, 3 * C)
     packed = flat_qkv[torch.from_numpy(gidx[:T].astype(np.int64)).cuda()].contiguous()   # setup of the padded inputs only
     pad = torch.zeros(B, n_max, 3 * C, dtype=td, device="cuda")
@@ -582,7 +599,7 @@ def measure_extras(wl, ctx, args, torch, spa, workloads, pipeline):
     dfn = spa.spa_padded_attention(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], lens_full, B, n_max, H, wl.Dh, pout,
                                    prepare=True)
     aout = torch.empty(B * N, C, dtype=td, device="cuda")
-    afn = spa.spa_packed_attention(packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:], fp.cu_seqlens, B, N, H, wl.Dh,
+    afn = spa.spa_packed_attention(packed[:, :C], packed[:, C:2 * C], packed[:, 2 * C:], fp4.cu_seqlens, B, N, H, wl.Dh,
                                    aout, None, prepare=True)
     for f_ in (pfn, dfn, afn):
         f_()

@@ -306,6 +306,23 @@ int spa_gathered_attention_unpack(const void* q, const void* k, const void* v, i
                                   void* stream);
 
 /*
+ * Selection, packing order and attention in ONE call, for images of at most 256 tokens (Section 3.2:
+ * the positive tokens, in token order, attend to each other inside their image; the negative tokens
+ * go on directly): spa_gathered_attention_unpack without a packing index.  Every wave derives its
+ * image's part of gather_idx from the mask bytes themselves (survivors in token order, exactly what
+ * spa_pack writes), so no packing launch precedes the call: gate + this call = a forward step in two
+ * launches.  y is bit for bit what spa_pack (index only) + spa_gathered_attention_unpack give.
+ * in:  q, k, v at TOKEN positions (row i = flat token i; strides in elements, as spa_packed_attention);
+ *      mask [B,N] uint8 as spa_gate_select writes it; base [B,N,C] or NULL; N <= 256; bf16 only
+ *      (other sizes / fp32: SPA_ERR_UNSUPPORTED, use the index-only spa_pack + spa_gathered_attention_unpack).
+ * out: y [B,N,C] as spa_packed_attention_unpack.  No packed output, no lse (forward only).
+ */
+int spa_selected_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                  int64_t k_row_stride, int64_t v_row_stride, const uint8_t* mask,
+                                  const void* base, int B, int N, int H, int Dh, int dtype,
+                                  float softmax_scale, void* y, void* stream);
+
+/*
  * spa_packed_attention_unpack for segments that are not whole images (the container-local
  * segments of spa_container_segments): attention inside every segment of seg_cu_seqlens and,
  * in the same launch, the scatter back to y with the fill of the bypassing rows.  Results equal

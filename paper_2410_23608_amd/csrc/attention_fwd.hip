@@ -41,7 +41,12 @@ struct Scatter {
   int gathered;                // 1: q, k, v are NOT packed: the row of packed position j is row
                                //    gather_idx[j] of q, k, v (token positions); packing then only
                                //    builds the index and no row is copied before the attention
+  const uint8_t* mask;         // [B*N] or nullptr: when given, a token bypasses attention iff its mask byte is 0
+                               //    (used in place of inv_pos by the form that is given no packing index)
 };
+__device__ __forceinline__ bool bypasses(const Scatter& sc, long row) {
+  return sc.mask != nullptr ? sc.mask[row] == 0 : sc.inv_pos[row] < 0;
+}
 
 // Row of q / k / v that holds packed position j of a segment starting at packed row row0:
 // gi = gather_idx + row0 when the rows are gathered through the index, else null.
@@ -93,7 +98,7 @@ __device__ __forceinline__ void scatter_fill(const Scatter& sc, int b, int t0, i
   const int work = (t1 - t0) * CPR;
   for (int i = tid; i < work; i += nthreads) {
     const int t = t0 + i / CPR, c = i % CPR;
-    if (sc.inv_pos[tok0 + t] < 0) {
+    if (bypasses(sc, tok0 + t)) {
       const long off = (tok0 + t) * C + h * DH + c * VE;
       uintx4 val = {0u, 0u, 0u, 0u};
       if (sc.base != nullptr) val = *reinterpret_cast<const uintx4*>(static_cast<const T*>(sc.base) + off);
@@ -891,6 +896,48 @@ attn_fwd_bf16_wave_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64);
 }
 
+// The one-wave work units driven by the selection mask itself: no packing launch precedes this
+// kernel.  The wave reads its image's N <= 256 mask bytes, ranks the survivors with ballots and
+// writes their token rows, in order, to a list in LDS: exactly the image's part of gather_idx, so
+// wave_attention runs on it as on gathered rows (packed position j of the image = row list[j] of
+// q, k, v and of y), and the bypass fill tests the mask byte instead of inv_pos.  Costs four byte
+// loads and four ballots per wave where the other forms cost a kernel launch.
+template <int DH, int STEP>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(3)))
+attn_fwd_bf16_wave_mask_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                               const __bf16* __restrict__ v, long qs, long ks, long vs,
+                               const uint8_t* __restrict__ mask, int N, int H, float scale_log2, Scatter sc, int B,
+                               int nqb) {
+  constexpr int RS = DH + 8;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[STEP * RS];
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[STEP * RS];
+  __shared__ int32_t list[256];
+
+  const TileId tile_id = xcd_tile(nqb, H, B);
+  if (!tile_id.valid) return;
+  const int h = tile_id.h, img = tile_id.rank, lane = threadIdx.x;
+  const long tok0 = (long)img * N;
+  int n = 0;                                       // survivors of the image so far
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int t = lane + 64 * i;
+    const bool sel = t < N && mask[tok0 + t] != 0;
+    const uint64_t bal = __ballot(sel);
+    if (sel) list[n + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u))] = (int32_t)(tok0 + t);
+    n += __popcll(bal);
+  }
+  __syncthreads();
+  const Segment seg = {0, n, n};                   // packed rows numbered inside the image: row j <-> list[j]
+  Scatter scl = sc;
+  scl.gather_idx = list;
+  const long C = (long)H * DH;
+  const FillRange fr = fill_range(sc, img, B, tile_id.qb, nqb);
+  const int q0 = tile_id.qb * 32;
+  if (q0 < n)
+    wave_attention<DH, STEP, true>(Ks, Vs, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, nullptr, nullptr, 0, scl);
+  scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, lane, 64);
+}
+
 // The same work units, dealt to the compute units by weight (batches of up to 64 images, one
 // per lane).  All one-wave workgroups of the launch are resident at once and workgroup j of
 // an XCD runs on compute unit j % 32 (the hardware id register says so), so which units get
@@ -909,7 +956,7 @@ __device__ __forceinline__ void scatter_fill_rows(const Scatter& sc, long r0, lo
   const int cpr = (int)(C / VE);
   for (long rb = r0; rb < r1; rb += kWave) {
     const long row = rb + lane;
-    uint64_t todo = __ballot(row < r1 && sc.inv_pos[row] < 0);
+    uint64_t todo = __ballot(row < r1 && bypasses(sc, row));
     while (todo != 0) {
       const long off0 = (rb + __ffsll((unsigned long long)todo) - 1) * C;
       todo &= todo - 1;
@@ -1347,7 +1394,7 @@ extern "C" int spa_packed_attention_unpack(const void* q, const void* k, const v
               "spa_packed_attention_unpack: null pointer");
   SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG,
               "spa_packed_attention_unpack: y / base not 16-byte aligned");
-  const Scatter sc = {gather_idx, inv_pos, base, y, N, 0, 0};
+  const Scatter sc = {gather_idx, inv_pos, base, y, N, 0, 0, nullptr};
   return attention_common("spa_packed_attention_unpack", q, k, v, q_row_stride, k_row_stride, v_row_stride,
                           cu_seqlens, nullptr, B, N, H, Dh, dtype, softmax_scale, out, lse, sc, stream);
 }
@@ -1361,9 +1408,44 @@ extern "C" int spa_gathered_attention_unpack(const void* q, const void* k, const
   const char* fn = "spa_gathered_attention_unpack";
   SPA_REQUIRE(cu_seqlens && gather_idx && inv_pos && y, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG, "%s: y / base not 16-byte aligned", fn);
-  const Scatter sc = {gather_idx, inv_pos, base, y, N, 0, 1};
+  const Scatter sc = {gather_idx, inv_pos, base, y, N, 0, 1, nullptr};
   return attention_common(fn, q, k, v, q_row_stride, k_row_stride, v_row_stride, cu_seqlens, nullptr, B, N, H, Dh,
                           dtype, softmax_scale, out, lse, sc, stream);
+}
+
+extern "C" int spa_selected_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                                             int64_t k_row_stride, int64_t v_row_stride, const uint8_t* mask,
+                                             const void* base, int B, int N, int H, int Dh, int dtype,
+                                             float softmax_scale, void* y, void* stream) {
+  const char* fn = "spa_selected_attention_unpack";
+  SPA_REQUIRE(q && k && v && mask && y, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
+  SPA_REQUIRE(B >= 1 && N >= 1 && H >= 1, SPA_ERR_INVALID_ARG, "%s: B, N, H must be >= 1", fn);
+  SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
+  SPA_REQUIRE(dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: bf16 only (fp32: index-only spa_pack + spa_gathered_attention_unpack)", fn);
+  SPA_REQUIRE(N <= 256, SPA_ERR_UNSUPPORTED, "%s: N = %d > 256 tokens per image (use index-only spa_pack + spa_gathered_attention_unpack)", fn, N);
+  SPA_REQUIRE(Dh == 32 || Dh == 64, SPA_ERR_UNSUPPORTED, "%s: head dim %d not supported (32 or 64)", fn, Dh);
+  SPA_REQUIRE(B <= 65535 && H <= 65535 && (long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B, H <= 65535 and B*N < 2^31", fn);
+  const int64_t strides[3] = {q_row_stride, k_row_stride, v_row_stride};
+  for (int64_t rs : strides) {
+    SPA_REQUIRE(rs >= (int64_t)H * Dh && rs < (1 << 24), SPA_ERR_INVALID_ARG, "%s: row stride %ld outside [H*Dh, 2^24)", fn, (long)rs);
+    SPA_REQUIRE((rs * 2) % 16 == 0, SPA_ERR_INVALID_ARG, "%s: row stride is not a multiple of 16 bytes", fn);
+  }
+  SPA_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG,
+              "%s: q / k / v / y / base not 16-byte aligned", fn);
+  SPA_REQUIRE(softmax_scale >= 0.f && std::isfinite(softmax_scale), SPA_ERR_INVALID_ARG,
+              "%s: softmax_scale must be finite and >= 0 (0 = 1/sqrt(Dh))", fn);
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)Dh);
+  const float scale_log2 = scale * 1.4426950408889634f;
+  const Scatter sc = {nullptr, nullptr, base, y, N, 0, 1, mask};
+  const int nqb = (N + 31) / 32;
+  const dim3 grid(xcd_grid(nqb, H, B));
+#define SPA_SEL(D)                                                                                              \
+  hipLaunchKernelGGL((attn_fwd_bf16_wave_mask_kernel<D, 32>), grid, dim3(64), 0, as_stream(stream), (const __bf16*)q, \
+                     (const __bf16*)k, (const __bf16*)v, (long)q_row_stride, (long)k_row_stride, (long)v_row_stride,    \
+                     mask, N, H, scale_log2, sc, B, nqb)
+  if (Dh == 32) SPA_SEL(32); else SPA_SEL(64);
+#undef SPA_SEL
+  return check_launch(fn);
 }
 
 extern "C" int spa_segment_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,
@@ -1376,7 +1458,7 @@ extern "C" int spa_segment_attention_unpack(const void* q, const void* k, const 
   SPA_REQUIRE(seg_cu_seqlens && gather_idx && inv_pos && y, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(rows >= 1 && rows < 2147483647L, SPA_ERR_INVALID_ARG, "%s: rows must be in [1, 2^31)", fn);
   SPA_REQUIRE(aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG, "%s: y / base not 16-byte aligned", fn);
-  const Scatter sc = {gather_idx, inv_pos, base, y, (int)rows, 1, 0};
+  const Scatter sc = {gather_idx, inv_pos, base, y, (int)rows, 1, 0, nullptr};
   return attention_common(fn, q, k, v, q_row_stride, k_row_stride, v_row_stride, seg_cu_seqlens, nullptr, n_segments,
                           max_seqlen, H, Dh, dtype, softmax_scale, out, lse, sc, stream);
 }

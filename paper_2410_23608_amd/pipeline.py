@@ -28,11 +28,14 @@ class ForwardPass:
     fills the bypassing rows); the results are bit-identical to the two separate calls.
     gathered=True (fused form only): packing builds the index only and the attention kernel
     fetches the q | k | v rows through gather_idx from where they lie, so no row is copied
-    (spa_pack with x = NULL, then spa_gathered_attention_unpack); same results, bit for bit."""
+    (spa_pack with x = NULL, then spa_gathered_attention_unpack); same results, bit for bit.
+    from_mask=True (with gathered; N <= 256, bf16, forward only): no packing launch at all, the attention
+    kernel derives each image's packing order from the mask (spa_selected_attention_unpack): two launches
+    per step, same y bit for bit; cu_seqlens, gather_idx, inv_pos and total are NOT produced."""
 
     def __init__(self, B: int, N: int, C: int, H: int, dtype: str, tau: float = 0.5, bias: float = 0.0,
                  container_len: int = 0, fused_unpack: bool = True, keep_packed_out: bool = True,
-                 gathered: bool = False, fused_index: bool = False):
+                 gathered: bool = False, fused_index: bool = False, from_mask: bool = False):
         """keep_packed_out=False (fused form only): the packed attention output and the
         log-sum-exp rows, which only a backward pass reads, are not written; y is the result.
         fused_index=True (with gathered): the gate launch builds the packing index itself
@@ -41,7 +44,9 @@ class ForwardPass:
             raise ValueError("gathered=True needs the fused form and no container padding")
         if fused_index and not gathered:
             raise ValueError("fused_index=True needs gathered=True")
-        self.gathered, self.fused_index = gathered, fused_index
+        if from_mask and not (gathered and not fused_index and not keep_packed_out and N <= 256 and dtype == "bf16"):
+            raise ValueError("from_mask=True needs gathered=True, keep_packed_out=False, N <= 256 and bf16")
+        self.gathered, self.fused_index, self.from_mask = gathered, fused_index, from_mask
         self.ws_index = torch.zeros(17 * 1088, dtype=torch.int32, device="cuda") if fused_index else None
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
         self.tau, self.bias, self.container_len = tau, bias, container_len
@@ -64,6 +69,14 @@ class ForwardPass:
         """The pass as named, prepared launches (bound to the stream that is current now), so a
         caller can time each of them or replay them with no marshalling cost."""
         C, p = self.C, self.packed_qkv
+        if self.from_mask:
+            t = qkv.view(self.B * self.N, 3 * C)
+            return [
+                ("gate_select", spa.spa_gate_select(x, w, self.bias, s_up, self.tau, self.scores, self.mask, None,
+                                                    prepare=True)),
+                ("selected_attention_unpack", spa.spa_selected_attention_unpack(
+                    t[:, :C], t[:, C:2 * C], t[:, 2 * C:], self.mask, base, self.H, self.Dh, self.y, prepare=True)),
+            ]
         if self.gathered:
             t = qkv.view(self.B * self.N, 3 * C)
             head = [

@@ -28,6 +28,7 @@ PRE = "cd /tmp && export TMPDIR=/tmp && "
 # call of the chain <- substring of the kernel name (first match wins); a call may launch two kernels
 CHAINS = {
     "forward_fused": [("gate_select_kernel", "gate_select_index"), ("attn_fwd", "gathered_attention_unpack")],
+    "forward_selected": [("gate_select_kernel", "gate_select"), ("attn_fwd", "selected_attention_unpack")],
     "forward_gathered": [("gate_select_kernel", "gate_select"), ("pack_kernel", "pack_indices"),
                          ("attn_fwd", "gathered_attention_unpack")],
     "forward_packed": [("gate_select_kernel", "gate_select"), ("pack_kernel", "pack"),

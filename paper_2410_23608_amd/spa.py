@@ -52,6 +52,8 @@ _SIGNATURES = {
                                             c_int, c_int, c_float, _P, _P, _P, _P]),
     "spa_gathered_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, _P, _P, c_int, c_int, c_int,
                                               c_int, c_int, c_float, _P, _P, _P, _P]),
+    "spa_selected_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, _P, c_int, c_int, c_int, c_int,
+                                              c_int, c_float, _P, _P]),
     "spa_segment_attention_unpack": (c_int, [_P, _P, _P, c_int64, c_int64, c_int64, _P, c_int, c_int, _P, _P, _P, c_int64,
                                              c_int, c_int, c_int, c_float, _P, _P, _P, _P]),
     "spa_ceiling_copy": (c_int, [_P, _P, c_size_t, _P]),
@@ -430,6 +432,25 @@ def spa_gathered_attention_unpack(q, k, v, cu_seqlens, gather_idx, inv_pos, base
                      (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(cu_seqlens),
                       _ptr(gather_idx), _ptr(inv_pos), _ptr(base), B, N, H, Dh, code, float(softmax_scale),
                       _ptr(out), _ptr(lse), _ptr(y), _stream(),), _keep, prepare)
+
+
+def spa_selected_attention_unpack(q, k, v, mask, base, H, Dh, y, softmax_scale=0.0, prepare=False):
+    """Attention over the selected tokens of every image straight from the mask (no packing index), scatter
+    and bypass included: q, k, v [B*N, H*Dh] tensors or column-slice views at token positions, mask [B,N]
+    uint8, y [B,N,C].  N <= 256, bf16."""
+    fn = "spa_selected_attention_unpack"
+    B, N, C = y.shape
+    if C != H * Dh:
+        raise ValueError(f"{fn}: y must be [B, N, H*Dh]")
+    code = _features(fn, q=q, k=k, v=v, base=base, y=y)
+    _typed(fn, torch.uint8, mask=mask)
+    _rows(fn, C, q=(q, B * N), k=(k, B * N), v=(v, B * N))
+    _holds(fn, mask=(mask, B * N), base=(base, B * N * C))
+    _keep = (q, k, v, mask, base, y,)
+    _contig(mask, base, y)
+    return _dispatch(lib.spa_selected_attention_unpack,
+                     (_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v), _ptr(mask), _ptr(base),
+                      B, N, H, Dh, code, float(softmax_scale), _ptr(y), _stream(),), _keep, prepare)
 
 
 def spa_segment_attention_unpack(q, k, v, seg_cu_seqlens, max_seqlen, gather_idx, inv_pos, base, H, Dh, y, out=None,
