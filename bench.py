@@ -458,7 +458,7 @@ def measure_hierarchy(args, torch, workloads, HierarchyPass, HierarchyTrainPass,
     hcfg = [(b_["workload"].B, *b_["workload"].grid, b_["workload"].C, b_["workload"].H, b_["workload"].dtype,
              b_["workload"].tau, b_["bias"]) for b_ in hb]
     hx, hw, hq = [up(b_["x"]) for b_ in hb], [up(b_["w"]) for b_ in hb], [up(b_["qkv"]) for b_ in hb]
-    hp = HierarchyPass(hcfg)
+    hp = HierarchyPass(hcfg, lean=True)
     hstages = hp.stages(hx, hw, hq)
 
     def hstep():
@@ -468,7 +468,7 @@ def measure_hierarchy(args, torch, workloads, HierarchyPass, HierarchyTrainPass,
     for _ in range(5):
         hstep()
     torch.cuda.synchronize()
-    hT = [int(p_.total.item()) for p_ in hp.passes]
+    hT = [int(p_.mask.sum().item()) for p_ in hp.passes]
     fmed, fmin = timed_regions(hstep, args.steps, args.repeats, torch)
     res = {"workload": "hierarchy: B=16, stages of 56^2/28^2/14^2/7^2 tokens, C=96/192/384/768, heads 3/6/12/24 of 32, "
                        "bf16, every stage's gate takes the finer stage's score map (max-pooled in the gate kernel)",

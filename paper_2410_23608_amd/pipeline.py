@@ -523,19 +523,28 @@ class HierarchyPass:
     """A multi-stage hierarchy (Section 3.1, Section 3.2 on multi-scale scores): every stage
     runs gate -> pack -> attention + scatter, and from the second stage on the gate takes the
     previous (2x finer) stage's score map, max-pooled inside the gate kernel, as s_up.
-    Three launches per stage, no host sync anywhere in the chain.  (Everything on one stream:
+    Three launches per stage (lean form: two for the coarse stages), no host sync anywhere in the chain.  (Everything on one stream:
     spreading the stages over two or four streams was measured and is slower for the forward
     chain, 129 and 166 us against 102 us; the events and the fork / join per chain cost more
     than the overlap of the small coarse stages brings.)"""
 
-    def __init__(self, stages):
+    def __init__(self, stages, lean: bool = False):
         """stages: one (B, grid_h, grid_w, C, H, dtype, tau, bias) tuple per stage, finest
-        first; consecutive grids halve."""
+        first; consecutive grids halve.
+        lean=True (forward only; y is the same bit for bit): no stage copies rows or keeps the packed
+        output and lse; stages of at most 256 tokens per image take their packing order from the mask
+        (two launches, no index arrays), the others fetch gathered rows through the index."""
         self.cfg = list(stages)
         for (a, b) in zip(self.cfg[:-1], self.cfg[1:]):
             if a[1] != 2 * b[1] or a[2] != 2 * b[2] or a[0] != b[0]:
                 raise ValueError("consecutive stages must share B and halve the grid")
-        self.passes = [ForwardPass(B, gh * gw, C, H, dtype, tau, bias) for (B, gh, gw, C, H, dtype, tau, bias) in self.cfg]
+        if lean:
+            self.passes = [ForwardPass(B, gh * gw, C, H, dtype, tau, bias, keep_packed_out=False, gathered=True,
+                                       from_mask=gh * gw <= 256 and dtype == "bf16")
+                           for (B, gh, gw, C, H, dtype, tau, bias) in self.cfg]
+        else:
+            self.passes = [ForwardPass(B, gh * gw, C, H, dtype, tau, bias)
+                           for (B, gh, gw, C, H, dtype, tau, bias) in self.cfg]
         self.s_up = [None] + [torch.empty(c[0], c[1] * c[2], dtype=torch.float32, device="cuda") for c in self.cfg[1:]]
 
     def stages(self, xs, ws, qkvs, bases=None) -> List[Tuple[str, Callable[[], None]]]:
