@@ -96,6 +96,11 @@ def grid_of(r) -> int:
 
 
 def call_of(name: str, chain: str):
+    if chain == "hierarchy":       # the run also holds the forward-only chain, whose stages use other attention forms
+        if "attn_fwd_bf16_wave_mask" in name:
+            return "selected_attention_unpack"
+        if re.search(r"attn_fwd_bf16_\w+_kernel(<[^>]*true>|I\w*Lb1EEE)", name):
+            return "gathered_attention_unpack"
     for sub, call in CHAINS[chain]:
         if sub in name:
             return call
@@ -117,7 +122,7 @@ def stage_labels(groups, chain):
         key = lambda g: (-g[2], g[0] if family == "gate_bwd_kernel" else "")
         ranks = sorted({key(g) for g in gs})
         # kernels of the long-segment forms serve the two finest stages, the short forms the two coarsest
-        first = 3 if (("wave" in family or "fused" in family) and len(ranks) <= 2) else 1
+        first = 3 if (("wave" in family or "fused" in family) and len(ranks) <= 2) else 1     # (wave: lpt64 and mask kernels)
         for g in gs:
             labels[g] = f"s{first + ranks.index(key(g))}.{g[1]}"
     return labels
