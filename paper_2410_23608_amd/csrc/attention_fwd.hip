@@ -1425,6 +1425,7 @@ extern "C" int spa_selected_attention_unpack(const void* q, const void* k, const
   SPA_REQUIRE(N <= 256, SPA_ERR_UNSUPPORTED, "%s: N = %d > 256 tokens per image (use index-only spa_pack + spa_gathered_attention_unpack)", fn, N);
   SPA_REQUIRE(Dh == 32 || Dh == 64, SPA_ERR_UNSUPPORTED, "%s: head dim %d not supported (32 or 64)", fn, Dh);
   SPA_REQUIRE(B <= 65535 && H <= 65535 && (long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B, H <= 65535 and B*N < 2^31", fn);
+  SPA_REQUIRE(((long)H * B + 8) * ((N + 31) / 32) < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B*H*ceil(N/32) must be < 2^31", fn);
   const int64_t strides[3] = {q_row_stride, k_row_stride, v_row_stride};
   for (int64_t rs : strides) {
     SPA_REQUIRE(rs >= (int64_t)H * Dh && rs < (1 << 24), SPA_ERR_INVALID_ARG, "%s: row stride %ld outside [H*Dh, 2^24)", fn, (long)rs);

@@ -87,6 +87,12 @@ int main() {
   refused(spa_packed_attention(p, p, p, 64, 64, (int64_t)1 << 40, i32, 2, 196, 2, 32, SPA_BF16, 0.f, p, nullptr, nullptr),
           "spa_packed_attention");
   refused(spa_packed_attention(p, p, p, 64, 64, 64, i32, 2, 196, 2, 32, SPA_BF16, -1.f, p, nullptr, nullptr), "spa_packed_attention");
+  refused(spa_selected_attention_unpack(p, p, p, 64, 64, 64, u8, nullptr, 2, 300, 2, 32, SPA_BF16, 0.f, p, nullptr),
+          "spa_selected_attention_unpack");
+  refused(spa_selected_attention_unpack(p, p, p, 64, 64, 64, u8, nullptr, 2, 196, 2, 32, SPA_F32, 0.f, p, nullptr),
+          "spa_selected_attention_unpack");
+  refused(spa_selected_attention_unpack(p, p, p, 64, 64, 64, nullptr, nullptr, 2, 196, 2, 32, SPA_BF16, 0.f, p, nullptr),
+          "spa_selected_attention_unpack");
   refused(spa_unpack(nullptr, i32, nullptr, 2, 196, 64, SPA_F32, p, nullptr), "spa_unpack");
   refused(spa_maxpool2x2(f, 2, 7, 7, f, nullptr), "spa_maxpool2x2");
   refused(spa_packed_attention_bwd(p, p, p, 64, 64, 64, p, p, f, i32, 2, 300, 2, 32, SPA_BF16, 0.f, p, p, p, 64, 64, 64, nullptr, 0,
