@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--form", default="auto", choices=["auto", "selected", "fused", "gathered", "packed"],
                     help="forward step.  gathered: gate, index-only pack, attention on gathered rows (3 launches); "
                          "selected: gate, attention that takes the packing order from the mask itself (2 launches; "
-                         "images of at most 256 tokens, bf16); auto (default): selected where it applies, else gathered; "
+                         "images of at most 256 tokens); auto (default): selected where it applies, else gathered; "
                          "fused: gate + packing index in one launch, attention on gathered rows (2 launches); packed: "
                          "gate, pack of the rows, attention on the packed rows (3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -251,8 +251,8 @@ def forward_work(wl, T, sum_n2, keep_out=False):
 
 
 def forward_form(requested, wl):
-    """The form a forward workload is timed in: `selected` needs images of at most 256 tokens and bf16."""
-    fits = wl.N <= 256 and wl.dtype == "bf16"
+    """The form a forward workload is timed in: `selected` needs images of at most 256 tokens."""
+    fits = wl.N <= 256
     if requested == "auto":
         return "selected" if fits else "gathered"
     if requested == "selected" and not fits:

@@ -306,15 +306,15 @@ int spa_gathered_attention_unpack(const void* q, const void* k, const void* v, i
                                   void* stream);
 
 /*
- * Selection, packing order and attention in ONE call, for images of at most 256 tokens (Section 3.2:
+ * Packing order, attention and scatter in ONE call, for images of at most 256 tokens (Section 3.2:
  * the positive tokens, in token order, attend to each other inside their image; the negative tokens
  * go on directly): spa_gathered_attention_unpack without a packing index.  Every wave derives its
  * image's part of gather_idx from the mask bytes themselves (survivors in token order, exactly what
  * spa_pack writes), so no packing launch precedes the call: gate + this call = a forward step in two
  * launches.  y is bit for bit what spa_pack (index only) + spa_gathered_attention_unpack give.
  * in:  q, k, v at TOKEN positions (row i = flat token i; strides in elements, as spa_packed_attention);
- *      mask [B,N] uint8 as spa_gate_select writes it; base [B,N,C] or NULL; N <= 256; bf16 only
- *      (other sizes / fp32: SPA_ERR_UNSUPPORTED, use the index-only spa_pack + spa_gathered_attention_unpack).
+ *      mask [B,N] uint8 as spa_gate_select writes it; base [B,N,C] or NULL; N <= 256 (larger images:
+ *      SPA_ERR_UNSUPPORTED, use the index-only spa_pack + spa_gathered_attention_unpack).
  * out: y [B,N,C] as spa_packed_attention_unpack.  No packed output, no lse (forward only).
  */
 int spa_selected_attention_unpack(const void* q, const void* k, const void* v, int64_t q_row_stride,

@@ -1141,8 +1141,34 @@ attn_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
   __shared__ __attribute__((aligned(16))) float Vs[BN * DH];
 
   const int h = blockIdx.y;
-  const Segment seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
   const long C = (long)H * DH;
+  // cu == key_lens == nullptr: no packing index exists; the first wave derives the image's packing
+  // order from its n_pad <= 256 mask bytes (see attn_fwd_bf16_wave_mask_kernel) and the workgroup
+  // works on that list as on gathered rows
+  __shared__ int32_t list[256];
+  __shared__ int s_n;
+  const bool from_mask = cu == nullptr && key_lens == nullptr;
+  Segment seg;
+  if (from_mask) {
+    if (threadIdx.x < kWave) {
+      const long tok0 = (long)blockIdx.z * n_pad;
+      int n = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = (int)threadIdx.x + 64 * i;
+        const bool sel = t < n_pad && sc.mask[tok0 + t] != 0;
+        const uint64_t bal = __ballot(sel);
+        if (sel) list[n + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u))] = (int32_t)(tok0 + t);
+        n += __popcll(bal);
+      }
+      if (threadIdx.x == 0) s_n = n;
+    }
+    __syncthreads();
+    seg = {0, s_n, s_n};
+    sc.gather_idx = list;
+  } else {
+    seg = segment_of(blockIdx.z, cu, key_lens, n_pad);
+  }
   if (sc.y != nullptr) {
     const FillRange fr = fill_range(sc, blockIdx.z, gridDim.z, blockIdx.x, gridDim.x);
     scatter_fill<float, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, THREADS);
@@ -1421,7 +1447,6 @@ extern "C" int spa_selected_attention_unpack(const void* q, const void* k, const
   SPA_REQUIRE(q && k && v && mask && y, SPA_ERR_INVALID_ARG, "%s: null pointer", fn);
   SPA_REQUIRE(B >= 1 && N >= 1 && H >= 1, SPA_ERR_INVALID_ARG, "%s: B, N, H must be >= 1", fn);
   SPA_REQUIRE(dtype == SPA_F32 || dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, dtype);
-  SPA_REQUIRE(dtype == SPA_BF16, SPA_ERR_UNSUPPORTED, "%s: bf16 only (fp32: index-only spa_pack + spa_gathered_attention_unpack)", fn);
   SPA_REQUIRE(N <= 256, SPA_ERR_UNSUPPORTED, "%s: N = %d > 256 tokens per image (use index-only spa_pack + spa_gathered_attention_unpack)", fn, N);
   SPA_REQUIRE(Dh == 32 || Dh == 64, SPA_ERR_UNSUPPORTED, "%s: head dim %d not supported (32 or 64)", fn, Dh);
   SPA_REQUIRE(B <= 65535 && H <= 65535 && (long)B * N < 2147483647L, SPA_ERR_INVALID_ARG, "%s: B, H <= 65535 and B*N < 2^31", fn);
@@ -1429,7 +1454,7 @@ extern "C" int spa_selected_attention_unpack(const void* q, const void* k, const
   const int64_t strides[3] = {q_row_stride, k_row_stride, v_row_stride};
   for (int64_t rs : strides) {
     SPA_REQUIRE(rs >= (int64_t)H * Dh && rs < (1 << 24), SPA_ERR_INVALID_ARG, "%s: row stride %ld outside [H*Dh, 2^24)", fn, (long)rs);
-    SPA_REQUIRE((rs * 2) % 16 == 0, SPA_ERR_INVALID_ARG, "%s: row stride is not a multiple of 16 bytes", fn);
+    SPA_REQUIRE((rs * elem_size(dtype)) % 16 == 0, SPA_ERR_INVALID_ARG, "%s: row stride is not a multiple of 16 bytes", fn);
   }
   SPA_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(y) && aligned16(base), SPA_ERR_INVALID_ARG,
               "%s: q / k / v / y / base not 16-byte aligned", fn);
@@ -1438,6 +1463,18 @@ extern "C" int spa_selected_attention_unpack(const void* q, const void* k, const
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)Dh);
   const float scale_log2 = scale * 1.4426950408889634f;
   const Scatter sc = {nullptr, nullptr, base, y, N, 0, 1, mask};
+  if (dtype == SPA_F32) {
+    const dim3 grid((N + 15) / 16, H, B), block(128);   // 16 queries per workgroup, 8 lanes each
+    if (Dh == 32)
+      hipLaunchKernelGGL((attn_fwd_f32_kernel<32>), grid, block, 0, as_stream(stream), (const float*)q, (const float*)k,
+                         (const float*)v, (long)q_row_stride, (long)k_row_stride, (long)v_row_stride, nullptr, nullptr, N,
+                         H, scale, (float*)nullptr, (float*)nullptr, 0L, sc);
+    else
+      hipLaunchKernelGGL((attn_fwd_f32_kernel<64>), grid, block, 0, as_stream(stream), (const float*)q, (const float*)k,
+                         (const float*)v, (long)q_row_stride, (long)k_row_stride, (long)v_row_stride, nullptr, nullptr, N,
+                         H, scale, (float*)nullptr, (float*)nullptr, 0L, sc);
+    return check_launch(fn);
+  }
   const int nqb = (N + 31) / 32;
   const dim3 grid(xcd_grid(nqb, H, B));
 #define SPA_SEL(D)                                                                                              \

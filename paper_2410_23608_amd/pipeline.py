@@ -29,7 +29,7 @@ class ForwardPass:
     gathered=True (fused form only): packing builds the index only and the attention kernel
     fetches the q | k | v rows through gather_idx from where they lie, so no row is copied
     (spa_pack with x = NULL, then spa_gathered_attention_unpack); same results, bit for bit.
-    from_mask=True (with gathered; N <= 256, bf16, forward only): no packing launch at all, the attention
+    from_mask=True (with gathered; N <= 256, forward only): no packing launch at all, the attention
     kernel derives each image's packing order from the mask (spa_selected_attention_unpack): two launches
     per step, same y bit for bit; cu_seqlens, gather_idx, inv_pos and total are NOT produced."""
 
@@ -44,8 +44,8 @@ class ForwardPass:
             raise ValueError("gathered=True needs the fused form and no container padding")
         if fused_index and not gathered:
             raise ValueError("fused_index=True needs gathered=True")
-        if from_mask and not (gathered and not fused_index and not keep_packed_out and N <= 256 and dtype == "bf16"):
-            raise ValueError("from_mask=True needs gathered=True, keep_packed_out=False, N <= 256 and bf16")
+        if from_mask and not (gathered and not fused_index and not keep_packed_out and N <= 256):
+            raise ValueError("from_mask=True needs gathered=True, keep_packed_out=False and N <= 256")
         self.gathered, self.fused_index, self.from_mask = gathered, fused_index, from_mask
         self.ws_index = torch.zeros(17 * 1088, dtype=torch.int32, device="cuda") if fused_index else None
         self.B, self.N, self.C, self.H, self.Dh = B, N, C, H, C // H
@@ -540,7 +540,7 @@ class HierarchyPass:
                 raise ValueError("consecutive stages must share B and halve the grid")
         if lean:
             self.passes = [ForwardPass(B, gh * gw, C, H, dtype, tau, bias, keep_packed_out=False, gathered=True,
-                                       from_mask=gh * gw <= 256 and dtype == "bf16")
+                                       from_mask=gh * gw <= 256)
                            for (B, gh, gw, C, H, dtype, tau, bias) in self.cfg]
         else:
             self.passes = [ForwardPass(B, gh * gw, C, H, dtype, tau, bias)

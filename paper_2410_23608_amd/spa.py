@@ -437,7 +437,7 @@ def spa_gathered_attention_unpack(q, k, v, cu_seqlens, gather_idx, inv_pos, base
 def spa_selected_attention_unpack(q, k, v, mask, base, H, Dh, y, softmax_scale=0.0, prepare=False):
     """Attention over the selected tokens of every image straight from the mask (no packing index), scatter
     and bypass included: q, k, v [B*N, H*Dh] tensors or column-slice views at token positions, mask [B,N]
-    uint8, y [B,N,C].  N <= 256, bf16."""
+    uint8, y [B,N,C].  N <= 256."""
     fn = "spa_selected_attention_unpack"
     B, N, C = y.shape
     if C != H * Dh:

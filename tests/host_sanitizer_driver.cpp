@@ -89,7 +89,7 @@ int main() {
   refused(spa_packed_attention(p, p, p, 64, 64, 64, i32, 2, 196, 2, 32, SPA_BF16, -1.f, p, nullptr, nullptr), "spa_packed_attention");
   refused(spa_selected_attention_unpack(p, p, p, 64, 64, 64, u8, nullptr, 2, 300, 2, 32, SPA_BF16, 0.f, p, nullptr),
           "spa_selected_attention_unpack");
-  refused(spa_selected_attention_unpack(p, p, p, 64, 64, 64, u8, nullptr, 2, 196, 2, 32, SPA_F32, 0.f, p, nullptr),
+  refused(spa_selected_attention_unpack(p, p, p, 96, 96, 96, u8, nullptr, 2, 196, 2, 48, SPA_F32, 0.f, p, nullptr),
           "spa_selected_attention_unpack");
   refused(spa_selected_attention_unpack(p, p, p, 64, 64, 64, nullptr, nullptr, 2, 196, 2, 32, SPA_BF16, 0.f, p, nullptr),
           "spa_selected_attention_unpack");

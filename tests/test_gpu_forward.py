@@ -490,29 +490,31 @@ def test_pack_pair_equals_two_packs(spa, dtype, B, N, C, C2, dens, use_counts):
     assert torch.isnan(qa[T:]).all() and torch.isnan(qb[T:]).all()       # rows past the total untouched
 
 
-@pytest.mark.parametrize("Dh,N,B", [(64, 196, 5), (32, 49, 9), (32, 256, 3), (64, 100, 70), (32, 7, 4)])
+@pytest.mark.parametrize("dtype,Dh,N,B", [("bf16", 64, 196, 5), ("bf16", 32, 49, 9), ("bf16", 32, 256, 3), ("bf16", 64, 100, 70),
+                                          ("bf16", 32, 7, 4), ("f32", 32, 196, 3), ("f32", 64, 77, 4), ("f32", 32, 256, 3)])
 @pytest.mark.parametrize("with_base", [False, True])
-def test_selected_attention_from_the_mask_equals_the_indexed_form(spa, Dh, N, B, with_base):
+def test_selected_attention_from_the_mask_equals_the_indexed_form(spa, dtype, Dh, N, B, with_base):
     """spa_selected_attention_unpack (no packing launch: every wave derives its image's packing order from
     the mask bytes) == index-only spa_pack + spa_gathered_attention_unpack, bit for bit, and both equal the
     oracle; images with nothing and with everything selected included."""
     H = 2
     C = H * Dh
     rng = np.random.default_rng(500 + N + B)
-    qkv = wlmod.round_bf16(rng.standard_normal((B, N, 3 * C)).astype(np.float32))
-    base = wlmod.round_bf16(rng.standard_normal((B, N, C)).astype(np.float32)) if with_base else None
+    mk = wlmod.round_bf16 if dtype == "bf16" else (lambda a: a)
+    qkv = mk(rng.standard_normal((B, N, 3 * C)).astype(np.float32))
+    base = mk(rng.standard_normal((B, N, C)).astype(np.float32)) if with_base else None
     mask = (rng.uniform(size=(B, N)) < rng.uniform(0.05, 0.95, size=(B, 1))).astype(np.uint8)
     mask[1] = 0
     mask[2] = 1
     cap = B * N
-    qkv_d, mask_d = dev(qkv, "bf16"), dev(mask)
-    base_d = None if base is None else dev(base, "bf16")
+    qkv_d, mask_d = dev(qkv, dtype), dev(mask)
+    base_d = None if base is None else dev(base, dtype)
     flat = qkv_d.view(cap, 3 * C)
     ints = lambda n: torch.full((n,), -9, dtype=torch.int32, device="cuda")
     cu, gidx, inv, tot = ints(B + 1), ints(cap), ints(cap), ints(1)
     spa.spa_pack(None, mask_d, None, None, 0, None, cu, gidx, inv, tot)
-    y1 = torch.full((B, N, C), float("nan"), dtype=torch.bfloat16, device="cuda")
-    y2 = torch.full((B, N, C), float("nan"), dtype=torch.bfloat16, device="cuda")
+    y1 = torch.full((B, N, C), float("nan"), dtype=tdtype(dtype), device="cuda")
+    y2 = torch.full((B, N, C), float("nan"), dtype=tdtype(dtype), device="cuda")
     spa.spa_gathered_attention_unpack(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], cu, gidx, inv, base_d, H, Dh, y1)
     spa.spa_selected_attention_unpack(flat[:, :C], flat[:, C:2 * C], flat[:, 2 * C:], mask_d, base_d, H, Dh, y2)
     torch.cuda.synchronize()
@@ -520,7 +522,7 @@ def test_selected_attention_from_the_mask_equals_the_indexed_form(spa, Dh, N, B,
     ref_out, _ = orc.attention_per_image(qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], mask, H)
     _, _, inv_r, _ = orc.pack_indices(mask)
     ref_y = orc.unpack(ref_out, inv_r, B, N, base)
-    assert np.max(np.abs(host(y2) - ref_y)) <= (2 * TOL["bf16"] if with_base else TOL["bf16"])
+    assert np.max(np.abs(host(y2) - ref_y)) <= (2 * TOL[dtype] if with_base and dtype == "bf16" else TOL[dtype])
 
 
 def test_selected_attention_refuses_what_it_does_not_cover(spa):
@@ -531,8 +533,3 @@ def test_selected_attention_refuses_what_it_does_not_cover(spa):
     y = torch.empty(B, N, C, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(spa.SpaError):                      # more than 256 tokens per image
         spa.spa_selected_attention_unpack(qkv[:, :C], qkv[:, C:2 * C], qkv[:, 2 * C:], mask, None, H, Dh, y)
-    qf = torch.zeros(2 * 64, 3 * C, dtype=torch.float32, device="cuda")
-    yf = torch.empty(2, 64, C, dtype=torch.float32, device="cuda")
-    with pytest.raises(spa.SpaError):                      # fp32
-        spa.spa_selected_attention_unpack(qf[:, :C], qf[:, C:2 * C], qf[:, 2 * C:], mask[:, :64].contiguous(), None, H,
-                                          Dh, yf)
