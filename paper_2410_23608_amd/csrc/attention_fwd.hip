@@ -309,6 +309,27 @@ struct KvStage {
   __device__ __forceinline__ void load(const __bf16* kh, const __bf16* vh, long ks, long vs) {
     const int c = threadIdx.x % CPR, lrow = 2 * (threadIdx.x / CPR);
     const uint32_t koff = (uint32_t)lrow * (uint32_t)ks + c * 8, voff = (uint32_t)lrow * (uint32_t)vs + c * 8;
+    // a tile that lies wholly inside the segment (all but the last one): no predicates, no zero fill
+    if (TASKS % THREADS == 0 && kt_ + 2 * TASKS / CPR <= nk_) {
+#pragma unroll
+      for (int t = 0; t < TPT; ++t) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const __bf16 *kp, *vp;
+          if (GATHER) {
+            kp = kh + row_offset(tok_rows[t][u], ks) + c * 8;
+            vp = vh + row_offset(tok_rows[t][u], vs) + c * 8;
+          } else {
+            const long r = row0_ + kt_ + t * RPP + u;     // uniform
+            kp = kh + r * ks + koff;
+            vp = vh + r * vs + voff;
+          }
+          kreg[t][u] = *reinterpret_cast<const bf16x8*>(kp);
+          vreg[t][u] = *reinterpret_cast<const bf16x8*>(vp);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int t = 0; t < TPT; ++t) {
 #pragma unroll
