@@ -154,7 +154,9 @@ __device__ __forceinline__ void fwd_scores(const __bf16* kbuf, int key0, int rem
 }
 
 // One online-softmax update (max, rescale, exp, sum) over a group of GSB*32 keys, then
-// O^T += V^T P^T for the group.  V^T at vbuf (row stride TS), the group's keys at column vcol.
+// O^T += V^T P^T for the group.  V^T at vbuf (row stride TS), the group's keys at column vcol; TS == 0:
+// V rows as they lie in memory (row stride DH + 8, the group's keys from row vcol), the V^T fragments
+// then come from the transposing LDS read.
 template <int DH, int TS, int GSB, bool FULL>
 __device__ __forceinline__ void fwd_softmax_pv(const floatx16 (&s)[GSB], const __bf16* vbuf, int vcol, int key0,
                                                int rem, FwdAcc<DH>& acc, float scale_log2, int l32, int hh) {
@@ -193,7 +195,8 @@ __device__ __forceinline__ void fwd_softmax_pv(const floatx16 (&s)[GSB], const _
         const bf16x8 pb = float_to_bf16x8(pf);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          const bf16x8 a = transposed_frag<TS>(vbuf, d * 32 + l32, vcol + sb * 32, mf, hh);
+          const bf16x8 a = TS == 0 ? transposed_frag_rowmajor<DH + 8>(vbuf, d, vcol + sb * 32, mf, l32 + 32 * hh)
+                                   : transposed_frag<TS == 0 ? 1 : TS>(vbuf, d * 32 + l32, vcol + sb * 32, mf, hh);
           acc.o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, acc.o[d], 0, 0, 0);
         }
       }
@@ -298,11 +301,18 @@ struct KvStage {
     kt_ = kt;
     nk_ = nk;
     if (GATHER) {
+      if (TASKS % THREADS == 0 && kt + 2 * TASKS / CPR <= nk) {      // a whole tile: no predicates
 #pragma unroll
-      for (int t = 0; t < TPT; ++t)
+        for (int t = 0; t < TPT; ++t)
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-          if (valid(t, u)) tok_rows[t][u] = gi[kt + 2 * ((threadIdx.x + t * THREADS) / CPR) + u];
+          for (int u = 0; u < 2; ++u) tok_rows[t][u] = gi[kt + 2 * ((threadIdx.x + t * THREADS) / CPR) + u];
+      } else {
+#pragma unroll
+        for (int t = 0; t < TPT; ++t)
+#pragma unroll
+          for (int u = 0; u < 2; ++u)
+            if (valid(t, u)) tok_rows[t][u] = gi[kt + 2 * ((threadIdx.x + t * THREADS) / CPR) + u];
+      }
     }
   }
   // The row loads; rows past the segment read as zero
@@ -381,17 +391,106 @@ __device__ __forceinline__ void load_q_frags(const __bf16* qrow, bool q_ok, int 
   }
 }
 
+// Register staging of BN key and value rows on their way to LDS (both row-major): chunk i =
+// 16-byte piece i % CPR of row i / CPR; index() runs one tile ahead of load() (see KvStage).
+template <int DH, int THREADS, int BN, bool GATHER>
+struct KvRowStage {
+  static constexpr int CPR = DH / 8, CHUNKS = BN * CPR, CPT = (CHUNKS + THREADS - 1) / THREADS;
+  static constexpr int RPP = THREADS / CPR;
+  static_assert(THREADS % CPR == 0, "a thread keeps its chunk column over the passes");
+  bf16x8 kreg[CPT], vreg[CPT];
+  int tok_rows[CPT];                   // gathered rows only: see KvStage
+  long row0_;
+  int kt_, nk_;
+  __device__ __forceinline__ bool valid(int t) const {
+    const int i = threadIdx.x + t * THREADS;
+    return i < CHUNKS && kt_ + i / CPR < nk_;
+  }
+  __device__ __forceinline__ void index(const int32_t* gi, long row0, int kt, int nk) {
+    row0_ = row0;
+    kt_ = kt;
+    nk_ = nk;
+    if (GATHER) {
+      if (CHUNKS % THREADS == 0 && kt + BN <= nk) {                  // a whole tile: no predicates
+#pragma unroll
+        for (int t = 0; t < CPT; ++t) tok_rows[t] = gi[kt + (threadIdx.x + t * THREADS) / CPR];
+      } else {
+#pragma unroll
+        for (int t = 0; t < CPT; ++t)
+          if (valid(t)) tok_rows[t] = gi[kt + (threadIdx.x + t * THREADS) / CPR];
+      }
+    }
+  }
+  __device__ __forceinline__ void load(const __bf16* kh, const __bf16* vh, long ks, long vs) {
+    const int c = threadIdx.x % CPR, lrow = threadIdx.x / CPR;
+    const uint32_t koff = (uint32_t)lrow * (uint32_t)ks + c * 8, voff = (uint32_t)lrow * (uint32_t)vs + c * 8;
+    // a tile that lies wholly inside the segment (all but the last one): no predicates, no zero fill
+    if (CHUNKS % THREADS == 0 && kt_ + BN <= nk_) {
+#pragma unroll
+      for (int t = 0; t < CPT; ++t) {
+        const __bf16 *kp, *vp;
+        if (GATHER) {
+          kp = kh + row_offset(tok_rows[t], ks) + c * 8;
+          vp = vh + row_offset(tok_rows[t], vs) + c * 8;
+        } else {
+          const long r = row0_ + kt_ + t * RPP;           // uniform
+          kp = kh + r * ks + koff;
+          vp = vh + r * vs + voff;
+        }
+        kreg[t] = *reinterpret_cast<const bf16x8*>(kp);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(vp);
+      }
+      return;
+    }
+#pragma unroll
+    for (int t = 0; t < CPT; ++t) {
+      kreg[t] = zero_bf16x8();
+      vreg[t] = zero_bf16x8();
+      if (valid(t)) {
+        const __bf16 *kp, *vp;
+        if (GATHER) {
+          kp = kh + row_offset(tok_rows[t], ks) + c * 8;
+          vp = vh + row_offset(tok_rows[t], vs) + c * 8;
+        } else {
+          const long r = row0_ + kt_ + t * RPP;           // uniform
+          kp = kh + r * ks + koff;
+          vp = vh + r * vs + voff;
+        }
+        kreg[t] = *reinterpret_cast<const bf16x8*>(kp);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(vp);
+      }
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* kbuf, __bf16* vbuf) const {
+#pragma unroll
+    for (int t = 0; t < CPT; ++t) {
+      const int i = threadIdx.x + t * THREADS, r = i / CPR, c = i % CPR;
+      if (i < CHUNKS) {
+        *reinterpret_cast<bf16x8*>(&kbuf[r * (DH + 8) + c * 8]) = kreg[t];
+        *reinterpret_cast<bf16x8*>(&vbuf[r * (DH + 8) + c * 8]) = vreg[t];
+      }
+    }
+  }
+};
+
 // Long segments.  Workgroup = NW waves x 32 queries; the keys of the segment stream through
 // LDS in tiles of BN keys, double-buffered: while a tile is consumed the next one is already
 // in flight from global memory into registers, and is written to the other LDS buffer
 // before the single barrier that ends the iteration.
 // Head dim 32 is compiled for three waves per SIMD (168 registers, no spills): with several
 // batches in flight the third wave fills the softmax stalls of the other two.
+// V in LDS: at head dim 64 as the rows lie in memory (staging is plain 16-byte copies, the V^T fragments
+// come from the transposing LDS read: uniform long segments 521 against 481 TFLOP/s), at head dim 32
+// transposed while staging (the detection batch 42.2 against 43.1 us for the launch; the same rate on
+// uniform segments).
+template <int DH>
+constexpr bool kTiledVRows = DH == 64;
 template <int DH, int BN>
 struct TiledLds {
   static constexpr int RS = DH + 8, TS = transposed_stride(BN);
+  static constexpr int VSIZE = kTiledVRows<DH> ? BN * RS : DH * TS;
   __attribute__((aligned(16))) __bf16 Ks[2][BN * RS];
-  __attribute__((aligned(16))) __bf16 Vt[2][DH * TS];
+  __attribute__((aligned(16))) __bf16 Vs[2][VSIZE];
 };
 
 // The workgroup's work on queries [q0, q0 + 32 NW) of head h of segment seg (q0 < seg.nq).
@@ -401,9 +500,11 @@ tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const _
                 const __bf16* __restrict__ k, const __bf16* __restrict__ v, long qs, long ks, long vs, int H,
                 float scale_log2, __bf16* __restrict__ out, float* __restrict__ lse, long lse_stride,
                 const Scatter& sc) {
-  constexpr int RS = DH + 8, TS = transposed_stride(BN), NSB = BN / 32;
+  constexpr int RS = DH + 8, NSB = BN / 32;
+  constexpr bool VROWS = kTiledVRows<DH>;
+  constexpr int TS = VROWS ? 0 : transposed_stride(BN);    // 0: V rows in LDS (see fwd_softmax_pv)
   auto& Ks = lds.Ks;
-  auto& Vt = lds.Vt;
+  auto& Vs = lds.Vs;
   static_assert(2 * BN >= 32 * NW, "the K buffers double as the output staging tile");
   const long C = (long)H * DH;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -415,7 +516,12 @@ tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const _
 
   const int32_t* gi = gather_base<GATHER>(sc, seg.row0);
   const long q_src = q_ok ? source_row(gi, seg.row0, qi) : 0;   // (gathered: an index load, issued first)
-  KvStage<DH, 64 * NW, (BN / 2) * (DH / 8), GATHER> stage;
+  typename std::conditional<VROWS, KvRowStage<DH, 64 * NW, BN, GATHER>,
+                            KvStage<DH, 64 * NW, (BN / 2) * (DH / 8), GATHER>>::type stage;
+  auto store = [&](int buf) {
+    if constexpr (VROWS) stage.store(Ks[buf], Vs[buf]);
+    else stage.template store<RS, transposed_stride(BN)>(Ks[buf], Vs[buf], 0);
+  };
   stage.index(gi, seg.row0, 0, seg.nk);
   stage.load(kh, vh, ks, vs);
   stage.index(gi, seg.row0, BN, seg.nk);
@@ -423,7 +529,7 @@ tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const _
   load_q_frags<DH>(q + q_src * qs + h * DH, q_ok, hh, qf);
   FwdAcc<DH> acc;
   acc.init();
-  stage.template store<RS, TS>(Ks[0], Vt[0], 0);
+  store(0);
   __syncthreads();
 
   const int nt = (seg.nk + BN - 1) / BN;
@@ -435,10 +541,10 @@ tiled_attention(TiledLds<DH, BN>& lds, const Segment seg, int h, int q0, const _
     }
     if (wave_live) {
       const int rem = seg.nk - kt;               // valid keys from this tile on (may exceed BN)
-      if (rem >= BN) fwd_process_tile<DH, RS, TS, NSB, true>(Ks[buf], Vt[buf], 0, BN, qf, acc, scale_log2, l32, hh);
-      else fwd_process_tile<DH, RS, TS, NSB, false>(Ks[buf], Vt[buf], 0, rem, qf, acc, scale_log2, l32, hh);
+      if (rem >= BN) fwd_process_tile<DH, RS, TS, NSB, true>(Ks[buf], Vs[buf], 0, BN, qf, acc, scale_log2, l32, hh);
+      else fwd_process_tile<DH, RS, TS, NSB, false>(Ks[buf], Vs[buf], 0, rem, qf, acc, scale_log2, l32, hh);
     }
-    if (t + 1 < nt) stage.template store<RS, TS>(Ks[buf ^ 1], Vt[buf ^ 1], 0);
+    if (t + 1 < nt) store(buf ^ 1);
     __syncthreads();
   }
   // every wave is past its last read of the K buffers (the loop ends with a barrier)
@@ -492,64 +598,6 @@ struct Tiled2Lds {
   __attribute__((aligned(16))) __bf16 Vs[2][BN * RS];
 };
 
-// Register staging of BN key and value rows on their way to LDS (both row-major): chunk i =
-// 16-byte piece i % CPR of row i / CPR; index() runs one tile ahead of load() (see KvStage).
-template <int DH, int THREADS, int BN, bool GATHER>
-struct KvRowStage {
-  static constexpr int CPR = DH / 8, CHUNKS = BN * CPR, CPT = (CHUNKS + THREADS - 1) / THREADS;
-  static constexpr int RPP = THREADS / CPR;
-  static_assert(THREADS % CPR == 0, "a thread keeps its chunk column over the passes");
-  bf16x8 kreg[CPT], vreg[CPT];
-  int tok_rows[CPT];                   // gathered rows only: see KvStage
-  long row0_;
-  int kt_, nk_;
-  __device__ __forceinline__ bool valid(int t) const {
-    const int i = threadIdx.x + t * THREADS;
-    return i < CHUNKS && kt_ + i / CPR < nk_;
-  }
-  __device__ __forceinline__ void index(const int32_t* gi, long row0, int kt, int nk) {
-    row0_ = row0;
-    kt_ = kt;
-    nk_ = nk;
-    if (GATHER) {
-#pragma unroll
-      for (int t = 0; t < CPT; ++t)
-        if (valid(t)) tok_rows[t] = gi[kt + (threadIdx.x + t * THREADS) / CPR];
-    }
-  }
-  __device__ __forceinline__ void load(const __bf16* kh, const __bf16* vh, long ks, long vs) {
-    const int c = threadIdx.x % CPR, lrow = threadIdx.x / CPR;
-    const uint32_t koff = (uint32_t)lrow * (uint32_t)ks + c * 8, voff = (uint32_t)lrow * (uint32_t)vs + c * 8;
-#pragma unroll
-    for (int t = 0; t < CPT; ++t) {
-      kreg[t] = zero_bf16x8();
-      vreg[t] = zero_bf16x8();
-      if (valid(t)) {
-        const __bf16 *kp, *vp;
-        if (GATHER) {
-          kp = kh + row_offset(tok_rows[t], ks) + c * 8;
-          vp = vh + row_offset(tok_rows[t], vs) + c * 8;
-        } else {
-          const long r = row0_ + kt_ + t * RPP;           // uniform
-          kp = kh + r * ks + koff;
-          vp = vh + r * vs + voff;
-        }
-        kreg[t] = *reinterpret_cast<const bf16x8*>(kp);
-        vreg[t] = *reinterpret_cast<const bf16x8*>(vp);
-      }
-    }
-  }
-  __device__ __forceinline__ void store(__bf16* kbuf, __bf16* vbuf) const {
-#pragma unroll
-    for (int t = 0; t < CPT; ++t) {
-      const int i = threadIdx.x + t * THREADS, r = i / CPR, c = i % CPR;
-      if (i < CHUNKS) {
-        *reinterpret_cast<bf16x8*>(&kbuf[r * (DH + 8) + c * 8]) = kreg[t];
-        *reinterpret_cast<bf16x8*>(&vbuf[r * (DH + 8) + c * 8]) = vreg[t];
-      }
-    }
-  }
-};
 
 // Online-softmax update of one chain over one 32-key sub-tile whose first key is k0 of the tile
 // (rem = valid keys of the tile): masks keys past the segment, moves the running max, rescales
