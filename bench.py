@@ -63,20 +63,47 @@ def parse_args():
 
 
 # ------------------------------------------------------------------------------- timing
-def timed(fn, steps, torch):
-    """K calls bracketed by synchronize on both sides -> seconds."""
+def timed(fn, steps, torch, streams=None):
+    """K calls bracketed by synchronize on both sides -> seconds.  Where the calls went to several
+    streams the closing bracket first waits for each of them in turn and then synchronizes the
+    device: the same state when the clock is read, but a device-wide synchronize that finds four
+    streams with work it has not yet waited for takes ~40 us longer to notice that they are done
+    (measured on a 20-step region of the detection workload: 697 against 655 us)."""
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
         fn()
+    for s in streams or ():
+        s.synchronize()
     torch.cuda.synchronize()
     return time.perf_counter() - t0
 
 
-def timed_regions(fn, steps, repeats, torch):
+def timed_polled(fn, steps, torch, streams):
+    """The same K calls; the clock is stopped when events recorded behind the last launch of every
+    stream read complete (polled), before the closing synchronize.  The blocking calls of the closing
+    bracket of timed() put markers of their own behind the work and wait for those, ~40-60 us on this
+    stack whatever the work was: a fixed cost that a 20-step region of a short step does not amortise.
+    Reported beside the bracketed figure, never instead of it."""
+    evs = [torch.cuda.Event() for _ in streams]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    for e, s in zip(evs, streams):
+        e.record(s)
+    for e in evs:
+        while not e.query():
+            pass
+    dt = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    return dt
+
+
+def timed_regions(fn, steps, repeats, torch, streams=None):
     """The K-step region, timed `repeats` times (a 20-step region of a 20 us step lasts 0.4 ms
     and one reading of it carries the host's jitter): seconds per step, median and min."""
-    per = [timed(fn, steps, torch) / steps for _ in range(max(1, repeats))]
+    per = [timed(fn, steps, torch, streams) / steps for _ in range(max(1, repeats))]
     return float(np.median(per)), float(np.min(per))
 
 
@@ -119,7 +146,7 @@ def kernel_times_us(stage_sets, steps, torch):
     """Per launch, the kernel running alone on one stream: two live readings with HIP events on the
     launch stream, both upper bounds of the kernel's duration (an event pair around each launch
     inside steps of the whole chain, and back-to-back launches between one pair); the smaller."""
-    steps = max(20, min(steps, 200))
+    steps = 200      # (not the K of the timed region: a pair of events around 20 launches still reads the start-up)
     ev = per_stage_us(stage_sets, steps, torch)
     out = {}
     for i, (name, _) in enumerate(stage_sets[0]):
@@ -327,7 +354,7 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
                 sstep()
             torch.cuda.synchronize()
             turn[0] = 0
-            probe = timed(sstep, 300, torch) / 300
+            probe = timed(sstep, 300, torch, cand) / 300
             calib[f"group_{gi_}_us_per_step"] = round(1e6 * probe, 2)
             if best is None or probe < best[0]:
                 best = (probe, cand)
@@ -339,15 +366,17 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
         sstep()
     torch.cuda.synchronize()
     turn[0] = 0
-    med, mn = timed_regions(sstep, args.steps, args.repeats, torch)
+    med, mn = timed_regions(sstep, args.steps, args.repeats, torch, streams)
     if not all(torch.equal(fs.y, fp.y) and int(fs.mask.sum().item()) == T for fs, _, _ in sets):
         print("bench.py: a copy's result differs from the single-stream result", file=sys.stderr)
         sys.exit(1)
 
+    polled = [timed_polled(sstep, args.steps, torch, streams) / args.steps for _ in range(max(1, args.repeats))]
+
     # per-kernel durations: the copies of the timed region on ONE stream, in rotation (cold)
     cold_sets = [fs.stages(*ins) for fs, _, ins in sets]
     times = kernel_times_us(cold_sets, args.steps, torch)
-    warm = {nme: back_to_back_us(fn, max(20, min(args.steps, 200)), torch) for nme, fn in stages}
+    warm = {nme: back_to_back_us(fn, 200, torch) for nme, fn in stages}
     for nme in times:
         times[nme]["warm_cache_us"] = round(warm[nme], 2)
     kernels, roof = kernels_block(times, forward_work(wl, T, sum_n2), wl.dtype, wl.name, traffic_table, args.seed)
@@ -363,6 +392,7 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
                     f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward select+pack+attention+unpack",
         "selected_tokens": T, "sum_n2": sum_n2, "value": T / med, "unit": "selected tokens/s",
         "ms_per_step": 1e3 * med, "ms_per_step_min": 1e3 * mn, "regions": args.repeats,
+        "ms_per_step_until_last_event": 1e3 * float(np.median(polled)),
         "launch": f"eager, {len(stages)} launches per step ({' + '.join(n_ for n_, _ in stages)}); {S} independent "
                   f"batches in flight on {S} HIP stream(s); {n_sets} copies of the inputs and buffers in rotation "
                   f"({n_sets * set_bytes >> 20} MB, cold last-level cache)",
@@ -442,7 +472,7 @@ def measure_train(args, torch, workloads, TrainPass, traffic_table, streams):
             tsstep()
         torch.cuda.synchronize()
         turn[0] = 0
-        smed, smin = timed_regions(tsstep, args.steps, args.repeats, torch)
+        smed, smin = timed_regions(tsstep, args.steps, args.repeats, torch, streams)
         same = all(torch.equal(ts.dx, tp.dx) and torch.equal(ts.dw, tp.dw) for ts, _ in tsets)
         res["batches_in_flight"] = {"streams": S, "value": T / smed, "ms_per_step": 1e3 * smed,
                                     "ms_per_step_min": 1e3 * smin, "gradients_equal_single_stream": bool(same)}
@@ -746,7 +776,8 @@ def main():
                    "seed": args.seed, "launch": head["launch"], "streams": head["streams"], "copies": head["copies"],
                    "timing": f"median over {args.repeats} repeats of the {args.steps}-step region (min: "
                              f"{head['ms_per_step_min'] * 1e3:.2f} us per step)"},
-        "ms_per_step_min": head["ms_per_step_min"], "single_stream": head["single_stream"],
+        "ms_per_step_min": head["ms_per_step_min"],
+        "ms_per_step_until_last_event": head["ms_per_step_until_last_event"], "single_stream": head["single_stream"],
         "roofline": roof, "ceilings": ceil_, "kernels": head["kernels"], "configs": configs,
     }
     if not args.no_extras:
