@@ -95,7 +95,8 @@ attn_bwd_dq_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __bf1
                  const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
                  const float* __restrict__ lse, long lse_stride, const int32_t* __restrict__ cu, int H,
                  float scale, __bf16* __restrict__ dq, long gstride, float* __restrict__ dvec, int B,
-                 const TokenIO tok = TokenIO{nullptr, nullptr, 0}) {
+                 const TokenIO tok = TokenIO{nullptr, nullptr, 0}, const bool have_live = false,
+                 const Segment live = Segment{0, 0, 0}) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW, NBUF = NW == 1 ? 1 : 2;
   const bool at_tokens = tok.gather_idx != nullptr;
   auto& Ks = lds.A;
@@ -106,8 +107,10 @@ attn_bwd_dq_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __bf1
 
   if (!tile_id.valid) return;
   const int h = tile_id.h;
-  const Segment seg = LPT ? lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick)
-                          : segment_of(tile_id.rank, cu, nullptr, 0);
+  // (live: the caller numbered the live blocks itself and hands over the block's segment)
+  const Segment seg = have_live ? live
+                      : LPT           ? lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick)
+                                      : segment_of(tile_id.rank, cu, nullptr, 0);
   const int q0 = tile_id.qb * (32 * NW);
   if (q0 >= seg.nq) return;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -243,7 +246,8 @@ attn_bwd_dkdv_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __b
                    const __bf16* __restrict__ dout, const float* __restrict__ lse,
                    const float* __restrict__ dvec, long lse_stride, const int32_t* __restrict__ cu, int H,
                    float scale, __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs, int B,
-                   const TokenIO tok = TokenIO{nullptr, nullptr, 0}) {
+                   const TokenIO tok = TokenIO{nullptr, nullptr, 0}, const bool have_live = false,
+                 const Segment live = Segment{0, 0, 0}) {
   constexpr int RS = DH + 8, KK = DH / 16, DB = DH / 32, THREADS = 64 * NW, NBUF = NW == 1 ? 1 : 2;
   const bool at_tokens = tok.gather_idx != nullptr;
   auto& Qs = lds.A;
@@ -256,8 +260,9 @@ attn_bwd_dkdv_body(BwdLds<DH, NW, BT, LPT>& lds, const TileId tile_id, const __b
 
   if (!tile_id.valid) return;
   const int h = tile_id.h;
-  const Segment seg = LPT ? lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick)
-                          : segment_of(tile_id.rank, cu, nullptr, 0);
+  const Segment seg = have_live ? live
+                      : LPT           ? lpt_segment<THREADS>(tile_id.rank, B, cu, nullptr, 0, s_cu, &s_pick)
+                                      : segment_of(tile_id.rank, cu, nullptr, 0);
   const int k0 = tile_id.qb * (32 * NW);
   if (k0 >= seg.nk) return;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -421,13 +426,22 @@ attn_bwd_both_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           TokenIO tok) {
   __shared__ BwdLds<DH, NW, BT, true> lds;
   const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
-  const TileId tile_id = xcd_tile_at(xcd, jj >> 1, nblk, H, B);
+  TileId tile_id;
+  Segment seg_live = {0, 0, 0};
+  const bool live = live_tiles_apply(H, B);     // live blocks first in launch order (see live_tile_wave)
+  if (live) {
+    const LiveTile lt = live_tile_wave(xcd, jj >> 1, H, B, cu, 32 * NW);
+    tile_id = {lt.qb, lt.h, lt.img, lt.valid};
+    seg_live = {lt.row0, lt.len, lt.len};
+  } else {
+    tile_id = xcd_tile_at(xcd, jj >> 1, nblk, H, B);
+  }
   if (jj & 1)
     attn_bwd_dkdv_body<DH, NW, BT, true>(lds, tile_id, q, k, v, qs, ks, vs, dout, lse, dvec, lse_stride, cu, H, scale,
-                                         dk, dks, dv, dvs, B, tok);
+                                         dk, dks, dv, dvs, B, tok, live, seg_live);
   else
     attn_bwd_dq_body<DH, NW, BT, true, true>(lds, tile_id, q, k, v, qs, ks, vs, out, dout, lse, lse_stride, cu, H,
-                                             scale, dq, dqs, dvec, B, tok);
+                                             scale, dq, dqs, dvec, B, tok, live, seg_live);
   if (tok.gather_idx != nullptr) {
     // gradients of the unselected tokens: every workgroup of a role (with or without a tile) zeroes an
     // even share of the rows, a quarter per wave: the dq role in dq, the dkdv role in dk and dv

@@ -107,6 +107,24 @@ __device__ __forceinline__ void scatter_fill(const Scatter& sc, int b, int t0, i
   }
 }
 
+// Fill every column of the bypassing rows among the flat token rows [r0, r1).
+template <typename T>
+__device__ __forceinline__ void scatter_fill_rows(const Scatter& sc, long r0, long r1, long C, int tid, int nthreads) {
+  constexpr int VE = 16 / sizeof(T);
+  const int cpr = (int)(C / VE);
+  const long work = (r1 - r0) * cpr;
+  for (long i = tid; i < work; i += nthreads) {
+    const long row = r0 + i / cpr;
+    const int c = (int)(i % cpr);
+    if (bypasses(sc, row)) {
+      const long off = row * C + c * VE;
+      uintx4 val = {0u, 0u, 0u, 0u};
+      if (sc.base != nullptr) val = *reinterpret_cast<const uintx4*>(static_cast<const T*>(sc.base) + off);
+      __builtin_nontemporal_store(val, reinterpret_cast<uintx4*>(static_cast<T*>(sc.y) + off));
+    }
+  }
+}
+
 // ------------------------------------------------------------------------- bf16 / MFMA
 // Per-wave state of the online softmax: O^T accumulators (rows = head dim, cols = this
 // wave's 32 queries), running max m (log2 domain, scale folded in) and running sum l (the
@@ -568,19 +586,42 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   __shared__ int s_cu[2 * kLptMaxB + 1];
   __shared__ int s_pick;
 
-  const TileId tile_id = xcd_tile(nqb, H, B);
-  if (!tile_id.valid) return;
-  const int h = tile_id.h;
-  const Segment seg = lpt_segment<64 * NW>(tile_id.rank, B, cu, key_lens, n_pad, s_cu, &s_pick);
   const long C = (long)H * DH;
-  // this workgroup's share of the image's bypassing tokens: filled right away by a
-  // workgroup that has no queries, after the main loop by one that has
-  const int fill_img = key_lens == nullptr && B > 1 && B <= kLptMaxB ? s_pick : tile_id.rank;
-  const FillRange fr = fill_range(sc, fill_img, B, tile_id.qb, nqb);
-  const int q0 = tile_id.qb * (32 * NW);
+  // live blocks first in launch order where the batch allows it (see live_tile_wave); the bypass fill
+  // is then whole rows, an even share of all tokens per workgroup.  Otherwise block qb of every
+  // (segment, head) pair in turn, the pair's share of its image's bypassing tokens per block.  The
+  // fill is done right away by a workgroup without queries, after the main loop by one that has some.
+  const bool live = key_lens == nullptr && live_tiles_apply(H, B);
+  Segment seg = {0, 0, 0};
+  int h = 0, q0 = 0;
+  FillRange fr = {0, 0, 0};
+  if (live) {
+    const LiveTile lt = live_tile_wave(blockIdx.x & 7, blockIdx.x >> 3, H, B, cu, 32 * NW);
+    if (lt.valid) {
+      seg = {lt.row0, lt.len, lt.len};
+      h = lt.h;
+      q0 = lt.qb * (32 * NW);
+    }
+  } else {
+    const TileId tile_id = xcd_tile(nqb, H, B);
+    if (!tile_id.valid) return;
+    h = tile_id.h;
+    seg = lpt_segment<64 * NW>(tile_id.rank, B, cu, key_lens, n_pad, s_cu, &s_pick);
+    const int fill_img = key_lens == nullptr && B > 1 && B <= kLptMaxB ? s_pick : tile_id.rank;
+    fr = fill_range(sc, fill_img, B, tile_id.qb, nqb);
+    q0 = tile_id.qb * (32 * NW);
+  }
   if (q0 < seg.nq)
     tiled_attention<DH, NW, BN, GATHER>(lds, seg, h, q0, q, k, v, qs, ks, vs, H, scale_log2, out, lse, lse_stride, sc);
-  if (sc.y != nullptr) scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64 * NW);
+  if (sc.y == nullptr) return;
+  if (live) {
+    const long rows = sc.flat ? (long)sc.N : (long)B * sc.N;
+    const long per = (rows + gridDim.x - 1) / gridDim.x;
+    const long r0 = min(rows, blockIdx.x * per);
+    scatter_fill_rows<__bf16>(sc, r0, min(rows, r0 + per), C, threadIdx.x, 64 * NW);
+  } else {
+    scatter_fill<__bf16, DH>(sc, fr.b, fr.t0, fr.t1, h, C, threadIdx.x, 64 * NW);
+  }
 }
 
 // Long segments, two query sub-tiles per wave.  A wave owns 64 queries as two independent
