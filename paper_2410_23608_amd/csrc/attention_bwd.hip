@@ -425,12 +425,13 @@ attn_bwd_both_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           __bf16* __restrict__ dk, long dks, __bf16* __restrict__ dv, long dvs, int B, int nblk,
                           TokenIO tok) {
   __shared__ BwdLds<DH, NW, BT, true> lds;
+  __shared__ LiveTile s_live;
   const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
   TileId tile_id;
   Segment seg_live = {0, 0, 0};
   const bool live = live_tiles_apply(H, B);     // live blocks first in launch order (see live_tile_wave)
   if (live) {
-    const LiveTile lt = live_tile_wave(xcd, jj >> 1, H, B, cu, 32 * NW);
+    const LiveTile lt = live_tile_block(xcd, jj >> 1, H, B, cu, 32 * NW, nblk, &s_live);
     tile_id = {lt.qb, lt.h, lt.img, lt.valid};
     seg_live = {lt.row0, lt.len, lt.len};
   } else {

@@ -585,6 +585,7 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   __shared__ TiledLds<DH, BN> lds;
   __shared__ int s_cu[2 * kLptMaxB + 1];
   __shared__ int s_pick;
+  __shared__ LiveTile s_live;
 
   const long C = (long)H * DH;
   // live blocks first in launch order where the batch allows it (see live_tile_wave); the bypass fill
@@ -596,7 +597,7 @@ attn_fwd_bf16_tiled_kernel(const __bf16* __restrict__ q, const __bf16* __restric
   int h = 0, q0 = 0;
   FillRange fr = {0, 0, 0};
   if (live) {
-    const LiveTile lt = live_tile_wave(blockIdx.x & 7, blockIdx.x >> 3, H, B, cu, 32 * NW);
+    const LiveTile lt = live_tile_block(blockIdx.x & 7, blockIdx.x >> 3, H, B, cu, 32 * NW, nqb, &s_live);
     if (lt.valid) {
       seg = {lt.row0, lt.len, lt.len};
       h = lt.h;
