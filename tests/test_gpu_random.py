@@ -2,7 +2,8 @@
 from-the-mask forward forms must agree bit for bit with each other and with the oracle within
 tolerance; the backward at token positions must agree with the oracle.  Shapes are drawn so that
 segments straddle every tile size of the kernels (32, 64, 128, 256 keys; one, several and many
-tiles; empty and full images; batches on both sides of the in-kernel ranking limits)."""
+tiles; empty and full images; batches on both sides of the in-kernel ranking limits; seeds 40-43:
+17 to 64 long images)."""
 import numpy as np
 import pytest
 import torch
@@ -27,6 +28,13 @@ def _draw(seed):
     Dh = [32, 64][seed % 2]
     H = int(rng.integers(1, 4))
     kind = seed % 4
+    if seed >= 40:       # 17 to 64 long images: the long-segment kernels number their blocks per workgroup, ranking
+        B, N = ((40, 500), (20, 2600), (64, 300), (33, 1100))[seed - 40]      # by block count (B > blocks) or pairwise
+        dtype, H = "bf16", 2
+        lens = rng.integers(0, N + 1, size=B)
+        lens[rng.integers(0, B)] = N
+        lens[rng.integers(0, B)] = 0
+        return rng, B, N, H, Dh, dtype, lens
     if kind == 0:        # many short images (the one-wave kernels, ranking of up to 64 images and beyond)
         B, N = int(rng.integers(40, 90)), int(rng.integers(20, 257))
     elif kind == 1:      # a few long images (the tiled kernels, several 128-key tiles and a ragged tail)
@@ -45,7 +53,7 @@ def _draw(seed):
     return rng, B, N, H, Dh, dtype, lens
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(44))
 def test_random_shapes_all_forward_forms_and_backward(spa, seed):
     rng, B, N, H, Dh, dtype, lens = _draw(seed)
     C, cap, td = H * Dh, B * N, tdtype(dtype)
