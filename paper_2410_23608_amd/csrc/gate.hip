@@ -10,7 +10,7 @@
 namespace spa {
 
 constexpr int kGateThreads = 256;
-constexpr int kMaxGateC = 8192;   // gate weight is staged in LDS as fp32
+constexpr int kMaxGateC = 8192;   // (the gate backward stages w in LDS as fp32)
 
 template <typename T> struct Vec16;
 template <> struct Vec16<float> {
@@ -183,10 +183,6 @@ gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
                    const float* __restrict__ s_up, const float* __restrict__ noise, float theta, int ntok, int N, int C,
                    PoolGrid pool, float* __restrict__ scores, uint8_t* __restrict__ mask, IndexOut idx) {
   constexpr int VE = Vec16<T>::kElems;
-  extern __shared__ float w_lds[];
-  for (int c = threadIdx.x; c < C; c += kGateThreads) w_lds[c] = static_cast<float>(w[c]);
-  __syncthreads();
-
   constexpr int kGroups = kGateThreads / G;
   const int grp = threadIdx.x / G;
   const int gl = threadIdx.x % G;
@@ -197,14 +193,17 @@ gate_select_kernel(const T* __restrict__ x, const T* __restrict__ w, float bias,
     const long tok = base + grp;
     float acc = 0.f;
     if (tok < ntok) {
+      // the lane's chunks of w come from memory like its chunks of the row (w is a few KB that every
+      // workgroup reads: cache hits), issued together with them: no staging of w in LDS, no barrier
+      // between the launch and the first row load
       const T* row = x + tok * (long)C;
 #pragma unroll 4
       for (int ch = gl; ch < chunks; ch += G) {
-        float f[VE];
+        float f[VE], wv[VE];
         Vec16<T>::load(row + ch * VE, f);
-        const float* wp = w_lds + ch * VE;
+        Vec16<T>::load(w + ch * VE, wv);
 #pragma unroll
-        for (int i = 0; i < VE; ++i) acc = fmaf(f[i], wp[i], acc);
+        for (int i = 0; i < VE; ++i) acc = fmaf(f[i], wv[i], acc);
       }
     }
     acc = group_sum<G>(acc);
@@ -490,7 +489,7 @@ static int launch_gate(const char* fn, const void* x, const void* w, float bias,
   constexpr int VE = Vec16<T>::kElems;
   const int chunks = C / VE;
   const long ntok = (long)B * N;
-  const size_t lds = (size_t)C * sizeof(float);
+  const size_t lds = 0;      // (the gate weight is read from memory, nothing is staged)
   auto go = [&](auto gtag) {
     constexpr int G = decltype(gtag)::value;
     const long per_wg = kGateThreads / G;
