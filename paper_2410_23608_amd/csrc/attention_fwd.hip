@@ -1506,7 +1506,7 @@ extern "C" int spa_packed_attention(const void* q, const void* k, const void* v,
                                     int dtype, float softmax_scale, void* out, float* lse, void* stream) {
   SPA_REQUIRE(cu_seqlens, SPA_ERR_INVALID_ARG, "spa_packed_attention: cu_seqlens is null");
   SPA_REQUIRE(out, SPA_ERR_INVALID_ARG, "spa_packed_attention: out is null");
-  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
+  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0, 0, 0, nullptr};
   return attention_common("spa_packed_attention", q, k, v, q_row_stride, k_row_stride, v_row_stride, cu_seqlens, nullptr, B, max_seqlen,
                           H, Dh, dtype, softmax_scale, out, lse, none, stream);
 }
@@ -1516,7 +1516,7 @@ extern "C" int spa_padded_attention(const void* q, const void* k, const void* v,
                                     float softmax_scale, void* out, void* stream) {
   SPA_REQUIRE(seqlens, SPA_ERR_INVALID_ARG, "spa_padded_attention: seqlens is null");
   SPA_REQUIRE(out, SPA_ERR_INVALID_ARG, "spa_padded_attention: out is null");
-  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
+  const Scatter none = {nullptr, nullptr, nullptr, nullptr, 0, 0, 0, nullptr};
   return attention_common("spa_padded_attention", q, k, v, row_stride, row_stride, row_stride, nullptr, seqlens, B, n_pad, H, Dh,
                           dtype, softmax_scale, out, nullptr, none, stream);
 }
