@@ -67,6 +67,8 @@ def _check(spa, B, N, H, Dh, dens, seed):
 @pytest.mark.parametrize("B,N,H,Dh", [(300, 40, 2, 64),      # one-wave forward without the weight numbering (B > 64), backward ranked through LDS
                                       (600, 40, 2, 32),      # backward beyond 512 images: launch order = image order
                                       (300, 300, 1, 32),     # long-segment kernels beyond 256 images
+                                      (100, 300, 2, 32),     # long-segment kernels, 65 to 256 images: ranked through LDS, blocks not compacted
+                                      (48, 300, 12, 32),     # the same with at most 64 images but more than 512 (image, head) pairs
                                       (70, 196, 3, 64)])     # ViT-shaped, just past one wave of images
 def test_many_images(spa, B, N, H, Dh):
     _check(spa, B, N, H, Dh, 0.5, seed=B + N)
