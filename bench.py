@@ -57,6 +57,8 @@ def parse_args():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the four-call form, graph replay, padded baseline, widened rows")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--kernel-launches", type=int, default=200,
+                    help="launches per kernel of the per-kernel timing passes (independent of --steps)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -144,11 +146,11 @@ def back_to_back_us(fn, steps, torch):
     return 1e3 * a.elapsed_time(b) / steps
 
 
-def kernel_times_us(stage_sets, steps, torch):
+def kernel_times_us(stage_sets, launches, torch):
     """Per launch, the kernel running alone on one stream: two live readings with HIP events on the
     launch stream, both upper bounds of the kernel's duration (an event pair around each launch
     inside steps of the whole chain, and back-to-back launches between one pair); the smaller."""
-    steps = 200      # (not the K of the timed region: a pair of events around 20 launches still reads the start-up)
+    steps = max(1, launches)     # (not the K of the timed region: a pair of events around 20 launches still reads the start-up)
     ev = per_stage_us(stage_sets, steps, torch)
     out = {}
     for i, (name, _) in enumerate(stage_sets[0]):
@@ -377,8 +379,8 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
 
     # per-kernel durations: the copies of the timed region on ONE stream, in rotation (cold)
     cold_sets = [fs.stages(*ins) for fs, _, ins in sets]
-    times = kernel_times_us(cold_sets, args.steps, torch)
-    warm = {nme: back_to_back_us(fn, 200, torch) for nme, fn in stages}
+    times = kernel_times_us(cold_sets, args.kernel_launches, torch)
+    warm = {nme: back_to_back_us(fn, args.kernel_launches, torch) for nme, fn in stages}
     for nme in times:
         times[nme]["warm_cache_us"] = round(warm[nme], 2)
     kernels, roof = kernels_block(times, forward_work(wl, T, sum_n2), wl.dtype, wl.name, traffic_table, args.seed)
@@ -446,7 +448,7 @@ def measure_train(args, torch, workloads, TrainPass, traffic_table, streams):
     n = np.diff(tp.cu_seqlens.cpu().numpy()).astype(np.float64)
     sum_n2 = float((n * n).sum())
     med, mn = timed_regions(step, args.steps, args.repeats, torch)
-    times = kernel_times_us([stages], args.steps, torch)
+    times = kernel_times_us([stages], args.kernel_launches, torch)
     kernels, roof = kernels_block(times, train_work(B, N, C, H, T, sum_n2), wl.dtype, wl.name, traffic_table, args.seed)
     res = {"workload": f"vit_b_train: B={B} N={N} C={C} H={H} Dh={wl.Dh} bf16, selected fraction "
                        f"U[{wl.frac[0]},{wl.frac[1]}] per image, forward + backward with the selection loss",
@@ -507,7 +509,7 @@ def measure_hierarchy(args, torch, workloads, HierarchyPass, HierarchyTrainPass,
            "stages": [b_["workload"].name for b_ in hb], "tokens": [c_[0] * c_[1] * c_[2] for c_ in hcfg],
            "forward": {"launches": len(hstages), "selected_tokens": hT, "value": sum(hT) / fmed,
                        "unit": "selected tokens/s", "ms_per_step": 1e3 * fmed, "ms_per_step_min": 1e3 * fmin,
-                       "stage_us": {nme: round(back_to_back_us(fn, 200, torch), 2)
+                       "stage_us": {nme: round(back_to_back_us(fn, args.kernel_launches, torch), 2)
                                     for nme, fn in hstages}}}
     htp = HierarchyTrainPass(hcfg)
     hqk = [up(b_["qkv"][:, :, :2 * b_["workload"].C]) for b_ in hb]
@@ -524,7 +526,7 @@ def measure_hierarchy(args, torch, workloads, HierarchyPass, HierarchyTrainPass,
     torch.cuda.synchronize()
     htT = [int(p_.total.item()) for p_ in htp.passes]
     med, mn = timed_regions(htstep, args.steps, args.repeats, torch)
-    times = kernel_times_us([htstages], args.steps, torch)
+    times = kernel_times_us([htstages], args.kernel_launches, torch)
     work, sum_n2s = {}, []
     for i, (b_, tp_) in enumerate(zip(hb, htp.passes)):
         wl_ = b_["workload"]
