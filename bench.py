@@ -43,8 +43,9 @@ def parse_args():
                     help="the K-step region is timed this many times; median and min are reported")
     ap.add_argument("--workload", default="det", choices=["tiny", "vit_s", "det"], help="headline forward workload")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--streams", type=int, default=4,
-                    help="independent batches in flight, one HIP stream each (1 = one stream, steps back to back)")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="independent batches in flight, one HIP stream each (1 = one stream, steps back to back; "
+                         "0 = 2 or 4, whichever is faster on regions of --steps steps)")
     ap.add_argument("--only", default=None, choices=["forward", "vit_s", "det", "vit_b_train", "hierarchy"],
                     help="measure one chain only (profiling runs): forward = the headline workload's forward chain")
     ap.add_argument("--form", default="auto", choices=["auto", "selected", "fused", "gathered", "packed"],
@@ -324,16 +325,19 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
     # S independent batches in flight: S HIP streams (default priority), steps dealt round-robin, the
     # launches of a step in order on their stream; every step works on its own copy of the inputs and
     # buffers, enough copies (> 512 MB in total) that no step finds anything in the last-level cache
-    S = max(1, args.streams)
     set_bytes = (x.numel() + qkv.numel() + (0 if gathered else fp.packed_qkv.numel()) + fp.y.numel()) * e
-    n_sets = S * max(2, -(-(512 << 20) // (S * set_bytes)))
+    cfg = {"S": 1, "n_sets": 2}
     turn = [0]
     holder = {}
 
+    def configure(S_):
+        cfg["S"] = S_
+        cfg["n_sets"] = S_ * max(2, -(-(512 << 20) // (S_ * set_bytes)))
+
     def build_sets(streams_):
         made = []
-        for i in range(n_sets):
-            with torch.cuda.stream(streams_[i % S]):
+        for i in range(cfg["n_sets"]):
+            with torch.cuda.stream(streams_[i % cfg["S"]]):
                 fp_s = mk()
                 ins = (x.clone(), w.clone(), qkv.clone())
                 made.append((fp_s, fp_s.stages(*ins), ins))
@@ -341,35 +345,63 @@ def measure_forward(wl, args, torch, workloads, ForwardPass, traffic_table, stre
         return made
 
     def sstep():   # step i -> copy i % n_sets, which lives on stream i % S
-        for _, fn in holder["sets"][turn[0] % n_sets][1]:
+        for _, fn in holder["sets"][turn[0] % cfg["n_sets"]][1]:
             fn()
         turn[0] += 1
 
     # Which HIP streams end up sharing one of the process's hardware queues (4 here) is the runtime's
     # business, and two batches on one queue run one after the other: three groups of S streams are
-    # tried for a few hundred untimed steps each and the fastest group is kept (once per process).
+    # tried for a few hundred untimed steps each and the fastest group is kept (once per process and S).
     calib = {}
-    if S > 1 and "streams" not in streams_cache:
-        best = None
-        for gi_ in range(3):
-            cand = [torch.cuda.Stream() for _ in range(S)]
-            holder["sets"] = build_sets(cand)
-            for _ in range(n_sets):
-                sstep()
-            torch.cuda.synchronize()
-            turn[0] = 0
-            probe = timed(sstep, 300, torch, cand) / 300
-            calib[f"group_{gi_}_us_per_step"] = round(1e6 * probe, 2)
-            if best is None or probe < best[0]:
-                best = (probe, cand)
+
+    def streams_for(S_):
+        if S_ == 1:
+            return [torch.cuda.current_stream()]
+        if ("streams", S_) not in streams_cache:
+            best = None
+            for gi_ in range(3):
+                cand = [torch.cuda.Stream() for _ in range(S_)]
+                holder["sets"] = build_sets(cand)
+                for _ in range(cfg["n_sets"]):
+                    sstep()
+                torch.cuda.synchronize()
+                turn[0] = 0
+                probe = timed(sstep, 300, torch, cand) / 300
+                calib[f"S{S_}_group_{gi_}_us_per_step"] = round(1e6 * probe, 2)
+                if best is None or probe < best[0]:
+                    best = (probe, cand)
+                holder["sets"] = None
+            streams_cache[("streams", S_)] = best[1]
+        return streams_cache[("streams", S_)]
+
+    def ready(S_):
+        """Copies built on the chosen streams of S_ batches in flight, warmed up; returns the streams."""
+        configure(S_)
+        streams_ = streams_for(S_)
+        holder["sets"] = build_sets(streams_)
+        for _ in range(max(args.warmup, cfg["n_sets"])):
+            sstep()
+        torch.cuda.synchronize()
+        turn[0] = 0
+        return streams_
+
+    # How many batches to keep in flight depends on the length of the timed region: a region of K steps
+    # starts and ends with the streams' pipelines filling and draining, which costs more the more
+    # streams there are (200-step regions of the detection workload: 4 streams 31.5 us per step, 2
+    # streams 33.3; 20-step regions: 36.9 and 35.1).  --streams 0 (the default) times a few regions
+    # of the K steps asked for with 2 and with 4 batches in flight and keeps the better.
+    if args.streams > 0:
+        S = args.streams
+    else:
+        probes = {}
+        for S_ in (2, 4):
+            streams_ = ready(S_)
+            probes[S_] = timed_regions(sstep, args.steps, 7, torch, streams_)[0]
+            calib[f"S{S_}_us_per_step_at_{args.steps}_steps"] = round(1e6 * probes[S_], 2)
             holder["sets"] = None
-        streams_cache["streams"] = best[1]
-    streams = streams_cache["streams"] if S > 1 else [torch.cuda.current_stream()]
-    sets = holder["sets"] = build_sets(streams)
-    for _ in range(max(args.warmup, n_sets)):
-        sstep()
-    torch.cuda.synchronize()
-    turn[0] = 0
+        S = min(probes, key=probes.get)
+    streams = ready(S)
+    sets, n_sets = holder["sets"], cfg["n_sets"]
     med, mn = timed_regions(sstep, args.steps, args.repeats, torch, streams)
     if not all(torch.equal(fs.y, fp.y) and int(fs.mask.sum().item()) == T for fs, _, _ in sets):
         print("bench.py: a copy's result differs from the single-stream result", file=sys.stderr)
